@@ -1,0 +1,138 @@
+/*
+ * parallax.h -- C ABI of the MI355X (gfx950) Parallax attention forward library.
+ *
+ * Parallax (paper Sec. 3.1) extends softmax attention with a probe matrix R that has the
+ * shape and head grouping of Q. For query row i with allowed key set J(i):
+ *
+ *     p_ij = softmax_j(scale * <q_i, k_j>)            scale = 1/h, natural exponential
+ *     u_ij = <rho_i, k_j>                             (never scaled)
+ *     o_i  = sum_j p_ij (1 + sum_j' p_ij' u_ij' - u_ij) v_j
+ *          = o_softmax_i - Sigma_KV^(i) rho_i         (softmax-weighted KV covariance)
+ *
+ * The kernels evaluate it in one pass over K/V tiles with the running state
+ * (m, d1, d2, O1, O2) of the paper's Algorithm 1 (Sec. 3.3) and finish with
+ * O = O1/d1 * (1 + d2/d1) - O2/d1; decode splits the key range over workgroups and merges
+ * the split partials with a log-sum-exp rescale (App. C, "in-kernel reduction" -- done here
+ * by a separate combine kernel).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller. The library never
+ *     allocates, frees or keeps device memory.
+ *   - Kernels are enqueued on the caller's hipStream_t (passed as void*, NULL = default
+ *     stream). Calls return without synchronising; outputs are valid once the stream
+ *     reaches that point.
+ *   - Arguments are validated on the host before anything is launched. On any error a
+ *     negative plx_status is returned and nothing has been enqueued. No call aborts or throws.
+ *   - GQA: G = Hq / Hkv must be an integer; query head h reads KV head h / G.
+ *   - Supported: dtype bf16 (MFMA kernels, d in {64, 128}, G <= 8) and fp32 (plain
+ *     correctness kernels, d <= 256). Innermost dimension contiguous; base pointers and
+ *     row strides 16-byte aligned. Output dtype = input dtype; all running state is fp32.
+ */
+#ifndef PARALLAX_H
+#define PARALLAX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { PLX_BF16 = 0, PLX_F32 = 1 } plx_dtype;
+
+typedef enum {
+    PLX_OK = 0,
+    PLX_ERR_NULL = -1,      /* a required pointer is NULL                          */
+    PLX_ERR_SHAPE = -2,     /* non-positive size, Hq % Hkv != 0, unsupported d / G */
+    PLX_ERR_DTYPE = -3,     /* unknown dtype                                       */
+    PLX_ERR_ALIGN = -4,     /* pointer or stride not 16-byte aligned               */
+    PLX_ERR_WORKSPACE = -5, /* split-KV workspace missing or too small             */
+    PLX_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch                    */
+    PLX_ERR_SPLITS = -7     /* num_splits outside [0, PLX_MAX_SPLITS]              */
+} plx_status;
+
+#define PLX_MAX_SPLITS 128
+
+/*
+ * Single-step decode (Algorithm 1 with one query row per head, Sec. 3.3; split-KV and merge,
+ * App. C). The KV cache already contains the current token: key j of sequence b is allowed
+ * iff j < L_b, L_b = seq_lens[b] (or Lmax when seq_lens is NULL).
+ *
+ *   q, r      [B, Hq, d]   contiguous
+ *   k, v      [B, Hkv, Lmax, d] addressed as base + b*stride_b + h*stride_h + l*stride_l
+ *             (strides in ELEMENTS, last dim contiguous)
+ *   o         [B, Hq, d]   contiguous, written
+ *   seq_lens  [B] int32 on the device, 0 <= L_b <= Lmax; rows with L_b = 0 (undefined in
+ *             the paper: empty softmax) are written as zeros
+ *   scale     multiplies q.k only (the probe score r.k is used as is)
+ *   use_r     1 = Parallax; 0 = softmax-only twin (r may be NULL, correction branch skipped)
+ *   num_splits 0 = library heuristic, else the number of key-range splits to use
+ *   workspace fp32 scratch for split partials, >= parallax_decode_workspace_bytes(...);
+ *             may be NULL only when num_splits == 1
+ */
+typedef struct {
+    const void *q, *r;
+    const void *k, *v;
+    void *o;
+    const int32_t *seq_lens;
+    int32_t B, Hq, Hkv, Lmax, d;
+    int64_t k_stride_b, k_stride_h, k_stride_l;
+    int64_t v_stride_b, v_stride_h, v_stride_l;
+    float scale;
+    int32_t use_r;
+    int32_t num_splits;
+    void *workspace;
+    size_t workspace_bytes;
+    plx_dtype dtype;
+} plx_decode_args;
+
+/* Bytes of workspace that is enough for any split count the library may pick or accept
+ * for this shape: B*Hq*PLX_MAX_SPLITS records of (2d+4) floats (m, d1, d2, pad, O1[d], O2[d]). */
+size_t parallax_decode_workspace_bytes(int32_t B, int32_t Hq, int32_t Hkv, int32_t Lmax, int32_t d);
+
+/* The split count the heuristic picks for a shape on a device with num_cus compute units
+ * (num_cus <= 0: ask the current device; 256 if none is visible). Pure host arithmetic. */
+int32_t parallax_decode_num_splits(int32_t B, int32_t Hq, int32_t Hkv, int32_t Lmax, int32_t d,
+                                   int32_t num_cus);
+
+plx_status parallax_decode(const plx_decode_args *args, void *hip_stream);
+
+/*
+ * Prefill forward over T query rows and T keys per sequence (Algorithm 1, Sec. 3.3; forward
+ * equation Sec. 3.1). causal != 0: key j allowed iff j <= i (diagonal included, so row 0
+ * returns v_0); causal == 0: every key.
+ *
+ *   q, r, o   [B, Hq, T, d]    k, v  [B, Hkv, T, d]
+ *   *_stride  element strides {batch, head, row}; last dim contiguous
+ */
+typedef struct {
+    const void *q, *r;
+    const void *k, *v;
+    void *o;
+    int32_t B, Hq, Hkv, T, d;
+    int64_t q_stride[3], r_stride[3], k_stride[3], v_stride[3], o_stride[3];
+    float scale;
+    int32_t causal;
+    int32_t use_r;
+    plx_dtype dtype;
+} plx_prefill_args;
+
+plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
+
+/* Plain device-to-device copy kernel (16 bytes per lane, grid-stride). Used to calibrate
+ * hardware byte counters and to measure the achievable streaming bandwidth next to the
+ * attention kernels. bytes must be a multiple of 16; pointers 16-byte aligned. */
+plx_status parallax_util_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+
+/* Streams `bytes` from src and writes one 16-byte checksum per workgroup to sink
+ * (>= 16 * parallax_util_read_sink_slots() bytes): a read-only bandwidth ceiling. */
+plx_status parallax_util_read(const void *src, size_t bytes, void *sink, void *hip_stream);
+int32_t parallax_util_read_sink_slots(void);
+
+const char *parallax_strerror(plx_status status);
+int parallax_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARALLAX_H */

@@ -1,0 +1,73 @@
+"""The pins must be able to fail: plant plausible mistakes in a COPY of the oracle's C source
+(on the CPU, in a temp dir), and check that the pinned facts reject every mutant."""
+import functools
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import parallax_oracle as po
+
+MUTANTS = {
+    "sign_of_correction": ("(1.0 + ubar - u[j])", "(1.0 - ubar + u[j])"),
+    "uncentred_probe": ("(1.0 + ubar - u[j])", "(1.0 - u[j])"),
+    "probe_scaled_like_q": ("u[j] = s2;", "u[j] = scale * s2;"),
+    "probe_uses_q": ("s2 += rho[c] * kj[c];", "s2 += q[c] * kj[c];"),
+    "ubar_unweighted": ("ubar += a[j] * u[j];", "ubar += u[j] / (double)n_keys;"),
+    "causal_excludes_diagonal": ("n_keys = (int64_t)i + 1;", "n_keys = (int64_t)i;"),
+    "gqa_modulo": ("const int hk = h / G;", "const int hk = h % Hkv;"),
+    "no_max_subtraction_no_norm": ("a[j] /= omega;", "a[j] /= 1.0;"),
+}
+
+
+def _pins(fwd):
+    """A compact subset of the pins; returns the names of those that FAIL."""
+    failed = []
+    rng = np.random.default_rng(5)
+    # hand-worked example (tests/golden/two_key_example.txt)
+    q = np.zeros((1, 1, 1, 2))
+    k = np.array([[[[1.0, 0.0], [-1.0, 0.0]]]])
+    v = np.array([[[[1.0, 0.0], [3.0, 0.0]]]])
+    if abs(fwd(q, np.array([[[[1.0, 0.0]]]]), k, v, 1.0)[0, 0, 0, 0] - 3.0) > 1e-12:
+        failed.append("hand")
+    # two-key closed form with scale != 1
+    d = 4
+    q, rho = rng.standard_normal((1, 1, 1, d)), rng.standard_normal((1, 1, 1, d))
+    k, v = rng.standard_normal((1, 1, 2, d)), rng.standard_normal((1, 1, 2, d))
+    a = 0.7 * (k[0, 0] @ q[0, 0, 0])
+    p = 1.0 / (1.0 + np.exp(a[1] - a[0]))
+    ref = p * v[0, 0, 0] + (1 - p) * v[0, 0, 1] - p * (1 - p) * (v[0, 0, 0] - v[0, 0, 1]) * (
+        (k[0, 0, 0] - k[0, 0, 1]) @ rho[0, 0, 0])
+    if np.abs(fwd(q, rho, k, v, 0.7)[0, 0, 0] - ref).max() > 1e-10:
+        failed.append("two_key")
+    # key-translation invariance, causal row 0 = v_0, constant values, GQA order
+    B, Hq, Hkv, T = 1, 4, 2, 7
+    q, r = rng.standard_normal((B, Hq, T, d)), rng.standard_normal((B, Hq, T, d))
+    k, v = rng.standard_normal((B, Hkv, T, d)), rng.standard_normal((B, Hkv, T, d))
+    base = fwd(q, r, k, v, 0.5, causal=True)
+    if np.abs(fwd(q, r, k + 2.0, v, 0.5, causal=True) - base).max() > 1e-8:
+        failed.append("translation")
+    if np.abs(base[0, :, 0] - np.repeat(v[0, :, 0], 2, axis=0)).max() > 1e-12:
+        failed.append("row0")
+    if np.abs(fwd(q, r, k, np.ones_like(v), 0.5, causal=True) - 1.0).max() > 1e-10:
+        failed.append("constant_values")
+    return failed
+
+
+def test_unmutated_source_passes_compact_pins():
+    assert _pins(po.forward) == []
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_mutant_is_rejected(name, tmp_path):
+    old, new = MUTANTS[name]
+    src = open(os.path.join(os.path.dirname(po.__file__), "parallax_oracle.c")).read()
+    assert src.count(old) >= 1, "mutation site vanished from the oracle source"
+    cfile = tmp_path / "mutant.c"
+    cfile.write_text(src.replace(old, new))
+    lib = tmp_path / "libmutant.so"
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-o",
+                           str(lib), str(cfile), "-lm"])
+    fwd = functools.partial(po.forward, _lib_override=po._bind(str(lib)))
+    assert _pins(fwd) != [], "no pin noticed the planted mistake '%s'" % name
