@@ -1,0 +1,239 @@
+"""Thin ctypes binding of the Parallax HIP library (same names as include/parallax.h).
+
+Only argument marshalling happens here: torch tensors supply device pointers, strides and the
+current HIP stream; every step of the attention path runs in the library's kernels. There is
+no CPU or PyTorch fallback: if the library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported before the library so both share one HIP runtime
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libparallax_hip.so")
+
+PLX_BF16, PLX_F32 = 0, 1
+PLX_MAX_SPLITS = 128
+(PLX_OK, PLX_ERR_NULL, PLX_ERR_SHAPE, PLX_ERR_DTYPE, PLX_ERR_ALIGN, PLX_ERR_WORKSPACE,
+ PLX_ERR_LAUNCH, PLX_ERR_SPLITS) = (0, -1, -2, -3, -4, -5, -6, -7)
+
+EXPORTED_SYMBOLS = (
+    "parallax_decode_workspace_bytes", "parallax_decode_num_splits", "parallax_decode",
+    "parallax_prefill", "parallax_util_copy", "parallax_util_read",
+    "parallax_util_read_sink_slots", "parallax_strerror", "parallax_version",
+)
+
+
+class plx_decode_args(ctypes.Structure):
+    _fields_ = [
+        ("q", ctypes.c_void_p), ("r", ctypes.c_void_p),
+        ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+        ("o", ctypes.c_void_p),
+        ("seq_lens", ctypes.c_void_p),
+        ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("Lmax", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_l", ctypes.c_int64),
+        ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_l", ctypes.c_int64),
+        ("scale", ctypes.c_float),
+        ("use_r", ctypes.c_int32),
+        ("num_splits", ctypes.c_int32),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("dtype", ctypes.c_int),
+    ]
+
+
+class plx_prefill_args(ctypes.Structure):
+    _fields_ = [
+        ("q", ctypes.c_void_p), ("r", ctypes.c_void_p),
+        ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+        ("o", ctypes.c_void_p),
+        ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("T", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("q_stride", ctypes.c_int64 * 3), ("r_stride", ctypes.c_int64 * 3),
+        ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
+        ("o_stride", ctypes.c_int64 * 3),
+        ("scale", ctypes.c_float),
+        ("causal", ctypes.c_int32),
+        ("use_r", ctypes.c_int32),
+        ("dtype", ctypes.c_int),
+    ]
+
+
+class ParallaxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, strerror(status), status))
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libparallax_hip.so (built by __graft_entry__.build()). Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "%s is missing: build it with `python -c 'import __graft_entry__ as g; "
+                "g.build()'` (there is no fallback path)" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.parallax_decode_workspace_bytes.argtypes = [ctypes.c_int32] * 5
+        lib.parallax_decode_workspace_bytes.restype = ctypes.c_size_t
+        lib.parallax_decode_num_splits.argtypes = [ctypes.c_int32] * 6
+        lib.parallax_decode_num_splits.restype = ctypes.c_int32
+        lib.parallax_decode.argtypes = [ctypes.POINTER(plx_decode_args), ctypes.c_void_p]
+        lib.parallax_decode.restype = ctypes.c_int
+        lib.parallax_prefill.argtypes = [ctypes.POINTER(plx_prefill_args), ctypes.c_void_p]
+        lib.parallax_prefill.restype = ctypes.c_int
+        lib.parallax_util_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                           ctypes.c_void_p]
+        lib.parallax_util_copy.restype = ctypes.c_int
+        lib.parallax_util_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                           ctypes.c_void_p]
+        lib.parallax_util_read.restype = ctypes.c_int
+        lib.parallax_util_read_sink_slots.argtypes = []
+        lib.parallax_util_read_sink_slots.restype = ctypes.c_int32
+        lib.parallax_strerror.argtypes = [ctypes.c_int]
+        lib.parallax_strerror.restype = ctypes.c_char_p
+        lib.parallax_version.argtypes = []
+        lib.parallax_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return load_library().parallax_strerror(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().parallax_version())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return PLX_BF16
+    if t.dtype == torch.float32:
+        return PLX_F32
+    raise TypeError("Parallax kernels take bfloat16 or float32 tensors, got %s" % t.dtype)
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def parallax_decode_workspace_bytes(B, Hq, Hkv, Lmax, d) -> int:
+    return int(load_library().parallax_decode_workspace_bytes(B, Hq, Hkv, Lmax, d))
+
+
+def parallax_decode_num_splits(B, Hq, Hkv, Lmax, d, num_cus=0) -> int:
+    return int(load_library().parallax_decode_num_splits(B, Hq, Hkv, Lmax, d, num_cus))
+
+
+def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None):
+    """Fill a plx_decode_args from tensors: q, r, out [B, Hq, d]; k, v [B, Hkv, Lmax, d]."""
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = k.shape
+    a = plx_decode_args()
+    a.q, a.k, a.v, a.o = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
+    a.r = r.data_ptr() if r is not None else None
+    a.seq_lens = seq_lens.data_ptr() if seq_lens is not None else None
+    a.B, a.Hq, a.Hkv, a.Lmax, a.d = B, Hq, Hkv, Lmax, d
+    a.k_stride_b, a.k_stride_h, a.k_stride_l = k.stride(0), k.stride(1), k.stride(2)
+    a.v_stride_b, a.v_stride_h, a.v_stride_l = v.stride(0), v.stride(1), v.stride(2)
+    a.scale = float(scale)
+    a.use_r = 1 if use_r else 0
+    a.num_splits = int(num_splits)
+    if workspace is not None:
+        a.workspace = workspace.data_ptr()
+        a.workspace_bytes = workspace.numel() * workspace.element_size()
+    a.dtype = _dtype_code(q)
+    return a
+
+
+def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None,
+                    out=None, stream=None):
+    """Single-step Parallax decode. Allocates `out` / `workspace` with torch when not given
+    (allocation only; all arithmetic is in the library)."""
+    for t in (q, k, v) + ((r,) if r is not None else ()):
+        if not t.is_cuda:
+            raise ValueError("parallax_decode needs device tensors")
+    if q.stride(-1) != 1 or k.stride(-1) != 1 or v.stride(-1) != 1 or not q.is_contiguous() or (
+            r is not None and not r.is_contiguous()):
+        raise ValueError("q, r must be contiguous and k, v contiguous in the last dimension")
+    if seq_lens is not None and seq_lens.dtype != torch.int32:
+        raise TypeError("seq_lens must be int32")
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = k.shape
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None and num_splits != 1 and q.dtype == torch.bfloat16:
+        S = num_splits or parallax_decode_num_splits(B, Hq, Hkv, Lmax, d)
+        if S > 1:
+            workspace = torch.empty(B * Hq * S * (2 * d + 4), dtype=torch.float32, device=q.device)
+    a = decode_args(q, r, k, v, out, scale, seq_lens, use_r, num_splits, workspace)
+    st = load_library().parallax_decode(ctypes.byref(a), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_decode")
+    return out
+
+
+def prefill_args(q, r, k, v, out, scale, causal=True, use_r=True):
+    """Fill a plx_prefill_args from tensors: q, r, out [B, Hq, T, d]; k, v [B, Hkv, T, d]."""
+    B, Hq, T, d = q.shape
+    Hkv = k.shape[1]
+    a = plx_prefill_args()
+    a.q, a.k, a.v, a.o = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
+    a.r = r.data_ptr() if r is not None else None
+    a.B, a.Hq, a.Hkv, a.T, a.d = B, Hq, Hkv, T, d
+    for name, t in (("q_stride", q), ("r_stride", r if r is not None else q), ("k_stride", k),
+                    ("v_stride", v), ("o_stride", out)):
+        setattr(a, name, (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2)))
+    a.scale = float(scale)
+    a.causal = 1 if causal else 0
+    a.use_r = 1 if use_r else 0
+    a.dtype = _dtype_code(q)
+    return a
+
+
+def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None):
+    """Parallax prefill forward over T query rows and T keys."""
+    for t in (q, k, v) + ((r,) if r is not None else ()):
+        if not t.is_cuda:
+            raise ValueError("parallax_prefill needs device tensors")
+        if t.stride(-1) != 1:
+            raise ValueError("the last dimension must be contiguous")
+    if k.shape[2] != q.shape[2]:
+        raise ValueError("prefill takes T query rows and T keys")
+    if out is None:
+        out = torch.empty_like(q)
+    a = prefill_args(q, r, k, v, out, scale, causal, use_r)
+    st = load_library().parallax_prefill(ctypes.byref(a), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_prefill")
+    return out
+
+
+def parallax_util_copy(dst, src, stream=None):
+    nbytes = src.numel() * src.element_size()
+    st = load_library().parallax_util_copy(dst.data_ptr(), src.data_ptr(), nbytes,
+                                           _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_util_copy")
+    return dst
+
+
+def parallax_util_read(src, sink, stream=None):
+    nbytes = src.numel() * src.element_size()
+    st = load_library().parallax_util_read(src.data_ptr(), nbytes, sink.data_ptr(),
+                                           _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_util_read")
+    return sink
+
+
+def parallax_util_read_sink_slots() -> int:
+    return int(load_library().parallax_util_read_sink_slots())

@@ -1,0 +1,319 @@
+// Split-KV Parallax decode for bf16 K/V caches on gfx950, plus the combine kernel.
+//
+// What it computes: Algorithm 1 of the paper (Sec. 3.3) for one query row per head -- running
+// state (m, d1, d2, O1, O2) over key tiles, S2 = R K^T unscaled, P2 = P1 * S2 -- with the key
+// range of each sequence cut into S splits whose unnormalised partials are merged by a
+// log-sum-exp rescale and finished with O1/d1 * (1 + d2/d1) - O2/d1 (App. C).
+//
+// How it is laid out for CDNA4 (not the paper's Hopper prototype):
+//   * grid (split, kv head, batch), 4 waves per workgroup. Every wave streams its own 32-key
+//     tiles (wave w takes tiles w, w+4, ... of the split) with private running state, so the
+//     main loop has no workgroup barrier; the four states are merged through LDS at the end.
+//   * K and V rows are fetched with 16-byte-per-lane loads in which 16 consecutive lanes cover
+//     one 256-byte row (fully coalesced), parked in registers one tile ahead, then written to
+//     a per-wave LDS tile with an XOR chunk swizzle and re-read in MFMA operand order.
+//   * scores are produced transposed, S^T = K [Q;R]^T, with v_mfma_f32_16x16x32_bf16: the K
+//     fragment is the A operand and is used twice (once against the q columns, once against
+//     the r columns), the G query heads of the GQA group are the live columns. The accumulator
+//     layout of S^T (lane = column, 4 consecutive keys per lane) is already the B-operand
+//     layout of the second contraction O^T = V^T P^T, so P1 and P2 = P1*S2 never leave their
+//     lane; only the running max needs a cross-lane exchange.
+//   * all state is fp32; P1 and P2 are rounded to bf16 only as MFMA operands.
+#include "plx_device.h"
+#include "plx_kernels.h"
+
+namespace plx {
+
+constexpr int kTileKeys = 32;  // keys per wave tile
+constexpr int kWaves = 4;      // waves per workgroup
+static_assert(kTileKeys * kWaves == kDecodeBlockKeys, "block tile = waves x wave tile");
+
+template <int D, bool USE_R>
+__global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
+    constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
+    constexpr int KPI = 64 / CPR;         // rows covered by one wave-wide 16-byte load
+    constexpr int NLD = kTileKeys / KPI;  // loads per lane per tile and tensor
+    constexpr int KSTEPS = D / 32;        // MFMA k-steps over the head dimension
+    constexpr int NDB = D / 16;           // 16-wide blocks of output dimensions
+    constexpr int TILE_CHUNKS = kTileKeys * CPR;
+
+    __shared__ u32x4 lds[kWaves * 2 * TILE_CHUNKS];
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, lane = tid & 63;
+    const int c = lane & 15;   // MFMA column: query head within the GQA group (live if c < G)
+    const int g = lane >> 4;   // 16-lane row of the wave
+    const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int G = p.G, S = p.S;
+
+    int Lb = p.seq_lens ? p.seq_lens[b] : p.Lmax;
+    Lb = min(max(Lb, 0), p.Lmax);
+    const int n_bt = (Lb + kDecodeBlockKeys - 1) / kDecodeBlockKeys;
+    const int bt_per_split = (n_bt + S - 1) / S;
+    const int key_lo = split * bt_per_split * kDecodeBlockKeys;
+    const int key_hi = min(key_lo + bt_per_split * kDecodeBlockKeys, Lb);
+
+    // ---- B operands: q and r rows of the group's heads, zero in the dead columns ----------
+    const bool live = c < G;
+    u32x4 qf[KSTEPS], rf[KSTEPS];
+    {
+        const int64_t row = ((int64_t)b * p.Hq + (int64_t)hk * G + (live ? c : 0)) * D;
+        const __bf16 *qrow = (const __bf16 *)p.q + row;
+        const __bf16 *rrow = (const __bf16 *)p.r + row;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            qf[s] = live ? *(const u32x4 *)(qrow + 8 * (4 * s + g)) : z;
+            if constexpr (USE_R) rf[s] = live ? *(const u32x4 *)(rrow + 8 * (4 * s + g)) : z;
+        }
+    }
+
+    const __bf16 *kbase = (const __bf16 *)p.k + (int64_t)b * p.ksb + (int64_t)hk * p.ksh;
+    const __bf16 *vbase = (const __bf16 *)p.v + (int64_t)b * p.vsb + (int64_t)hk * p.vsh;
+    u32x4 *ldsK = lds + w * (2 * TILE_CHUNKS);
+    u32x4 *ldsV = ldsK + TILE_CHUNKS;
+    const unsigned short *ldsV16 = (const unsigned short *)ldsV;
+
+    const int ld_row = lane / CPR, ld_chunk = lane % CPR;  // this lane's place in a load
+    u32x4 kst[NLD], vst[NLD];
+    auto issue_loads = [&](int tk0) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            // rows past the sequence end re-read its last row (finite data, masked below)
+            const int key = min(tk0 + i * KPI + ld_row, Lb - 1);
+            kst[i] = *(const u32x4 *)(kbase + (int64_t)key * p.ksl + ld_chunk * 8);
+            vst[i] = *(const u32x4 *)(vbase + (int64_t)key * p.vsl + ld_chunk * 8);
+        }
+    };
+
+    // ---- running state (per lane: column c, partial over this lane's keys) ----------------
+    float m_run = kNegInf, dsum1 = 0.f, dsum2 = 0.f;
+    f32x4 o1[NDB], o2[NDB];
+#pragma unroll
+    for (int n = 0; n < NDB; ++n) {
+        o1[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+        o2[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const float scale_log2 = p.scale * kLog2e;
+
+    int tk = key_lo + w * kTileKeys;
+    if (tk < key_hi) issue_loads(tk);
+    for (; tk < key_hi; tk += kWaves * kTileKeys) {
+        // registers -> swizzled LDS tile (private to this wave)
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int slot = lds_chunk_slot<D>(i * KPI + ld_row, ld_chunk);
+            ldsK[slot] = kst[i];
+            ldsV[slot] = vst[i];
+        }
+        const int tk_next = tk + kWaves * kTileKeys;
+        if (tk_next < key_hi) issue_loads(tk_next);
+        // lanes exchange data through LDS inside one wave: LDS executes a wave's accesses in
+        // order, the fence only stops the compiler from moving reads above the writes
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // ---- S1^T = K q^T, S2^T = K r^T : 2 sub-tiles of 16 keys ---------------------------
+        f32x4 s1[2], s2[2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            s1[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
+            s2[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const u32x4 kf = ldsK[lds_chunk_slot<D>(16 * sub + c, 4 * s + g)];
+                s1[sub] = mfma16(kf, qf[s], s1[sub]);
+                if constexpr (USE_R) s2[sub] = mfma16(kf, rf[s], s2[sub]);
+            }
+        }
+
+        // ---- online softmax on this lane's 8 keys (key = tk + 16*sub + 4*g + i) ------------
+        float x[2][4];
+        float tmax = kNegInf;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int key = tk + 16 * sub + 4 * g + i;
+                x[sub][i] = key < key_hi ? s1[sub][i] * scale_log2 : kNegInf;
+                tmax = fmaxf(tmax, x[sub][i]);
+            }
+        tmax = rows_max(tmax);
+        const float m_new = fmaxf(m_run, tmax);
+        const float m_use = m_new == kNegInf ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run - m_use);  // 0 on the first live tile
+        m_run = m_new;
+        // P1, P2 are rounded to bf16 once (they are MFMA operands) and the row sums d1, d2 add
+        // the ROUNDED values: numerators and denominators then use identical weights, so the
+        // effective attention weights still sum to one exactly.
+        // B operand k-element e of lane (c, g) is key 4g+e (e<4) or 16+4g+(e-4): exactly the
+        // keys this lane already holds from the two S^T accumulators.
+        float p1[2][4];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) p1[sub][i] = fast_exp2(x[sub][i] - m_use);  // 0 if masked
+        const u32x4 pb1 = {pack_bf16(p1[0][0], p1[0][1]), pack_bf16(p1[0][2], p1[0][3]),
+                           pack_bf16(p1[1][0], p1[1][1]), pack_bf16(p1[1][2], p1[1][3])};
+        dsum1 = alpha * dsum1 + sum_bf16x8(pb1);
+        u32x4 pb2 = {0u, 0u, 0u, 0u};
+        if constexpr (USE_R) {
+            float p2[2][4];
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    p2[sub][i] = x[sub][i] == kNegInf ? 0.f : p1[sub][i] * s2[sub][i];
+            pb2 = u32x4{pack_bf16(p2[0][0], p2[0][1]), pack_bf16(p2[0][2], p2[0][3]),
+                        pack_bf16(p2[1][0], p2[1][1]), pack_bf16(p2[1][2], p2[1][3])};
+            dsum2 = alpha * dsum2 + sum_bf16x8(pb2);
+        }
+
+        if (!__all(alpha == 1.f)) {
+#pragma unroll
+            for (int n = 0; n < NDB; ++n) {
+                o1[n] *= alpha;
+                if constexpr (USE_R) o2[n] *= alpha;
+            }
+        }
+
+        // ---- O1^T += V^T P1^T, O2^T += V^T P2^T -------------------------------------------
+        // A operand: row = output dimension 16n + c, k-elements = the same 8 keys, fetched
+        // with two transposing LDS reads (keys 4g..4g+3 and 16+4g..16+4g+3).
+        {
+            const int tr_key = 4 * g + (c >> 2);          // row this lane addresses
+            const int tr_half = (c & 1) * 4;              // element offset inside the chunk
+#pragma unroll
+            for (int n = 0; n < NDB; ++n) {
+                const int chunk = 2 * n + ((c & 3) >> 1);
+                const u32x2 lo = lds_read_tr16(ldsV16 + lds_chunk_slot<D>(tr_key, chunk) * 8 + tr_half);
+                const u32x2 hi =
+                    lds_read_tr16(ldsV16 + lds_chunk_slot<D>(16 + tr_key, chunk) * 8 + tr_half);
+                const u32x4 vt = {lo[0], lo[1], hi[0], hi[1]};
+                o1[n] = mfma16(vt, pb1, o1[n]);
+                if constexpr (USE_R) o2[n] = mfma16(vt, pb2, o2[n]);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- wave partial -> LDS; merge the 4 waves; write the split partial or the output ----
+    dsum1 = rows_sum(dsum1);
+    dsum2 = rows_sum(dsum2);
+    __syncthreads();  // every wave is done with its tile buffers
+    float *mrg = (float *)lds;
+    float *mrg_m = mrg;                        // [kWaves][16]
+    float *mrg_d1 = mrg + kWaves * 16;         // [kWaves][16]
+    float *mrg_d2 = mrg + 2 * kWaves * 16;     // [kWaves][16]
+    float *mrg_o1 = mrg + 3 * kWaves * 16;     // [kWaves][G][D]
+    float *mrg_o2 = mrg_o1 + kWaves * G * D;   // [kWaves][G][D]
+    if (live) {
+        if (g == 0) {
+            mrg_m[w * 16 + c] = m_run;
+            mrg_d1[w * 16 + c] = dsum1;
+            mrg_d2[w * 16 + c] = dsum2;
+        }
+#pragma unroll
+        for (int n = 0; n < NDB; ++n)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int dim = 16 * n + 4 * g + i;  // accumulator row of O^T
+                mrg_o1[(w * G + c) * D + dim] = o1[n][i];
+                mrg_o2[(w * G + c) * D + dim] = USE_R ? o2[n][i] : 0.f;
+            }
+    }
+    __syncthreads();
+
+    for (int idx = tid; idx < G * D; idx += 256) {
+        const int hh = idx / D, dim = idx - hh * D;
+        float m_star = kNegInf;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) m_star = fmaxf(m_star, mrg_m[ww * 16 + hh]);
+        float d1 = 0.f, d2 = 0.f, a1 = 0.f, a2 = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) {
+            const float mw = mrg_m[ww * 16 + hh];
+            const float wt = mw == kNegInf ? 0.f : fast_exp2(mw - m_star);
+            d1 += wt * mrg_d1[ww * 16 + hh];
+            d2 += wt * mrg_d2[ww * 16 + hh];
+            a1 += wt * mrg_o1[(ww * G + hh) * D + dim];
+            a2 += wt * mrg_o2[(ww * G + hh) * D + dim];
+        }
+        const int64_t hq = (int64_t)b * p.Hq + (int64_t)hk * G + hh;
+        if (S == 1) {
+            float out = 0.f;  // empty key set: zeros
+            if (d1 > 0.f) {
+                const float inv = 1.f / d1;
+                out = a1 * inv * (1.f + d2 * inv) - a2 * inv;
+            }
+            ((__bf16 *)p.o)[hq * D + dim] = (__bf16)out;
+        } else {
+            float *rec = p.ws + (hq * S + split) * (int64_t)(2 * D + 4);
+            if (dim == 0) {
+                rec[0] = m_star;
+                rec[1] = d1;
+                rec[2] = d2;
+                rec[3] = 0.f;
+            }
+            rec[4 + dim] = a1;
+            rec[4 + D + dim] = a2;
+        }
+    }
+}
+
+// Merge the S split partials of one (batch, query head): m* = max_s m_s, weights
+// exp2(m_s - m*), then the closing formula of Algorithm 1. One thread per output dimension.
+template <int D>
+__global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams p) {
+    const int dim = threadIdx.x;
+    const int64_t hq = (int64_t)blockIdx.y * p.Hq + blockIdx.x;
+    const int S = p.S;
+    const float *rec0 = p.ws + hq * S * (int64_t)(2 * D + 4);
+    float m_star = kNegInf;
+    for (int s = 0; s < S; ++s) m_star = fmaxf(m_star, rec0[(int64_t)s * (2 * D + 4)]);
+    float d1 = 0.f, d2 = 0.f, a1 = 0.f, a2 = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const float *rec = rec0 + (int64_t)s * (2 * D + 4);
+        const float ms = rec[0];
+        const float wt = ms == kNegInf ? 0.f : fast_exp2(ms - m_star);
+        d1 += wt * rec[1];
+        d2 += wt * rec[2];
+        a1 += wt * rec[4 + dim];
+        a2 += wt * rec[4 + D + dim];
+    }
+    float out = 0.f;
+    if (d1 > 0.f) {
+        const float inv = 1.f / d1;
+        out = a1 * inv * (1.f + d2 * inv) - a2 * inv;
+    }
+    ((__bf16 *)p.o)[hq * D + dim] = (__bf16)out;
+}
+
+hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream) {
+    const dim3 grid(p.S, p.Hkv, p.B), block(256);
+    if (p.d == 128) {
+        if (p.use_r)
+            hipLaunchKernelGGL((decode_bf16_kernel<128, true>), grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((decode_bf16_kernel<128, false>), grid, block, 0, stream, p);
+    } else {
+        if (p.use_r)
+            hipLaunchKernelGGL((decode_bf16_kernel<64, true>), grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((decode_bf16_kernel<64, false>), grid, block, 0, stream, p);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_combine(const DecodeParams &p, hipStream_t stream) {
+    const dim3 grid(p.Hq, p.B);
+    if (p.d == 128)
+        hipLaunchKernelGGL((decode_combine_kernel<128>), grid, dim3(128), 0, stream, p);
+    else
+        hipLaunchKernelGGL((decode_combine_kernel<64>), grid, dim3(64), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace plx

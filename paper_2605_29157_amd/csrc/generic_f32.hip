@@ -1,0 +1,154 @@
+// fp32 Parallax forward for decode and prefill: a plain, untuned correctness path
+// (one workgroup per query row, vector ALU only). It follows Algorithm 1 of the paper
+// (Sec. 3.3) over key tiles of 256 with the running state (m, d1, d2, O1, O2) and closes with
+// O1/d1 * (1 + d2/d1) - O2/d1. The tuned kernels are the bf16 MFMA ones.
+#include "plx_device.h"
+#include "plx_kernels.h"
+
+namespace plx {
+
+struct GenericParams {
+    const float *q, *r, *k, *v;
+    float *o;
+    const int32_t *seq_lens;
+    int32_t B, Hq, Hkv, G, Tq, Lk, d;
+    int64_t qs[3], rs[3], ks[3], vs[3], os[3];
+    float scale;
+    int32_t causal, use_r;
+};
+
+constexpr int kGenThreads = 256;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams p) {
+    __shared__ float sq[256], sr[256], sp1[kGenThreads], sp2[kGenThreads];
+    __shared__ float red[3][kGenThreads / 64];
+
+    const int t = threadIdx.x, wv = t >> 6, ln = t & 63;
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / p.G, d = p.d;
+    int n_keys;
+    if (p.causal)
+        n_keys = i + 1;
+    else
+        n_keys = p.seq_lens ? min(max(p.seq_lens[b], 0), p.Lk) : p.Lk;
+
+    const float *qrow = p.q + b * p.qs[0] + h * p.qs[1] + i * p.qs[2];
+    const float *rrow = p.r ? p.r + b * p.rs[0] + h * p.rs[1] + i * p.rs[2] : nullptr;
+    const float *kb = p.k + b * p.ks[0] + hk * p.ks[1];
+    const float *vb = p.v + b * p.vs[0] + hk * p.vs[1];
+    if (t < d) {
+        sq[t] = qrow[t];
+        sr[t] = (p.use_r && rrow) ? rrow[t] : 0.f;
+    }
+    __syncthreads();
+
+    const float scale_log2 = p.scale * kLog2e;
+    float m_run = kNegInf, d1 = 0.f, d2 = 0.f, o1 = 0.f, o2 = 0.f;  // o1/o2: dimension t
+
+    for (int j0 = 0; j0 < n_keys; j0 += kGenThreads) {
+        const int j = j0 + t;
+        const bool valid = j < n_keys;
+        float s1 = kNegInf, s2 = 0.f;
+        if (valid) {
+            const float *kj = kb + (int64_t)j * p.ks[2];
+            float a1 = 0.f, a2 = 0.f;
+            for (int c = 0; c < d; ++c) {
+                const float kv = kj[c];
+                a1 = fmaf(sq[c], kv, a1);
+                a2 = fmaf(sr[c], kv, a2);
+            }
+            s1 = a1 * scale_log2;
+            s2 = a2;
+        }
+        float tm = wave_max(s1);
+        if (ln == 0) red[0][wv] = tm;
+        __syncthreads();
+        tm = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+        const float m_new = fmaxf(m_run, tm);  // finite: the tile has at least one valid key
+        const float alpha = exp2f(m_run - m_new);
+        m_run = m_new;
+        const float p1 = valid ? exp2f(s1 - m_new) : 0.f;
+        const float p2 = valid ? p1 * s2 : 0.f;
+        sp1[t] = p1;
+        sp2[t] = p2;
+        const float w1 = wave_sum(p1), w2 = wave_sum(p2);
+        if (ln == 0) {
+            red[1][wv] = w1;
+            red[2][wv] = w2;
+        }
+        __syncthreads();
+        d1 = alpha * d1 + (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+        d2 = alpha * d2 + (red[2][0] + red[2][1]) + (red[2][2] + red[2][3]);
+        if (t < d) {
+            o1 *= alpha;
+            o2 *= alpha;
+            const int n = min(kGenThreads, n_keys - j0);
+            for (int jj = 0; jj < n; ++jj) {
+                const float vv = vb[(int64_t)(j0 + jj) * p.vs[2] + t];
+                o1 = fmaf(sp1[jj], vv, o1);
+                o2 = fmaf(sp2[jj], vv, o2);
+            }
+        }
+        __syncthreads();  // sp1/sp2/red are rewritten by the next tile
+    }
+
+    if (t < d) {
+        float out = 0.f;  // empty key set: zeros
+        if (d1 > 0.f) out = (o1 / d1) * (1.f + d2 / d1) - o2 / d1;
+        p.o[b * p.os[0] + h * p.os[1] + i * p.os[2] + t] = out;
+    }
+}
+
+static hipError_t launch_generic(const GenericParams &g, hipStream_t stream) {
+    const dim3 grid(g.Tq, g.Hq, g.B);
+    hipLaunchKernelGGL(generic_f32_kernel, grid, dim3(kGenThreads), 0, stream, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream) {
+    GenericParams g{};
+    g.q = (const float *)p.q;
+    g.r = (const float *)p.r;
+    g.k = (const float *)p.k;
+    g.v = (const float *)p.v;
+    g.o = (float *)p.o;
+    g.seq_lens = p.seq_lens;
+    g.B = p.B, g.Hq = p.Hq, g.Hkv = p.Hkv, g.G = p.G, g.Tq = 1, g.Lk = p.Lmax, g.d = p.d;
+    g.qs[0] = g.rs[0] = g.os[0] = (int64_t)p.Hq * p.d;
+    g.qs[1] = g.rs[1] = g.os[1] = p.d;
+    g.qs[2] = g.rs[2] = g.os[2] = 0;
+    g.ks[0] = p.ksb, g.ks[1] = p.ksh, g.ks[2] = p.ksl;
+    g.vs[0] = p.vsb, g.vs[1] = p.vsh, g.vs[2] = p.vsl;
+    g.scale = p.scale, g.causal = 0, g.use_r = p.use_r;
+    return launch_generic(g, stream);
+}
+
+hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream) {
+    GenericParams g{};
+    g.q = (const float *)p.q;
+    g.r = (const float *)p.r;
+    g.k = (const float *)p.k;
+    g.v = (const float *)p.v;
+    g.o = (float *)p.o;
+    g.seq_lens = nullptr;
+    g.B = p.B, g.Hq = p.Hq, g.Hkv = p.Hkv, g.G = p.G, g.Tq = p.T, g.Lk = p.T, g.d = p.d;
+    for (int a = 0; a < 3; ++a) {
+        g.qs[a] = p.qs[a], g.rs[a] = p.rs[a], g.ks[a] = p.ks[a], g.vs[a] = p.vs[a];
+        g.os[a] = p.os[a];
+    }
+    g.scale = p.scale, g.causal = p.causal, g.use_r = p.use_r;
+    return launch_generic(g, stream);
+}
+
+}  // namespace plx

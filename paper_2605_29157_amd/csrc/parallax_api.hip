@@ -1,0 +1,202 @@
+// C ABI of the Parallax attention library: argument validation, split heuristic, dispatch.
+// Everything is checked on the host before the first launch; no call allocates or synchronises.
+#include "../../include/parallax.h"
+
+#include <hip/hip_runtime.h>
+
+#include "plx_kernels.h"
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int elem_size(plx_dtype t) { return t == PLX_BF16 ? 2 : 4; }
+
+bool stride_aligned(int64_t stride_elems, plx_dtype t) {
+    return ((stride_elems * elem_size(t)) & 15) == 0;
+}
+
+plx_status check_common(plx_dtype dtype, int32_t B, int32_t Hq, int32_t Hkv, int32_t len,
+                        int32_t d) {
+    if (dtype != PLX_BF16 && dtype != PLX_F32) return PLX_ERR_DTYPE;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || len <= 0 || d <= 0) return PLX_ERR_SHAPE;
+    if (B > 65535 || Hq > 65535) return PLX_ERR_SHAPE;
+    if (Hq % Hkv != 0) return PLX_ERR_SHAPE;
+    if (dtype == PLX_BF16) {
+        if (d != 64 && d != 128) return PLX_ERR_SHAPE;
+        if (Hq / Hkv > 8) return PLX_ERR_SHAPE;
+    } else {
+        if (d > 256 || d % 4 != 0) return PLX_ERR_SHAPE;
+    }
+    return PLX_OK;
+}
+
+int query_num_cus() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus <= 0)
+        return 256;
+    return cus;
+}
+
+size_t ws_bytes(int64_t B, int64_t Hq, int64_t S, int64_t d) {
+    return (size_t)(B * Hq * S * (2 * d + 4)) * sizeof(float);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t parallax_decode_workspace_bytes(int32_t B, int32_t Hq, int32_t Hkv, int32_t Lmax,
+                                       int32_t d) {
+    (void)Hkv;
+    (void)Lmax;
+    if (B <= 0 || Hq <= 0 || d <= 0) return 0;
+    return ws_bytes(B, Hq, PLX_MAX_SPLITS, d);
+}
+
+int32_t parallax_decode_num_splits(int32_t B, int32_t Hq, int32_t Hkv, int32_t Lmax, int32_t d,
+                                   int32_t num_cus) {
+    (void)d;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Lmax <= 0) return 1;
+    if (num_cus <= 0) num_cus = query_num_cus();
+    // Two workgroups are resident per compute unit; aim at two rounds of them so that the
+    // tail of a ragged batch is filled, and bound the work of one split to 4096 keys.
+    const int64_t pairs = (int64_t)B * Hkv;
+    const int64_t target = 4LL * num_cus;
+    int64_t s = (target + pairs - 1) / pairs;
+    const int64_t by_len = ((int64_t)Lmax + 4095) / 4096;
+    if (s < by_len) s = by_len;
+    // ... but keep at least two 128-key block tiles per split
+    const int64_t n_bt = ((int64_t)Lmax + plx::kDecodeBlockKeys - 1) / plx::kDecodeBlockKeys;
+    int64_t cap = n_bt / 2;
+    if (cap < 1) cap = 1;
+    if (s > cap) s = cap;
+    if (s > PLX_MAX_SPLITS) s = PLX_MAX_SPLITS;
+    if (s < 1) s = 1;
+    return (int32_t)s;
+}
+
+plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
+    if (!a) return PLX_ERR_NULL;
+    if (!a->q || !a->k || !a->v || !a->o) return PLX_ERR_NULL;
+    if (a->use_r && !a->r) return PLX_ERR_NULL;
+    plx_status st = check_common(a->dtype, a->B, a->Hq, a->Hkv, a->Lmax, a->d);
+    if (st != PLX_OK) return st;
+    if (a->num_splits < 0 || a->num_splits > PLX_MAX_SPLITS) return PLX_ERR_SPLITS;
+    if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || !aligned16(a->o) ||
+        (a->r && !aligned16(a->r)))
+        return PLX_ERR_ALIGN;
+    if (a->seq_lens && (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u)) return PLX_ERR_ALIGN;
+    const int64_t strides[6] = {a->k_stride_b, a->k_stride_h, a->k_stride_l,
+                                a->v_stride_b, a->v_stride_h, a->v_stride_l};
+    for (int64_t s : strides) {
+        if (s < 0) return PLX_ERR_SHAPE;
+        if (!stride_aligned(s, a->dtype)) return PLX_ERR_ALIGN;
+    }
+    if (a->k_stride_l < a->d || a->v_stride_l < a->d) return PLX_ERR_SHAPE;
+    if (((int64_t)a->d * elem_size(a->dtype)) % 16 != 0) return PLX_ERR_ALIGN;
+
+    plx::DecodeParams p{};
+    p.q = a->q, p.r = a->use_r ? a->r : a->q, p.k = a->k, p.v = a->v, p.o = a->o;
+    p.seq_lens = a->seq_lens;
+    p.B = a->B, p.Hq = a->Hq, p.Hkv = a->Hkv, p.G = a->Hq / a->Hkv, p.Lmax = a->Lmax, p.d = a->d;
+    p.ksb = a->k_stride_b, p.ksh = a->k_stride_h, p.ksl = a->k_stride_l;
+    p.vsb = a->v_stride_b, p.vsh = a->v_stride_h, p.vsl = a->v_stride_l;
+    p.scale = a->scale, p.use_r = a->use_r ? 1 : 0;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    if (a->dtype == PLX_F32) {
+        p.S = 1;
+        p.r = a->r;
+        return plx::launch_decode_f32(p, stream) == hipSuccess ? PLX_OK : PLX_ERR_LAUNCH;
+    }
+
+    int32_t S = a->num_splits;
+    if (S == 0) S = parallax_decode_num_splits(a->B, a->Hq, a->Hkv, a->Lmax, a->d, 0);
+    p.S = S;
+    if (S > 1) {
+        if (!a->workspace || !aligned16(a->workspace)) return PLX_ERR_WORKSPACE;
+        if (a->workspace_bytes < ws_bytes(a->B, a->Hq, S, a->d)) return PLX_ERR_WORKSPACE;
+        p.ws = static_cast<float *>(a->workspace);
+    }
+    if (plx::launch_decode_bf16(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
+    if (S > 1 && plx::launch_decode_combine(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
+    return PLX_OK;
+}
+
+plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
+    if (!a) return PLX_ERR_NULL;
+    if (!a->q || !a->k || !a->v || !a->o) return PLX_ERR_NULL;
+    if (a->use_r && !a->r) return PLX_ERR_NULL;
+    plx_status st = check_common(a->dtype, a->B, a->Hq, a->Hkv, a->T, a->d);
+    if (st != PLX_OK) return st;
+    if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || !aligned16(a->o) ||
+        (a->r && !aligned16(a->r)))
+        return PLX_ERR_ALIGN;
+    if (((int64_t)a->d * elem_size(a->dtype)) % 16 != 0) return PLX_ERR_ALIGN;
+    const int64_t *sets[5] = {a->q_stride, a->r_stride, a->k_stride, a->v_stride, a->o_stride};
+    for (int t = 0; t < 5; ++t) {
+        if (t == 1 && !a->use_r) continue;
+        for (int j = 0; j < 3; ++j) {
+            if (sets[t][j] < 0) return PLX_ERR_SHAPE;
+            if (!stride_aligned(sets[t][j], a->dtype)) return PLX_ERR_ALIGN;
+        }
+        if (sets[t][2] < a->d) return PLX_ERR_SHAPE;
+    }
+
+    plx::PrefillParams p{};
+    p.q = a->q, p.r = a->use_r ? a->r : a->q, p.k = a->k, p.v = a->v, p.o = a->o;
+    p.B = a->B, p.Hq = a->Hq, p.Hkv = a->Hkv, p.G = a->Hq / a->Hkv, p.T = a->T, p.d = a->d;
+    for (int j = 0; j < 3; ++j) {
+        p.qs[j] = a->q_stride[j];
+        p.rs[j] = a->use_r ? a->r_stride[j] : a->q_stride[j];
+        p.ks[j] = a->k_stride[j];
+        p.vs[j] = a->v_stride[j];
+        p.os[j] = a->o_stride[j];
+    }
+    p.scale = a->scale, p.causal = a->causal ? 1 : 0, p.use_r = a->use_r ? 1 : 0;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t err = a->dtype == PLX_F32 ? plx::launch_prefill_f32(p, stream)
+                                         : plx::launch_prefill_bf16(p, stream);
+    return err == hipSuccess ? PLX_OK : PLX_ERR_LAUNCH;
+}
+
+plx_status parallax_util_copy(void *dst, const void *src, size_t bytes, void *hip_stream) {
+    if (!dst || !src) return PLX_ERR_NULL;
+    if (bytes % 16 != 0) return PLX_ERR_SHAPE;
+    if (!aligned16(dst) || !aligned16(src)) return PLX_ERR_ALIGN;
+    return plx::launch_util_copy(dst, src, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
+}
+
+plx_status parallax_util_read(const void *src, size_t bytes, void *sink, void *hip_stream) {
+    if (!src || !sink) return PLX_ERR_NULL;
+    if (bytes % 16 != 0) return PLX_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(sink)) return PLX_ERR_ALIGN;
+    return plx::launch_util_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
+}
+
+int32_t parallax_util_read_sink_slots(void) { return plx::kReadSinkSlots; }
+
+const char *parallax_strerror(plx_status status) {
+    switch (status) {
+        case PLX_OK: return "ok";
+        case PLX_ERR_NULL: return "a required pointer is NULL";
+        case PLX_ERR_SHAPE: return "unsupported or inconsistent shape / stride";
+        case PLX_ERR_DTYPE: return "unknown dtype";
+        case PLX_ERR_ALIGN: return "pointer or stride is not 16-byte aligned";
+        case PLX_ERR_WORKSPACE: return "split-KV workspace missing, misaligned or too small";
+        case PLX_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+        case PLX_ERR_SPLITS: return "num_splits outside [0, PLX_MAX_SPLITS]";
+    }
+    return "unknown status";
+}
+
+int parallax_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,41 @@
+// Host-side launch interface between the C ABI (parallax_api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace plx {
+
+// Keys handled by one workgroup iteration of the bf16 decode kernel (4 waves x 32 keys).
+constexpr int kDecodeBlockKeys = 128;
+
+struct DecodeParams {
+    const void *q, *r, *k, *v;
+    void *o;
+    const int32_t *seq_lens;
+    float *ws;  // split partials: [B][Hq][S] records of (2d+4) floats
+    int32_t B, Hq, Hkv, G, Lmax, d, S;
+    int64_t ksb, ksh, ksl, vsb, vsh, vsl;  // element strides
+    float scale;
+    int32_t use_r;
+};
+
+struct PrefillParams {
+    const void *q, *r, *k, *v;
+    void *o;
+    int32_t B, Hq, Hkv, G, T, d;
+    int64_t qs[3], rs[3], ks[3], vs[3], os[3];  // element strides {batch, head, row}
+    float scale;
+    int32_t causal, use_r;
+};
+
+// Each returns hipSuccess or the launch error. No allocation, no synchronisation.
+hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream);
+hipError_t launch_decode_combine(const DecodeParams &p, hipStream_t stream);
+hipError_t launch_prefill_bf16(const PrefillParams &p, hipStream_t stream);
+hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream);
+hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream);
+hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);
+hipError_t launch_util_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
+constexpr int kReadSinkSlots = 4096;
+
+}  // namespace plx

@@ -1,0 +1,54 @@
+// Plain streaming kernels: a device-to-device copy (calibrates hardware byte counters against
+// a known size) and a read-only stream (achievable HBM read bandwidth next to the attention
+// kernels). 16 bytes per lane, grid-stride.
+#include "plx_device.h"
+#include "plx_kernels.h"
+
+namespace plx {
+
+__global__ __launch_bounds__(256) void util_copy_kernel(u32x4 *dst, const u32x4 *src, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void util_read_kernel(const u32x4 *src, size_t n, u32x4 *sink) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    // four independent 16-byte loads per lane and trip keep several KB per wave in flight
+    for (size_t i = (size_t)blockIdx.x * blockDim.x * 4 + threadIdx.x; i < n; i += stride) {
+        u32x4 a = src[i];
+        u32x4 b = i + 256 < n ? src[i + 256] : u32x4{0u, 0u, 0u, 0u};
+        u32x4 c = i + 512 < n ? src[i + 512] : u32x4{0u, 0u, 0u, 0u};
+        u32x4 d = i + 768 < n ? src[i + 768] : u32x4{0u, 0u, 0u, 0u};
+        acc ^= a ^ b ^ c ^ d;
+    }
+    // fold the workgroup into one value so the loads cannot be dropped
+    __shared__ u32x4 part[256];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32x4 t = {0u, 0u, 0u, 0u};
+        for (int j = 0; j < 256; ++j) t ^= part[j];
+        sink[blockIdx.x] = t;
+    }
+}
+
+hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream) {
+    const size_t n = bytes / 16;
+    if (n == 0) return hipSuccess;
+    const size_t want = (n + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
+    hipLaunchKernelGGL(util_copy_kernel, dim3(blocks), dim3(256), 0, stream, (u32x4 *)dst,
+                       (const u32x4 *)src, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_util_read(const void *src, size_t bytes, void *sink, hipStream_t stream) {
+    const size_t n = bytes / 16;
+    hipLaunchKernelGGL(util_read_kernel, dim3(kReadSinkSlots), dim3(256), 0, stream,
+                       (const u32x4 *)src, n, (u32x4 *)sink);
+    return hipGetLastError();
+}
+
+}  // namespace plx

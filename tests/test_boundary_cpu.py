@@ -1,0 +1,152 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2605_29157_amd import binding as b
+
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2605_29157_amd import build
+
+        build.build_library(verbose=False)
+    b.load_library()
+    return b
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "parallax.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(parallax_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(binding):
+    names = _declared_functions()
+    assert len(names) >= 9
+    lib = binding.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTED_SYMBOLS) == names
+
+
+def test_struct_sizes_match_c_layout(binding):
+    # 6 pointers, 5 int32 (+pad), 6 int64, float + 2 int32 (+pad), pointer, size_t, enum (+pad)
+    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8
+    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16
+
+
+def test_version_and_strerror(binding):
+    assert binding.version() >= 100
+    assert binding.strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert binding.strerror(code) not in ("ok", "unknown status")
+    assert binding.strerror(-99) == "unknown status"
+
+
+def test_workspace_bytes(binding):
+    n = binding.parallax_decode_workspace_bytes(8, 16, 8, 4096, 128)
+    assert n == 8 * 16 * binding.PLX_MAX_SPLITS * (2 * 128 + 4) * 4
+    assert binding.parallax_decode_workspace_bytes(0, 16, 8, 4096, 128) == 0
+
+
+def test_split_heuristic_is_sane(binding):
+    f = binding.parallax_decode_num_splits
+    # explicit CU count: pure host arithmetic
+    for (B, L) in [(1, 1024), (8, 4096), (16, 16384), (128, 65536), (32, 131072), (1, 1), (2, 100)]:
+        s = f(B, 16, 8, L, 128, 256)
+        assert 1 <= s <= binding.PLX_MAX_SPLITS
+        n_bt = (L + 127) // 128
+        assert s <= max(1, n_bt // 2)          # at least two block tiles per split
+        if L >= 2 * 4096:
+            assert s >= (L + 4095) // 4096 or s == binding.PLX_MAX_SPLITS
+    assert f(8, 16, 8, 4096, 128, 256) == 16   # 1024 workgroups over 64 (batch, kv head) pairs
+    assert f(1, 16, 8, 256, 128, 256) == 1
+
+
+def _good_decode_args(binding):
+    a = binding.plx_decode_args()
+    a.q = a.r = a.k = a.v = a.o = 0x1000
+    a.B, a.Hq, a.Hkv, a.Lmax, a.d = 2, 4, 2, 64, 128
+    a.k_stride_b, a.k_stride_h, a.k_stride_l = 2 * 64 * 128, 64 * 128, 128
+    a.v_stride_b, a.v_stride_h, a.v_stride_l = 2 * 64 * 128, 64 * 128, 128
+    a.scale, a.use_r, a.num_splits, a.dtype = 0.1, 1, 1, binding.PLX_BF16
+    return a
+
+
+def test_decode_rejects_bad_arguments_before_launch(binding):
+    lib = binding.load_library()
+    call = lambda a: lib.parallax_decode(ctypes.byref(a), None)
+    assert lib.parallax_decode(None, None) == binding.PLX_ERR_NULL
+    a = _good_decode_args(binding); a.k = None
+    assert call(a) == binding.PLX_ERR_NULL
+    a = _good_decode_args(binding); a.r = None
+    assert call(a) == binding.PLX_ERR_NULL
+    a = _good_decode_args(binding); a.Hq = 5
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = _good_decode_args(binding); a.d = 96
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = _good_decode_args(binding); a.Hq, a.Hkv = 32, 2      # G = 16 > 8
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = _good_decode_args(binding); a.Lmax = 0
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = _good_decode_args(binding); a.dtype = 7
+    assert call(a) == binding.PLX_ERR_DTYPE
+    a = _good_decode_args(binding); a.q = 0x1004
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = _good_decode_args(binding); a.k_stride_l = 132
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = _good_decode_args(binding); a.k_stride_l = 64
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = _good_decode_args(binding); a.num_splits = binding.PLX_MAX_SPLITS + 1
+    assert call(a) == binding.PLX_ERR_SPLITS
+    a = _good_decode_args(binding); a.num_splits = 4          # no workspace
+    assert call(a) == binding.PLX_ERR_WORKSPACE
+    a = _good_decode_args(binding); a.num_splits = 4
+    a.workspace, a.workspace_bytes = 0x2000, 16
+    assert call(a) == binding.PLX_ERR_WORKSPACE
+
+
+def test_prefill_rejects_bad_arguments_before_launch(binding):
+    lib = binding.load_library()
+
+    def good():
+        a = binding.plx_prefill_args()
+        a.q = a.r = a.k = a.v = a.o = 0x1000
+        a.B, a.Hq, a.Hkv, a.T, a.d = 1, 4, 2, 128, 128
+        for name, H in (("q_stride", 4), ("r_stride", 4), ("o_stride", 4), ("k_stride", 2),
+                        ("v_stride", 2)):
+            setattr(a, name, (ctypes.c_int64 * 3)(H * 128 * 128, 128 * 128, 128))
+        a.scale, a.causal, a.use_r, a.dtype = 0.1, 1, 1, binding.PLX_BF16
+        return a
+
+    call = lambda a: lib.parallax_prefill(ctypes.byref(a), None)
+    assert lib.parallax_prefill(None, None) == binding.PLX_ERR_NULL
+    a = good(); a.v = None
+    assert call(a) == binding.PLX_ERR_NULL
+    a = good(); a.Hkv = 3
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.d = 100
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.dtype = binding.PLX_F32; a.d = 260
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.o = 0x1008
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = good(); a.q_stride = (ctypes.c_int64 * 3)(4 * 128 * 128, 128 * 128, 130)
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = good(); a.k_stride = (ctypes.c_int64 * 3)(4 * 128 * 128, 128 * 128, 64)
+    assert call(a) == binding.PLX_ERR_SHAPE
+
+
+def test_util_argument_checks(binding):
+    lib = binding.load_library()
+    assert lib.parallax_util_copy(None, 0x1000, 16, None) == binding.PLX_ERR_NULL
+    assert lib.parallax_util_copy(0x1000, 0x2000, 10, None) == binding.PLX_ERR_SHAPE
+    assert lib.parallax_util_copy(0x1001, 0x2000, 16, None) == binding.PLX_ERR_ALIGN
+    assert binding.parallax_util_read_sink_slots() > 0

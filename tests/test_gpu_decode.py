@@ -1,0 +1,189 @@
+"""GPU parity of parallax_decode (through the C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from parity import BF16_REL_L2, F32_MAX_REL, host, max_rel, oracle_decode, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def plx():
+    from paper_2605_29157_amd import binding
+
+    binding.load_library()  # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def synth():
+    from paper_2605_29157_amd import synth as s
+
+    return s
+
+
+DEV = "cuda:0"
+
+
+def _run(plx, x, **kw):
+    out = plx.parallax_decode(x["q"], x["r"], x["k"], x["v"], x["scale"],
+                              seq_lens=x.get("seq_lens"), **kw)
+    torch.cuda.synchronize()
+    return host(out)
+
+
+def test_config2_decode_bf16_full(plx, synth, oracle):
+    """BASELINE config 2: B=8, 16 q heads / 8 kv heads, d=128, L=4096, library split heuristic
+    (the launch configuration bench.py times)."""
+    x = synth.decode_inputs(8, 16, 8, 4096, 128, seed=1002, device=DEV)
+    ref = oracle_decode(oracle, x)
+    got = _run(plx, x)
+    assert rel_l2(got, ref) <= BF16_REL_L2
+    assert max_rel(got, ref) <= 3e-2
+    # softmax-only twin == oracle with R = 0
+    got0 = _run(plx, x, use_r=False)
+    assert rel_l2(got0, oracle_decode(oracle, x, use_r=False)) <= BF16_REL_L2
+
+
+@pytest.mark.parametrize("L", [1, 2, 15, 16, 31, 32, 33, 127, 128, 129, 511, 1000])
+def test_lengths_and_tails(plx, synth, oracle, L):
+    x = synth.decode_inputs(2, 4, 2, L, 128, seed=200 + L, device=DEV)
+    ref = oracle_decode(oracle, x)
+    for S in (0, 1, 3):
+        got = _run(plx, x, num_splits=S)
+        assert rel_l2(got, ref) <= BF16_REL_L2, (L, S)
+    if L == 1:  # one key: the output is that value row exactly (bf16 in, bf16 out)
+        v = host(x["v"])[:, :, 0, :]
+        np.testing.assert_array_equal(_run(plx, x, num_splits=1), np.repeat(v, 2, axis=1))
+
+
+@pytest.mark.parametrize("S", [1, 2, 5, 16, 128])
+def test_split_counts_agree_incl_empty_splits(plx, synth, oracle, S):
+    x = synth.decode_inputs(3, 8, 4, 1500, 128, seed=31, device=DEV, ragged=True)
+    ref = oracle_decode(oracle, x)
+    got = _run(plx, x, num_splits=S)  # S=128 leaves most splits empty
+    assert rel_l2(got, ref) <= BF16_REL_L2
+
+
+def test_ragged_with_zero_length_sequence(plx, synth, oracle):
+    x = synth.decode_inputs(4, 4, 2, 700, 128, seed=41, device=DEV, ragged=True)
+    x["seq_lens"][1] = 0
+    x["seq_lens"][2] = 1
+    ref = oracle_decode(oracle, x)
+    for S in (1, 4):
+        got = _run(plx, x, num_splits=S)
+        assert np.all(got[1] == 0.0)  # documented reading of the empty key set
+        keep = [0, 2, 3]
+        assert rel_l2(got[keep], ref[keep]) <= BF16_REL_L2
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (8, 2), (8, 1), (6, 2)])
+def test_gqa_group_sizes(plx, synth, oracle, Hq, Hkv):
+    x = synth.decode_inputs(2, Hq, Hkv, 300, 128, seed=50 + Hq, device=DEV)
+    ref = oracle_decode(oracle, x)
+    got = _run(plx, x, num_splits=2)
+    assert rel_l2(got, ref) <= BF16_REL_L2
+
+
+def test_head_dim_64(plx, synth, oracle):
+    x = synth.decode_inputs(3, 8, 4, 777, 64, seed=64, device=DEV, ragged=True)
+    ref = oracle_decode(oracle, x)
+    for S in (1, 4):
+        assert rel_l2(_run(plx, x, num_splits=S), ref) <= BF16_REL_L2
+
+
+def test_strided_cache_layout(plx, synth, oracle):
+    """K/V stored as [B, L, Hkv, d] and passed as a permuted view (row stride = Hkv*d)."""
+    x = synth.decode_inputs(2, 4, 2, 400, 128, seed=71, device=DEV)
+    ref = oracle_decode(oracle, x)
+    xs = dict(x)
+    xs["k"] = x["k"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    xs["v"] = x["v"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert xs["k"].stride(2) == 2 * 128
+    assert rel_l2(_run(plx, xs, num_splits=2), ref) <= BF16_REL_L2
+
+
+def test_key_offset_and_small_probe(plx, synth, oracle):
+    """Keys with a common offset (the correction must centre them) and a probe scaled by 0.1."""
+    x = synth.decode_inputs(2, 16, 8, 2048, 128, seed=81, device=DEV, r_scale=0.1)
+    off = torch.randn(2, 8, 1, 128, device=DEV, generator=torch.Generator(DEV).manual_seed(5))
+    x["k"] = (x["k"].float() + 0.5 * off).to(torch.bfloat16)
+    ref = oracle_decode(oracle, x)
+    assert rel_l2(_run(plx, x), ref) <= BF16_REL_L2
+
+
+def test_deterministic_run_to_run(plx, synth):
+    x = synth.decode_inputs(4, 16, 8, 3000, 128, seed=91, device=DEV, ragged=True)
+    a = _run(plx, x, num_splits=8)
+    b = _run(plx, x, num_splits=8)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_workspace_partials_match_streaming_form(plx, synth):
+    """The split workspace holds, per split, the unnormalised state of Algorithm 1 over that
+    split's key range. Compare what is unique: log-sum-exp m + log2 d1, d2/d1, O1/d1, O2/d1."""
+    from oracle import forms
+
+    B, Hq, Hkv, L, d, S = 1, 4, 2, 1024, 128, 4
+    x = synth.decode_inputs(B, Hq, Hkv, L, d, seed=101, device=DEV)
+    ws = torch.zeros(B * Hq * S * (2 * d + 4), dtype=torch.float32, device=DEV)
+    plx.parallax_decode(x["q"], x["r"], x["k"], x["v"], x["scale"], num_splits=S, workspace=ws)
+    torch.cuda.synchronize()
+    rec = ws.cpu().numpy().reshape(B, Hq, S, 2 * d + 4).astype(np.float64)
+    q, r, k, v = (host(x[n]).astype(np.float64) for n in "qrkv")
+    per = L // S  # 8 block tiles of 128 keys, two per split
+    for h in range(Hq):
+        for s in range(S):
+            m, d1, d2, O1, O2 = forms.streaming_partial(q[0, h][None], r[0, h][None], k[0, h // 2],
+                                                        v[0, h // 2], x["scale"], 32,
+                                                        s * per, (s + 1) * per)
+            g = rec[0, h, s]
+            assert abs((g[0] + np.log2(g[1])) - (m[0] + np.log2(d1[0]))) < 2e-3
+            assert abs(g[2] / g[1] - d2[0] / d1[0]) < 2e-2 * max(1.0, abs(d2[0] / d1[0]))
+            assert rel_l2(g[4:4 + d] / g[1], O1[0] / d1[0]) < BF16_REL_L2
+            assert rel_l2(g[4 + d:] / g[1], O2[0] / d1[0]) < BF16_REL_L2
+
+
+def test_decode_fp32_path(plx, synth, oracle):
+    x = synth.decode_inputs(2, 4, 2, 700, 64, seed=111, dtype=torch.float32, device=DEV, ragged=True)
+    ref = oracle_decode(oracle, x)
+    got = _run(plx, x)
+    assert max_rel(got, ref) <= F32_MAX_REL
+
+
+def test_errors_surface_as_exceptions(plx, synth):
+    x = synth.decode_inputs(1, 4, 2, 64, 128, seed=1, device=DEV)
+    with pytest.raises(plx.ParallaxError) as e:
+        plx.parallax_decode(x["q"], x["r"], x["k"], x["v"], x["scale"], num_splits=4,
+                            workspace=torch.empty(8, dtype=torch.float32, device=DEV))
+    assert e.value.status == plx.PLX_ERR_WORKSPACE
+
+
+def _sampled_sequences(B, lens):
+    lens = lens.cpu().numpy()
+    picks = {int(np.argmin(lens)), int(np.argmax(lens)), 1 % B, B - 1}
+    return sorted(picks)
+
+
+def test_config3_sweep_corner_sampled(plx, synth, oracle):
+    """Config 3's largest ragged point that is cheap to hold: B=64, L=16384 (ragged), heuristic
+    split count; oracle on 4 sampled sequences, all heads."""
+    x = synth.decode_inputs(64, 16, 8, 16384, 128, seed=1003, device=DEV, ragged=True)
+    got = _run(plx, x)
+    seqs = _sampled_sequences(64, x["seq_lens"])
+    ref = oracle_decode(oracle, x, seqs=seqs)
+    assert rel_l2(got[seqs], ref) <= BF16_REL_L2
+    assert np.isfinite(got).all()
+
+
+def test_config5b_long_context_sampled(plx, synth, oracle):
+    """Config 5 part two: B=32, KV length 131072, probe scaled by 0.1 (K and V are 8.6 GB each,
+    offsets beyond 2^31 elements); oracle on 3 sampled sequences."""
+    x = synth.decode_inputs(32, 16, 8, 131072, 128, seed=1005, device=DEV, r_scale=0.1)
+    got = _run(plx, x)
+    seqs = [0, 17, 31]
+    ref = oracle_decode(oracle, x, seqs=seqs)
+    assert rel_l2(got[seqs], ref) <= BF16_REL_L2
+    assert np.isfinite(got).all()

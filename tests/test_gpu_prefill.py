@@ -1,0 +1,137 @@
+"""GPU parity of parallax_prefill (through the C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from parity import BF16_REL_L2, F32_MAX_REL, host, max_rel, oracle_prefill, rel_l2
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def plx():
+    from paper_2605_29157_amd import binding
+
+    binding.load_library()
+    assert torch.cuda.is_available()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def synth():
+    from paper_2605_29157_amd import synth as s
+
+    return s
+
+
+def _run(plx, y, **kw):
+    out = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], **kw)
+    torch.cuda.synchronize()
+    return host(out)
+
+
+def test_config1_tiny_causal_fp32(plx, synth, oracle):
+    """BASELINE config 1: B=1, 2 heads (no GQA), T=128, d=64, fp32, scale 1/8."""
+    y = synth.prefill_inputs(1, 2, 2, 128, 64, seed=1001, dtype=torch.float32, device=DEV)
+    assert abs(y["scale"] - 0.125) < 1e-12
+    ref = oracle_prefill(oracle, y)
+    got = _run(plx, y)
+    assert max_rel(got, ref) <= F32_MAX_REL
+    # row 0 sees exactly key 0
+    np.testing.assert_allclose(got[0, :, 0], host(y["v"])[0, :, 0], rtol=1e-6, atol=1e-6)
+    # element-wise relative error where the output is not near a zero crossing
+    rms = np.sqrt((ref ** 2).mean())
+    el = np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms)
+    assert el.max() <= 1e-3
+
+
+@pytest.mark.parametrize("T", [1, 31, 32, 33, 64, 65, 127, 128, 129, 300, 513])
+@pytest.mark.parametrize("causal", [True, False])
+def test_small_lengths_bf16(plx, synth, oracle, T, causal):
+    y = synth.prefill_inputs(2, 4, 2, T, 128, seed=300 + T, device=DEV, k_offset_sigma=0.5)
+    ref = oracle_prefill(oracle, y, causal=causal)
+    got = _run(plx, y, causal=causal)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, ref) <= BF16_REL_L2, (T, causal)
+    if causal:  # row 0 = v_0 exactly
+        np.testing.assert_array_equal(got[:, :, 0], np.repeat(host(y["v"])[:, :, 0], 2, axis=1))
+
+
+def test_softmax_only_twin(plx, synth, oracle):
+    y = synth.prefill_inputs(1, 4, 2, 400, 128, seed=401, device=DEV)
+    ref = oracle_prefill(oracle, y, use_r=False)
+    assert rel_l2(_run(plx, y, use_r=False), ref) <= BF16_REL_L2
+    # and a zero probe through the Parallax kernel gives the same thing
+    y0 = dict(y)
+    y0["r"] = torch.zeros_like(y["r"])
+    assert rel_l2(_run(plx, y0), ref) <= BF16_REL_L2
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(2, 2, 128), (8, 2, 128), (4, 2, 64), (16, 8, 64)])
+def test_head_layouts(plx, synth, oracle, Hq, Hkv, d):
+    y = synth.prefill_inputs(1, Hq, Hkv, 333, d, seed=500 + Hq + d, device=DEV)
+    ref = oracle_prefill(oracle, y)
+    assert rel_l2(_run(plx, y), ref) <= BF16_REL_L2
+
+
+def test_strided_inputs(plx, synth, oracle):
+    """[B, T, H, d] storage passed as permuted views."""
+    y = synth.prefill_inputs(2, 4, 2, 200, 128, seed=601, device=DEV)
+    ref = oracle_prefill(oracle, y)
+    ys = dict(y)
+    for n in "qrkv":
+        ys[n] = y[n].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert rel_l2(_run(plx, ys), ref) <= BF16_REL_L2
+
+
+def test_prefill_last_row_equals_decode(plx, synth):
+    """The last causal row sees every key: it must agree with a decode step over the same cache
+    (two different kernels, same operator)."""
+    y = synth.prefill_inputs(2, 16, 8, 1024, 128, seed=701, device=DEV)
+    pre = _run(plx, y)[:, :, -1, :]
+    dec = plx.parallax_decode(y["q"][:, :, -1, :].contiguous(), y["r"][:, :, -1, :].contiguous(),
+                              y["k"], y["v"], y["scale"])
+    torch.cuda.synchronize()
+    assert rel_l2(host(dec), pre.astype(np.float64)) <= BF16_REL_L2
+
+
+def _sample_rows(B, Hq, T, n_random, seed, tile=128):
+    rng = np.random.default_rng(seed)
+    rows = set()
+    for b in range(B):
+        for h in (0, Hq - 1):
+            for i in list(range(0, 8)) + list(range(T - 8, T)):
+                rows.add((b, h, i))
+    for edge in range(tile, T, max(tile, T // 16 // tile * tile)):
+        for i in (edge - 1, edge, edge + 1, edge - 33, edge + 31):
+            if 0 <= i < T:
+                rows.add((int(rng.integers(B)), int(rng.integers(Hq)), i))
+    while len(rows) < n_random:
+        rows.add((int(rng.integers(B)), int(rng.integers(Hq)), int(rng.integers(T))))
+    return np.array(sorted(rows), dtype=np.int32)
+
+
+def test_config4_prefill_bf16_sampled(plx, synth, oracle):
+    """BASELINE config 4: B=4, T=4096, 16/8 heads, d=128, keys offset per (b, kv head) by
+    N(0, 0.5^2); oracle on sampled rows (first/last rows, tile edges, random)."""
+    y = synth.prefill_inputs(4, 16, 8, 4096, 128, seed=1004, device=DEV, k_offset_sigma=0.5)
+    got = _run(plx, y)
+    assert np.isfinite(got).all()
+    rows = _sample_rows(4, 16, 4096, 700, seed=4)
+    ref = oracle_prefill(oracle, y, rows=rows)
+    sub = got[rows[:, 0], rows[:, 1], rows[:, 2]]
+    assert rel_l2(sub, ref) <= BF16_REL_L2
+    per_row = np.linalg.norm(sub - ref, axis=1) / np.linalg.norm(ref, axis=1)
+    assert per_row.max() <= 5e-2
+
+
+def test_config5a_long_prefill_sampled(plx, synth, oracle):
+    """Config 5 part one: B=2, T=16384, probe scaled by 0.1."""
+    y = synth.prefill_inputs(2, 16, 8, 16384, 128, seed=1005, device=DEV, r_scale=0.1)
+    got = _run(plx, y)
+    assert np.isfinite(got).all()
+    rows = _sample_rows(2, 16, 16384, 300, seed=5)
+    ref = oracle_prefill(oracle, y, rows=rows)
+    sub = got[rows[:, 0], rows[:, 1], rows[:, 2]]
+    assert rel_l2(sub, ref) <= BF16_REL_L2
