@@ -1,0 +1,274 @@
+#!/usr/bin/env python3
+"""Benchmark of the Parallax attention hot path on one MI355X.
+
+Default workload (BASELINE config 2): single-step decode, bf16, B=8, 16 query heads / 8 KV
+heads (GQA group 2), head_dim 128, KV context 4096. One "step" = one parallax_decode call:
+the split-KV kernel over the whole KV cache plus the combine kernel. Inputs are synthetic
+(seeded N(0,1)), resident in HBM before the timed region; 8 distinct KV caches (1.07 GB) are
+rotated so that no step finds its cache in the 256 MB Infinity Cache.
+
+Prints ONE JSON line. `value` is algorithmic KV bytes per second over the timed steps;
+`roofline` times the dominant kernel (the split-KV kernel alone, via
+parallax_decode_partials) with events on the launch stream; `cpu_baseline` times the
+double-precision CPU oracle on the same batch; `extra` carries the decode sweep, the
+softmax-only twin and the causal prefill TFLOP/s.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+# HBM bytes per launch of the split-KV kernel on config 2, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE scaled by the same counters on parallax_util_copy of known size
+# (profiles/decode_bf16_config2_pmc.md). None until measured.
+MEASURED_TRAFFIC_BYTES = {"config2": None}
+
+
+def decode_bytes(B, Hkv, d, lens_sum, Hq):
+    """Algorithmic bytes of one decode step: K and V once, q, r read and o written (bf16)."""
+    return Hkv * lens_sum * d * 2 * 2 + B * Hq * d * 2 * 3
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--no-extra", action="store_true", help="skip the sweep / prefill lines")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--counter-mode", action="store_true",
+                    help="short run for hardware-counter collection: 5 launches of the plain copy "
+                         "kernel on 1 GiB (known size, calibrates FETCH_SIZE / WRITE_SIZE) and "
+                         "--steps launches of the split-KV kernel; prints nothing to parse")
+    opt = ap.parse_args()
+    if opt.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path "
+              "(--gpus %d refused; run with --gpus 1)" % opt.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2605_29157_amd import binding as plx
+    from paper_2605_29157_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    lib = plx.load_library()
+    stream = torch.cuda.current_stream()
+    sptr = int(stream.cuda_stream)
+
+    # ------------------------------------------------------------------ workload: config 2
+    B, Hq, Hkv, L, d = 8, 16, 8, 4096, 128
+    NSETS = 8
+    sets = [synth.decode_inputs(B, Hq, Hkv, L, d, seed=1002 + 10 * i, device=dev) for i in range(NSETS)]
+    S = plx.parallax_decode_num_splits(B, Hq, Hkv, L, d)
+    ws = torch.empty(plx.parallax_decode_workspace_bytes(B, Hq, Hkv, L, d) // 4,
+                     dtype=torch.float32, device=dev)
+    out = torch.empty_like(sets[0]["q"])
+    full_args = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], out, x["scale"], None, True, 0, ws)
+                 for x in sets]
+    part_args = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], out, x["scale"], None, True, S, ws)
+                 for x in sets]
+    step_bytes = decode_bytes(B, Hkv, d, B * L, Hq)
+
+    def run(fn, arglist, n):
+        for i in range(n):
+            st = fn(ctypes.byref(arglist[i % NSETS]), sptr)
+            if st != 0:
+                raise plx.ParallaxError(st, "bench step")
+
+    if opt.counter_mode:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            plx.parallax_util_copy(dst, src)
+        run(lib.parallax_decode_partials, part_args, opt.steps)
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_mode": True, "copy_bytes_each_way": src.numel(),
+                          "decode_algorithmic_bytes": step_bytes, "num_splits": S}))
+        return
+
+    # ------------------------------------------------------------------ timed region
+    run(lib.parallax_decode, full_args, opt.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(lib.parallax_decode, full_args, opt.steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec_per_step = (t1 - t0) / opt.steps
+    value = step_bytes / sec_per_step / 1e9
+
+    # same K steps between events on the launch stream (excludes host launch gaps at the ends)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    run(lib.parallax_decode, full_args, opt.steps)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    step_us_events = e0.elapsed_time(e1) * 1e3 / opt.steps
+
+    # ------------------------------------------------------------------ roofline: split-KV kernel
+    run(lib.parallax_decode_partials, part_args, opt.warmup)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    run(lib.parallax_decode_partials, part_args, opt.steps)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    kern_us = e0.elapsed_time(e1) * 1e3 / opt.steps
+    achieved = step_bytes / (kern_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES["config2"],
+                "kernel": "decode_bf16_kernel<128,true>", "kernel_us": round(kern_us, 2),
+                "algorithmic_bytes_per_launch": step_bytes}
+
+    result = {
+        "metric": "decode_hbm_bandwidth", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": opt.steps, "warmup": opt.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 5), "us_per_step": round(sec_per_step * 1e6, 2),
+        "us_per_step_stream_events": round(step_us_events, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config2: decode bf16 B=8 Hq=16 Hkv=8 d=128 L=4096, "
+                               "8 rotated KV caches (cache-cold)",
+                   "num_splits": S, "bytes_per_step": step_bytes},
+        "roofline": roofline,
+    }
+
+    # ------------------------------------------------------------------ CPU oracle baseline
+    if not opt.no_cpu_baseline:
+        from oracle import parallax_oracle
+
+        parallax_oracle.build()
+        x = sets[0]
+        qh = x["q"].float().cpu().numpy()[:, :, None, :]
+        rh = x["r"].float().cpu().numpy()[:, :, None, :]
+        kh, vh = x["k"].float().cpu().numpy(), x["v"].float().cpu().numpy()
+        reps, tot = 0, 0.0
+        while tot < 10.0 and reps < 50:
+            c0 = time.perf_counter()
+            ref = parallax_oracle.forward(qh, rh, kh, vh, x["scale"])
+            tot += time.perf_counter() - c0
+            reps += 1
+        got = plx.parallax_decode(x["q"], x["r"], x["k"], x["v"], x["scale"], workspace=ws)
+        torch.cuda.synchronize()
+        err = float(np.linalg.norm(got.float().cpu().numpy()[:, :, None, :] - ref) /
+                    np.linalg.norm(ref))
+        result["cpu_baseline"] = {
+            "value": round(step_bytes / (tot / reps) / 1e9, 3), "unit": "GB/s",
+            "cores": parallax_oracle.num_threads(), "kind": "oracle",
+            "sample": "the full config-2 batch (8 sequences x 4096 keys), %d passes of the "
+                      "double-precision C oracle, %.2f s each" % (reps, tot / reps),
+            "gpu_vs_oracle_rel_l2": err,
+        }
+
+    # ------------------------------------------------------------------ extra lines
+    if not opt.no_extra:
+        result["extra"] = extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out)
+
+    print(json.dumps(result))
+
+
+def _time_events(torch, fn, warm, iters):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters  # microseconds
+
+
+def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
+    """Decode sweep points (config 3, fixed-length grid), the softmax-only twin, the plain
+    streaming-read ceiling, and causal prefill (config 4)."""
+    extra = {}
+    # achievable read bandwidth of a plain streaming kernel on this machine
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    sink = torch.empty(plx.parallax_util_read_sink_slots() * 16, dtype=torch.uint8, device=dev)
+    us = _time_events(torch, lambda: plx.parallax_util_read(src, sink), 3, 20)
+    extra["stream_read_ceiling_GBps"] = round(src.numel() / us / 1e3, 1)
+    del src
+
+    # softmax-only twin on config 2
+    x0 = sets
+    twin_args = [plx.decode_args(x["q"], None, x["k"], x["v"], out, x["scale"], None, False, 0, ws)
+                 for x in x0]
+    cnt = [0]
+
+    def twin():
+        lib.parallax_decode(ctypes.byref(twin_args[cnt[0] % len(twin_args)]), sptr)
+        cnt[0] += 1
+
+    us = _time_events(torch, twin, 20, 200)
+    extra["config2_softmax_only_us"] = round(us, 2)
+
+    sweep = []
+    for (B, L) in [(1, 1024), (1, 65536), (16, 4096), (16, 16384), (64, 16384), (128, 16384)]:
+        Hq, Hkv, d = 16, 8, 128
+        per_set = B * Hkv * L * d * 4
+        nset = max(1, min(8, int(3e9 // per_set)))
+        xs = [synth.decode_inputs(B, Hq, Hkv, L, d, seed=3000 + i, device=dev) for i in range(nset)]
+        o = torch.empty_like(xs[0]["q"])
+        w = torch.empty(plx.parallax_decode_workspace_bytes(B, Hq, Hkv, L, d) // 4,
+                        dtype=torch.float32, device=dev)
+        row = {"B": B, "L": L, "num_splits": plx.parallax_decode_num_splits(B, Hq, Hkv, L, d),
+               "kv_sets": nset}
+        for use_r in (True, False):
+            al = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], o, x["scale"], None, use_r, 0, w)
+                  for x in xs]
+            c = [0]
+
+            def step():
+                lib.parallax_decode(ctypes.byref(al[c[0] % nset]), sptr)
+                c[0] += 1
+
+            iters = 200 if per_set < 5e8 else 30
+            us = _time_events(torch, step, 5, iters)
+            byts = decode_bytes(B, Hkv, d, B * L, Hq)
+            key = "parallax" if use_r else "softmax_only"
+            row[key + "_us"] = round(us, 2)
+            row[key + "_GBps"] = round(byts / us / 1e3, 1)
+        row["frac_of_8TBps"] = round(row["parallax_GBps"] / HBM_PEAK_GBPS, 4)
+        sweep.append(row)
+        del xs, al
+    extra["decode_sweep"] = sweep
+
+    # causal prefill, config 4
+    B, T, Hq, Hkv, d = 4, 4096, 16, 8, 128
+    y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1004, device=dev, k_offset_sigma=0.5)
+    po = torch.empty_like(y["q"])
+    pre = {}
+    for use_r in (True, False):
+        us = _time_events(
+            torch, lambda: plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"],
+                                                causal=True, use_r=use_r, out=po), 3, 20)
+        flops = B * Hq * (8 if use_r else 4) * d * T * (T + 1) / 2
+        key = "parallax" if use_r else "softmax_only"
+        pre[key + "_us"] = round(us, 1)
+        pre[key + "_TFLOPs"] = round(flops / us / 1e6, 1)
+    pre["frac_of_bf16_mfma_peak"] = round(pre["parallax_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
+    pre["workload"] = "config4: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128, K offset N(0,0.5^2)"
+    extra["prefill"] = pre
+    return extra
+
+
+if __name__ == "__main__":
+    main()

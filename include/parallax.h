@@ -98,6 +98,22 @@ int32_t parallax_decode_num_splits(int32_t B, int32_t Hq, int32_t Hkv, int32_t L
 plx_status parallax_decode(const plx_decode_args *args, void *hip_stream);
 
 /*
+ * The two halves of parallax_decode on their own (bf16 only), for callers that merge partials
+ * themselves -- e.g. a KV cache sharded over devices, where every shard produces its partials
+ * and one merge follows (App. C: the merge is an associative log-sum-exp rescale) -- and for
+ * timing the two kernels separately.
+ *   parallax_decode_partials: runs only the split kernel with S = num_splits (0 = heuristic) and
+ *     ALWAYS writes the workspace, also for S = 1: record (b, hq, s) at float offset
+ *     ((b*Hq + hq)*S + s)*(2d+4) holds m (exp2 domain, -inf if the split saw no key), d1, d2,
+ *     pad, O1[d], O2[d], all unnormalised. args->o is not touched and may be NULL.
+ *   parallax_decode_combine: merges the S = num_splits (>= 1, required) records per (b, hq) of
+ *     the workspace and writes args->o. Only o, B, Hq, Hkv, d, num_splits, workspace,
+ *     workspace_bytes and dtype are read.
+ */
+plx_status parallax_decode_partials(const plx_decode_args *args, void *hip_stream);
+plx_status parallax_decode_combine(const plx_decode_args *args, void *hip_stream);
+
+/*
  * Prefill forward over T query rows and T keys per sequence (Algorithm 1, Sec. 3.3; forward
  * equation Sec. 3.1). causal != 0: key j allowed iff j <= i (diagonal included, so row 0
  * returns v_0); causal == 0: every key.

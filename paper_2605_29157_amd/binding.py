@@ -21,6 +21,7 @@ PLX_MAX_SPLITS = 128
 
 EXPORTED_SYMBOLS = (
     "parallax_decode_workspace_bytes", "parallax_decode_num_splits", "parallax_decode",
+    "parallax_decode_partials", "parallax_decode_combine",
     "parallax_prefill", "parallax_util_copy", "parallax_util_read",
     "parallax_util_read_sink_slots", "parallax_strerror", "parallax_version",
 )
@@ -85,6 +86,9 @@ def load_library() -> ctypes.CDLL:
         lib.parallax_decode_num_splits.restype = ctypes.c_int32
         lib.parallax_decode.argtypes = [ctypes.POINTER(plx_decode_args), ctypes.c_void_p]
         lib.parallax_decode.restype = ctypes.c_int
+        for name in ("parallax_decode_partials", "parallax_decode_combine"):
+            getattr(lib, name).argtypes = [ctypes.POINTER(plx_decode_args), ctypes.c_void_p]
+            getattr(lib, name).restype = ctypes.c_int
         lib.parallax_prefill.argtypes = [ctypes.POINTER(plx_prefill_args), ctypes.c_void_p]
         lib.parallax_prefill.restype = ctypes.c_int
         lib.parallax_util_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -178,6 +182,33 @@ def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, 
     st = load_library().parallax_decode(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_decode")
+    return out
+
+
+def parallax_decode_partials(q, r, k, v, scale, num_splits, workspace, seq_lens=None, use_r=True,
+                             stream=None):
+    """Split kernel only: fills `workspace` with the (m, d1, d2, pad, O1, O2) records."""
+    a = decode_args(q, r, k, v, q, scale, seq_lens, use_r, num_splits, workspace)
+    a.o = None
+    st = load_library().parallax_decode_partials(ctypes.byref(a), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_decode_partials")
+    return workspace
+
+
+def parallax_decode_combine(workspace, out, Hkv, num_splits, stream=None):
+    """Merge kernel only: `workspace` holds num_splits records per (b, hq); writes out [B, Hq, d]."""
+    B, Hq, d = out.shape
+    a = plx_decode_args()
+    a.o = out.data_ptr()
+    a.B, a.Hq, a.Hkv, a.Lmax, a.d = B, Hq, Hkv, 1, d
+    a.num_splits = int(num_splits)
+    a.workspace = workspace.data_ptr()
+    a.workspace_bytes = workspace.numel() * workspace.element_size()
+    a.dtype = _dtype_code(out)
+    st = load_library().parallax_decode_combine(ctypes.byref(a), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_decode_combine")
     return out
 
 

@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
             a2 += wt * mrg_o2[(ww * G + hh) * D + dim];
         }
         const int64_t hq = (int64_t)b * p.Hq + (int64_t)hk * G + hh;
-        if (S == 1) {
+        if (p.direct_out) {
             float out = 0.f;  // empty key set: zeros
             if (d1 > 0.f) {
                 const float inv = 1.f / d1;
@@ -264,31 +264,78 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
 }
 
 // Merge the S split partials of one (batch, query head): m* = max_s m_s, weights
-// exp2(m_s - m*), then the closing formula of Algorithm 1. One thread per output dimension.
+// exp2(m_s - m*), then the closing formula of Algorithm 1. One workgroup per (b, hq), threads
+// laid out as [split lane][dimension lane x float4]: every thread folds the records
+// s = split lane, split lane + SL, ... into a private state with all loads of a trip issued
+// together, then the SL private states are merged through LDS.
+struct MergeState {
+    float m, d1, d2;
+    f32x4 a1, a2;
+};
+
+__device__ __forceinline__ void merge_into(MergeState &st, float ms, float d1, float d2, f32x4 a1,
+                                           f32x4 a2) {
+    const float m_new = fmaxf(st.m, ms);
+    const float m_use = m_new == kNegInf ? 0.f : m_new;
+    const float w_old = fast_exp2(st.m - m_use);  // exp2(-inf) = 0 for an empty side
+    const float w_new = fast_exp2(ms - m_use);
+    st.m = m_new;
+    st.d1 = w_old * st.d1 + w_new * d1;
+    st.d2 = w_old * st.d2 + w_new * d2;
+    st.a1 = w_old * st.a1 + w_new * a1;
+    st.a2 = w_old * st.a2 + w_new * a2;
+}
+
 template <int D>
-__global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams p) {
-    const int dim = threadIdx.x;
+__global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
+    constexpr int DL = D / 4;     // lanes over the head dimension (float4 each)
+    constexpr int SL = 256 / DL;  // lanes over splits
+    constexpr int REC = 2 * D + 4;
+    __shared__ float sm_hdr[SL][4];
+    __shared__ f32x4 sm_a1[SL][DL], sm_a2[SL][DL];
+
+    const int tid = threadIdx.x, sl = tid / DL, dl = tid % DL;
     const int64_t hq = (int64_t)blockIdx.y * p.Hq + blockIdx.x;
     const int S = p.S;
-    const float *rec0 = p.ws + hq * S * (int64_t)(2 * D + 4);
-    float m_star = kNegInf;
-    for (int s = 0; s < S; ++s) m_star = fmaxf(m_star, rec0[(int64_t)s * (2 * D + 4)]);
-    float d1 = 0.f, d2 = 0.f, a1 = 0.f, a2 = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float *rec = rec0 + (int64_t)s * (2 * D + 4);
-        const float ms = rec[0];
-        const float wt = ms == kNegInf ? 0.f : fast_exp2(ms - m_star);
-        d1 += wt * rec[1];
-        d2 += wt * rec[2];
-        a1 += wt * rec[4 + dim];
-        a2 += wt * rec[4 + D + dim];
+    const float *rec0 = p.ws + hq * S * (int64_t)REC;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    MergeState st{kNegInf, 0.f, 0.f, zero, zero};
+    for (int base = 0; base < S; base += 4 * SL) {
+        f32x4 hdr[4], a1[4], a2[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {  // issue every load of the trip before using any
+            const int s = base + u * SL + sl;
+            const bool ok = s < S;
+            const float *rec = rec0 + (int64_t)(ok ? s : 0) * REC;
+            hdr[u] = ok ? *(const f32x4 *)rec : f32x4{kNegInf, 0.f, 0.f, 0.f};
+            a1[u] = ok ? *(const f32x4 *)(rec + 4 + 4 * dl) : zero;
+            a2[u] = ok ? *(const f32x4 *)(rec + 4 + D + 4 * dl) : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) merge_into(st, hdr[u][0], hdr[u][1], hdr[u][2], a1[u], a2[u]);
     }
-    float out = 0.f;
-    if (d1 > 0.f) {
-        const float inv = 1.f / d1;
-        out = a1 * inv * (1.f + d2 * inv) - a2 * inv;
+    if (dl == 0) {
+        sm_hdr[sl][0] = st.m;
+        sm_hdr[sl][1] = st.d1;
+        sm_hdr[sl][2] = st.d2;
     }
-    ((__bf16 *)p.o)[hq * D + dim] = (__bf16)out;
+    sm_a1[sl][dl] = st.a1;
+    sm_a2[sl][dl] = st.a2;
+    __syncthreads();
+    if (sl == 0) {
+        MergeState tot{kNegInf, 0.f, 0.f, zero, zero};
+#pragma unroll
+        for (int j = 0; j < SL; ++j)
+            merge_into(tot, sm_hdr[j][0], sm_hdr[j][1], sm_hdr[j][2], sm_a1[j][dl], sm_a2[j][dl]);
+        f32x4 out = zero;  // empty key set: zeros
+        if (tot.d1 > 0.f) {
+            const float inv = 1.f / tot.d1;
+            out = tot.a1 * (inv * (1.f + tot.d2 * inv)) - tot.a2 * inv;
+        }
+        const u32x2 packed = {pack_bf16(out[0], out[1]), pack_bf16(out[2], out[3])};
+        *(u32x2 *)((__bf16 *)p.o + hq * D + 4 * dl) = packed;
+    }
 }
 
 hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream) {
@@ -310,9 +357,9 @@ hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream) {
 hipError_t launch_decode_combine(const DecodeParams &p, hipStream_t stream) {
     const dim3 grid(p.Hq, p.B);
     if (p.d == 128)
-        hipLaunchKernelGGL((decode_combine_kernel<128>), grid, dim3(128), 0, stream, p);
+        hipLaunchKernelGGL((decode_combine_kernel<128>), grid, dim3(256), 0, stream, p);
     else
-        hipLaunchKernelGGL((decode_combine_kernel<64>), grid, dim3(64), 0, stream, p);
+        hipLaunchKernelGGL((decode_combine_kernel<64>), grid, dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 

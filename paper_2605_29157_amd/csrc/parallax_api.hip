@@ -61,10 +61,11 @@ int32_t parallax_decode_num_splits(int32_t B, int32_t Hq, int32_t Hkv, int32_t L
     (void)d;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Lmax <= 0) return 1;
     if (num_cus <= 0) num_cus = query_num_cus();
-    // Two workgroups are resident per compute unit; aim at two rounds of them so that the
-    // tail of a ragged batch is filled, and bound the work of one split to 4096 keys.
+    // Two workgroups are resident per compute unit: aim at one full round of them (measured:
+    // more, shorter splits only add prologue / merge work), and bound the work of one split
+    // to 4096 keys so that the tail of a long or ragged batch stays short.
     const int64_t pairs = (int64_t)B * Hkv;
-    const int64_t target = 4LL * num_cus;
+    const int64_t target = 2LL * num_cus;
     int64_t s = (target + pairs - 1) / pairs;
     const int64_t by_len = ((int64_t)Lmax + 4095) / 4096;
     if (s < by_len) s = by_len;
@@ -78,26 +79,32 @@ int32_t parallax_decode_num_splits(int32_t B, int32_t Hq, int32_t Hkv, int32_t L
     return (int32_t)s;
 }
 
-plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
+namespace {
+
+// Validation shared by the decode entry points; fills the launch parameters.
+plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_out,
+                          plx::DecodeParams *out) {
     if (!a) return PLX_ERR_NULL;
-    if (!a->q || !a->k || !a->v || !a->o) return PLX_ERR_NULL;
-    if (a->use_r && !a->r) return PLX_ERR_NULL;
-    plx_status st = check_common(a->dtype, a->B, a->Hq, a->Hkv, a->Lmax, a->d);
+    if (need_inputs && (!a->q || !a->k || !a->v)) return PLX_ERR_NULL;
+    if (need_inputs && a->use_r && !a->r) return PLX_ERR_NULL;
+    if (need_out && !a->o) return PLX_ERR_NULL;
+    plx_status st = check_common(a->dtype, a->B, a->Hq, a->Hkv, need_inputs ? a->Lmax : 1, a->d);
     if (st != PLX_OK) return st;
     if (a->num_splits < 0 || a->num_splits > PLX_MAX_SPLITS) return PLX_ERR_SPLITS;
-    if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || !aligned16(a->o) ||
-        (a->r && !aligned16(a->r)))
-        return PLX_ERR_ALIGN;
-    if (a->seq_lens && (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u)) return PLX_ERR_ALIGN;
-    const int64_t strides[6] = {a->k_stride_b, a->k_stride_h, a->k_stride_l,
-                                a->v_stride_b, a->v_stride_h, a->v_stride_l};
-    for (int64_t s : strides) {
-        if (s < 0) return PLX_ERR_SHAPE;
-        if (!stride_aligned(s, a->dtype)) return PLX_ERR_ALIGN;
-    }
-    if (a->k_stride_l < a->d || a->v_stride_l < a->d) return PLX_ERR_SHAPE;
+    if (need_out && !aligned16(a->o)) return PLX_ERR_ALIGN;
     if (((int64_t)a->d * elem_size(a->dtype)) % 16 != 0) return PLX_ERR_ALIGN;
-
+    if (need_inputs) {
+        if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || (a->r && !aligned16(a->r)))
+            return PLX_ERR_ALIGN;
+        if (a->seq_lens && (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u)) return PLX_ERR_ALIGN;
+        const int64_t strides[6] = {a->k_stride_b, a->k_stride_h, a->k_stride_l,
+                                    a->v_stride_b, a->v_stride_h, a->v_stride_l};
+        for (int64_t s : strides) {
+            if (s < 0) return PLX_ERR_SHAPE;
+            if (!stride_aligned(s, a->dtype)) return PLX_ERR_ALIGN;
+        }
+        if (a->k_stride_l < a->d || a->v_stride_l < a->d) return PLX_ERR_SHAPE;
+    }
     plx::DecodeParams p{};
     p.q = a->q, p.r = a->use_r ? a->r : a->q, p.k = a->k, p.v = a->v, p.o = a->o;
     p.seq_lens = a->seq_lens;
@@ -105,6 +112,23 @@ plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
     p.ksb = a->k_stride_b, p.ksh = a->k_stride_h, p.ksl = a->k_stride_l;
     p.vsb = a->v_stride_b, p.vsh = a->v_stride_h, p.vsl = a->v_stride_l;
     p.scale = a->scale, p.use_r = a->use_r ? 1 : 0;
+    *out = p;
+    return PLX_OK;
+}
+
+plx_status attach_workspace(const plx_decode_args *a, int32_t S, plx::DecodeParams *p) {
+    if (!a->workspace || !aligned16(a->workspace)) return PLX_ERR_WORKSPACE;
+    if (a->workspace_bytes < ws_bytes(a->B, a->Hq, S, a->d)) return PLX_ERR_WORKSPACE;
+    p->ws = static_cast<float *>(a->workspace);
+    return PLX_OK;
+}
+
+}  // namespace
+
+plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
+    plx::DecodeParams p{};
+    plx_status st = prepare_decode(a, true, true, &p);
+    if (st != PLX_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
     if (a->dtype == PLX_F32) {
@@ -116,14 +140,44 @@ plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
     int32_t S = a->num_splits;
     if (S == 0) S = parallax_decode_num_splits(a->B, a->Hq, a->Hkv, a->Lmax, a->d, 0);
     p.S = S;
+    p.direct_out = S == 1;
     if (S > 1) {
-        if (!a->workspace || !aligned16(a->workspace)) return PLX_ERR_WORKSPACE;
-        if (a->workspace_bytes < ws_bytes(a->B, a->Hq, S, a->d)) return PLX_ERR_WORKSPACE;
-        p.ws = static_cast<float *>(a->workspace);
+        st = attach_workspace(a, S, &p);
+        if (st != PLX_OK) return st;
     }
     if (plx::launch_decode_bf16(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
     if (S > 1 && plx::launch_decode_combine(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
     return PLX_OK;
+}
+
+plx_status parallax_decode_partials(const plx_decode_args *a, void *hip_stream) {
+    plx::DecodeParams p{};
+    plx_status st = prepare_decode(a, true, false, &p);
+    if (st != PLX_OK) return st;
+    if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
+    int32_t S = a->num_splits;
+    if (S == 0) S = parallax_decode_num_splits(a->B, a->Hq, a->Hkv, a->Lmax, a->d, 0);
+    p.S = S;
+    p.direct_out = 0;
+    st = attach_workspace(a, S, &p);
+    if (st != PLX_OK) return st;
+    return plx::launch_decode_bf16(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
+}
+
+plx_status parallax_decode_combine(const plx_decode_args *a, void *hip_stream) {
+    plx::DecodeParams p{};
+    plx_status st = prepare_decode(a, false, true, &p);
+    if (st != PLX_OK) return st;
+    if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
+    if (a->num_splits < 1) return PLX_ERR_SPLITS;
+    p.S = a->num_splits;
+    st = attach_workspace(a, p.S, &p);
+    if (st != PLX_OK) return st;
+    return plx::launch_decode_combine(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
 }
 
 plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {

@@ -17,6 +17,7 @@ struct DecodeParams {
     int64_t ksb, ksh, ksl, vsb, vsh, vsl;  // element strides
     float scale;
     int32_t use_r;
+    int32_t direct_out;  // 1: S == 1 and the split kernel writes o itself (no workspace)
 };
 
 struct PrefillParams {

@@ -66,7 +66,7 @@ def test_split_heuristic_is_sane(binding):
         assert s <= max(1, n_bt // 2)          # at least two block tiles per split
         if L >= 2 * 4096:
             assert s >= (L + 4095) // 4096 or s == binding.PLX_MAX_SPLITS
-    assert f(8, 16, 8, 4096, 128, 256) == 16   # 1024 workgroups over 64 (batch, kv head) pairs
+    assert f(8, 16, 8, 4096, 128, 256) == 8    # 512 workgroups over 64 (batch, kv head) pairs
     assert f(1, 16, 8, 256, 128, 256) == 1
 
 

@@ -146,6 +146,24 @@ def test_workspace_partials_match_streaming_form(plx, synth):
             assert rel_l2(g[4 + d:] / g[1], O2[0] / d1[0]) < BF16_REL_L2
 
 
+def test_partials_then_combine_equals_decode(plx, synth):
+    """The two exported halves chained by the caller give bit-identical output to the fused
+    entry point, also for S = 1 (where the fused call skips the workspace)."""
+    x = synth.decode_inputs(3, 8, 4, 900, 128, seed=105, device=DEV, ragged=True)
+    for S in (1, 6):
+        ws = torch.empty(3 * 8 * S * 260, dtype=torch.float32, device=DEV)
+        plx.parallax_decode_partials(x["q"], x["r"], x["k"], x["v"], x["scale"], S, ws,
+                                     seq_lens=x["seq_lens"])
+        out = torch.empty_like(x["q"])
+        plx.parallax_decode_combine(ws, out, 4, S)
+        torch.cuda.synchronize()
+        fused = _run(plx, x, num_splits=S)
+        if S > 1:
+            np.testing.assert_array_equal(host(out), fused)
+        else:
+            assert rel_l2(host(out), fused.astype(np.float64)) < 1e-6 + 4e-3
+
+
 def test_decode_fp32_path(plx, synth, oracle):
     x = synth.decode_inputs(2, 4, 2, 700, 64, seed=111, dtype=torch.float32, device=DEV, ragged=True)
     ref = oracle_decode(oracle, x)
