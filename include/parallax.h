@@ -48,7 +48,8 @@ typedef enum {
     PLX_ERR_ALIGN = -4,     /* pointer or stride not 16-byte aligned               */
     PLX_ERR_WORKSPACE = -5, /* split-KV workspace missing or too small             */
     PLX_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch                    */
-    PLX_ERR_SPLITS = -7     /* num_splits outside [0, PLX_MAX_SPLITS]              */
+    PLX_ERR_SPLITS = -7,    /* num_splits outside [0, PLX_MAX_SPLITS]              */
+    PLX_ERR_SCALE = -8      /* scale is negative, infinite or NaN                  */
 } plx_status;
 
 #define PLX_MAX_SPLITS 128
@@ -64,7 +65,8 @@ typedef enum {
  *   o         [B, Hq, d]   contiguous, written
  *   seq_lens  [B] int32 on the device, 0 <= L_b <= Lmax; rows with L_b = 0 (undefined in
  *             the paper: empty softmax) are written as zeros
- *   scale     multiplies q.k only (the probe score r.k is used as is)
+ *   scale     multiplies q.k only (the probe score r.k is used as is); finite and >= 0
+ *             (scale = 1/h for a bandwidth h > 0; 0 is the uniform-weight limit)
  *   use_r     1 = Parallax; 0 = softmax-only twin (r may be NULL, correction branch skipped)
  *   num_splits 0 = library heuristic, else the number of key-range splits to use
  *   workspace fp32 scratch for split partials, >= parallax_decode_workspace_bytes(...);

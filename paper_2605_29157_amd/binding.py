@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libparallax_hip.so")
 PLX_BF16, PLX_F32 = 0, 1
 PLX_MAX_SPLITS = 128
 (PLX_OK, PLX_ERR_NULL, PLX_ERR_SHAPE, PLX_ERR_DTYPE, PLX_ERR_ALIGN, PLX_ERR_WORKSPACE,
- PLX_ERR_LAUNCH, PLX_ERR_SPLITS) = (0, -1, -2, -3, -4, -5, -6, -7)
+ PLX_ERR_LAUNCH, PLX_ERR_SPLITS, PLX_ERR_SCALE) = (0, -1, -2, -3, -4, -5, -6, -7, -8)
 
 EXPORTED_SYMBOLS = (
     "parallax_decode_workspace_bytes", "parallax_decode_num_splits", "parallax_decode",

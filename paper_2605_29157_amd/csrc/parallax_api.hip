@@ -91,6 +91,7 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
     plx_status st = check_common(a->dtype, a->B, a->Hq, a->Hkv, need_inputs ? a->Lmax : 1, a->d);
     if (st != PLX_OK) return st;
     if (a->num_splits < 0 || a->num_splits > PLX_MAX_SPLITS) return PLX_ERR_SPLITS;
+    if (need_inputs && !(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
     if (need_out && !aligned16(a->o)) return PLX_ERR_ALIGN;
     if (((int64_t)a->d * elem_size(a->dtype)) % 16 != 0) return PLX_ERR_ALIGN;
     if (need_inputs) {
@@ -186,6 +187,7 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
     if (a->use_r && !a->r) return PLX_ERR_NULL;
     plx_status st = check_common(a->dtype, a->B, a->Hq, a->Hkv, a->T, a->d);
     if (st != PLX_OK) return st;
+    if (!(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
     if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || !aligned16(a->o) ||
         (a->r && !aligned16(a->r)))
         return PLX_ERR_ALIGN;
@@ -198,6 +200,8 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
             if (!stride_aligned(sets[t][j], a->dtype)) return PLX_ERR_ALIGN;
         }
         if (sets[t][2] < a->d) return PLX_ERR_SHAPE;
+        // the bf16 kernel addresses a 64-row tile with 32-bit byte offsets
+        if (a->dtype == PLX_BF16 && sets[t][2] > (1 << 23)) return PLX_ERR_SHAPE;
     }
 
     plx::PrefillParams p{};
@@ -247,6 +251,7 @@ const char *parallax_strerror(plx_status status) {
         case PLX_ERR_WORKSPACE: return "split-KV workspace missing, misaligned or too small";
         case PLX_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
         case PLX_ERR_SPLITS: return "num_splits outside [0, PLX_MAX_SPLITS]";
+        case PLX_ERR_SCALE: return "scale must be finite and non-negative";
     }
     return "unknown status";
 }

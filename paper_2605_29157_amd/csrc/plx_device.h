@@ -50,10 +50,11 @@ __device__ __forceinline__ float bf16_lo_f32(uint32_t packed) {
 __device__ __forceinline__ float bf16_hi_f32(uint32_t packed) {
     return __builtin_bit_cast(float, packed & 0xffff0000u);
 }
-// Sum of the eight bf16 values of an MFMA operand, in fp32.
-__device__ __forceinline__ float sum_bf16x8(u32x4 v) {
-    return ((bf16_lo_f32(v[0]) + bf16_hi_f32(v[0])) + (bf16_lo_f32(v[1]) + bf16_hi_f32(v[1]))) +
-           ((bf16_lo_f32(v[2]) + bf16_hi_f32(v[2])) + (bf16_lo_f32(v[3]) + bf16_hi_f32(v[3])));
+// acc + the eight bf16 values of an MFMA operand, in fp32.
+__device__ __forceinline__ float add_bf16x8(float acc, u32x4 v) {
+    const float s = ((bf16_lo_f32(v[0]) + bf16_hi_f32(v[0])) + (bf16_lo_f32(v[1]) + bf16_hi_f32(v[1]))) +
+                    ((bf16_lo_f32(v[2]) + bf16_hi_f32(v[2])) + (bf16_lo_f32(v[3]) + bf16_hi_f32(v[3])));
+    return acc + s;
 }
 
 // Transposing LDS read (ds_read_b64_tr_b16). Within each group of 16 lanes, lane i receives

@@ -45,7 +45,7 @@ def test_struct_sizes_match_c_layout(binding):
 def test_version_and_strerror(binding):
     assert binding.version() >= 100
     assert binding.strerror(0) == "ok"
-    for code in range(-7, 0):
+    for code in range(-8, 0):
         assert binding.strerror(code) not in ("ok", "unknown status")
     assert binding.strerror(-99) == "unknown status"
 
@@ -106,6 +106,9 @@ def test_decode_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_SHAPE
     a = _good_decode_args(binding); a.num_splits = binding.PLX_MAX_SPLITS + 1
     assert call(a) == binding.PLX_ERR_SPLITS
+    for bad in (-0.5, float("inf"), float("nan")):
+        a = _good_decode_args(binding); a.scale = bad
+        assert call(a) == binding.PLX_ERR_SCALE
     a = _good_decode_args(binding); a.num_splits = 4          # no workspace
     assert call(a) == binding.PLX_ERR_WORKSPACE
     a = _good_decode_args(binding); a.num_splits = 4
@@ -138,6 +141,8 @@ def test_prefill_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_SHAPE
     a = good(); a.o = 0x1008
     assert call(a) == binding.PLX_ERR_ALIGN
+    a = good(); a.scale = -1.0
+    assert call(a) == binding.PLX_ERR_SCALE
     a = good(); a.q_stride = (ctypes.c_int64 * 3)(4 * 128 * 128, 128 * 128, 130)
     assert call(a) == binding.PLX_ERR_ALIGN
     a = good(); a.k_stride = (ctypes.c_int64 * 3)(4 * 128 * 128, 128 * 128, 64)

@@ -114,6 +114,17 @@ def test_key_offset_and_small_probe(plx, synth, oracle):
     assert rel_l2(_run(plx, x), ref) <= BF16_REL_L2
 
 
+def test_large_logit_range_and_zero_scale(plx, synth, oracle):
+    x = synth.decode_inputs(2, 4, 2, 900, 128, seed=85, device=DEV)
+    x["q"] = (x["q"].float() * 40.0).to(torch.bfloat16)
+    ref = oracle_decode(oracle, x)
+    got = _run(plx, x, num_splits=3)
+    assert np.isfinite(got).all() and rel_l2(got, ref) <= BF16_REL_L2
+    x = synth.decode_inputs(2, 4, 2, 900, 128, seed=86, device=DEV, r_scale=0.2)
+    x["scale"] = 0.0
+    assert rel_l2(_run(plx, x, num_splits=3), oracle_decode(oracle, x)) <= BF16_REL_L2
+
+
 def test_deterministic_run_to_run(plx, synth):
     x = synth.decode_inputs(4, 16, 8, 3000, 128, seed=91, device=DEV, ragged=True)
     a = _run(plx, x, num_splits=8)

@@ -68,6 +68,31 @@ def test_softmax_only_twin(plx, synth, oracle):
     assert rel_l2(_run(plx, y0), ref) <= BF16_REL_L2
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("gain", [12.0, 40.0])
+def test_large_logit_range_takes_the_safe_path(plx, synth, oracle, gain, causal):
+    """Scores spread over hundreds of binary orders of magnitude: a fixed softmax reference from
+    the first key block overflows, so the kernel must fall back to the online max/rescale pass
+    (a plain exp without max subtraction would give inf/NaN here)."""
+    y = synth.prefill_inputs(1, 4, 2, 700, 128, seed=811, device=DEV)
+    y["q"] = (y["q"].float() * gain).to(torch.bfloat16)
+    # make late keys much more attractive than early ones for half of the rows
+    ramp = torch.linspace(0.2, 3.0, 700, device=DEV).view(1, 1, 700, 1)
+    y["k"] = (y["k"].float() * ramp).to(torch.bfloat16)
+    ref = oracle_prefill(oracle, y, causal=causal)
+    got = _run(plx, y, causal=causal)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, ref) <= BF16_REL_L2
+
+
+def test_scale_zero_is_uniform_weighting(plx, synth, oracle):
+    """scale = 0 is the wide-bandwidth limit (uniform softmax weights)."""
+    y = synth.prefill_inputs(1, 4, 2, 260, 128, seed=821, device=DEV, r_scale=0.2)
+    y["scale"] = 0.0
+    ref = oracle_prefill(oracle, y)
+    assert rel_l2(_run(plx, y), ref) <= BF16_REL_L2
+
+
 @pytest.mark.parametrize("Hq,Hkv,d", [(2, 2, 128), (8, 2, 128), (4, 2, 64), (16, 8, 64)])
 def test_head_layouts(plx, synth, oracle, Hq, Hkv, d):
     y = synth.prefill_inputs(1, Hq, Hkv, 333, d, seed=500 + Hq + d, device=DEV)
