@@ -31,8 +31,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per launch of the split-KV kernel on config 2, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE scaled by the same counters on parallax_util_copy of known size
-# (profiles/decode_bf16_config2_pmc.md). None until measured.
-MEASURED_TRAFFIC_BYTES = {"config2": None}
+# (profiles/decode_bf16_config2_hbm_counters.md): 134 879 000 read + 1 081 344 written.
+MEASURED_TRAFFIC_BYTES = {"config2": 135960000}
 
 
 def decode_bytes(B, Hkv, d, lens_sum, Hq):
@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-extra", action="store_true", help="skip the sweep / prefill lines")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
+                    help="decode = config 2 (the headline line); prefill = config 4 causal "
+                         "prefill alone, for profiling that kernel")
     ap.add_argument("--counter-mode", action="store_true",
                     help="short run for hardware-counter collection: 5 launches of the plain copy "
                          "kernel on 1 GiB (known size, calibrates FETCH_SIZE / WRITE_SIZE) and "
@@ -71,6 +74,10 @@ def main():
     lib = plx.load_library()
     stream = torch.cuda.current_stream()
     sptr = int(stream.cuda_stream)
+
+    if opt.workload == "prefill":
+        print(json.dumps(prefill_line(torch, plx, synth, dev, opt)))
+        return
 
     # ------------------------------------------------------------------ workload: config 2
     B, Hq, Hkv, L, d = 8, 16, 8, 4096, 128
@@ -181,6 +188,34 @@ def main():
         result["extra"] = extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out)
 
     print(json.dumps(result))
+
+
+def prefill_line(torch, plx, synth, dev, opt):
+    """Config 4 on its own: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128."""
+    B, T, Hq, Hkv, d = 4, 4096, 16, 8, 128
+    y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1004, device=dev, k_offset_sigma=0.5)
+    out = torch.empty_like(y["q"])
+    steps = min(opt.steps, 50)
+    warm = min(opt.warmup, 5)
+
+    def step():
+        plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True, out=out)
+
+    us = _time_events(torch, step, warm, steps)
+    flops = B * Hq * 8 * d * T * (T + 1) / 2
+    tf = flops / us / 1e6
+    return {
+        "metric": "prefill_bf16_throughput", "value": round(tf, 1), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(us / 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "config4: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128, "
+                               "K offset N(0,0.5^2)", "algorithmic_flops": flops},
+        "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": None, "kernel": "prefill_bf16_kernel<128,true,true>",
+                     "kernel_us": round(us, 1)},
+    }
 
 
 def _time_events(torch, fn, warm, iters):
