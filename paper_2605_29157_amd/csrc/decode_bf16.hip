@@ -154,9 +154,9 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int i = 0; i < 4; ++i) p1[sub][i] = fast_exp2(x[sub][i] - m_use);  // 0 if masked
-        const u32x4 pb1 = {pack_bf16(p1[0][0], p1[0][1]), pack_bf16(p1[0][2], p1[0][3]),
-                           pack_bf16(p1[1][0], p1[1][1]), pack_bf16(p1[1][2], p1[1][3])};
-        dsum1 = add_bf16x8(alpha * dsum1, pb1);
+        dsum1 *= alpha;
+        const u32x4 pb1 = pack8_bf16_accumulate(p1[0][0], p1[0][1], p1[0][2], p1[0][3], p1[1][0],
+                                                p1[1][1], p1[1][2], p1[1][3], dsum1);
         u32x4 pb2 = {0u, 0u, 0u, 0u};
         if constexpr (USE_R) {
             float p2[2][4];
@@ -165,9 +165,9 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     p2[sub][i] = x[sub][i] == kNegInf ? 0.f : p1[sub][i] * s2[sub][i];
-            pb2 = u32x4{pack_bf16(p2[0][0], p2[0][1]), pack_bf16(p2[0][2], p2[0][3]),
-                        pack_bf16(p2[1][0], p2[1][1]), pack_bf16(p2[1][2], p2[1][3])};
-            dsum2 = add_bf16x8(alpha * dsum2, pb2);
+            dsum2 *= alpha;
+            pb2 = pack8_bf16_accumulate(p2[0][0], p2[0][1], p2[0][2], p2[0][3], p2[1][0], p2[1][1],
+                                        p2[1][2], p2[1][3], dsum2);
         }
 
         if (!__all(alpha == 1.f)) {

@@ -50,11 +50,26 @@ __device__ __forceinline__ float bf16_lo_f32(uint32_t packed) {
 __device__ __forceinline__ float bf16_hi_f32(uint32_t packed) {
     return __builtin_bit_cast(float, packed & 0xffff0000u);
 }
-// acc + the eight bf16 values of an MFMA operand, in fp32.
-__device__ __forceinline__ float add_bf16x8(float acc, u32x4 v) {
-    const float s = ((bf16_lo_f32(v[0]) + bf16_hi_f32(v[0])) + (bf16_lo_f32(v[1]) + bf16_hi_f32(v[1]))) +
-                    ((bf16_lo_f32(v[2]) + bf16_hi_f32(v[2])) + (bf16_lo_f32(v[3]) + bf16_hi_f32(v[3])));
-    return acc + s;
+// Round eight fp32 values to bf16 -- one MFMA operand -- and add the ROUNDED values to acc
+// (v_dot2_f32_bf16 against (1, 1): one instruction per packed pair). The pairs are built as
+// bf16 vectors first and only then viewed as dwords: taking a dword of an integer vector and
+// viewing it as a bf16 pair is miscompiled by this toolchain (all four dot products read the
+// same register).
+__device__ __forceinline__ u32x4 pack8_bf16_accumulate(float p0, float p1, float p2, float p3,
+                                                      float p4, float p5, float p6, float p7,
+                                                      float &acc) {
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    bf16x2 a, b, c, d;
+    a[0] = (__bf16)p0, a[1] = (__bf16)p1;
+    b[0] = (__bf16)p2, b[1] = (__bf16)p3;
+    c[0] = (__bf16)p4, c[1] = (__bf16)p5;
+    d[0] = (__bf16)p6, d[1] = (__bf16)p7;
+    acc = __builtin_amdgcn_fdot2_f32_bf16(a, ones, acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(b, ones, acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(c, ones, acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(d, ones, acc, false);
+    return u32x4{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b),
+                 __builtin_bit_cast(uint32_t, c), __builtin_bit_cast(uint32_t, d)};
 }
 
 // Transposing LDS read (ds_read_b64_tr_b16). Within each group of 16 lanes, lane i receives

@@ -9,10 +9,10 @@
 //   * one workgroup = 4 waves = 128 query rows of one query head (32 rows per wave, one wave
 //     per SIMD, so a wave may use the whole 512-register budget: O1^T, O2^T live in the
 //     accumulation registers and the Q, R fragments in vector registers for the whole pass);
-//   * K/V tiles of 64 keys are fetched coalesced (16 lanes = one 256-byte row), parked in
-//     registers for one tile time, and written to a three-stage LDS ring whose rows are padded
-//     (not swizzled) so that every operand address is a per-lane base plus a constant: one
-//     workgroup barrier per tile;
+//   * K/V tiles of 64 keys go straight from global memory into a three-stage LDS ring
+//     (global_load_lds_dwordx4: no staging registers, no LDS write instructions; 16 lanes cover
+//     one 256-byte row). Rows are padded, not swizzled, so that every operand address is a
+//     per-lane base plus a constant: one workgroup barrier per tile;
 //   * scores are produced transposed with v_mfma_f32_32x32x16_bf16, S^T = K Q^T: each K
 //     fragment read from LDS feeds two MFMAs (the q branch and the r branch). In the S^T
 //     accumulator a lane owns ONE query row (column) and 16 of the 32 keys, so softmax
@@ -40,32 +40,123 @@ constexpr int kBR = 128;  // query rows per workgroup
 constexpr int kBC = 64;   // keys per LDS tile
 constexpr int kKB = 32;   // keys per inner block (one MFMA row block)
 
-#ifndef PLX_PF_SCHED
-#define PLX_PF_SCHED 0
+// The score MFMAs of the pipelined loop are emitted as inline assembly with VECTOR-register
+// destinations: their results feed the exp arithmetic directly. (With the compiler's choice,
+// accumulation registers, every score has to be copied out first, and such copies stall while
+// MFMAs are in flight: measured +6 cycles per copy, ~100 copies per 64-key tile.) The compiler
+// does not know these statements are MFMAs, so the two hazards it would otherwise cover are
+// handled here: the first read of a finished score block is kept >= 16 issue slots behind its
+// last MFMA (s_nop below; the ISA asks for 11 after an 8-pass MFMA), and operand order is
+// pinned by the scheduling fences of the pipeline.
+#ifndef PLX_PF_ASM_SCORES
+#define PLX_PF_ASM_SCORES 1
 #endif
-#if PLX_PF_SCHED == 0
-#define PLX_PF_SCHED_HINT() ((void)0)
+
+// Tile loads go global -> LDS directly (global_load_lds_dwordx4: LDS address = M0 + 16 * lane).
+// They are emitted as inline assembly: through the compiler builtin, the first LDS read after
+// a tile load waits for that load to land (the compiler assumes every LDS read may alias the
+// incoming tile), which exposes the full memory latency once per tile. In this kernel a tile
+// in flight is never read before the workgroup barrier that publishes it, so the only wait
+// needed is the explicit vmcnt(0) in front of that barrier (tile_barrier below).
+__device__ __forceinline__ void tile_load16(const void *gptr, uint32_t lds_byte_addr) {
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_byte_addr);
+    uint32_t saved_m0;  // M0 belongs to the compiler: put its value back
+    asm volatile(
+        "s_mov_b32 %0, m0\n\t"
+        "s_mov_b32 m0, %2\n\t"
+        "global_load_lds_dwordx4 %1, off\n\t"
+        "s_mov_b32 m0, %0"
+        : "=&s"(saved_m0)
+        : "v"(gptr), "s"(m0v));
+}
+__device__ __forceinline__ void tile_barrier() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+__device__ __forceinline__ uint32_t lds_byte_address(const void *p) {
+    typedef const char __attribute__((address_space(3))) * lds_cptr_t;
+    return (uint32_t)(uintptr_t)(lds_cptr_t)p;
+}
+
+#ifndef PLX_PF_LOOKAHEAD
+#define PLX_PF_LOOKAHEAD 3  // fragments read ahead of their MFMAs
+#endif
+
+// Timing instrumentation for kernel analysis (off in the product build): wave 0 of every
+// workgroup records wall-clock stamps (10 ns units) at phase boundaries.
+#ifdef PLX_PF_TIMING
+__device__ unsigned long long plx_pf_stamps[8192 * 12];
+#define PLX_STAMP(slot)                                                          \
+    do {                                                                         \
+        if (tid == 0 && blockIdx.x < 8192)                                       \
+            plx_pf_stamps[blockIdx.x * 12 + (slot)] = wall_clock64();            \
+    } while (0)
 #else
-#define PLX_PF_SCHED_HINT() __builtin_amdgcn_iglp_opt(PLX_PF_SCHED - 1)
+#define PLX_STAMP(slot) ((void)0)
 #endif
+
+#ifndef PLX_PF_EXIT
+#define PLX_PF_EXIT 0  // timing only: leave the kernel early at stage 1, 2, 3 (no output)
+#endif
+
+// Timing-only ablation switches for kernel analysis (results are wrong when non-zero):
+// 1 = no exp / pack arithmetic, 2 = no fragment LDS reads, 4 = no tile loads / barrier.
+#ifndef PLX_PF_ABLATE
+#define PLX_PF_ABLATE 0
+#endif
+
+// acc = A * B (first k-step) and acc += A * B, 32x32x16 bf16, all operands in vector registers
+__device__ __forceinline__ void mfma32_scores_first(f32x16 &acc, u32x4 a, u32x4 b) {
+#if PLX_PF_ASM_SCORES
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(acc) : "v"(a), "v"(b));
+#else
+    f32x16 z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+    acc = mfma32(a, b, z);
+#endif
+}
+__device__ __forceinline__ void mfma32_scores(f32x16 &acc, u32x4 a, u32x4 b) {
+#if PLX_PF_ASM_SCORES
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+#else
+    acc = mfma32(a, b, acc);
+#endif
+}
+__device__ __forceinline__ void scores_settle() {
+#if PLX_PF_ASM_SCORES
+    asm volatile("s_nop 15");
+#endif
+}
 
 template <int D, bool USE_R, bool CAUSAL>
 __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int KSTEPS = D / 16;        // k-steps of the score contraction
     constexpr int NDB = D / 32;           // 32-wide blocks of output dimensions
-    constexpr int NLD = kBC * CPR / 256;  // staging loads per thread, tile and tensor
     constexpr int STAGES = 3;
     // K rows are padded by one 16-byte chunk (16 consecutive rows, same chunk -> 16 different
     // bank groups), V rows by four chunks (the 4 consecutive rows of a transposing read land in
-    // 4 different 64-byte bank groups).
+    // 4 different 64-byte bank groups). Tiles are filled by direct global->LDS loads: one
+    // wave-wide instruction writes 64 consecutive chunks, so each lane fetches the global chunk
+    // that belongs at its LDS position (padding positions re-fetch a neighbour), and both tiles
+    // are rounded up to NDMA * 4 * 64 chunks.
     constexpr int KROW = CPR + 1, VROW = CPR + 4;  // row strides in chunks
-    constexpr int K_CHUNKS = kBC * KROW, V_CHUNKS = kBC * VROW;
+    constexpr int NDMA = (kBC * VROW + 255) / 256; // load instructions per wave, tile and tensor
+    constexpr int K_CHUNKS = NDMA * 256, V_CHUNKS = NDMA * 256;
+    static_assert(kBC * KROW <= K_CHUNKS && kBC * VROW <= V_CHUNKS, "tile allocation");
     constexpr int STAGE_CHUNKS = K_CHUNKS + V_CHUNKS;
 
     __shared__ u32x4 lds[STAGES * STAGE_CHUNKS];  // [stage][K tile | V tile]
 
     const int tid = threadIdx.x;
+    PLX_STAMP(0);
+#ifdef PLX_PF_TIMING
+    if (tid == 0 && blockIdx.x < 8192) {
+        plx_pf_stamps[blockIdx.x * 12 + 10] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);   // HW_ID
+        plx_pf_stamps[blockIdx.x * 12 + 11] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20);  // XCC_ID
+    }
+#endif
     const int w = tid >> 6, lane = tid & 63;
     const int col = lane & 31;  // MFMA column: query row within the wave's 32 rows
     const int h = lane >> 5;    // half-wave
@@ -121,39 +212,49 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // so that the tile prefetched two ahead inside that loop is always a complete one
     const int n_full = max(0, min(CAUSAL ? 2 * rb : T / kBC, T / kBC - 2));
 
-    const int st_row = tid / CPR, st_chunk = tid % CPR;  // this thread's place in a staging pass
-    u32x4 kst[NLD], vst[NLD];
-    auto issue_loads = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            // rows past T re-read row T-1: finite data, masked where it matters
-            const int key = min(kt * kBC + i * (256 / CPR) + st_row, T - 1);
-            kst[i] = *(const u32x4 *)(kbase + (int64_t)key * p.ks[2] + st_chunk * 8);
-            vst[i] = *(const u32x4 *)(vbase + (int64_t)key * p.vs[2] + st_chunk * 8);
-        }
+    // ---- global -> LDS tile loads (no staging registers, no LDS write instructions) --------
+    // Load instruction i of wave w fills LDS chunks [64*(w + 4i), +64) of a tile; lane l owns
+    // chunk g = 64*(w + 4i) + l = (row, pos) in the padded row-major layout.
+    auto dma_src = [&](int i, int row_stride_chunks, int &row, int &pos) {
+        const int g = 64 * (w + 4 * i) + lane;
+        row = min(g / row_stride_chunks, kBC - 1);
+        pos = min(g % row_stride_chunks, CPR - 1);
     };
-    // same for a tile whose 64 rows all exist: uniform 64-bit tile base + 32-bit per-thread
-    // offset, so the loop spends no vector ALU on addresses (the host bounds the row strides)
-    const uint32_t st_off_k = (uint32_t)(st_row * p.ks[2] + st_chunk * 8) * 2u;
-    const uint32_t st_off_v = (uint32_t)(st_row * p.vs[2] + st_chunk * 8) * 2u;
-    const uint32_t st_step_k = (uint32_t)((256 / CPR) * p.ks[2]) * 2u;
-    const uint32_t st_step_v = (uint32_t)((256 / CPR) * p.vs[2]) * 2u;
-    auto issue_loads_full_tile = [&](int kt) {
+    const uint32_t lds_base = lds_byte_address(lds);
+    uint32_t koff[NDMA], voff[NDMA];  // byte offsets inside a tile whose 64 rows all exist
+#pragma unroll
+    for (int i = 0; i < NDMA; ++i) {
+        int row, pos;
+        dma_src(i, KROW, row, pos);
+        koff[i] = (uint32_t)(row * p.ks[2] + pos * 8) * 2u;
+        dma_src(i, VROW, row, pos);
+        voff[i] = (uint32_t)(row * p.vs[2] + pos * 8) * 2u;
+    }
+    // tile kt with all 64 rows < T: uniform tile base + the precomputed lane offsets
+    auto dma_full_tile = [&](int kt, int stage) {
         const char *tk = (const char *)kbase + (int64_t)kt * (kBC * 2) * p.ks[2];
         const char *tv = (const char *)vbase + (int64_t)kt * (kBC * 2) * p.vs[2];
+        const uint32_t dk = lds_base + (uint32_t)(stage * STAGE_CHUNKS + 64 * w) * 16u;
+        const uint32_t dv = dk + K_CHUNKS * 16u;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            kst[i] = *(const u32x4 *)(tk + (st_off_k + i * st_step_k));
-            vst[i] = *(const u32x4 *)(tv + (st_off_v + i * st_step_v));
+        for (int i = 0; i < NDMA; ++i) {
+            tile_load16(tk + koff[i], dk + 4096u * i);
+            tile_load16(tv + voff[i], dv + 4096u * i);
         }
     };
-    auto stage_to_lds = [&](int stage) {
-        u32x4 *dk = lds + stage * STAGE_CHUNKS + st_row * KROW + st_chunk;
-        u32x4 *dv = lds + stage * STAGE_CHUNKS + K_CHUNKS + st_row * VROW + st_chunk;
+    // any tile: rows past T re-read row T-1 (finite data, masked where it matters)
+    auto dma_tile = [&](int kt, int stage) {
+        const uint32_t dk = lds_base + (uint32_t)(stage * STAGE_CHUNKS + 64 * w) * 16u;
+        const uint32_t dv = dk + K_CHUNKS * 16u;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            dk[i * (256 / CPR) * KROW] = kst[i];
-            dv[i * (256 / CPR) * VROW] = vst[i];
+        for (int i = 0; i < NDMA; ++i) {
+            int row, pos;
+            dma_src(i, KROW, row, pos);
+            const __bf16 *sk = kbase + (int64_t)min(kt * kBC + row, T - 1) * p.ks[2] + pos * 8;
+            tile_load16(sk, dk + 4096u * i);
+            dma_src(i, VROW, row, pos);
+            const __bf16 *sv = vbase + (int64_t)min(kt * kBC + row, T - 1) * p.vs[2] + pos * 8;
+            tile_load16(sv, dv + 4096u * i);
         }
     };
 
@@ -179,13 +280,18 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         return key < T && (!CAUSAL || key <= my_row);
     };
 
-    float m_ref = kNegInf, dsum1 = 0.f, dsum2 = 0.f;
-    f32x16 o1[NDB], o2[NDB];
+    // d1 / d2 are accumulated by MFMAs as well: Ones(32 x 16 keys) x P^T gives a block whose
+    // every row is the column sum of the bf16-ROUNDED P over the keys, i.e. the row sums of
+    // Algorithm 1 taken over exactly the numbers that enter O1 / O2 -- the effective attention
+    // weights then sum to one exactly, and no vector-ALU work is spent on the sums (a dot-product
+    // instruction would share the matrix pipeline and stall it; measured).
+    float m_ref = kNegInf;
+    f32x16 o1[NDB], o2[NDB], dacc1, dacc2;
+    const u32x4 ones_frag = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const float scale_log2 = p.scale * kLog2e;  // >= 0 (checked by the host)
 
     // P1 = exp2(S1*scale - m_ref), P2 = P1*S2 for one key block, left as packed bf16 MFMA
-    // operands (two groups of 16 keys). d1 / d2 add the ROUNDED values, so the effective
-    // attention weights sum to one exactly.
+    // operands (two groups of 16 keys).
     auto probs = [&](auto masked_tag, int key_base, f32x16 &s1, f32x16 &s2, u32x4(&pb1)[2],
                      u32x4(&pb2)[2]) {
         constexpr bool MASKED = decltype(masked_tag)::value;
@@ -203,12 +309,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             // B operand k-element e <-> register 8j+e <-> key 16j + 8*(e/4) + 4h + e%4
             pb1[j] = u32x4{pack_bf16(s1[8 * j + 0], s1[8 * j + 1]), pack_bf16(s1[8 * j + 2], s1[8 * j + 3]),
                            pack_bf16(s1[8 * j + 4], s1[8 * j + 5]), pack_bf16(s1[8 * j + 6], s1[8 * j + 7])};
-            dsum1 = add_bf16x8(dsum1, pb1[j]);
-            if constexpr (USE_R) {
+            if constexpr (USE_R)
                 pb2[j] = u32x4{pack_bf16(s2[8 * j + 0], s2[8 * j + 1]), pack_bf16(s2[8 * j + 2], s2[8 * j + 3]),
                                pack_bf16(s2[8 * j + 4], s2[8 * j + 5]), pack_bf16(s2[8 * j + 6], s2[8 * j + 7])};
-                dsum2 = add_bf16x8(dsum2, pb2[j]);
-            }
         }
     };
 
@@ -233,18 +336,24 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                 o1[n] = mfma32(vt, pb1[j], o1[n]);
                 if constexpr (USE_R) o2[n] = mfma32(vt, pb2[j], o2[n]);
             }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            dacc1 = mfma32(ones_frag, pb1[j], dacc1);
+            if constexpr (USE_R) dacc2 = mfma32(ones_frag, pb2[j], dacc2);
+        }
     };
 
     auto zero_state = [&]() {
-        dsum1 = 0.f;
-        dsum2 = 0.f;
 #pragma unroll
-        for (int n = 0; n < NDB; ++n)
+        for (int r = 0; r < 16; ++r) {
+            dacc1[r] = 0.f;
+            dacc2[r] = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int n = 0; n < NDB; ++n) {
                 o1[n][r] = 0.f;
                 o2[n][r] = 0.f;
             }
+        }
     };
 
     // does this wave see any key of the block starting at key_base / is every key visible?
@@ -258,63 +367,225 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     u32x4 pb1[2], pb2[2];
     pb2[0] = pb2[1] = u32x4{0u, 0u, 0u, 0u};
 
-    // =========================== fast pass: fixed reference ================================
-    zero_state();
-    issue_loads(0);
-    stage_to_lds(0);
-    issue_loads(1);  // tiles past the end re-read the last row and are never consumed
-    __syncthreads();
-    {   // reference = row maximum over the first key block (key 0 is visible to every row)
-        f32x16 t1, t2;
-        scores(0, 0, t1, t2);
-        float tmax = kNegInf;
+    // One step of the software pipeline over fully visible key blocks, written as slots of ONE
+    // MFMA each followed by its share of vector-ALU work (measured on this chip: a wave can
+    // issue about four vector instructions in the shadow of a 32x32x16 MFMA):
+    //   phase 1 : score MFMAs of the NEXT block (S1 and S2 alternate), while the vector ALU
+    //             turns the upper 16 keys of the CURRENT block into P1 / P2 (bf16 operands);
+    //   phase 2 : PV and row-sum MFMAs of the CURRENT block, while the vector ALU already turns
+    //             the lower 16 keys of the NEXT block into its P1 / P2.
+    // Every fragment slot issues the LDS read of the fragment needed kLookAhead fragments later
+    // ([K of next block | V^T of current block | K of the block after]). The scheduling fences
+    // keep this order.
+    constexpr int kLookAhead = PLX_PF_LOOKAHEAD;
+    static_assert(2 * NDB == KSTEPS, "as many V^T fragments as K fragments per key block");
+    u32x4 kf[KSTEPS], vt[KSTEPS];
+    if (PLX_PF_ABLATE & 2) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, key_ok(0, r) ? t1[r] : kNegInf);
-        m_ref = halves_max(tmax) * scale_log2;
+        for (int i = 0; i < KSTEPS; ++i) kf[i] = vt[i] = u32x4{0x3f803f80u + i, 1u, 2u, 3u};
     }
+    auto k_block_ptr = [&](int stage, int kb) {
+        return (const u32x4 *)(lds + stage * STAGE_CHUNKS + col * KROW + h + kb * kKB * KROW);
+    };
+    auto v_block_ptr = [&](int stage, int kb) {
+        return (const unsigned short *)(lds + stage * STAGE_CHUNKS + K_CHUNKS) + tr_lane_off +
+               kb * kKB * VROW * 8;
+    };
+    auto load_kfrag = [&](const u32x4 *tk_block, int ks) {
+        if (!(PLX_PF_ABLATE & 2)) kf[ks] = tk_block[2 * ks];
+    };
+    auto load_vfrag = [&](const unsigned short *tv_block, int f) {
+        if (PLX_PF_ABLATE & 2) return;
+        const int j = f / NDB, n = f % NDB;  // key group of 16, dim block of 32
+        const int off = (16 * j * VROW + 4 * n) * 8;
+        const u32x2 lo = lds_read_tr16(tv_block + off);
+        const u32x2 hi = lds_read_tr16(tv_block + off + 8 * VROW * 8);
+        vt[f] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+    };
+    auto prefetch = [&](int frag, const u32x4 *tk_next, const unsigned short *tv_cur,
+                        const u32x4 *tk_after) {
+        const int f = frag + kLookAhead;
+        if (f < KSTEPS)
+            load_kfrag(tk_next, f);
+        else if (f < 2 * KSTEPS)
+            load_vfrag(tv_cur, f - KSTEPS);
+        else
+            load_kfrag(tk_after, f - 2 * KSTEPS);
+    };
+    // exp / P2 of the 8 score registers [r0, r0+8) of a block, spread over the MFMA slots of a
+    // phase as three separate stages (scale-and-shift, exp2, times S2) in consecutive slots: a
+    // slot then holds independent instructions only, so the single wave of the SIMD never
+    // waits on the latency of its own previous vector instruction.
+    // With MASKED, `lim` is this lane's largest allowed key offset inside the block (its 4*h
+    // already subtracted): register r holds key offset 8*(r/4) + r%4.
+    const int row_lim = CAUSAL ? min(my_row, T - 1) : T - 1;  // last key this lane's row may see
+    auto exp_stages = [&](auto masked_tag, f32x16 &s1, f32x16 &s2, int r0, int slot, int n_slots,
+                          float neg_m, int lim) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        if (PLX_PF_ABLATE & 1) return;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = r0 + u;
+            const int first = u * (n_slots - 4) / 8;  // stages in slots first, first+1, first+2
+            if (slot == first) s1[r] = fmaf(s1[r], scale_log2, neg_m);
+            if (slot == first + 1) {
+                const float p1 = fast_exp2(s1[r]);
+                s1[r] = (!MASKED || 8 * (r >> 2) + (r & 3) <= lim) ? p1 : 0.f;
+            }
+            // P2: S2 is finite (rows past T re-read row T-1) and P1 = 0 where masked
+            if constexpr (USE_R)
+                if (slot == first + 2) s2[r] = s1[r] * s2[r];
+        }
+    };
+    auto pack_group = [&](const f32x16 &s, int j) {
+        if (PLX_PF_ABLATE & (1 | 32)) return ones_frag;
+        return u32x4{pack_bf16(s[8 * j + 0], s[8 * j + 1]), pack_bf16(s[8 * j + 2], s[8 * j + 3]),
+                     pack_bf16(s[8 * j + 4], s[8 * j + 5]), pack_bf16(s[8 * j + 6], s[8 * j + 7])};
+    };
+    auto pipeline_step = [&](auto masked_tag, int key_base_cur, const u32x4 *tk_next,
+                             const unsigned short *tv_cur, const u32x4 *tk_after, f32x16 &sc1,
+                             f32x16 &sc2, f32x16 &sn1, f32x16 &sn2) {
+        const int lim_cur = row_lim - key_base_cur - 4 * h;  // current block, next block
+        const int lim_next = lim_cur - kKB;
+        constexpr int SLOTS1 = 2 * KSTEPS;           // phase 1: one slot per score MFMA
+        constexpr int GROUP2 = 2 * NDB + 2;          // phase 2, per key group: PV + row sums
+        constexpr int SLOTS2 = 2 * GROUP2;
+        const float neg_m = -m_ref;
+        // ---- phase 1: scores of the next block | upper key group of the current block ------
+#pragma unroll
+        for (int sl = 0; sl < SLOTS1; ++sl) {
+            const int ks = sl / 2;
+            if (sl % 2 == 0) {
+                if (ks == 0)
+                    mfma32_scores_first(sn1, kf[ks], qf[ks]);
+                else
+                    mfma32_scores(sn1, kf[ks], qf[ks]);
+                prefetch(ks, tk_next, tv_cur, tk_after);
+            } else if constexpr (USE_R) {
+                if (ks == 0)
+                    mfma32_scores_first(sn2, kf[ks], rf[ks]);
+                else
+                    mfma32_scores(sn2, kf[ks], rf[ks]);
+            }
+            exp_stages(masked_tag, sc1, sc2, 8, sl, SLOTS1, neg_m, lim_cur);
+            if (sl == SLOTS1 - 2) pb1[1] = pack_group(sc1, 1);
+            if (sl == SLOTS1 - 1) {
+                if constexpr (USE_R) pb2[1] = pack_group(sc2, 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // ---- phase 2: PV + row sums of the current block | lower key group of the next block
+        scores_settle();
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 nb1 = {0u, 0u, 0u, 0u}, nb2 = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int sl = 0; sl < SLOTS2; ++sl) {
+            const int j = sl / GROUP2, t = sl % GROUP2;
+            if (t < 2 * NDB) {
+                const int n = t / 2, f = j * NDB + n;
+                if (t % 2 == 0) {
+                    o1[n] = mfma32(vt[f], pb1[j], o1[n]);
+                    prefetch(KSTEPS + f, tk_next, tv_cur, tk_after);
+                } else if constexpr (USE_R) {
+                    o2[n] = mfma32(vt[f], pb2[j], o2[n]);
+                }
+            } else if (t == 2 * NDB) {
+                dacc1 = mfma32(ones_frag, pb1[j], dacc1);
+            } else if constexpr (USE_R) {
+                dacc2 = mfma32(ones_frag, pb2[j], dacc2);
+            }
+            exp_stages(masked_tag, sn1, sn2, 0, sl, SLOTS2, neg_m, lim_next);
+            if (sl == SLOTS2 - 2) nb1 = pack_group(sn1, 0);
+            if (sl == SLOTS2 - 1) {
+                if constexpr (USE_R) nb2 = pack_group(sn2, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        pb1[0] = nb1;
+        pb2[0] = nb2;
+    };
 
+    // =========================== fast pass: fixed reference ================================
+    // Ring invariant at the top of iteration kt: tiles kt and (after the barrier) kt+1 are in
+    // stages kt % 3 and (kt+1) % 3 and visible to all waves. The barrier (every wave first waits
+    // for its own tile loads) also proves that nobody reads tile kt-1 any more, whose stage then
+    // receives tile kt+2: each tile load has a whole iteration to land.
+    zero_state();
+    dma_tile(0, 0);
+    dma_tile(1, 1);
+    PLX_STAMP(1);
+    tile_barrier();
+    PLX_STAMP(2);
+    if (PLX_PF_EXIT == 1) {
+        if (qf[0][0] == 0x12345678u && rf[KSTEPS - 1][3] == 0x9abcdef0u) ((uint32_t *)p.o)[tid] = qf[1][1];
+        return;
+    }
     int stage = 0;
     f32x16 sa1, sa2, sb1, sb2;
-    if (n_full > 0) scores(0, 0, sa1, sa2);
+    {
+        // Pipeline prologue: scores of block (0, 0); reference = its row maximum (key 0 is
+        // visible to every row); lower key group -> P. (Everything the loops read from registers
+        // loaded out of global memory -- the Q, R fragments -- is consumed here first, so the
+        // loops contain no wait on the vector-memory counter, which the tile loads in flight
+        // would turn into a full memory round trip.)
+        scores(0, 0, sa1, sa2);
+#pragma unroll
+        for (int f = 0; f < kLookAhead; ++f) load_kfrag(k_block_ptr(0, 1), f);
+        float tmax = kNegInf;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, key_ok(0, r) ? sa1[r] : kNegInf);
+        m_ref = halves_max(tmax) * scale_log2;
+#pragma unroll
+        for (int sl = 0; sl < 12; ++sl)
+            exp_stages(std::true_type{}, sa1, sa2, 0, sl, 12, -m_ref, row_lim - 4 * h);
+        pb1[0] = pack_group(sa1, 0);
+        if constexpr (USE_R) pb2[0] = pack_group(sa2, 0);
+    }
+    if (PLX_PF_EXIT == 2) {
+        if (pb1[0][0] == 0x12345678u && pb2[0][1] == 0x9abcdef0u) ((uint32_t *)p.o)[tid] = kf[0][0];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+    PLX_STAMP(3);
+    auto tile_steps = [&](auto masked_tag, int kt, int stage, int next_stage) {
+        // block (kt,0) -> P, PV; scores of (kt,1); K fragments of (kt+1,0)
+        pipeline_step(masked_tag, kt * kBC, k_block_ptr(stage, 1), v_block_ptr(stage, 0),
+                      k_block_ptr(next_stage, 0), sa1, sa2, sb1, sb2);
+        // block (kt,1) -> P, PV; scores of (kt+1,0); K fragments of (kt+1,1)
+        pipeline_step(masked_tag, kt * kBC + kKB, k_block_ptr(next_stage, 0), v_block_ptr(stage, 1),
+                      k_block_ptr(next_stage, 1), sb1, sb2, sa1, sa2);
+    };
     int kt = 0;
-    // tiles in which every key is visible to every row: software-pipelined, branch-free body
-    for (; kt < n_full; ++kt) {
+    // Tiles whose keys -- and those of the tile after -- are visible to every row: no masks, a
+    // branch-free body. (A step also prepares the lower half of the NEXT block, hence the -1.)
+    for (; kt < n_full - 1; ++kt) {
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
-        scores(stage, 1, sb1, sb2);
-        probs(std::false_type{}, 0, sa1, sa2, pb1, pb2);
-        accumulate(stage, 0, pb1, pb2);
-        stage_to_lds(next_stage);  // unconditional: no branch in this loop body
-        issue_loads_full_tile(kt + 2);
-        PLX_PF_SCHED_HINT();
-        __syncthreads();
-        scores(next_stage, 0, sa1, sa2);  // unused after the last full tile
-        probs(std::false_type{}, 0, sb1, sb2, pb1, pb2);
-        accumulate(stage, 1, pb1, pb2);
-        PLX_PF_SCHED_HINT();
+        const int free_stage = next_stage == STAGES - 1 ? 0 : next_stage + 1;
+        if (!(PLX_PF_ABLATE & 4)) {
+            tile_barrier();
+            dma_full_tile(kt + 2, free_stage);  // kt + 2 <= T/64 - 1 inside this loop
+        }
+        tile_steps(std::false_type{}, kt, stage, next_stage);
         stage = next_stage;
     }
-    // diagonal / tail tiles: per-wave visibility and masks
+    PLX_STAMP(4);
+    // Remaining tiles (diagonal / tail): the same pipeline with per-lane key masks. Blocks a wave
+    // cannot see at all contribute exact zeros.
     for (; kt < n_tiles; ++kt) {
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
-#pragma unroll
-        for (int kb = 0; kb < kBC / kKB; ++kb) {
-            const int key_base = kt * kBC + kb * kKB;
-            if (!block_visible(key_base)) continue;  // wave-uniform
-            scores(stage, kb, sa1, sa2);
-            if (block_full(key_base))
-                probs(std::false_type{}, key_base, sa1, sa2, pb1, pb2);
-            else
-                probs(std::true_type{}, key_base, sa1, sa2, pb1, pb2);
-            accumulate(stage, kb, pb1, pb2);
-        }
-        stage_to_lds(next_stage);
-        issue_loads(kt + 2);
-        __syncthreads();
+        const int free_stage = next_stage == STAGES - 1 ? 0 : next_stage + 1;
+        tile_barrier();
+        if ((kt + 3) * kBC <= T)  // workgroup-uniform: the tile exists completely
+            dma_full_tile(kt + 2, free_stage);
+        else
+            dma_tile(kt + 2, free_stage);
+        tile_steps(std::true_type{}, kt, stage, next_stage);
         stage = next_stage;
     }
 
+    PLX_STAMP(5);
     // overflow check: any inf/NaN in the sums means the fixed reference was too small
-    float chk = dsum1 * 0.f + dsum2 * 0.f;
+    float chk = dacc1[0] * 0.f + dacc2[0] * 0.f;
 #pragma unroll
     for (int n = 0; n < NDB; ++n)
 #pragma unroll
@@ -322,22 +593,29 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             chk = fmaf(o1[n][r], 0.f, chk);
             if constexpr (USE_R) chk = fmaf(o2[n][r], 0.f, chk);
         }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // tile loads past the end have landed
     const bool overflow = __syncthreads_or(chk != 0.f);  // NaN != 0 is true; all waves agree
+    PLX_STAMP(6);
+    if (PLX_PF_EXIT == 3) {
+        if (overflow) ((uint32_t *)p.o)[tid] = 1u;
+        return;
+    }
 
     // =========================== fallback: online max / rescale ============================
     if (overflow) {
         zero_state();
         m_ref = kNegInf;
-        issue_loads(0);
+        dma_tile(0, 0);
+        stage = 0;
         for (int t = 0; t < n_tiles; ++t) {
-            stage_to_lds(0);
-            if (t + 1 < n_tiles) issue_loads(t + 1);
-            __syncthreads();
+            const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
+            tile_barrier();  // tile t has landed; tile t-2's stage is free for tile t+1
+            dma_tile(t + 1, next_stage);
 #pragma unroll 1
             for (int kb = 0; kb < kBC / kKB; ++kb) {
                 const int key_base = t * kBC + kb * kKB;
                 if (!block_visible(key_base)) continue;
-                scores(0, kb, sa1, sa2);
+                scores(stage, kb, sa1, sa2);
                 float tmax = kNegInf;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
@@ -347,29 +625,36 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                 const float m_use = m_new == kNegInf ? 0.f : m_new;
                 const float alpha = fast_exp2(m_ref - m_use);  // 0 while m_ref = -inf
                 m_ref = m_new;
-                dsum1 *= alpha;
-                dsum2 *= alpha;
 #pragma unroll
-                for (int n = 0; n < NDB; ++n)
+                for (int r = 0; r < 16; ++r) {
+                    dacc1[r] *= alpha;
+                    if constexpr (USE_R) dacc2[r] *= alpha;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
+                    for (int n = 0; n < NDB; ++n) {
                         o1[n][r] *= alpha;
                         if constexpr (USE_R) o2[n][r] *= alpha;
                     }
+                }
                 probs(std::true_type{}, key_base, sa1, sa2, pb1, pb2);
-                accumulate(0, kb, pb1, pb2);
+                accumulate(stage, kb, pb1, pb2);
             }
-            __syncthreads();
+            stage = next_stage;
         }
+        tile_barrier();  // outstanding tile loads land before the workgroup may exit
     }
 
     // ---- epilogue: O^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4, row my_row ----
-    dsum1 = halves_sum(dsum1);
-    dsum2 = halves_sum(dsum2);
-    if (my_row < T) {
-        const float inv = dsum1 > 0.f ? 1.f / dsum1 : 0.f;
+    // Every row of the row-sum accumulators holds the sum over all keys of this lane's query
+    // row. A lane owns one output ROW, so direct stores would scatter 8 bytes over 32 rows per
+    // instruction; the wave instead transposes its 32 x D tile through LDS (all tile loads have
+    // landed, every wave is past its last read) and writes whole 256-byte rows, 16 bytes a lane.
+    {
+        const float dsum1 = dacc1[0], dsum2 = dacc2[0];
+        const float inv = dsum1 > 0.f ? 1.f / dsum1 : 0.f;  // empty key set: zeros
         const float gain = inv * (1.f + dsum2 * inv);
-        __bf16 *orow = (__bf16 *)p.o + b * p.os[0] + hq * p.os[1] + my_row * p.os[2];
+        constexpr int OROW = CPR + 1;  // padded row of the staging tile, in 16-byte chunks
+        u32x4 *otile = lds + w * (32 * OROW);
+        unsigned short *otile16 = (unsigned short *)otile;
 #pragma unroll
         for (int n = 0; n < NDB; ++n)
 #pragma unroll
@@ -380,11 +665,33 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                     const int r = 4 * q4 + i;
                     y[i] = o1[n][r] * gain - (USE_R ? o2[n][r] * inv : 0.f);
                 }
-                u32x2 packed = {pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
-                *(u32x2 *)(orow + 32 * n + 8 * q4 + 4 * h) = packed;
+                const u32x2 packed = {pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
+                *(u32x2 *)(otile16 + col * (OROW * 8) + 32 * n + 8 * q4 + 4 * h) = packed;
             }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __bf16 *obase = (__bf16 *)p.o + b * p.os[0] + hq * p.os[1];
+        constexpr int RPI = 64 / CPR;  // rows covered by one wave-wide 16-byte store
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int rr = i * RPI + lane / CPR, chunk = lane % CPR;
+            const int row = row0 + rr;
+            if (row < T) *(u32x4 *)(obase + (int64_t)row * p.os[2] + chunk * 8) = otile[rr * OROW + chunk];
+        }
     }
+    PLX_STAMP(7);
+#ifdef PLX_PF_TIMING
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    PLX_STAMP(8);
+#endif
 }
+
+#ifdef PLX_PF_TIMING
+extern "C" int parallax_debug_read_prefill_stamps(void *host_dst, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(plx_pf_stamps), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif
 
 template <int D>
 static hipError_t launch_prefill_d(const PrefillParams &p, hipStream_t stream) {
