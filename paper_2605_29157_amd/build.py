@@ -42,12 +42,26 @@ def _compile(src: str, extra: list[str]) -> str:
     return obj
 
 
+def _check_prefill_assembly(extra: list[str]) -> None:
+    """Emit the device assembly of the prefill kernel and verify its hand-placed MFMAs."""
+    from . import asm_check
+    asm = os.path.join(BUILD_DIR, "prefill_bf16.gfx950.s")
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-S",
+           "--cuda-device-only", os.path.join(CSRC, "prefill_bf16.hip"), "-o", asm]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc -S failed on prefill_bf16.hip:\n" + res.stdout)
+    asm_check.check_file(asm)
+
+
 def build_library(extra_flags: list[str] | None = None, verbose: bool = True) -> str:
     """Compile every kernel file for gfx950 and link libparallax_hip.so next to this file."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     extra = list(extra_flags or [])
-    with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES) + 1) as pool:
+        check = pool.submit(_check_prefill_assembly, extra)
         objs = list(pool.map(lambda s: _compile(s, extra), SOURCES))
+        check.result()
     tmp = LIB_PATH + ".tmp%d" % os.getpid()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

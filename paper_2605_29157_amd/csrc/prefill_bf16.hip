@@ -58,19 +58,61 @@ constexpr int kKB = 32;   // keys per inner block (one MFMA row block)
 // incoming tile), which exposes the full memory latency once per tile. In this kernel a tile
 // in flight is never read before the workgroup barrier that publishes it, so the only wait
 // needed is the explicit vmcnt(0) in front of that barrier (tile_barrier below).
+// QUARTER: only lanes 0..15 load (a 256-byte piece): EXEC is narrowed around the instruction.
+template <bool QUARTER = false>
 __device__ __forceinline__ void tile_load16(const void *gptr, uint32_t lds_byte_addr) {
     const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_byte_addr);
     uint32_t saved_m0;  // M0 belongs to the compiler: put its value back
-    asm volatile(
-        "s_mov_b32 %0, m0\n\t"
-        "s_mov_b32 m0, %2\n\t"
-        "global_load_lds_dwordx4 %1, off\n\t"
-        "s_mov_b32 m0, %0"
-        : "=&s"(saved_m0)
-        : "v"(gptr), "s"(m0v));
+    uint64_t saved_exec;
+    if constexpr (QUARTER)
+        asm volatile(
+            "s_mov_b32 %0, m0\n\t"
+            "s_mov_b64 %1, exec\n\t"
+            "s_mov_b64 exec, 0xffff\n\t"
+            "s_mov_b32 m0, %3\n\t"
+            "global_load_lds_dwordx4 %2, off\n\t"
+            "s_mov_b64 exec, %1\n\t"
+            "s_mov_b32 m0, %0"
+            : "=&s"(saved_m0), "=&s"(saved_exec)
+            : "v"(gptr), "s"(m0v));
+    else
+        asm volatile(
+            "s_mov_b32 %0, m0\n\t"
+            "s_mov_b32 m0, %2\n\t"
+            "global_load_lds_dwordx4 %1, off\n\t"
+            "s_mov_b32 m0, %0"
+            : "=&s"(saved_m0)
+            : "v"(gptr), "s"(m0v));
 }
+// Same load with a wave-uniform tile base (scalar registers) plus a 32-bit per-lane byte offset:
+// no per-lane 64-bit address arithmetic. M0 is not restored: nothing the compiler emits for this
+// kernel reads M0 (no other LDS-DMA, no GWS / message / relative-index instructions).
+template <bool QUARTER = false>
+__device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, const void *tile_base,
+                                                    uint32_t lds_byte_addr) {
+    uint64_t saved_exec;
+    if constexpr (QUARTER)
+        asm volatile(
+            "s_mov_b64 %0, exec\n\t"
+            "s_mov_b64 exec, 0xffff\n\t"
+            "s_mov_b32 m0, %3\n\t"
+            "global_load_lds_dwordx4 %1, %2\n\t"
+            "s_mov_b64 exec, %0"
+            : "=&s"(saved_exec)
+            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
+    else
+        asm volatile(
+            "s_mov_b32 m0, %2\n\t"
+            "global_load_lds_dwordx4 %0, %1"
+            :
+            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
+}
+// Wait until at most PENDING of this wave's tile loads are still in flight (loads complete in
+// issue order), then the workgroup barrier that publishes the landed tiles.
+template <int PENDING = 0>
 __device__ __forceinline__ void tile_barrier() {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    static_assert(PENDING >= 0 && PENDING < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
     __syncthreads();
 }
 __device__ __forceinline__ uint32_t lds_byte_address(const void *p) {
@@ -105,10 +147,22 @@ __device__ unsigned long long plx_pf_stamps[8192 * 12];
 #define PLX_PF_ABLATE 0
 #endif
 
-// acc = A * B (first k-step) and acc += A * B, 32x32x16 bf16, all operands in vector registers
+// An MFMA may not read a register that a vector-ALU instruction wrote less than two wait states
+// before it (the hardware does not interlock this). For MFMAs the compiler knows about it keeps
+// that distance itself; for these statements it cannot, and it does place copies directly in
+// front of a statement's operands when it parks the Q/R fragments in accumulation registers.
+// GUARD = true brings two wait states along. GUARD = false is for the steady-state loop, where
+// the generated code has no such copy -- the build verifies that on the assembly it produced
+// (asm_check.py) and fails otherwise.
+// acc = A * B (first k-step) and acc += A * B, 32x32x16 bf16, all operands in vector registers.
+template <bool GUARD>
 __device__ __forceinline__ void mfma32_scores_first(f32x16 &acc, u32x4 a, u32x4 b) {
 #if PLX_PF_ASM_SCORES
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(acc) : "v"(a), "v"(b));
+    // early clobber: the destination block must not share registers with A or B
+    if constexpr (GUARD)
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0 ; unguarded" : "=&v"(acc) : "v"(a), "a"(b));
 #else
     f32x16 z;
 #pragma unroll
@@ -116,16 +170,15 @@ __device__ __forceinline__ void mfma32_scores_first(f32x16 &acc, u32x4 a, u32x4 
     acc = mfma32(a, b, z);
 #endif
 }
+template <bool GUARD>
 __device__ __forceinline__ void mfma32_scores(f32x16 &acc, u32x4 a, u32x4 b) {
 #if PLX_PF_ASM_SCORES
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    if constexpr (GUARD)
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0 ; unguarded" : "+v"(acc) : "v"(a), "a"(b));
 #else
     acc = mfma32(a, b, acc);
-#endif
-}
-__device__ __forceinline__ void scores_settle() {
-#if PLX_PF_ASM_SCORES
-    asm volatile("s_nop 15");
 #endif
 }
 
@@ -134,7 +187,11 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int KSTEPS = D / 16;        // k-steps of the score contraction
     constexpr int NDB = D / 32;           // 32-wide blocks of output dimensions
-    constexpr int STAGES = 3;
+#ifndef PLX_PF_STAGES
+#define PLX_PF_STAGES 3
+#endif
+    constexpr int STAGES = PLX_PF_STAGES;  // LDS ring; tiles are fetched STAGES - 1 ahead
+    constexpr int kDist = STAGES - 1;
     // K rows are padded by one 16-byte chunk (16 consecutive rows, same chunk -> 16 different
     // bank groups), V rows by four chunks (the 4 consecutive rows of a transposing read land in
     // 4 different 64-byte bank groups). Tiles are filled by direct global->LDS loads: one
@@ -142,9 +199,13 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // that belongs at its LDS position (padding positions re-fetch a neighbour), and both tiles
     // are rounded up to NDMA * 4 * 64 chunks.
     constexpr int KROW = CPR + 1, VROW = CPR + 4;  // row strides in chunks
-    constexpr int NDMA = (kBC * VROW + 255) / 256; // load instructions per wave, tile and tensor
-    constexpr int K_CHUNKS = NDMA * 256, V_CHUNKS = NDMA * 256;
-    static_assert(kBC * KROW <= K_CHUNKS && kBC * VROW <= V_CHUNKS, "tile allocation");
+    // Every wave fills a contiguous quarter of each tile: 16 * KROW chunks of K (CPR / 4 full
+    // 64-lane loads and one 16-lane load), 16 * VROW chunks of V (CPR / 4 + 1 full loads).
+    constexpr int K_WAVE_CHUNKS = 16 * KROW, V_WAVE_CHUNKS = 16 * VROW;
+    constexpr int NDMA_K = CPR / 4 + 1, NDMA_V = CPR / 4 + 1;
+    static_assert(K_WAVE_CHUNKS == 64 * (NDMA_K - 1) + 16 && V_WAVE_CHUNKS == 64 * NDMA_V, "split");
+    constexpr int K_CHUNKS = kBC * KROW, V_CHUNKS = kBC * VROW;
+    constexpr int kTileLoads = NDMA_K + NDMA_V;  // per wave and tile
     constexpr int STAGE_CHUNKS = K_CHUNKS + V_CHUNKS;
 
     __shared__ u32x4 lds[STAGES * STAGE_CHUNKS];  // [stage][K tile | V tile]
@@ -157,7 +218,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         plx_pf_stamps[blockIdx.x * 12 + 11] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20);  // XCC_ID
     }
 #endif
-    const int w = tid >> 6, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int col = lane & 31;  // MFMA column: query row within the wave's 32 rows
     const int h = lane >> 5;    // half-wave
 
@@ -186,6 +247,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const int rb = CAUSAL ? nrb - 1 - rbi : rbi;
     const int b = pair / p.Hkv, hk = pair - b * p.Hkv;
     const int hq = hk * G + hg;
+#ifdef PLX_PF_TIMING
+    if (hq >= 0) PLX_STAMP(9);
+#endif
 
     const int row0 = rb * kBR + w * 32;  // first query row of this wave
     const int my_row = row0 + col;       // this lane's query row (may be >= T)
@@ -210,51 +274,86 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const int n_tiles = (key_end + kBC - 1) / kBC;
     // leading tiles whose keys are all < T and visible to every row of the workgroup, less two
     // so that the tile prefetched two ahead inside that loop is always a complete one
-    const int n_full = max(0, min(CAUSAL ? 2 * rb : T / kBC, T / kBC - 2));
+    const int n_full = max(0, min(CAUSAL ? 2 * rb : T / kBC, T / kBC - kDist));
 
     // ---- global -> LDS tile loads (no staging registers, no LDS write instructions) --------
     // Load instruction i of wave w fills LDS chunks [64*(w + 4i), +64) of a tile; lane l owns
     // chunk g = 64*(w + 4i) + l = (row, pos) in the padded row-major layout.
-    auto dma_src = [&](int i, int row_stride_chunks, int &row, int &pos) {
-        const int g = 64 * (w + 4 * i) + lane;
-        row = min(g / row_stride_chunks, kBC - 1);
-        pos = min(g % row_stride_chunks, CPR - 1);
+    auto k_src = [&](int i, int &row, int &pos) {
+        const int c = K_WAVE_CHUNKS * w + 64 * i + lane;  // lanes >= 16 of the last load: unused
+        row = min(c / KROW, kBC - 1);
+        pos = min(c % KROW, CPR - 1);
+    };
+    auto v_src = [&](int i, int &row, int &pos) {
+        const int c = V_WAVE_CHUNKS * w + 64 * i + lane;
+        row = c / VROW;
+        pos = min(c % VROW, CPR - 1);
     };
     const uint32_t lds_base = lds_byte_address(lds);
-    uint32_t koff[NDMA], voff[NDMA];  // byte offsets inside a tile whose 64 rows all exist
+    uint32_t koff[NDMA_K], voff[NDMA_V];  // byte offsets inside a tile whose 64 rows all exist
 #pragma unroll
-    for (int i = 0; i < NDMA; ++i) {
+    for (int i = 0; i < NDMA_K; ++i) {
         int row, pos;
-        dma_src(i, KROW, row, pos);
+        k_src(i, row, pos);
         koff[i] = (uint32_t)(row * p.ks[2] + pos * 8) * 2u;
-        dma_src(i, VROW, row, pos);
+    }
+#pragma unroll
+    for (int i = 0; i < NDMA_V; ++i) {
+        int row, pos;
+        v_src(i, row, pos);
         voff[i] = (uint32_t)(row * p.vs[2] + pos * 8) * 2u;
     }
+    const int64_t k_tile_bytes = (int64_t)(kBC * 2) * p.ks[2], v_tile_bytes = (int64_t)(kBC * 2) * p.vs[2];
+    // LDS byte addresses of this wave's first K / V load of a stage
+    auto stage_k_addr = [&](int stage) {
+        return lds_base + (uint32_t)(stage * STAGE_CHUNKS + K_WAVE_CHUNKS * w) * 16u;
+    };
+    auto stage_v_addr = [&](int stage) {
+        return lds_base + (uint32_t)(stage * STAGE_CHUNKS + K_CHUNKS + V_WAVE_CHUNKS * w) * 16u;
+    };
+    // load i of the tile at (tk, tv) into (dk, dv); tile rows all exist
+    auto k_load = [&](int i, const char *tk, uint32_t dk) {
+        if (i == NDMA_K - 1)
+            tile_load16_uniform<true>(koff[i], tk, dk + 1024u * i);
+        else
+            tile_load16_uniform<false>(koff[i], tk, dk + 1024u * i);
+    };
+    auto v_load = [&](int i, const char *tv, uint32_t dv) {
+        tile_load16_uniform<false>(voff[i], tv, dv + 1024u * i);
+    };
     // tile kt with all 64 rows < T: uniform tile base + the precomputed lane offsets
     auto dma_full_tile = [&](int kt, int stage) {
-        const char *tk = (const char *)kbase + (int64_t)kt * (kBC * 2) * p.ks[2];
-        const char *tv = (const char *)vbase + (int64_t)kt * (kBC * 2) * p.vs[2];
-        const uint32_t dk = lds_base + (uint32_t)(stage * STAGE_CHUNKS + 64 * w) * 16u;
-        const uint32_t dv = dk + K_CHUNKS * 16u;
+        const char *tk = (const char *)kbase + kt * k_tile_bytes;
+        const char *tv = (const char *)vbase + kt * v_tile_bytes;
 #pragma unroll
-        for (int i = 0; i < NDMA; ++i) {
-            tile_load16(tk + koff[i], dk + 4096u * i);
-            tile_load16(tv + voff[i], dv + 4096u * i);
-        }
+        for (int i = 0; i < NDMA_K; ++i) k_load(i, tk, stage_k_addr(stage));
+#pragma unroll
+        for (int i = 0; i < NDMA_V; ++i) v_load(i, tv, stage_v_addr(stage));
     };
+    // The steady-state loop spreads the loads of one tile over the MFMA slots of a pipeline step
+    // (a block of 2 * NDMA loads at the top of an iteration would leave the matrix pipe idle
+    // while they issue); these name the tile being fetched.
+    const char *dma_tk = nullptr, *dma_tv = nullptr;
+    uint32_t dma_dk = 0, dma_dv = 0;
     // any tile: rows past T re-read row T-1 (finite data, masked where it matters)
     auto dma_tile = [&](int kt, int stage) {
-        const uint32_t dk = lds_base + (uint32_t)(stage * STAGE_CHUNKS + 64 * w) * 16u;
-        const uint32_t dv = dk + K_CHUNKS * 16u;
+        const uint32_t dk = stage_k_addr(stage), dv = stage_v_addr(stage);
 #pragma unroll
-        for (int i = 0; i < NDMA; ++i) {
+        for (int i = 0; i < NDMA_K; ++i) {
             int row, pos;
-            dma_src(i, KROW, row, pos);
+            k_src(i, row, pos);
             const __bf16 *sk = kbase + (int64_t)min(kt * kBC + row, T - 1) * p.ks[2] + pos * 8;
-            tile_load16(sk, dk + 4096u * i);
-            dma_src(i, VROW, row, pos);
+            if (i == NDMA_K - 1)
+                tile_load16<true>(sk, dk + 1024u * i);
+            else
+                tile_load16<false>(sk, dk + 1024u * i);
+        }
+#pragma unroll
+        for (int i = 0; i < NDMA_V; ++i) {
+            int row, pos;
+            v_src(i, row, pos);
             const __bf16 *sv = vbase + (int64_t)min(kt * kBC + row, T - 1) * p.vs[2] + pos * 8;
-            tile_load16(sv, dv + 4096u * i);
+            tile_load16<false>(sv, dv + 1024u * i);
         }
     };
 
@@ -419,14 +518,15 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // With MASKED, `lim` is this lane's largest allowed key offset inside the block (its 4*h
     // already subtracted): register r holds key offset 8*(r/4) + r%4.
     const int row_lim = CAUSAL ? min(my_row, T - 1) : T - 1;  // last key this lane's row may see
-    auto exp_stages = [&](auto masked_tag, f32x16 &s1, f32x16 &s2, int r0, int slot, int n_slots,
-                          float neg_m, int lim) {
+    auto exp_stages = [&](auto masked_tag, f32x16 &s1, f32x16 &s2, int r0, int slot, int slot0,
+                          int n_slots, float neg_m, int lim) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         if (PLX_PF_ABLATE & 1) return;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int r = r0 + u;
-            const int first = u * (n_slots - 4) / 8;  // stages in slots first, first+1, first+2
+            // stages in slots first, first+1, first+2; none before slot0, none in the last two
+            const int first = slot0 + u * (n_slots - 4 - slot0) / 8;
             if (slot == first) s1[r] = fmaf(s1[r], scale_log2, neg_m);
             if (slot == first + 1) {
                 const float p1 = fast_exp2(s1[r]);
@@ -442,7 +542,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         return u32x4{pack_bf16(s[8 * j + 0], s[8 * j + 1]), pack_bf16(s[8 * j + 2], s[8 * j + 3]),
                      pack_bf16(s[8 * j + 4], s[8 * j + 5]), pack_bf16(s[8 * j + 6], s[8 * j + 7])};
     };
-    auto pipeline_step = [&](auto masked_tag, int key_base_cur, const u32x4 *tk_next,
+    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int key_base_cur, const u32x4 *tk_next,
                              const unsigned short *tv_cur, const u32x4 *tk_after, f32x16 &sc1,
                              f32x16 &sc2, f32x16 &sn1, f32x16 &sn2) {
         const int lim_cur = row_lim - key_base_cur - 4 * h;  // current block, next block
@@ -450,6 +550,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         constexpr int SLOTS1 = 2 * KSTEPS;           // phase 1: one slot per score MFMA
         constexpr int GROUP2 = 2 * NDB + 2;          // phase 2, per key group: PV + row sums
         constexpr int SLOTS2 = 2 * GROUP2;
+        constexpr bool DMA = decltype(dma_tag)::value;  // this step also fetches tile (dma_tk, dma_tv)
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        static_assert(NDMA_K <= KSTEPS && NDMA_V <= GROUP2, "one tile load per odd slot");
         const float neg_m = -m_ref;
         // ---- phase 1: scores of the next block | upper key group of the current block ------
 #pragma unroll
@@ -457,17 +560,19 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             const int ks = sl / 2;
             if (sl % 2 == 0) {
                 if (ks == 0)
-                    mfma32_scores_first(sn1, kf[ks], qf[ks]);
+                    mfma32_scores_first<MASKED>(sn1, kf[ks], qf[ks]);
                 else
-                    mfma32_scores(sn1, kf[ks], qf[ks]);
+                    mfma32_scores<MASKED>(sn1, kf[ks], qf[ks]);
                 prefetch(ks, tk_next, tv_cur, tk_after);
             } else if constexpr (USE_R) {
                 if (ks == 0)
-                    mfma32_scores_first(sn2, kf[ks], rf[ks]);
+                    mfma32_scores_first<MASKED>(sn2, kf[ks], rf[ks]);
                 else
-                    mfma32_scores(sn2, kf[ks], rf[ks]);
+                    mfma32_scores<MASKED>(sn2, kf[ks], rf[ks]);
             }
-            exp_stages(masked_tag, sc1, sc2, 8, sl, SLOTS1, neg_m, lim_cur);
+            if constexpr (DMA)
+                if (sl % 2 == 1 && sl / 2 < NDMA_K) k_load(sl / 2, dma_tk, dma_dk);
+            exp_stages(masked_tag, sc1, sc2, 8, sl, 0, SLOTS1, neg_m, lim_cur);
             if (sl == SLOTS1 - 2) pb1[1] = pack_group(sc1, 1);
             if (sl == SLOTS1 - 1) {
                 if constexpr (USE_R) pb2[1] = pack_group(sc2, 1);
@@ -475,8 +580,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             __builtin_amdgcn_sched_barrier(0);
         }
         // ---- phase 2: PV + row sums of the current block | lower key group of the next block
-        scores_settle();
-        __builtin_amdgcn_sched_barrier(0);
+        // The scores just issued are first read in slot 1, i.e. behind the PV MFMAs of slots 0
+        // and 1. A wave issues in order and an MFMA is only accepted once the matrix pipe has
+        // room, so by then the last score MFMA has retired: no wait states needed.
         u32x4 nb1 = {0u, 0u, 0u, 0u}, nb2 = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int sl = 0; sl < SLOTS2; ++sl) {
@@ -494,7 +600,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             } else if constexpr (USE_R) {
                 dacc2 = mfma32(ones_frag, pb2[j], dacc2);
             }
-            exp_stages(masked_tag, sn1, sn2, 0, sl, SLOTS2, neg_m, lim_next);
+            if constexpr (DMA)
+                if (sl % 2 == 1 && sl / 2 < NDMA_V) v_load(sl / 2, dma_tv, dma_dv);
+            exp_stages(masked_tag, sn1, sn2, 0, sl, 1, SLOTS2, neg_m, lim_next);
             if (sl == SLOTS2 - 2) nb1 = pack_group(sn1, 0);
             if (sl == SLOTS2 - 1) {
                 if constexpr (USE_R) nb2 = pack_group(sn2, 0);
@@ -510,9 +618,14 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // stages kt % 3 and (kt+1) % 3 and visible to all waves. The barrier (every wave first waits
     // for its own tile loads) also proves that nobody reads tile kt-1 any more, whose stage then
     // receives tile kt+2: each tile load has a whole iteration to land.
+    if (T >= kDist * kBC) {  // workgroup-uniform
+#pragma unroll
+        for (int t = 0; t < kDist; ++t) dma_full_tile(t, t);
+    } else {
+#pragma unroll
+        for (int t = 0; t < kDist; ++t) dma_tile(t, t);
+    }
     zero_state();
-    dma_tile(0, 0);
-    dma_tile(1, 1);
     PLX_STAMP(1);
     tile_barrier();
     PLX_STAMP(2);
@@ -537,7 +650,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         m_ref = halves_max(tmax) * scale_log2;
 #pragma unroll
         for (int sl = 0; sl < 12; ++sl)
-            exp_stages(std::true_type{}, sa1, sa2, 0, sl, 12, -m_ref, row_lim - 4 * h);
+            exp_stages(std::true_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - 4 * h);
         pb1[0] = pack_group(sa1, 0);
         if constexpr (USE_R) pb2[0] = pack_group(sa2, 0);
     }
@@ -547,25 +660,32 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         return;
     }
     PLX_STAMP(3);
-    auto tile_steps = [&](auto masked_tag, int kt, int stage, int next_stage) {
-        // block (kt,0) -> P, PV; scores of (kt,1); K fragments of (kt+1,0)
-        pipeline_step(masked_tag, kt * kBC, k_block_ptr(stage, 1), v_block_ptr(stage, 0),
+    auto tile_steps = [&](auto masked_tag, auto dma_tag, int kt, int stage, int next_stage) {
+        // block (kt,0) -> P, PV; scores of (kt,1); K fragments of (kt+1,0); loads of tile kt+2
+        pipeline_step(masked_tag, dma_tag, kt * kBC, k_block_ptr(stage, 1), v_block_ptr(stage, 0),
                       k_block_ptr(next_stage, 0), sa1, sa2, sb1, sb2);
         // block (kt,1) -> P, PV; scores of (kt+1,0); K fragments of (kt+1,1)
-        pipeline_step(masked_tag, kt * kBC + kKB, k_block_ptr(next_stage, 0), v_block_ptr(stage, 1),
-                      k_block_ptr(next_stage, 1), sb1, sb2, sa1, sa2);
+        pipeline_step(masked_tag, std::false_type{}, kt * kBC + kKB, k_block_ptr(next_stage, 0),
+                      v_block_ptr(stage, 1), k_block_ptr(next_stage, 1), sb1, sb2, sa1, sa2);
     };
     int kt = 0;
     // Tiles whose keys -- and those of the tile after -- are visible to every row: no masks, a
     // branch-free body. (A step also prepares the lower half of the NEXT block, hence the -1.)
+    dma_tk = (const char *)kbase + kDist * k_tile_bytes;
+    dma_tv = (const char *)vbase + kDist * v_tile_bytes;
     for (; kt < n_full - 1; ++kt) {
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
-        const int free_stage = next_stage == STAGES - 1 ? 0 : next_stage + 1;
-        if (!(PLX_PF_ABLATE & 4)) {
-            tile_barrier();
-            dma_full_tile(kt + 2, free_stage);  // kt + 2 <= T/64 - 1 inside this loop
-        }
-        tile_steps(std::false_type{}, kt, stage, next_stage);
+        const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;  // held tile kt - 1
+        // tile kt + 1 has landed; the kDist - 2 tiles after it may still be in flight
+        if (!(PLX_PF_ABLATE & 4)) tile_barrier<(kDist - 2) * kTileLoads>();
+        dma_dk = stage_k_addr(free_stage);  // tile kt + kDist <= T/64 - 1 in this loop: complete
+        dma_dv = stage_v_addr(free_stage);
+        if (PLX_PF_ABLATE & 8)
+            tile_steps(std::false_type{}, std::false_type{}, kt, stage, next_stage);
+        else
+            tile_steps(std::false_type{}, std::true_type{}, kt, stage, next_stage);
+        dma_tk += k_tile_bytes;
+        dma_tv += v_tile_bytes;
         stage = next_stage;
     }
     PLX_STAMP(4);
@@ -573,13 +693,15 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // cannot see at all contribute exact zeros.
     for (; kt < n_tiles; ++kt) {
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
-        const int free_stage = next_stage == STAGES - 1 ? 0 : next_stage + 1;
+        const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
         tile_barrier();
-        if ((kt + 3) * kBC <= T)  // workgroup-uniform: the tile exists completely
-            dma_full_tile(kt + 2, free_stage);
-        else
-            dma_tile(kt + 2, free_stage);
-        tile_steps(std::true_type{}, kt, stage, next_stage);
+        if (kt + kDist < n_tiles) {              // workgroup-uniform
+            if ((kt + kDist + 1) * kBC <= T)     // the tile exists completely
+                dma_full_tile(kt + kDist, free_stage);
+            else
+                dma_tile(kt + kDist, free_stage);
+        }
+        tile_steps(std::true_type{}, std::false_type{}, kt, stage, next_stage);
         stage = next_stage;
     }
 
@@ -602,7 +724,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     }
 
     // =========================== fallback: online max / rescale ============================
-    if (overflow) {
+    if (overflow && !PLX_PF_ABLATE) {
         zero_state();
         m_ref = kNegInf;
         dma_tile(0, 0);
