@@ -58,23 +58,25 @@ constexpr int kKB = 32;   // keys per inner block (one MFMA row block)
 // incoming tile), which exposes the full memory latency once per tile. In this kernel a tile
 // in flight is never read before the workgroup barrier that publishes it, so the only wait
 // needed is the explicit vmcnt(0) in front of that barrier (tile_barrier below).
-// QUARTER: only lanes 0..15 load (a 256-byte piece): EXEC is narrowed around the instruction.
-template <bool QUARTER = false>
+// LANES < 64: only lanes 0..LANES-1 load (a shorter piece): EXEC is narrowed around the
+// instruction.
+template <int LANES = 64>
 __device__ __forceinline__ void tile_load16(const void *gptr, uint32_t lds_byte_addr) {
+    static_assert(LANES == 64 || LANES == 32 || LANES == 16, "piece sizes in use");
     const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_byte_addr);
     uint32_t saved_m0;  // M0 belongs to the compiler: put its value back
     uint64_t saved_exec;
-    if constexpr (QUARTER)
+    if constexpr (LANES < 64)
         asm volatile(
             "s_mov_b32 %0, m0\n\t"
             "s_mov_b64 %1, exec\n\t"
-            "s_mov_b64 exec, 0xffff\n\t"
+            "s_mov_b64 exec, %4\n\t"
             "s_mov_b32 m0, %3\n\t"
             "global_load_lds_dwordx4 %2, off\n\t"
             "s_mov_b64 exec, %1\n\t"
             "s_mov_b32 m0, %0"
             : "=&s"(saved_m0), "=&s"(saved_exec)
-            : "v"(gptr), "s"(m0v));
+            : "v"(gptr), "s"(m0v), "n"((1ull << (LANES % 64)) - 1ull));
     else
         asm volatile(
             "s_mov_b32 %0, m0\n\t"
@@ -119,6 +121,12 @@ __device__ __forceinline__ uint32_t lds_byte_address(const void *p) {
     typedef const char __attribute__((address_space(3))) * lds_cptr_t;
     return (uint32_t)(uintptr_t)(lds_cptr_t)p;
 }
+
+// Row sums d1, d2 of tiles that every row sees completely: per-lane fp32 adds of the unrounded
+// P1 / P2 (1) instead of MFMAs against a matrix of ones over the bf16-rounded values (0).
+#ifndef PLX_PF_VALU_SUMS
+#define PLX_PF_VALU_SUMS 1
+#endif
 
 #ifndef PLX_PF_LOOKAHEAD
 #define PLX_PF_LOOKAHEAD 3  // fragments read ahead of their MFMAs
@@ -208,7 +216,12 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     constexpr int kTileLoads = NDMA_K + NDMA_V;  // per wave and tile
     constexpr int STAGE_CHUNKS = K_CHUNKS + V_CHUNKS;
 
-    __shared__ u32x4 lds[STAGES * STAGE_CHUNKS];  // [stage][K tile | V tile]
+    // Behind the ring: one padded 32 x D tile per wave. It receives the wave's Q rows at the
+    // start and stages its output rows at the end.
+    constexpr int WAVE_TILE_CHUNKS = 32 * KROW;
+    constexpr int QZONE = STAGES * STAGE_CHUNKS;
+    static_assert(STAGES >= 3 && 4 * WAVE_TILE_CHUNKS <= STAGE_CHUNKS, "R rows land in ring stage 2");
+    __shared__ u32x4 lds[STAGES * STAGE_CHUNKS + 4 * WAVE_TILE_CHUNKS];  // [stage][K tile | V tile], Q
 
     const int tid = threadIdx.x;
     PLX_STAMP(0);
@@ -255,17 +268,36 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const int my_row = row0 + col;       // this lane's query row (may be >= T)
     const int ld_qrow = min(my_row, T - 1);
 
-    // ---- Q^T / R^T B operands: column = query row, k-elements = 8 dims of chunk 2*ks + h ----
-    u32x4 qf[KSTEPS], rf[KSTEPS];
+    // ---- Q / R rows of this wave: global -> LDS, whole rows (a lane fetching its own MFMA
+    // fragments straight from global memory would touch 64 different rows per instruction).
+    // Padded like a K tile; nobody else reads them, so no barrier is needed for them. Q lands
+    // behind the ring, R in ring stage 2, which the tile loads do not reach before the first
+    // loop iteration -- by then the fragments are in registers.
+    constexpr int NDMA_Q = CPR / 2 + 1;  // 32 * KROW chunks = CPR / 2 full loads + one 32-lane load
+    static_assert(WAVE_TILE_CHUNKS == 64 * (NDMA_Q - 1) + 32, "split");
+    const uint32_t lds_base = lds_byte_address(lds);
     {
-        const __bf16 *qrow = (const __bf16 *)p.q + b * p.qs[0] + hq * p.qs[1] + ld_qrow * p.qs[2];
-        const __bf16 *rrow = (const __bf16 *)p.r + b * p.rs[0] + hq * p.rs[1] + ld_qrow * p.rs[2];
+        const __bf16 *qhead = (const __bf16 *)p.q + b * p.qs[0] + hq * p.qs[1];
+        const __bf16 *rhead = (const __bf16 *)p.r + b * p.rs[0] + hq * p.rs[1];
+        const uint32_t dq = lds_base + (uint32_t)(QZONE + w * WAVE_TILE_CHUNKS) * 16u;
+        const uint32_t dr = lds_base + (uint32_t)(2 * STAGE_CHUNKS + w * WAVE_TILE_CHUNKS) * 16u;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            qf[ks] = *(const u32x4 *)(qrow + 8 * (2 * ks + h));
-            if constexpr (USE_R) rf[ks] = *(const u32x4 *)(rrow + 8 * (2 * ks + h));
+        for (int i = 0; i < NDMA_Q; ++i) {
+            const int c = 64 * i + lane;  // lanes >= 32 of the last load: unused
+            const int64_t grow = min(row0 + min(c / KROW, 31), T - 1);
+            const int pos = min(c % KROW, CPR - 1);
+            const __bf16 *sq = qhead + grow * p.qs[2] + pos * 8;
+            const __bf16 *sr = rhead + grow * p.rs[2] + pos * 8;
+            if (i == NDMA_Q - 1) {
+                tile_load16<32>(sq, dq + 1024u * i);
+                if constexpr (USE_R) tile_load16<32>(sr, dr + 1024u * i);
+            } else {
+                tile_load16<64>(sq, dq + 1024u * i);
+                if constexpr (USE_R) tile_load16<64>(sr, dr + 1024u * i);
+            }
         }
     }
+    u32x4 qf[KSTEPS], rf[KSTEPS];
 
     const __bf16 *kbase = (const __bf16 *)p.k + b * p.ks[0] + hk * p.ks[1];
     const __bf16 *vbase = (const __bf16 *)p.v + b * p.vs[0] + hk * p.vs[1];
@@ -289,7 +321,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         row = c / VROW;
         pos = min(c % VROW, CPR - 1);
     };
-    const uint32_t lds_base = lds_byte_address(lds);
     uint32_t koff[NDMA_K], voff[NDMA_V];  // byte offsets inside a tile whose 64 rows all exist
 #pragma unroll
     for (int i = 0; i < NDMA_K; ++i) {
@@ -344,16 +375,16 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             k_src(i, row, pos);
             const __bf16 *sk = kbase + (int64_t)min(kt * kBC + row, T - 1) * p.ks[2] + pos * 8;
             if (i == NDMA_K - 1)
-                tile_load16<true>(sk, dk + 1024u * i);
+                tile_load16<16>(sk, dk + 1024u * i);
             else
-                tile_load16<false>(sk, dk + 1024u * i);
+                tile_load16<64>(sk, dk + 1024u * i);
         }
 #pragma unroll
         for (int i = 0; i < NDMA_V; ++i) {
             int row, pos;
             v_src(i, row, pos);
             const __bf16 *sv = vbase + (int64_t)min(kt * kBC + row, T - 1) * p.vs[2] + pos * 8;
-            tile_load16<false>(sv, dv + 1024u * i);
+            tile_load16<64>(sv, dv + 1024u * i);
         }
     };
 
@@ -386,6 +417,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // instruction would share the matrix pipeline and stall it; measured).
     float m_ref = kNegInf;
     f32x16 o1[NDB], o2[NDB], dacc1, dacc2;
+    float vsum1[2] = {0.f, 0.f}, vsum2[2] = {0.f, 0.f};  // per-lane partial row sums (this lane's keys)
     const u32x4 ones_frag = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const float scale_log2 = p.scale * kLog2e;  // >= 0 (checked by the host)
 
@@ -518,15 +550,22 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // With MASKED, `lim` is this lane's largest allowed key offset inside the block (its 4*h
     // already subtracted): register r holds key offset 8*(r/4) + r%4.
     const int row_lim = CAUSAL ? min(my_row, T - 1) : T - 1;  // last key this lane's row may see
-    auto exp_stages = [&](auto masked_tag, f32x16 &s1, f32x16 &s2, int r0, int slot, int slot0,
-                          int n_slots, float neg_m, int lim) {
+    auto exp_stages = [&](auto masked_tag, auto sums_tag, f32x16 &s1, f32x16 &s2, int r0, int slot,
+                          int slot0, int n_slots, float neg_m, int lim) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        constexpr bool SUMS = decltype(sums_tag)::value;  // a fourth stage adds P1, P2 to the row sums
         if (PLX_PF_ABLATE & 1) return;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int r = r0 + u;
-            // stages in slots first, first+1, first+2; none before slot0, none in the last two
-            const int first = slot0 + u * (n_slots - 4 - slot0) / 8;
+            // stages in slots first, first+1, first+2 (, first+3); none before slot0, none in
+            // the last two
+            const int first = slot0 + u * (n_slots - (SUMS ? 5 : 4) - slot0) / 8;
+            if constexpr (SUMS)
+                if (slot == first + 3) {
+                    vsum1[u & 1] += s1[r];
+                    if constexpr (USE_R) vsum2[u & 1] += s2[r];
+                }
             if (slot == first) s1[r] = fmaf(s1[r], scale_log2, neg_m);
             if (slot == first + 1) {
                 const float p1 = fast_exp2(s1[r]);
@@ -548,10 +587,17 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         const int lim_cur = row_lim - key_base_cur - 4 * h;  // current block, next block
         const int lim_next = lim_cur - kKB;
         constexpr int SLOTS1 = 2 * KSTEPS;           // phase 1: one slot per score MFMA
-        constexpr int GROUP2 = 2 * NDB + 2;          // phase 2, per key group: PV + row sums
-        constexpr int SLOTS2 = 2 * GROUP2;
         constexpr bool DMA = decltype(dma_tag)::value;  // this step also fetches tile (dma_tk, dma_tv)
         constexpr bool MASKED = decltype(masked_tag)::value;
+        // Row sums of the CURRENT block belong to this step. Masked steps (a row may see only a
+        // few keys, so the sums must be those of the rounded operands exactly): two MFMAs against
+        // ones per key group. Unmasked steps: vector adds of the fp32 values, which stay in the
+        // score registers until the next step -- upper key group behind its exp stages in phase
+        // 1, lower key group (finished by the previous step) during phase 2.
+        constexpr bool SUMS = !MASKED && PLX_PF_VALU_SUMS;
+        constexpr int GROUP2 = 2 * NDB + (SUMS ? 0 : 2);  // phase 2, per key group: PV (+ row sums)
+        constexpr int SLOTS2 = 2 * GROUP2;
+        const std::integral_constant<bool, SUMS> sums_tag{};
         static_assert(NDMA_K <= KSTEPS && NDMA_V <= GROUP2, "one tile load per odd slot");
         const float neg_m = -m_ref;
         // ---- phase 1: scores of the next block | upper key group of the current block ------
@@ -572,7 +618,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             }
             if constexpr (DMA)
                 if (sl % 2 == 1 && sl / 2 < NDMA_K) k_load(sl / 2, dma_tk, dma_dk);
-            exp_stages(masked_tag, sc1, sc2, 8, sl, 0, SLOTS1, neg_m, lim_cur);
+            exp_stages(masked_tag, sums_tag, sc1, sc2, 8, sl, 0, SLOTS1, neg_m, lim_cur);
             if (sl == SLOTS1 - 2) pb1[1] = pack_group(sc1, 1);
             if (sl == SLOTS1 - 1) {
                 if constexpr (USE_R) pb2[1] = pack_group(sc2, 1);
@@ -602,7 +648,13 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             }
             if constexpr (DMA)
                 if (sl % 2 == 1 && sl / 2 < NDMA_V) v_load(sl / 2, dma_tv, dma_dv);
-            exp_stages(masked_tag, sn1, sn2, 0, sl, 1, SLOTS2, neg_m, lim_next);
+            exp_stages(masked_tag, std::false_type{}, sn1, sn2, 0, sl, 1, SLOTS2, neg_m, lim_next);
+            if constexpr (SUMS)
+                if (sl % (SLOTS2 / 8) == 0) {
+                    const int r = sl / (SLOTS2 / 8);  // lower key group of the current block
+                    vsum1[r & 1] += sc1[r];
+                    if constexpr (USE_R) vsum2[r & 1] += sc2[r];
+                }
             if (sl == SLOTS2 - 2) nb1 = pack_group(sn1, 0);
             if (sl == SLOTS2 - 1) {
                 if constexpr (USE_R) nb2 = pack_group(sn2, 0);
@@ -627,8 +679,19 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     }
     zero_state();
     PLX_STAMP(1);
-    tile_barrier();
+    static_assert(kDist == 2, "the wait below leaves exactly tile 1 in flight");
+    tile_barrier<kTileLoads>();  // Q, R and tile 0 have landed
     PLX_STAMP(2);
+    {
+        // B operands: column = query row, k-elements = the 8 dims of chunk 2*ks + h
+        const u32x4 *zq = lds + QZONE + w * WAVE_TILE_CHUNKS + col * KROW + h;
+        const u32x4 *zr = lds + 2 * STAGE_CHUNKS + w * WAVE_TILE_CHUNKS + col * KROW + h;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            qf[ks] = zq[2 * ks];
+            if constexpr (USE_R) rf[ks] = zr[2 * ks];
+        }
+    }
     if (PLX_PF_EXIT == 1) {
         if (qf[0][0] == 0x12345678u && rf[KSTEPS - 1][3] == 0x9abcdef0u) ((uint32_t *)p.o)[tid] = qf[1][1];
         return;
@@ -650,7 +713,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         m_ref = halves_max(tmax) * scale_log2;
 #pragma unroll
         for (int sl = 0; sl < 12; ++sl)
-            exp_stages(std::true_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - 4 * h);
+            exp_stages(std::true_type{}, std::false_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - 4 * h);
         pb1[0] = pack_group(sa1, 0);
         if constexpr (USE_R) pb2[0] = pack_group(sa2, 0);
     }
@@ -707,7 +770,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
 
     PLX_STAMP(5);
     // overflow check: any inf/NaN in the sums means the fixed reference was too small
-    float chk = dacc1[0] * 0.f + dacc2[0] * 0.f;
+    float chk = dacc1[0] * 0.f + dacc2[0] * 0.f + (vsum1[0] + vsum1[1]) * 0.f + (vsum2[0] + vsum2[1]) * 0.f;
 #pragma unroll
     for (int n = 0; n < NDB; ++n)
 #pragma unroll
@@ -726,6 +789,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // =========================== fallback: online max / rescale ============================
     if (overflow && !PLX_PF_ABLATE) {
         zero_state();
+        vsum1[0] = vsum1[1] = vsum2[0] = vsum2[1] = 0.f;
         m_ref = kNegInf;
         dma_tile(0, 0);
         stage = 0;
@@ -771,11 +835,15 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // instruction; the wave instead transposes its 32 x D tile through LDS (all tile loads have
     // landed, every wave is past its last read) and writes whole 256-byte rows, 16 bytes a lane.
     {
-        const float dsum1 = dacc1[0], dsum2 = dacc2[0];
+        // Every row of the MFMA row-sum accumulators holds the sum over this lane's query row;
+        // the vector partial sums cover this lane's keys only: add the other half-wave's.
+        const float dsum1 = dacc1[0] + halves_sum(vsum1[0] + vsum1[1]);
+        const float dsum2 = dacc2[0] + halves_sum(vsum2[0] + vsum2[1]);
         const float inv = dsum1 > 0.f ? 1.f / dsum1 : 0.f;  // empty key set: zeros
         const float gain = inv * (1.f + dsum2 * inv);
         constexpr int OROW = CPR + 1;  // padded row of the staging tile, in 16-byte chunks
-        u32x4 *otile = lds + w * (32 * OROW);
+        static_assert(OROW == KROW, "the staging tile is the wave's Q tile");
+        u32x4 *otile = lds + QZONE + w * WAVE_TILE_CHUNKS;
         unsigned short *otile16 = (unsigned short *)otile;
 #pragma unroll
         for (int n = 0; n < NDB; ++n)
