@@ -7,20 +7,26 @@
 //
 // Layout for CDNA4:
 //   * one workgroup = 4 waves = 128 query rows of one query head (32 rows per wave, one wave
-//     per SIMD, so a wave may use the whole 512-register budget: O1^T, O2^T live in the
-//     accumulation registers and the Q, R fragments in vector registers for the whole pass);
-//   * K/V tiles of 64 keys go straight from global memory into a three-stage LDS ring
-//     (global_load_lds_dwordx4: no staging registers, no LDS write instructions; 16 lanes cover
-//     one 256-byte row). Rows are padded, not swizzled, so that every operand address is a
-//     per-lane base plus a constant: one workgroup barrier per tile;
+//     per SIMD, so a wave may use the whole 512-register budget: O1^T, O2^T and the Q, R
+//     fragments live in the accumulation registers for the whole pass -- an MFMA can take its
+//     B operand from there -- and the vector registers hold scores, P and LDS fragments);
+//   * every global read is a direct global -> LDS load of whole rows (global_load_lds_dwordx4:
+//     no staging registers, no LDS write instructions): the wave's own Q and R rows once, then
+//     K/V tiles of 64 keys into a three-stage ring, fetched two tiles ahead, one load per MFMA
+//     slot of the pipeline. Rows are padded, not swizzled, so that every operand address is a
+//     per-lane base plus a constant; one workgroup barrier per tile;
 //   * scores are produced transposed with v_mfma_f32_32x32x16_bf16, S^T = K Q^T: each K
 //     fragment read from LDS feeds two MFMAs (the q branch and the r branch). In the S^T
 //     accumulator a lane owns ONE query row (column) and 16 of the 32 keys, so softmax
 //     statistics are per lane, S1 and S2 of a (row, key) pair share lane and register, and the
 //     accumulator registers are already the B operand of O^T += V^T P^T (V^T fragments come
 //     from transposing LDS reads);
-//   * key blocks of 32 are software-pipelined: the score MFMAs of block i+1 are issued before
-//     the softmax arithmetic of block i, so matrix cores and vector ALU overlap inside a wave.
+//   * key blocks of 32 are software-pipelined in slots of one MFMA plus its share of vector
+//     work: the score MFMAs of block i+1 run under the exp arithmetic of block i, the PV MFMAs
+//     of block i under the exp arithmetic of block i+1;
+//   * row sums d1, d2: per-lane fp32 adds in tiles every row sees completely; in diagonal /
+//     tail tiles MFMAs against a matrix of ones, i.e. sums of exactly the bf16 operands that
+//     enter O1 / O2, so that rows with very few keys come out exact (row 0 returns v_0).
 //
 // The running max m of Algorithm 1 only has to keep exp2 in range: ANY per-row reference gives
 // the same O after the final division. The fast pass therefore fixes m to the row maximum over
@@ -35,6 +41,13 @@
 #include "plx_kernels.h"
 
 namespace plx {
+
+// Timing-only ablation switches for kernel analysis (results are wrong when non-zero; every
+// access stays inside the same buffers): 4 = no barrier in the steady-state loop, 8 = no tile
+// loads there, 64 = tile loads without their LDS address updates.
+#ifndef PLX_PF_ABLATE
+#define PLX_PF_ABLATE 0
+#endif
 
 constexpr int kBR = 128;  // query rows per workgroup
 constexpr int kBC = 64;   // keys per LDS tile
@@ -102,6 +115,8 @@ __device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, cons
             "s_mov_b64 exec, %0"
             : "=&s"(saved_exec)
             : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
+    else if (PLX_PF_ABLATE & 64)  // timing only: every load lands at the same LDS address
+        asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(lane_byte_off), "s"(tile_base));
     else
         asm volatile(
             "s_mov_b32 m0, %2\n\t"
@@ -145,15 +160,6 @@ __device__ unsigned long long plx_pf_stamps[8192 * 12];
 #define PLX_STAMP(slot) ((void)0)
 #endif
 
-#ifndef PLX_PF_EXIT
-#define PLX_PF_EXIT 0  // timing only: leave the kernel early at stage 1, 2, 3 (no output)
-#endif
-
-// Timing-only ablation switches for kernel analysis (results are wrong when non-zero):
-// 1 = no exp / pack arithmetic, 2 = no fragment LDS reads, 4 = no tile loads / barrier.
-#ifndef PLX_PF_ABLATE
-#define PLX_PF_ABLATE 0
-#endif
 
 // An MFMA may not read a register that a vector-ALU instruction wrote less than two wait states
 // before it (the hardware does not interlock this). For MFMAs the compiler knows about it keeps
@@ -195,10 +201,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int KSTEPS = D / 16;        // k-steps of the score contraction
     constexpr int NDB = D / 32;           // 32-wide blocks of output dimensions
-#ifndef PLX_PF_STAGES
-#define PLX_PF_STAGES 3
-#endif
-    constexpr int STAGES = PLX_PF_STAGES;  // LDS ring; tiles are fetched STAGES - 1 ahead
+    constexpr int STAGES = 3;  // LDS ring; tiles are fetched STAGES - 1 ahead
     constexpr int kDist = STAGES - 1;
     // K rows are padded by one 16-byte chunk (16 consecutive rows, same chunk -> 16 different
     // bank groups), V rows by four chunks (the 4 consecutive rows of a transposing read land in
@@ -511,10 +514,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     constexpr int kLookAhead = PLX_PF_LOOKAHEAD;
     static_assert(2 * NDB == KSTEPS, "as many V^T fragments as K fragments per key block");
     u32x4 kf[KSTEPS], vt[KSTEPS];
-    if (PLX_PF_ABLATE & 2) {
-#pragma unroll
-        for (int i = 0; i < KSTEPS; ++i) kf[i] = vt[i] = u32x4{0x3f803f80u + i, 1u, 2u, 3u};
-    }
     auto k_block_ptr = [&](int stage, int kb) {
         return (const u32x4 *)(lds + stage * STAGE_CHUNKS + col * KROW + h + kb * kKB * KROW);
     };
@@ -523,10 +522,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                kb * kKB * VROW * 8;
     };
     auto load_kfrag = [&](const u32x4 *tk_block, int ks) {
-        if (!(PLX_PF_ABLATE & 2)) kf[ks] = tk_block[2 * ks];
+        kf[ks] = tk_block[2 * ks];
     };
     auto load_vfrag = [&](const unsigned short *tv_block, int f) {
-        if (PLX_PF_ABLATE & 2) return;
         const int j = f / NDB, n = f % NDB;  // key group of 16, dim block of 32
         const int off = (16 * j * VROW + 4 * n) * 8;
         const u32x2 lo = lds_read_tr16(tv_block + off);
@@ -554,7 +552,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                           int slot0, int n_slots, float neg_m, int lim) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr bool SUMS = decltype(sums_tag)::value;  // a fourth stage adds P1, P2 to the row sums
-        if (PLX_PF_ABLATE & 1) return;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int r = r0 + u;
@@ -577,7 +574,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         }
     };
     auto pack_group = [&](const f32x16 &s, int j) {
-        if (PLX_PF_ABLATE & (1 | 32)) return ones_frag;
         return u32x4{pack_bf16(s[8 * j + 0], s[8 * j + 1]), pack_bf16(s[8 * j + 2], s[8 * j + 3]),
                      pack_bf16(s[8 * j + 4], s[8 * j + 5]), pack_bf16(s[8 * j + 6], s[8 * j + 7])};
     };
@@ -692,10 +688,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             if constexpr (USE_R) rf[ks] = zr[2 * ks];
         }
     }
-    if (PLX_PF_EXIT == 1) {
-        if (qf[0][0] == 0x12345678u && rf[KSTEPS - 1][3] == 0x9abcdef0u) ((uint32_t *)p.o)[tid] = qf[1][1];
-        return;
-    }
     int stage = 0;
     f32x16 sa1, sa2, sb1, sb2;
     {
@@ -716,11 +708,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             exp_stages(std::true_type{}, std::false_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - 4 * h);
         pb1[0] = pack_group(sa1, 0);
         if constexpr (USE_R) pb2[0] = pack_group(sa2, 0);
-    }
-    if (PLX_PF_EXIT == 2) {
-        if (pb1[0][0] == 0x12345678u && pb2[0][1] == 0x9abcdef0u) ((uint32_t *)p.o)[tid] = kf[0][0];
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        return;
     }
     PLX_STAMP(3);
     auto tile_steps = [&](auto masked_tag, auto dma_tag, int kt, int stage, int next_stage) {
@@ -781,10 +768,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // tile loads past the end have landed
     const bool overflow = __syncthreads_or(chk != 0.f);  // NaN != 0 is true; all waves agree
     PLX_STAMP(6);
-    if (PLX_PF_EXIT == 3) {
-        if (overflow) ((uint32_t *)p.o)[tid] = 1u;
-        return;
-    }
 
     // =========================== fallback: online max / rescale ============================
     if (overflow && !PLX_PF_ABLATE) {
