@@ -255,6 +255,23 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
     us = _time_events(torch, twin, 20, 200)
     extra["config2_softmax_only_us"] = round(us, 2)
 
+    # config 2 again as a HIP graph: the 8 rotated steps captured once, replayed (removes the
+    # host's launch cost from the step time; every replay is the same 16 kernels)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g_args = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], out, x["scale"], None, True, 0, ws)
+              for x in x0]
+    with torch.cuda.graph(graph, stream=side):
+        cap = int(torch.cuda.current_stream().cuda_stream)
+        for a in g_args:
+            st = lib.parallax_decode(ctypes.byref(a), cap)
+            if st != 0:
+                raise plx.ParallaxError(st, "graph capture")
+    torch.cuda.current_stream().wait_stream(side)
+    us = _time_events(torch, graph.replay, 5, 50) / len(g_args)
+    extra["config2_hip_graph_replay_us_per_step"] = round(us, 2)
+
     sweep = []
     for (B, L) in [(1, 1024), (1, 65536), (16, 4096), (16, 16384), (64, 16384), (128, 16384)]:
         Hq, Hkv, d = 16, 8, 128
@@ -302,6 +319,25 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
     pre["frac_of_bf16_mfma_peak"] = round(pre["parallax_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
     pre["workload"] = "config4: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128, K offset N(0,0.5^2)"
     extra["prefill"] = pre
+    del y, po
+
+    # other prefill shapes: config 5a (long causal), full attention, and the compute-matched
+    # d = 64 layout (twice the heads, half the head dimension)
+    more = []
+    for (name, B, T, Hq, Hkv, d, causal, r_scale) in [
+            ("config5a: causal B=2 T=16384 d=128, R x0.1", 2, 16384, 16, 8, 128, True, 0.1),
+            ("full attention B=4 T=4096 d=128", 4, 4096, 16, 8, 128, False, 1.0),
+            ("causal B=4 T=4096 d=64, 32 query / 16 KV heads", 4, 4096, 32, 16, 64, True, 1.0)]:
+        y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1005, device=dev, r_scale=r_scale)
+        po = torch.empty_like(y["q"])
+        us = _time_events(
+            torch, lambda: plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"],
+                                                causal=causal, out=po), 2, 10)
+        flops = B * Hq * 8 * d * (T * (T + 1) / 2 if causal else T * T)
+        more.append({"workload": name, "us": round(us, 1), "TFLOPs": round(flops / us / 1e6, 1),
+                     "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
+        del y, po
+    extra["prefill_more"] = more
     return extra
 
 

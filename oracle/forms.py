@@ -24,8 +24,11 @@ import numpy as np
 LOG2E = 1.4426950408889634
 
 
-def _allowed(i, Lk, causal, len_b):
-    return i + 1 if causal else min(len_b, Lk)
+def _allowed(i, Lk, causal, len_b, Tq=None):
+    """Number of allowed keys of query row i; causal rows are the last Tq positions of Lk."""
+    if causal:
+        return i + 1 + (Lk - (Lk if Tq is None else Tq))
+    return min(len_b, Lk)
 
 
 def covariance_form(q, r, k, v, scale, causal=False, seq_lens=None):
@@ -39,7 +42,7 @@ def covariance_form(q, r, k, v, scale, causal=False, seq_lens=None):
         for h in range(Hq):
             kb, vb = k[b, h // G], v[b, h // G]
             for i in range(Tq):
-                n = _allowed(i, Lk, causal, Lk if seq_lens is None else int(seq_lens[b]))
+                n = _allowed(i, Lk, causal, Lk if seq_lens is None else int(seq_lens[b]), Tq)
                 if n <= 0:
                     continue
                 kk, vv = kb[:n], vb[:n]
@@ -129,7 +132,7 @@ def streaming_form(q, r, k, v, scale, causal=False, seq_lens=None, tile=16, row_
             kb, vb = k[b, h // G], v[b, h // G]
             for r0 in range(0, Tq, row_block):
                 r1 = min(r0 + row_block, Tq)
-                limit = [(_allowed(i, Lk, causal, len_b)) for i in range(r0, r1)]
+                limit = [(_allowed(i, Lk, causal, len_b, Tq)) for i in range(r0, r1)]
                 parts = [
                     streaming_partial(q[b, h, r0:r1], r[b, h, r0:r1], kb, vb, scale, tile,
                                       cuts[s], cuts[s + 1], row_limit=limit)

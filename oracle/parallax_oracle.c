@@ -14,8 +14,11 @@
  * t_ij = rho^T (k_j - q_i) in the paper differs from u_j by the j-independent
  * rho^T q_i, which cancels in (tbar - t_ij) = (ubar - u_j).
  *
- * Allowed key set J(i): causal => j <= i (diagonal included, Sec. 2.1 D_i);
- * otherwise j < len_b, with len_b = seq_lens[b] or Lk when seq_lens is NULL.
+ * Allowed key set J(i): causal => keys at positions <= the query's position (diagonal
+ * included, Sec. 2.1 D_i). With Tq query rows over Lk >= Tq keys the queries are the LAST Tq
+ * positions of the sequence (chunked prefill), so row i sits at position i + (Lk - Tq) and
+ * sees j <= i + (Lk - Tq); Tq == Lk is the paper's square case j <= i.
+ * Otherwise j < len_b, with len_b = seq_lens[b] or Lk when seq_lens is NULL.
  * GQA: query head h reads KV head h / (Hq/Hkv); R is shaped and grouped like Q (App. E).
  *
  * No tiling, no online softmax, no fusion: three plain passes per row. Only tests,
@@ -75,7 +78,7 @@ static void plx_row(const double *q, const double *rho, const double *kmat, cons
 /*
  * Full evaluation on double inputs.
  *   q, r : [B][Hq][Tq][d]      k, v : [B][Hkv][Lk][d]      o : [B][Hq][Tq][d]
- *   causal != 0 requires Tq == Lk; seq_lens ([B], may be NULL) is ignored when causal.
+ *   causal != 0 requires Tq <= Lk; seq_lens ([B], may be NULL) is ignored when causal.
  *   rows: optional list of n_rows triples (b, h, i); when NULL every row is computed.
  *   For a row list, o is [n_rows][d].
  * Returns 0, or -1 on a bad argument.
@@ -87,7 +90,7 @@ int plx_oracle_f64(const double *q, const double *r, const double *k, const doub
     if (!q || !r || !k || !v || !o) return -1;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Tq <= 0 || Lk <= 0 || d <= 0) return -1;
     if (Hq % Hkv != 0) return -1;
-    if (causal && Tq != Lk) return -1;
+    if (causal && Tq > Lk) return -1;
     const int G = Hq / Hkv;
     const int64_t total = rows ? n_rows : (int64_t)B * Hq * Tq;
 
@@ -110,7 +113,7 @@ int plx_oracle_f64(const double *q, const double *r, const double *k, const doub
             const int hk = h / G;
             int64_t n_keys;
             if (causal)
-                n_keys = (int64_t)i + 1;
+                n_keys = (int64_t)i + 1 + (Lk - Tq);
             else
                 n_keys = seq_lens ? seq_lens[b] : Lk;
             if (n_keys > Lk) n_keys = Lk;
@@ -140,7 +143,7 @@ int plx_oracle_f32in(const float *q, const float *r, const float *k, const float
     if (!q || !r || !k || !v || !o) return -1;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Tq <= 0 || Lk <= 0 || d <= 0) return -1;
     if (Hq % Hkv != 0) return -1;
-    if (causal && Tq != Lk) return -1;
+    if (causal && Tq > Lk) return -1;
     const int G = Hq / Hkv;
     const int64_t slab = (int64_t)Lk * d;
     double *kd = (double *)malloc(sizeof(double) * (size_t)slab);
@@ -190,7 +193,7 @@ int plx_oracle_f32in(const float *q, const float *r, const float *k, const float
                     if (bb != b || h / G != hk) continue;
                     int64_t n_keys;
                     if (causal)
-                        n_keys = (int64_t)i + 1;
+                        n_keys = (int64_t)i + 1 + (Lk - Tq);
                     else
                         n_keys = seq_lens ? seq_lens[b] : Lk;
                     if (n_keys > Lk) n_keys = Lk;

@@ -61,7 +61,8 @@ def forward(q, r, k, v, scale, causal=False, seq_lens=None, rows=None, _lib_over
 
     q, r : [B, Hq, Tq, d]; k, v : [B, Hkv, Lk, d]; all float64 or all float32 numpy arrays
     (float32 holds bf16/fp32 inputs exactly; it is widened to double before any arithmetic).
-    causal : key j allowed iff j <= i (needs Tq == Lk); else j < seq_lens[b] (default Lk).
+    causal : key j allowed iff j <= i + (Lk - Tq) (queries are the last Tq positions; needs
+             Tq <= Lk; the square case is j <= i); else j < seq_lens[b] (default Lk).
     rows : optional int array [n, 3] of (b, h, i); then the result is [n, d].
     Returns float64.
     """

@@ -132,6 +132,42 @@ def test_deterministic_run_to_run(plx, synth):
     np.testing.assert_array_equal(a, b)
 
 
+def test_hip_graph_replays_match_eager(plx, synth, oracle):
+    """Decode and prefill captured in one HIP graph: every replay, with eager work and
+    synchronisation in between and inputs changed in place, equals the eager result."""
+    x = synth.decode_inputs(4, 16, 8, 2500, 128, seed=92, device=DEV, ragged=True)
+    y = synth.prefill_inputs(1, 4, 2, 300, 128, seed=93, device=DEV)
+    B, Hq, d = x["q"].shape
+    ws = torch.empty(plx.parallax_decode_workspace_bytes(B, Hq, 8, 2500, d) // 4,
+                     dtype=torch.float32, device=DEV)
+    out_d, out_p = torch.empty_like(x["q"]), torch.empty_like(y["q"])
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        cap = torch.cuda.current_stream()
+        plx.parallax_decode(x["q"], x["r"], x["k"], x["v"], x["scale"], seq_lens=x["seq_lens"],
+                            workspace=ws, out=out_d, stream=cap)
+        plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True, out=out_p,
+                             stream=cap)
+    torch.cuda.current_stream().wait_stream(side)
+    gen = torch.Generator(device=DEV).manual_seed(94)
+    for rep in range(4):
+        if rep:  # new inputs in the captured buffers
+            x["q"].copy_(torch.randn(x["q"].shape, generator=gen, device=DEV))
+            y["r"].copy_(torch.randn(y["r"].shape, generator=gen, device=DEV))
+        out_d.zero_()
+        out_p.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_d, got_p = host(out_d), host(out_p)
+        eager_d = _run(plx, x, workspace=ws)
+        eager_p = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(got_d, eager_d)
+        np.testing.assert_array_equal(got_p, host(eager_p))
+    assert rel_l2(got_d, oracle_decode(oracle, x)) <= BF16_REL_L2
+
+
 def test_workspace_partials_match_streaming_form(plx, synth):
     """The split workspace holds, per split, the unnormalised state of Algorithm 1 over that
     split's key range. Compare what is unique: log-sum-exp m + log2 d1, d2/d1, O1/d1, O2/d1."""

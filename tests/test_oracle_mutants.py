@@ -15,7 +15,10 @@ MUTANTS = {
     "probe_scaled_like_q": ("u[j] = s2;", "u[j] = scale * s2;"),
     "probe_uses_q": ("s2 += rho[c] * kj[c];", "s2 += q[c] * kj[c];"),
     "ubar_unweighted": ("ubar += a[j] * u[j];", "ubar += u[j] / (double)n_keys;"),
-    "causal_excludes_diagonal": ("n_keys = (int64_t)i + 1;", "n_keys = (int64_t)i;"),
+    "causal_excludes_diagonal": ("n_keys = (int64_t)i + 1 + (Lk - Tq);",
+                                 "n_keys = (int64_t)i + (Lk - Tq);"),
+    "causal_chunk_top_left_aligned": ("n_keys = (int64_t)i + 1 + (Lk - Tq);",
+                                      "n_keys = (int64_t)i + 1;"),
     "gqa_modulo": ("const int hk = h / G;", "const int hk = h % Hkv;"),
     "no_max_subtraction_no_norm": ("a[j] /= omega;", "a[j] /= 1.0;"),
 }
@@ -52,6 +55,10 @@ def _pins(fwd):
         failed.append("row0")
     if np.abs(fwd(q, r, k, np.ones_like(v), 0.5, causal=True) - 1.0).max() > 1e-10:
         failed.append("constant_values")
+    # causal chunk of one query row over T keys = that row with every key allowed
+    one = fwd(q[:, :, -1:], r[:, :, -1:], k, v, 0.5, causal=True)
+    if np.abs(one - fwd(q[:, :, -1:], r[:, :, -1:], k, v, 0.5)).max() > 1e-12:
+        failed.append("chunk_alignment")
     return failed
 
 

@@ -48,7 +48,7 @@ def _brute(q, r, k, v, scale, causal, seq_lens=None):
             A = scale * q[b, h] @ K.T
             mask = np.ones((Tq, Lk), dtype=bool)
             if causal:
-                mask = np.tril(mask)
+                mask = np.tril(mask, k=Lk - Tq)  # row i is position i + Lk - Tq
             elif seq_lens is not None:
                 mask[:, seq_lens[b]:] = False
             A = np.where(mask, A, -np.inf)
@@ -71,6 +71,40 @@ def test_brute_force_weight_matrix(oracle, causal):
     # the Parallax weights of a row sum to one and may be negative (Sec. 4.4)
     np.testing.assert_allclose(W.sum(axis=-1), 1.0, atol=1e-12)
     assert (W < 0).any()
+
+
+def test_chunked_causal_is_the_tail_of_the_square_case(oracle):
+    """Tq query rows over Lk > Tq keys with the causal flag: the queries are the last Tq
+    positions, so the result is the last Tq rows of the square causal problem (pinned above),
+    a one-row chunk is plain decode over all keys, and a top-left aligned mask is wrong."""
+    from oracle import forms
+
+    B, Hq, Hkv, L, d, Tq = 2, 4, 2, 13, 5, 4
+    q, r = _rand((B, Hq, L, d), 31), _rand((B, Hq, L, d), 32)
+    k, v = _rand((B, Hkv, L, d), 33), _rand((B, Hkv, L, d), 34)
+    square = oracle.forward(q, r, k, v, 0.41, causal=True)
+    qc, rc = q[:, :, L - Tq:], r[:, :, L - Tq:]
+    chunk = oracle.forward(qc, rc, k, v, 0.41, causal=True)
+    np.testing.assert_allclose(chunk, square[:, :, L - Tq:], rtol=1e-14, atol=1e-14)
+    ref, W = _brute(qc, rc, k, v, 0.41, True)
+    np.testing.assert_allclose(chunk, ref, rtol=1e-12, atol=1e-12)
+    assert (W[:, :, 0, L - Tq + 1:] == 0).all() and (W[:, :, 0, :L - Tq + 1] != 0).all()
+    # top-left alignment (row i sees keys <= i) is a different, wrong, result
+    topleft = np.stack([oracle.forward(qc[:, :, i:i + 1], rc[:, :, i:i + 1], k[:, :, :i + 1],
+                                       v[:, :, :i + 1], 0.41)[:, :, 0] for i in range(Tq)], axis=2)
+    assert np.abs(topleft - chunk).max() > 1e-3
+    # one query row: decode over all L keys
+    one = oracle.forward(q[:, :, L - 1:], r[:, :, L - 1:], k, v, 0.41, causal=True)
+    np.testing.assert_allclose(one, oracle.forward(q[:, :, L - 1:], r[:, :, L - 1:], k, v, 0.41),
+                               rtol=1e-14, atol=1e-14)
+    # the covariance and streaming forms take the same alignment
+    np.testing.assert_allclose(forms.covariance_form(qc, rc, k, v, 0.41, causal=True), chunk,
+                               rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(forms.streaming_form(qc, rc, k, v, 0.41, causal=True, tile=4,
+                                                    row_block=3, split_points=[5, 9]), chunk,
+                               rtol=1e-10, atol=1e-10)
+    with pytest.raises(ValueError):
+        oracle.forward(q, r, k[:, :, :L - 1], v[:, :, :L - 1], 0.41, causal=True)  # Tq > Lk
 
 
 def test_brute_force_ragged_decode_and_gqa(oracle):
