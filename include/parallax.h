@@ -116,11 +116,14 @@ plx_status parallax_decode_partials(const plx_decode_args *args, void *hip_strea
 plx_status parallax_decode_combine(const plx_decode_args *args, void *hip_stream);
 
 /*
- * Prefill forward over T query rows and T keys per sequence (Algorithm 1, Sec. 3.3; forward
- * equation Sec. 3.1). causal != 0: key j allowed iff j <= i (diagonal included, so row 0
- * returns v_0); causal == 0: every key.
+ * Prefill forward over T query rows and Tkv keys per sequence (Algorithm 1, Sec. 3.3; forward
+ * equation Sec. 3.1). Tkv = 0 means Tkv = T (the paper's square case).
+ * causal != 0: the query rows are the LAST T positions of the Tkv-long sequence (a prefill
+ * chunk behind an existing cache, or a few speculative rows): key j allowed iff
+ * j <= i + (Tkv - T), diagonal included -- for Tkv = T that is j <= i and row 0 returns v_0.
+ * Needs Tkv >= T. causal == 0: every key.
  *
- *   q, r, o   [B, Hq, T, d]    k, v  [B, Hkv, T, d]
+ *   q, r, o   [B, Hq, T, d]    k, v  [B, Hkv, Tkv, d]
  *   *_stride  element strides {batch, head, row}; last dim contiguous
  */
 typedef struct {
@@ -133,6 +136,7 @@ typedef struct {
     int32_t causal;
     int32_t use_r;
     plx_dtype dtype;
+    int32_t Tkv; /* keys per sequence; 0 = T */
 } plx_prefill_args;
 
 plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);

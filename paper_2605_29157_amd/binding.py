@@ -59,6 +59,7 @@ class plx_prefill_args(ctypes.Structure):
         ("causal", ctypes.c_int32),
         ("use_r", ctypes.c_int32),
         ("dtype", ctypes.c_int),
+        ("Tkv", ctypes.c_int32),
     ]
 
 
@@ -213,9 +214,9 @@ def parallax_decode_combine(workspace, out, Hkv, num_splits, stream=None):
 
 
 def prefill_args(q, r, k, v, out, scale, causal=True, use_r=True):
-    """Fill a plx_prefill_args from tensors: q, r, out [B, Hq, T, d]; k, v [B, Hkv, T, d]."""
+    """Fill a plx_prefill_args from tensors: q, r, out [B, Hq, T, d]; k, v [B, Hkv, Tkv, d]."""
     B, Hq, T, d = q.shape
-    Hkv = k.shape[1]
+    Hkv, Tkv = k.shape[1], k.shape[2]
     a = plx_prefill_args()
     a.q, a.k, a.v, a.o = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
     a.r = r.data_ptr() if r is not None else None
@@ -227,18 +228,20 @@ def prefill_args(q, r, k, v, out, scale, causal=True, use_r=True):
     a.causal = 1 if causal else 0
     a.use_r = 1 if use_r else 0
     a.dtype = _dtype_code(q)
+    a.Tkv = Tkv
     return a
 
 
 def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None):
-    """Parallax prefill forward over T query rows and T keys."""
+    """Parallax prefill forward over T query rows and Tkv keys (causal: the rows are the last
+    T positions of the Tkv-long sequence)."""
     for t in (q, k, v) + ((r,) if r is not None else ()):
         if not t.is_cuda:
             raise ValueError("parallax_prefill needs device tensors")
         if t.stride(-1) != 1:
             raise ValueError("the last dimension must be contiguous")
-    if k.shape[2] != q.shape[2]:
-        raise ValueError("prefill takes T query rows and T keys")
+    if v.shape[2] != k.shape[2]:
+        raise ValueError("k and v must hold the same number of keys")
     if out is None:
         out = torch.empty_like(q)
     a = prefill_args(q, r, k, v, out, scale, causal, use_r)

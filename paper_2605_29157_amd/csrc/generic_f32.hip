@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams 
     const int hk = h / p.G, d = p.d;
     int n_keys;
     if (p.causal)
-        n_keys = i + 1;
+        n_keys = i + 1 + (p.Lk - p.Tq);  // the query rows are the last Tq positions
     else
         n_keys = p.seq_lens ? min(max(p.seq_lens[b], 0), p.Lk) : p.Lk;
 
@@ -142,7 +142,7 @@ hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream) {
     g.v = (const float *)p.v;
     g.o = (float *)p.o;
     g.seq_lens = nullptr;
-    g.B = p.B, g.Hq = p.Hq, g.Hkv = p.Hkv, g.G = p.G, g.Tq = p.T, g.Lk = p.T, g.d = p.d;
+    g.B = p.B, g.Hq = p.Hq, g.Hkv = p.Hkv, g.G = p.G, g.Tq = p.T, g.Lk = p.Tk, g.d = p.d;
     for (int a = 0; a < 3; ++a) {
         g.qs[a] = p.qs[a], g.rs[a] = p.rs[a], g.ks[a] = p.ks[a], g.vs[a] = p.vs[a];
         g.os[a] = p.os[a];

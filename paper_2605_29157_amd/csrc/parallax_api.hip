@@ -187,6 +187,9 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
     if (a->use_r && !a->r) return PLX_ERR_NULL;
     plx_status st = check_common(a->dtype, a->B, a->Hq, a->Hkv, a->T, a->d);
     if (st != PLX_OK) return st;
+    if (a->Tkv < 0) return PLX_ERR_SHAPE;
+    const int32_t Tk = a->Tkv ? a->Tkv : a->T;
+    if (a->causal && Tk < a->T) return PLX_ERR_SHAPE;
     if (!(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
     if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || !aligned16(a->o) ||
         (a->r && !aligned16(a->r)))
@@ -206,7 +209,7 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
 
     plx::PrefillParams p{};
     p.q = a->q, p.r = a->use_r ? a->r : a->q, p.k = a->k, p.v = a->v, p.o = a->o;
-    p.B = a->B, p.Hq = a->Hq, p.Hkv = a->Hkv, p.G = a->Hq / a->Hkv, p.T = a->T, p.d = a->d;
+    p.B = a->B, p.Hq = a->Hq, p.Hkv = a->Hkv, p.G = a->Hq / a->Hkv, p.T = a->T, p.Tk = Tk, p.d = a->d;
     for (int j = 0; j < 3; ++j) {
         p.qs[j] = a->q_stride[j];
         p.rs[j] = a->use_r ? a->r_stride[j] : a->q_stride[j];

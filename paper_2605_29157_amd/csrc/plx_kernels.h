@@ -23,7 +23,7 @@ struct DecodeParams {
 struct PrefillParams {
     const void *q, *r, *k, *v;
     void *o;
-    int32_t B, Hq, Hkv, G, T, d;
+    int32_t B, Hq, Hkv, G, T, Tk, d;  // T query rows, Tk keys
     int64_t qs[3], rs[3], ks[3], vs[3], os[3];  // element strides {batch, head, row}
     float scale;
     int32_t causal, use_r;

@@ -3,7 +3,8 @@
 // What it computes: Algorithm 1 of the paper (Sec. 3.3) -- for a block of query rows, one pass
 // over key tiles with the running state (m, d1, d2, O1, O2); S1 = Q K^T * scale (masked),
 // S2 = R K^T (unscaled), P1 = exp2(S1 - m), P2 = P1 * S2, O1 += P1 V, O2 += P2 V; closing
-// formula O1/d1 * (1 + d2/d1) - O2/d1. Causal: key j allowed iff j <= i (Sec. 3.1).
+// formula O1/d1 * (1 + d2/d1) - O2/d1. Causal: key j allowed iff j <= i (Sec. 3.1); with more
+// keys than query rows the rows are the last positions of the sequence, j <= i + (Tk - T).
 //
 // Layout for CDNA4:
 //   * one workgroup = 4 waves = 128 query rows of one query head (32 rows per wave, one wave
@@ -239,7 +240,8 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const int h = lane >> 5;    // half-wave
 
     // ---- work item: heavy row blocks first; blocks of one (batch, kv head) share an XCD ----
-    const int T = p.T, G = p.G;
+    const int T = p.T, Tk = p.Tk, G = p.G;  // query rows, keys
+    const int off = Tk - T;                 // causal: row i sits at key position i + off
     const int nrb = (T + kBR - 1) / kBR;
     const int pairs = p.B * p.Hkv;
     int rbi, pair, hg;
@@ -305,11 +307,11 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const __bf16 *kbase = (const __bf16 *)p.k + b * p.ks[0] + hk * p.ks[1];
     const __bf16 *vbase = (const __bf16 *)p.v + b * p.vs[0] + hk * p.vs[1];
 
-    const int key_end = CAUSAL ? min(T, (rb + 1) * kBR) : T;  // keys this workgroup may need
+    const int key_end = CAUSAL ? min(Tk, (rb + 1) * kBR + off) : Tk;  // keys this workgroup may need
     const int n_tiles = (key_end + kBC - 1) / kBC;
-    // leading tiles whose keys are all < T and visible to every row of the workgroup, less two
+    // leading tiles whose keys all exist and are visible to every row of the workgroup, less two
     // so that the tile prefetched two ahead inside that loop is always a complete one
-    const int n_full = max(0, min(CAUSAL ? 2 * rb : T / kBC, T / kBC - kDist));
+    const int n_full = max(0, min(CAUSAL ? (rb * kBR + off + 1) / kBC : Tk / kBC, Tk / kBC - kDist));
 
     // ---- global -> LDS tile loads (no staging registers, no LDS write instructions) --------
     // Load instruction i of wave w fills LDS chunks [64*(w + 4i), +64) of a tile; lane l owns
@@ -369,14 +371,14 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // while they issue); these name the tile being fetched.
     const char *dma_tk = nullptr, *dma_tv = nullptr;
     uint32_t dma_dk = 0, dma_dv = 0;
-    // any tile: rows past T re-read row T-1 (finite data, masked where it matters)
+    // any tile: rows past the last key re-read that key's row (finite data, masked where it matters)
     auto dma_tile = [&](int kt, int stage) {
         const uint32_t dk = stage_k_addr(stage), dv = stage_v_addr(stage);
 #pragma unroll
         for (int i = 0; i < NDMA_K; ++i) {
             int row, pos;
             k_src(i, row, pos);
-            const __bf16 *sk = kbase + (int64_t)min(kt * kBC + row, T - 1) * p.ks[2] + pos * 8;
+            const __bf16 *sk = kbase + (int64_t)min(kt * kBC + row, Tk - 1) * p.ks[2] + pos * 8;
             if (i == NDMA_K - 1)
                 tile_load16<16>(sk, dk + 1024u * i);
             else
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         for (int i = 0; i < NDMA_V; ++i) {
             int row, pos;
             v_src(i, row, pos);
-            const __bf16 *sv = vbase + (int64_t)min(kt * kBC + row, T - 1) * p.vs[2] + pos * 8;
+            const __bf16 *sv = vbase + (int64_t)min(kt * kBC + row, Tk - 1) * p.vs[2] + pos * 8;
             tile_load16<64>(sv, dv + 1024u * i);
         }
     };
@@ -410,7 +412,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // accumulator register r of an S^T block <-> key key_base + 8*(r/4) + 4*h + r%4
     auto key_ok = [&](int key_base, int r) {
         const int key = key_base + 8 * (r >> 2) + 4 * h + (r & 3);
-        return key < T && (!CAUSAL || key <= my_row);
+        return key < Tk && (!CAUSAL || key <= my_row + off);
     };
 
     // d1 / d2 are accumulated by MFMAs as well: Ones(32 x 16 keys) x P^T gives a block whose
@@ -435,7 +437,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             float p1 = fast_exp2(fmaf(s1[r], scale_log2, neg_m));
             if constexpr (MASKED) p1 = key_ok(key_base, r) ? p1 : 0.f;
             s1[r] = p1;
-            // s2 is finite (rows past T re-read row T-1) and P1 = 0 where masked
+            // s2 is finite (rows past the last key re-read it) and P1 = 0 where masked
             if constexpr (USE_R) s2[r] = p1 * s2[r];
         }
 #pragma unroll
@@ -492,10 +494,10 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
 
     // does this wave see any key of the block starting at key_base / is every key visible?
     auto block_visible = [&](int key_base) {
-        return key_base < T && (!CAUSAL || key_base <= row0 + 31);
+        return key_base < Tk && (!CAUSAL || key_base <= row0 + 31 + off);
     };
     auto block_full = [&](int key_base) {
-        return key_base + kKB <= T && (!CAUSAL || key_base + kKB - 1 <= row0);
+        return key_base + kKB <= Tk && (!CAUSAL || key_base + kKB - 1 <= row0 + off);
     };
 
     u32x4 pb1[2], pb2[2];
@@ -547,7 +549,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // waits on the latency of its own previous vector instruction.
     // With MASKED, `lim` is this lane's largest allowed key offset inside the block (its 4*h
     // already subtracted): register r holds key offset 8*(r/4) + r%4.
-    const int row_lim = CAUSAL ? min(my_row, T - 1) : T - 1;  // last key this lane's row may see
+    const int row_lim = CAUSAL ? min(my_row + off, Tk - 1) : Tk - 1;  // last key this lane's row may see
     auto exp_stages = [&](auto masked_tag, auto sums_tag, f32x16 &s1, f32x16 &s2, int r0, int slot,
                           int slot0, int n_slots, float neg_m, int lim) {
         constexpr bool MASKED = decltype(masked_tag)::value;
@@ -568,7 +570,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                 const float p1 = fast_exp2(s1[r]);
                 s1[r] = (!MASKED || 8 * (r >> 2) + (r & 3) <= lim) ? p1 : 0.f;
             }
-            // P2: S2 is finite (rows past T re-read row T-1) and P1 = 0 where masked
+            // P2: S2 is finite (rows past the last key re-read it) and P1 = 0 where masked
             if constexpr (USE_R)
                 if (slot == first + 2) s2[r] = s1[r] * s2[r];
         }
@@ -666,7 +668,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // stages kt % 3 and (kt+1) % 3 and visible to all waves. The barrier (every wave first waits
     // for its own tile loads) also proves that nobody reads tile kt-1 any more, whose stage then
     // receives tile kt+2: each tile load has a whole iteration to land.
-    if (T >= kDist * kBC) {  // workgroup-uniform
+    if (Tk >= kDist * kBC) {  // workgroup-uniform
 #pragma unroll
         for (int t = 0; t < kDist; ++t) dma_full_tile(t, t);
     } else {
@@ -746,7 +748,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
         tile_barrier();
         if (kt + kDist < n_tiles) {              // workgroup-uniform
-            if ((kt + kDist + 1) * kBC <= T)     // the tile exists completely
+            if ((kt + kDist + 1) * kBC <= Tk)    // the tile exists completely
                 dma_full_tile(kt + kDist, free_stage);
             else
                 dma_tile(kt + kDist, free_stage);

@@ -39,7 +39,8 @@ def test_header_symbols_are_exported(binding):
 def test_struct_sizes_match_c_layout(binding):
     # 6 pointers, 5 int32 (+pad), 6 int64, float + 2 int32 (+pad), pointer, size_t, enum (+pad)
     assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8
-    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16
+    # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, int32 (+pad)
+    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8
 
 
 def test_version_and_strerror(binding):
@@ -146,6 +147,10 @@ def test_prefill_rejects_bad_arguments_before_launch(binding):
     a = good(); a.q_stride = (ctypes.c_int64 * 3)(4 * 128 * 128, 128 * 128, 130)
     assert call(a) == binding.PLX_ERR_ALIGN
     a = good(); a.k_stride = (ctypes.c_int64 * 3)(4 * 128 * 128, 128 * 128, 64)
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.Tkv = -1
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.Tkv = 64  # causal with fewer keys than query rows
     assert call(a) == binding.PLX_ERR_SHAPE
 
 

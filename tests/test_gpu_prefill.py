@@ -121,6 +121,55 @@ def test_prefill_last_row_equals_decode(plx, synth):
     assert rel_l2(host(dec), pre.astype(np.float64)) <= BF16_REL_L2
 
 
+def _chunk(y, T):
+    """The last T query rows of a square problem over all its keys."""
+    c = dict(y)
+    c["q"], c["r"] = y["q"][:, :, -T:].contiguous(), y["r"][:, :, -T:].contiguous()
+    return c
+
+
+@pytest.mark.parametrize("T,Tkv", [(1, 1), (1, 300), (5, 69), (64, 64 + 37), (128, 1000), (130, 515),
+                                   (257, 2048), (100, 100 + 64), (31, 4096)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_chunked_prefill_bf16(plx, synth, oracle, T, Tkv, causal):
+    """T query rows over Tkv >= T keys: causal rows are the last T positions of the sequence."""
+    y = _chunk(synth.prefill_inputs(2, 4, 2, Tkv, 128, seed=800 + T + Tkv, device=DEV,
+                                    k_offset_sigma=0.5), T)
+    ref = oracle_prefill(oracle, y, causal=causal)
+    got = _run(plx, y, causal=causal)
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    assert rel_l2(got, ref) <= BF16_REL_L2, (T, Tkv, causal)
+    # per-row check: a wrong diagonal offset shows up in single rows long before the total
+    row_err = np.linalg.norm(got - ref, axis=-1) / np.maximum(np.linalg.norm(ref, axis=-1), 1e-6)
+    assert row_err.max() <= 5 * BF16_REL_L2, (T, Tkv, causal, int(row_err.argmax()))
+
+
+def test_chunked_prefill_matches_square_tail_and_decode(plx, synth):
+    """Same kernel, two launches: the chunk equals the tail rows of the square problem; a
+    one-row chunk equals a decode step over the cache."""
+    y = synth.prefill_inputs(2, 16, 8, 1536, 128, seed=811, device=DEV)
+    square = _run(plx, y)
+    for T in (1, 200):
+        c = _chunk(y, T)
+        got = _run(plx, c)
+        assert rel_l2(got, square[:, :, -T:].astype(np.float64)) <= BF16_REL_L2
+    dec = plx.parallax_decode(y["q"][:, :, -1].contiguous(), y["r"][:, :, -1].contiguous(),
+                              y["k"], y["v"], y["scale"])
+    torch.cuda.synchronize()
+    assert rel_l2(host(dec), _run(plx, _chunk(y, 1))[:, :, 0].astype(np.float64)) <= BF16_REL_L2
+
+
+def test_chunked_prefill_fp32_and_d64(plx, synth, oracle):
+    y = _chunk(synth.prefill_inputs(1, 2, 2, 200, 64, seed=812, dtype=torch.float32, device=DEV), 50)
+    assert max_rel(_run(plx, y), oracle_prefill(oracle, y)) <= F32_MAX_REL
+    y = _chunk(synth.prefill_inputs(2, 4, 4, 333, 64, seed=813, device=DEV), 77)
+    assert rel_l2(_run(plx, y), oracle_prefill(oracle, y)) <= BF16_REL_L2
+    with pytest.raises(plx.ParallaxError):  # causal needs at least as many keys as rows
+        bad = dict(y)
+        bad["k"], bad["v"] = y["k"][:, :, :50].contiguous(), y["v"][:, :, :50].contiguous()
+        _run(plx, bad)
+
+
 def _sample_rows(B, Hq, T, n_random, seed, tile=128):
     rng = np.random.default_rng(seed)
     rows = set()
