@@ -31,8 +31,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per launch of the split-KV kernel on config 2, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE scaled by the same counters on parallax_util_copy of known size
-# (profiles/decode_bf16_config2_hbm_counters.md): 134 879 000 read + 1 081 344 written.
-MEASURED_TRAFFIC_BYTES = {"config2": 135960000}
+# (profiles/decode_bf16_config2_hbm_counters.md): 134 877 000 read + 1 081 344 written.
+# Prefill, config 4 (profiles/prefill_bf16_config4_hbm_counters.md): 431 631 000 read + 67 108 864
+# written.
+MEASURED_TRAFFIC_BYTES = {"config2": 135960000, "config4_prefill": 498740000}
 
 
 def decode_bytes(B, Hkv, d, lens_sum, Hq):
@@ -213,7 +215,8 @@ def prefill_line(torch, plx, synth, dev, opt):
                                "K offset N(0,0.5^2)", "algorithmic_flops": flops},
         "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": None, "kernel": "prefill_bf16_kernel<128,true,true>",
+                     "traffic": MEASURED_TRAFFIC_BYTES["config4_prefill"],
+                     "kernel": "prefill_bf16_kernel<128,true,true>",
                      "kernel_us": round(us, 1)},
     }
 
