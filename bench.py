@@ -168,7 +168,7 @@ def main():
         rh = x["r"].float().cpu().numpy()[:, :, None, :]
         kh, vh = x["k"].float().cpu().numpy(), x["v"].float().cpu().numpy()
         reps, tot = 0, 0.0
-        while tot < 10.0 and reps < 50:
+        while tot < 12.0 and reps < 1000:  # about 12 s of oracle work
             c0 = time.perf_counter()
             ref = parallax_oracle.forward(qh, rh, kh, vh, x["scale"])
             tot += time.perf_counter() - c0
@@ -274,6 +274,23 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
     torch.cuda.current_stream().wait_stream(side)
     us = _time_events(torch, graph.replay, 5, 50) / len(g_args)
     extra["config2_hip_graph_replay_us_per_step"] = round(us, 2)
+
+    # config 2 behind a block table (paged cache, shuffled page pool), 8 rotated pools
+    paged = {}
+    for page_size in (16, 128):
+        pools = [synth.paged_cache(x, page_size, seed=7000 + i) for i, x in enumerate(x0)]
+        p_args = [plx.decode_args(x["q"], x["r"], kp, vp, out, x["scale"], None, True, 0, ws,
+                                  block_table=tb, max_len=x["k"].shape[2])
+                  for x, (kp, vp, tb) in zip(x0, pools)]
+        pc = [0]
+
+        def paged_step():
+            lib.parallax_decode(ctypes.byref(p_args[pc[0] % len(p_args)]), sptr)
+            pc[0] += 1
+
+        paged["page_size_%d_us" % page_size] = round(_time_events(torch, paged_step, 20, 200), 2)
+        del pools, p_args
+    extra["config2_paged_cache"] = paged
 
     sweep = []
     for (B, L) in [(1, 1024), (1, 65536), (16, 4096), (16, 16384), (64, 16384), (128, 16384)]:

@@ -71,6 +71,14 @@ typedef enum {
  *   num_splits 0 = library heuristic, else the number of key-range splits to use
  *   workspace fp32 scratch for split partials, >= parallax_decode_workspace_bytes(...);
  *             may be NULL only when num_splits == 1
+ *
+ * Paged cache (block_table != NULL; the paper's Sec. 5 remark that cache layouts carry over --
+ * same loop, different tile iterator): k, v point to a pool of pages
+ *   [num_pages, Hkv, page_size, d] addressed as base + page*stride_b + h*stride_h + row*stride_l,
+ * and key j of sequence b lives in page block_table[b*block_table_stride + j / page_size], row
+ * j % page_size. block_table is int32 on the device; page_size >= 1;
+ * block_table_stride * page_size >= Lmax. Entries are clamped to [0, num_pages) before use but
+ * not otherwise checked. Lmax is the largest logical length (seq_lens bounds each sequence).
  */
 typedef struct {
     const void *q, *r;
@@ -86,6 +94,8 @@ typedef struct {
     void *workspace;
     size_t workspace_bytes;
     plx_dtype dtype;
+    const int32_t *block_table; /* NULL = contiguous cache */
+    int32_t page_size, block_table_stride, num_pages;
 } plx_decode_args;
 
 /* Bytes of workspace that is enough for any split count the library may pick or accept

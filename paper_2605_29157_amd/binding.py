@@ -42,6 +42,9 @@ class plx_decode_args(ctypes.Structure):
         ("num_splits", ctypes.c_int32),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("dtype", ctypes.c_int),
+        ("block_table", ctypes.c_void_p),
+        ("page_size", ctypes.c_int32), ("block_table_stride", ctypes.c_int32),
+        ("num_pages", ctypes.c_int32),
     ]
 
 
@@ -138,10 +141,15 @@ def parallax_decode_num_splits(B, Hq, Hkv, Lmax, d, num_cus=0) -> int:
     return int(load_library().parallax_decode_num_splits(B, Hq, Hkv, Lmax, d, num_cus))
 
 
-def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None):
-    """Fill a plx_decode_args from tensors: q, r, out [B, Hq, d]; k, v [B, Hkv, Lmax, d]."""
+def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None,
+                block_table=None, max_len=None):
+    """Fill a plx_decode_args from tensors: q, r, out [B, Hq, d]; k, v [B, Hkv, Lmax, d], or,
+    with block_table [B, pages per sequence] (int32), page pools [num_pages, Hkv, page_size, d]
+    (max_len = largest logical length, default: pages per sequence x page_size)."""
     B, Hq, d = q.shape
     _, Hkv, Lmax, _ = k.shape
+    if block_table is not None:
+        Lmax = int(max_len) if max_len is not None else block_table.shape[1] * k.shape[2]
     a = plx_decode_args()
     a.q, a.k, a.v, a.o = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
     a.r = r.data_ptr() if r is not None else None
@@ -156,11 +164,14 @@ def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0,
         a.workspace = workspace.data_ptr()
         a.workspace_bytes = workspace.numel() * workspace.element_size()
     a.dtype = _dtype_code(q)
+    if block_table is not None:
+        a.block_table = block_table.data_ptr()
+        a.page_size, a.block_table_stride, a.num_pages = k.shape[2], block_table.stride(0), k.shape[0]
     return a
 
 
 def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None,
-                    out=None, stream=None):
+                    out=None, stream=None, block_table=None, max_len=None):
     """Single-step Parallax decode. Allocates `out` / `workspace` with torch when not given
     (allocation only; all arithmetic is in the library)."""
     for t in (q, k, v) + ((r,) if r is not None else ()):
@@ -173,13 +184,20 @@ def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, 
         raise TypeError("seq_lens must be int32")
     B, Hq, d = q.shape
     _, Hkv, Lmax, _ = k.shape
+    if block_table is not None:
+        if block_table.dtype != torch.int32 or not block_table.is_cuda or block_table.stride(1) != 1:
+            raise TypeError("block_table must be an int32 device tensor [B, pages per sequence]")
+        if block_table.shape[0] != B or v.shape != k.shape:
+            raise ValueError("block_table needs one row per sequence; k and v pools of one shape")
+        Lmax = int(max_len) if max_len is not None else block_table.shape[1] * k.shape[2]
     if out is None:
         out = torch.empty_like(q)
     if workspace is None and num_splits != 1 and q.dtype == torch.bfloat16:
         S = num_splits or parallax_decode_num_splits(B, Hq, Hkv, Lmax, d)
         if S > 1:
             workspace = torch.empty(B * Hq * S * (2 * d + 4), dtype=torch.float32, device=q.device)
-    a = decode_args(q, r, k, v, out, scale, seq_lens, use_r, num_splits, workspace)
+    a = decode_args(q, r, k, v, out, scale, seq_lens, use_r, num_splits, workspace, block_table,
+                    max_len)
     st = load_library().parallax_decode(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_decode")

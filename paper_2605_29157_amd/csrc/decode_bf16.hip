@@ -28,7 +28,7 @@ constexpr int kTileKeys = 32;  // keys per wave tile
 constexpr int kWaves = 4;      // waves per workgroup
 static_assert(kTileKeys * kWaves == kDecodeBlockKeys, "block tile = waves x wave tile");
 
-template <int D, bool USE_R>
+template <int D, bool USE_R, bool PAGED>
 __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
     constexpr int KPI = 64 / CPR;         // rows covered by one wave-wide 16-byte load
@@ -68,21 +68,39 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
         }
     }
 
-    const __bf16 *kbase = (const __bf16 *)p.k + (int64_t)b * p.ksb + (int64_t)hk * p.ksh;
-    const __bf16 *vbase = (const __bf16 *)p.v + (int64_t)b * p.vsb + (int64_t)hk * p.vsh;
+    // paged cache: the batch stride is the page stride and is applied per row below
+    const __bf16 *kbase = (const __bf16 *)p.k + (PAGED ? 0 : (int64_t)b * p.ksb) + (int64_t)hk * p.ksh;
+    const __bf16 *vbase = (const __bf16 *)p.v + (PAGED ? 0 : (int64_t)b * p.vsb) + (int64_t)hk * p.vsh;
     u32x4 *ldsK = lds + w * (2 * TILE_CHUNKS);
     u32x4 *ldsV = ldsK + TILE_CHUNKS;
     const unsigned short *ldsV16 = (const unsigned short *)ldsV;
 
     const int ld_row = lane / CPR, ld_chunk = lane % CPR;  // this lane's place in a load
     u32x4 kst[NLD], vst[NLD];
+    // paged cache: page numbers of this lane's rows, looked up one tile before the rows
+    // themselves are fetched so that the table read is off the critical path
+    int32_t pg[NLD];
+    const int32_t *table = PAGED ? p.block_table + (int64_t)b * p.table_stride : nullptr;
+    auto lookup_pages = [&](int tk0) {
+        if constexpr (PAGED) {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) pg[i] = table[min(tk0 + i * KPI + ld_row, Lb - 1) / p.page_size];
+        }
+    };
     auto issue_loads = [&](int tk0) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             // rows past the sequence end re-read its last row (finite data, masked below)
             const int key = min(tk0 + i * KPI + ld_row, Lb - 1);
-            kst[i] = *(const u32x4 *)(kbase + (int64_t)key * p.ksl + ld_chunk * 8);
-            vst[i] = *(const u32x4 *)(vbase + (int64_t)key * p.vsl + ld_chunk * 8);
+            int64_t koff = (int64_t)key * p.ksl, voff = (int64_t)key * p.vsl;
+            if constexpr (PAGED) {
+                const int64_t page = min(max(pg[i], 0), p.num_pages - 1);
+                const int row = key % p.page_size;
+                koff = page * p.ksb + (int64_t)row * p.ksl;
+                voff = page * p.vsb + (int64_t)row * p.vsl;
+            }
+            kst[i] = *(const u32x4 *)(kbase + koff + ld_chunk * 8);
+            vst[i] = *(const u32x4 *)(vbase + voff + ld_chunk * 8);
         }
     };
 
@@ -97,7 +115,11 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     const float scale_log2 = p.scale * kLog2e;
 
     int tk = key_lo + w * kTileKeys;
-    if (tk < key_hi) issue_loads(tk);
+    if (tk < key_hi) {
+        lookup_pages(tk);
+        issue_loads(tk);
+        if (tk + kWaves * kTileKeys < key_hi) lookup_pages(tk + kWaves * kTileKeys);
+    }
     for (; tk < key_hi; tk += kWaves * kTileKeys) {
         // registers -> swizzled LDS tile (private to this wave)
 #pragma unroll
@@ -107,7 +129,10 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
             ldsV[slot] = vst[i];
         }
         const int tk_next = tk + kWaves * kTileKeys;
-        if (tk_next < key_hi) issue_loads(tk_next);
+        if (tk_next < key_hi) {
+            issue_loads(tk_next);
+            if (tk_next + kWaves * kTileKeys < key_hi) lookup_pages(tk_next + kWaves * kTileKeys);
+        }
         // lanes exchange data through LDS inside one wave: LDS executes a wave's accesses in
         // order, the fence only stops the compiler from moving reads above the writes
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -338,18 +363,26 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
     }
 }
 
+template <int D, bool USE_R>
+static void launch_decode_variant(const DecodeParams &p, dim3 grid, hipStream_t stream) {
+    if (p.block_table)
+        hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, true>), grid, dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, false>), grid, dim3(256), 0, stream, p);
+}
+
 hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream) {
-    const dim3 grid(p.S, p.Hkv, p.B), block(256);
+    const dim3 grid(p.S, p.Hkv, p.B);
     if (p.d == 128) {
         if (p.use_r)
-            hipLaunchKernelGGL((decode_bf16_kernel<128, true>), grid, block, 0, stream, p);
+            launch_decode_variant<128, true>(p, grid, stream);
         else
-            hipLaunchKernelGGL((decode_bf16_kernel<128, false>), grid, block, 0, stream, p);
+            launch_decode_variant<128, false>(p, grid, stream);
     } else {
         if (p.use_r)
-            hipLaunchKernelGGL((decode_bf16_kernel<64, true>), grid, block, 0, stream, p);
+            launch_decode_variant<64, true>(p, grid, stream);
         else
-            hipLaunchKernelGGL((decode_bf16_kernel<64, false>), grid, block, 0, stream, p);
+            launch_decode_variant<64, false>(p, grid, stream);
     }
     return hipGetLastError();
 }

@@ -15,6 +15,8 @@ struct GenericParams {
     int64_t qs[3], rs[3], ks[3], vs[3], os[3];
     float scale;
     int32_t causal, use_r;
+    const int32_t *block_table;  // paged decode cache (see DecodeParams); NULL = contiguous
+    int32_t page_size, table_stride, num_pages;
 };
 
 constexpr int kGenThreads = 256;
@@ -45,8 +47,16 @@ __global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams 
 
     const float *qrow = p.q + b * p.qs[0] + h * p.qs[1] + i * p.qs[2];
     const float *rrow = p.r ? p.r + b * p.rs[0] + h * p.rs[1] + i * p.rs[2] : nullptr;
-    const float *kb = p.k + b * p.ks[0] + hk * p.ks[1];
-    const float *vb = p.v + b * p.vs[0] + hk * p.vs[1];
+    const bool paged = p.block_table != nullptr;
+    const float *kb = p.k + (paged ? 0 : b * p.ks[0]) + hk * p.ks[1];
+    const float *vb = p.v + (paged ? 0 : b * p.vs[0]) + hk * p.vs[1];
+    // element offset of key j's row inside kb / vb (stride0 = page stride when paged)
+    auto row_off = [&](int j, const int64_t *st) -> int64_t {
+        if (!paged) return (int64_t)j * st[2];
+        const int pg = min(max(p.block_table[(int64_t)b * p.table_stride + j / p.page_size], 0),
+                           p.num_pages - 1);
+        return (int64_t)pg * st[0] + (int64_t)(j % p.page_size) * st[2];
+    };
     if (t < d) {
         sq[t] = qrow[t];
         sr[t] = (p.use_r && rrow) ? rrow[t] : 0.f;
@@ -61,7 +71,7 @@ __global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams 
         const bool valid = j < n_keys;
         float s1 = kNegInf, s2 = 0.f;
         if (valid) {
-            const float *kj = kb + (int64_t)j * p.ks[2];
+            const float *kj = kb + row_off(j, p.ks);
             float a1 = 0.f, a2 = 0.f;
             for (int c = 0; c < d; ++c) {
                 const float kv = kj[c];
@@ -95,7 +105,7 @@ __global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams 
             o2 *= alpha;
             const int n = min(kGenThreads, n_keys - j0);
             for (int jj = 0; jj < n; ++jj) {
-                const float vv = vb[(int64_t)(j0 + jj) * p.vs[2] + t];
+                const float vv = vb[row_off(j0 + jj, p.vs) + t];
                 o1 = fmaf(sp1[jj], vv, o1);
                 o2 = fmaf(sp2[jj], vv, o2);
             }
@@ -131,6 +141,8 @@ hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream) {
     g.ks[0] = p.ksb, g.ks[1] = p.ksh, g.ks[2] = p.ksl;
     g.vs[0] = p.vsb, g.vs[1] = p.vsh, g.vs[2] = p.vsl;
     g.scale = p.scale, g.causal = 0, g.use_r = p.use_r;
+    g.block_table = p.block_table;
+    g.page_size = p.page_size, g.table_stride = p.table_stride, g.num_pages = p.num_pages;
     return launch_generic(g, stream);
 }
 

@@ -105,6 +105,12 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
             if (!stride_aligned(s, a->dtype)) return PLX_ERR_ALIGN;
         }
         if (a->k_stride_l < a->d || a->v_stride_l < a->d) return PLX_ERR_SHAPE;
+        if (a->block_table) {
+            if (reinterpret_cast<uintptr_t>(a->block_table) & 3u) return PLX_ERR_ALIGN;
+            if (a->page_size < 1 || a->num_pages < 1 || a->block_table_stride < 1)
+                return PLX_ERR_SHAPE;
+            if ((int64_t)a->block_table_stride * a->page_size < a->Lmax) return PLX_ERR_SHAPE;
+        }
     }
     plx::DecodeParams p{};
     p.q = a->q, p.r = a->use_r ? a->r : a->q, p.k = a->k, p.v = a->v, p.o = a->o;
@@ -113,6 +119,11 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
     p.ksb = a->k_stride_b, p.ksh = a->k_stride_h, p.ksl = a->k_stride_l;
     p.vsb = a->v_stride_b, p.vsh = a->v_stride_h, p.vsl = a->v_stride_l;
     p.scale = a->scale, p.use_r = a->use_r ? 1 : 0;
+    if (need_inputs && a->block_table) {
+        p.block_table = a->block_table;
+        p.page_size = a->page_size, p.table_stride = a->block_table_stride;
+        p.num_pages = a->num_pages;
+    }
     *out = p;
     return PLX_OK;
 }

@@ -18,6 +18,10 @@ struct DecodeParams {
     float scale;
     int32_t use_r;
     int32_t direct_out;  // 1: S == 1 and the split kernel writes o itself (no workspace)
+    // paged cache: key j of sequence b is row j % page_size of page
+    // block_table[b * table_stride + j / page_size]; ksb / vsb are then the page strides
+    const int32_t *block_table;
+    int32_t page_size, table_stride, num_pages;
 };
 
 struct PrefillParams {

@@ -63,3 +63,24 @@ def prefill_inputs(B, Hq, Hkv, T, d, seed, dtype=torch.bfloat16, device="cpu",
     del kf
     v = _randn((B, Hkv, T, d), gen, device, dtype)
     return dict(q=q, r=r, k=k, v=v, scale=1.0 / math.sqrt(d))
+
+
+def paged_cache(x, page_size, seed, spare_pages=3):
+    """Scatter the contiguous caches x["k"], x["v"] [B, Hkv, L, d] into page pools
+    [num_pages, Hkv, page_size, d] in a seeded random page order (plus a few unused pages) and
+    return (k_pool, v_pool, block_table [B, pages per sequence] int32). Layout only."""
+    k, v = x["k"], x["v"]
+    B, Hkv, L, d = k.shape
+    per_seq = (L + page_size - 1) // page_size
+    n_pages = B * per_seq + spare_pages
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    order = torch.randperm(n_pages, generator=g)[: B * per_seq].reshape(B, per_seq)
+    pad = per_seq * page_size - L
+    kp = torch.nn.functional.pad(k, (0, 0, 0, pad)).reshape(B, Hkv, per_seq, page_size, d)
+    vp = torch.nn.functional.pad(v, (0, 0, 0, pad)).reshape(B, Hkv, per_seq, page_size, d)
+    k_pool = torch.zeros(n_pages, Hkv, page_size, d, dtype=k.dtype, device=k.device)
+    v_pool = torch.zeros_like(k_pool)
+    idx = order.reshape(-1).to(k.device)
+    k_pool[idx] = kp.permute(0, 2, 1, 3, 4).reshape(B * per_seq, Hkv, page_size, d)
+    v_pool[idx] = vp.permute(0, 2, 1, 3, 4).reshape(B * per_seq, Hkv, page_size, d)
+    return k_pool, v_pool, order.to(torch.int32).to(k.device)

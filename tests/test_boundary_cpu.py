@@ -37,8 +37,9 @@ def test_header_symbols_are_exported(binding):
 
 
 def test_struct_sizes_match_c_layout(binding):
-    # 6 pointers, 5 int32 (+pad), 6 int64, float + 2 int32 (+pad), pointer, size_t, enum (+pad)
-    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8
+    # 6 pointers, 5 int32 (+pad), 6 int64, float + 2 int32 (+pad), pointer, size_t, enum (+pad),
+    # pointer, 3 int32 (+pad)
+    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16
     # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, int32 (+pad)
     assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8
 
@@ -115,6 +116,19 @@ def test_decode_rejects_bad_arguments_before_launch(binding):
     a = _good_decode_args(binding); a.num_splits = 4
     a.workspace, a.workspace_bytes = 0x2000, 16
     assert call(a) == binding.PLX_ERR_WORKSPACE
+    # paged cache descriptors
+    def paged():
+        a = _good_decode_args(binding)
+        a.block_table, a.page_size, a.block_table_stride, a.num_pages = 0x3000, 16, 4, 8
+        return a
+    a = paged(); a.block_table = 0x3002
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = paged(); a.page_size = 0
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = paged(); a.num_pages = 0
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = paged(); a.block_table_stride = 3                   # 3 pages x 16 rows < Lmax = 64
+    assert call(a) == binding.PLX_ERR_SHAPE
 
 
 def test_prefill_rejects_bad_arguments_before_launch(binding):
