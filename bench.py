@@ -49,9 +49,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-extra", action="store_true", help="skip the sweep / prefill lines")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "prefill", "sweep"], default="decode",
                     help="decode = config 2 (the headline line); prefill = config 4 causal "
-                         "prefill alone, for profiling that kernel")
+                         "prefill alone, for profiling that kernel; sweep = the config 3 decode "
+                         "grid (B x L, fixed and ragged lengths, d = 128 and 64), one JSON line")
     ap.add_argument("--counter-mode", action="store_true",
                     help="short run for hardware-counter collection: 5 launches of the plain copy "
                          "kernel on 1 GiB (known size, calibrates FETCH_SIZE / WRITE_SIZE) and "
@@ -79,6 +80,9 @@ def main():
 
     if opt.workload == "prefill":
         print(json.dumps(prefill_line(torch, plx, synth, dev, opt)))
+        return
+    if opt.workload == "sweep":
+        print(json.dumps(decode_sweep(torch, plx, synth, lib, dev, sptr)))
         return
 
     # ------------------------------------------------------------------ workload: config 2
@@ -219,6 +223,48 @@ def prefill_line(torch, plx, synth, dev, opt):
                      "kernel": "prefill_bf16_kernel<128,true,true>",
                      "kernel_us": round(us, 1)},
     }
+
+
+def decode_sweep(torch, plx, synth, lib, dev, sptr):
+    """Config 3: B in {1, 16, 64, 128} x L in {1024, 4096, 16384, 65536}, bf16, 16 query / 8 KV
+    heads at d = 128 and the compute-matched 32 / 16 heads at d = 64; fixed lengths and ragged
+    lengths uniform on [L/2, L]. KV caches are rotated (>= 1 GB in total where one is smaller)."""
+    rows = []
+    for (Hq, Hkv, d) in [(16, 8, 128), (32, 16, 64)]:
+        for B in (1, 16, 64, 128):
+            for L in (1024, 4096, 16384, 65536):
+                per_set = B * Hkv * L * d * 4
+                nset = max(1, min(8, int(1.2e9 // per_set) + 1))
+                for ragged in (False, True):
+                    xs = [synth.decode_inputs(B, Hq, Hkv, L, d, seed=3000 + i, device=dev,
+                                              ragged=ragged) for i in range(nset)]
+                    o = torch.empty_like(xs[0]["q"])
+                    w = torch.empty(plx.parallax_decode_workspace_bytes(B, Hq, Hkv, L, d) // 4,
+                                    dtype=torch.float32, device=dev)
+                    row = {"d": d, "B": B, "L": L, "ragged": ragged, "kv_sets": nset,
+                           "num_splits": plx.parallax_decode_num_splits(B, Hq, Hkv, L, d)}
+                    lens_sum = [int(x["seq_lens"].sum().item()) if ragged else B * L for x in xs]
+                    for use_r in (True, False):
+                        al = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], o, x["scale"],
+                                              x.get("seq_lens"), use_r, 0, w) for x in xs]
+                        c = [0]
+
+                        def step():
+                            lib.parallax_decode(ctypes.byref(al[c[0] % nset]), sptr)
+                            c[0] += 1
+
+                        iters = 200 if per_set < 2e8 else (50 if per_set < 4e9 else 10)
+                        us = _time_events(torch, step, 3, iters)
+                        byts = sum(decode_bytes(B, Hkv, d, ls, Hq) for ls in lens_sum) / nset
+                        key = "parallax" if use_r else "softmax_only"
+                        row[key + "_us"] = round(us, 2)
+                        row[key + "_GBps"] = round(byts / us / 1e3, 1)
+                    row["frac_of_8TBps"] = round(row["parallax_GBps"] / HBM_PEAK_GBPS, 4)
+                    rows.append(row)
+                    print("sweep", json.dumps(row), file=sys.stderr, flush=True)
+                    del xs, al, o, w
+    return {"metric": "decode_hbm_bandwidth_sweep", "unit": "GB/s", "n_gpus": 1, "dtype": "bf16",
+            "data": "synthetic", "config": {"workload": "config3: decode sweep"}, "rows": rows}
 
 
 def _time_events(torch, fn, warm, iters):
