@@ -61,18 +61,24 @@ int32_t parallax_decode_num_splits(int32_t B, int32_t Hq, int32_t Hkv, int32_t L
     (void)d;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Lmax <= 0) return 1;
     if (num_cus <= 0) num_cus = query_num_cus();
-    // Two workgroups are resident per compute unit: aim at one full round of them (measured:
-    // more, shorter splits only add prologue / merge work), and bound the work of one split
-    // to 4096 keys so that the tail of a long or ragged batch stays short.
+    // Measured on MI355X (sweeps over B, L and S). With few (batch, kv head) pairs the kernel is
+    // latency bound and wants many short splits: aim at one full round of the two workgroups
+    // that are resident per compute unit. From half a workgroup per compute unit on, the pairs
+    // alone keep enough loads in flight and every further split only adds partials and the
+    // merge: split by length only, at most 4096 keys per split so that the tail of a long or
+    // ragged batch stays short.
     const int64_t pairs = (int64_t)B * Hkv;
-    const int64_t target = 2LL * num_cus;
-    int64_t s = (target + pairs - 1) / pairs;
     const int64_t by_len = ((int64_t)Lmax + 4095) / 4096;
-    if (s < by_len) s = by_len;
-    // ... but keep at least two 128-key block tiles per split
+    int64_t s = by_len;
+    if (2 * pairs < num_cus) {
+        const int64_t target = 2LL * num_cus;
+        s = (target + pairs - 1) / pairs;
+        if (s < by_len) s = by_len;
+    }
+    // ... but keep at least two 128-key block tiles per split, and do not split below 1024 keys
+    // at all (the merge kernel then costs more than the shorter loop saves)
     const int64_t n_bt = ((int64_t)Lmax + plx::kDecodeBlockKeys - 1) / plx::kDecodeBlockKeys;
-    int64_t cap = n_bt / 2;
-    if (cap < 1) cap = 1;
+    int64_t cap = n_bt >= 8 ? n_bt / 2 : 1;
     if (s > cap) s = cap;
     if (s > PLX_MAX_SPLITS) s = PLX_MAX_SPLITS;
     if (s < 1) s = 1;

@@ -70,6 +70,13 @@ def test_split_heuristic_is_sane(binding):
             assert s >= (L + 4095) // 4096 or s == binding.PLX_MAX_SPLITS
     assert f(8, 16, 8, 4096, 128, 256) == 8    # 512 workgroups over 64 (batch, kv head) pairs
     assert f(1, 16, 8, 256, 128, 256) == 1
+    assert f(1, 16, 8, 512, 128, 256) == 1     # no split below 1024 keys
+    assert f(1, 16, 8, 1024, 128, 256) == 4
+    # from half a workgroup per compute unit on: split by length only
+    assert f(16, 16, 8, 2048, 128, 256) == 1
+    assert f(16, 16, 8, 16384, 128, 256) == 4
+    assert f(32, 16, 8, 4096, 128, 256) == 1
+    assert f(32, 16, 8, 8192, 128, 256) == 2
 
 
 def _good_decode_args(binding):
