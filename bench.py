@@ -146,7 +146,7 @@ def main():
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES["config2"],
-                "kernel": "decode_bf16_kernel<128,true>", "kernel_us": round(kern_us, 2),
+                "kernel": "decode_bf16_kernel<128,true,false>", "kernel_us": round(kern_us, 2),
                 "algorithmic_bytes_per_launch": step_bytes}
 
     result = {
