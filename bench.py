@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the Parallax attention hot path on one MI355X.
 
-Default workload (BASELINE config 2): single-step decode, bf16, B=8, 16 query heads / 8 KV
+Default workload (benchmark configuration 2): single-step decode, bf16, B=8, 16 query heads / 8 KV
 heads (GQA group 2), head_dim 128, KV context 4096. One "step" = one parallax_decode call:
 the split-KV kernel over the whole KV cache plus the combine kernel. Inputs are synthetic
 (seeded N(0,1)), resident in HBM before the timed region; 8 distinct KV caches (1.07 GB) are

@@ -35,7 +35,7 @@ def _run(plx, x, **kw):
 
 
 def test_config2_decode_bf16_full(plx, synth, oracle):
-    """BASELINE config 2: B=8, 16 q heads / 8 kv heads, d=128, L=4096, library split heuristic
+    """benchmark configuration 2: B=8, 16 q heads / 8 kv heads, d=128, L=4096, library split heuristic
     (the launch configuration bench.py times)."""
     x = synth.decode_inputs(8, 16, 8, 4096, 128, seed=1002, device=DEV)
     ref = oracle_decode(oracle, x)

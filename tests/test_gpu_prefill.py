@@ -32,7 +32,7 @@ def _run(plx, y, **kw):
 
 
 def test_config1_tiny_causal_fp32(plx, synth, oracle):
-    """BASELINE config 1: B=1, 2 heads (no GQA), T=128, d=64, fp32, scale 1/8."""
+    """benchmark configuration 1: B=1, 2 heads (no GQA), T=128, d=64, fp32, scale 1/8."""
     y = synth.prefill_inputs(1, 2, 2, 128, 64, seed=1001, dtype=torch.float32, device=DEV)
     assert abs(y["scale"] - 0.125) < 1e-12
     ref = oracle_prefill(oracle, y)
@@ -187,7 +187,7 @@ def _sample_rows(B, Hq, T, n_random, seed, tile=128):
 
 
 def test_config4_prefill_bf16_sampled(plx, synth, oracle):
-    """BASELINE config 4: B=4, T=4096, 16/8 heads, d=128, keys offset per (b, kv head) by
+    """benchmark configuration 4: B=4, T=4096, 16/8 heads, d=128, keys offset per (b, kv head) by
     N(0, 0.5^2); oracle on sampled rows (first/last rows, tile edges, random)."""
     y = synth.prefill_inputs(4, 16, 8, 4096, 128, seed=1004, device=DEV, k_offset_sigma=0.5)
     got = _run(plx, y)
