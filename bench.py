@@ -403,6 +403,22 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
         more.append({"workload": name, "us": round(us, 1), "TFLOPs": round(flops / us / 1e6, 1),
                      "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
         del y, po
+    # chunked prefill: T new rows behind an existing cache (causal, rows = the last T positions)
+    for (B, T, Tkv) in [(8, 512, 8192), (4, 2048, 16384), (64, 4, 4096)]:
+        Hq, Hkv, d = 16, 8, 128
+        y = synth.prefill_inputs(B, Hq, Hkv, Tkv, d, seed=1006, device=dev)
+        qc, rc = y["q"][:, :, -T:].contiguous(), y["r"][:, :, -T:].contiguous()
+        po = torch.empty_like(qc)
+        us = _time_events(
+            torch, lambda: plx.parallax_prefill(qc, rc, y["k"], y["v"], y["scale"], causal=True,
+                                                out=po), 2, 10)
+        pairs = T * (Tkv - T) + T * (T + 1) / 2  # allowed (row, key) pairs per head
+        flops = B * Hq * 8 * d * pairs
+        more.append({"workload": "chunked causal B=%d T=%d rows over Tkv=%d keys, d=128" % (B, T, Tkv),
+                     "us": round(us, 1), "TFLOPs": round(flops / us / 1e6, 1),
+                     "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "kv_GBps": round(B * Hkv * Tkv * d * 4 / us / 1e3, 1)})
+        del y, po, qc, rc
     extra["prefill_more"] = more
     return extra
 
