@@ -338,6 +338,31 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
         del pools, p_args
     extra["config2_paged_cache"] = paged
 
+    # several query rows per sequence (speculative rows): same K/V traffic as one row
+    multi = []
+    for (B, L, Tq) in [(64, 4096, 4), (64, 4096, 8), (8, 16384, 4)]:
+        Hq, Hkv, d = 16, 8, 128
+        per_set = B * Hkv * L * d * 4
+        nset = max(1, min(8, int(1.2e9 // per_set) + 1))
+        xs = [synth.decode_inputs(B, Hq, Hkv, L, d, seed=3100 + i, device=dev) for i in range(nset)]
+        qr = synth.prefill_inputs(B, Hq, Hkv, Tq, d, seed=3200, device=dev)
+        o = torch.empty_like(qr["q"])
+        w = torch.empty(Tq * plx.parallax_decode_workspace_bytes(B, Hq, Hkv, L, d) // 4,
+                        dtype=torch.float32, device=dev)
+        al = [plx.decode_args(qr["q"], qr["r"], x["k"], x["v"], o, x["scale"], None, True, 0, w)
+              for x in xs]
+        mc = [0]
+
+        def multi_step():
+            lib.parallax_decode(ctypes.byref(al[mc[0] % nset]), sptr)
+            mc[0] += 1
+
+        us = _time_events(torch, multi_step, 5, 50)
+        multi.append({"B": B, "L": L, "Tq": Tq, "us": round(us, 2),
+                      "kv_GBps": round(per_set / us / 1e3, 1)})
+        del xs, al
+    extra["decode_several_query_rows"] = multi
+
     sweep = []
     for (B, L) in [(1, 1024), (1, 65536), (16, 4096), (16, 16384), (64, 16384), (128, 16384)]:
         Hq, Hkv, d = 16, 8, 128

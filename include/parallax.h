@@ -72,6 +72,12 @@ typedef enum {
  *   workspace fp32 scratch for split partials, >= parallax_decode_workspace_bytes(...);
  *             may be NULL only when num_splits == 1
  *
+ * Several query rows (Tq > 1; speculative rows or a short chunk, the causal set of Sec. 2.1 at
+ * absolute positions): q, r, o are [B, Hq, Tq, d] and the rows are the LAST Tq positions of the
+ * sequence, so row t sees key j iff j < L_b - (Tq - 1 - t). All rows of all heads of a GQA group
+ * ride in one MFMA operand and share every K/V fetch: bf16 needs (Hq / Hkv) * Tq <= 16. The
+ * workspace then needs Tq times parallax_decode_workspace_bytes(...).
+ *
  * Paged cache (block_table != NULL; the paper's Sec. 5 remark that cache layouts carry over --
  * same loop, different tile iterator): k, v point to a pool of pages
  *   [num_pages, Hkv, page_size, d] addressed as base + page*stride_b + h*stride_h + row*stride_l,
@@ -96,6 +102,7 @@ typedef struct {
     plx_dtype dtype;
     const int32_t *block_table; /* NULL = contiguous cache */
     int32_t page_size, block_table_stride, num_pages;
+    int32_t Tq; /* query rows per sequence; 0 or 1 = one */
 } plx_decode_args;
 
 /* Bytes of workspace that is enough for any split count the library may pick or accept

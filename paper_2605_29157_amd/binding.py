@@ -45,6 +45,7 @@ class plx_decode_args(ctypes.Structure):
         ("block_table", ctypes.c_void_p),
         ("page_size", ctypes.c_int32), ("block_table_stride", ctypes.c_int32),
         ("num_pages", ctypes.c_int32),
+        ("Tq", ctypes.c_int32),
     ]
 
 
@@ -145,8 +146,12 @@ def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0,
                 block_table=None, max_len=None):
     """Fill a plx_decode_args from tensors: q, r, out [B, Hq, d]; k, v [B, Hkv, Lmax, d], or,
     with block_table [B, pages per sequence] (int32), page pools [num_pages, Hkv, page_size, d]
-    (max_len = largest logical length, default: pages per sequence x page_size)."""
-    B, Hq, d = q.shape
+    (max_len = largest logical length, default: pages per sequence x page_size).
+    q, r, out may also be [B, Hq, Tq, d]: Tq query rows, the last Tq positions of each sequence."""
+    Tq = 1
+    if q.dim() == 4:
+        Tq = q.shape[2]
+    B, Hq, d = q.shape[0], q.shape[1], q.shape[-1]
     _, Hkv, Lmax, _ = k.shape
     if block_table is not None:
         Lmax = int(max_len) if max_len is not None else block_table.shape[1] * k.shape[2]
@@ -164,6 +169,7 @@ def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0,
         a.workspace = workspace.data_ptr()
         a.workspace_bytes = workspace.numel() * workspace.element_size()
     a.dtype = _dtype_code(q)
+    a.Tq = Tq
     if block_table is not None:
         a.block_table = block_table.data_ptr()
         a.page_size, a.block_table_stride, a.num_pages = k.shape[2], block_table.stride(0), k.shape[0]
@@ -182,7 +188,8 @@ def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, 
         raise ValueError("q, r must be contiguous and k, v contiguous in the last dimension")
     if seq_lens is not None and seq_lens.dtype != torch.int32:
         raise TypeError("seq_lens must be int32")
-    B, Hq, d = q.shape
+    B, Hq, d = q.shape[0], q.shape[1], q.shape[-1]
+    Tq = q.shape[2] if q.dim() == 4 else 1
     _, Hkv, Lmax, _ = k.shape
     if block_table is not None:
         if block_table.dtype != torch.int32 or not block_table.is_cuda or block_table.stride(1) != 1:
@@ -195,7 +202,8 @@ def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, 
     if workspace is None and num_splits != 1 and q.dtype == torch.bfloat16:
         S = num_splits or parallax_decode_num_splits(B, Hq, Hkv, Lmax, d)
         if S > 1:
-            workspace = torch.empty(B * Hq * S * (2 * d + 4), dtype=torch.float32, device=q.device)
+            workspace = torch.empty(B * Hq * Tq * S * (2 * d + 4), dtype=torch.float32,
+                                    device=q.device)
     a = decode_args(q, r, k, v, out, scale, seq_lens, use_r, num_splits, workspace, block_table,
                     max_len)
     st = load_library().parallax_decode(ctypes.byref(a), _stream_ptr(stream))

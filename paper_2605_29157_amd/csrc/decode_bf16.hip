@@ -37,14 +37,20 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     constexpr int NDB = D / 16;           // 16-wide blocks of output dimensions
     constexpr int TILE_CHUNKS = kTileKeys * CPR;
 
-    __shared__ u32x4 lds[kWaves * 2 * TILE_CHUNKS];
+    // K/V tiles of the four waves; reused at the end for the merge of their states, which for 16
+    // live columns needs 768 bytes more than the tiles
+    __shared__ u32x4 lds[kWaves * 2 * TILE_CHUNKS + 48];
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63;
-    const int c = lane & 15;   // MFMA column: query head within the GQA group (live if c < G)
+    const int c = lane & 15;   // MFMA column: (query row t, head of the GQA group), live if c < GC
     const int g = lane >> 4;   // 16-lane row of the wave
     const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const int G = p.G, S = p.S;
+    // With Tq query rows per sequence (the last Tq positions: speculative rows, a short chunk)
+    // column c = t * G + head: all rows of all heads of the group share every K/V fetch.
+    const int Tq = p.Tq, GC = G * Tq;
+    const int col_t = c / G, col_h = c - col_t * G;
 
     int Lb = p.seq_lens ? p.seq_lens[b] : p.Lmax;
     Lb = min(max(Lb, 0), p.Lmax);
@@ -54,10 +60,11 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     const int key_hi = min(key_lo + bt_per_split * kDecodeBlockKeys, Lb);
 
     // ---- B operands: q and r rows of the group's heads, zero in the dead columns ----------
-    const bool live = c < G;
+    const bool live = c < GC;
     u32x4 qf[KSTEPS], rf[KSTEPS];
     {
-        const int64_t row = ((int64_t)b * p.Hq + (int64_t)hk * G + (live ? c : 0)) * D;
+        const int64_t row =
+            (((int64_t)b * p.Hq + (int64_t)hk * G + (live ? col_h : 0)) * Tq + (live ? col_t : 0)) * D;
         const __bf16 *qrow = (const __bf16 *)p.q + row;
         const __bf16 *rrow = (const __bf16 *)p.r + row;
 #pragma unroll
@@ -113,6 +120,8 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
         o2[n] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const float scale_log2 = p.scale * kLog2e;
+    // last-positions alignment: row t of Tq sees the keys before position Lb - (Tq - 1 - t)
+    const int col_hi = min(key_hi, Lb - (Tq - 1 - (live ? col_t : Tq - 1)));
 
     int tk = key_lo + w * kTileKeys;
     if (tk < key_hi) {
@@ -161,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int key = tk + 16 * sub + 4 * g + i;
-                x[sub][i] = key < key_hi ? s1[sub][i] * scale_log2 : kNegInf;
+                x[sub][i] = key < col_hi ? s1[sub][i] * scale_log2 : kNegInf;
                 tmax = fmaxf(tmax, x[sub][i]);
             }
         tmax = rows_max(tmax);
@@ -232,8 +241,8 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     float *mrg_m = mrg;                        // [kWaves][16]
     float *mrg_d1 = mrg + kWaves * 16;         // [kWaves][16]
     float *mrg_d2 = mrg + 2 * kWaves * 16;     // [kWaves][16]
-    float *mrg_o1 = mrg + 3 * kWaves * 16;     // [kWaves][G][D]
-    float *mrg_o2 = mrg_o1 + kWaves * G * D;   // [kWaves][G][D]
+    float *mrg_o1 = mrg + 3 * kWaves * 16;     // [kWaves][GC][D]
+    float *mrg_o2 = mrg_o1 + kWaves * GC * D;  // [kWaves][GC][D]
     if (live) {
         if (g == 0) {
             mrg_m[w * 16 + c] = m_run;
@@ -245,14 +254,14 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int dim = 16 * n + 4 * g + i;  // accumulator row of O^T
-                mrg_o1[(w * G + c) * D + dim] = o1[n][i];
-                mrg_o2[(w * G + c) * D + dim] = USE_R ? o2[n][i] : 0.f;
+                mrg_o1[(w * GC + c) * D + dim] = o1[n][i];
+                mrg_o2[(w * GC + c) * D + dim] = USE_R ? o2[n][i] : 0.f;
             }
     }
     __syncthreads();
 
-    for (int idx = tid; idx < G * D; idx += 256) {
-        const int hh = idx / D, dim = idx - hh * D;
+    for (int idx = tid; idx < GC * D; idx += 256) {
+        const int hh = idx / D, dim = idx - hh * D;  // hh: column (t, head)
         float m_star = kNegInf;
 #pragma unroll
         for (int ww = 0; ww < kWaves; ++ww) m_star = fmaxf(m_star, mrg_m[ww * 16 + hh]);
@@ -263,10 +272,12 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
             const float wt = mw == kNegInf ? 0.f : fast_exp2(mw - m_star);
             d1 += wt * mrg_d1[ww * 16 + hh];
             d2 += wt * mrg_d2[ww * 16 + hh];
-            a1 += wt * mrg_o1[(ww * G + hh) * D + dim];
-            a2 += wt * mrg_o2[(ww * G + hh) * D + dim];
+            a1 += wt * mrg_o1[(ww * GC + hh) * D + dim];
+            a2 += wt * mrg_o2[(ww * GC + hh) * D + dim];
         }
-        const int64_t hq = (int64_t)b * p.Hq + (int64_t)hk * G + hh;
+        const int ot = hh / G, oh = hh - ot * G;
+        // output / workspace row of (batch, query head, query row)
+        const int64_t hq = ((int64_t)b * p.Hq + (int64_t)hk * G + oh) * Tq + ot;
         if (p.direct_out) {
             float out = 0.f;  // empty key set: zeros
             if (d1 > 0.f) {
@@ -320,7 +331,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
     __shared__ f32x4 sm_a1[SL][DL], sm_a2[SL][DL];
 
     const int tid = threadIdx.x, sl = tid / DL, dl = tid % DL;
-    const int64_t hq = (int64_t)blockIdx.y * p.Hq + blockIdx.x;
+    const int64_t hq = (int64_t)blockIdx.y * p.Hq * p.Tq + blockIdx.x;  // (batch, head, query row)
     const int S = p.S;
     const float *rec0 = p.ws + hq * S * (int64_t)REC;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -388,7 +399,7 @@ hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream) {
 }
 
 hipError_t launch_decode_combine(const DecodeParams &p, hipStream_t stream) {
-    const dim3 grid(p.Hq, p.B);
+    const dim3 grid(p.Hq * p.Tq, p.B);
     if (p.d == 128)
         hipLaunchKernelGGL((decode_combine_kernel<128>), grid, dim3(256), 0, stream, p);
     else

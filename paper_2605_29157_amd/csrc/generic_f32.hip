@@ -17,6 +17,7 @@ struct GenericParams {
     int32_t causal, use_r;
     const int32_t *block_table;  // paged decode cache (see DecodeParams); NULL = contiguous
     int32_t page_size, table_stride, num_pages;
+    int32_t tail_rows;  // decode with Tq rows: row i sees the keys before len_b - (Tq - 1 - i)
 };
 
 constexpr int kGenThreads = 256;
@@ -44,6 +45,7 @@ __global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams 
         n_keys = i + 1 + (p.Lk - p.Tq);  // the query rows are the last Tq positions
     else
         n_keys = p.seq_lens ? min(max(p.seq_lens[b], 0), p.Lk) : p.Lk;
+    if (p.tail_rows) n_keys = max(n_keys - (p.Tq - 1 - i), 0);
 
     const float *qrow = p.q + b * p.qs[0] + h * p.qs[1] + i * p.qs[2];
     const float *rrow = p.r ? p.r + b * p.rs[0] + h * p.rs[1] + i * p.rs[2] : nullptr;
@@ -134,10 +136,11 @@ hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream) {
     g.v = (const float *)p.v;
     g.o = (float *)p.o;
     g.seq_lens = p.seq_lens;
-    g.B = p.B, g.Hq = p.Hq, g.Hkv = p.Hkv, g.G = p.G, g.Tq = 1, g.Lk = p.Lmax, g.d = p.d;
-    g.qs[0] = g.rs[0] = g.os[0] = (int64_t)p.Hq * p.d;
-    g.qs[1] = g.rs[1] = g.os[1] = p.d;
-    g.qs[2] = g.rs[2] = g.os[2] = 0;
+    g.B = p.B, g.Hq = p.Hq, g.Hkv = p.Hkv, g.G = p.G, g.Tq = p.Tq, g.Lk = p.Lmax, g.d = p.d;
+    g.qs[0] = g.rs[0] = g.os[0] = (int64_t)p.Hq * p.Tq * p.d;
+    g.qs[1] = g.rs[1] = g.os[1] = (int64_t)p.Tq * p.d;
+    g.qs[2] = g.rs[2] = g.os[2] = p.d;
+    g.tail_rows = 1;
     g.ks[0] = p.ksb, g.ks[1] = p.ksh, g.ks[2] = p.ksl;
     g.vs[0] = p.vsb, g.vs[1] = p.vsh, g.vs[2] = p.vsl;
     g.scale = p.scale, g.causal = 0, g.use_r = p.use_r;

@@ -97,6 +97,9 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
     plx_status st = check_common(a->dtype, a->B, a->Hq, a->Hkv, need_inputs ? a->Lmax : 1, a->d);
     if (st != PLX_OK) return st;
     if (a->num_splits < 0 || a->num_splits > PLX_MAX_SPLITS) return PLX_ERR_SPLITS;
+    if (a->Tq < 0 || a->Tq > 65535) return PLX_ERR_SHAPE;
+    const int32_t Tq = a->Tq ? a->Tq : 1;
+    if (a->dtype == PLX_BF16 && (a->Hq / a->Hkv) * Tq > 16) return PLX_ERR_SHAPE;
     if (need_inputs && !(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
     if (need_out && !aligned16(a->o)) return PLX_ERR_ALIGN;
     if (((int64_t)a->d * elem_size(a->dtype)) % 16 != 0) return PLX_ERR_ALIGN;
@@ -125,6 +128,7 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
     p.ksb = a->k_stride_b, p.ksh = a->k_stride_h, p.ksl = a->k_stride_l;
     p.vsb = a->v_stride_b, p.vsh = a->v_stride_h, p.vsl = a->v_stride_l;
     p.scale = a->scale, p.use_r = a->use_r ? 1 : 0;
+    p.Tq = Tq;
     if (need_inputs && a->block_table) {
         p.block_table = a->block_table;
         p.page_size = a->page_size, p.table_stride = a->block_table_stride;
@@ -136,7 +140,7 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
 
 plx_status attach_workspace(const plx_decode_args *a, int32_t S, plx::DecodeParams *p) {
     if (!a->workspace || !aligned16(a->workspace)) return PLX_ERR_WORKSPACE;
-    if (a->workspace_bytes < ws_bytes(a->B, a->Hq, S, a->d)) return PLX_ERR_WORKSPACE;
+    if (a->workspace_bytes < ws_bytes(a->B, (int64_t)a->Hq * p->Tq, S, a->d)) return PLX_ERR_WORKSPACE;
     p->ws = static_cast<float *>(a->workspace);
     return PLX_OK;
 }

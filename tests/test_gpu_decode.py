@@ -166,6 +166,87 @@ def test_paged_cache_other_layouts(plx, synth, oracle):
     assert max_rel(host(out), oracle_decode(oracle, x)) <= F32_MAX_REL
 
 
+def _multirow_inputs(synth, B, Hq, Hkv, L, d, Tq, seed, dtype=torch.bfloat16, lens=None):
+    """Decode inputs whose q, r hold Tq rows per head: [B, Hq, Tq, d]."""
+    x = synth.decode_inputs(B, Hq, Hkv, L, d, seed=seed, dtype=dtype, device=DEV)
+    more = synth.prefill_inputs(B, Hq, Hkv, Tq, d, seed=seed + 1, dtype=dtype, device=DEV)
+    x["q"], x["r"] = more["q"].contiguous(), more["r"].contiguous()
+    if lens is not None:
+        x["seq_lens"] = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    return x
+
+
+def _multirow_oracle(oracle, x, use_r=True):
+    """Row t of the Tq rows is position L_b - Tq + t: causal chunk over the first L_b keys."""
+    q, r, k, v = (host(x[n]) for n in "qrkv")
+    B, Hq, Tq, d = q.shape
+    lens = host(x["seq_lens"]).astype(int) if x.get("seq_lens") is not None else [k.shape[2]] * B
+    out = np.zeros((B, Hq, Tq, d))
+    for b in range(B):
+        Lb = int(lens[b])
+        t0 = max(0, Tq - Lb)  # rows before position 0 see nothing: zeros
+        if Lb == 0:
+            continue
+        rr = r[b:b + 1, :, t0:] if use_r else np.zeros_like(r[b:b + 1, :, t0:])
+        out[b, :, t0:] = oracle.forward(q[b:b + 1, :, t0:], rr, k[b:b + 1, :, :Lb], v[b:b + 1, :, :Lb],
+                                        x["scale"], causal=True)[0]
+    return out
+
+
+@pytest.mark.parametrize("Hq,Hkv,Tq", [(16, 8, 2), (16, 8, 5), (16, 8, 8), (4, 4, 16), (8, 1, 2),
+                                       (8, 2, 4), (6, 2, 3)])
+@pytest.mark.parametrize("S", [0, 1, 5])
+def test_several_query_rows_per_sequence(plx, synth, oracle, Hq, Hkv, Tq, S):
+    """Tq query rows as extra MFMA columns: the rows are the last Tq positions (speculative rows)."""
+    lens = [1500, 3, 777, 1][:3] if S else [1500, 1024, 129]
+    x = _multirow_inputs(synth, 3, Hq, Hkv, 1500, 128, Tq, seed=400 + Tq + Hq, lens=lens)
+    ref = _multirow_oracle(oracle, x)
+    out = plx.parallax_decode(x["q"], x["r"], x["k"], x["v"], x["scale"], seq_lens=x["seq_lens"],
+                              num_splits=S)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    assert rel_l2(got, ref) <= BF16_REL_L2, (Hq, Hkv, Tq, S)
+    row_err = np.linalg.norm(got - ref, axis=-1) / np.maximum(np.linalg.norm(ref, axis=-1), 1e-6)
+    assert row_err.max() <= 5 * BF16_REL_L2, (Hq, Hkv, Tq, S, np.unravel_index(row_err.argmax(), row_err.shape))
+
+
+def test_several_query_rows_other_paths(plx, synth, oracle):
+    # one row given as [B, Hq, 1, d] is the ordinary decode step, bit for bit
+    x = synth.decode_inputs(2, 16, 8, 900, 128, seed=420, device=DEV, ragged=True)
+    a = _run(plx, x, num_splits=3)
+    b4 = plx.parallax_decode(x["q"][:, :, None].contiguous(), x["r"][:, :, None].contiguous(), x["k"],
+                             x["v"], x["scale"], seq_lens=x["seq_lens"], num_splits=3)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(b4)[:, :, 0], a)
+    # the same rows through the prefill kernel (chunked causal): two kernels, one operator
+    y = _multirow_inputs(synth, 2, 16, 8, 640, 128, 6, seed=421)
+    dec = plx.parallax_decode(y["q"], y["r"], y["k"], y["v"], y["scale"])
+    pre = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True)
+    torch.cuda.synchronize()
+    assert rel_l2(host(dec), host(pre)) <= BF16_REL_L2
+    # rows that sit before position 0 (sequence shorter than Tq) come out as zeros
+    z = _multirow_inputs(synth, 2, 16, 8, 256, 128, 4, seed=422, lens=[2, 256])
+    got = host(plx.parallax_decode(z["q"], z["r"], z["k"], z["v"], z["scale"], seq_lens=z["seq_lens"]))
+    torch.cuda.synchronize()
+    assert (got[0, :, :2] == 0).all() and rel_l2(got, _multirow_oracle(oracle, z)) <= BF16_REL_L2
+    # d = 64, softmax-only twin, paged cache, fp32
+    w = _multirow_inputs(synth, 2, 8, 4, 500, 64, 3, seed=423, lens=[500, 77])
+    kp, vp, table = synth.paged_cache(w, 16, seed=424)
+    got = plx.parallax_decode(w["q"], None, kp, vp, w["scale"], seq_lens=w["seq_lens"], use_r=False,
+                              block_table=table, max_len=500)
+    torch.cuda.synchronize()
+    assert rel_l2(host(got), _multirow_oracle(oracle, w, use_r=False)) <= BF16_REL_L2
+    f = _multirow_inputs(synth, 2, 4, 2, 200, 64, 20, seed=425, dtype=torch.float32, lens=[200, 31])
+    got = plx.parallax_decode(f["q"], f["r"], f["k"], f["v"], f["scale"], seq_lens=f["seq_lens"])
+    torch.cuda.synchronize()
+    assert max_rel(host(got), _multirow_oracle(oracle, f)) <= F32_MAX_REL
+    # more columns than one MFMA operand holds
+    bad = _multirow_inputs(synth, 1, 16, 8, 256, 128, 9, seed=426)
+    with pytest.raises(plx.ParallaxError):
+        plx.parallax_decode(bad["q"], bad["r"], bad["k"], bad["v"], bad["scale"])
+
+
 def test_hip_graph_replays_match_eager(plx, synth, oracle):
     """Decode and prefill captured in one HIP graph: every replay, with eager work and
     synchronisation in between and inputs changed in place, equals the eager result."""
