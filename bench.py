@@ -53,6 +53,9 @@ def main():
                     help="decode = config 2 (the headline line); prefill = config 4 causal "
                          "prefill alone, for profiling that kernel; sweep = the config 3 decode "
                          "grid (B x L, fixed and ragged lengths, d = 128 and 64), one JSON line")
+    ap.add_argument("--decode-shape", default="8,4096", metavar="B,L",
+                    help="batch and KV length of the decode workload (default 8,4096 = config 2; "
+                         "other shapes are for profiling the same kernels at larger sizes)")
     ap.add_argument("--counter-mode", action="store_true",
                     help="short run for hardware-counter collection: 5 launches of the plain copy "
                          "kernel on 1 GiB (known size, calibrates FETCH_SIZE / WRITE_SIZE) and "
@@ -86,8 +89,11 @@ def main():
         return
 
     # ------------------------------------------------------------------ workload: config 2
-    B, Hq, Hkv, L, d = 8, 16, 8, 4096, 128
-    NSETS = 8
+    B, L = (int(v) for v in opt.decode_shape.split(","))
+    Hq, Hkv, d = 16, 8, 128
+    is_config2 = (B, L) == (8, 4096)
+    # rotate enough KV caches that no step finds its cache in the 256 MB Infinity Cache
+    NSETS = max(2, min(8, int(2.2e9 // (B * Hkv * L * d * 4))))
     sets = [synth.decode_inputs(B, Hq, Hkv, L, d, seed=1002 + 10 * i, device=dev) for i in range(NSETS)]
     S = plx.parallax_decode_num_splits(B, Hq, Hkv, L, d)
     ws = torch.empty(plx.parallax_decode_workspace_bytes(B, Hq, Hkv, L, d) // 4,
@@ -145,7 +151,7 @@ def main():
     achieved = step_bytes / (kern_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES["config2"],
+                "traffic": MEASURED_TRAFFIC_BYTES["config2"] if is_config2 else None,
                 "kernel": "decode_bf16_kernel<128,true,false>", "kernel_us": round(kern_us, 2),
                 "algorithmic_bytes_per_launch": step_bytes}
 
@@ -156,14 +162,15 @@ def main():
         "us_per_step_stream_events": round(step_us_events, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "config2: decode bf16 B=8 Hq=16 Hkv=8 d=128 L=4096, "
-                               "8 rotated KV caches (cache-cold)",
+        "config": {"workload": "%sdecode bf16 B=%d Hq=16 Hkv=8 d=128 L=%d, "
+                               "%d rotated KV caches (cache-cold)"
+                               % ("config2: " if is_config2 else "", B, L, NSETS),
                    "num_splits": S, "bytes_per_step": step_bytes},
         "roofline": roofline,
     }
 
     # ------------------------------------------------------------------ CPU oracle baseline
-    if not opt.no_cpu_baseline:
+    if not opt.no_cpu_baseline and is_config2:
         from oracle import parallax_oracle
 
         parallax_oracle.build()
@@ -190,7 +197,7 @@ def main():
         }
 
     # ------------------------------------------------------------------ extra lines
-    if not opt.no_extra:
+    if not opt.no_extra and is_config2:
         result["extra"] = extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out)
 
     print(json.dumps(result))
