@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--decode-shape", default="8,4096", metavar="B,L",
                     help="batch and KV length of the decode workload (default 8,4096 = config 2; "
                          "other shapes are for profiling the same kernels at larger sizes)")
+    ap.add_argument("--prefill-shape", default="4,4096", metavar="B,T",
+                    help="batch and length of the causal prefill workload (default 4,4096 = config 4)")
     ap.add_argument("--counter-mode", action="store_true",
                     help="short run for hardware-counter collection: 5 launches of the plain copy "
                          "kernel on 1 GiB (known size, calibrates FETCH_SIZE / WRITE_SIZE) and "
@@ -205,7 +207,9 @@ def main():
 
 def prefill_line(torch, plx, synth, dev, opt):
     """Config 4 on its own: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128."""
-    B, T, Hq, Hkv, d = 4, 4096, 16, 8, 128
+    B, T = (int(v) for v in opt.prefill_shape.split(","))
+    Hq, Hkv, d = 16, 8, 128
+    is_config4 = (B, T) == (4, 4096)
     y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1004, device=dev, k_offset_sigma=0.5)
     out = torch.empty_like(y["q"])
     steps = min(opt.steps, 50)
@@ -222,11 +226,12 @@ def prefill_line(torch, plx, synth, dev, opt):
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(us / 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "config4: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128, "
-                               "K offset N(0,0.5^2)", "algorithmic_flops": flops},
+        "config": {"workload": "%scausal prefill bf16 B=%d T=%d Hq=16 Hkv=8 d=128, "
+                               "K offset N(0,0.5^2)" % ("config4: " if is_config4 else "", B, T),
+                   "algorithmic_flops": flops},
         "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES["config4_prefill"],
+                     "traffic": MEASURED_TRAFFIC_BYTES["config4_prefill"] if is_config4 else None,
                      "kernel": "prefill_bf16_kernel<128,true,true>",
                      "kernel_us": round(us, 1)},
     }
