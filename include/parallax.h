@@ -122,11 +122,11 @@ plx_status parallax_decode(const plx_decode_args *args, void *hip_stream);
  * and one merge follows (App. C: the merge is an associative log-sum-exp rescale) -- and for
  * timing the two kernels separately.
  *   parallax_decode_partials: runs only the split kernel with S = num_splits (0 = heuristic) and
- *     ALWAYS writes the workspace, also for S = 1: record (b, hq, s) at float offset
- *     ((b*Hq + hq)*S + s)*(2d+4) holds m (exp2 domain, -inf if the split saw no key), d1, d2,
- *     pad, O1[d], O2[d], all unnormalised. args->o is not touched and may be NULL.
+ *     ALWAYS writes the workspace, also for S = 1: record (b, hq, t, s) at float offset
+ *     (((b*Hq + hq)*Tq + t)*S + s)*(2d+4) holds m (exp2 domain, -inf if the split saw no key),
+ *     d1, d2, pad, O1[d], O2[d], all unnormalised. args->o is not touched and may be NULL.
  *   parallax_decode_combine: merges the S = num_splits (>= 1, required) records per (b, hq) of
- *     the workspace and writes args->o. Only o, B, Hq, Hkv, d, num_splits, workspace,
+ *     the workspace and writes args->o. Only o, B, Hq, Hkv, d, Tq, num_splits, workspace,
  *     workspace_bytes and dtype are read.
  */
 plx_status parallax_decode_partials(const plx_decode_args *args, void *hip_stream);
