@@ -72,8 +72,25 @@ def find_violations(asm_text: str) -> list[str]:
     return bad
 
 
+def find_m0_uses_outside_inline_asm(asm_text: str) -> list[str]:
+    """The tile loads set M0 without restoring it, which is only valid while nothing the
+    compiler itself emits reads or writes M0: report every M0 reference outside the
+    hand-written assembly statements."""
+    bad, inside = [], False
+    for n, line in enumerate(asm_text.splitlines(), 1):
+        t = line.strip()
+        if t.startswith(";;#ASMSTART"):
+            inside = True
+        elif t.startswith(";;#ASMEND"):
+            inside = False
+        elif not inside and _is_instruction(line) and re.search(r"\bm0\b", t.split(";")[0]):
+            bad.append("line %d: compiler-generated use of M0: '%s'" % (n, t))
+    return bad
+
+
 def check_file(path: str) -> None:
     with open(path) as f:
-        bad = find_violations(f.read())
+        text = f.read()
+    bad = find_violations(text) + find_m0_uses_outside_inline_asm(text)
     if bad:
         raise RuntimeError("MFMA source hazard in %s:\n  %s" % (path, "\n  ".join(bad[:20])))

@@ -102,7 +102,8 @@ __device__ __forceinline__ void tile_load16(const void *gptr, uint32_t lds_byte_
 }
 // Same load with a wave-uniform tile base (scalar registers) plus a 32-bit per-lane byte offset:
 // no per-lane 64-bit address arithmetic. M0 is not restored: nothing the compiler emits for this
-// kernel reads M0 (no other LDS-DMA, no GWS / message / relative-index instructions).
+// kernel touches M0 (no other LDS-DMA, no GWS / message / relative-index instructions) -- the
+// build checks that on the generated assembly (asm_check.py).
 template <bool QUARTER = false>
 __device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, const void *tile_base,
                                                     uint32_t lds_byte_addr) {

@@ -32,3 +32,11 @@ def test_branch_target_just_before_is_flagged_and_marker_is_required():
     assert any("branch target" in b for b in asm_check.find_violations(asm))
     guarded = "\ts_nop 1\n\tv_mfma_f32_32x32x16_bf16 v[34:49], v[70:73], a[160:163], v[34:49]\n"
     assert any("no unguarded MFMA" in b for b in asm_check.find_violations(guarded))
+
+
+def test_m0_must_only_be_touched_by_the_inline_assembly():
+    ok = "\t;;#ASMSTART\n\ts_mov_b32 m0, s4\n\tglobal_load_lds_dwordx4 v1, s[2:3]\n\t;;#ASMEND\n\ts_add_i32 s1, s1, 1\n"
+    assert asm_check.find_m0_uses_outside_inline_asm(ok) == []
+    bad = ok + "\ts_mov_b32 m0, -1\n\tds_read_b32 v1, v2\n"
+    found = asm_check.find_m0_uses_outside_inline_asm(bad)
+    assert len(found) == 1 and "s_mov_b32 m0, -1" in found[0]
