@@ -272,7 +272,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
 
     const int row0 = rb * kBR + w * 32;  // first query row of this wave
     const int my_row = row0 + col;       // this lane's query row (may be >= T)
-    const int ld_qrow = min(my_row, T - 1);
 
     // ---- Q / R rows of this wave: global -> LDS, whole rows (a lane fetching its own MFMA
     // fragments straight from global memory would touch 64 different rows per instruction).
@@ -493,12 +492,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         }
     };
 
-    // does this wave see any key of the block starting at key_base / is every key visible?
+    // does this wave see any key of the block starting at key_base?
     auto block_visible = [&](int key_base) {
         return key_base < Tk && (!CAUSAL || key_base <= row0 + 31 + off);
-    };
-    auto block_full = [&](int key_base) {
-        return key_base + kKB <= Tk && (!CAUSAL || key_base + kKB - 1 <= row0 + off);
     };
 
     u32x4 pb1[2], pb2[2];
