@@ -247,6 +247,34 @@ def test_several_query_rows_other_paths(plx, synth, oracle):
         plx.parallax_decode(bad["q"], bad["r"], bad["k"], bad["v"], bad["scale"])
 
 
+def test_two_streams_with_their_own_workspaces(plx, synth):
+    """The library keeps no state: launches on different streams, each with its own workspace and
+    output, interleave freely and return what the same calls return alone."""
+    xs = [synth.decode_inputs(4, 16, 8, 6000, 128, seed=430 + i, device=DEV, ragged=True) for i in range(2)]
+    ys = [synth.prefill_inputs(1, 16, 8, 700, 128, seed=440 + i, device=DEV) for i in range(2)]
+    alone_d = [_run(plx, x, num_splits=8) for x in xs]
+    alone_p = [host(plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"])) for y in ys]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ws = [torch.empty(plx.parallax_decode_workspace_bytes(4, 16, 8, 6000, 128) // 4,
+                      dtype=torch.float32, device=DEV) for _ in range(2)]
+    out_d = [torch.empty_like(x["q"]) for x in xs]
+    out_p = [torch.empty_like(y["q"]) for y in ys]
+    for s_ in streams:
+        s_.wait_stream(torch.cuda.current_stream())
+    for rep in range(5):
+        for i, s_ in enumerate(streams):
+            plx.parallax_decode(xs[i]["q"], xs[i]["r"], xs[i]["k"], xs[i]["v"], xs[i]["scale"],
+                                seq_lens=xs[i]["seq_lens"], num_splits=8, workspace=ws[i],
+                                out=out_d[i], stream=s_)
+            plx.parallax_prefill(ys[i]["q"], ys[i]["r"], ys[i]["k"], ys[i]["v"], ys[i]["scale"],
+                                 out=out_p[i], stream=s_)
+    torch.cuda.synchronize()
+    for i in range(2):
+        np.testing.assert_array_equal(host(out_d[i]), alone_d[i])
+        np.testing.assert_array_equal(host(out_p[i]), alone_p[i])
+
+
 def test_hip_graph_replays_match_eager(plx, synth, oracle):
     """Decode and prefill captured in one HIP graph: every replay, with eager work and
     synchronisation in between and inputs changed in place, equals the eager result."""
