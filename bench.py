@@ -333,6 +333,59 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
     us = _time_events(torch, graph.replay, 5, 50) / len(g_args)
     extra["config2_hip_graph_replay_us_per_step"] = round(us, 2)
 
+    # config 2 with the merge inside the split kernel (one launch per step), interleaved with
+    # the two-kernel path so that both see the same clocks
+    counters = torch.zeros(64, dtype=torch.int32, device=dev)
+    f_args = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], out, x["scale"], None, True, 0, ws)
+              for x in x0]
+    for a in f_args:
+        a.split_counters = counters.data_ptr()
+    fc = [0]
+
+    def fused_step():
+        lib.parallax_decode_fused(ctypes.byref(f_args[fc[0] % len(f_args)]), sptr)
+        fc[0] += 1
+
+    def plain_step():
+        lib.parallax_decode(ctypes.byref(g_args[fc[0] % len(g_args)]), sptr)
+        fc[0] += 1
+
+    pair = [[], []]
+    for _ in range(3):
+        pair[0].append(_time_events(torch, plain_step, 20, 200))
+        pair[1].append(_time_events(torch, fused_step, 20, 200))
+    fused = {"config2": {"two_kernels_us": round(min(pair[0]), 2), "one_kernel_us": round(min(pair[1]), 2)}}
+    # ... and where the launch boundary weighs most (one sequence) or the merge is widest
+    # (several query rows: 8 merged rows per group)
+    for name, (B, L, Tq) in (("B1_L8192", (1, 8192, 1)), ("B4_L16384_Tq4", (4, 16384, 4))):
+        xs = [synth.decode_inputs(B, 16, 8, L, 128, seed=3300 + i, device=dev) for i in range(4)]
+        if Tq > 1:
+            qr = synth.prefill_inputs(B, 16, 8, Tq, 128, seed=3310, device=dev)
+            for x in xs:
+                x["q"], x["r"] = qr["q"].contiguous(), qr["r"].contiguous()
+        o2 = torch.empty_like(xs[0]["q"])
+        ws2 = torch.empty(plx.parallax_decode_workspace_bytes(B, 16 * Tq, 8, L, 128) // 4,
+                          dtype=torch.float32, device=dev)
+        s_args = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], o2, x["scale"], None, True, 0, ws2)
+                  for x in xs]
+        for a in s_args:
+            a.split_counters = counters.data_ptr()
+        sc = [0]
+
+        def step(entry):
+            st = entry(ctypes.byref(s_args[sc[0] % len(s_args)]), sptr)
+            sc[0] += 1
+            if st != 0:
+                raise plx.ParallaxError(st, "in-kernel reduction bench")
+
+        t2, t1 = [], []
+        for _ in range(3):
+            t2.append(_time_events(torch, lambda: step(lib.parallax_decode), 20, 200))
+            t1.append(_time_events(torch, lambda: step(lib.parallax_decode_fused), 20, 200))
+        fused[name] = {"two_kernels_us": round(min(t2), 2), "one_kernel_us": round(min(t1), 2)}
+        del xs, s_args, ws2
+    extra["in_kernel_reduction"] = fused
+
     # config 2 behind a block table (paged cache, shuffled page pool), 8 rotated pools
     paged = {}
     for page_size in (16, 128):

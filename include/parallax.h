@@ -103,6 +103,7 @@ typedef struct {
     const int32_t *block_table; /* NULL = contiguous cache */
     int32_t page_size, block_table_stride, num_pages;
     int32_t Tq; /* query rows per sequence; 0 or 1 = one */
+    int32_t *split_counters; /* parallax_decode_fused only: B*Hkv int32 on the device */
 } plx_decode_args;
 
 /* Bytes of workspace that is enough for any split count the library may pick or accept
@@ -131,6 +132,23 @@ plx_status parallax_decode(const plx_decode_args *args, void *hip_stream);
  */
 plx_status parallax_decode_partials(const plx_decode_args *args, void *hip_stream);
 plx_status parallax_decode_combine(const plx_decode_args *args, void *hip_stream);
+
+/*
+ * parallax_decode with the merge done inside the split kernel (the in-kernel reduction of
+ * App. C): every workgroup writes its record, bumps an arrival counter of its (batch, kv head)
+ * group, and the workgroup that arrives last merges the group's S records and writes o -- one
+ * launch instead of two, nobody waits. bf16 only; same arguments as parallax_decode, plus
+ *   split_counters  [B*Hkv] int32 on the device, 4-byte aligned. ALL ZERO when the call is
+ *                   enqueued; the kernel puts every counter back to zero before it ends, so the
+ *                   array is cleared once after allocation and then reused by later calls on the
+ *                   same stream (any shape that fits). Calls that may overlap on the device need
+ *                   counters (and workspaces) of their own. A launch that is aborted half-way
+ *                   leaves counters undefined: clear them again.
+ * The records are merged in the same order and with the same arithmetic as by
+ * parallax_decode_combine: o is bit-identical to parallax_decode's for the same num_splits.
+ * num_splits = 1 (given or picked) needs neither workspace nor counters.
+ */
+plx_status parallax_decode_fused(const plx_decode_args *args, void *hip_stream);
 
 /*
  * Prefill forward over T query rows and Tkv keys per sequence (Algorithm 1, Sec. 3.3; forward

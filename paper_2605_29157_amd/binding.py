@@ -21,7 +21,7 @@ PLX_MAX_SPLITS = 128
 
 EXPORTED_SYMBOLS = (
     "parallax_decode_workspace_bytes", "parallax_decode_num_splits", "parallax_decode",
-    "parallax_decode_partials", "parallax_decode_combine",
+    "parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused",
     "parallax_prefill", "parallax_util_copy", "parallax_util_read",
     "parallax_util_read_sink_slots", "parallax_strerror", "parallax_version",
 )
@@ -46,6 +46,7 @@ class plx_decode_args(ctypes.Structure):
         ("page_size", ctypes.c_int32), ("block_table_stride", ctypes.c_int32),
         ("num_pages", ctypes.c_int32),
         ("Tq", ctypes.c_int32),
+        ("split_counters", ctypes.c_void_p),
     ]
 
 
@@ -91,7 +92,7 @@ def load_library() -> ctypes.CDLL:
         lib.parallax_decode_num_splits.restype = ctypes.c_int32
         lib.parallax_decode.argtypes = [ctypes.POINTER(plx_decode_args), ctypes.c_void_p]
         lib.parallax_decode.restype = ctypes.c_int
-        for name in ("parallax_decode_partials", "parallax_decode_combine"):
+        for name in ("parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused"):
             getattr(lib, name).argtypes = [ctypes.POINTER(plx_decode_args), ctypes.c_void_p]
             getattr(lib, name).restype = ctypes.c_int
         lib.parallax_prefill.argtypes = [ctypes.POINTER(plx_prefill_args), ctypes.c_void_p]
@@ -177,9 +178,11 @@ def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0,
 
 
 def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None,
-                    out=None, stream=None, block_table=None, max_len=None):
+                    out=None, stream=None, block_table=None, max_len=None, split_counters=None):
     """Single-step Parallax decode. Allocates `out` / `workspace` with torch when not given
-    (allocation only; all arithmetic is in the library)."""
+    (allocation only; all arithmetic is in the library). With `split_counters` (zeroed int32
+    device tensor, >= B * Hkv entries) the call goes to parallax_decode_fused: one launch, the
+    last split of every group to arrive merges inside the kernel."""
     for t in (q, k, v) + ((r,) if r is not None else ()):
         if not t.is_cuda:
             raise ValueError("parallax_decode needs device tensors")
@@ -206,10 +209,22 @@ def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, 
                                     device=q.device)
     a = decode_args(q, r, k, v, out, scale, seq_lens, use_r, num_splits, workspace, block_table,
                     max_len)
-    st = load_library().parallax_decode(ctypes.byref(a), _stream_ptr(stream))
+    entry = "parallax_decode"
+    if split_counters is not None:
+        if (split_counters.dtype != torch.int32 or not split_counters.is_cuda
+                or not split_counters.is_contiguous() or split_counters.numel() < B * Hkv):
+            raise TypeError("split_counters must be a contiguous int32 device tensor, >= B * Hkv")
+        a.split_counters = split_counters.data_ptr()
+        entry = "parallax_decode_fused"
+    st = getattr(load_library(), entry)(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
-        raise ParallaxError(st, "parallax_decode")
+        raise ParallaxError(st, entry)
     return out
+
+
+def parallax_decode_fused(q, r, k, v, scale, split_counters, **kw):
+    """parallax_decode with the merge inside the split kernel; see parallax_decode."""
+    return parallax_decode(q, r, k, v, scale, split_counters=split_counters, **kw)
 
 
 def parallax_decode_partials(q, r, k, v, scale, num_splits, workspace, seq_lens=None, use_r=True,

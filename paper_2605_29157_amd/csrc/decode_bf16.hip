@@ -28,6 +28,122 @@ constexpr int kTileKeys = 32;  // keys per wave tile
 constexpr int kWaves = 4;      // waves per workgroup
 static_assert(kTileKeys * kWaves == kDecodeBlockKeys, "block tile = waves x wave tile");
 
+// Merge the S split partials of one (batch, query head, query row): m* = max_s m_s, weights
+// exp2(m_s - m*), then the closing formula of Algorithm 1 (App. C). 256 threads laid out as
+// [split lane][dimension lane x float4]: every thread folds the records s = split lane,
+// split lane + SL, ... into a private state with all loads of a trip issued together, then the SL
+// private states are merged through shared memory (MergeScratch). Deterministic: no float
+// atomics, a fixed order.
+struct MergeState {
+    float m, d1, d2;
+    f32x4 a1, a2;
+};
+
+__device__ __forceinline__ void merge_into(MergeState &st, float ms, float d1, float d2, f32x4 a1,
+                                           f32x4 a2) {
+    const float m_new = fmaxf(st.m, ms);
+    const float m_use = m_new == kNegInf ? 0.f : m_new;
+    const float w_old = fast_exp2(st.m - m_use);  // exp2(-inf) = 0 for an empty side
+    const float w_new = fast_exp2(ms - m_use);
+    st.m = m_new;
+    st.d1 = w_old * st.d1 + w_new * d1;
+    st.d2 = w_old * st.d2 + w_new * d2;
+    st.a1 = w_old * st.a1 + w_new * a1;
+    st.a2 = w_old * st.a2 + w_new * a2;
+}
+
+__device__ __forceinline__ void record_store(float *p, float x) {
+    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int D>
+struct MergeScratch {
+    static constexpr int DL = D / 4;     // lanes over the head dimension (float4 each)
+    static constexpr int SL = 256 / DL;  // lanes over splits
+    float hdr[SL][4];
+    f32x4 a1[SL][DL], a2[SL][DL];
+};
+
+// Four floats of a record. COHERENT: as device-scope atomic loads, which are served from the
+// point where the eight XCDs' private L2 caches agree -- for records that other workgroups of
+// the SAME launch wrote with record_store's device-scope stores.
+template <bool COHERENT>
+__device__ __forceinline__ f32x4 record_load4(const float *p) {
+    if constexpr (COHERENT) {
+        union { unsigned long long u[2]; f32x4 f; } x;
+        x.u[0] = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        x.u[1] = __hip_atomic_load((const unsigned long long *)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return x.f;
+    } else {
+        return *(const f32x4 *)p;
+    }
+}
+
+// Merges NROW output rows at once (their loads are all in flight together). rec0[i]: the S
+// records of row i; out_row[i]: its D bf16 outputs. All 256 threads take part (one
+// __syncthreads inside); sm holds NROW scratch areas.
+template <int D, bool COHERENT, int NROW>
+__device__ __forceinline__ void merge_records(const float *const (&rec0)[NROW], int S,
+                                              __bf16 *const (&out_row)[NROW], int tid,
+                                              MergeScratch<D> *sm) {
+    constexpr int DL = MergeScratch<D>::DL, SL = MergeScratch<D>::SL;
+    constexpr int REC = 2 * D + 4;
+    constexpr int U = NROW == 1 ? 4 : 2;  // records per thread and trip
+    const int sl = tid / DL, dl = tid % DL;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    MergeState st[NROW];
+#pragma unroll
+    for (int i = 0; i < NROW; ++i) st[i] = MergeState{kNegInf, 0.f, 0.f, zero, zero};
+    for (int base = 0; base < S; base += U * SL) {
+        f32x4 hdr[NROW][U], a1[NROW][U], a2[NROW][U];
+#pragma unroll
+        for (int i = 0; i < NROW; ++i)
+#pragma unroll
+            for (int u = 0; u < U; ++u) {  // issue every load of the trip before using any
+                const int s = base + u * SL + sl;
+                const bool ok = s < S;
+                const float *rec = rec0[i] + (int64_t)(ok ? s : 0) * REC;
+                hdr[i][u] = ok ? record_load4<COHERENT>(rec) : f32x4{kNegInf, 0.f, 0.f, 0.f};
+                a1[i][u] = ok ? record_load4<COHERENT>(rec + 4 + 4 * dl) : zero;
+                a2[i][u] = ok ? record_load4<COHERENT>(rec + 4 + D + 4 * dl) : zero;
+            }
+#pragma unroll
+        for (int i = 0; i < NROW; ++i)
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                merge_into(st[i], hdr[i][u][0], hdr[i][u][1], hdr[i][u][2], a1[i][u], a2[i][u]);
+    }
+#pragma unroll
+    for (int i = 0; i < NROW; ++i) {
+        if (dl == 0) {
+            sm[i].hdr[sl][0] = st[i].m;
+            sm[i].hdr[sl][1] = st[i].d1;
+            sm[i].hdr[sl][2] = st[i].d2;
+        }
+        sm[i].a1[sl][dl] = st[i].a1;
+        sm[i].a2[sl][dl] = st[i].a2;
+    }
+    __syncthreads();
+    if (sl < NROW) {  // split lane i finishes row i
+        const MergeScratch<D> &my = sm[sl];
+        MergeState tot{kNegInf, 0.f, 0.f, zero, zero};
+#pragma unroll
+        for (int j = 0; j < SL; ++j)
+            merge_into(tot, my.hdr[j][0], my.hdr[j][1], my.hdr[j][2], my.a1[j][dl], my.a2[j][dl]);
+        f32x4 out = zero;  // empty key set: zeros
+        if (tot.d1 > 0.f) {
+            const float inv = 1.f / tot.d1;
+            out = tot.a1 * (inv * (1.f + tot.d2 * inv)) - tot.a2 * inv;
+        }
+        const u32x2 packed = {pack_bf16(out[0], out[1]), pack_bf16(out[2], out[3])};
+        __bf16 *dst = out_row[0];
+#pragma unroll
+        for (int i = 1; i < NROW; ++i) dst = sl == i ? out_row[i] : dst;
+        *(u32x2 *)(dst + 4 * dl) = packed;
+    }
+}
+
 template <int D, bool USE_R, bool PAGED>
 __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
@@ -260,6 +376,7 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     }
     __syncthreads();
 
+    const bool fused = p.counters != nullptr;
     for (int idx = tid; idx < GC * D; idx += 256) {
         const int hh = idx / D, dim = idx - hh * D;  // hh: column (t, head)
         float m_star = kNegInf;
@@ -287,91 +404,79 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
             ((__bf16 *)p.o)[hq * D + dim] = (__bf16)out;
         } else {
             float *rec = p.ws + (hq * S + split) * (int64_t)(2 * D + 4);
-            if (dim == 0) {
-                rec[0] = m_star;
-                rec[1] = d1;
-                rec[2] = d2;
-                rec[3] = 0.f;
+            if (fused) {  // device-scope stores: written through to where every XCD sees them
+                if (dim == 0) {
+                    record_store(rec + 0, m_star);
+                    record_store(rec + 1, d1);
+                    record_store(rec + 2, d2);
+                    record_store(rec + 3, 0.f);
+                }
+                record_store(rec + 4 + dim, a1);
+                record_store(rec + 4 + D + dim, a2);
+            } else {
+                if (dim == 0) {
+                    rec[0] = m_star;
+                    rec[1] = d1;
+                    rec[2] = d2;
+                    rec[3] = 0.f;
+                }
+                rec[4 + dim] = a1;
+                rec[4 + D + dim] = a2;
             }
-            rec[4 + dim] = a1;
-            rec[4 + D + dim] = a2;
         }
     }
-}
 
-// Merge the S split partials of one (batch, query head): m* = max_s m_s, weights
-// exp2(m_s - m*), then the closing formula of Algorithm 1. One workgroup per (b, hq), threads
-// laid out as [split lane][dimension lane x float4]: every thread folds the records
-// s = split lane, split lane + SL, ... into a private state with all loads of a trip issued
-// together, then the SL private states are merged through LDS.
-struct MergeState {
-    float m, d1, d2;
-    f32x4 a1, a2;
-};
-
-__device__ __forceinline__ void merge_into(MergeState &st, float ms, float d1, float d2, f32x4 a1,
-                                           f32x4 a2) {
-    const float m_new = fmaxf(st.m, ms);
-    const float m_use = m_new == kNegInf ? 0.f : m_new;
-    const float w_old = fast_exp2(st.m - m_use);  // exp2(-inf) = 0 for an empty side
-    const float w_new = fast_exp2(ms - m_use);
-    st.m = m_new;
-    st.d1 = w_old * st.d1 + w_new * d1;
-    st.d2 = w_old * st.d2 + w_new * d2;
-    st.a1 = w_old * st.a1 + w_new * a1;
-    st.a2 = w_old * st.a2 + w_new * a2;
+    // ---- in-kernel reduction (App. C): the last split of a (batch, kv head) group to arrive
+    // merges the group's records itself; nobody waits on anybody. The XCDs have private L2
+    // caches, and a device-scope release / acquire fence pair would write back and invalidate a
+    // whole L2 per workgroup (measured: the step takes four times as long). Instead only the
+    // records travel at device scope: written with device-scope stores above, which the barrier
+    // below waits for (it drains the wave's outstanding stores) before the group's arrival
+    // counter is bumped with a device-scope atomic, and read back with device-scope loads by
+    // the workgroup that reads S - 1. That one also puts the counter back to zero for the next
+    // launch.
+    if (fused) {
+        __shared__ int is_last;
+        __syncthreads();
+        if (tid == 0) {
+            const int arrived = __hip_atomic_fetch_add(p.counters + (int64_t)b * p.Hkv + hk, 1,
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = arrived == S - 1;
+        }
+        __syncthreads();
+        if (is_last) {
+            MergeScratch<D> *sm = reinterpret_cast<MergeScratch<D> *>(lds);
+            auto row_of = [&](int cc) {  // output / workspace row of column cc = (t, head)
+                const int ot = cc / G, oh = cc - ot * G;
+                return ((int64_t)b * p.Hq + (int64_t)hk * G + oh) * Tq + ot;
+            };
+            constexpr int64_t REC = 2 * D + 4;
+            int cc = 0;
+            for (; cc + 2 <= GC; cc += 2) {  // two rows at a time: their loads overlap
+                const int64_t h0 = row_of(cc), h1 = row_of(cc + 1);
+                const float *const recs[2] = {p.ws + h0 * S * REC, p.ws + h1 * S * REC};
+                __bf16 *const outs[2] = {(__bf16 *)p.o + h0 * D, (__bf16 *)p.o + h1 * D};
+                merge_records<D, true, 2>(recs, S, outs, tid, sm);
+                __syncthreads();  // the scratch is reused by the next rows
+            }
+            if (cc < GC) {
+                const int64_t h0 = row_of(cc);
+                const float *const recs[1] = {p.ws + h0 * S * REC};
+                __bf16 *const outs[1] = {(__bf16 *)p.o + h0 * D};
+                merge_records<D, true, 1>(recs, S, outs, tid, sm);
+            }
+            if (tid == 0) p.counters[(int64_t)b * p.Hkv + hk] = 0;
+        }
+    }
 }
 
 template <int D>
 __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
-    constexpr int DL = D / 4;     // lanes over the head dimension (float4 each)
-    constexpr int SL = 256 / DL;  // lanes over splits
-    constexpr int REC = 2 * D + 4;
-    __shared__ float sm_hdr[SL][4];
-    __shared__ f32x4 sm_a1[SL][DL], sm_a2[SL][DL];
-
-    const int tid = threadIdx.x, sl = tid / DL, dl = tid % DL;
+    __shared__ MergeScratch<D> sm;
     const int64_t hq = (int64_t)blockIdx.y * p.Hq * p.Tq + blockIdx.x;  // (batch, head, query row)
-    const int S = p.S;
-    const float *rec0 = p.ws + hq * S * (int64_t)REC;
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-
-    MergeState st{kNegInf, 0.f, 0.f, zero, zero};
-    for (int base = 0; base < S; base += 4 * SL) {
-        f32x4 hdr[4], a1[4], a2[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {  // issue every load of the trip before using any
-            const int s = base + u * SL + sl;
-            const bool ok = s < S;
-            const float *rec = rec0 + (int64_t)(ok ? s : 0) * REC;
-            hdr[u] = ok ? *(const f32x4 *)rec : f32x4{kNegInf, 0.f, 0.f, 0.f};
-            a1[u] = ok ? *(const f32x4 *)(rec + 4 + 4 * dl) : zero;
-            a2[u] = ok ? *(const f32x4 *)(rec + 4 + D + 4 * dl) : zero;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) merge_into(st, hdr[u][0], hdr[u][1], hdr[u][2], a1[u], a2[u]);
-    }
-    if (dl == 0) {
-        sm_hdr[sl][0] = st.m;
-        sm_hdr[sl][1] = st.d1;
-        sm_hdr[sl][2] = st.d2;
-    }
-    sm_a1[sl][dl] = st.a1;
-    sm_a2[sl][dl] = st.a2;
-    __syncthreads();
-    if (sl == 0) {
-        MergeState tot{kNegInf, 0.f, 0.f, zero, zero};
-#pragma unroll
-        for (int j = 0; j < SL; ++j)
-            merge_into(tot, sm_hdr[j][0], sm_hdr[j][1], sm_hdr[j][2], sm_a1[j][dl], sm_a2[j][dl]);
-        f32x4 out = zero;  // empty key set: zeros
-        if (tot.d1 > 0.f) {
-            const float inv = 1.f / tot.d1;
-            out = tot.a1 * (inv * (1.f + tot.d2 * inv)) - tot.a2 * inv;
-        }
-        const u32x2 packed = {pack_bf16(out[0], out[1]), pack_bf16(out[2], out[3])};
-        *(u32x2 *)((__bf16 *)p.o + hq * D + 4 * dl) = packed;
-    }
+    const float *const recs[1] = {p.ws + hq * p.S * (int64_t)(2 * D + 4)};
+    __bf16 *const outs[1] = {(__bf16 *)p.o + hq * D};
+    merge_records<D, false, 1>(recs, p.S, outs, threadIdx.x, &sm);
 }
 
 template <int D, bool USE_R>

@@ -172,6 +172,27 @@ plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
     return PLX_OK;
 }
 
+plx_status parallax_decode_fused(const plx_decode_args *a, void *hip_stream) {
+    plx::DecodeParams p{};
+    plx_status st = prepare_decode(a, true, true, &p);
+    if (st != PLX_OK) return st;
+    if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
+    int32_t S = a->num_splits;
+    if (S == 0) S = parallax_decode_num_splits(a->B, a->Hq, a->Hkv, a->Lmax, a->d, 0);
+    p.S = S;
+    p.direct_out = S == 1;
+    if (S > 1) {
+        st = attach_workspace(a, S, &p);
+        if (st != PLX_OK) return st;
+        if (!a->split_counters || (reinterpret_cast<uintptr_t>(a->split_counters) & 3u))
+            return PLX_ERR_WORKSPACE;
+        p.counters = a->split_counters;
+    }
+    return plx::launch_decode_bf16(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
+}
+
 plx_status parallax_decode_partials(const plx_decode_args *a, void *hip_stream) {
     plx::DecodeParams p{};
     plx_status st = prepare_decode(a, true, false, &p);

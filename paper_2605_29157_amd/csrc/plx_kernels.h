@@ -22,6 +22,7 @@ struct DecodeParams {
     // block_table[b * table_stride + j / page_size]; ksb / vsb are then the page strides
     const int32_t *block_table;
     int32_t page_size, table_stride, num_pages;
+    int32_t *counters;  // in-kernel reduction: one arrival counter per (batch, kv head), zero on entry
     int32_t Tq;  // query rows per sequence (>= 1): the last Tq positions; q, r, o are [B, Hq, Tq, d]
 };
 

@@ -38,8 +38,8 @@ def test_header_symbols_are_exported(binding):
 
 def test_struct_sizes_match_c_layout(binding):
     # 6 pointers, 5 int32 (+pad), 6 int64, float + 2 int32 (+pad), pointer, size_t, enum (+pad),
-    # pointer, 3 int32 (+pad)
-    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16
+    # pointer, 4 int32, pointer
+    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16 + 8
     # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, int32 (+pad)
     assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8
 
@@ -123,6 +123,15 @@ def test_decode_rejects_bad_arguments_before_launch(binding):
     a = _good_decode_args(binding); a.num_splits = 4
     a.workspace, a.workspace_bytes = 0x2000, 16
     assert call(a) == binding.PLX_ERR_WORKSPACE
+    # in-kernel reduction: needs bf16, and workspace + counters as soon as there are splits
+    fused = lib.parallax_decode_fused
+    a = _good_decode_args(binding); a.num_splits = 4
+    a.workspace, a.workspace_bytes = 0x2000, 1 << 30
+    assert fused(ctypes.byref(a), None) == binding.PLX_ERR_WORKSPACE   # no counters
+    a.split_counters = 0x4002
+    assert fused(ctypes.byref(a), None) == binding.PLX_ERR_WORKSPACE   # misaligned counters
+    a = _good_decode_args(binding); a.dtype = binding.PLX_F32
+    assert fused(ctypes.byref(a), None) == binding.PLX_ERR_DTYPE
     # paged cache descriptors
     def paged():
         a = _good_decode_args(binding)
