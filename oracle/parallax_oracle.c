@@ -19,6 +19,11 @@
  * positions of the sequence (chunked prefill), so row i sits at position i + (Lk - Tq) and
  * sees j <= i + (Lk - Tq); Tq == Lk is the paper's square case j <= i.
  * Otherwise j < len_b, with len_b = seq_lens[b] or Lk when seq_lens is NULL.
+ * Sliding window (one of the sparsity patterns Sec. 5 says carry over from softmax attention;
+ * the paper gives no formula, the usual one is taken): with window W > 0 a query at position
+ * pos sees only the W positions pos - W + 1 .. pos, i.e. of its n allowed keys the last
+ * min(n, W). Defined where the query's position is: causal, or a single query row (decode,
+ * position len_b - 1).
  * GQA: query head h reads KV head h / (Hq/Hkv); R is shaped and grouped like Q (App. E).
  *
  * No tiling, no online softmax, no fusion: three plain passes per row. Only tests,
@@ -79,18 +84,20 @@ static void plx_row(const double *q, const double *rho, const double *kmat, cons
  * Full evaluation on double inputs.
  *   q, r : [B][Hq][Tq][d]      k, v : [B][Hkv][Lk][d]      o : [B][Hq][Tq][d]
  *   causal != 0 requires Tq <= Lk; seq_lens ([B], may be NULL) is ignored when causal.
+ *   window: 0 = none; W > 0 keeps the last W allowed keys of every row (causal or Tq == 1 only).
  *   rows: optional list of n_rows triples (b, h, i); when NULL every row is computed.
  *   For a row list, o is [n_rows][d].
  * Returns 0, or -1 on a bad argument.
  */
 int plx_oracle_f64(const double *q, const double *r, const double *k, const double *v, double *o,
                    int B, int Hq, int Hkv, int Tq, int Lk, int d, double scale, int causal,
-                   const int32_t *seq_lens, const int32_t *rows, int64_t n_rows)
+                   const int32_t *seq_lens, const int32_t *rows, int64_t n_rows, int window)
 {
     if (!q || !r || !k || !v || !o) return -1;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Tq <= 0 || Lk <= 0 || d <= 0) return -1;
     if (Hq % Hkv != 0) return -1;
     if (causal && Tq > Lk) return -1;
+    if (window < 0 || (window > 0 && !causal && Tq != 1)) return -1;
     const int G = Hq / Hkv;
     const int64_t total = rows ? n_rows : (int64_t)B * Hq * Tq;
 
@@ -117,12 +124,13 @@ int plx_oracle_f64(const double *q, const double *r, const double *k, const doub
             else
                 n_keys = seq_lens ? seq_lens[b] : Lk;
             if (n_keys > Lk) n_keys = Lk;
+            const int64_t first = (window > 0 && n_keys > window) ? n_keys - window : 0;
             const double *qi = q + (((int64_t)b * Hq + h) * Tq + i) * d;
             const double *ri = r + (((int64_t)b * Hq + h) * Tq + i) * d;
             const double *kb = k + ((int64_t)b * Hkv + hk) * (int64_t)Lk * d;
             const double *vb = v + ((int64_t)b * Hkv + hk) * (int64_t)Lk * d;
             double *oi = rows ? o + t * d : o + (((int64_t)b * Hq + h) * Tq + i) * d;
-            plx_row(qi, ri, kb, vb, n_keys, d, scale, oi, a, u);
+            plx_row(qi, ri, kb + first * d, vb + first * d, n_keys - first, d, scale, oi, a, u);
         }
         free(a);
         free(u);
@@ -138,12 +146,13 @@ int plx_oracle_f64(const double *q, const double *r, const double *k, const doub
  */
 int plx_oracle_f32in(const float *q, const float *r, const float *k, const float *v, double *o,
                      int B, int Hq, int Hkv, int Tq, int Lk, int d, double scale, int causal,
-                     const int32_t *seq_lens, const int32_t *rows, int64_t n_rows)
+                     const int32_t *seq_lens, const int32_t *rows, int64_t n_rows, int window)
 {
     if (!q || !r || !k || !v || !o) return -1;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Tq <= 0 || Lk <= 0 || d <= 0) return -1;
     if (Hq % Hkv != 0) return -1;
     if (causal && Tq > Lk) return -1;
+    if (window < 0 || (window > 0 && !causal && Tq != 1)) return -1;
     const int G = Hq / Hkv;
     const int64_t slab = (int64_t)Lk * d;
     double *kd = (double *)malloc(sizeof(double) * (size_t)slab);
@@ -197,6 +206,7 @@ int plx_oracle_f32in(const float *q, const float *r, const float *k, const float
                     else
                         n_keys = seq_lens ? seq_lens[b] : Lk;
                     if (n_keys > Lk) n_keys = Lk;
+                    const int64_t first = (window > 0 && n_keys > window) ? n_keys - window : 0;
                     const float *qi = q + (((int64_t)b * Hq + h) * Tq + i) * d;
                     const float *ri = r + (((int64_t)b * Hq + h) * Tq + i) * d;
                     for (int c = 0; c < d; ++c) {
@@ -204,7 +214,8 @@ int plx_oracle_f32in(const float *q, const float *r, const float *k, const float
                         rd[c] = (double)ri[c];
                     }
                     double *oi = rows ? o + t * d : o + (((int64_t)b * Hq + h) * Tq + i) * d;
-                    plx_row(qd, rd, kd, vd, n_keys, d, scale, oi, a, u);
+                    plx_row(qd, rd, kd + first * d, vd + first * d, n_keys - first, d, scale, oi,
+                            a, u);
                 }
                 free(a);
                 free(u);

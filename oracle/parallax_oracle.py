@@ -34,7 +34,7 @@ def _bind(path):
     """Load an oracle library (the built one, or a mutant a test compiled) and type it."""
     lib = ctypes.CDLL(path)
     common = [ctypes.c_int] * 6 + [ctypes.c_double, ctypes.c_int, ctypes.c_void_p,
-                                   ctypes.c_void_p, ctypes.c_int64]
+                                   ctypes.c_void_p, ctypes.c_int64, ctypes.c_int]
     lib.plx_oracle_f64.argtypes = [ctypes.c_void_p] * 5 + common
     lib.plx_oracle_f64.restype = ctypes.c_int
     lib.plx_oracle_f32in.argtypes = [ctypes.c_void_p] * 5 + common
@@ -56,13 +56,16 @@ def num_threads() -> int:
     return int(_load().plx_oracle_num_threads())
 
 
-def forward(q, r, k, v, scale, causal=False, seq_lens=None, rows=None, _lib_override=None):
+def forward(q, r, k, v, scale, causal=False, seq_lens=None, rows=None, _lib_override=None,
+            window=0):
     """Parallax forward by the plain definition.
 
     q, r : [B, Hq, Tq, d]; k, v : [B, Hkv, Lk, d]; all float64 or all float32 numpy arrays
     (float32 holds bf16/fp32 inputs exactly; it is widened to double before any arithmetic).
     causal : key j allowed iff j <= i + (Lk - Tq) (queries are the last Tq positions; needs
              Tq <= Lk; the square case is j <= i); else j < seq_lens[b] (default Lk).
+    window : 0 = none; W > 0: a row sees only the last W of its allowed keys (the query's own
+             position and the W - 1 before it); causal or Tq == 1 only.
     rows : optional int array [n, 3] of (b, h, i); then the result is [n, d].
     Returns float64.
     """
@@ -88,7 +91,7 @@ def forward(q, r, k, v, scale, causal=False, seq_lens=None, rows=None, _lib_over
     rc = fn(q.ctypes.data, r.ctypes.data, k.ctypes.data, v.ctypes.data, out.ctypes.data,
             B, Hq, Hkv, Tq, Lk, d, float(scale), int(bool(causal)),
             sl.ctypes.data if sl is not None else None,
-            rows.ctypes.data if rows is not None else None, n_rows)
+            rows.ctypes.data if rows is not None else None, n_rows, int(window))
     if rc != 0:
         raise ValueError("parallax oracle rejected its arguments (rc=%d)" % rc)
     return out

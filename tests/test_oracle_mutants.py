@@ -19,6 +19,10 @@ MUTANTS = {
                                  "n_keys = (int64_t)i + (Lk - Tq);"),
     "causal_chunk_top_left_aligned": ("n_keys = (int64_t)i + 1 + (Lk - Tq);",
                                       "n_keys = (int64_t)i + 1;"),
+    "window_one_key_too_many": ("n_keys > window) ? n_keys - window : 0;",
+                                "n_keys > window) ? n_keys - window - 1 : 0;"),
+    "window_counted_from_the_start": ("kb + first * d, vb + first * d, n_keys - first,",
+                                      "kb, vb, n_keys - first,"),
     "gqa_modulo": ("const int hk = h / G;", "const int hk = h % Hkv;"),
     "no_max_subtraction_no_norm": ("a[j] /= omega;", "a[j] /= 1.0;"),
 }
@@ -59,6 +63,18 @@ def _pins(fwd):
     one = fwd(q[:, :, -1:], r[:, :, -1:], k, v, 0.5, causal=True)
     if np.abs(one - fwd(q[:, :, -1:], r[:, :, -1:], k, v, 0.5)).max() > 1e-12:
         failed.append("chunk_alignment")
+    # sliding window of one position returns the value row at the query's own position, and a
+    # window of two is the two-key closed form on the last two allowed keys
+    w1 = fwd(q, r, k, v, 0.5, causal=True, window=1)
+    if np.abs(w1 - np.repeat(v, 2, axis=1)).max() > 1e-12:
+        failed.append("window_one")
+    w2 = fwd(q[:, :1, -1:], r[:, :1, -1:], k[:, :1], v[:, :1], 0.5, causal=True, window=2)[0, 0, 0]
+    k2, v2 = k[0, 0, -2:], v[0, 0, -2:]
+    a = 0.5 * (k2 @ q[0, 0, -1])
+    p = 1.0 / (1.0 + np.exp(a[1] - a[0]))
+    ref = p * v2[0] + (1 - p) * v2[1] - p * (1 - p) * (v2[0] - v2[1]) * ((k2[0] - k2[1]) @ r[0, 0, -1])
+    if np.abs(w2 - ref).max() > 1e-10:
+        failed.append("window_two")
     return failed
 
 

@@ -36,7 +36,7 @@ def test_hand_worked_two_key_example(oracle):
 
 
 # ---- P1: brute force with explicit weight matrices (Sec. 4.4, s_ij) -----------------------
-def _brute(q, r, k, v, scale, causal, seq_lens=None):
+def _brute(q, r, k, v, scale, causal, seq_lens=None, window=0):
     B, Hq, Tq, d = q.shape
     _, Hkv, Lk, _ = k.shape
     G = Hq // Hkv
@@ -51,6 +51,10 @@ def _brute(q, r, k, v, scale, causal, seq_lens=None):
                 mask = np.tril(mask, k=Lk - Tq)  # row i is position i + Lk - Tq
             elif seq_lens is not None:
                 mask[:, seq_lens[b]:] = False
+            if window:  # position of row i minus key position < window
+                n_b = Lk if causal or seq_lens is None else int(seq_lens[b])
+                pos = np.arange(Tq)[:, None] + (n_b - Tq)
+                mask &= pos - np.arange(Lk)[None, :] < window
             A = np.where(mask, A, -np.inf)
             P = np.exp(A - A.max(axis=1, keepdims=True))
             P = P / P.sum(axis=1, keepdims=True)
@@ -105,6 +109,44 @@ def test_chunked_causal_is_the_tail_of_the_square_case(oracle):
                                rtol=1e-10, atol=1e-10)
     with pytest.raises(ValueError):
         oracle.forward(q, r, k[:, :, :L - 1], v[:, :, :L - 1], 0.41, causal=True)  # Tq > Lk
+
+
+@pytest.mark.parametrize("window", [1, 2, 3, 5, 12, 13, 40])
+def test_sliding_window_brute_force_and_special_cases(oracle, window):
+    """Sliding window (the usual definition: a query at position pos sees positions
+    pos - W + 1 .. pos): explicit band mask; W = 1 returns the value row at the query's own
+    position; W >= the sequence is no window; a windowed row equals the unwindowed problem on
+    the slice of keys it sees; decode rows take the window from their own length."""
+    B, Hq, Hkv, L, d, Tq = 2, 4, 2, 13, 5, 6
+    q, r = _rand((B, Hq, Tq, d), 41), _rand((B, Hq, Tq, d), 42)
+    k, v = _rand((B, Hkv, L, d), 43), _rand((B, Hkv, L, d), 44)
+    out = oracle.forward(q, r, k, v, 0.43, causal=True, window=window)
+    ref, W = _brute(q, r, k, v, 0.43, True, window=window)
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-12)
+    # exactly min(window, position + 1) non-zero weights per row, ending on the diagonal
+    for i in range(Tq):
+        pos = i + L - Tq
+        nz = np.nonzero(W[0, 0, i])[0]
+        assert nz.max() == pos and nz.min() == max(0, pos - window + 1)
+    if window == 1:
+        np.testing.assert_allclose(out, np.repeat(v[:, :, L - Tq:], 2, axis=1), atol=1e-14)
+    if window >= L:
+        np.testing.assert_array_equal(out, oracle.forward(q, r, k, v, 0.43, causal=True))
+    # row i alone, over exactly the keys it sees, with no mask at all
+    i = 3
+    pos = i + L - Tq
+    lo = max(0, pos - window + 1)
+    alone = oracle.forward(q[:, :, i:i + 1], r[:, :, i:i + 1], k[:, :, lo:pos + 1], v[:, :, lo:pos + 1], 0.43)
+    np.testing.assert_allclose(out[:, :, i:i + 1], alone, rtol=1e-13, atol=1e-13)
+    # decode: one query row per sequence at position len_b - 1
+    lens = np.array([13, 4], dtype=np.int32)
+    dec = oracle.forward(q[:, :, :1], r[:, :, :1], k, v, 0.43, seq_lens=lens, window=window)
+    refd, Wd = _brute(q[:, :, :1], r[:, :, :1], k, v, 0.43, False, lens, window=window)
+    np.testing.assert_allclose(dec, refd, rtol=1e-12, atol=1e-12)
+    assert np.count_nonzero(Wd[1, 0, 0]) == min(window, 4)
+    # several rows without a position (not causal) have no window
+    with pytest.raises(ValueError):
+        oracle.forward(q, r, k, v, 0.43, window=window)
 
 
 def test_brute_force_ragged_decode_and_gqa(oracle):
