@@ -510,6 +510,45 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
                      "kv_GBps": round(B * Hkv * Tkv * d * 4 / us / 1e3, 1)})
         del y, po, qc, rc
     extra["prefill_more"] = more
+
+    # sliding window (a row sees its own position and the window - 1 before it)
+    win = []
+    for (B, T, W) in [(2, 16384, 4096), (2, 16384, 1024)]:
+        Hq, Hkv, d = 16, 8, 128
+        y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1007, device=dev)
+        po = torch.empty_like(y["q"])
+        us = _time_events(
+            torch, lambda: plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"],
+                                                causal=True, out=po, window=W), 2, 10)
+        pairs = W * (W + 1) / 2 + (T - W) * W  # allowed (row, key) pairs per head
+        flops = B * Hq * 8 * d * pairs
+        win.append({"workload": "causal prefill B=%d T=%d window=%d d=128" % (B, T, W),
+                    "us": round(us, 1), "TFLOPs": round(flops / us / 1e6, 1),
+                    "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
+        del y, po
+    for (B, L, W) in [(16, 65536, 4096), (16, 4096, 0)]:
+        Hq, Hkv, d = 16, 8, 128
+        xs = [synth.decode_inputs(B, Hq, Hkv, L, d, seed=1008 + i, device=dev)
+              for i in range(2 if L > 4096 else 8)]
+        o2 = torch.empty_like(xs[0]["q"])
+        ws2 = torch.empty(plx.parallax_decode_workspace_bytes(B, Hq, Hkv, L, d) // 4,
+                          dtype=torch.float32, device=dev)
+        w_args = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], o2, x["scale"], None, True, 0, ws2,
+                                  window=W) for x in xs]
+        wc = [0]
+
+        def wstep():
+            st = lib.parallax_decode(ctypes.byref(w_args[wc[0] % len(w_args)]), sptr)
+            wc[0] += 1
+            if st != 0:
+                raise plx.ParallaxError(st, "window bench")
+
+        us = _time_events(torch, wstep, 20, 200)
+        keys = min(L, W) if W else L
+        win.append({"workload": "decode B=%d L=%d window=%d d=128" % (B, L, W), "us": round(us, 2),
+                    "kv_GBps_of_keys_in_window": round(B * Hkv * keys * d * 4 / us / 1e3, 1)})
+        del xs, w_args, ws2
+    extra["sliding_window"] = win
     return extra
 
 

@@ -85,6 +85,12 @@ typedef enum {
  * j % page_size. block_table is int32 on the device; page_size >= 1;
  * block_table_stride * page_size >= Lmax. Entries are clamped to [0, num_pages) before use but
  * not otherwise checked. Lmax is the largest logical length (seq_lens bounds each sequence).
+ *
+ * Sliding window (window > 0; one of the sparsity patterns that Sec. 5 says carry over from
+ * softmax attention -- the paper gives no formula, the usual one is taken): a query row at
+ * position pos sees only the keys pos - window + 1 .. pos. The one decode row sits at position
+ * L_b - 1 (row t of Tq at L_b - Tq + t). Key tiles outside the window are neither read nor
+ * computed. 0 = no window.
  */
 typedef struct {
     const void *q, *r;
@@ -103,6 +109,7 @@ typedef struct {
     const int32_t *block_table; /* NULL = contiguous cache */
     int32_t page_size, block_table_stride, num_pages;
     int32_t Tq; /* query rows per sequence; 0 or 1 = one */
+    int32_t window; /* sliding window in keys; 0 = none */
     int32_t *split_counters; /* parallax_decode_fused only: B*Hkv int32 on the device */
 } plx_decode_args;
 
@@ -157,6 +164,9 @@ plx_status parallax_decode_fused(const plx_decode_args *args, void *hip_stream);
  * chunk behind an existing cache, or a few speculative rows): key j allowed iff
  * j <= i + (Tkv - T), diagonal included -- for Tkv = T that is j <= i and row 0 returns v_0.
  * Needs Tkv >= T. causal == 0: every key.
+ * window > 0 (causal only): sliding window as for decode -- row i sees the keys
+ * i + (Tkv - T) - window + 1 .. i + (Tkv - T); key tiles left of a row block's window are
+ * skipped.
  *
  *   q, r, o   [B, Hq, T, d]    k, v  [B, Hkv, Tkv, d]
  *   *_stride  element strides {batch, head, row}; last dim contiguous
@@ -172,6 +182,7 @@ typedef struct {
     int32_t use_r;
     plx_dtype dtype;
     int32_t Tkv; /* keys per sequence; 0 = T */
+    int32_t window; /* sliding window in keys (needs causal); 0 = none */
 } plx_prefill_args;
 
 plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);

@@ -46,6 +46,7 @@ class plx_decode_args(ctypes.Structure):
         ("page_size", ctypes.c_int32), ("block_table_stride", ctypes.c_int32),
         ("num_pages", ctypes.c_int32),
         ("Tq", ctypes.c_int32),
+        ("window", ctypes.c_int32),
         ("split_counters", ctypes.c_void_p),
     ]
 
@@ -65,6 +66,7 @@ class plx_prefill_args(ctypes.Structure):
         ("use_r", ctypes.c_int32),
         ("dtype", ctypes.c_int),
         ("Tkv", ctypes.c_int32),
+        ("window", ctypes.c_int32),
     ]
 
 
@@ -144,7 +146,7 @@ def parallax_decode_num_splits(B, Hq, Hkv, Lmax, d, num_cus=0) -> int:
 
 
 def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None,
-                block_table=None, max_len=None):
+                block_table=None, max_len=None, window=0):
     """Fill a plx_decode_args from tensors: q, r, out [B, Hq, d]; k, v [B, Hkv, Lmax, d], or,
     with block_table [B, pages per sequence] (int32), page pools [num_pages, Hkv, page_size, d]
     (max_len = largest logical length, default: pages per sequence x page_size).
@@ -171,6 +173,7 @@ def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0,
         a.workspace_bytes = workspace.numel() * workspace.element_size()
     a.dtype = _dtype_code(q)
     a.Tq = Tq
+    a.window = int(window)
     if block_table is not None:
         a.block_table = block_table.data_ptr()
         a.page_size, a.block_table_stride, a.num_pages = k.shape[2], block_table.stride(0), k.shape[0]
@@ -178,7 +181,8 @@ def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0,
 
 
 def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None,
-                    out=None, stream=None, block_table=None, max_len=None, split_counters=None):
+                    out=None, stream=None, block_table=None, max_len=None, split_counters=None,
+                    window=0):
     """Single-step Parallax decode. Allocates `out` / `workspace` with torch when not given
     (allocation only; all arithmetic is in the library). With `split_counters` (zeroed int32
     device tensor, >= B * Hkv entries) the call goes to parallax_decode_fused: one launch, the
@@ -203,12 +207,13 @@ def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, 
     if out is None:
         out = torch.empty_like(q)
     if workspace is None and num_splits != 1 and q.dtype == torch.bfloat16:
+        # (with a window the library may pick fewer splits than for Lmax, never more)
         S = num_splits or parallax_decode_num_splits(B, Hq, Hkv, Lmax, d)
         if S > 1:
             workspace = torch.empty(B * Hq * Tq * S * (2 * d + 4), dtype=torch.float32,
                                     device=q.device)
     a = decode_args(q, r, k, v, out, scale, seq_lens, use_r, num_splits, workspace, block_table,
-                    max_len)
+                    max_len, window)
     entry = "parallax_decode"
     if split_counters is not None:
         if (split_counters.dtype != torch.int32 or not split_counters.is_cuda
@@ -254,7 +259,7 @@ def parallax_decode_combine(workspace, out, Hkv, num_splits, stream=None):
     return out
 
 
-def prefill_args(q, r, k, v, out, scale, causal=True, use_r=True):
+def prefill_args(q, r, k, v, out, scale, causal=True, use_r=True, window=0):
     """Fill a plx_prefill_args from tensors: q, r, out [B, Hq, T, d]; k, v [B, Hkv, Tkv, d]."""
     B, Hq, T, d = q.shape
     Hkv, Tkv = k.shape[1], k.shape[2]
@@ -270,10 +275,11 @@ def prefill_args(q, r, k, v, out, scale, causal=True, use_r=True):
     a.use_r = 1 if use_r else 0
     a.dtype = _dtype_code(q)
     a.Tkv = Tkv
+    a.window = int(window)
     return a
 
 
-def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None):
+def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None, window=0):
     """Parallax prefill forward over T query rows and Tkv keys (causal: the rows are the last
     T positions of the Tkv-long sequence)."""
     for t in (q, k, v) + ((r,) if r is not None else ()):
@@ -285,7 +291,7 @@ def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, strea
         raise ValueError("k and v must hold the same number of keys")
     if out is None:
         out = torch.empty_like(q)
-    a = prefill_args(q, r, k, v, out, scale, causal, use_r)
+    a = prefill_args(q, r, k, v, out, scale, causal, use_r, window)
     st = load_library().parallax_prefill(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_prefill")

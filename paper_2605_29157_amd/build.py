@@ -54,14 +54,32 @@ def _check_prefill_assembly(extra: list[str]) -> None:
     asm_check.check_file(asm)
 
 
+def _check_decode_assembly(extra: list[str]) -> None:
+    """The bf16 decode kernel sits at the 256-register limit of two workgroups per compute
+    unit; one spilled register costs it 10 %. Fail the build if any decode kernel spills."""
+    import re
+    asm = os.path.join(BUILD_DIR, "decode_bf16.gfx950.s")
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-S",
+           "--cuda-device-only", os.path.join(CSRC, "decode_bf16.hip"), "-o", asm]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc -S failed on decode_bf16.hip:\n" + res.stdout)
+    with open(asm) as f:
+        text = f.read()
+    spills = re.findall(r"\.vgpr_spill_count:\s+(\d+)", text)
+    if not spills or any(int(n) for n in spills):
+        raise RuntimeError("decode_bf16.hip: register spills in a decode kernel (%s)" % spills)
+
+
 def build_library(extra_flags: list[str] | None = None, verbose: bool = True) -> str:
     """Compile every kernel file for gfx950 and link libparallax_hip.so next to this file."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     extra = list(extra_flags or [])
-    with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES) + 1) as pool:
-        check = pool.submit(_check_prefill_assembly, extra)
+    with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES) + 2) as pool:
+        checks = [pool.submit(_check_prefill_assembly, extra), pool.submit(_check_decode_assembly, extra)]
         objs = list(pool.map(lambda s: _compile(s, extra), SOURCES))
-        check.result()
+        for c in checks:
+            c.result()
     tmp = LIB_PATH + ".tmp%d" % os.getpid()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -171,8 +171,12 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     int Lb = p.seq_lens ? p.seq_lens[b] : p.Lmax;
     Lb = min(max(Lb, 0), p.Lmax);
     const int n_bt = (Lb + kDecodeBlockKeys - 1) / kDecodeBlockKeys;
-    const int bt_per_split = (n_bt + S - 1) / S;
-    const int key_lo = split * bt_per_split * kDecodeBlockKeys;
+    // sliding window: a row at position pos sees the keys pos - window + 1 .. pos, so the block
+    // tiles before the first key of the earliest row (position Lb - Tq) are never read and the
+    // splits divide what is left
+    const int bt_first = p.window > 0 ? max(Lb - Tq + 1 - p.window, 0) / kDecodeBlockKeys : 0;
+    const int bt_per_split = (n_bt - bt_first + S - 1) / S;
+    const int key_lo = (bt_first + split * bt_per_split) * kDecodeBlockKeys;
     const int key_hi = min(key_lo + bt_per_split * kDecodeBlockKeys, Lb);
 
     // ---- B operands: q and r rows of the group's heads, zero in the dead columns ----------
@@ -237,7 +241,12 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     }
     const float scale_log2 = p.scale * kLog2e;
     // last-positions alignment: row t of Tq sees the keys before position Lb - (Tq - 1 - t)
-    const int col_hi = min(key_hi, Lb - (Tq - 1 - (live ? col_t : Tq - 1)));
+    // ... and, with a sliding window, not before position (its own) - window + 1. Both bounds in
+    // one unsigned compare: key - col_lo < col_span, with key = tk + 16*sub + i + 4*g.
+    const int col_end = Lb - (Tq - 1 - (live ? col_t : Tq - 1));
+    const int col_lo = p.window > 0 ? max(col_end - p.window, 0) : 0;
+    const int lane_rel = 4 * g - col_lo;
+    const unsigned col_span = (unsigned)max(min(key_hi, col_end) - col_lo, 0);
 
     int tk = key_lo + w * kTileKeys;
     if (tk < key_hi) {
@@ -285,8 +294,8 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int key = tk + 16 * sub + 4 * g + i;
-                x[sub][i] = key < col_hi ? s1[sub][i] * scale_log2 : kNegInf;
+                const bool seen = (unsigned)(tk + 16 * sub + i + lane_rel) < col_span;
+                x[sub][i] = seen ? s1[sub][i] * scale_log2 : kNegInf;
                 tmax = fmaxf(tmax, x[sub][i]);
             }
         tmax = rows_max(tmax);

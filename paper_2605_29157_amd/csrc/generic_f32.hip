@@ -18,6 +18,7 @@ struct GenericParams {
     const int32_t *block_table;  // paged decode cache (see DecodeParams); NULL = contiguous
     int32_t page_size, table_stride, num_pages;
     int32_t tail_rows;  // decode with Tq rows: row i sees the keys before len_b - (Tq - 1 - i)
+    int32_t window;     // > 0: a row sees only the last `window` of its keys
 };
 
 constexpr int kGenThreads = 256;
@@ -46,6 +47,7 @@ __global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams 
     else
         n_keys = p.seq_lens ? min(max(p.seq_lens[b], 0), p.Lk) : p.Lk;
     if (p.tail_rows) n_keys = max(n_keys - (p.Tq - 1 - i), 0);
+    const int j_first = (p.window > 0 && n_keys > p.window) ? n_keys - p.window : 0;
 
     const float *qrow = p.q + b * p.qs[0] + h * p.qs[1] + i * p.qs[2];
     const float *rrow = p.r ? p.r + b * p.rs[0] + h * p.rs[1] + i * p.rs[2] : nullptr;
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams 
     const float scale_log2 = p.scale * kLog2e;
     float m_run = kNegInf, d1 = 0.f, d2 = 0.f, o1 = 0.f, o2 = 0.f;  // o1/o2: dimension t
 
-    for (int j0 = 0; j0 < n_keys; j0 += kGenThreads) {
+    for (int j0 = j_first; j0 < n_keys; j0 += kGenThreads) {
         const int j = j0 + t;
         const bool valid = j < n_keys;
         float s1 = kNegInf, s2 = 0.f;
@@ -144,6 +146,7 @@ hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream) {
     g.ks[0] = p.ksb, g.ks[1] = p.ksh, g.ks[2] = p.ksl;
     g.vs[0] = p.vsb, g.vs[1] = p.vsh, g.vs[2] = p.vsl;
     g.scale = p.scale, g.causal = 0, g.use_r = p.use_r;
+    g.window = p.window;
     g.block_table = p.block_table;
     g.page_size = p.page_size, g.table_stride = p.table_stride, g.num_pages = p.num_pages;
     return launch_generic(g, stream);
@@ -163,6 +166,7 @@ hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream) {
         g.os[a] = p.os[a];
     }
     g.scale = p.scale, g.causal = p.causal, g.use_r = p.use_r;
+    g.window = p.window;
     return launch_generic(g, stream);
 }
 

@@ -98,6 +98,7 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
     if (st != PLX_OK) return st;
     if (a->num_splits < 0 || a->num_splits > PLX_MAX_SPLITS) return PLX_ERR_SPLITS;
     if (a->Tq < 0 || a->Tq > 65535) return PLX_ERR_SHAPE;
+    if (a->window < 0) return PLX_ERR_SHAPE;
     const int32_t Tq = a->Tq ? a->Tq : 1;
     if (a->dtype == PLX_BF16 && (a->Hq / a->Hkv) * Tq > 16) return PLX_ERR_SHAPE;
     if (need_inputs && !(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
@@ -129,6 +130,7 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
     p.vsb = a->v_stride_b, p.vsh = a->v_stride_h, p.vsl = a->v_stride_l;
     p.scale = a->scale, p.use_r = a->use_r ? 1 : 0;
     p.Tq = Tq;
+    p.window = a->window;
     if (need_inputs && a->block_table) {
         p.block_table = a->block_table;
         p.page_size = a->page_size, p.table_stride = a->block_table_stride;
@@ -136,6 +138,13 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
     }
     *out = p;
     return PLX_OK;
+}
+
+// Heuristic split count of a call: with a sliding window only the keys inside it are read.
+int32_t pick_splits(const plx_decode_args *a, int32_t Tq) {
+    int64_t len = a->Lmax;
+    if (a->window > 0 && (int64_t)a->window + Tq - 1 < len) len = (int64_t)a->window + Tq - 1;
+    return parallax_decode_num_splits(a->B, a->Hq, a->Hkv, (int32_t)len, a->d, 0);
 }
 
 plx_status attach_workspace(const plx_decode_args *a, int32_t S, plx::DecodeParams *p) {
@@ -160,7 +169,7 @@ plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
     }
 
     int32_t S = a->num_splits;
-    if (S == 0) S = parallax_decode_num_splits(a->B, a->Hq, a->Hkv, a->Lmax, a->d, 0);
+    if (S == 0) S = pick_splits(a, p.Tq);
     p.S = S;
     p.direct_out = S == 1;
     if (S > 1) {
@@ -178,7 +187,7 @@ plx_status parallax_decode_fused(const plx_decode_args *a, void *hip_stream) {
     if (st != PLX_OK) return st;
     if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
     int32_t S = a->num_splits;
-    if (S == 0) S = parallax_decode_num_splits(a->B, a->Hq, a->Hkv, a->Lmax, a->d, 0);
+    if (S == 0) S = pick_splits(a, p.Tq);
     p.S = S;
     p.direct_out = S == 1;
     if (S > 1) {
@@ -199,7 +208,7 @@ plx_status parallax_decode_partials(const plx_decode_args *a, void *hip_stream) 
     if (st != PLX_OK) return st;
     if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
     int32_t S = a->num_splits;
-    if (S == 0) S = parallax_decode_num_splits(a->B, a->Hq, a->Hkv, a->Lmax, a->d, 0);
+    if (S == 0) S = pick_splits(a, p.Tq);
     p.S = S;
     p.direct_out = 0;
     st = attach_workspace(a, S, &p);
@@ -232,6 +241,7 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
     if (a->Tkv < 0) return PLX_ERR_SHAPE;
     const int32_t Tk = a->Tkv ? a->Tkv : a->T;
     if (a->causal && Tk < a->T) return PLX_ERR_SHAPE;
+    if (a->window < 0 || (a->window > 0 && !a->causal)) return PLX_ERR_SHAPE;
     if (!(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
     if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || !aligned16(a->o) ||
         (a->r && !aligned16(a->r)))
@@ -260,6 +270,7 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
         p.os[j] = a->o_stride[j];
     }
     p.scale = a->scale, p.causal = a->causal ? 1 : 0, p.use_r = a->use_r ? 1 : 0;
+    p.window = a->window;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t err = a->dtype == PLX_F32 ? plx::launch_prefill_f32(p, stream)
                                          : plx::launch_prefill_bf16(p, stream);

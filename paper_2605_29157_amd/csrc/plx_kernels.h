@@ -22,6 +22,7 @@ struct DecodeParams {
     // block_table[b * table_stride + j / page_size]; ksb / vsb are then the page strides
     const int32_t *block_table;
     int32_t page_size, table_stride, num_pages;
+    int32_t window;  // > 0: sliding window, a row at position pos sees keys pos - window + 1 .. pos
     int32_t *counters;  // in-kernel reduction: one arrival counter per (batch, kv head), zero on entry
     int32_t Tq;  // query rows per sequence (>= 1): the last Tq positions; q, r, o are [B, Hq, Tq, d]
 };
@@ -33,6 +34,7 @@ struct PrefillParams {
     int64_t qs[3], rs[3], ks[3], vs[3], os[3];  // element strides {batch, head, row}
     float scale;
     int32_t causal, use_r;
+    int32_t window;  // > 0 (causal only): row at position pos sees keys pos - window + 1 .. pos
 };
 
 // Each returns hipSuccess or the launch error. No allocation, no synchronisation.

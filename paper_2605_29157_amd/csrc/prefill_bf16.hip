@@ -198,8 +198,9 @@ __device__ __forceinline__ void mfma32_scores(f32x16 &acc, u32x4 a, u32x4 b) {
 #endif
 }
 
-template <int D, bool USE_R, bool CAUSAL>
+template <int D, bool USE_R, bool CAUSAL, bool WINDOW>
 __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
+    static_assert(CAUSAL || !WINDOW, "a sliding window needs the rows' positions");
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int KSTEPS = D / 16;        // k-steps of the score contraction
     constexpr int NDB = D / 32;           // 32-wide blocks of output dimensions
@@ -241,8 +242,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const int h = lane >> 5;    // half-wave
 
     // ---- work item: heavy row blocks first; blocks of one (batch, kv head) share an XCD ----
-    const int T = p.T, Tk = p.Tk, G = p.G;  // query rows, keys
-    const int off = Tk - T;                 // causal: row i sits at key position i + off
+    const int T = p.T, G = p.G;  // query rows
     const int nrb = (T + kBR - 1) / kBR;
     const int pairs = p.B * p.Hkv;
     int rbi, pair, hg;
@@ -264,6 +264,12 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         }
     }
     const int rb = CAUSAL ? nrb - 1 - rbi : rbi;
+    // Sliding window: row i sees the keys i + off - window + 1 .. i + off. The key tiles before
+    // the first key of the workgroup's first row are skipped by moving the K / V base; from
+    // here on key positions, Tk and off are relative to that first tile.
+    const int kt_skip = WINDOW ? max(rb * kBR + (p.Tk - T) - p.window + 1, 0) / kBC : 0;
+    const int Tk = p.Tk - kt_skip * kBC;  // keys
+    const int off = Tk - T;               // causal: row i sits at key position i + off
     const int b = pair / p.Hkv, hk = pair - b * p.Hkv;
     const int hq = hk * G + hg;
 #ifdef PLX_PF_TIMING
@@ -304,14 +310,18 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     }
     u32x4 qf[KSTEPS], rf[KSTEPS];
 
-    const __bf16 *kbase = (const __bf16 *)p.k + b * p.ks[0] + hk * p.ks[1];
-    const __bf16 *vbase = (const __bf16 *)p.v + b * p.vs[0] + hk * p.vs[1];
+    const __bf16 *kbase = (const __bf16 *)p.k + b * p.ks[0] + hk * p.ks[1] + (int64_t)kt_skip * kBC * p.ks[2];
+    const __bf16 *vbase = (const __bf16 *)p.v + b * p.vs[0] + hk * p.vs[1] + (int64_t)kt_skip * kBC * p.vs[2];
 
     const int key_end = CAUSAL ? min(Tk, (rb + 1) * kBR + off) : Tk;  // keys this workgroup may need
     const int n_tiles = (key_end + kBC - 1) / kBC;
     // leading tiles whose keys all exist and are visible to every row of the workgroup, less two
     // so that the tile prefetched two ahead inside that loop is always a complete one
     const int n_full = max(0, min(CAUSAL ? (rb * kBR + off + 1) / kBC : Tk / kBC, Tk / kBC - kDist));
+    // sliding window: first key this lane's row sees, and the leading tiles that hold a key
+    // some row of the workgroup does not see (its last row starts latest)
+    const int row_lo = WINDOW ? my_row + off - p.window + 1 : 0;
+    const int n_left = WINDOW ? min(n_tiles, max(rb * kBR + kBR + off - p.window + kBC - 1, 0) / kBC) : 0;
 
     // ---- global -> LDS tile loads (no staging registers, no LDS write instructions) --------
     // Load instruction i of wave w fills LDS chunks [64*(w + 4i), +64) of a tile; lane l owns
@@ -412,7 +422,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // accumulator register r of an S^T block <-> key key_base + 8*(r/4) + 4*h + r%4
     auto key_ok = [&](int key_base, int r) {
         const int key = key_base + 8 * (r >> 2) + 4 * h + (r & 3);
-        return key < Tk && (!CAUSAL || key <= my_row + off);
+        return key < Tk && (!CAUSAL || key <= my_row + off) && (!WINDOW || key >= row_lo);
     };
 
     // d1 / d2 are accumulated by MFMAs as well: Ones(32 x 16 keys) x P^T gives a block whose
@@ -494,7 +504,8 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
 
     // does this wave see any key of the block starting at key_base?
     auto block_visible = [&](int key_base) {
-        return key_base < Tk && (!CAUSAL || key_base <= row0 + 31 + off);
+        return key_base < Tk && (!CAUSAL || key_base <= row0 + 31 + off) &&
+               (!WINDOW || key_base + kKB > row0 + off - p.window + 1);
     };
 
     u32x4 pb1[2], pb2[2];
@@ -545,10 +556,11 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // slot then holds independent instructions only, so the single wave of the SIMD never
     // waits on the latency of its own previous vector instruction.
     // With MASKED, `lim` is this lane's largest allowed key offset inside the block (its 4*h
-    // already subtracted): register r holds key offset 8*(r/4) + r%4.
+    // already subtracted) and, with a sliding window, `lo` its smallest: register r holds key
+    // offset 8*(r/4) + r%4.
     const int row_lim = CAUSAL ? min(my_row + off, Tk - 1) : Tk - 1;  // last key this lane's row may see
     auto exp_stages = [&](auto masked_tag, auto sums_tag, f32x16 &s1, f32x16 &s2, int r0, int slot,
-                          int slot0, int n_slots, float neg_m, int lim) {
+                          int slot0, int n_slots, float neg_m, int lim, int lo) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr bool SUMS = decltype(sums_tag)::value;  // a fourth stage adds P1, P2 to the row sums
 #pragma unroll
@@ -565,7 +577,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             if (slot == first) s1[r] = fmaf(s1[r], scale_log2, neg_m);
             if (slot == first + 1) {
                 const float p1 = fast_exp2(s1[r]);
-                s1[r] = (!MASKED || 8 * (r >> 2) + (r & 3) <= lim) ? p1 : 0.f;
+                const int key_off = 8 * (r >> 2) + (r & 3);
+                const bool seen = !MASKED || (key_off <= lim && (!WINDOW || key_off >= lo));
+                s1[r] = seen ? p1 : 0.f;
             }
             // P2: S2 is finite (rows past the last key re-read it) and P1 = 0 where masked
             if constexpr (USE_R)
@@ -581,6 +595,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                              f32x16 &sc2, f32x16 &sn1, f32x16 &sn2) {
         const int lim_cur = row_lim - key_base_cur - 4 * h;  // current block, next block
         const int lim_next = lim_cur - kKB;
+        const int lo_cur = row_lo - key_base_cur - 4 * h, lo_next = lo_cur - kKB;
         constexpr int SLOTS1 = 2 * KSTEPS;           // phase 1: one slot per score MFMA
         constexpr bool DMA = decltype(dma_tag)::value;  // this step also fetches tile (dma_tk, dma_tv)
         constexpr bool MASKED = decltype(masked_tag)::value;
@@ -613,7 +628,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             }
             if constexpr (DMA)
                 if (sl % 2 == 1 && sl / 2 < NDMA_K) k_load(sl / 2, dma_tk, dma_dk);
-            exp_stages(masked_tag, sums_tag, sc1, sc2, 8, sl, 0, SLOTS1, neg_m, lim_cur);
+            exp_stages(masked_tag, sums_tag, sc1, sc2, 8, sl, 0, SLOTS1, neg_m, lim_cur, lo_cur);
             if (sl == SLOTS1 - 2) pb1[1] = pack_group(sc1, 1);
             if (sl == SLOTS1 - 1) {
                 if constexpr (USE_R) pb2[1] = pack_group(sc2, 1);
@@ -643,7 +658,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             }
             if constexpr (DMA)
                 if (sl % 2 == 1 && sl / 2 < NDMA_V) v_load(sl / 2, dma_tv, dma_dv);
-            exp_stages(masked_tag, std::false_type{}, sn1, sn2, 0, sl, 1, SLOTS2, neg_m, lim_next);
+            exp_stages(masked_tag, std::false_type{}, sn1, sn2, 0, sl, 1, SLOTS2, neg_m, lim_next, lo_next);
             if constexpr (SUMS)
                 if (sl % (SLOTS2 / 8) == 0) {
                     const int r = sl / (SLOTS2 / 8);  // lower key group of the current block
@@ -701,10 +716,21 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         float tmax = kNegInf;
 #pragma unroll
         for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, key_ok(0, r) ? sa1[r] : kNegInf);
-        m_ref = halves_max(tmax) * scale_log2;
+        tmax = halves_max(tmax);
+        if constexpr (WINDOW) {
+            // a row whose window starts behind this block takes the block's plain maximum: any
+            // finite reference will do (the check after the loops catches one that was too far off)
+            float tall = sa1[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tall = fmaxf(tall, sa1[r]);
+            tall = halves_max(tall);
+            tmax = tmax == kNegInf ? tall : tmax;
+        }
+        m_ref = tmax * scale_log2;
 #pragma unroll
         for (int sl = 0; sl < 12; ++sl)
-            exp_stages(std::true_type{}, std::false_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - 4 * h);
+            exp_stages(std::true_type{}, std::false_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - 4 * h,
+                       row_lo - 4 * h);
         pb1[0] = pack_group(sa1, 0);
         if constexpr (USE_R) pb2[0] = pack_group(sa2, 0);
     }
@@ -717,11 +743,29 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         pipeline_step(masked_tag, std::false_type{}, kt * kBC + kKB, k_block_ptr(next_stage, 0),
                       v_block_ptr(stage, 1), k_block_ptr(next_stage, 1), sb1, sb2, sa1, sa2);
     };
+    // One tile of the pipeline with per-lane key masks. Blocks a wave cannot see at all
+    // contribute exact zeros.
+    auto masked_tile = [&](int kt) {
+        const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
+        const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
+        tile_barrier();
+        if (kt + kDist < n_tiles) {              // workgroup-uniform
+            if ((kt + kDist + 1) * kBC <= Tk)    // the tile exists completely
+                dma_full_tile(kt + kDist, free_stage);
+            else
+                dma_tile(kt + kDist, free_stage);
+        }
+        tile_steps(std::true_type{}, std::false_type{}, kt, stage, next_stage);
+        stage = next_stage;
+    };
     int kt = 0;
+    // Sliding window: the leading tiles are cut by the left edge of some row's window.
+    if constexpr (WINDOW)
+        for (; kt < n_left; ++kt) masked_tile(kt);
     // Tiles whose keys -- and those of the tile after -- are visible to every row: no masks, a
     // branch-free body. (A step also prepares the lower half of the NEXT block, hence the -1.)
-    dma_tk = (const char *)kbase + kDist * k_tile_bytes;
-    dma_tv = (const char *)vbase + kDist * v_tile_bytes;
+    dma_tk = (const char *)kbase + (kt + kDist) * k_tile_bytes;
+    dma_tv = (const char *)vbase + (kt + kDist) * v_tile_bytes;
     for (; kt < n_full - 1; ++kt) {
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
         const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;  // held tile kt - 1
@@ -738,21 +782,8 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         stage = next_stage;
     }
     PLX_STAMP(4);
-    // Remaining tiles (diagonal / tail): the same pipeline with per-lane key masks. Blocks a wave
-    // cannot see at all contribute exact zeros.
-    for (; kt < n_tiles; ++kt) {
-        const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
-        const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
-        tile_barrier();
-        if (kt + kDist < n_tiles) {              // workgroup-uniform
-            if ((kt + kDist + 1) * kBC <= Tk)    // the tile exists completely
-                dma_full_tile(kt + kDist, free_stage);
-            else
-                dma_tile(kt + kDist, free_stage);
-        }
-        tile_steps(std::true_type{}, std::false_type{}, kt, stage, next_stage);
-        stage = next_stage;
-    }
+    // Remaining tiles (diagonal / tail): the same pipeline with per-lane key masks.
+    for (; kt < n_tiles; ++kt) masked_tile(kt);
 
     PLX_STAMP(5);
     // overflow check: any inf/NaN in the sums means the fixed reference was too small
@@ -764,6 +795,12 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             chk = fmaf(o1[n][r], 0.f, chk);
             if constexpr (USE_R) chk = fmaf(o2[n][r], 0.f, chk);
         }
+    if constexpr (WINDOW) {
+        // the reference of a row may come from keys outside its window; if it was so far above
+        // the row's own scores that the sum underflowed, take the exact path as well
+        const float d1 = dacc1[0] + halves_sum(vsum1[0] + vsum1[1]);
+        if (my_row < T && !(d1 > 1e-30f)) chk = 1.f;
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // tile loads past the end have landed
     const bool overflow = __syncthreads_or(chk != 0.f);  // NaN != 0 is true; all waves agree
     PLX_STAMP(6);
@@ -871,16 +908,21 @@ static hipError_t launch_prefill_d(const PrefillParams &p, hipStream_t stream) {
     const long long total = (long long)nrb * p.Hq * p.B;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)total), block(256);
-    if (p.use_r) {
-        if (p.causal)
-            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true>), grid, block, 0, stream, p);
+    if (p.window > 0) {  // causal only (checked by the caller)
+        if (p.use_r)
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, true>), grid, block, 0, stream, p);
         else
-            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, false>), grid, block, 0, stream, p);
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, false, true, true>), grid, block, 0, stream, p);
+    } else if (p.use_r) {
+        if (p.causal)
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false>), grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, false, false>), grid, block, 0, stream, p);
     } else {
         if (p.causal)
-            hipLaunchKernelGGL((prefill_bf16_kernel<D, false, true>), grid, block, 0, stream, p);
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, false, true, false>), grid, block, 0, stream, p);
         else
-            hipLaunchKernelGGL((prefill_bf16_kernel<D, false, false>), grid, block, 0, stream, p);
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, false, false, false>), grid, block, 0, stream, p);
     }
     return hipGetLastError();
 }

@@ -38,9 +38,9 @@ def test_header_symbols_are_exported(binding):
 
 def test_struct_sizes_match_c_layout(binding):
     # 6 pointers, 5 int32 (+pad), 6 int64, float + 2 int32 (+pad), pointer, size_t, enum (+pad),
-    # pointer, 4 int32, pointer
-    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16 + 8
-    # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, int32 (+pad)
+    # pointer, 4 int32, int32 (+pad), pointer
+    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16 + 8 + 8
+    # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, 2 int32
     assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8
 
 
@@ -123,6 +123,8 @@ def test_decode_rejects_bad_arguments_before_launch(binding):
     a = _good_decode_args(binding); a.num_splits = 4
     a.workspace, a.workspace_bytes = 0x2000, 16
     assert call(a) == binding.PLX_ERR_WORKSPACE
+    a = _good_decode_args(binding); a.window = -1
+    assert call(a) == binding.PLX_ERR_SHAPE
     # in-kernel reduction: needs bf16, and workspace + counters as soon as there are splits
     fused = lib.parallax_decode_fused
     a = _good_decode_args(binding); a.num_splits = 4
@@ -181,6 +183,10 @@ def test_prefill_rejects_bad_arguments_before_launch(binding):
     a = good(); a.Tkv = -1
     assert call(a) == binding.PLX_ERR_SHAPE
     a = good(); a.Tkv = 64  # causal with fewer keys than query rows
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.window = -3
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.window, a.causal = 64, 0  # a window needs the rows' positions
     assert call(a) == binding.PLX_ERR_SHAPE
 
 
