@@ -183,9 +183,43 @@ typedef struct {
     plx_dtype dtype;
     int32_t Tkv; /* keys per sequence; 0 = T */
     int32_t window; /* sliding window in keys (needs causal); 0 = none */
+    /* Row cache for parallax_prefill_backward (App. D), both or neither (bf16, use_r, no window):
+     *   vbar       [B, Hq, T, d] like o (same strides): the softmax value mean O1 / d1
+     *   row_stats  [B, Hq, T, 2] fp32 contiguous: log2 of sum_j exp(scale q.k_j) (i.e. the
+     *              log-sum-exp in the exp2 domain) and ubar = sum_j p_j rho.k_j */
+    void *vbar;
+    float *row_stats;
 } plx_prefill_args;
 
 plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
+
+/*
+ * Backward of parallax_prefill (closed-form gradients, App. D): given the upstream gradient d_o,
+ * the forward's inputs, its output o and its row cache (vbar, row_stats), writes dq, dr
+ * [B, Hq, T, d] and dk, dv [B, Hkv, Tkv, d]; the gradients of a KV head add up over the query
+ * heads of its group. bf16 only; EVERY tensor contiguous (row-major, head dimension innermost),
+ * 16-byte aligned; d = 64 or 128. causal and Tkv as in the forward (no window).
+ *   workspace  fp32 scratch, >= parallax_prefill_backward_workspace_bytes(B, Hq, T) = 16 bytes
+ *              per query row (lse, ubar, tau = dO.o, beta = dO.vbar)
+ * Three kernels are enqueued (row scalars; dQ, dR; dK, dV); nothing is accumulated with atomics,
+ * so results are deterministic and the outputs need no zeroing.
+ */
+typedef struct {
+    const void *q, *r, *k, *v;
+    const void *o, *vbar;
+    const float *row_stats;
+    const void *d_o;
+    void *dq, *dr, *dk, *dv;
+    int32_t B, Hq, Hkv, T, Tkv, d; /* Tkv = 0 means T */
+    float scale;
+    int32_t causal;
+    plx_dtype dtype;
+    void *workspace;
+    size_t workspace_bytes;
+} plx_prefill_bwd_args;
+
+size_t parallax_prefill_backward_workspace_bytes(int32_t B, int32_t Hq, int32_t T);
+plx_status parallax_prefill_backward(const plx_prefill_bwd_args *args, void *hip_stream);
 
 /* Plain device-to-device copy kernel (16 bytes per lane, grid-stride). Used to calibrate
  * hardware byte counters and to measure the achievable streaming bandwidth next to the

@@ -22,7 +22,8 @@ PLX_MAX_SPLITS = 128
 EXPORTED_SYMBOLS = (
     "parallax_decode_workspace_bytes", "parallax_decode_num_splits", "parallax_decode",
     "parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused",
-    "parallax_prefill", "parallax_util_copy", "parallax_util_read",
+    "parallax_prefill", "parallax_prefill_backward", "parallax_prefill_backward_workspace_bytes",
+    "parallax_util_copy", "parallax_util_read",
     "parallax_util_read_sink_slots", "parallax_strerror", "parallax_version",
 )
 
@@ -67,6 +68,25 @@ class plx_prefill_args(ctypes.Structure):
         ("dtype", ctypes.c_int),
         ("Tkv", ctypes.c_int32),
         ("window", ctypes.c_int32),
+        ("vbar", ctypes.c_void_p), ("row_stats", ctypes.c_void_p),
+    ]
+
+
+class plx_prefill_bwd_args(ctypes.Structure):
+    _fields_ = [
+        ("q", ctypes.c_void_p), ("r", ctypes.c_void_p),
+        ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+        ("o", ctypes.c_void_p), ("vbar", ctypes.c_void_p),
+        ("row_stats", ctypes.c_void_p),
+        ("d_o", ctypes.c_void_p),
+        ("dq", ctypes.c_void_p), ("dr", ctypes.c_void_p),
+        ("dk", ctypes.c_void_p), ("dv", ctypes.c_void_p),
+        ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("T", ctypes.c_int32), ("Tkv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("causal", ctypes.c_int32),
+        ("dtype", ctypes.c_int),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
     ]
 
 
@@ -99,6 +119,10 @@ def load_library() -> ctypes.CDLL:
             getattr(lib, name).restype = ctypes.c_int
         lib.parallax_prefill.argtypes = [ctypes.POINTER(plx_prefill_args), ctypes.c_void_p]
         lib.parallax_prefill.restype = ctypes.c_int
+        lib.parallax_prefill_backward.argtypes = [ctypes.POINTER(plx_prefill_bwd_args), ctypes.c_void_p]
+        lib.parallax_prefill_backward.restype = ctypes.c_int
+        lib.parallax_prefill_backward_workspace_bytes.argtypes = [ctypes.c_int32] * 3
+        lib.parallax_prefill_backward_workspace_bytes.restype = ctypes.c_size_t
         lib.parallax_util_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                            ctypes.c_void_p]
         lib.parallax_util_copy.restype = ctypes.c_int
@@ -279,9 +303,11 @@ def prefill_args(q, r, k, v, out, scale, causal=True, use_r=True, window=0):
     return a
 
 
-def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None, window=0):
+def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None, window=0,
+                     save_for_backward=False):
     """Parallax prefill forward over T query rows and Tkv keys (causal: the rows are the last
-    T positions of the Tkv-long sequence)."""
+    T positions of the Tkv-long sequence). With save_for_backward the kernel also writes the row
+    cache of the backward pass and (out, vbar, row_stats) is returned."""
     for t in (q, k, v) + ((r,) if r is not None else ()):
         if not t.is_cuda:
             raise ValueError("parallax_prefill needs device tensors")
@@ -292,10 +318,53 @@ def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, strea
     if out is None:
         out = torch.empty_like(q)
     a = prefill_args(q, r, k, v, out, scale, causal, use_r, window)
+    if save_for_backward:
+        vbar = torch.empty_like(out)
+        row_stats = torch.empty(q.shape[:3] + (2,), dtype=torch.float32, device=q.device)
+        a.vbar, a.row_stats = vbar.data_ptr(), row_stats.data_ptr()
     st = load_library().parallax_prefill(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_prefill")
-    return out
+    return (out, vbar, row_stats) if save_for_backward else out
+
+
+def parallax_prefill_backward_workspace_bytes(B, Hq, T) -> int:
+    return int(load_library().parallax_prefill_backward_workspace_bytes(B, Hq, T))
+
+
+def prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale, causal, workspace):
+    """Fill a plx_prefill_bwd_args from contiguous tensors."""
+    for t in (q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, workspace):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("parallax_prefill_backward needs contiguous device tensors")
+    B, Hq, T, d = q.shape
+    a = plx_prefill_bwd_args()
+    a.q, a.r, a.k, a.v = q.data_ptr(), r.data_ptr(), k.data_ptr(), v.data_ptr()
+    a.o, a.vbar, a.row_stats, a.d_o = o.data_ptr(), vbar.data_ptr(), row_stats.data_ptr(), d_o.data_ptr()
+    a.dq, a.dr, a.dk, a.dv = dq.data_ptr(), dr.data_ptr(), dk.data_ptr(), dv.data_ptr()
+    a.B, a.Hq, a.Hkv, a.T, a.Tkv, a.d = B, Hq, k.shape[1], T, k.shape[2], d
+    a.scale = float(scale)
+    a.causal = 1 if causal else 0
+    a.dtype = _dtype_code(q)
+    a.workspace = workspace.data_ptr()
+    a.workspace_bytes = workspace.numel() * workspace.element_size()
+    return a
+
+
+def parallax_prefill_backward(q, r, k, v, o, vbar, row_stats, d_o, scale, causal=True, stream=None,
+                              workspace=None):
+    """Gradients (dq, dr, dk, dv) of parallax_prefill for the upstream gradient d_o, from the
+    forward's output and row cache (save_for_backward=True)."""
+    dq, dr = torch.empty_like(q), torch.empty_like(q)
+    dk, dv = torch.empty_like(k), torch.empty_like(k)
+    if workspace is None:
+        workspace = torch.empty(q.shape[0] * q.shape[1] * q.shape[2] * 4, dtype=torch.float32,
+                                device=q.device)
+    a = prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale, causal, workspace)
+    st = load_library().parallax_prefill_backward(ctypes.byref(a), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_prefill_backward")
+    return dq, dr, dk, dv
 
 
 def parallax_util_copy(dst, src, stream=None):

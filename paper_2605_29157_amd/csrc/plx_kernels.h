@@ -35,12 +35,30 @@ struct PrefillParams {
     float scale;
     int32_t causal, use_r;
     int32_t window;  // > 0 (causal only): row at position pos sees keys pos - window + 1 .. pos
+    // row cache for the backward pass, both or neither: vbar laid out like o, row_stats
+    // [B, Hq, T, 2] fp32 = (log-sum-exp of the scaled scores in the exp2 domain, ubar)
+    void *vbar;
+    float *row_stats;
+};
+
+// Backward of the prefill forward; every tensor contiguous: q-like [B, Hq, T, d], k-like
+// [B, Hkv, Tk, d].
+struct PrefillBwdParams {
+    const void *q, *r, *k, *v, *d_o;
+    const void *o, *vbar;    // forward output and cached softmax value mean
+    const float *row_stats;  // [B, Hq, T, 2] from the forward: (log-sum-exp in the exp2 domain, ubar)
+    float *row_cache;        // workspace [B, Hq, T, 4]: (lse, ubar, tau, beta)
+    void *dq, *dr, *dk, *dv;
+    int32_t B, Hq, Hkv, G, T, Tk, d;
+    float scale;
+    int32_t causal;
 };
 
 // Each returns hipSuccess or the launch error. No allocation, no synchronisation.
 hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_decode_combine(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_prefill_bf16(const PrefillParams &p, hipStream_t stream);
+hipError_t launch_prefill_bwd_bf16(const PrefillBwdParams &p, hipStream_t stream);
 hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream);
 hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);

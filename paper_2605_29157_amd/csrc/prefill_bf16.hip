@@ -40,6 +40,7 @@
 
 #include "plx_device.h"
 #include "plx_kernels.h"
+#include "plx_lds_dma.h"
 
 namespace plx {
 
@@ -66,40 +67,6 @@ constexpr int kKB = 32;   // keys per inner block (one MFMA row block)
 #define PLX_PF_ASM_SCORES 1
 #endif
 
-// Tile loads go global -> LDS directly (global_load_lds_dwordx4: LDS address = M0 + 16 * lane).
-// They are emitted as inline assembly: through the compiler builtin, the first LDS read after
-// a tile load waits for that load to land (the compiler assumes every LDS read may alias the
-// incoming tile), which exposes the full memory latency once per tile. In this kernel a tile
-// in flight is never read before the workgroup barrier that publishes it, so the only wait
-// needed is the explicit vmcnt(0) in front of that barrier (tile_barrier below).
-// LANES < 64: only lanes 0..LANES-1 load (a shorter piece): EXEC is narrowed around the
-// instruction.
-template <int LANES = 64>
-__device__ __forceinline__ void tile_load16(const void *gptr, uint32_t lds_byte_addr) {
-    static_assert(LANES == 64 || LANES == 32 || LANES == 16, "piece sizes in use");
-    const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_byte_addr);
-    uint32_t saved_m0;  // M0 belongs to the compiler: put its value back
-    uint64_t saved_exec;
-    if constexpr (LANES < 64)
-        asm volatile(
-            "s_mov_b32 %0, m0\n\t"
-            "s_mov_b64 %1, exec\n\t"
-            "s_mov_b64 exec, %4\n\t"
-            "s_mov_b32 m0, %3\n\t"
-            "global_load_lds_dwordx4 %2, off\n\t"
-            "s_mov_b64 exec, %1\n\t"
-            "s_mov_b32 m0, %0"
-            : "=&s"(saved_m0), "=&s"(saved_exec)
-            : "v"(gptr), "s"(m0v), "n"((1ull << (LANES % 64)) - 1ull));
-    else
-        asm volatile(
-            "s_mov_b32 %0, m0\n\t"
-            "s_mov_b32 m0, %2\n\t"
-            "global_load_lds_dwordx4 %1, off\n\t"
-            "s_mov_b32 m0, %0"
-            : "=&s"(saved_m0)
-            : "v"(gptr), "s"(m0v));
-}
 // Same load with a wave-uniform tile base (scalar registers) plus a 32-bit per-lane byte offset:
 // no per-lane 64-bit address arithmetic. M0 is not restored: nothing the compiler emits for this
 // kernel touches M0 (no other LDS-DMA, no GWS / message / relative-index instructions) -- the
@@ -126,19 +93,6 @@ __device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, cons
             :
             : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
 }
-// Wait until at most PENDING of this wave's tile loads are still in flight (loads complete in
-// issue order), then the workgroup barrier that publishes the landed tiles.
-template <int PENDING = 0>
-__device__ __forceinline__ void tile_barrier() {
-    static_assert(PENDING >= 0 && PENDING < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
-    __syncthreads();
-}
-__device__ __forceinline__ uint32_t lds_byte_address(const void *p) {
-    typedef const char __attribute__((address_space(3))) * lds_cptr_t;
-    return (uint32_t)(uintptr_t)(lds_cptr_t)p;
-}
-
 // Row sums d1, d2 of tiles that every row sees completely: per-lane fp32 adds of the unrounded
 // P1 / P2 (1) instead of MFMAs against a matrix of ones over the bf16-rounded values (0).
 #ifndef PLX_PF_VALU_SUMS
@@ -198,9 +152,10 @@ __device__ __forceinline__ void mfma32_scores(f32x16 &acc, u32x4 a, u32x4 b) {
 #endif
 }
 
-template <int D, bool USE_R, bool CAUSAL, bool WINDOW>
+template <int D, bool USE_R, bool CAUSAL, bool WINDOW, bool STATS = false>
 __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     static_assert(CAUSAL || !WINDOW, "a sliding window needs the rows' positions");
+    static_assert(!STATS || (USE_R && !WINDOW), "the row cache is written for the backward pass only");
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int KSTEPS = D / 16;        // k-steps of the score contraction
     constexpr int NDB = D / 32;           // 32-wide blocks of output dimensions
@@ -888,6 +843,37 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             const int row = row0 + rr;
             if (row < T) *(u32x4 *)(obase + (int64_t)row * p.os[2] + chunk * 8) = otile[rr * OROW + chunk];
         }
+        if constexpr (STATS) {
+            // Row cache for the backward pass (App. D): vbar_i = O1 / d1 through the same
+            // staging tile, and per row the log-sum-exp of the scaled scores in the exp2 domain
+            // (P1 = exp2(S1 * scale * log2 e - lse) needs no further division) and ubar = d2 / d1.
+            if (h == 0 && my_row < T) {
+                float *st = p.row_stats + (((int64_t)b * p.Hq + hq) * T + my_row) * 2;
+                st[0] = dsum1 > 0.f ? m_ref + log2f(dsum1) : kNegInf;
+                st[1] = dsum2 * inv;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int n = 0; n < NDB; ++n)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const u32x2 packed = {pack_bf16(o1[n][4 * q4] * inv, o1[n][4 * q4 + 1] * inv),
+                                          pack_bf16(o1[n][4 * q4 + 2] * inv, o1[n][4 * q4 + 3] * inv)};
+                    *(u32x2 *)(otile16 + col * (OROW * 8) + 32 * n + 8 * q4 + 4 * h) = packed;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __bf16 *vbase_out = (__bf16 *)p.vbar + b * p.os[0] + hq * p.os[1];
+#pragma unroll
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const int rr = i * RPI + lane / CPR, chunk = lane % CPR;
+                const int row = row0 + rr;
+                if (row < T)
+                    *(u32x4 *)(vbase_out + (int64_t)row * p.os[2] + chunk * 8) = otile[rr * OROW + chunk];
+            }
+        }
     }
     PLX_STAMP(7);
 #ifdef PLX_PF_TIMING
@@ -908,7 +894,12 @@ static hipError_t launch_prefill_d(const PrefillParams &p, hipStream_t stream) {
     const long long total = (long long)nrb * p.Hq * p.B;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)total), block(256);
-    if (p.window > 0) {  // causal only (checked by the caller)
+    if (p.row_stats != nullptr) {  // with the row cache of the backward pass (use_r, no window)
+        if (p.causal)
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false, true>), grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, false, false, true>), grid, block, 0, stream, p);
+    } else if (p.window > 0) {  // causal only (checked by the caller)
         if (p.use_r)
             hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, true>), grid, block, 0, stream, p);
         else

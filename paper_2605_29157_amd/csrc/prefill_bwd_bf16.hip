@@ -1,0 +1,390 @@
+// Parallax prefill backward for bf16 on gfx950 (closed-form gradients of the paper's App. D).
+//
+// With p_ij = exp2(S1_ij * scale * log2 e - lse_i), u_ij = rho_i.k_j, a_ij = dO_i.v_j and the
+// row scalars ubar_i (cached by the forward), tau_i = dO_i.o_i, beta_i = dO_i.vbar_i:
+//     g1_ij = p_ij [a_ij - tau_i + (ubar_i - u_ij)(a_ij - beta_i)],   g2_ij = -p_ij (a_ij - beta_i)
+//     dQ_i = scale * sum_j g1_ij k_j      dR_i = sum_j g2_ij k_j
+//     dK_j = scale * sum_i g1_ij q_i + sum_i g2_ij rho_i
+//     dV_j = sum_i p_ij (1 + ubar_i - u_ij) dO_i
+// As the appendix says, the two reduction directions make two passes:
+//   * rows prepare: one wave per query row folds (lse, ubar) of the forward's row cache and
+//     tau, beta into one float4 per row;
+//   * row pass (dQ, dR): a workgroup owns 128 query rows of one head (32 per wave), keeps their
+//     Q, R, dO fragments in registers and streams K/V tiles of 64 keys. Scores are produced
+//     transposed, as in the forward: S1^T = K Q^T, S2^T = K R^T, A^T = V dO^T, so a lane owns one
+//     query row, the row scalars are per lane, and the accumulator registers of g1, g2 are
+//     already the B operand of dQ^T += K^T g1^T, dR^T += K^T g2^T (K^T fragments by transposing
+//     LDS reads);
+//   * column pass (dK, dV): a workgroup owns 128 keys of one KV head (32 per wave), keeps their
+//     K, V fragments in registers as B operands and streams Q, R, dO tiles of 64 rows of every
+//     query head of the group. S1 = Q K^T, S2 = R K^T, A = dO V^T put a key in each lane and the
+//     rows in its registers (row scalars come from LDS); the registers of p(1 + ubar - u), g1, g2
+//     are the B operands of dV^T += dO^T W, dK^T += Q^T g1 + R^T g2 (transposing LDS reads of the
+//     same tiles).
+// Eleven contractions of 2d flops per (row, key) pair against the forward's four. Tiles go
+// global -> LDS directly into a two-stage ring, one workgroup barrier per tile; the MFMA order is
+// left to the compiler (no hand-placed slots as in the forward kernel).
+#include "plx_device.h"
+#include "plx_kernels.h"
+#include "plx_lds_dma.h"
+
+namespace plx {
+
+namespace {
+
+constexpr int kTileRows = 64;  // rows (keys or query rows) per LDS tile
+constexpr int kBlk = 32;       // rows per MFMA block
+
+template <int D>
+struct BwdTile {
+    static constexpr int CPR = D / 8;           // 16-byte chunks per row
+    static constexpr int ROWP = CPR + 4;        // padded row stride: the 4 rows of a transposing
+                                                // read land in 4 different 64-byte bank groups
+    static constexpr int CHUNKS = kTileRows * ROWP;
+    static constexpr int NDMA = CHUNKS / 256;   // loads per wave and tile
+    static_assert(CHUNKS % 256 == 0, "four waves fill a tile with whole 64-lane loads");
+};
+
+// Rows [row0, row0 + 64) of a row-major [n_rows][D] bf16 matrix -> padded LDS tile. Rows past
+// the end re-read the last row (finite data; masked where it matters). Each wave fills a quarter.
+template <int D>
+__device__ __forceinline__ void load_tile64(const __bf16 *base, int row0, int n_rows,
+                                            uint32_t lds_tile_addr, int w, int lane) {
+    using TL = BwdTile<D>;
+#pragma unroll
+    for (int i = 0; i < TL::NDMA; ++i) {
+        const int c = (w * TL::NDMA + i) * 64 + lane;
+        const int row = c / TL::ROWP;
+        const int pos = min(c % TL::ROWP, TL::CPR - 1);  // padding re-fetches a neighbour
+        const __bf16 *g = base + (int64_t)min(row0 + row, n_rows - 1) * D + pos * 8;
+        tile_load16<64>(g, lds_tile_addr + (uint32_t)(w * TL::NDMA + i) * 1024u);
+    }
+}
+
+__device__ __forceinline__ u32x4 pack_group(const f32x16 &s, int j) {
+    return u32x4{pack_bf16(s[8 * j + 0], s[8 * j + 1]), pack_bf16(s[8 * j + 2], s[8 * j + 3]),
+                 pack_bf16(s[8 * j + 4], s[8 * j + 5]), pack_bf16(s[8 * j + 6], s[8 * j + 7])};
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+    return z;
+}
+
+}  // namespace
+
+// ---- rows prepare: (lse, ubar, tau, beta) per query row ---------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void bwd_rows_prepare_kernel(PrefillBwdParams p) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t n_rows = (int64_t)p.B * p.Hq * p.T;
+    if (row >= n_rows) return;
+    float tau = 0.f, beta = 0.f;
+    if (lane < D / 2) {
+        const uint32_t g = ((const uint32_t *)p.d_o)[row * (D / 2) + lane];
+        const uint32_t o = ((const uint32_t *)p.o)[row * (D / 2) + lane];
+        const uint32_t vb = ((const uint32_t *)p.vbar)[row * (D / 2) + lane];
+        tau = bf16_lo_f32(g) * bf16_lo_f32(o) + bf16_hi_f32(g) * bf16_hi_f32(o);
+        beta = bf16_lo_f32(g) * bf16_lo_f32(vb) + bf16_hi_f32(g) * bf16_hi_f32(vb);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        tau += __shfl_xor(tau, off, 64);
+        beta += __shfl_xor(beta, off, 64);
+    }
+    if (lane == 0) {
+        const f32x4 out = {p.row_stats[2 * row], p.row_stats[2 * row + 1], tau, beta};
+        ((f32x4 *)p.row_cache)[row] = out;
+    }
+}
+
+// ---- row pass: dQ, dR -------------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
+    using TL = BwdTile<D>;
+    constexpr int ROWP = TL::ROWP, KSTEPS = D / 16, NDB = D / 32;
+    __shared__ u32x4 lds[2 * 2 * TL::CHUNKS];  // [stage][K tile | V tile]
+
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int col = lane & 31, h = lane >> 5;
+    const int T = p.T, Tk = p.Tk, off = Tk - T;
+    const int nrb = (T + 127) / 128;
+    const int rbi = blockIdx.x % nrb;
+    const int rb = CAUSAL ? nrb - 1 - rbi : rbi;  // heavy row blocks first
+    const int hq = (blockIdx.x / nrb) % p.Hq, b = blockIdx.x / (nrb * p.Hq);
+    const int hk = hq / p.G;
+    const int row0 = rb * 128 + w * 32, my_row = row0 + col;
+    const int ld_row = min(my_row, T - 1);
+
+    // B operands of the score MFMAs: column = query row, k-elements = the 8 dims of chunk 2*ks + h
+    const int64_t qrow = (((int64_t)b * p.Hq + hq) * T + ld_row) * D;
+    u32x4 qf[KSTEPS], rf[KSTEPS], gf[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        qf[ks] = *(const u32x4 *)((const __bf16 *)p.q + qrow + 8 * (2 * ks + h));
+        rf[ks] = *(const u32x4 *)((const __bf16 *)p.r + qrow + 8 * (2 * ks + h));
+        gf[ks] = *(const u32x4 *)((const __bf16 *)p.d_o + qrow + 8 * (2 * ks + h));
+    }
+    const f32x4 rc = ((const f32x4 *)p.row_cache)[((int64_t)b * p.Hq + hq) * T + ld_row];
+    const float lse = rc[0], ubar = rc[1], tau = rc[2], beta = rc[3];
+    const float scale_log2 = p.scale * kLog2e;
+
+    const __bf16 *kbase = (const __bf16 *)p.k + ((int64_t)b * p.Hkv + hk) * Tk * D;
+    const __bf16 *vbase = (const __bf16 *)p.v + ((int64_t)b * p.Hkv + hk) * Tk * D;
+    const uint32_t lds_base = lds_byte_address(lds);
+    auto issue_tile = [&](int t, int stage) {
+        load_tile64<D>(kbase, t * kTileRows, Tk, lds_base + (uint32_t)(stage * 2 * TL::CHUNKS) * 16u, w, lane);
+        load_tile64<D>(vbase, t * kTileRows, Tk, lds_base + (uint32_t)((stage * 2 + 1) * TL::CHUNKS) * 16u, w, lane);
+    };
+
+    const int key_end = CAUSAL ? min(Tk, (rb + 1) * 128 + off) : Tk;
+    const int n_tiles = (key_end + kTileRows - 1) / kTileRows;
+
+    f32x16 dq[NDB], dr[NDB];
+#pragma unroll
+    for (int n = 0; n < NDB; ++n) dq[n] = dr[n] = zero16();
+
+    // transposing reads: lane -> (row, chunk, half) inside a [4 rows][16 elements] group
+    const int tr_row = 4 * h + ((lane & 15) >> 2);
+    const int tr_half = (lane & 1) * 4;
+    const int tr_chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+    const int tr_lane_off = (tr_row * ROWP + tr_chunk) * 8 + tr_half;  // in bf16 elements
+
+    issue_tile(0, 0);
+    for (int t = 0; t < n_tiles; ++t) {
+        const int stage = t & 1;
+        tile_barrier<0>();  // tile t has landed; everybody is done with tile t - 1
+        if (t + 1 < n_tiles) issue_tile(t + 1, stage ^ 1);
+        const u32x4 *tk = lds + stage * 2 * TL::CHUNKS;
+        const u32x4 *tv = tk + TL::CHUNKS;
+#pragma unroll 1
+        for (int kb = 0; kb < kTileRows / kBlk; ++kb) {
+            const int key_base = t * kTileRows + kb * kBlk;
+            // wave-uniform: does any row of this wave see a key of the block?
+            if (key_base >= Tk || (CAUSAL && key_base > row0 + 31 + off)) continue;
+            f32x16 s1 = zero16(), s2 = zero16(), aa = zero16();
+            const u32x4 *kfp = tk + (kb * kBlk + col) * ROWP + h;
+            const u32x4 *vfp = tv + (kb * kBlk + col) * ROWP + h;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                const u32x4 kf = kfp[2 * ks], vf = vfp[2 * ks];
+                s1 = mfma32(kf, qf[ks], s1);
+                s2 = mfma32(kf, rf[ks], s2);
+                aa = mfma32(vf, gf[ks], aa);
+            }
+            // accumulator register r <-> key key_base + 8*(r/4) + 4*h + r%4, column = my_row
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key_base + 8 * (r >> 2) + 4 * h + (r & 3);
+                const bool ok = key < Tk && (!CAUSAL || key <= my_row + off);
+                const float pr = ok ? fast_exp2(fmaf(s1[r], scale_log2, -lse)) : 0.f;
+                const float dlt = aa[r] - beta;
+                s1[r] = pr * (aa[r] - tau + (ubar - s2[r]) * dlt);  // g1
+                s2[r] = -pr * dlt;                                  // g2
+            }
+            u32x4 pg1[2], pg2[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                pg1[j] = pack_group(s1, j);
+                pg2[j] = pack_group(s2, j);
+            }
+            // dQ^T += K^T g1^T, dR^T += K^T g2^T. A operand: row = dim 32n + col, k-elements =
+            // the 8 keys of the B operand (keys 16j+4h..+3 and 16j+8+4h..+3 of the block)
+            const unsigned short *tk16 = (const unsigned short *)tk + tr_lane_off + kb * kBlk * ROWP * 8;
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int n = 0; n < NDB; ++n) {
+                    const int o = (16 * j * ROWP + 4 * n) * 8;
+                    const u32x2 lo = lds_read_tr16(tk16 + o);
+                    const u32x2 hi = lds_read_tr16(tk16 + o + 8 * ROWP * 8);
+                    const u32x4 kt = {lo[0], lo[1], hi[0], hi[1]};
+                    dq[n] = mfma32(kt, pg1[j], dq[n]);
+                    dr[n] = mfma32(kt, pg2[j], dr[n]);
+                }
+        }
+    }
+
+    // dQ^T / dR^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of row my_row
+    if (my_row < T) {
+        __bf16 *dq_row = (__bf16 *)p.dq + qrow;
+        __bf16 *dr_row = (__bf16 *)p.dr + qrow;
+#pragma unroll
+        for (int n = 0; n < NDB; ++n)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int dim = 32 * n + 8 * q4 + 4 * h;
+                const u32x2 a = {pack_bf16(dq[n][4 * q4] * p.scale, dq[n][4 * q4 + 1] * p.scale),
+                                 pack_bf16(dq[n][4 * q4 + 2] * p.scale, dq[n][4 * q4 + 3] * p.scale)};
+                const u32x2 c = {pack_bf16(dr[n][4 * q4], dr[n][4 * q4 + 1]),
+                                 pack_bf16(dr[n][4 * q4 + 2], dr[n][4 * q4 + 3])};
+                *(u32x2 *)(dq_row + dim) = a;
+                *(u32x2 *)(dr_row + dim) = c;
+            }
+    }
+}
+
+// ---- column pass: dK, dV ----------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
+    using TL = BwdTile<D>;
+    constexpr int ROWP = TL::ROWP, KSTEPS = D / 16, NDB = D / 32;
+    constexpr int STAGE = 3 * TL::CHUNKS + kTileRows;  // Q, R, dO tiles + one float4 per row
+    __shared__ u32x4 lds[2 * STAGE];
+
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int col = lane & 31, h = lane >> 5;
+    const int T = p.T, Tk = p.Tk, off = Tk - T, G = p.G;
+    const int ncb = (Tk + 127) / 128;
+    const int cb = blockIdx.x % ncb;  // causal: low key blocks see the most rows; they come first
+    const int hk = (blockIdx.x / ncb) % p.Hkv, b = blockIdx.x / (ncb * p.Hkv);
+    const int key0 = cb * 128 + w * 32, my_key = key0 + col;
+    const int ld_key = min(my_key, Tk - 1);
+
+    // B operands of the score MFMAs: column = key, k-elements = the 8 dims of chunk 2*ks + h
+    const int64_t krow = (((int64_t)b * p.Hkv + hk) * Tk + ld_key) * D;
+    u32x4 kf[KSTEPS], vf[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        kf[ks] = *(const u32x4 *)((const __bf16 *)p.k + krow + 8 * (2 * ks + h));
+        vf[ks] = *(const u32x4 *)((const __bf16 *)p.v + krow + 8 * (2 * ks + h));
+    }
+    const float scale_log2 = p.scale * kLog2e;
+
+    // row tiles that hold a row which sees a key of this block: rows i >= key - off
+    const int rt_lo = CAUSAL ? max(cb * 128 - off, 0) / kTileRows : 0;
+    const int n_rt = (T + kTileRows - 1) / kTileRows;
+    const int per_head = n_rt - rt_lo;
+    const int n_items = per_head * G;  // (head of the group, row tile)
+
+    const uint32_t lds_base = lds_byte_address(lds);
+    auto issue_item = [&](int it, int stage) {
+        const int g = it / per_head, rt = rt_lo + it % per_head;
+        const int64_t head = ((int64_t)b * p.Hq + hk * G + g) * T;
+        const uint32_t s0 = lds_base + (uint32_t)(stage * STAGE) * 16u;
+        load_tile64<D>((const __bf16 *)p.q + head * D, rt * kTileRows, T, s0, w, lane);
+        load_tile64<D>((const __bf16 *)p.r + head * D, rt * kTileRows, T, s0 + (uint32_t)TL::CHUNKS * 16u, w, lane);
+        load_tile64<D>((const __bf16 *)p.d_o + head * D, rt * kTileRows, T, s0 + (uint32_t)(2 * TL::CHUNKS) * 16u, w,
+                       lane);
+        if (w == 0) {  // the rows' scalars, one float4 per lane
+            const f32x4 *src = (const f32x4 *)p.row_cache + head + min(rt * kTileRows + lane, T - 1);
+            tile_load16<64>(src, s0 + (uint32_t)(3 * TL::CHUNKS) * 16u);
+        }
+    };
+
+    f32x16 dk[NDB], dv[NDB];
+#pragma unroll
+    for (int n = 0; n < NDB; ++n) dk[n] = dv[n] = zero16();
+
+    const int tr_row = 4 * h + ((lane & 15) >> 2);
+    const int tr_half = (lane & 1) * 4;
+    const int tr_chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+    const int tr_lane_off = (tr_row * ROWP + tr_chunk) * 8 + tr_half;
+
+    if (n_items > 0) issue_item(0, 0);
+    for (int it = 0; it < n_items; ++it) {
+        const int stage = it & 1;
+        tile_barrier<0>();
+        if (it + 1 < n_items) issue_item(it + 1, stage ^ 1);
+        const int rt = rt_lo + it % per_head;
+        const u32x4 *tq = lds + stage * STAGE;
+        const u32x4 *tr_ = tq + TL::CHUNKS;
+        const u32x4 *tg = tq + 2 * TL::CHUNKS;
+        const f32x4 *rows = (const f32x4 *)(tq + 3 * TL::CHUNKS);
+#pragma unroll 1
+        for (int rbk = 0; rbk < kTileRows / kBlk; ++rbk) {
+            const int row_base = rt * kTileRows + rbk * kBlk;
+            // wave-uniform: does any row of the block see a key of this wave?
+            if (row_base >= T || (CAUSAL && row_base + 31 + off < key0)) continue;
+            f32x16 s1 = zero16(), s2 = zero16(), aa = zero16();
+            const u32x4 *qfp = tq + (rbk * kBlk + col) * ROWP + h;
+            const u32x4 *rfp = tr_ + (rbk * kBlk + col) * ROWP + h;
+            const u32x4 *gfp = tg + (rbk * kBlk + col) * ROWP + h;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                s1 = mfma32(qfp[2 * ks], kf[ks], s1);
+                s2 = mfma32(rfp[2 * ks], kf[ks], s2);
+                aa = mfma32(gfp[2 * ks], vf[ks], aa);
+            }
+            // accumulator register r <-> row row_base + 8*(r/4) + 4*h + r%4, column = my_key
+            f32x16 wgt;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = rbk * kBlk + 8 * (r >> 2) + 4 * h + (r & 3);
+                const int row = rt * kTileRows + lr;
+                const f32x4 rc = rows[lr];  // (lse, ubar, tau, beta)
+                const bool ok = row < T && my_key < Tk && (!CAUSAL || my_key <= row + off);
+                const float pr = ok ? fast_exp2(fmaf(s1[r], scale_log2, -rc[0])) : 0.f;
+                const float um = rc[1] - s2[r];
+                const float dlt = aa[r] - rc[3];
+                wgt[r] = pr * (1.f + um);
+                s1[r] = pr * (aa[r] - rc[2] + um * dlt) * p.scale;  // g1 / h
+                s2[r] = -pr * dlt;                                  // g2
+            }
+            const unsigned short *tq16 = (const unsigned short *)tq + tr_lane_off + rbk * kBlk * ROWP * 8;
+            const unsigned short *tr16 = (const unsigned short *)tr_ + tr_lane_off + rbk * kBlk * ROWP * 8;
+            const unsigned short *tg16 = (const unsigned short *)tg + tr_lane_off + rbk * kBlk * ROWP * 8;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const u32x4 pw = pack_group(wgt, j), pg1 = pack_group(s1, j), pg2 = pack_group(s2, j);
+#pragma unroll
+                for (int n = 0; n < NDB; ++n) {
+                    const int o = (16 * j * ROWP + 4 * n) * 8;
+                    const u32x2 glo = lds_read_tr16(tg16 + o), ghi = lds_read_tr16(tg16 + o + 8 * ROWP * 8);
+                    const u32x2 qlo = lds_read_tr16(tq16 + o), qhi = lds_read_tr16(tq16 + o + 8 * ROWP * 8);
+                    const u32x2 rlo = lds_read_tr16(tr16 + o), rhi = lds_read_tr16(tr16 + o + 8 * ROWP * 8);
+                    dv[n] = mfma32(u32x4{glo[0], glo[1], ghi[0], ghi[1]}, pw, dv[n]);
+                    dk[n] = mfma32(u32x4{qlo[0], qlo[1], qhi[0], qhi[1]}, pg1, dk[n]);
+                    dk[n] = mfma32(u32x4{rlo[0], rlo[1], rhi[0], rhi[1]}, pg2, dk[n]);
+                }
+            }
+        }
+    }
+
+    // dK^T / dV^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of key my_key
+    if (my_key < Tk) {
+        __bf16 *dk_row = (__bf16 *)p.dk + krow;
+        __bf16 *dv_row = (__bf16 *)p.dv + krow;
+#pragma unroll
+        for (int n = 0; n < NDB; ++n)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int dim = 32 * n + 8 * q4 + 4 * h;
+                const u32x2 a = {pack_bf16(dk[n][4 * q4], dk[n][4 * q4 + 1]),
+                                 pack_bf16(dk[n][4 * q4 + 2], dk[n][4 * q4 + 3])};
+                const u32x2 c = {pack_bf16(dv[n][4 * q4], dv[n][4 * q4 + 1]),
+                                 pack_bf16(dv[n][4 * q4 + 2], dv[n][4 * q4 + 3])};
+                *(u32x2 *)(dk_row + dim) = a;
+                *(u32x2 *)(dv_row + dim) = c;
+            }
+    }
+}
+
+template <int D>
+static hipError_t launch_bwd_d(const PrefillBwdParams &p, hipStream_t stream) {
+    const long long n_rows = (long long)p.B * p.Hq * p.T;
+    const long long g0 = (n_rows + 3) / 4;
+    const long long g1 = (long long)((p.T + 127) / 128) * p.Hq * p.B;
+    const long long g2 = (long long)((p.Tk + 127) / 128) * p.Hkv * p.B;
+    if (g0 > 0x7fffffffLL || g1 > 0x7fffffffLL || g2 > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_rows_prepare_kernel<D>), dim3((unsigned)g0), dim3(256), 0, stream, p);
+    if (p.causal) {
+        hipLaunchKernelGGL((bwd_dq_dr_kernel<D, true>), dim3((unsigned)g1), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+    } else {
+        hipLaunchKernelGGL((bwd_dq_dr_kernel<D, false>), dim3((unsigned)g1), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((bwd_dk_dv_kernel<D, false>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_bwd_bf16(const PrefillBwdParams &p, hipStream_t stream) {
+    return p.d == 128 ? launch_bwd_d<128>(p, stream) : launch_bwd_d<64>(p, stream);
+}
+
+}  // namespace plx

@@ -40,8 +40,10 @@ def test_struct_sizes_match_c_layout(binding):
     # 6 pointers, 5 int32 (+pad), 6 int64, float + 2 int32 (+pad), pointer, size_t, enum (+pad),
     # pointer, 4 int32, int32 (+pad), pointer
     assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16 + 8 + 8
-    # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, 2 int32
-    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8
+    # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, 2 int32, 2 pointers
+    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8 + 16
+    # 12 pointers, 6 int32, float + int32, enum (+pad), pointer, size_t
+    assert ctypes.sizeof(binding.plx_prefill_bwd_args) == 12 * 8 + 24 + 8 + 8 + 16
 
 
 def test_version_and_strerror(binding):
@@ -196,3 +198,48 @@ def test_util_argument_checks(binding):
     assert lib.parallax_util_copy(0x1000, 0x2000, 10, None) == binding.PLX_ERR_SHAPE
     assert lib.parallax_util_copy(0x1001, 0x2000, 16, None) == binding.PLX_ERR_ALIGN
     assert binding.parallax_util_read_sink_slots() > 0
+
+
+def test_prefill_backward_rejects_bad_arguments_before_launch(binding):
+    lib = binding.load_library()
+
+    def good():
+        a = binding.plx_prefill_bwd_args()
+        for name in ("q", "r", "k", "v", "o", "vbar", "row_stats", "d_o", "dq", "dr", "dk", "dv"):
+            setattr(a, name, 0x1000)
+        a.B, a.Hq, a.Hkv, a.T, a.Tkv, a.d = 1, 4, 2, 128, 0, 128
+        a.scale, a.causal, a.dtype = 0.1, 1, binding.PLX_BF16
+        a.workspace, a.workspace_bytes = 0x2000, 1 * 4 * 128 * 16
+        return a
+
+    call = lambda a: lib.parallax_prefill_backward(ctypes.byref(a), None)
+    assert binding.parallax_prefill_backward_workspace_bytes(1, 4, 128) == 4 * 128 * 16
+    assert lib.parallax_prefill_backward(None, None) == binding.PLX_ERR_NULL
+    a = good(); a.vbar = None
+    assert call(a) == binding.PLX_ERR_NULL
+    a = good(); a.dk = 0x1008
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = good(); a.dtype = binding.PLX_F32
+    assert call(a) == binding.PLX_ERR_DTYPE
+    a = good(); a.d = 96
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.Tkv = 64
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.scale = float("nan")
+    assert call(a) == binding.PLX_ERR_SCALE
+    a = good(); a.workspace_bytes -= 1
+    assert call(a) == binding.PLX_ERR_WORKSPACE
+    # the forward's row cache: both pointers or neither, bf16 with the probe and no window
+    f = binding.plx_prefill_args()
+    f.q = f.r = f.k = f.v = f.o = 0x1000
+    f.B, f.Hq, f.Hkv, f.T, f.d = 1, 4, 2, 128, 128
+    for name, H in (("q_stride", 4), ("r_stride", 4), ("o_stride", 4), ("k_stride", 2), ("v_stride", 2)):
+        setattr(f, name, (ctypes.c_int64 * 3)(H * 128 * 128, 128 * 128, 128))
+    f.scale, f.causal, f.use_r, f.dtype = 0.1, 1, 1, binding.PLX_BF16
+    f.vbar = 0x3000
+    assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_NULL
+    f.row_stats = 0x4000
+    f.window = 16
+    assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_SHAPE
+    f.window, f.use_r = 0, 0
+    assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_SHAPE

@@ -1,0 +1,137 @@
+"""GPU parity of parallax_prefill_backward (through the C ABI) against the backward oracle
+(closed forms of the paper's App. D in float64, pinned by tests/test_oracle_backward.py), and of
+the row cache the forward writes for it."""
+import numpy as np
+import pytest
+import torch
+
+from parity import BF16_REL_L2, host, rel_l2
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+LOG2E = 1.4426950408889634
+
+
+@pytest.fixture(scope="module")
+def plx():
+    from paper_2605_29157_amd import binding
+
+    binding.load_library()
+    assert torch.cuda.is_available()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def synth():
+    from paper_2605_29157_amd import synth as s
+
+    return s
+
+
+@pytest.fixture(scope="module")
+def bwd_oracle():
+    from oracle import parallax_backward
+
+    return parallax_backward
+
+
+def _inputs(synth, B, Hq, Hkv, T, Tkv, d, seed, r_scale=1.0):
+    y = synth.prefill_inputs(B, Hq, Hkv, Tkv, d, seed=seed, device=DEV, r_scale=r_scale)
+    if Tkv > T:
+        y["q"], y["r"] = y["q"][:, :, Tkv - T:].contiguous(), y["r"][:, :, Tkv - T:].contiguous()
+    g = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=seed + 1, device=DEV)["q"].contiguous()  # N(0,1) bf16
+    return y, g
+
+
+def _run(plx, y, g, causal):
+    o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=causal,
+                                          save_for_backward=True)
+    grads = plx.parallax_prefill_backward(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g, y["scale"],
+                                          causal=causal)
+    torch.cuda.synchronize()
+    return o, vbar, stats, grads
+
+
+def _check(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, causal, seed, r_scale=1.0, tol=BF16_REL_L2):
+    y, g = _inputs(synth, B, Hq, Hkv, T, Tkv, d, seed, r_scale)
+    _, _, _, grads = _run(plx, y, g, causal)
+    want = bwd_oracle.backward(*(host(y[n]) for n in "qrkv"), host(g), y["scale"], causal=causal)
+    for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
+        got = host(got)
+        assert np.isfinite(got).all(), name
+        # (a gradient that is exactly zero -- dQ and dR of a row with one key -- has no relative
+        # error: allow an absolute 1e-3 rms on top)
+        err = np.linalg.norm(got - ref)
+        assert err <= tol * np.linalg.norm(ref) + 1e-3 * np.sqrt(ref.size), (
+            name, err, np.linalg.norm(ref), B, Hq, Hkv, T, Tkv, d, causal)
+
+
+@pytest.mark.parametrize("T", [1, 31, 64, 65, 128, 129, 300, 513])
+@pytest.mark.parametrize("causal", [True, False])
+def test_backward_small_lengths(plx, synth, bwd_oracle, T, causal):
+    # One key per row: the weight 1 + ubar - u is 1 exactly, but the forward's ubar = d2 / d1
+    # carries the bf16 rounding of P2 = p * u (|u| * 2^-9 with |u| ~ sqrt(d)), which nothing
+    # averages out here: 3 % instead of the 0.3 % of longer rows.
+    _check(plx, synth, bwd_oracle, 2, 4, 2, T, T, 128, causal, seed=2000 + T,
+           tol=BF16_REL_L2 if T > 1 else 5 * BF16_REL_L2)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(2, 2, 128), (8, 2, 128), (8, 1, 128), (6, 2, 64), (4, 4, 64)])
+def test_backward_gqa_groups_and_head_dims(plx, synth, bwd_oracle, Hq, Hkv, d):
+    """The gradients of a KV head add up over the query heads of its group."""
+    _check(plx, synth, bwd_oracle, 2, Hq, Hkv, 200, 200, d, True, seed=2100 + Hq + d)
+
+
+@pytest.mark.parametrize("T,Tkv,causal", [(128, 1000, True), (200, 777, True), (5, 300, True), (100, 333, False)])
+def test_backward_more_keys_than_rows(plx, synth, bwd_oracle, T, Tkv, causal):
+    _check(plx, synth, bwd_oracle, 1, 8, 2, T, Tkv, 128, causal, seed=2200 + T)
+
+
+def test_backward_small_probe_and_zero_probe(plx, synth, bwd_oracle):
+    _check(plx, synth, bwd_oracle, 1, 4, 2, 400, 400, 128, True, seed=2300, r_scale=0.1)
+    # R = 0: dQ, dK, dV are those of softmax attention; dR is the value/key covariance term
+    y, g = _inputs(synth, 1, 4, 2, 300, 300, 128, 2301)
+    y["r"] = torch.zeros_like(y["r"])
+    _, _, _, grads = _run(plx, y, g, True)
+    want = bwd_oracle.backward(*(host(y[n]) for n in "qrkv"), host(g), y["scale"], causal=True)
+    for got, ref in zip(grads, want):
+        assert rel_l2(host(got), ref) <= BF16_REL_L2
+
+
+def test_forward_row_cache(plx, synth, bwd_oracle):
+    """save_for_backward changes nothing in o and adds vbar = sum_j p_j v_j, the log-sum-exp of
+    the scaled scores (exp2 domain) and ubar."""
+    for causal in (True, False):
+        y, g = _inputs(synth, 2, 4, 2, 333, 333, 128, 2400)
+        o, vbar, stats, _ = _run(plx, y, g, causal)
+        plain = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=causal)
+        np.testing.assert_array_equal(host(o), host(plain))
+        _, vb, ub, lw = bwd_oracle.forward_with_cache(*(host(y[n]) for n in "qrkv"), y["scale"], causal=causal)
+        assert rel_l2(host(vbar), vb) <= BF16_REL_L2
+        st = host(stats)
+        np.testing.assert_allclose(st[..., 0], lw * LOG2E, rtol=0, atol=2e-2)
+        assert rel_l2(st[..., 1], ub) <= BF16_REL_L2
+
+
+def test_backward_is_deterministic_and_conserves(plx, synth):
+    y, g = _inputs(synth, 2, 8, 2, 500, 500, 128, 2500)
+    _, _, _, a = _run(plx, y, g, True)
+    _, _, _, b = _run(plx, y, g, True)
+    for x, z in zip(a, b):
+        assert torch.equal(x, z)
+    # key-translation invariance of the forward: sum_j dK_j = 0 (up to bf16 rounding of 500 terms);
+    # value translation: sum_j dV_j = sum_i dO_i per KV head
+    dk, dv = a[2].float(), a[3].float()
+    assert dk.sum(dim=2).abs().max().item() <= 2e-2 * dk.abs().sum(dim=2).max().item()
+    want = g.float().reshape(2, 2, 4, 500, 128).sum(dim=(2, 3))
+    assert (dv.sum(dim=2) - want).abs().max().item() <= 2e-2 * want.abs().max().item() + 0.5
+
+
+def test_backward_config4_shape_sampled(plx, synth, bwd_oracle):
+    """One batch entry of benchmark configuration 4 (T = 4096, 16 query / 8 KV heads, d = 128): full
+    oracle gradients of two KV heads' groups against the kernel's."""
+    y, g = _inputs(synth, 1, 4, 2, 4096, 4096, 128, 2600)
+    _, _, _, grads = _run(plx, y, g, True)
+    want = bwd_oracle.backward(*(host(y[n]) for n in "qrkv"), host(g), y["scale"], causal=True)
+    for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
+        assert rel_l2(host(got), ref) <= BF16_REL_L2, name
