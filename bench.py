@@ -49,9 +49,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-extra", action="store_true", help="skip the sweep / prefill lines")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["decode", "prefill", "sweep"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "prefill", "backward", "sweep"], default="decode",
                     help="decode = config 2 (the headline line); prefill = config 4 causal "
-                         "prefill alone, for profiling that kernel; sweep = the config 3 decode "
+                         "prefill alone, for profiling that kernel; backward = the backward pass "
+                         "of that prefill shape; sweep = the config 3 decode "
                          "grid (B x L, fixed and ragged lengths, d = 128 and 64), one JSON line")
     ap.add_argument("--decode-shape", default="8,4096", metavar="B,L",
                     help="batch and KV length of the decode workload (default 8,4096 = config 2; "
@@ -85,6 +86,9 @@ def main():
 
     if opt.workload == "prefill":
         print(json.dumps(prefill_line(torch, plx, synth, dev, opt)))
+        return
+    if opt.workload == "backward":
+        print(json.dumps(backward_line(torch, plx, synth, dev, opt)))
         return
     if opt.workload == "sweep":
         print(json.dumps(decode_sweep(torch, plx, synth, lib, dev, sptr)))
@@ -233,6 +237,53 @@ def prefill_line(torch, plx, synth, dev, opt):
                      "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES["config4_prefill"] if is_config4 else None,
                      "kernel": "prefill_bf16_kernel<128,true,true>",
+                     "kernel_us": round(us, 1)},
+    }
+
+
+def backward_line(torch, plx, synth, dev, opt):
+    """Backward pass of the causal prefill shape (default config 4): rows prepare + dQ/dR pass +
+    dK/dV pass, from the row cache a forward call left behind. 22 d flops per allowed (row, key)
+    pair: eleven contractions of 2 d flops (five in the row pass, six in the column pass)."""
+    B, T = (int(v) for v in opt.prefill_shape.split(","))
+    Hq, Hkv, d = 16, 8, 128
+    y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1004, device=dev, k_offset_sigma=0.5)
+    g = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1014, device=dev)["q"].contiguous()
+    o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True,
+                                          save_for_backward=True)
+    dq, dr = torch.empty_like(y["q"]), torch.empty_like(y["q"])
+    dk, dv = torch.empty_like(y["k"]), torch.empty_like(y["k"])
+    ws = torch.empty(plx.parallax_prefill_backward_workspace_bytes(B, Hq, T) // 4,
+                     dtype=torch.float32, device=dev)
+    a = plx.prefill_bwd_args(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g, dq, dr, dk, dv,
+                             y["scale"], True, ws)
+    lib = plx.load_library()
+    sptr = int(torch.cuda.current_stream().cuda_stream)
+    steps = min(opt.steps, 20)
+    warm = min(opt.warmup, 3)
+
+    def step():
+        st = lib.parallax_prefill_backward(ctypes.byref(a), sptr)
+        if st != 0:
+            raise plx.ParallaxError(st, "parallax_prefill_backward")
+
+    us = _time_events(torch, step, warm, steps)
+    fwd_us = _time_events(
+        torch, lambda: plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True,
+                                            out=o), warm, steps)
+    flops = B * Hq * 22 * d * T * (T + 1) / 2
+    tf = flops / us / 1e6
+    return {
+        "metric": "prefill_backward_bf16_throughput", "value": round(tf, 1), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(us / 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "backward of causal prefill bf16 B=%d T=%d Hq=16 Hkv=8 d=128, "
+                               "K offset N(0,0.5^2)" % (B, T),
+                   "algorithmic_flops": flops, "forward_ms": round(fwd_us / 1e3, 4)},
+        "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "bwd_dq_dr_kernel<128,true> + bwd_dk_dv_kernel<128,true>",
                      "kernel_us": round(us, 1)},
     }
 

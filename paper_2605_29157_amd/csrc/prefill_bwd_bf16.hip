@@ -35,18 +35,21 @@ namespace {
 constexpr int kTileRows = 64;  // rows (keys or query rows) per LDS tile
 constexpr int kBlk = 32;       // rows per MFMA block
 
+// Every tile is read both ways -- whole chunks of 32 consecutive rows (A / B operand of a score
+// MFMA) and transposed, 4 consecutive rows x 4 chunks (A operand of an output MFMA) -- so rows are
+// not padded but their chunks permuted (lds_chunk_slot): both patterns then spread over all banks.
 template <int D>
 struct BwdTile {
-    static constexpr int CPR = D / 8;           // 16-byte chunks per row
-    static constexpr int ROWP = CPR + 4;        // padded row stride: the 4 rows of a transposing
-                                                // read land in 4 different 64-byte bank groups
-    static constexpr int CHUNKS = kTileRows * ROWP;
-    static constexpr int NDMA = CHUNKS / 256;   // loads per wave and tile
+    static constexpr int CPR = D / 8;  // 16-byte chunks per row
+    static constexpr int CHUNKS = kTileRows * CPR;
+    static constexpr int NDMA = CHUNKS / 256;  // loads per wave and tile
     static_assert(CHUNKS % 256 == 0, "four waves fill a tile with whole 64-lane loads");
 };
 
-// Rows [row0, row0 + 64) of a row-major [n_rows][D] bf16 matrix -> padded LDS tile. Rows past
-// the end re-read the last row (finite data; masked where it matters). Each wave fills a quarter.
+// Rows [row0, row0 + 64) of a row-major [n_rows][D] bf16 matrix -> LDS tile. A wave-wide load
+// fills 64 consecutive LDS chunks, so every lane fetches the global chunk that belongs at its
+// LDS position. Rows past the end re-read the last row (finite data; masked where it matters).
+// Each wave fills a quarter.
 template <int D>
 __device__ __forceinline__ void load_tile64(const __bf16 *base, int row0, int n_rows,
                                             uint32_t lds_tile_addr, int w, int lane) {
@@ -54,12 +57,44 @@ __device__ __forceinline__ void load_tile64(const __bf16 *base, int row0, int n_
 #pragma unroll
     for (int i = 0; i < TL::NDMA; ++i) {
         const int c = (w * TL::NDMA + i) * 64 + lane;
-        const int row = c / TL::ROWP;
-        const int pos = min(c % TL::ROWP, TL::CPR - 1);  // padding re-fetches a neighbour
-        const __bf16 *g = base + (int64_t)min(row0 + row, n_rows - 1) * D + pos * 8;
+        const int row = c / TL::CPR;
+        const int chunk = (c % TL::CPR) ^ lds_row_swizzle<D>(row);
+        const __bf16 *g = base + (int64_t)min(row0 + row, n_rows - 1) * D + chunk * 8;
         tile_load16<64>(g, lds_tile_addr + (uint32_t)(w * TL::NDMA + i) * 1024u);
     }
 }
+
+// Per-lane chunk offsets of the two read patterns inside a 32-row block (they repeat every 16
+// rows, so one set serves every block of every tile).
+template <int D>
+struct BwdLaneOffsets {
+    static constexpr int CPR = D / 8, KSTEPS = D / 16, NDB = D / 32;
+    int nt[KSTEPS];             // whole chunk 2*ks + h of row col: u32x4 index
+    int tr_lo[NDB], tr_hi[NDB];  // transposing reads of rows tr_row / tr_row + 8: bf16 index
+
+    __device__ __forceinline__ BwdLaneOffsets(int lane) {
+        const int col = lane & 31, h = lane >> 5;
+        const int f = lds_row_swizzle<D>(col);
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) nt[ks] = col * CPR + ((2 * ks + h) ^ f);
+        // lane -> (row, chunk, half) inside a [4 rows][16 elements] group of a transposing read
+        const int tr_row = 4 * h + ((lane & 15) >> 2);
+        const int tr_half = (lane & 1) * 4;
+        const int tr_chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+#pragma unroll
+        for (int n = 0; n < NDB; ++n) {
+            tr_lo[n] = (tr_row * CPR + ((4 * n + tr_chunk) ^ lds_row_swizzle<D>(tr_row))) * 8 + tr_half;
+            tr_hi[n] = ((tr_row + 8) * CPR + ((4 * n + tr_chunk) ^ lds_row_swizzle<D>(tr_row + 8))) * 8 + tr_half;
+        }
+    }
+    // A operand with row = dim 32n + col, k-elements = rows 16j + 4h..+3 and 16j + 8 + 4h..+3 of
+    // the 32-row block that starts at tile16
+    __device__ __forceinline__ u32x4 transposed(const unsigned short *block16, int j, int n) const {
+        const u32x2 lo = lds_read_tr16(block16 + 16 * j * CPR * 8 + tr_lo[n]);
+        const u32x2 hi = lds_read_tr16(block16 + 16 * j * CPR * 8 + tr_hi[n]);
+        return u32x4{lo[0], lo[1], hi[0], hi[1]};
+    }
+};
 
 __device__ __forceinline__ u32x4 pack_group(const f32x16 &s, int j) {
     return u32x4{pack_bf16(s[8 * j + 0], s[8 * j + 1]), pack_bf16(s[8 * j + 2], s[8 * j + 3]),
@@ -105,7 +140,7 @@ __global__ __launch_bounds__(256) void bwd_rows_prepare_kernel(PrefillBwdParams 
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     using TL = BwdTile<D>;
-    constexpr int ROWP = TL::ROWP, KSTEPS = D / 16, NDB = D / 32;
+    constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
     __shared__ u32x4 lds[2 * 2 * TL::CHUNKS];  // [stage][K tile | V tile]
 
     const int tid = threadIdx.x;
@@ -132,6 +167,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     const f32x4 rc = ((const f32x4 *)p.row_cache)[((int64_t)b * p.Hq + hq) * T + ld_row];
     const float lse = rc[0], ubar = rc[1], tau = rc[2], beta = rc[3];
     const float scale_log2 = p.scale * kLog2e;
+    const BwdLaneOffsets<D> lo(lane);
 
     const __bf16 *kbase = (const __bf16 *)p.k + ((int64_t)b * p.Hkv + hk) * Tk * D;
     const __bf16 *vbase = (const __bf16 *)p.v + ((int64_t)b * p.Hkv + hk) * Tk * D;
@@ -143,35 +179,32 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
 
     const int key_end = CAUSAL ? min(Tk, (rb + 1) * 128 + off) : Tk;
     const int n_tiles = (key_end + kTileRows - 1) / kTileRows;
+    const int wave_key_end = CAUSAL ? min(Tk, row0 + 32 + off) : Tk;  // keys some row of this wave sees
 
     f32x16 dq[NDB], dr[NDB];
 #pragma unroll
     for (int n = 0; n < NDB; ++n) dq[n] = dr[n] = zero16();
-
-    // transposing reads: lane -> (row, chunk, half) inside a [4 rows][16 elements] group
-    const int tr_row = 4 * h + ((lane & 15) >> 2);
-    const int tr_half = (lane & 1) * 4;
-    const int tr_chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-    const int tr_lane_off = (tr_row * ROWP + tr_chunk) * 8 + tr_half;  // in bf16 elements
 
     issue_tile(0, 0);
     for (int t = 0; t < n_tiles; ++t) {
         const int stage = t & 1;
         tile_barrier<0>();  // tile t has landed; everybody is done with tile t - 1
         if (t + 1 < n_tiles) issue_tile(t + 1, stage ^ 1);
+        if (t * kTileRows >= wave_key_end) continue;  // wave-uniform: nothing of this tile is visible
         const u32x4 *tk = lds + stage * 2 * TL::CHUNKS;
         const u32x4 *tv = tk + TL::CHUNKS;
+        // (one 32-key block at a time: with both blocks of a tile in flight the kernel needs
+        // more registers than a wave has, and the copies between the two register files that
+        // follow cost more than the overlap gains)
 #pragma unroll 1
-        for (int kb = 0; kb < kTileRows / kBlk; ++kb) {
+        for (int kb = 0; kb < 2; ++kb) {
             const int key_base = t * kTileRows + kb * kBlk;
-            // wave-uniform: does any row of this wave see a key of the block?
-            if (key_base >= Tk || (CAUSAL && key_base > row0 + 31 + off)) continue;
+            if (key_base >= wave_key_end) break;  // wave-uniform
             f32x16 s1 = zero16(), s2 = zero16(), aa = zero16();
-            const u32x4 *kfp = tk + (kb * kBlk + col) * ROWP + h;
-            const u32x4 *vfp = tv + (kb * kBlk + col) * ROWP + h;
+            const u32x4 *kfp = tk + kb * kBlk * CPR, *vfp = tv + kb * kBlk * CPR;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
-                const u32x4 kf = kfp[2 * ks], vf = vfp[2 * ks];
+                const u32x4 kf = kfp[lo.nt[ks]], vf = vfp[lo.nt[ks]];
                 s1 = mfma32(kf, qf[ks], s1);
                 s2 = mfma32(kf, rf[ks], s2);
                 aa = mfma32(vf, gf[ks], aa);
@@ -186,26 +219,18 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
                 s1[r] = pr * (aa[r] - tau + (ubar - s2[r]) * dlt);  // g1
                 s2[r] = -pr * dlt;                                  // g2
             }
-            u32x4 pg1[2], pg2[2];
+            // dQ^T += K^T g1^T, dR^T += K^T g2^T: the accumulator registers are the B operands
+            const unsigned short *kb16 = (const unsigned short *)(tk + kb * kBlk * CPR);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                pg1[j] = pack_group(s1, j);
-                pg2[j] = pack_group(s2, j);
-            }
-            // dQ^T += K^T g1^T, dR^T += K^T g2^T. A operand: row = dim 32n + col, k-elements =
-            // the 8 keys of the B operand (keys 16j+4h..+3 and 16j+8+4h..+3 of the block)
-            const unsigned short *tk16 = (const unsigned short *)tk + tr_lane_off + kb * kBlk * ROWP * 8;
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
+                const u32x4 pg1 = pack_group(s1, j), pg2 = pack_group(s2, j);
 #pragma unroll
                 for (int n = 0; n < NDB; ++n) {
-                    const int o = (16 * j * ROWP + 4 * n) * 8;
-                    const u32x2 lo = lds_read_tr16(tk16 + o);
-                    const u32x2 hi = lds_read_tr16(tk16 + o + 8 * ROWP * 8);
-                    const u32x4 kt = {lo[0], lo[1], hi[0], hi[1]};
-                    dq[n] = mfma32(kt, pg1[j], dq[n]);
-                    dr[n] = mfma32(kt, pg2[j], dr[n]);
+                    const u32x4 kt = lo.transposed(kb16, j, n);
+                    dq[n] = mfma32(kt, pg1, dq[n]);
+                    dr[n] = mfma32(kt, pg2, dr[n]);
                 }
+            }
         }
     }
 
@@ -232,7 +257,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     using TL = BwdTile<D>;
-    constexpr int ROWP = TL::ROWP, KSTEPS = D / 16, NDB = D / 32;
+    constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
     constexpr int STAGE = 3 * TL::CHUNKS + kTileRows;  // Q, R, dO tiles + one float4 per row
     __shared__ u32x4 lds[2 * STAGE];
 
@@ -255,12 +280,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         vf[ks] = *(const u32x4 *)((const __bf16 *)p.v + krow + 8 * (2 * ks + h));
     }
     const float scale_log2 = p.scale * kLog2e;
+    const BwdLaneOffsets<D> lo(lane);
 
     // row tiles that hold a row which sees a key of this block: rows i >= key - off
     const int rt_lo = CAUSAL ? max(cb * 128 - off, 0) / kTileRows : 0;
     const int n_rt = (T + kTileRows - 1) / kTileRows;
     const int per_head = n_rt - rt_lo;
     const int n_items = per_head * G;  // (head of the group, row tile)
+    const int wave_row_lo = CAUSAL ? key0 - off : 0;  // first row that sees a key of this wave
 
     const uint32_t lds_base = lds_byte_address(lds);
     auto issue_item = [&](int it, int stage) {
@@ -281,35 +308,29 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
 #pragma unroll
     for (int n = 0; n < NDB; ++n) dk[n] = dv[n] = zero16();
 
-    const int tr_row = 4 * h + ((lane & 15) >> 2);
-    const int tr_half = (lane & 1) * 4;
-    const int tr_chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-    const int tr_lane_off = (tr_row * ROWP + tr_chunk) * 8 + tr_half;
-
     if (n_items > 0) issue_item(0, 0);
     for (int it = 0; it < n_items; ++it) {
         const int stage = it & 1;
         tile_barrier<0>();
         if (it + 1 < n_items) issue_item(it + 1, stage ^ 1);
         const int rt = rt_lo + it % per_head;
+        if (rt * kTileRows + kTileRows <= wave_row_lo) continue;  // wave-uniform: no row of the tile sees us
         const u32x4 *tq = lds + stage * STAGE;
         const u32x4 *tr_ = tq + TL::CHUNKS;
         const u32x4 *tg = tq + 2 * TL::CHUNKS;
         const f32x4 *rows = (const f32x4 *)(tq + 3 * TL::CHUNKS);
 #pragma unroll 1
-        for (int rbk = 0; rbk < kTileRows / kBlk; ++rbk) {
+        for (int rbk = 0; rbk < 2; ++rbk) {
             const int row_base = rt * kTileRows + rbk * kBlk;
-            // wave-uniform: does any row of the block see a key of this wave?
-            if (row_base >= T || (CAUSAL && row_base + 31 + off < key0)) continue;
+            // wave-uniform: does any row of the block exist and see a key of this wave?
+            if (row_base >= T || row_base + kBlk <= wave_row_lo) continue;
             f32x16 s1 = zero16(), s2 = zero16(), aa = zero16();
-            const u32x4 *qfp = tq + (rbk * kBlk + col) * ROWP + h;
-            const u32x4 *rfp = tr_ + (rbk * kBlk + col) * ROWP + h;
-            const u32x4 *gfp = tg + (rbk * kBlk + col) * ROWP + h;
+            const u32x4 *qfp = tq + rbk * kBlk * CPR, *rfp = tr_ + rbk * kBlk * CPR, *gfp = tg + rbk * kBlk * CPR;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
-                s1 = mfma32(qfp[2 * ks], kf[ks], s1);
-                s2 = mfma32(rfp[2 * ks], kf[ks], s2);
-                aa = mfma32(gfp[2 * ks], vf[ks], aa);
+                s1 = mfma32(qfp[lo.nt[ks]], kf[ks], s1);
+                s2 = mfma32(rfp[lo.nt[ks]], kf[ks], s2);
+                aa = mfma32(gfp[lo.nt[ks]], vf[ks], aa);
             }
             // accumulator register r <-> row row_base + 8*(r/4) + 4*h + r%4, column = my_key
             f32x16 wgt;
@@ -326,21 +347,17 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
                 s1[r] = pr * (aa[r] - rc[2] + um * dlt) * p.scale;  // g1 / h
                 s2[r] = -pr * dlt;                                  // g2
             }
-            const unsigned short *tq16 = (const unsigned short *)tq + tr_lane_off + rbk * kBlk * ROWP * 8;
-            const unsigned short *tr16 = (const unsigned short *)tr_ + tr_lane_off + rbk * kBlk * ROWP * 8;
-            const unsigned short *tg16 = (const unsigned short *)tg + tr_lane_off + rbk * kBlk * ROWP * 8;
+            const unsigned short *q16 = (const unsigned short *)(tq + rbk * kBlk * CPR);
+            const unsigned short *r16 = (const unsigned short *)(tr_ + rbk * kBlk * CPR);
+            const unsigned short *g16 = (const unsigned short *)(tg + rbk * kBlk * CPR);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const u32x4 pw = pack_group(wgt, j), pg1 = pack_group(s1, j), pg2 = pack_group(s2, j);
 #pragma unroll
                 for (int n = 0; n < NDB; ++n) {
-                    const int o = (16 * j * ROWP + 4 * n) * 8;
-                    const u32x2 glo = lds_read_tr16(tg16 + o), ghi = lds_read_tr16(tg16 + o + 8 * ROWP * 8);
-                    const u32x2 qlo = lds_read_tr16(tq16 + o), qhi = lds_read_tr16(tq16 + o + 8 * ROWP * 8);
-                    const u32x2 rlo = lds_read_tr16(tr16 + o), rhi = lds_read_tr16(tr16 + o + 8 * ROWP * 8);
-                    dv[n] = mfma32(u32x4{glo[0], glo[1], ghi[0], ghi[1]}, pw, dv[n]);
-                    dk[n] = mfma32(u32x4{qlo[0], qlo[1], qhi[0], qhi[1]}, pg1, dk[n]);
-                    dk[n] = mfma32(u32x4{rlo[0], rlo[1], rhi[0], rhi[1]}, pg2, dk[n]);
+                    dv[n] = mfma32(lo.transposed(g16, j, n), pw, dv[n]);
+                    dk[n] = mfma32(lo.transposed(q16, j, n), pg1, dk[n]);
+                    dk[n] = mfma32(lo.transposed(r16, j, n), pg2, dk[n]);
                 }
             }
         }
