@@ -41,6 +41,7 @@
 #include "plx_device.h"
 #include "plx_kernels.h"
 #include "plx_lds_dma.h"
+#include "plx_mfma_asm.h"
 
 namespace plx {
 
@@ -55,17 +56,6 @@ constexpr int kBR = 128;  // query rows per workgroup
 constexpr int kBC = 64;   // keys per LDS tile
 constexpr int kKB = 32;   // keys per inner block (one MFMA row block)
 
-// The score MFMAs of the pipelined loop are emitted as inline assembly with VECTOR-register
-// destinations: their results feed the exp arithmetic directly. (With the compiler's choice,
-// accumulation registers, every score has to be copied out first, and such copies stall while
-// MFMAs are in flight: measured +6 cycles per copy, ~100 copies per 64-key tile.) The compiler
-// does not know these statements are MFMAs, so the two hazards it would otherwise cover are
-// handled here: the first read of a finished score block is kept >= 16 issue slots behind its
-// last MFMA (s_nop below; the ISA asks for 11 after an 8-pass MFMA), and operand order is
-// pinned by the scheduling fences of the pipeline.
-#ifndef PLX_PF_ASM_SCORES
-#define PLX_PF_ASM_SCORES 1
-#endif
 
 // Same load with a wave-uniform tile base (scalar registers) plus a 32-bit per-lane byte offset:
 // no per-lane 64-bit address arithmetic. M0 is not restored: nothing the compiler emits for this
@@ -116,41 +106,6 @@ __device__ unsigned long long plx_pf_stamps[8192 * 12];
 #define PLX_STAMP(slot) ((void)0)
 #endif
 
-
-// An MFMA may not read a register that a vector-ALU instruction wrote less than two wait states
-// before it (the hardware does not interlock this). For MFMAs the compiler knows about it keeps
-// that distance itself; for these statements it cannot, and it does place copies directly in
-// front of a statement's operands when it parks the Q/R fragments in accumulation registers.
-// GUARD = true brings two wait states along. GUARD = false is for the steady-state loop, where
-// the generated code has no such copy -- the build verifies that on the assembly it produced
-// (asm_check.py) and fails otherwise.
-// acc = A * B (first k-step) and acc += A * B, 32x32x16 bf16, all operands in vector registers.
-template <bool GUARD>
-__device__ __forceinline__ void mfma32_scores_first(f32x16 &acc, u32x4 a, u32x4 b) {
-#if PLX_PF_ASM_SCORES
-    // early clobber: the destination block must not share registers with A or B
-    if constexpr (GUARD)
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
-    else
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0 ; unguarded" : "=&v"(acc) : "v"(a), "a"(b));
-#else
-    f32x16 z;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) z[r] = 0.f;
-    acc = mfma32(a, b, z);
-#endif
-}
-template <bool GUARD>
-__device__ __forceinline__ void mfma32_scores(f32x16 &acc, u32x4 a, u32x4 b) {
-#if PLX_PF_ASM_SCORES
-    if constexpr (GUARD)
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
-    else
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0 ; unguarded" : "+v"(acc) : "v"(a), "a"(b));
-#else
-    acc = mfma32(a, b, acc);
-#endif
-}
 
 template <int D, bool USE_R, bool CAUSAL, bool WINDOW, bool STATS = false>
 __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {

@@ -26,7 +26,10 @@
 // left to the compiler (no hand-placed slots as in the forward kernel).
 #include "plx_device.h"
 #include "plx_kernels.h"
+#include <type_traits>
+
 #include "plx_lds_dma.h"
+#include "plx_mfma_asm.h"
 
 namespace plx {
 
@@ -137,11 +140,21 @@ __global__ __launch_bounds__(256) void bwd_rows_prepare_kernel(PrefillBwdParams 
 }
 
 // ---- row pass: dQ, dR -------------------------------------------------------------------------
+// Software pipeline over 32-key blocks, written as slots of ONE MFMA plus its share of vector
+// work (the single wave of a SIMD issues in order, so vector instructions only run in the shadow
+// of an MFMA that was issued before them):
+//   phase 1 : the 3 * d/16 score MFMAs of the NEXT block (S1^T, S2^T, A^T alternate), while the
+//             vector ALU turns the upper 16 keys of the CURRENT block into g1 / g2;
+//   phase 2 : the output MFMAs of the CURRENT block (dQ^T, dR^T alternate), while the vector ALU
+//             already turns the lower 16 keys of the NEXT block into its g1 / g2.
+// Each slot that first uses an LDS fragment issues the read of the fragment needed three
+// fragments later ([K, V of the next block | K^T of the current block | K, V of the block after]).
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     using TL = BwdTile<D>;
     constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
-    __shared__ u32x4 lds[2 * 2 * TL::CHUNKS];  // [stage][K tile | V tile]
+    constexpr int STAGES = 3, STAGE_CHUNKS = 2 * TL::CHUNKS;  // ring of [K tile | V tile]
+    __shared__ u32x4 lds[STAGES * STAGE_CHUNKS];
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -165,74 +178,176 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
         gf[ks] = *(const u32x4 *)((const __bf16 *)p.d_o + qrow + 8 * (2 * ks + h));
     }
     const f32x4 rc = ((const f32x4 *)p.row_cache)[((int64_t)b * p.Hq + hq) * T + ld_row];
-    const float lse = rc[0], ubar = rc[1], tau = rc[2], beta = rc[3];
+    const float neg_lse = -rc[0], ubar = rc[1], tau = rc[2], beta = rc[3];
     const float scale_log2 = p.scale * kLog2e;
     const BwdLaneOffsets<D> lo(lane);
 
     const __bf16 *kbase = (const __bf16 *)p.k + ((int64_t)b * p.Hkv + hk) * Tk * D;
     const __bf16 *vbase = (const __bf16 *)p.v + ((int64_t)b * p.Hkv + hk) * Tk * D;
     const uint32_t lds_base = lds_byte_address(lds);
-    auto issue_tile = [&](int t, int stage) {
-        load_tile64<D>(kbase, t * kTileRows, Tk, lds_base + (uint32_t)(stage * 2 * TL::CHUNKS) * 16u, w, lane);
-        load_tile64<D>(vbase, t * kTileRows, Tk, lds_base + (uint32_t)((stage * 2 + 1) * TL::CHUNKS) * 16u, w, lane);
+    auto issue_tile = [&](int t, int stage) __attribute__((always_inline)) {
+        load_tile64<D>(kbase, t * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u, w, lane);
+        load_tile64<D>(vbase, t * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS + TL::CHUNKS) * 16u, w,
+                       lane);
     };
+    auto k_block = [&](int stage, int kb) __attribute__((always_inline)) { return (const u32x4 *)(lds + stage * STAGE_CHUNKS + kb * kBlk * CPR); };
 
     const int key_end = CAUSAL ? min(Tk, (rb + 1) * 128 + off) : Tk;
     const int n_tiles = (key_end + kTileRows - 1) / kTileRows;
-    const int wave_key_end = CAUSAL ? min(Tk, row0 + 32 + off) : Tk;  // keys some row of this wave sees
+    const int lim_row = CAUSAL ? min(my_row + off, Tk - 1) : Tk - 1;  // last key this lane's row sees
 
     f32x16 dq[NDB], dr[NDB];
 #pragma unroll
     for (int n = 0; n < NDB; ++n) dq[n] = dr[n] = zero16();
 
-    issue_tile(0, 0);
-    for (int t = 0; t < n_tiles; ++t) {
-        const int stage = t & 1;
-        tile_barrier<0>();  // tile t has landed; everybody is done with tile t - 1
-        if (t + 1 < n_tiles) issue_tile(t + 1, stage ^ 1);
-        if (t * kTileRows >= wave_key_end) continue;  // wave-uniform: nothing of this tile is visible
-        const u32x4 *tk = lds + stage * 2 * TL::CHUNKS;
-        const u32x4 *tv = tk + TL::CHUNKS;
-        // (one 32-key block at a time: with both blocks of a tile in flight the kernel needs
-        // more registers than a wave has, and the copies between the two register files that
-        // follow cost more than the overlap gains)
-#pragma unroll 1
-        for (int kb = 0; kb < 2; ++kb) {
-            const int key_base = t * kTileRows + kb * kBlk;
-            if (key_base >= wave_key_end) break;  // wave-uniform
-            f32x16 s1 = zero16(), s2 = zero16(), aa = zero16();
-            const u32x4 *kfp = tk + kb * kBlk * CPR, *vfp = tv + kb * kBlk * CPR;
+    // fragments in flight
+    constexpr int NF1 = 2 * KSTEPS, NF2 = 2 * NDB, LA = 3;
+    u32x4 f1[NF1], f2[NF2];
+    auto load_f1 = [&](const u32x4 *kblk, int f) __attribute__((always_inline)) {  // even: K chunk, odd: V chunk of k-step f / 2
+        f1[f] = (f & 1) ? kblk[TL::CHUNKS + lo.nt[f >> 1]] : kblk[lo.nt[f >> 1]];
+    };
+    auto load_f2 = [&](const u32x4 *kblk, int f) __attribute__((always_inline)) {
+        f2[f] = lo.transposed((const unsigned short *)kblk, f / NDB, f % NDB);
+    };
+    auto prefetch = [&](int f, const u32x4 *next_blk, const u32x4 *cur_blk, const u32x4 *after_blk) __attribute__((always_inline)) {
+        const int g = f + LA;
+        if (g < NF1)
+            load_f1(next_blk, g);
+        else if (g < NF1 + NF2)
+            load_f2(cur_blk, g - NF1);
+        else
+            load_f1(after_blk, g - NF1 - NF2);
+    };
+
+    // Element-wise work of the 8 score registers [r0, r0 + 8) of a block, as four stages in
+    // consecutive slots so that a slot holds independent instructions only; the results replace
+    // the scores: g1 in aa, g2 in s2. Register r holds key offset 8*(r/4) + r%4 (+ 4h, already
+    // taken off lim).
+    float dl[8];
+    auto elem_stages = [&](auto masked_tag, f32x16 &s1, f32x16 &s2, f32x16 &aa, int r0, int slot, int slot0,
+                           int n_slots, int lim) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                const u32x4 kf = kfp[lo.nt[ks]], vf = vfp[lo.nt[ks]];
-                s1 = mfma32(kf, qf[ks], s1);
-                s2 = mfma32(kf, rf[ks], s2);
-                aa = mfma32(vf, gf[ks], aa);
+        for (int u = 0; u < 8; ++u) {
+            const int r = r0 + u;
+            const int first = slot0 + u * (n_slots - 6 - slot0) / 7;
+            if (slot == first) {
+                s1[r] = fmaf(s1[r], scale_log2, neg_lse);
+                dl[u] = aa[r] - beta;     // delta
+                s2[r] = ubar - s2[r];     // ubar - u
+                aa[r] = aa[r] - tau;
             }
-            // accumulator register r <-> key key_base + 8*(r/4) + 4*h + r%4, column = my_row
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = key_base + 8 * (r >> 2) + 4 * h + (r & 3);
-                const bool ok = key < Tk && (!CAUSAL || key <= my_row + off);
-                const float pr = ok ? fast_exp2(fmaf(s1[r], scale_log2, -lse)) : 0.f;
-                const float dlt = aa[r] - beta;
-                s1[r] = pr * (aa[r] - tau + (ubar - s2[r]) * dlt);  // g1
-                s2[r] = -pr * dlt;                                  // g2
+            if (slot == first + 1) {
+                s1[r] = fast_exp2(s1[r]);            // p
+                aa[r] = fmaf(s2[r], dl[u], aa[r]);   // a - tau + (ubar - u) delta
             }
-            // dQ^T += K^T g1^T, dR^T += K^T g2^T: the accumulator registers are the B operands
-            const unsigned short *kb16 = (const unsigned short *)(tk + kb * kBlk * CPR);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const u32x4 pg1 = pack_group(s1, j), pg2 = pack_group(s2, j);
-#pragma unroll
-                for (int n = 0; n < NDB; ++n) {
-                    const u32x4 kt = lo.transposed(kb16, j, n);
-                    dq[n] = mfma32(kt, pg1, dq[n]);
-                    dr[n] = mfma32(kt, pg2, dr[n]);
-                }
+            if constexpr (MASKED)
+                if (slot == first + 2) s1[r] = (8 * (r >> 2) + (r & 3) <= lim) ? s1[r] : 0.f;
+            if (slot == first + 3) {
+                aa[r] = s1[r] * aa[r];    // g1
+                s2[r] = -(s1[r] * dl[u]);  // g2
             }
         }
+    };
+
+    // The score MFMAs are assembly statements with vector-register destinations (their results
+    // feed the vector ALU; the compiler would put them in accumulation registers and copy every
+    // one out). Each brings two wait states for its operands; the first vector read of a block
+    // comes in slot 1 of phase 2, behind two more MFMAs: by then the block's last MFMA retired.
+    u32x4 pg1[2], pg2[2];
+    auto pipeline_step = [&](auto masked_tag, int key_base_cur, const u32x4 *next_blk, const u32x4 *cur_blk, const u32x4 *after_blk,
+                             f32x16 &c1, f32x16 &c2, f32x16 &ca, f32x16 &n1, f32x16 &n2, f32x16 &na) __attribute__((always_inline)) {
+        const int lim_cur = lim_row - key_base_cur - 4 * h, lim_next = lim_cur - kBlk;
+        constexpr int SLOTS1 = 3 * KSTEPS, SLOTS2 = 4 * NDB;
+#pragma unroll
+        for (int sl = 0; sl < SLOTS1; ++sl) {
+            const int ks = sl / 3, which = sl % 3;
+            if (which == 0) {
+                if (ks == 0) mfma32_scores_first<true>(n1, f1[2 * ks], qf[ks]);
+                else mfma32_scores<true>(n1, f1[2 * ks], qf[ks]);
+                prefetch(2 * ks, next_blk, cur_blk, after_blk);
+            } else if (which == 1) {
+                if (ks == 0) mfma32_scores_first<true>(n2, f1[2 * ks], rf[ks]);
+                else mfma32_scores<true>(n2, f1[2 * ks], rf[ks]);
+            } else {
+                if (ks == 0) mfma32_scores_first<true>(na, f1[2 * ks + 1], gf[ks]);
+                else mfma32_scores<true>(na, f1[2 * ks + 1], gf[ks]);
+                prefetch(2 * ks + 1, next_blk, cur_blk, after_blk);
+            }
+            elem_stages(masked_tag, c1, c2, ca, 8, sl, 0, SLOTS1, lim_cur);
+            if (sl == SLOTS1 - 2) pg1[1] = pack_group(ca, 1);
+            if (sl == SLOTS1 - 1) pg2[1] = pack_group(c2, 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        u32x4 nb1 = {0u, 0u, 0u, 0u}, nb2 = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int sl = 0; sl < SLOTS2; ++sl) {
+            const int j = sl / (2 * NDB), t = sl % (2 * NDB), n = t / 2, f = j * NDB + n;
+            if (t % 2 == 0) {
+                dq[n] = mfma32(f2[f], pg1[j], dq[n]);
+                prefetch(NF1 + f, next_blk, cur_blk, after_blk);
+            } else {
+                dr[n] = mfma32(f2[f], pg2[j], dr[n]);
+            }
+            elem_stages(masked_tag, n1, n2, na, 0, sl, 1, SLOTS2, lim_next);
+            if (sl == SLOTS2 - 2) nb1 = pack_group(na, 0);
+            if (sl == SLOTS2 - 1) nb2 = pack_group(n2, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        pg1[0] = nb1;
+        pg2[0] = nb2;
+    };
+
+    // Ring invariant at the top of iteration t: tiles t and (after the barrier) t + 1 are in
+    // stages t % 3 and (t + 1) % 3; the barrier also proves that nobody reads tile t - 1 any more,
+    // whose stage then receives tile t + 2.
+    issue_tile(0, 0);
+    if (n_tiles > 1) issue_tile(1, 1);
+    if (n_tiles > 1)
+        tile_barrier<2 * TL::NDMA>();  // tile 0 has landed (loads complete in order)
+    else
+        tile_barrier<0>();
+    f32x16 a1, a2, a3, b1, b2, b3;
+    {
+        // prologue: scores of block (0, 0); its lower 16 keys -> g1 / g2; first fragments of (0, 1)
+        const u32x4 *blk = k_block(0, 0);
+        a1 = a2 = a3 = zero16();
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const u32x4 kf = blk[lo.nt[ks]], vf = blk[TL::CHUNKS + lo.nt[ks]];
+            a1 = mfma32(kf, qf[ks], a1);
+            a2 = mfma32(kf, rf[ks], a2);
+            a3 = mfma32(vf, gf[ks], a3);
+        }
+#pragma unroll
+        for (int sl = 0; sl < 12; ++sl)
+            elem_stages(std::true_type{}, a1, a2, a3, 0, sl, 0, 12, lim_row - 4 * h);
+        pg1[0] = pack_group(a3, 0);
+        pg2[0] = pack_group(a2, 0);
+#pragma unroll
+        for (int f = 0; f < LA; ++f) load_f1(k_block(0, 1), f);
     }
+    int stage = 0;
+    auto tile_steps = [&](auto masked_tag, int t) __attribute__((always_inline)) {
+        const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
+        const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
+        tile_barrier<0>();  // tile t + 1 has landed; tile t - 1 is free
+        if (t + 2 < n_tiles) issue_tile(t + 2, free_stage);
+        // block (t, 0) -> g, dQ / dR; scores of (t, 1); fragments of (t + 1, 0)
+        pipeline_step(masked_tag, t * kTileRows, k_block(stage, 1), k_block(stage, 0), k_block(next_stage, 0), a1,
+                      a2, a3, b1, b2, b3);
+        // block (t, 1) -> g, dQ / dR; scores of (t + 1, 0); fragments of (t + 1, 1)
+        pipeline_step(masked_tag, t * kTileRows + kBlk, k_block(next_stage, 0), k_block(stage, 1),
+                      k_block(next_stage, 1), b1, b2, b3, a1, a2, a3);
+        stage = next_stage;
+    };
+    // tiles whose keys -- and those of the tile after (a step also prepares the lower half of the
+    // next block) -- every row of the workgroup sees: no masks; then the diagonal / tail tiles
+    const int n_full = min(CAUSAL ? (rb * 128 + off + 1) / kTileRows : Tk / kTileRows, Tk / kTileRows);
+    int t = 0;
+    for (; t < n_full - 1; ++t) tile_steps(std::false_type{}, t);
+    for (; t < n_tiles; ++t) tile_steps(std::true_type{}, t);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no tile load may land after the workgroup ends
 
     // dQ^T / dR^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of row my_row
     if (my_row < T) {
