@@ -88,9 +88,62 @@ def find_m0_uses_outside_inline_asm(asm_text: str) -> list[str]:
     return bad
 
 
+MFMA_RESULT_WAIT_STATES = 12  # an 8-pass MFMA result may be read by the vector ALU after 11
+MFMA_PASSES = 8               # v_mfma_f32_32x32x16_bf16: the pipe accepts the next one 8 states later
+
+
+def find_early_reads_of_asm_mfma_results(asm_text: str) -> list[str]:
+    """An MFMA written as inline assembly is invisible to the compiler, which therefore adds no
+    wait states between it and the first instruction that reads its result. The kernels place
+    that first read well behind the MFMA (other MFMAs and vector work in between). Verify it on
+    the generated code: between an assembly MFMA and the first non-MFMA instruction that reads
+    one of its destination registers there must be MFMA_RESULT_WAIT_STATES wait states -- one
+    per instruction (s_nop n: n + 1), MFMA_PASSES per further MFMA, which the matrix pipe only
+    accepts once the previous one is through. (A later MFMA that reads the block as its
+    accumulator input is the normal dependent chain.) This also catches register-allocator
+    copies or spills of a freshly written block."""
+    instrs = []  # (line number, text, inside inline assembly)
+    inside = False
+    for n, line in enumerate(asm_text.splitlines(), 1):
+        t = line.strip()
+        if t.startswith(";;#ASMSTART"):
+            inside = True
+            continue
+        if t.startswith(";;#ASMEND"):
+            inside = False
+            continue
+        if _is_instruction(line):
+            instrs.append((n, t.split(";")[0].strip(), inside))
+    bad = []
+    for i, (n, ins, inside) in enumerate(instrs):
+        if not (inside and ins.startswith("v_mfma")):
+            continue
+        dst = _regs(ins.split(None, 1)[1].split(",")[0])
+        states = 0
+        for pn, nxt, _ in instrs[i + 1:]:
+            if states >= MFMA_RESULT_WAIT_STATES or nxt.endswith(":") or nxt.startswith("s_endpgm"):
+                break
+            if nxt.startswith("v_mfma"):
+                states += MFMA_PASSES
+                continue
+            parts = nxt.split(None, 1)
+            if len(parts) == 2:
+                ops = parts[1].split(",")
+                # stores and LDS writes read every operand; everything else writes its first
+                stores = ("ds_write", "global_store", "scratch_store", "buffer_store")
+                reads = ops if parts[0].startswith(stores) else ops[1:]
+                if any(_regs(o) & dst for o in reads):
+                    bad.append("line %d: '%s' reads the result of the assembly MFMA at line %d after "
+                               "only %d wait states" % (pn, nxt, n, states))
+                    break
+            states += _wait_states(nxt)
+    return bad
+
+
 def check_file(path: str) -> None:
     with open(path) as f:
         text = f.read()
-    bad = find_violations(text) + find_m0_uses_outside_inline_asm(text)
+    bad = (find_violations(text) + find_m0_uses_outside_inline_asm(text)
+           + find_early_reads_of_asm_mfma_results(text))
     if bad:
         raise RuntimeError("MFMA source hazard in %s:\n  %s" % (path, "\n  ".join(bad[:20])))

@@ -42,16 +42,22 @@ def _compile(src: str, extra: list[str]) -> str:
     return obj
 
 
-def _check_prefill_assembly(extra: list[str]) -> None:
-    """Emit the device assembly of the prefill kernel and verify its hand-placed MFMAs."""
+def _check_prefill_assembly(extra: list[str], src: str = "prefill_bf16.hip", m0: bool = True) -> None:
+    """Emit the device assembly of a prefill kernel file and verify its hand-placed MFMAs."""
     from . import asm_check
-    asm = os.path.join(BUILD_DIR, "prefill_bf16.gfx950.s")
+    asm = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".gfx950.s")
     cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-S",
-           "--cuda-device-only", os.path.join(CSRC, "prefill_bf16.hip"), "-o", asm]
+           "--cuda-device-only", os.path.join(CSRC, src), "-o", asm]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc -S failed on prefill_bf16.hip:\n" + res.stdout)
-    asm_check.check_file(asm)
+        raise RuntimeError("hipcc -S failed on %s:\n%s" % (src, res.stdout))
+    if m0:
+        asm_check.check_file(asm)
+    else:  # the backward kernels restore M0 after every tile load and use guarded MFMAs only
+        with open(asm) as f:
+            bad = asm_check.find_early_reads_of_asm_mfma_results(f.read())
+        if bad:
+            raise RuntimeError("MFMA result hazard in %s:\n  %s" % (asm, "\n  ".join(bad[:20])))
 
 
 def _check_decode_assembly(extra: list[str]) -> None:
@@ -75,8 +81,10 @@ def build_library(extra_flags: list[str] | None = None, verbose: bool = True) ->
     """Compile every kernel file for gfx950 and link libparallax_hip.so next to this file."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     extra = list(extra_flags or [])
-    with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES) + 2) as pool:
-        checks = [pool.submit(_check_prefill_assembly, extra), pool.submit(_check_decode_assembly, extra)]
+    with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES) + 3) as pool:
+        checks = [pool.submit(_check_prefill_assembly, extra),
+                  pool.submit(_check_prefill_assembly, extra, "prefill_bwd_bf16.hip", False),
+                  pool.submit(_check_decode_assembly, extra)]
         objs = list(pool.map(lambda s: _compile(s, extra), SOURCES))
         for c in checks:
             c.result()

@@ -31,6 +31,10 @@
 #include "plx_lds_dma.h"
 #include "plx_mfma_asm.h"
 
+#ifndef PLX_BWD_COL_ASM
+#define PLX_BWD_COL_ASM 0
+#endif
+
 namespace plx {
 
 namespace {
@@ -368,9 +372,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     }
 }
 
-// ---- column pass: dK, dV ----------------------------------------------------------------------
+// ---- column pass, plain form: one 32-row block at a time, MFMA order left to the compiler. Used
+// for d = 128, where the pipelined form below needs about 70 registers more than a wave has (it
+// spills, and then runs slower than this one).
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
+__global__ __launch_bounds__(256, 1) void bwd_dk_dv_plain_kernel(PrefillBwdParams p) {
     using TL = BwdTile<D>;
     constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
     constexpr int STAGE = 3 * TL::CHUNKS + kTileRows;  // Q, R, dO tiles + one float4 per row
@@ -497,6 +503,300 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     }
 }
 
+// ---- column pass: dK, dV ----------------------------------------------------------------------
+// The same software pipeline over 32-row blocks of the streamed (Q, R, dO) tiles:
+//   phase 1 : the 3 * d/16 score MFMAs of the NEXT row block (S1 = Q K^T, S2 = R K^T, A = dO V^T
+//             alternate; the K, V fragments are the resident B operands), while the vector ALU
+//             turns the upper 16 rows of the CURRENT block into w = p (1 + ubar - u), g1, g2;
+//   phase 2 : the output MFMAs of the CURRENT block (dV^T += dO^T w, dK^T += Q^T g1, dK^T += R^T g2
+//             alternate), while the vector ALU turns the lower 16 rows of the NEXT block.
+// A lane owns a key, its registers the rows: the row scalars (lse, ubar, tau, beta) come from LDS,
+// one float4 per register, read one slot ahead of their use.
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
+    using TL = BwdTile<D>;
+    constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
+    constexpr int STAGES = 3;
+    constexpr int STAGE_CHUNKS = 3 * TL::CHUNKS + kTileRows;  // Q, R, dO tiles + one float4 per row
+    __shared__ u32x4 lds[STAGES * STAGE_CHUNKS];
+
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int col = lane & 31, h = lane >> 5;
+    const int T = p.T, Tk = p.Tk, off = Tk - T, G = p.G;
+    const int ncb = (Tk + 127) / 128;
+    const int cb = blockIdx.x % ncb;  // causal: low key blocks see the most rows; they come first
+    const int hk = (blockIdx.x / ncb) % p.Hkv, b = blockIdx.x / (ncb * p.Hkv);
+    const int key0 = cb * 128 + w * 32, my_key = key0 + col;
+    const int ld_key = min(my_key, Tk - 1);
+
+    // B operands of the score MFMAs: column = key, k-elements = the 8 dims of chunk 2*ks + h
+    const int64_t krow = (((int64_t)b * p.Hkv + hk) * Tk + ld_key) * D;
+    u32x4 kf[KSTEPS], vf[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        kf[ks] = *(const u32x4 *)((const __bf16 *)p.k + krow + 8 * (2 * ks + h));
+        vf[ks] = *(const u32x4 *)((const __bf16 *)p.v + krow + 8 * (2 * ks + h));
+    }
+    const float scale_log2 = p.scale * kLog2e, scale = p.scale;
+    const BwdLaneOffsets<D> lo(lane);
+
+    // row tiles that hold a row which sees a key of this block: rows i >= key - off
+    const int rt_lo = CAUSAL ? max(cb * 128 - off, 0) / kTileRows : 0;
+    const int n_rt = (T + kTileRows - 1) / kTileRows;
+    const int per_head = n_rt - rt_lo;
+    const int n_items = per_head * G;  // (head of the group, row tile)
+    // first row tile all of whose rows see every key of the block, one past the last complete tile
+    const int rt_full_lo = CAUSAL ? max(cb * 128 + 127 - off + kTileRows - 1, 0) / kTileRows : 0;
+    const int rt_full_hi = (cb + 1) * 128 <= Tk ? T / kTileRows : 0;  // a ragged key block is always masked
+
+    const uint32_t lds_base = lds_byte_address(lds);
+    auto issue_item = [&](int it, int stage) __attribute__((always_inline)) {
+        const int g = it / per_head, rt = rt_lo + it % per_head;
+        const int64_t head = ((int64_t)b * p.Hq + hk * G + g) * T;
+        const uint32_t s0 = lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u;
+        load_tile64<D>((const __bf16 *)p.q + head * D, rt * kTileRows, T, s0, w, lane);
+        load_tile64<D>((const __bf16 *)p.r + head * D, rt * kTileRows, T, s0 + (uint32_t)TL::CHUNKS * 16u, w, lane);
+        load_tile64<D>((const __bf16 *)p.d_o + head * D, rt * kTileRows, T, s0 + (uint32_t)(2 * TL::CHUNKS) * 16u, w,
+                       lane);
+        if (w == 0) {  // the rows' scalars, one float4 per lane
+            const f32x4 *src = (const f32x4 *)p.row_cache + head + min(rt * kTileRows + lane, T - 1);
+            tile_load16<64>(src, s0 + (uint32_t)(3 * TL::CHUNKS) * 16u);
+        }
+    };
+    constexpr int kItemLoads = 3 * TL::NDMA;  // per wave (wave 0 issues one more, last)
+    // Q-tile pointer of row block rbk of a stage; the R and dO tiles follow at + CHUNKS each
+    auto q_block = [&](int stage, int rbk) __attribute__((always_inline)) {
+        return (const u32x4 *)(lds + stage * STAGE_CHUNKS + rbk * kBlk * CPR);
+    };
+    auto row_scalars = [&](int stage, int rbk) __attribute__((always_inline)) {
+        return (const f32x4 *)(lds + stage * STAGE_CHUNKS + 3 * TL::CHUNKS) + rbk * kBlk + 4 * h;
+    };
+
+    f32x16 dk[NDB], dv[NDB];
+#pragma unroll
+    for (int n = 0; n < NDB; ++n) dk[n] = dv[n] = zero16();
+
+    // fragments in flight
+    constexpr int NF1 = 3 * KSTEPS, NF2 = 6 * NDB, LA = 2;
+    u32x4 f1[NF1], f2[NF2];
+    auto load_f1 = [&](const u32x4 *qblk, int f) __attribute__((always_inline)) {  // (k-step, Q / R / dO chunk)
+        f1[f] = qblk[(f % 3) * TL::CHUNKS + lo.nt[f / 3]];
+    };
+    auto load_f2 = [&](const u32x4 *qblk, int f) __attribute__((always_inline)) {  // (j, n, dO^T / Q^T / R^T)
+        const int j = f / (3 * NDB), n = (f % (3 * NDB)) / 3, which = f % 3;
+        const int tile = which == 0 ? 2 : which - 1;
+        f2[f] = lo.transposed((const unsigned short *)(qblk + tile * TL::CHUNKS), j, n);
+    };
+    auto prefetch = [&](int f, const u32x4 *next_blk, const u32x4 *cur_blk, const u32x4 *after_blk)
+                        __attribute__((always_inline)) {
+        const int g = f + LA;
+        if (g < NF1)
+            load_f1(next_blk, g);
+        else if (g < NF1 + NF2)
+            load_f2(cur_blk, g - NF1);
+        else
+            load_f1(after_blk, g - NF1 - NF2);
+    };
+
+    // Element-wise work of the 8 score registers [r0, r0 + 8) of a block in five stages (row
+    // scalars from LDS first); the results replace the scores: g1 / h in aa, g2 in s2, and
+    // w = p (1 + ubar - u) in wv. Register r holds row offset 8*(r/4) + r%4 (+ 4h): with MASKED a
+    // pair counts iff lo <= offset < lo + span (rows that exist and see this lane's key).
+    f32x4 rcv[8];
+    float dl[8], wodd = 0.f;
+    uint32_t wp[4];  // w of the 8 registers, packed in pairs as they are produced
+    auto elem_stages = [&](auto masked_tag, f32x16 &s1, f32x16 &s2, f32x16 &aa, const f32x4 *rows, int r0,
+                           int slot, int slot0, int n_slots, int neg_lo, unsigned span)
+                           __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = r0 + u;
+            const int first = slot0 + u * (n_slots - 7 - slot0) / 7;
+            if (slot == first) rcv[u] = rows[8 * (r >> 2) + (r & 3)];  // (lse, ubar, tau, beta)
+            if (slot == first + 1) {
+                s1[r] = fmaf(s1[r], scale_log2, -rcv[u][0]);
+                dl[u] = aa[r] - rcv[u][3];       // delta
+                s2[r] = rcv[u][1] - s2[r];       // ubar - u
+                aa[r] = aa[r] - rcv[u][2];
+            }
+            if (slot == first + 2) {
+                s1[r] = fast_exp2(s1[r]);           // p
+                aa[r] = fmaf(s2[r], dl[u], aa[r]);  // a - tau + (ubar - u) delta
+            }
+            if constexpr (MASKED)
+                if (slot == first + 3)
+                    s1[r] = ((unsigned)(8 * (r >> 2) + (r & 3) + neg_lo) < span) ? s1[r] : 0.f;
+            if (slot == first + 4) {
+                const float wgt = fmaf(s1[r], s2[r], s1[r]);  // p (1 + ubar - u)
+                if (u % 2 == 0)
+                    wodd = wgt;
+                else
+                    wp[u / 2] = pack_bf16(wodd, wgt);
+                aa[r] = (s1[r] * scale) * aa[r];    // g1 / h
+                s2[r] = -(s1[r] * dl[u]);           // g2
+            }
+        }
+    };
+    auto pack_w = [&]() __attribute__((always_inline)) { return u32x4{wp[0], wp[1], wp[2], wp[3]}; };
+
+    u32x4 pw[2], pg1[2], pg2[2];
+    // rows of the block that starts at row_base which exist and see this lane's key:
+    // offsets [lo, hi) relative to row_base + 4h
+    auto row_window = [&](int row_base, int &neg_lo, unsigned &span) __attribute__((always_inline)) {
+        const int first_row = my_key < Tk ? (CAUSAL ? max(my_key - off, 0) : 0) : T;  // no row at all
+        const int lo_off = max(first_row - row_base - 4 * h, 0);
+        const int hi_off = T - row_base - 4 * h;
+        neg_lo = -lo_off;
+        span = (unsigned)max(hi_off - lo_off, 0);
+    };
+    auto pipeline_step = [&](auto masked_tag, int row_base_cur, int row_base_next, const u32x4 *next_blk,
+                             const u32x4 *cur_blk, const u32x4 *after_blk, const f32x4 *rows_cur,
+                             const f32x4 *rows_next, f32x16 &c1, f32x16 &c2, f32x16 &ca, f32x16 &n1,
+                             f32x16 &n2, f32x16 &na) __attribute__((always_inline)) {
+        int nlo_c, nlo_n;
+        unsigned span_c, span_n;
+        row_window(row_base_cur, nlo_c, span_c);
+        row_window(row_base_next, nlo_n, span_n);
+        constexpr int SLOTS1 = 3 * KSTEPS, SLOTS2 = 6 * NDB;
+#pragma unroll
+        for (int sl = 0; sl < SLOTS1; ++sl) {
+            const int ks = sl / 3, which = sl % 3;
+            f32x16 &dst = which == 0 ? n1 : which == 1 ? n2 : na;
+#if PLX_BWD_COL_ASM == 1
+            if (ks == 0)
+                mfma32_scores_first<true>(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
+            else
+                mfma32_scores<true>(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
+#elif PLX_BWD_COL_ASM == 2
+            if (ks == 0)
+                mfma32_scores_first_acc(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
+            else
+                mfma32_scores_acc(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
+#else
+            dst = mfma32(f1[sl], which == 2 ? vf[ks] : kf[ks], ks == 0 ? zero16() : dst);
+#endif
+            prefetch(sl, next_blk, cur_blk, after_blk);
+            elem_stages(masked_tag, c1, c2, ca, rows_cur, 8, sl, 0, SLOTS1, nlo_c, span_c);
+            if (sl == SLOTS1 - 2) {
+                pw[1] = pack_w();
+                pg1[1] = pack_group(ca, 1);
+            }
+            if (sl == SLOTS1 - 1) pg2[1] = pack_group(c2, 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        u32x4 nw = {0u, 0u, 0u, 0u}, nb1 = {0u, 0u, 0u, 0u}, nb2 = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int sl = 0; sl < SLOTS2; ++sl) {
+            const int j = sl / (3 * NDB), n = (sl % (3 * NDB)) / 3, which = sl % 3;
+            if (which == 0)
+                dv[n] = mfma32(f2[sl], pw[j], dv[n]);
+            else if (which == 1)
+                dk[n] = mfma32(f2[sl], pg1[j], dk[n]);
+            else
+                dk[n] = mfma32(f2[sl], pg2[j], dk[n]);
+            prefetch(NF1 + sl, next_blk, cur_blk, after_blk);
+            elem_stages(masked_tag, n1, n2, na, rows_next, 0, sl, 1, SLOTS2, nlo_n, span_n);
+            if (sl == SLOTS2 - 2) {
+                nw = pack_w();
+                nb1 = pack_group(na, 0);
+            }
+            if (sl == SLOTS2 - 1) nb2 = pack_group(n2, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        pw[0] = nw;
+        pg1[0] = nb1;
+        pg2[0] = nb2;
+    };
+
+    // Ring invariant at the top of iteration it: items it and (after the barrier) it + 1 are in
+    // stages it % 3 and (it + 1) % 3; the barrier also proves that nobody reads item it - 1 any
+    // more, whose stage then receives item it + 2.
+    issue_item(0, 0);
+    if (n_items > 1) issue_item(1, 1);
+    // item 0 has landed (loads complete in order; wave 0 has one more in flight per item)
+    if (n_items > 1) {
+        if (w == 0)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kItemLoads + 1) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kItemLoads) : "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();
+    f32x16 a1, a2, a3, b1, b2, b3;
+    {
+        // prologue: scores of row block 0 of item 0; its lower 16 rows -> w, g1, g2
+        const u32x4 *blk = q_block(0, 0);
+        a1 = a2 = a3 = zero16();
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            a1 = mfma32(blk[lo.nt[ks]], kf[ks], a1);
+            a2 = mfma32(blk[TL::CHUNKS + lo.nt[ks]], kf[ks], a2);
+            a3 = mfma32(blk[2 * TL::CHUNKS + lo.nt[ks]], vf[ks], a3);
+        }
+        int nlo;
+        unsigned span;
+        row_window(rt_lo * kTileRows, nlo, span);
+#pragma unroll
+        for (int sl = 0; sl < 16; ++sl)
+            elem_stages(std::true_type{}, a1, a2, a3, row_scalars(0, 0), 0, sl, 0, 16, nlo, span);
+        pw[0] = pack_w();
+        pg1[0] = pack_group(a3, 0);
+        pg2[0] = pack_group(a2, 0);
+#pragma unroll
+        for (int f = 0; f < LA; ++f) load_f1(q_block(0, 1), f);
+    }
+    int stage = 0;
+    auto item_steps = [&](auto masked_tag, int it) __attribute__((always_inline)) {
+        const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
+        const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
+        tile_barrier<0>();  // item it + 1 has landed; item it - 1 is free
+        if (it + 2 < n_items) issue_item(it + 2, free_stage);
+        const int row_base = (rt_lo + it % per_head) * kTileRows;
+        const int row_base_after = (rt_lo + (it + 1) % per_head) * kTileRows;
+        // row block 0 -> w, g; dV / dK; scores of row block 1; fragments of the next item
+        pipeline_step(masked_tag, row_base, row_base + kBlk, q_block(stage, 1), q_block(stage, 0),
+                      q_block(next_stage, 0), row_scalars(stage, 0), row_scalars(stage, 1), a1, a2, a3, b1, b2,
+                      b3);
+        // row block 1 -> w, g; dV / dK; scores of row block 0 of the next item
+        pipeline_step(masked_tag, row_base + kBlk, row_base_after, q_block(next_stage, 0), q_block(stage, 1),
+                      q_block(next_stage, 1), row_scalars(stage, 1), row_scalars(next_stage, 0), b1, b2, b3, a1,
+                      a2, a3);
+        stage = next_stage;
+    };
+    for (int it = 0; it < n_items; ++it) {
+        // no masks if every (row, key) pair of this item and of the next one (a step also prepares
+        // the lower half of the next block) counts
+        const int rt = rt_lo + it % per_head, rt_next = rt_lo + (it + 1) % per_head;
+        const bool full = rt >= rt_full_lo && rt < rt_full_hi && rt_next >= rt_full_lo && rt_next < rt_full_hi;
+        if (full)  // workgroup-uniform
+            item_steps(std::false_type{}, it);
+        else
+            item_steps(std::true_type{}, it);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no tile load may land after the workgroup ends
+
+    // dK^T / dV^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of key my_key
+    if (my_key < Tk) {
+        __bf16 *dk_row = (__bf16 *)p.dk + krow;
+        __bf16 *dv_row = (__bf16 *)p.dv + krow;
+#pragma unroll
+        for (int n = 0; n < NDB; ++n)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int dim = 32 * n + 8 * q4 + 4 * h;
+                const u32x2 a = {pack_bf16(dk[n][4 * q4], dk[n][4 * q4 + 1]),
+                                 pack_bf16(dk[n][4 * q4 + 2], dk[n][4 * q4 + 3])};
+                const u32x2 c = {pack_bf16(dv[n][4 * q4], dv[n][4 * q4 + 1]),
+                                 pack_bf16(dv[n][4 * q4 + 2], dv[n][4 * q4 + 3])};
+                *(u32x2 *)(dk_row + dim) = a;
+                *(u32x2 *)(dv_row + dim) = c;
+            }
+    }
+}
+
 template <int D>
 static hipError_t launch_bwd_d(const PrefillBwdParams &p, hipStream_t stream) {
     const long long n_rows = (long long)p.B * p.Hq * p.T;
@@ -507,10 +807,16 @@ static hipError_t launch_bwd_d(const PrefillBwdParams &p, hipStream_t stream) {
     hipLaunchKernelGGL((bwd_rows_prepare_kernel<D>), dim3((unsigned)g0), dim3(256), 0, stream, p);
     if (p.causal) {
         hipLaunchKernelGGL((bwd_dq_dr_kernel<D, true>), dim3((unsigned)g1), dim3(256), 0, stream, p);
-        hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+        if constexpr (D == 128)
+            hipLaunchKernelGGL((bwd_dk_dv_plain_kernel<D, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
     } else {
         hipLaunchKernelGGL((bwd_dq_dr_kernel<D, false>), dim3((unsigned)g1), dim3(256), 0, stream, p);
-        hipLaunchKernelGGL((bwd_dk_dv_kernel<D, false>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+        if constexpr (D == 128)
+            hipLaunchKernelGGL((bwd_dk_dv_plain_kernel<D, false>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL((bwd_dk_dv_kernel<D, false>), dim3((unsigned)g2), dim3(256), 0, stream, p);
     }
     return hipGetLastError();
 }

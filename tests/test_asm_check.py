@@ -40,3 +40,31 @@ def test_m0_must_only_be_touched_by_the_inline_assembly():
     bad = ok + "\ts_mov_b32 m0, -1\n\tds_read_b32 v1, v2\n"
     found = asm_check.find_m0_uses_outside_inline_asm(bad)
     assert len(found) == 1 and "s_mov_b32 m0, -1" in found[0]
+
+
+ASM_MFMA = ("\t;;#ASMSTART\n\ts_nop 1\n\tv_mfma_f32_32x32x16_bf16 v[34:49], v[70:73], a[160:163], v[34:49]\n"
+            "\t;;#ASMEND\n")
+OTHER_MFMA = "\tv_mfma_f32_32x32x16_bf16 a[0:15], v[80:83], v[90:93], a[0:15]\n"
+
+
+def test_early_read_of_an_assembly_mfma_result_is_flagged():
+    # a register-allocator copy straight behind the MFMA, a spill, a vector op after one more MFMA
+    for reader in ("\tv_accvgpr_write_b32 a200, v40\n", "\tscratch_store_dword off, v34, off offset:16\n",
+                   "\tv_fma_f32 v1, v49, v2, v3\n"):
+        bad = asm_check.find_early_reads_of_asm_mfma_results(ASM_MFMA + reader)
+        assert len(bad) == 1 and "0 wait states" in bad[0], reader
+    bad = asm_check.find_early_reads_of_asm_mfma_results(ASM_MFMA + OTHER_MFMA + "\tv_add_f32 v1, v34, v2\n")
+    assert len(bad) == 1 and "8 wait states" in bad[0]
+
+
+def test_late_reads_chained_mfmas_and_writes_pass():
+    check = asm_check.find_early_reads_of_asm_mfma_results
+    # two further MFMAs, or one and a few instructions, or twelve plain instructions
+    assert check(ASM_MFMA + OTHER_MFMA + OTHER_MFMA + "\tv_add_f32 v1, v34, v2\n") == []
+    assert check(ASM_MFMA + OTHER_MFMA + "\ts_nop 3\n" + "\tv_add_f32 v1, v34, v2\n") == []
+    assert check(ASM_MFMA + "\ts_add_i32 s1, s1, 1\n" * 12 + "\tv_add_f32 v1, v34, v2\n") == []
+    # the next MFMA of the same chain reads the block as its accumulator input
+    assert check(ASM_MFMA + ASM_MFMA + ASM_MFMA) == []
+    # other registers; an MFMA the compiler knows about is its own business
+    assert check(ASM_MFMA + "\tv_add_f32 v1, v50, v2\n\tv_mov_b32_e32 v60, v33\n") == []
+    assert check(OTHER_MFMA + "\tv_accvgpr_read_b32 v1, a0\n") == []
