@@ -52,14 +52,4 @@ __device__ __forceinline__ void mfma32_scores(f32x16 &acc, u32x4 a, u32x4 b) {
 #endif
 }
 
-// The same two statements with the result block in ACCUMULATION registers, for kernels whose
-// vector registers are full: the scores are then copied out value by value where the vector ALU
-// consumes them. Always with the two wait states in front.
-__device__ __forceinline__ void mfma32_scores_first_acc(f32x16 &acc, u32x4 a, u32x4 b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&a"(acc) : "v"(a), "a"(b));
-}
-__device__ __forceinline__ void mfma32_scores_acc(f32x16 &acc, u32x4 a, u32x4 b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "a"(b));
-}
-
 }  // namespace plx

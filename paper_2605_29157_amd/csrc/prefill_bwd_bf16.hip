@@ -31,10 +31,6 @@
 #include "plx_lds_dma.h"
 #include "plx_mfma_asm.h"
 
-#ifndef PLX_BWD_COL_ASM
-#define PLX_BWD_COL_ASM 0
-#endif
-
 namespace plx {
 
 namespace {
@@ -372,137 +368,6 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     }
 }
 
-// ---- column pass, plain form: one 32-row block at a time, MFMA order left to the compiler. Used
-// for d = 128, where the pipelined form below needs about 70 registers more than a wave has (it
-// spills, and then runs slower than this one).
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 1) void bwd_dk_dv_plain_kernel(PrefillBwdParams p) {
-    using TL = BwdTile<D>;
-    constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
-    constexpr int STAGE = 3 * TL::CHUNKS + kTileRows;  // Q, R, dO tiles + one float4 per row
-    __shared__ u32x4 lds[2 * STAGE];
-
-    const int tid = threadIdx.x;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int col = lane & 31, h = lane >> 5;
-    const int T = p.T, Tk = p.Tk, off = Tk - T, G = p.G;
-    const int ncb = (Tk + 127) / 128;
-    const int cb = blockIdx.x % ncb;  // causal: low key blocks see the most rows; they come first
-    const int hk = (blockIdx.x / ncb) % p.Hkv, b = blockIdx.x / (ncb * p.Hkv);
-    const int key0 = cb * 128 + w * 32, my_key = key0 + col;
-    const int ld_key = min(my_key, Tk - 1);
-
-    // B operands of the score MFMAs: column = key, k-elements = the 8 dims of chunk 2*ks + h
-    const int64_t krow = (((int64_t)b * p.Hkv + hk) * Tk + ld_key) * D;
-    u32x4 kf[KSTEPS], vf[KSTEPS];
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-        kf[ks] = *(const u32x4 *)((const __bf16 *)p.k + krow + 8 * (2 * ks + h));
-        vf[ks] = *(const u32x4 *)((const __bf16 *)p.v + krow + 8 * (2 * ks + h));
-    }
-    const float scale_log2 = p.scale * kLog2e;
-    const BwdLaneOffsets<D> lo(lane);
-
-    // row tiles that hold a row which sees a key of this block: rows i >= key - off
-    const int rt_lo = CAUSAL ? max(cb * 128 - off, 0) / kTileRows : 0;
-    const int n_rt = (T + kTileRows - 1) / kTileRows;
-    const int per_head = n_rt - rt_lo;
-    const int n_items = per_head * G;  // (head of the group, row tile)
-    const int wave_row_lo = CAUSAL ? key0 - off : 0;  // first row that sees a key of this wave
-
-    const uint32_t lds_base = lds_byte_address(lds);
-    auto issue_item = [&](int it, int stage) {
-        const int g = it / per_head, rt = rt_lo + it % per_head;
-        const int64_t head = ((int64_t)b * p.Hq + hk * G + g) * T;
-        const uint32_t s0 = lds_base + (uint32_t)(stage * STAGE) * 16u;
-        load_tile64<D>((const __bf16 *)p.q + head * D, rt * kTileRows, T, s0, w, lane);
-        load_tile64<D>((const __bf16 *)p.r + head * D, rt * kTileRows, T, s0 + (uint32_t)TL::CHUNKS * 16u, w, lane);
-        load_tile64<D>((const __bf16 *)p.d_o + head * D, rt * kTileRows, T, s0 + (uint32_t)(2 * TL::CHUNKS) * 16u, w,
-                       lane);
-        if (w == 0) {  // the rows' scalars, one float4 per lane
-            const f32x4 *src = (const f32x4 *)p.row_cache + head + min(rt * kTileRows + lane, T - 1);
-            tile_load16<64>(src, s0 + (uint32_t)(3 * TL::CHUNKS) * 16u);
-        }
-    };
-
-    f32x16 dk[NDB], dv[NDB];
-#pragma unroll
-    for (int n = 0; n < NDB; ++n) dk[n] = dv[n] = zero16();
-
-    if (n_items > 0) issue_item(0, 0);
-    for (int it = 0; it < n_items; ++it) {
-        const int stage = it & 1;
-        tile_barrier<0>();
-        if (it + 1 < n_items) issue_item(it + 1, stage ^ 1);
-        const int rt = rt_lo + it % per_head;
-        if (rt * kTileRows + kTileRows <= wave_row_lo) continue;  // wave-uniform: no row of the tile sees us
-        const u32x4 *tq = lds + stage * STAGE;
-        const u32x4 *tr_ = tq + TL::CHUNKS;
-        const u32x4 *tg = tq + 2 * TL::CHUNKS;
-        const f32x4 *rows = (const f32x4 *)(tq + 3 * TL::CHUNKS);
-#pragma unroll 1
-        for (int rbk = 0; rbk < 2; ++rbk) {
-            const int row_base = rt * kTileRows + rbk * kBlk;
-            // wave-uniform: does any row of the block exist and see a key of this wave?
-            if (row_base >= T || row_base + kBlk <= wave_row_lo) continue;
-            f32x16 s1 = zero16(), s2 = zero16(), aa = zero16();
-            const u32x4 *qfp = tq + rbk * kBlk * CPR, *rfp = tr_ + rbk * kBlk * CPR, *gfp = tg + rbk * kBlk * CPR;
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                s1 = mfma32(qfp[lo.nt[ks]], kf[ks], s1);
-                s2 = mfma32(rfp[lo.nt[ks]], kf[ks], s2);
-                aa = mfma32(gfp[lo.nt[ks]], vf[ks], aa);
-            }
-            // accumulator register r <-> row row_base + 8*(r/4) + 4*h + r%4, column = my_key
-            f32x16 wgt;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lr = rbk * kBlk + 8 * (r >> 2) + 4 * h + (r & 3);
-                const int row = rt * kTileRows + lr;
-                const f32x4 rc = rows[lr];  // (lse, ubar, tau, beta)
-                const bool ok = row < T && my_key < Tk && (!CAUSAL || my_key <= row + off);
-                const float pr = ok ? fast_exp2(fmaf(s1[r], scale_log2, -rc[0])) : 0.f;
-                const float um = rc[1] - s2[r];
-                const float dlt = aa[r] - rc[3];
-                wgt[r] = pr * (1.f + um);
-                s1[r] = pr * (aa[r] - rc[2] + um * dlt) * p.scale;  // g1 / h
-                s2[r] = -pr * dlt;                                  // g2
-            }
-            const unsigned short *q16 = (const unsigned short *)(tq + rbk * kBlk * CPR);
-            const unsigned short *r16 = (const unsigned short *)(tr_ + rbk * kBlk * CPR);
-            const unsigned short *g16 = (const unsigned short *)(tg + rbk * kBlk * CPR);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const u32x4 pw = pack_group(wgt, j), pg1 = pack_group(s1, j), pg2 = pack_group(s2, j);
-#pragma unroll
-                for (int n = 0; n < NDB; ++n) {
-                    dv[n] = mfma32(lo.transposed(g16, j, n), pw, dv[n]);
-                    dk[n] = mfma32(lo.transposed(q16, j, n), pg1, dk[n]);
-                    dk[n] = mfma32(lo.transposed(r16, j, n), pg2, dk[n]);
-                }
-            }
-        }
-    }
-
-    // dK^T / dV^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of key my_key
-    if (my_key < Tk) {
-        __bf16 *dk_row = (__bf16 *)p.dk + krow;
-        __bf16 *dv_row = (__bf16 *)p.dv + krow;
-#pragma unroll
-        for (int n = 0; n < NDB; ++n)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const int dim = 32 * n + 8 * q4 + 4 * h;
-                const u32x2 a = {pack_bf16(dk[n][4 * q4], dk[n][4 * q4 + 1]),
-                                 pack_bf16(dk[n][4 * q4 + 2], dk[n][4 * q4 + 3])};
-                const u32x2 c = {pack_bf16(dv[n][4 * q4], dv[n][4 * q4 + 1]),
-                                 pack_bf16(dv[n][4 * q4 + 2], dv[n][4 * q4 + 3])};
-                *(u32x2 *)(dk_row + dim) = a;
-                *(u32x2 *)(dv_row + dim) = c;
-            }
-    }
-}
-
 // ---- column pass: dK, dV ----------------------------------------------------------------------
 // The same software pipeline over 32-row blocks of the streamed (Q, R, dO) tiles:
 //   phase 1 : the 3 * d/16 score MFMAs of the NEXT row block (S1 = Q K^T, S2 = R K^T, A = dO V^T
@@ -546,13 +411,30 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     const int n_rt = (T + kTileRows - 1) / kTileRows;
     const int per_head = n_rt - rt_lo;
     const int n_items = per_head * G;  // (head of the group, row tile)
-    // first row tile all of whose rows see every key of the block, one past the last complete tile
-    const int rt_full_lo = CAUSAL ? max(cb * 128 + 127 - off + kTileRows - 1, 0) / kTileRows : 0;
-    const int rt_full_hi = (cb + 1) * 128 <= Tk ? T / kTileRows : 0;  // a ragged key block is always masked
+    // Row tiles in which every (row, key) pair counts -- all rows exist and see every key of the
+    // block, and the key block is complete -- need no masks. The items are taken in an order that
+    // puts those of all heads first, so that the two forms of the pipeline are two loops.
+    const int rt_full_lo = max(CAUSAL ? max(cb * 128 + 127 - off + kTileRows - 1, 0) / kTileRows : 0, rt_lo);
+    const int rt_full_hi = (cb + 1) * 128 <= Tk ? T / kTileRows : 0;
+    const int full_per_head = max(rt_full_hi - rt_full_lo, 0);
+    const int n_full_items = full_per_head * G;
+    const int rest_per_head = per_head - full_per_head;
+    auto item_of = [&](int it, int &g, int &rt) __attribute__((always_inline)) {
+        if (it < n_full_items) {
+            g = it / full_per_head;
+            rt = rt_full_lo + it % full_per_head;
+        } else {
+            const int j = it - n_full_items;
+            g = j / rest_per_head;
+            const int k = j % rest_per_head;  // the head's tiles before, then after, its full ones
+            rt = rt_lo + k + (k >= rt_full_lo - rt_lo ? full_per_head : 0);
+        }
+    };
 
     const uint32_t lds_base = lds_byte_address(lds);
     auto issue_item = [&](int it, int stage) __attribute__((always_inline)) {
-        const int g = it / per_head, rt = rt_lo + it % per_head;
+        int g, rt;
+        item_of(it, g, rt);
         const int64_t head = ((int64_t)b * p.Hq + hk * G + g) * T;
         const uint32_t s0 = lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u;
         load_tile64<D>((const __bf16 *)p.q + head * D, rt * kTileRows, T, s0, w, lane);
@@ -664,19 +546,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         for (int sl = 0; sl < SLOTS1; ++sl) {
             const int ks = sl / 3, which = sl % 3;
             f32x16 &dst = which == 0 ? n1 : which == 1 ? n2 : na;
-#if PLX_BWD_COL_ASM == 1
             if (ks == 0)
                 mfma32_scores_first<true>(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
             else
                 mfma32_scores<true>(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
-#elif PLX_BWD_COL_ASM == 2
-            if (ks == 0)
-                mfma32_scores_first_acc(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
-            else
-                mfma32_scores_acc(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
-#else
-            dst = mfma32(f1[sl], which == 2 ? vf[ks] : kf[ks], ks == 0 ? zero16() : dst);
-#endif
             prefetch(sl, next_blk, cur_blk, after_blk);
             elem_stages(masked_tag, c1, c2, ca, rows_cur, 8, sl, 0, SLOTS1, nlo_c, span_c);
             if (sl == SLOTS1 - 2) {
@@ -738,7 +611,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         }
         int nlo;
         unsigned span;
-        row_window(rt_lo * kTileRows, nlo, span);
+        int g0, rt0;
+        item_of(0, g0, rt0);
+        row_window(rt0 * kTileRows, nlo, span);
 #pragma unroll
         for (int sl = 0; sl < 16; ++sl)
             elem_stages(std::true_type{}, a1, a2, a3, row_scalars(0, 0), 0, sl, 0, 16, nlo, span);
@@ -754,8 +629,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
         tile_barrier<0>();  // item it + 1 has landed; item it - 1 is free
         if (it + 2 < n_items) issue_item(it + 2, free_stage);
-        const int row_base = (rt_lo + it % per_head) * kTileRows;
-        const int row_base_after = (rt_lo + (it + 1) % per_head) * kTileRows;
+        int g_cur, rt_cur, g_after, rt_after;
+        item_of(it, g_cur, rt_cur);
+        item_of(it + 1 < n_items ? it + 1 : it, g_after, rt_after);  // (past the end: never used)
+        const int row_base = rt_cur * kTileRows, row_base_after = rt_after * kTileRows;
         // row block 0 -> w, g; dV / dK; scores of row block 1; fragments of the next item
         pipeline_step(masked_tag, row_base, row_base + kBlk, q_block(stage, 1), q_block(stage, 0),
                       q_block(next_stage, 0), row_scalars(stage, 0), row_scalars(stage, 1), a1, a2, a3, b1, b2,
@@ -766,16 +643,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
                       a2, a3);
         stage = next_stage;
     };
-    for (int it = 0; it < n_items; ++it) {
-        // no masks if every (row, key) pair of this item and of the next one (a step also prepares
-        // the lower half of the next block) counts
-        const int rt = rt_lo + it % per_head, rt_next = rt_lo + (it + 1) % per_head;
-        const bool full = rt >= rt_full_lo && rt < rt_full_hi && rt_next >= rt_full_lo && rt_next < rt_full_hi;
-        if (full)  // workgroup-uniform
-            item_steps(std::false_type{}, it);
-        else
-            item_steps(std::true_type{}, it);
-    }
+    // a step also prepares the lower half of the next item's first block, hence the - 1
+    int it = 0;
+    for (; it < n_full_items - 1; ++it) item_steps(std::false_type{}, it);
+    for (; it < n_items; ++it) item_steps(std::true_type{}, it);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no tile load may land after the workgroup ends
 
     // dK^T / dV^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of key my_key
@@ -807,16 +678,10 @@ static hipError_t launch_bwd_d(const PrefillBwdParams &p, hipStream_t stream) {
     hipLaunchKernelGGL((bwd_rows_prepare_kernel<D>), dim3((unsigned)g0), dim3(256), 0, stream, p);
     if (p.causal) {
         hipLaunchKernelGGL((bwd_dq_dr_kernel<D, true>), dim3((unsigned)g1), dim3(256), 0, stream, p);
-        if constexpr (D == 128)
-            hipLaunchKernelGGL((bwd_dk_dv_plain_kernel<D, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
-        else
-            hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
     } else {
         hipLaunchKernelGGL((bwd_dq_dr_kernel<D, false>), dim3((unsigned)g1), dim3(256), 0, stream, p);
-        if constexpr (D == 128)
-            hipLaunchKernelGGL((bwd_dk_dv_plain_kernel<D, false>), dim3((unsigned)g2), dim3(256), 0, stream, p);
-        else
-            hipLaunchKernelGGL((bwd_dk_dv_kernel<D, false>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((bwd_dk_dv_kernel<D, false>), dim3((unsigned)g2), dim3(256), 0, stream, p);
     }
     return hipGetLastError();
 }
