@@ -460,7 +460,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     for (int n = 0; n < NDB; ++n) dk[n] = dv[n] = zero16();
 
     // fragments in flight
-    constexpr int NF1 = 3 * KSTEPS, NF2 = 6 * NDB, LA = 2;
+    constexpr int NF1 = 3 * KSTEPS, NF2 = 6 * NDB, LA = 3;
     u32x4 f1[NF1], f2[NF2];
     auto load_f1 = [&](const u32x4 *qblk, int f) __attribute__((always_inline)) {  // (k-step, Q / R / dO chunk)
         f1[f] = qblk[(f % 3) * TL::CHUNKS + lo.nt[f / 3]];
@@ -495,22 +495,24 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int r = r0 + u;
-            const int first = slot0 + u * (n_slots - 7 - slot0) / 7;
+            // (the row scalars are read two slots ahead of their use: an LDS read takes longer
+            // than one MFMA slot)
+            const int first = slot0 + u * (n_slots - 8 - slot0) / 7;
             if (slot == first) rcv[u] = rows[8 * (r >> 2) + (r & 3)];  // (lse, ubar, tau, beta)
-            if (slot == first + 1) {
+            if (slot == first + 2) {
                 s1[r] = fmaf(s1[r], scale_log2, -rcv[u][0]);
                 dl[u] = aa[r] - rcv[u][3];       // delta
                 s2[r] = rcv[u][1] - s2[r];       // ubar - u
                 aa[r] = aa[r] - rcv[u][2];
             }
-            if (slot == first + 2) {
+            if (slot == first + 3) {
                 s1[r] = fast_exp2(s1[r]);           // p
                 aa[r] = fmaf(s2[r], dl[u], aa[r]);  // a - tau + (ubar - u) delta
             }
             if constexpr (MASKED)
-                if (slot == first + 3)
+                if (slot == first + 4)
                     s1[r] = ((unsigned)(8 * (r >> 2) + (r & 3) + neg_lo) < span) ? s1[r] : 0.f;
-            if (slot == first + 4) {
+            if (slot == first + 5) {
                 const float wgt = fmaf(s1[r], s2[r], s1[r]);  // p (1 + ubar - u)
                 if (u % 2 == 0)
                     wodd = wgt;
