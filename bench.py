@@ -526,7 +526,21 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
     pre["frac_of_bf16_mfma_peak"] = round(pre["parallax_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
     pre["workload"] = "config4: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128, K offset N(0,0.5^2)"
     extra["prefill"] = pre
-    del y, po
+    # ... and its backward pass (rows prepare + dQ/dR pass + dK/dV pass; 22 d flops per pair)
+    g = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1014, device=dev)["q"].contiguous()
+    o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True,
+                                          save_for_backward=True)
+    bws = torch.empty(plx.parallax_prefill_backward_workspace_bytes(B, Hq, T) // 4,
+                      dtype=torch.float32, device=dev)
+    us = _time_events(
+        torch, lambda: plx.parallax_prefill_backward(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g,
+                                                     y["scale"], causal=True, workspace=bws), 2, 10)
+    bflops = B * Hq * 22 * d * T * (T + 1) / 2
+    extra["prefill_backward"] = {
+        "workload": "backward of config 4 (causal B=4 T=4096 d=128)", "us": round(us, 1),
+        "TFLOPs": round(bflops / us / 1e6, 1),
+        "frac_of_bf16_mfma_peak": round(bflops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    del y, po, g, o, vbar, stats, bws
 
     # other prefill shapes: config 5a (long causal), full attention, and the compute-matched
     # d = 64 layout (twice the heads, half the head dimension)
