@@ -183,7 +183,7 @@ typedef struct {
     plx_dtype dtype;
     int32_t Tkv; /* keys per sequence; 0 = T */
     int32_t window; /* sliding window in keys (needs causal); 0 = none */
-    /* Row cache for parallax_prefill_backward (App. D), both or neither (bf16, use_r, no window):
+    /* Row cache for parallax_prefill_backward (App. D), both or neither (use_r, no window):
      *   vbar       [B, Hq, T, d] like o (same strides): the softmax value mean O1 / d1
      *   row_stats  [B, Hq, T, 2] fp32 contiguous: log2 of sum_j exp(scale q.k_j) (i.e. the
      *              log-sum-exp in the exp2 domain) and ubar = sum_j p_j rho.k_j */
@@ -197,8 +197,9 @@ plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
  * Backward of parallax_prefill (closed-form gradients, App. D): given the upstream gradient d_o,
  * the forward's inputs, its output o and its row cache (vbar, row_stats), writes dq, dr
  * [B, Hq, T, d] and dk, dv [B, Hkv, Tkv, d]; the gradients of a KV head add up over the query
- * heads of its group. bf16 only; EVERY tensor contiguous (row-major, head dimension innermost),
- * 16-byte aligned; d = 64 or 128. causal and Tkv as in the forward (no window).
+ * heads of its group. EVERY tensor contiguous (row-major, head dimension innermost), 16-byte
+ * aligned; bf16 (d = 64 or 128; MFMA kernels) or fp32 (d <= 256, plain untuned path, vbar in fp32
+ * too). causal and Tkv as in the forward (no window).
  *   workspace  fp32 scratch, >= parallax_prefill_backward_workspace_bytes(B, Hq, T) = 16 bytes
  *              per query row (lse, ubar, tau = dO.o, beta = dO.vbar)
  * Three kernels are enqueued (row scalars; dQ, dR; dK, dV); nothing is accumulated with atomics,

@@ -19,6 +19,8 @@ struct GenericParams {
     int32_t page_size, table_stride, num_pages;
     int32_t tail_rows;  // decode with Tq rows: row i sees the keys before len_b - (Tq - 1 - i)
     int32_t window;     // > 0: a row sees only the last `window` of its keys
+    float *vbar;        // row cache of the backward pass (prefill only), laid out like o; or NULL
+    float *row_stats;   // [B, Hq, Tq, 2]: log-sum-exp (exp2 domain), ubar
 };
 
 constexpr int kGenThreads = 256;
@@ -121,6 +123,12 @@ __global__ __launch_bounds__(kGenThreads) void generic_f32_kernel(GenericParams 
         float out = 0.f;  // empty key set: zeros
         if (d1 > 0.f) out = (o1 / d1) * (1.f + d2 / d1) - o2 / d1;
         p.o[b * p.os[0] + h * p.os[1] + i * p.os[2] + t] = out;
+        if (p.row_stats) p.vbar[b * p.os[0] + h * p.os[1] + i * p.os[2] + t] = d1 > 0.f ? o1 / d1 : 0.f;
+    }
+    if (p.row_stats && t == 0) {
+        float *st = p.row_stats + (((int64_t)b * p.Hq + h) * p.Tq + i) * 2;
+        st[0] = d1 > 0.f ? m_run + log2f(d1) : kNegInf;
+        st[1] = d1 > 0.f ? d2 / d1 : 0.f;
     }
 }
 
@@ -167,7 +175,135 @@ hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream) {
     }
     g.scale = p.scale, g.causal = p.causal, g.use_r = p.use_r;
     g.window = p.window;
+    g.vbar = (float *)p.vbar, g.row_stats = p.row_stats;
     return launch_generic(g, stream);
+}
+
+// ---- fp32 backward (closed forms of the paper's App. D): plain, untuned correctness path ------
+// Row kernel: one workgroup per query row; tau = dO.o and beta = dO.vbar first, then key tiles of
+// 256 (one key per thread for p, u, a; one output dimension per thread for the sums over keys).
+// It also leaves (lse, ubar, tau, beta) of its row in the workspace for the column kernel.
+__global__ __launch_bounds__(kGenThreads) void generic_bwd_rows_f32_kernel(PrefillBwdParams p) {
+    __shared__ float sq[256], sr[256], sg[256], s1s[kGenThreads], s2s[kGenThreads];
+    __shared__ float red[2][kGenThreads / 64];
+    const int t = threadIdx.x, wv = t >> 6, ln = t & 63;
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / p.G, d = p.d, off = p.Tk - p.T;
+    const int64_t row = ((int64_t)b * p.Hq + h) * p.T + i;
+    const float *k = (const float *)p.k + ((int64_t)b * p.Hkv + hk) * p.Tk * d;
+    const float *v = (const float *)p.v + ((int64_t)b * p.Hkv + hk) * p.Tk * d;
+    float tau = 0.f, beta = 0.f;
+    if (t < d) {
+        sq[t] = ((const float *)p.q)[row * d + t];
+        sr[t] = ((const float *)p.r)[row * d + t];
+        sg[t] = ((const float *)p.d_o)[row * d + t];
+        tau = sg[t] * ((const float *)p.o)[row * d + t];
+        beta = sg[t] * ((const float *)p.vbar)[row * d + t];
+    }
+    tau = wave_sum(tau), beta = wave_sum(beta);
+    if (ln == 0) red[0][wv] = tau, red[1][wv] = beta;
+    __syncthreads();
+    tau = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    beta = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    const float lse = p.row_stats[2 * row], ubar = p.row_stats[2 * row + 1];
+    if (t == 0) ((f32x4 *)p.row_cache)[row] = f32x4{lse, ubar, tau, beta};
+    const float scale_log2 = p.scale * kLog2e;
+    const int n_keys = p.causal ? min(i + 1 + off, p.Tk) : p.Tk;
+    float dq = 0.f, dr = 0.f;  // dimension t
+    for (int j0 = 0; j0 < n_keys; j0 += kGenThreads) {
+        const int j = j0 + t;
+        float g1 = 0.f, g2 = 0.f;
+        if (j < n_keys) {
+            float a1 = 0.f, a2 = 0.f, a3 = 0.f;
+            for (int c = 0; c < d; ++c) {
+                const float kv = k[(int64_t)j * d + c];
+                a1 = fmaf(sq[c], kv, a1);
+                a2 = fmaf(sr[c], kv, a2);
+                a3 = fmaf(sg[c], v[(int64_t)j * d + c], a3);
+            }
+            const float pr = exp2f(a1 * scale_log2 - lse);
+            const float dlt = a3 - beta;
+            g1 = pr * (a3 - tau + (ubar - a2) * dlt);
+            g2 = -pr * dlt;
+        }
+        s1s[t] = g1, s2s[t] = g2;
+        __syncthreads();
+        if (t < d) {
+            const int n = min(kGenThreads, n_keys - j0);
+            for (int jj = 0; jj < n; ++jj) {
+                const float kv = k[(int64_t)(j0 + jj) * d + t];
+                dq = fmaf(s1s[jj], kv, dq);
+                dr = fmaf(s2s[jj], kv, dr);
+            }
+        }
+        __syncthreads();
+    }
+    if (t < d) {
+        ((float *)p.dq)[row * d + t] = dq * p.scale;
+        ((float *)p.dr)[row * d + t] = dr;
+    }
+}
+
+// Column kernel: one workgroup per key; rows of every query head of the group in tiles of 256.
+__global__ __launch_bounds__(kGenThreads) void generic_bwd_cols_f32_kernel(PrefillBwdParams p) {
+    __shared__ float sk[256], sv[256], s1s[kGenThreads], s2s[kGenThreads], sws[kGenThreads];
+    const int t = threadIdx.x;
+    const int j = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int d = p.d, off = p.Tk - p.T;
+    const int64_t krow = ((int64_t)b * p.Hkv + hk) * p.Tk + j;
+    if (t < d) {
+        sk[t] = ((const float *)p.k)[krow * d + t];
+        sv[t] = ((const float *)p.v)[krow * d + t];
+    }
+    __syncthreads();
+    const float scale_log2 = p.scale * kLog2e;
+    const int i_lo = p.causal ? max(j - off, 0) : 0;  // rows that see key j
+    float dk = 0.f, dv = 0.f;  // dimension t
+    for (int g = 0; g < p.G; ++g) {
+        const int64_t head = ((int64_t)b * p.Hq + hk * p.G + g) * p.T;
+        const float *q = (const float *)p.q + head * d, *r = (const float *)p.r + head * d;
+        const float *go = (const float *)p.d_o + head * d;
+        for (int i0 = i_lo; i0 < p.T; i0 += kGenThreads) {
+            const int i = i0 + t;
+            float g1 = 0.f, g2 = 0.f, w = 0.f;
+            if (i < p.T) {
+                float a1 = 0.f, a2 = 0.f, a3 = 0.f;
+                for (int c = 0; c < d; ++c) {
+                    a1 = fmaf(q[(int64_t)i * d + c], sk[c], a1);
+                    a2 = fmaf(r[(int64_t)i * d + c], sk[c], a2);
+                    a3 = fmaf(go[(int64_t)i * d + c], sv[c], a3);
+                }
+                const f32x4 rc = ((const f32x4 *)p.row_cache)[head + i];  // (lse, ubar, tau, beta)
+                const float pr = exp2f(a1 * scale_log2 - rc[0]);
+                const float um = rc[1] - a2, dlt = a3 - rc[3];
+                w = pr * (1.f + um);
+                g1 = pr * (a3 - rc[2] + um * dlt) * p.scale;
+                g2 = -pr * dlt;
+            }
+            s1s[t] = g1, s2s[t] = g2, sws[t] = w;
+            __syncthreads();
+            if (t < d) {
+                const int n = min(kGenThreads, p.T - i0);
+                for (int ii = 0; ii < n; ++ii) {
+                    const int64_t e = (int64_t)(i0 + ii) * d + t;
+                    dk = fmaf(s1s[ii], q[e], dk);
+                    dk = fmaf(s2s[ii], r[e], dk);
+                    dv = fmaf(sws[ii], go[e], dv);
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (t < d) {
+        ((float *)p.dk)[krow * d + t] = dk;
+        ((float *)p.dv)[krow * d + t] = dv;
+    }
+}
+
+hipError_t launch_prefill_bwd_f32(const PrefillBwdParams &p, hipStream_t stream) {
+    hipLaunchKernelGGL(generic_bwd_rows_f32_kernel, dim3(p.T, p.Hq, p.B), dim3(kGenThreads), 0, stream, p);
+    hipLaunchKernelGGL(generic_bwd_cols_f32_kernel, dim3(p.Tk, p.Hkv, p.B), dim3(kGenThreads), 0, stream, p);
+    return hipGetLastError();
 }
 
 }  // namespace plx

@@ -59,6 +59,7 @@ hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_decode_combine(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_prefill_bf16(const PrefillParams &p, hipStream_t stream);
 hipError_t launch_prefill_bwd_bf16(const PrefillBwdParams &p, hipStream_t stream);
+hipError_t launch_prefill_bwd_f32(const PrefillBwdParams &p, hipStream_t stream);
 hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream);
 hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);

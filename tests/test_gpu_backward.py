@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from parity import BF16_REL_L2, host, rel_l2
+from parity import BF16_REL_L2, F32_MAX_REL, host, max_rel, rel_l2
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -135,3 +135,25 @@ def test_backward_config4_shape_sampled(plx, synth, bwd_oracle):
     want = bwd_oracle.backward(*(host(y[n]) for n in "qrkv"), host(g), y["scale"], causal=True)
     for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
         assert rel_l2(host(got), ref) <= BF16_REL_L2, name
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,T,Tkv,d,causal", [(1, 2, 2, 128, 128, 64, True), (2, 4, 2, 77, 77, 32, True),
+                                                      (1, 6, 2, 50, 301, 128, True), (2, 4, 4, 130, 257, 16, False),
+                                                      (1, 2, 1, 1, 1, 8, True), (1, 2, 2, 300, 300, 256, True)])
+def test_backward_fp32_path(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, causal):
+    """fp32 tensors take the plain kernels: forward row cache and all four gradients to 1e-4."""
+    y = synth.prefill_inputs(B, Hq, Hkv, Tkv, d, seed=2700 + T, dtype=torch.float32, device=DEV)
+    if Tkv > T:
+        y["q"], y["r"] = y["q"][:, :, Tkv - T:].contiguous(), y["r"][:, :, Tkv - T:].contiguous()
+    g = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=2701, dtype=torch.float32, device=DEV)["q"].contiguous()
+    o, vbar, stats, grads = _run(plx, y, g, causal)
+    assert vbar.dtype == torch.float32
+    hq, hr, hk, hv = (host(y[n]) for n in "qrkv")
+    _, vb, ub, lw = bwd_oracle.forward_with_cache(hq, hr, hk, hv, y["scale"], causal=causal)
+    assert max_rel(host(vbar), vb) <= F32_MAX_REL
+    np.testing.assert_allclose(host(stats)[..., 0], lw * LOG2E, rtol=0, atol=1e-4)
+    assert max_rel(host(stats)[..., 1], ub) <= F32_MAX_REL
+    want = bwd_oracle.backward(hq, hr, hk, hv, host(g), y["scale"], causal=causal)
+    for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
+        scale = max(np.abs(ref).max(), 1.0)   # dQ = dR = 0 exactly when a row has one key (a - tau cancels)
+        assert np.abs(host(got) - ref).max() <= F32_MAX_REL * scale, (name, np.abs(host(got) - ref).max(), scale)
