@@ -42,7 +42,7 @@ def _compile(src: str, extra: list[str]) -> str:
     return obj
 
 
-def _check_prefill_assembly(extra: list[str], src: str = "prefill_bf16.hip", m0: bool = True) -> None:
+def _check_prefill_assembly(extra: list[str], src: str = "prefill_bf16.hip", m0: bool = True) -> None:  # m0: full check
     """Emit the device assembly of a prefill kernel file and verify its hand-placed MFMAs."""
     from . import asm_check
     asm = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".gfx950.s")
@@ -53,11 +53,13 @@ def _check_prefill_assembly(extra: list[str], src: str = "prefill_bf16.hip", m0:
         raise RuntimeError("hipcc -S failed on %s:\n%s" % (src, res.stdout))
     if m0:
         asm_check.check_file(asm)
-    else:  # the backward kernels restore M0 after every tile load and use guarded MFMAs only
+    else:  # the backward kernels use guarded assembly MFMAs only (nothing "unguarded" to find)
         with open(asm) as f:
-            bad = asm_check.find_early_reads_of_asm_mfma_results(f.read())
+            text = f.read()
+        bad = (asm_check.find_early_reads_of_asm_mfma_results(text)
+               + asm_check.find_m0_uses_outside_inline_asm(text))
         if bad:
-            raise RuntimeError("MFMA result hazard in %s:\n  %s" % (asm, "\n  ".join(bad[:20])))
+            raise RuntimeError("hazard in %s:\n  %s" % (asm, "\n  ".join(bad[:20])))
 
 
 def _check_decode_assembly(extra: list[str]) -> None:

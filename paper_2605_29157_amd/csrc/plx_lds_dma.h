@@ -5,6 +5,13 @@
 
 namespace plx {
 
+// Timing-only ablation switches for kernel analysis (results are wrong when non-zero; every
+// access stays inside the same buffers): 4 = no barrier in the steady-state loop, 8 = no tile
+// loads there, 64 = tile loads without their LDS address updates.
+#ifndef PLX_PF_ABLATE
+#define PLX_PF_ABLATE 0
+#endif
+
 // Tile loads go global -> LDS directly (global_load_lds_dwordx4: LDS address = M0 + 16 * lane).
 // They are emitted as inline assembly: through the compiler builtin, the first LDS read after
 // a tile load waits for that load to land (the compiler assumes every LDS read may alias the
@@ -38,6 +45,32 @@ __device__ __forceinline__ void tile_load16(const void *gptr, uint32_t lds_byte_
             "s_mov_b32 m0, %0"
             : "=&s"(saved_m0)
             : "v"(gptr), "s"(m0v));
+}
+// Same load with a wave-uniform tile base (scalar registers) plus a 32-bit per-lane byte offset:
+// no per-lane 64-bit address arithmetic. M0 is not restored: nothing the compiler emits for this
+// kernel touches M0 (no other LDS-DMA, no GWS / message / relative-index instructions) -- the
+// build checks that on the generated assembly (asm_check.py).
+template <bool QUARTER = false>
+__device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, const void *tile_base,
+                                                    uint32_t lds_byte_addr) {
+    uint64_t saved_exec;
+    if constexpr (QUARTER)
+        asm volatile(
+            "s_mov_b64 %0, exec\n\t"
+            "s_mov_b64 exec, 0xffff\n\t"
+            "s_mov_b32 m0, %3\n\t"
+            "global_load_lds_dwordx4 %1, %2\n\t"
+            "s_mov_b64 exec, %0"
+            : "=&s"(saved_exec)
+            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
+    else if (PLX_PF_ABLATE & 64)  // timing only: every load lands at the same LDS address
+        asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(lane_byte_off), "s"(tile_base));
+    else
+        asm volatile(
+            "s_mov_b32 m0, %2\n\t"
+            "global_load_lds_dwordx4 %0, %1"
+            :
+            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
 }
 // Wait until at most PENDING of this wave's tile loads are still in flight (loads complete in
 // issue order), then the workgroup barrier that publishes the landed tiles.

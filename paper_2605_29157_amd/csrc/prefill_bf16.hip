@@ -45,44 +45,12 @@
 
 namespace plx {
 
-// Timing-only ablation switches for kernel analysis (results are wrong when non-zero; every
-// access stays inside the same buffers): 4 = no barrier in the steady-state loop, 8 = no tile
-// loads there, 64 = tile loads without their LDS address updates.
-#ifndef PLX_PF_ABLATE
-#define PLX_PF_ABLATE 0
-#endif
 
 constexpr int kBR = 128;  // query rows per workgroup
 constexpr int kBC = 64;   // keys per LDS tile
 constexpr int kKB = 32;   // keys per inner block (one MFMA row block)
 
 
-// Same load with a wave-uniform tile base (scalar registers) plus a 32-bit per-lane byte offset:
-// no per-lane 64-bit address arithmetic. M0 is not restored: nothing the compiler emits for this
-// kernel touches M0 (no other LDS-DMA, no GWS / message / relative-index instructions) -- the
-// build checks that on the generated assembly (asm_check.py).
-template <bool QUARTER = false>
-__device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, const void *tile_base,
-                                                    uint32_t lds_byte_addr) {
-    uint64_t saved_exec;
-    if constexpr (QUARTER)
-        asm volatile(
-            "s_mov_b64 %0, exec\n\t"
-            "s_mov_b64 exec, 0xffff\n\t"
-            "s_mov_b32 m0, %3\n\t"
-            "global_load_lds_dwordx4 %1, %2\n\t"
-            "s_mov_b64 exec, %0"
-            : "=&s"(saved_exec)
-            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
-    else if (PLX_PF_ABLATE & 64)  // timing only: every load lands at the same LDS address
-        asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(lane_byte_off), "s"(tile_base));
-    else
-        asm volatile(
-            "s_mov_b32 m0, %2\n\t"
-            "global_load_lds_dwordx4 %0, %1"
-            :
-            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
-}
 // Row sums d1, d2 of tiles that every row sees completely: per-lane fp32 adds of the unrounded
 // P1 / P2 (1) instead of MFMAs against a matrix of ones over the bf16-rounded values (0).
 #ifndef PLX_PF_VALU_SUMS

@@ -190,6 +190,25 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
         load_tile64<D>(vbase, t * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS + TL::CHUNKS) * 16u, w,
                        lane);
     };
+    // The steady-state loop spreads the loads of tile t + 2 over the MFMA slots of a step (as a
+    // block at the top of an iteration they cost about a tenth of it): per-lane byte offsets
+    // inside a complete tile, a wave-uniform tile base.
+    uint32_t toff[TL::NDMA];
+#pragma unroll
+    for (int i = 0; i < TL::NDMA; ++i) {
+        const int c = (w * TL::NDMA + i) * 64 + lane;
+        const int row = c / CPR;
+        toff[i] = (uint32_t)(row * D + ((c % CPR) ^ lds_row_swizzle<D>(row)) * 8) * 2u;
+    }
+    const char *dma_k = nullptr, *dma_v = nullptr;  // tile being fetched by the current step
+    uint32_t dma_lds = 0;                           // this wave's first K chunk of its stage
+    auto dma_slot = [&](int i) __attribute__((always_inline)) {  // load i of 2 * NDMA (K, then V)
+        if (i < TL::NDMA)
+            tile_load16_uniform<false>(toff[i], dma_k, dma_lds + 1024u * i);
+        else
+            tile_load16_uniform<false>(toff[i - TL::NDMA], dma_v,
+                                       dma_lds + (uint32_t)TL::CHUNKS * 16u + 1024u * (i - TL::NDMA));
+    };
     auto k_block = [&](int stage, int kb) __attribute__((always_inline)) { return (const u32x4 *)(lds + stage * STAGE_CHUNKS + kb * kBlk * CPR); };
 
     const int key_end = CAUSAL ? min(Tk, (rb + 1) * 128 + off) : Tk;
@@ -255,13 +274,17 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     // one out). Each brings two wait states for its operands; the first vector read of a block
     // comes in slot 1 of phase 2, behind two more MFMAs: by then the block's last MFMA retired.
     u32x4 pg1[2], pg2[2];
-    auto pipeline_step = [&](auto masked_tag, int key_base_cur, const u32x4 *next_blk, const u32x4 *cur_blk, const u32x4 *after_blk,
+    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int key_base_cur, const u32x4 *next_blk, const u32x4 *cur_blk, const u32x4 *after_blk,
                              f32x16 &c1, f32x16 &c2, f32x16 &ca, f32x16 &n1, f32x16 &n2, f32x16 &na) __attribute__((always_inline)) {
         const int lim_cur = lim_row - key_base_cur - 4 * h, lim_next = lim_cur - kBlk;
         constexpr int SLOTS1 = 3 * KSTEPS, SLOTS2 = 4 * NDB;
+        constexpr bool DMA = decltype(dma_tag)::value;  // this step also fetches tile (dma_k, dma_v)
+        static_assert(2 * TL::NDMA <= SLOTS1, "one tile load per slot");
 #pragma unroll
         for (int sl = 0; sl < SLOTS1; ++sl) {
             const int ks = sl / 3, which = sl % 3;
+            if constexpr (DMA)
+                if (sl < 2 * TL::NDMA) dma_slot(sl);
             if (which == 0) {
                 if (ks == 0) mfma32_scores_first<true>(n1, f1[2 * ks], qf[ks]);
                 else mfma32_scores<true>(n1, f1[2 * ks], qf[ks]);
@@ -328,25 +351,39 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
         for (int f = 0; f < LA; ++f) load_f1(k_block(0, 1), f);
     }
     int stage = 0;
-    auto tile_steps = [&](auto masked_tag, int t) __attribute__((always_inline)) {
+    auto tile_steps = [&](auto masked_tag, auto dma_tag, int t) __attribute__((always_inline)) {
+        constexpr bool DMA = decltype(dma_tag)::value;
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
         const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
         tile_barrier<0>();  // tile t + 1 has landed; tile t - 1 is free
-        if (t + 2 < n_tiles) issue_tile(t + 2, free_stage);
+        if constexpr (DMA) {  // tile t + 2 is complete: fetched by the first step, slot by slot
+            dma_lds = lds_base + (uint32_t)(free_stage * STAGE_CHUNKS + w * TL::NDMA * 64) * 16u;
+        } else {
+            if (t + 2 < n_tiles) issue_tile(t + 2, free_stage);
+        }
         // block (t, 0) -> g, dQ / dR; scores of (t, 1); fragments of (t + 1, 0)
-        pipeline_step(masked_tag, t * kTileRows, k_block(stage, 1), k_block(stage, 0), k_block(next_stage, 0), a1,
-                      a2, a3, b1, b2, b3);
+        pipeline_step(masked_tag, dma_tag, t * kTileRows, k_block(stage, 1), k_block(stage, 0),
+                      k_block(next_stage, 0), a1, a2, a3, b1, b2, b3);
         // block (t, 1) -> g, dQ / dR; scores of (t + 1, 0); fragments of (t + 1, 1)
-        pipeline_step(masked_tag, t * kTileRows + kBlk, k_block(next_stage, 0), k_block(stage, 1),
-                      k_block(next_stage, 1), b1, b2, b3, a1, a2, a3);
+        pipeline_step(masked_tag, std::false_type{}, t * kTileRows + kBlk, k_block(next_stage, 0),
+                      k_block(stage, 1), k_block(next_stage, 1), b1, b2, b3, a1, a2, a3);
         stage = next_stage;
     };
     // tiles whose keys -- and those of the tile after (a step also prepares the lower half of the
-    // next block) -- every row of the workgroup sees: no masks; then the diagonal / tail tiles
-    const int n_full = min(CAUSAL ? (rb * 128 + off + 1) / kTileRows : Tk / kTileRows, Tk / kTileRows);
+    // next block) -- every row of the workgroup sees: no masks; then the diagonal / tail tiles.
+    // The unmasked loop also stops two short of the last complete tile, so that the tile it
+    // fetches exists completely.
+    const int n_full = min(CAUSAL ? (rb * 128 + off + 1) / kTileRows : Tk / kTileRows, Tk / kTileRows - 1);
     int t = 0;
-    for (; t < n_full - 1; ++t) tile_steps(std::false_type{}, t);
-    for (; t < n_tiles; ++t) tile_steps(std::true_type{}, t);
+    const int64_t tile_bytes = (int64_t)kTileRows * D * 2;
+    dma_k = (const char *)kbase + 2 * tile_bytes;
+    dma_v = (const char *)vbase + 2 * tile_bytes;
+    for (; t < n_full - 1; ++t) {
+        tile_steps(std::false_type{}, std::true_type{}, t);
+        dma_k += tile_bytes;
+        dma_v += tile_bytes;
+    }
+    for (; t < n_tiles; ++t) tile_steps(std::true_type{}, std::false_type{}, t);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no tile load may land after the workgroup ends
 
     // dQ^T / dR^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of row my_row
