@@ -484,6 +484,41 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         }
     };
     constexpr int kItemLoads = 3 * TL::NDMA;  // per wave (wave 0 issues one more, last)
+    // The unmasked loop spreads the loads of item it + 2 over the MFMA slots of a step: per-lane
+    // byte offsets inside a complete tile, wave-uniform tile bases. (There every wave fetches the
+    // 64 row scalars -- the same bytes to the same place -- so that the slots hold no branch.)
+    uint32_t toff[TL::NDMA];
+#pragma unroll
+    for (int i = 0; i < TL::NDMA; ++i) {
+        const int c = (w * TL::NDMA + i) * 64 + lane;
+        const int row = c / CPR;
+        toff[i] = (uint32_t)(row * D + ((c % CPR) ^ lds_row_swizzle<D>(row)) * 8) * 2u;
+    }
+    const char *dma_q = nullptr, *dma_r = nullptr, *dma_g = nullptr, *dma_rc = nullptr;
+    uint32_t dma_lds = 0, dma_lds_rc = 0;
+    auto set_dma_item = [&](int it, int stage) __attribute__((always_inline)) {
+        int g, rt;
+        item_of(it, g, rt);
+        const int64_t row = ((int64_t)b * p.Hq + hk * G + g) * T + (int64_t)rt * kTileRows;
+        dma_q = (const char *)p.q + row * D * 2;
+        dma_r = (const char *)p.r + row * D * 2;
+        dma_g = (const char *)p.d_o + row * D * 2;
+        dma_rc = (const char *)p.row_cache + row * 16;
+        dma_lds = lds_base + (uint32_t)(stage * STAGE_CHUNKS + w * TL::NDMA * 64) * 16u;
+        dma_lds_rc = lds_base + (uint32_t)(stage * STAGE_CHUNKS + 3 * TL::CHUNKS) * 16u;
+    };
+    auto dma_slot = [&](int i) __attribute__((always_inline)) {  // load i of 3 * NDMA + 1
+        if (i < TL::NDMA)
+            tile_load16_uniform<false>(toff[i], dma_q, dma_lds + 1024u * i);
+        else if (i < 2 * TL::NDMA)
+            tile_load16_uniform<false>(toff[i - TL::NDMA], dma_r,
+                                       dma_lds + (uint32_t)TL::CHUNKS * 16u + 1024u * (i - TL::NDMA));
+        else if (i < 3 * TL::NDMA)
+            tile_load16_uniform<false>(toff[i - 2 * TL::NDMA], dma_g,
+                                       dma_lds + (uint32_t)(2 * TL::CHUNKS) * 16u + 1024u * (i - 2 * TL::NDMA));
+        else
+            tile_load16_uniform<false>((uint32_t)lane * 16u, dma_rc, dma_lds_rc);
+    };
     // Q-tile pointer of row block rbk of a stage; the R and dO tiles follow at + CHUNKS each
     auto q_block = [&](int stage, int rbk) __attribute__((always_inline)) {
         return (const u32x4 *)(lds + stage * STAGE_CHUNKS + rbk * kBlk * CPR);
@@ -572,7 +607,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         neg_lo = -lo_off;
         span = (unsigned)max(hi_off - lo_off, 0);
     };
-    auto pipeline_step = [&](auto masked_tag, int row_base_cur, int row_base_next, const u32x4 *next_blk,
+    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int row_base_cur, int row_base_next, const u32x4 *next_blk,
                              const u32x4 *cur_blk, const u32x4 *after_blk, const f32x4 *rows_cur,
                              const f32x4 *rows_next, f32x16 &c1, f32x16 &c2, f32x16 &ca, f32x16 &n1,
                              f32x16 &n2, f32x16 &na) __attribute__((always_inline)) {
@@ -581,9 +616,13 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         row_window(row_base_cur, nlo_c, span_c);
         row_window(row_base_next, nlo_n, span_n);
         constexpr int SLOTS1 = 3 * KSTEPS, SLOTS2 = 6 * NDB;
+        constexpr bool DMA = decltype(dma_tag)::value;  // this step also fetches the item set_dma_item named
+        static_assert(3 * TL::NDMA + 1 <= SLOTS1, "one tile load per slot");
 #pragma unroll
         for (int sl = 0; sl < SLOTS1; ++sl) {
             const int ks = sl / 3, which = sl % 3;
+            if constexpr (DMA)
+                if (sl < 3 * TL::NDMA + 1) dma_slot(sl);
             f32x16 &dst = which == 0 ? n1 : which == 1 ? n2 : na;
             if (ks == 0)
                 mfma32_scores_first<true>(dst, f1[sl], which == 2 ? vf[ks] : kf[ks]);
@@ -663,29 +702,36 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         for (int f = 0; f < LA; ++f) load_f1(q_block(0, 1), f);
     }
     int stage = 0;
-    auto item_steps = [&](auto masked_tag, int it) __attribute__((always_inline)) {
+    auto item_steps = [&](auto masked_tag, auto dma_tag, int it) __attribute__((always_inline)) {
+        constexpr bool DMA = decltype(dma_tag)::value;
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
         const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
         tile_barrier<0>();  // item it + 1 has landed; item it - 1 is free
-        if (it + 2 < n_items) issue_item(it + 2, free_stage);
+        if constexpr (DMA) {  // item it + 2 is a complete tile: fetched by the first step, slot by slot
+            set_dma_item(it + 2, free_stage);
+        } else {
+            if (it + 2 < n_items) issue_item(it + 2, free_stage);
+        }
         int g_cur, rt_cur, g_after, rt_after;
         item_of(it, g_cur, rt_cur);
         item_of(it + 1 < n_items ? it + 1 : it, g_after, rt_after);  // (past the end: never used)
         const int row_base = rt_cur * kTileRows, row_base_after = rt_after * kTileRows;
         // row block 0 -> w, g; dV / dK; scores of row block 1; fragments of the next item
-        pipeline_step(masked_tag, row_base, row_base + kBlk, q_block(stage, 1), q_block(stage, 0),
+        pipeline_step(masked_tag, dma_tag, row_base, row_base + kBlk, q_block(stage, 1), q_block(stage, 0),
                       q_block(next_stage, 0), row_scalars(stage, 0), row_scalars(stage, 1), a1, a2, a3, b1, b2,
                       b3);
         // row block 1 -> w, g; dV / dK; scores of row block 0 of the next item
-        pipeline_step(masked_tag, row_base + kBlk, row_base_after, q_block(next_stage, 0), q_block(stage, 1),
+        pipeline_step(masked_tag, std::false_type{}, row_base + kBlk, row_base_after, q_block(next_stage, 0),
+                      q_block(stage, 1),
                       q_block(next_stage, 1), row_scalars(stage, 1), row_scalars(next_stage, 0), b1, b2, b3, a1,
                       a2, a3);
         stage = next_stage;
     };
-    // a step also prepares the lower half of the next item's first block, hence the - 1
+    // a step also prepares the lower half of the next item's first block, and the unmasked loop
+    // fetches item it + 2 as a complete tile: it stops two short of the last unmasked item
     int it = 0;
-    for (; it < n_full_items - 1; ++it) item_steps(std::false_type{}, it);
-    for (; it < n_items; ++it) item_steps(std::true_type{}, it);
+    for (; it < n_full_items - 2; ++it) item_steps(std::false_type{}, std::true_type{}, it);
+    for (; it < n_items; ++it) item_steps(std::true_type{}, std::false_type{}, it);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no tile load may land after the workgroup ends
 
     // dK^T / dV^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of key my_key
