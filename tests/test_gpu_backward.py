@@ -157,3 +157,42 @@ def test_backward_fp32_path(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, causa
     for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
         scale = max(np.abs(ref).max(), 1.0)   # dQ = dR = 0 exactly when a row has one key (a - tau cancels)
         assert np.abs(host(got) - ref).max() <= F32_MAX_REL * scale, (name, np.abs(host(got) - ref).max(), scale)
+
+
+def test_forward_and_backward_in_a_hip_graph(plx, synth):
+    """Forward (with the row cache) and backward captured once, replayed with new inputs in the
+    captured buffers: every replay equals the eager result bit for bit."""
+    import ctypes
+
+    y, g = _inputs(synth, 1, 8, 2, 300, 300, 128, 2800)
+    lib = plx.load_library()
+    o, vbar = torch.empty_like(y["q"]), torch.empty_like(y["q"])
+    stats = torch.empty(y["q"].shape[:3] + (2,), dtype=torch.float32, device=DEV)
+    dq, dr = torch.empty_like(y["q"]), torch.empty_like(y["q"])
+    dk, dv = torch.empty_like(y["k"]), torch.empty_like(y["k"])
+    ws = torch.empty(plx.parallax_prefill_backward_workspace_bytes(1, 8, 300) // 4, dtype=torch.float32,
+                     device=DEV)
+    fa = plx.prefill_args(y["q"], y["r"], y["k"], y["v"], o, y["scale"], True, True)
+    fa.vbar, fa.row_stats = vbar.data_ptr(), stats.data_ptr()
+    ba = plx.prefill_bwd_args(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g, dq, dr, dk, dv, y["scale"],
+                              True, ws)
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        cap = int(torch.cuda.current_stream().cuda_stream)
+        assert lib.parallax_prefill(ctypes.byref(fa), cap) == 0
+        assert lib.parallax_prefill_backward(ctypes.byref(ba), cap) == 0
+    torch.cuda.current_stream().wait_stream(side)
+    gen = torch.Generator(device=DEV).manual_seed(2801)
+    for rep in range(3):
+        if rep:
+            y["q"].copy_(torch.randn(y["q"].shape, generator=gen, device=DEV))
+            g.copy_(torch.randn(g.shape, generator=gen, device=DEV))
+        for t in (dq, dr, dk, dv):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (dq, dr, dk, dv)]
+        _, _, _, eager = _run(plx, y, g, True)
+        for a, b in zip(got, eager):
+            assert torch.equal(a, b)
