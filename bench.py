@@ -576,6 +576,26 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
         del y, po, qc, rc
     extra["prefill_more"] = more
 
+    # RMSNorm + RoPE on q, rho, k of the config-4 shape in one launch (read once, written once)
+    B, T, Hq, Hkv, d = 4, 4096, 16, 8, 128
+    y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1009, device=dev)
+    gam = [torch.ones(d, dtype=torch.float32, device=dev) for _ in range(3)]
+    outs = [torch.empty_like(y[n]) for n in ("q", "r", "k")]
+    na = plx.norm_rope_args([(y["q"], gam[0], True, outs[0]), (y["r"], gam[1], True, outs[1]),
+                             (y["k"], gam[2], True, outs[2])])
+
+    def nr_step():
+        st = lib.parallax_norm_rope(ctypes.byref(na), sptr)
+        if st != 0:
+            raise plx.ParallaxError(st, "parallax_norm_rope")
+
+    us = _time_events(torch, nr_step, 5, 50)
+    nbytes = 2 * sum(t.numel() * 2 for t in outs)
+    extra["norm_rope"] = {"workload": "RMSNorm + RoPE on q, rho [4,16,4096,128] and k [4,8,4096,128] bf16, one launch",
+                          "us": round(us, 1), "GBps": round(nbytes / us / 1e3, 1),
+                          "frac_of_8TBps": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+    del y, outs
+
     # sliding window (a row sees its own position and the window - 1 before it)
     win = []
     for (B, T, W) in [(2, 16384, 4096), (2, 16384, 1024)]:

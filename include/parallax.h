@@ -222,6 +222,40 @@ typedef struct {
 size_t parallax_prefill_backward_workspace_bytes(int32_t B, int32_t Hq, int32_t T);
 plx_status parallax_prefill_backward(const plx_prefill_bwd_args *args, void *hip_stream);
 
+/*
+ * RMSNorm over the head dimension, then rotary position embedding, on up to three tensors of one
+ * layer (q, rho, k) in one launch -- what the paper's language-model runs apply in front of the
+ * attention call (Sec. 5 experiment setup, backbone appendix: RMSNorm on q, k and rho; RoPE with
+ * base 1e6 on q, k and optionally rho). The paper gives no formulas; the standard ones are used:
+ *     y = x / sqrt(mean_c(x_c^2) + eps) * gamma
+ *     (y_2i, y_2i+1) rotated by pos * theta^(-2i/d), pos = pos0[b] + t   (adjacent pairs)
+ *   tensors[i].x, .y  [B, H_i, T, d] contiguous, 16-byte aligned; y may be x (in place)
+ *   tensors[i].gamma  [d] fp32 on the device
+ *   tensors[i].rope   0 = RMSNorm only
+ *   pos0              [B] int32 on the device (position of row 0; a decode step passes L_b - 1),
+ *                     or NULL = 0
+ *   d                 bf16: 64 or 128; fp32: 16, 32, 64, 128 or 256
+ */
+typedef struct {
+    const void *x;
+    void *y;
+    const float *gamma;
+    int32_t H;
+    int32_t rope;
+} plx_norm_rope_tensor;
+
+typedef struct {
+    plx_norm_rope_tensor tensors[3];
+    int32_t n_tensors; /* 1..3 */
+    int32_t B, T, d;
+    const int32_t *pos0;
+    float eps;   /* >= 0 */
+    float theta; /* > 1 */
+    plx_dtype dtype;
+} plx_norm_rope_args;
+
+plx_status parallax_norm_rope(const plx_norm_rope_args *args, void *hip_stream);
+
 /* Plain device-to-device copy kernel (16 bytes per lane, grid-stride). Used to calibrate
  * hardware byte counters and to measure the achievable streaming bandwidth next to the
  * attention kernels. bytes must be a multiple of 16; pointers 16-byte aligned. */

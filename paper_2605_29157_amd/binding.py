@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "parallax_decode_workspace_bytes", "parallax_decode_num_splits", "parallax_decode",
     "parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused",
     "parallax_prefill", "parallax_prefill_backward", "parallax_prefill_backward_workspace_bytes",
-    "parallax_util_copy", "parallax_util_read",
+    "parallax_norm_rope", "parallax_util_copy", "parallax_util_read",
     "parallax_util_read_sink_slots", "parallax_strerror", "parallax_version",
 )
 
@@ -90,6 +90,18 @@ class plx_prefill_bwd_args(ctypes.Structure):
     ]
 
 
+class plx_norm_rope_tensor(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("y", ctypes.c_void_p), ("gamma", ctypes.c_void_p),
+                ("H", ctypes.c_int32), ("rope", ctypes.c_int32)]
+
+
+class plx_norm_rope_args(ctypes.Structure):
+    _fields_ = [("tensors", plx_norm_rope_tensor * 3), ("n_tensors", ctypes.c_int32),
+                ("B", ctypes.c_int32), ("T", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("pos0", ctypes.c_void_p), ("eps", ctypes.c_float), ("theta", ctypes.c_float),
+                ("dtype", ctypes.c_int)]
+
+
 class ParallaxError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -123,6 +135,8 @@ def load_library() -> ctypes.CDLL:
         lib.parallax_prefill_backward.restype = ctypes.c_int
         lib.parallax_prefill_backward_workspace_bytes.argtypes = [ctypes.c_int32] * 3
         lib.parallax_prefill_backward_workspace_bytes.restype = ctypes.c_size_t
+        lib.parallax_norm_rope.argtypes = [ctypes.POINTER(plx_norm_rope_args), ctypes.c_void_p]
+        lib.parallax_norm_rope.restype = ctypes.c_int
         lib.parallax_util_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                            ctypes.c_void_p]
         lib.parallax_util_copy.restype = ctypes.c_int
@@ -365,6 +379,39 @@ def parallax_prefill_backward(q, r, k, v, o, vbar, row_stats, d_o, scale, causal
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_prefill_backward")
     return dq, dr, dk, dv
+
+
+def norm_rope_args(tensors, pos0=None, eps=1e-6, theta=1.0e6):
+    """Fill a plx_norm_rope_args. tensors: up to three (x, gamma, rope, out) with x, out
+    [B, H, T, d] contiguous (out may be x) and gamma [d] fp32."""
+    a = plx_norm_rope_args()
+    a.n_tensors = len(tensors)
+    B, _, T, d = tensors[0][0].shape
+    for i, (x, gamma, use_rope, out) in enumerate(tensors):
+        if not (x.is_cuda and x.is_contiguous() and out.is_contiguous() and gamma.dtype == torch.float32):
+            raise ValueError("parallax_norm_rope needs contiguous device tensors and fp32 weights")
+        if x.shape[0] != B or x.shape[2] != T or x.shape[3] != d or out.shape != x.shape:
+            raise ValueError("the tensors of one call share B, T and d")
+        a.tensors[i].x, a.tensors[i].y, a.tensors[i].gamma = x.data_ptr(), out.data_ptr(), gamma.data_ptr()
+        a.tensors[i].H, a.tensors[i].rope = x.shape[1], 1 if use_rope else 0
+    a.B, a.T, a.d = B, T, d
+    a.pos0 = pos0.data_ptr() if pos0 is not None else None
+    a.eps, a.theta = float(eps), float(theta)
+    a.dtype = _dtype_code(tensors[0][0])
+    return a
+
+
+def parallax_norm_rope(tensors, pos0=None, eps=1e-6, theta=1.0e6, stream=None, inplace=False):
+    """RMSNorm + RoPE on up to three tensors in one launch. tensors: list of (x, gamma, rope);
+    returns the list of results (the inputs themselves with inplace=True)."""
+    if pos0 is not None and pos0.dtype != torch.int32:
+        raise TypeError("pos0 must be int32")
+    full = [(x, g, rp, x if inplace else torch.empty_like(x)) for (x, g, rp) in tensors]
+    a = norm_rope_args(full, pos0, eps, theta)
+    st = load_library().parallax_norm_rope(ctypes.byref(a), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_norm_rope")
+    return [t[3] for t in full]
 
 
 def parallax_util_copy(dst, src, stream=None):

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(PKG, "libparallax_hip.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
 
 SOURCES = ["parallax_api.hip", "decode_bf16.hip", "prefill_bf16.hip", "prefill_bwd_bf16.hip",
-           "generic_f32.hip", "util_kernels.hip"]
+           "generic_f32.hip", "norm_rope.hip", "util_kernels.hip"]
 
 # packed-fp32 instructions are disabled for all device code (hipcc's host pass prints a
 # harmless "not a recognized feature" note for the flag)

@@ -1,0 +1,117 @@
+// RMSNorm over the head dimension followed by rotary position embedding, for up to three
+// tensors (q, rho, k of one layer) in ONE launch -- the operations the paper's language-model
+// runs apply to q, k and rho in front of the attention call (experiment setup of Sec. 5 and the
+// backbone appendix: RMSNorm on q, k, rho; RoPE with base 1e6). Standard formulas:
+//     y = x / sqrt(mean_c(x_c^2) + eps) * gamma
+//     (y_2i, y_2i+1) rotated by pos * theta^(-2i/d)   (adjacent pairs)
+// HBM bound: every element is read once and written once, 16 bytes per lane; the lanes of one row
+// (d * element size / 16 of them) share the sum of squares through lane shuffles. The angle is
+// formed and reduced modulo 2 pi in double precision (pos * frequency reaches 1e5 and more, where
+// fp32 would lose the fraction), sine and cosine are taken in single precision -- once per
+// (position, pair), for all heads of all tensors.
+#include "plx_device.h"
+#include "plx_kernels.h"
+
+namespace plx {
+
+template <typename T>
+struct Chunk;  // 16 bytes of a row
+template <>
+struct Chunk<__bf16> {
+    static constexpr int E = 8;
+    u32x4 raw;
+    __device__ float get(int e) const { return (e & 1) ? bf16_hi_f32(raw[e >> 1]) : bf16_lo_f32(raw[e >> 1]); }
+    __device__ void set_pair(int j, float a, float b) { raw[j] = pack_bf16(a, b); }
+};
+template <>
+struct Chunk<float> {
+    static constexpr int E = 4;
+    f32x4 raw;
+    __device__ float get(int e) const { return raw[e]; }
+    __device__ void set_pair(int j, float a, float b) { raw[2 * j] = a, raw[2 * j + 1] = b; }
+};
+
+// A wave owns 64 / (lanes per row) consecutive positions of one sequence and walks over every
+// head of every tensor at those positions: sine and cosine of a (position, pair) are computed
+// once and serve all heads of q, rho and k.
+template <typename T>
+__global__ __launch_bounds__(256) void norm_rope_kernel(NormRopeParams p) {
+    constexpr int E = Chunk<T>::E;
+    constexpr int UNROLL = 4;                      // heads in flight per lane
+    const int lpr = p.d / E;                       // lanes per row (a power of two <= 64)
+    const int rows_per_wave = 64 / lpr;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lr = lane % lpr;                     // this lane's chunk of its row
+    const int t_per_seq = (p.T + rows_per_wave - 1) / rows_per_wave;  // waves per sequence
+    const int64_t wid = (int64_t)blockIdx.x * 4 + wave;
+    if (wid >= (int64_t)p.B * t_per_seq) return;   // whole waves only: no barrier below
+    const int b = (int)(wid / t_per_seq);
+    const int t = (int)(wid % t_per_seq) * rows_per_wave + lane / lpr;
+    const bool live = t < p.T;
+    const int ld_t = live ? t : p.T - 1;
+
+    float cs[E / 2], sn[E / 2];
+    {
+        const double pos = (double)((p.pos0 ? p.pos0[b] : 0) + ld_t);
+        const double log2_theta = log2((double)p.theta);
+#pragma unroll
+        for (int j = 0; j < E / 2; ++j) {
+            const int dim = lr * E + 2 * j;  // even dimension of the pair
+            double ang = pos * exp2(-(double)dim / (double)p.d * log2_theta);
+            ang -= floor(ang * 0.15915494309189535) * 6.283185307179586;  // modulo 2 pi
+            sincosf((float)ang, &sn[j], &cs[j]);
+        }
+    }
+    const float inv_d = 1.0f / (float)p.d;
+    for (int i = 0; i < p.n_tensors; ++i) {
+        const NormRopeTensor ten = p.t[i];
+        float gam[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) gam[e] = ten.gamma[lr * E + e];
+        const decltype(Chunk<T>::raw) *src = (const decltype(Chunk<T>::raw) *)ten.x;
+        decltype(Chunk<T>::raw) *dst = (decltype(Chunk<T>::raw) *)ten.y;
+        for (int h0 = 0; h0 < ten.H; h0 += UNROLL) {
+            Chunk<T> c[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {  // all loads of the trip first
+                const int h = min(h0 + u, ten.H - 1);
+                c[u].raw = src[(((int64_t)b * ten.H + h) * p.T + ld_t) * lpr + lr];
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                float ss = 0.f;
+#pragma unroll
+                for (int e = 0; e < E; ++e) ss = fmaf(c[u].get(e), c[u].get(e), ss);
+                for (int off = 1; off < lpr; off <<= 1) ss += __shfl_xor(ss, off, 64);
+                const float rinv = 1.0f / sqrtf(ss * inv_d + p.eps);
+#pragma unroll
+                for (int j = 0; j < E / 2; ++j) {
+                    float y0 = c[u].get(2 * j) * rinv * gam[2 * j];
+                    float y1 = c[u].get(2 * j + 1) * rinv * gam[2 * j + 1];
+                    if (ten.rope) {
+                        const float r0 = y0 * cs[j] - y1 * sn[j], r1 = y0 * sn[j] + y1 * cs[j];
+                        y0 = r0, y1 = r1;
+                    }
+                    c[u].set_pair(j, y0, y1);
+                }
+                if (live && h0 + u < ten.H)
+                    dst[(((int64_t)b * ten.H + h0 + u) * p.T + t) * lpr + lr] = c[u].raw;
+            }
+        }
+    }
+}
+
+hipError_t launch_norm_rope(const NormRopeParams &p, bool f32, hipStream_t stream) {
+    const int elems = f32 ? 4 : 8;
+    const int rows_per_wave = 64 / (p.d / elems);
+    const int64_t waves = (int64_t)p.B * ((p.T + rows_per_wave - 1) / rows_per_wave);
+    const int64_t blocks = (waves + 3) / 4;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (f32)
+        hipLaunchKernelGGL(norm_rope_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL(norm_rope_kernel<__bf16>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace plx

@@ -321,6 +321,33 @@ plx_status parallax_prefill_backward(const plx_prefill_bwd_args *a, void *hip_st
     return err == hipSuccess ? PLX_OK : PLX_ERR_LAUNCH;
 }
 
+plx_status parallax_norm_rope(const plx_norm_rope_args *a, void *hip_stream) {
+    if (!a) return PLX_ERR_NULL;
+    if (a->dtype != PLX_BF16 && a->dtype != PLX_F32) return PLX_ERR_DTYPE;
+    if (a->n_tensors < 1 || a->n_tensors > 3 || a->B <= 0 || a->T <= 0) return PLX_ERR_SHAPE;
+    const bool f32 = a->dtype == PLX_F32;
+    const int32_t d = a->d;
+    if (f32 ? !(d == 16 || d == 32 || d == 64 || d == 128 || d == 256) : !(d == 64 || d == 128))
+        return PLX_ERR_SHAPE;
+    if (!(a->eps >= 0.f && a->eps <= 3.0e38f) || !(a->theta > 1.f && a->theta <= 3.0e38f))
+        return PLX_ERR_SCALE;
+    if (a->pos0 && (reinterpret_cast<uintptr_t>(a->pos0) & 3u)) return PLX_ERR_ALIGN;
+    plx::NormRopeParams p{};
+    for (int i = 0; i < a->n_tensors; ++i) {
+        const plx_norm_rope_tensor &t = a->tensors[i];
+        if (!t.x || !t.y || !t.gamma) return PLX_ERR_NULL;
+        if (!aligned16(t.x) || !aligned16(t.y) || (reinterpret_cast<uintptr_t>(t.gamma) & 3u))
+            return PLX_ERR_ALIGN;
+        if (t.H <= 0 || (int64_t)a->B * t.H * a->T > 0x7fffffffLL) return PLX_ERR_SHAPE;
+        p.t[i].x = t.x, p.t[i].y = t.y, p.t[i].gamma = t.gamma, p.t[i].H = t.H, p.t[i].rope = t.rope ? 1 : 0;
+    }
+    p.n_tensors = a->n_tensors, p.B = a->B, p.T = a->T, p.d = d;
+    p.pos0 = a->pos0, p.eps = a->eps, p.theta = a->theta;
+    return plx::launch_norm_rope(p, f32, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
+}
+
 plx_status parallax_util_copy(void *dst, const void *src, size_t bytes, void *hip_stream) {
     if (!dst || !src) return PLX_ERR_NULL;
     if (bytes % 16 != 0) return PLX_ERR_SHAPE;

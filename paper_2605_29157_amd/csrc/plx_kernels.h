@@ -54,6 +54,20 @@ struct PrefillBwdParams {
     int32_t causal;
 };
 
+// RMSNorm + RoPE on up to three contiguous [B, H, T, d] tensors of one (B, T, d).
+struct NormRopeTensor {
+    const void *x;
+    void *y;             // may be x
+    const float *gamma;  // [d]
+    int32_t H, rope;     // heads of this tensor; 0 = RMSNorm only
+};
+struct NormRopeParams {
+    NormRopeTensor t[3];
+    int32_t n_tensors, B, T, d;
+    const int32_t *pos0;  // [B] position of row 0 of every sequence, or NULL = 0
+    float eps, theta;
+};
+
 // Each returns hipSuccess or the launch error. No allocation, no synchronisation.
 hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_decode_combine(const DecodeParams &p, hipStream_t stream);
@@ -62,6 +76,7 @@ hipError_t launch_prefill_bwd_bf16(const PrefillBwdParams &p, hipStream_t stream
 hipError_t launch_prefill_bwd_f32(const PrefillBwdParams &p, hipStream_t stream);
 hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream);
+hipError_t launch_norm_rope(const NormRopeParams &p, bool f32, hipStream_t stream);
 hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);
 hipError_t launch_util_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
 constexpr int kReadSinkSlots = 4096;

@@ -243,3 +243,38 @@ def test_prefill_backward_rejects_bad_arguments_before_launch(binding):
     assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_SHAPE
     f.window, f.use_r = 0, 0
     assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_SHAPE
+
+
+def test_norm_rope_rejects_bad_arguments_before_launch(binding):
+    lib = binding.load_library()
+
+    def good():
+        a = binding.plx_norm_rope_args()
+        a.n_tensors, a.B, a.T, a.d = 2, 1, 4, 128
+        for i in range(2):
+            a.tensors[i].x = a.tensors[i].y = 0x1000
+            a.tensors[i].gamma, a.tensors[i].H, a.tensors[i].rope = 0x2000, 2, 1
+        a.eps, a.theta, a.dtype = 1e-6, 1.0e6, binding.PLX_BF16
+        return a
+
+    call = lambda a: lib.parallax_norm_rope(ctypes.byref(a), None)
+    assert lib.parallax_norm_rope(None, None) == binding.PLX_ERR_NULL
+    a = good(); a.n_tensors = 4
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.d = 96
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.dtype = binding.PLX_F32; a.d = 48
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.theta = 1.0
+    assert call(a) == binding.PLX_ERR_SCALE
+    a = good(); a.eps = float("nan")
+    assert call(a) == binding.PLX_ERR_SCALE
+    a = good(); a.tensors[1].gamma = None
+    assert call(a) == binding.PLX_ERR_NULL
+    a = good(); a.tensors[0].y = 0x1004
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = good(); a.tensors[1].H = 0
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.pos0 = 0x3001
+    assert call(a) == binding.PLX_ERR_ALIGN
+    assert ctypes.sizeof(binding.plx_norm_rope_args) == 3 * 32 + 16 + 8 + 8 + 8
