@@ -395,3 +395,29 @@ def test_config5b_long_context_sampled(plx, synth, oracle):
     ref = oracle_decode(oracle, x, seqs=seqs)
     assert rel_l2(got[seqs], ref) <= BF16_REL_L2
     assert np.isfinite(got).all()
+
+
+def test_block_sparse_decode_is_a_block_table_of_selected_pages(plx, synth, oracle):
+    """Block-sparse decode needs no kernel of its own: a block table that lists only the selected
+    pages of a sequence (any order is fine for a single query row -- the sum over keys does not
+    depend on it) is attention over exactly those keys. Checked against the oracle on the
+    gathered keys."""
+    page = 64
+    x = synth.decode_inputs(3, 16, 8, 2048, 128, seed=130, device=DEV)
+    kp, vp, table = synth.paged_cache(x, page, seed=131)
+    rng = np.random.default_rng(132)
+    keep = [np.sort(rng.choice(2048 // page, size=n, replace=False)) for n in (5, 17, 32)]
+    width = max(len(s) for s in keep)
+    sel = torch.zeros((3, width), dtype=torch.int32, device=DEV)
+    for b, s in enumerate(keep):
+        sel[b, :len(s)] = table[b, torch.as_tensor(s, device=DEV)]
+    lens = torch.tensor([len(s) * page for s in keep], dtype=torch.int32, device=DEV)
+    out = plx.parallax_decode(x["q"], x["r"], kp, vp, x["scale"], seq_lens=lens, block_table=sel,
+                              max_len=width * page)
+    torch.cuda.synchronize()
+    q, r, k, v = (host(x[n]) for n in "qrkv")
+    for b, s in enumerate(keep):
+        cols = np.concatenate([np.arange(p * page, (p + 1) * page) for p in s])
+        ref = oracle.forward(q[b:b + 1, :, None], r[b:b + 1, :, None], k[b:b + 1][:, :, cols],
+                             v[b:b + 1][:, :, cols], x["scale"])[0, :, 0]
+        assert rel_l2(host(out)[b], ref) <= BF16_REL_L2, b
