@@ -634,6 +634,47 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
                     "kv_GBps_of_keys_in_window": round(B * Hkv * keys * d * 4 / us / 1e3, 1)})
         del xs, w_args, ws2
     extra["sliding_window"] = win
+
+    # block-sparse prefill: each 128-row block visits a listed subset of the 64-key tiles
+    # (flops = 8 d per allowed (row, key) pair inside the listed tiles, intersected with the causal set)
+    import numpy as np
+
+    bs = []
+    for (B, T) in [(4, 4096), (2, 16384)]:
+        Hq, Hkv, d = 16, 8, 128
+        y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1010, device=dev)
+        po = torch.empty_like(y["q"])
+        nrb, nkt = T // plx.BLOCK_ROWS, T // plx.BLOCK_KEYS
+        diag = 2 * np.arange(nrb)[:, None] + 1                  # last tile a row block can see
+        band = (np.arange(nkt)[None, :] > diag - 32) | (np.arange(nkt)[None, :] < 4)
+        rnd = np.random.default_rng(1011).random((nrb, nkt)) < 0.25
+        for name, bm in [("every causal tile", np.ones((nrb, nkt), bool)),
+                         ("band of 32 tiles + first 4", band), ("random 25% of tiles", rnd)]:
+            bm = bm & (np.arange(nkt)[None, :] <= diag)
+            row_ptr, tile_idx, Bs, Hs = plx.block_mask_lists(torch.as_tensor(bm, device=dev))
+            a = plx.prefill_args(y["q"], y["r"], y["k"], y["v"], po, y["scale"], True, True)
+            a.sparse_row_ptr, a.sparse_tile_idx = row_ptr.data_ptr(), tile_idx.data_ptr()
+            a.sparse_batch, a.sparse_heads = Bs, Hs
+
+            def sstep():
+                st = lib.parallax_prefill(ctypes.byref(a), sptr)
+                if st != 0:
+                    raise plx.ParallaxError(st, "block-sparse bench")
+
+            us = _time_events(torch, sstep, 2, 10)
+            # a listed tile strictly below the diagonal holds 128 * 64 pairs; the two on it 64 * 65 / 2
+            # + 64 * 64 and 64 * 65 / 2 (row block i: tiles 2i and 2i + 1)
+            below = int((bm & (np.arange(nkt)[None, :] < diag - 1)).sum())
+            on_lo = int(bm[np.arange(nrb), 2 * np.arange(nrb)].sum())
+            on_hi = int(bm[np.arange(nrb), 2 * np.arange(nrb) + 1].sum())
+            pairs = below * 128 * 64 + on_lo * (64 * 65 // 2 + 64 * 64) + on_hi * (64 * 65 // 2)
+            flops = B * Hq * 8 * d * pairs
+            bs.append({"workload": "block-sparse causal prefill B=%d T=%d d=128, %s" % (B, T, name),
+                       "tiles_listed": int(bm.sum()), "tiles_causal": int((np.arange(nkt)[None, :] <= diag).sum()),
+                       "us": round(us, 1), "TFLOPs": round(flops / us / 1e6, 1),
+                       "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
+        del y, po
+    extra["block_sparse"] = bs
     return extra
 
 

@@ -189,6 +189,20 @@ typedef struct {
      *              log-sum-exp in the exp2 domain) and ubar = sum_j p_j rho.k_j */
     void *vbar;
     float *row_stats;
+    /* Block-sparse attention (one of the sparsity patterns Sec. 5 says carry over; bf16, use_r,
+     * no window, no row cache): softmax, ubar and the output run over the listed key tiles
+     * only (intersected with the causal set when causal != 0). Blocks are the kernel's tiles:
+     * 128 query rows x 64 keys. Row block rb of list-batch sb and list-head sh visits the key
+     * tiles sparse_tile_idx[sparse_row_ptr[e] .. sparse_row_ptr[e + 1]),
+     * e = (sb * sparse_heads + sh) * ceil(T / 128) + rb, in ASCENDING order, each at most once.
+     * sparse_batch / sparse_heads are 1 (lists shared by all sequences / heads) or B / Hq. Both
+     * arrays are int32 on the device; entries are clamped to existing tiles but not otherwise
+     * checked (a list that does not ascend gives wrong results for its row block, never an access
+     * outside the tensors); the arrays must not be written while the kernel runs. A row block with an empty list (and any row none of whose listed keys is causal-
+     * visible) returns zeros. NULL sparse_row_ptr = dense. */
+    const int32_t *sparse_row_ptr;
+    const int32_t *sparse_tile_idx;
+    int32_t sparse_batch, sparse_heads;
 } plx_prefill_args;
 
 plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);

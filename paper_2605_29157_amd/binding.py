@@ -69,6 +69,8 @@ class plx_prefill_args(ctypes.Structure):
         ("Tkv", ctypes.c_int32),
         ("window", ctypes.c_int32),
         ("vbar", ctypes.c_void_p), ("row_stats", ctypes.c_void_p),
+        ("sparse_row_ptr", ctypes.c_void_p), ("sparse_tile_idx", ctypes.c_void_p),
+        ("sparse_batch", ctypes.c_int32), ("sparse_heads", ctypes.c_int32),
     ]
 
 
@@ -317,8 +319,29 @@ def prefill_args(q, r, k, v, out, scale, causal=True, use_r=True, window=0):
     return a
 
 
+BLOCK_ROWS, BLOCK_KEYS = 128, 64  # the block-sparse granularity: the prefill kernel's tiles
+
+
+def block_mask_lists(block_mask):
+    """Block mask [(B,) (Hq,) ceil(T/128), ceil(Tkv/64)] (bool, device) -> (row_ptr, tile_idx,
+    sparse_batch, sparse_heads) for plx_prefill_args: per row block the ascending indices of its
+    key tiles. Index bookkeeping only."""
+    m = block_mask.to(torch.bool)
+    while m.dim() < 4:
+        m = m.unsqueeze(0)
+    Bs, Hs, nrb, nkt = m.shape
+    flat = m.reshape(-1, nkt)
+    counts = flat.sum(dim=1)
+    row_ptr = torch.zeros(flat.shape[0] + 1, dtype=torch.int32, device=m.device)
+    row_ptr[1:] = torch.cumsum(counts, 0).to(torch.int32)
+    tile_idx = torch.nonzero(flat)[:, 1].to(torch.int32).contiguous()  # row-major: ascending per row
+    if tile_idx.numel() == 0:
+        tile_idx = torch.zeros(1, dtype=torch.int32, device=m.device)
+    return row_ptr, tile_idx, Bs, Hs
+
+
 def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None, window=0,
-                     save_for_backward=False):
+                     save_for_backward=False, block_mask=None):
     """Parallax prefill forward over T query rows and Tkv keys (causal: the rows are the last
     T positions of the Tkv-long sequence). With save_for_backward the kernel also writes the row
     cache of the backward pass and (out, vbar, row_stats) is returned."""
@@ -332,6 +355,13 @@ def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, strea
     if out is None:
         out = torch.empty_like(q)
     a = prefill_args(q, r, k, v, out, scale, causal, use_r, window)
+    if block_mask is not None:
+        nrb, nkt = -(-q.shape[2] // BLOCK_ROWS), -(-k.shape[2] // BLOCK_KEYS)
+        if tuple(block_mask.shape[-2:]) != (nrb, nkt):
+            raise ValueError("block_mask must end in [ceil(T/128), ceil(Tkv/64)] = [%d, %d]" % (nrb, nkt))
+        row_ptr, tile_idx, Bs, Hs = block_mask_lists(block_mask.to(q.device))
+        a.sparse_row_ptr, a.sparse_tile_idx = row_ptr.data_ptr(), tile_idx.data_ptr()
+        a.sparse_batch, a.sparse_heads = Bs, Hs
     if save_for_backward:
         vbar = torch.empty_like(out)
         row_stats = torch.empty(q.shape[:3] + (2,), dtype=torch.float32, device=q.device)

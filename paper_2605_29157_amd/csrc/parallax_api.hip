@@ -271,6 +271,18 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
     }
     p.scale = a->scale, p.causal = a->causal ? 1 : 0, p.use_r = a->use_r ? 1 : 0;
     p.window = a->window;
+    if ((a->sparse_row_ptr != nullptr) != (a->sparse_tile_idx != nullptr)) return PLX_ERR_NULL;
+    if (a->sparse_row_ptr) {
+        if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
+        if (!a->use_r || a->window > 0 || a->row_stats || a->vbar) return PLX_ERR_SHAPE;
+        if ((a->sparse_batch != 1 && a->sparse_batch != a->B) ||
+            (a->sparse_heads != 1 && a->sparse_heads != a->Hq))
+            return PLX_ERR_SHAPE;
+        if ((reinterpret_cast<uintptr_t>(a->sparse_row_ptr) | reinterpret_cast<uintptr_t>(a->sparse_tile_idx)) & 3u)
+            return PLX_ERR_ALIGN;
+        p.sparse_row_ptr = a->sparse_row_ptr, p.sparse_tile_idx = a->sparse_tile_idx;
+        p.sparse_batch = a->sparse_batch, p.sparse_heads = a->sparse_heads;
+    }
     if ((a->vbar != nullptr) != (a->row_stats != nullptr)) return PLX_ERR_NULL;
     if (a->row_stats) {
         if (!a->use_r || a->window > 0) return PLX_ERR_SHAPE;

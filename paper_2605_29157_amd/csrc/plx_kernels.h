@@ -39,6 +39,11 @@ struct PrefillParams {
     // [B, Hq, T, 2] fp32 = (log-sum-exp of the scaled scores in the exp2 domain, ubar)
     void *vbar;
     float *row_stats;
+    // block-sparse (bf16, use_r, no window): row block rb of (batch sb, head sh) visits the key
+    // tiles sparse_tile_idx[sparse_row_ptr[e] .. sparse_row_ptr[e + 1]), e = (sb * sparse_heads +
+    // sh) * ceil(T / 128) + rb, ascending; sparse_batch / sparse_heads = 1 shares the lists
+    const int32_t *sparse_row_ptr, *sparse_tile_idx;
+    int32_t sparse_batch, sparse_heads;
 };
 
 // Backward of the prefill forward; every tensor contiguous: q-like [B, Hq, T, d], k-like

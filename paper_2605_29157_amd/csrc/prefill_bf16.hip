@@ -75,10 +75,11 @@ __device__ unsigned long long plx_pf_stamps[8192 * 12];
 #endif
 
 
-template <int D, bool USE_R, bool CAUSAL, bool WINDOW, bool STATS = false>
+template <int D, bool USE_R, bool CAUSAL, bool WINDOW, bool STATS = false, bool SPARSE = false>
 __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     static_assert(CAUSAL || !WINDOW, "a sliding window needs the rows' positions");
     static_assert(!STATS || (USE_R && !WINDOW), "the row cache is written for the backward pass only");
+    static_assert(!SPARSE || (!WINDOW && !STATS), "block-sparse: its own tile iterator, forward only");
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int KSTEPS = D / 16;        // k-steps of the score contraction
     constexpr int NDB = D / 32;           // 32-wide blocks of output dimensions
@@ -192,10 +193,58 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const __bf16 *vbase = (const __bf16 *)p.v + b * p.vs[0] + hk * p.vs[1] + (int64_t)kt_skip * kBC * p.vs[2];
 
     const int key_end = CAUSAL ? min(Tk, (rb + 1) * kBR + off) : Tk;  // keys this workgroup may need
-    const int n_tiles = (key_end + kBC - 1) / kBC;
+    // Block-sparse: the workgroup visits only the key tiles its row block lists (ascending tile
+    // indices, caller's arrays); the ring position i and the key tile tile_at(i) then differ.
+    // Entries are clamped to existing tiles, listed tiles past the causal limit are dropped.
+    // (read through the constant address space: uniform, never written while the kernel runs, so the
+    // reads are scalar loads that the tile loads in flight do not hold up)
+    using const_i32 = const __attribute__((address_space(4))) int32_t;
+    const_i32 *tile_list = nullptr;
+    int n_list = 0;
+    if constexpr (SPARSE) {
+        const int sb = p.sparse_batch > 1 ? b : 0, sh = p.sparse_heads > 1 ? hq : 0;
+        const int64_t e = ((int64_t)sb * p.sparse_heads + sh) * nrb + rb;
+        const_i32 *row_ptr = (const_i32 *)(uintptr_t)p.sparse_row_ptr;
+        const int first = row_ptr[e];
+        tile_list = (const_i32 *)(uintptr_t)p.sparse_tile_idx + first;
+        n_list = max(row_ptr[e + 1] - first, 0);
+    }
+    // number of leading list entries whose first key lies below `bound` (binary search: the list ascends)
+    auto list_count = [&](int bound) {
+        int lo = 0, hi = n_list;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if ((int64_t)max(tile_list[mid], 0) * kBC < bound)
+                lo = mid + 1;
+            else
+                hi = mid;
+        }
+        return lo;
+    };
+    // all 64 keys of these leading entries exist and are visible to every row of the workgroup
+    const int vis_end = CAUSAL ? min(rb * kBR + off + 1, Tk) : Tk;
+    const int n_list_full = SPARSE ? list_count(vis_end - kBC + 1) : 0;
+    if constexpr (SPARSE) n_list = list_count(key_end);
+    // a row block that lists nothing runs one tile with every key masked: sums of zero, zeros out
+    const bool no_tiles = SPARSE && n_list == 0;
+    auto tile_at = [&](int i) {
+        if constexpr (SPARSE)
+            return no_tiles ? 0 : min(max(tile_list[min(i, n_list - 1)], 0), (Tk - 1) / kBC);
+        else
+            return i;
+    };
+    int n_tiles_ = SPARSE ? max(n_list, 1) : (key_end + kBC - 1) / kBC;
+    // (block-sparse: the count is handed over as an opaque value. Knowing it is at least 1, the
+    // compiler merges the pipeline prologue into the first loop iteration, and that one long
+    // region needs more registers than the file holds.)
+    if constexpr (SPARSE) asm volatile("" : "+s"(n_tiles_));
+    const int n_tiles = n_tiles_;
     // leading tiles whose keys all exist and are visible to every row of the workgroup, less two
     // so that the tile prefetched two ahead inside that loop is always a complete one
-    const int n_full = max(0, min(CAUSAL ? (rb * kBR + off + 1) / kBC : Tk / kBC, Tk / kBC - kDist));
+    // (block-sparse: leading list entries; the entry prefetched two ahead is then not the last
+    // one, the only one that may be the partial tile)
+    const int n_full = SPARSE ? max(0, min(n_list_full, n_list - kDist))
+                              : max(0, min(CAUSAL ? (rb * kBR + off + 1) / kBC : Tk / kBC, Tk / kBC - kDist));
     // sliding window: first key this lane's row sees, and the leading tiles that hold a key
     // some row of the workgroup does not see (its last row starts latest)
     const int row_lo = WINDOW ? my_row + off - p.window + 1 : 0;
@@ -300,7 +349,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // accumulator register r of an S^T block <-> key key_base + 8*(r/4) + 4*h + r%4
     auto key_ok = [&](int key_base, int r) {
         const int key = key_base + 8 * (r >> 2) + 4 * h + (r & 3);
-        return key < Tk && (!CAUSAL || key <= my_row + off) && (!WINDOW || key >= row_lo);
+        return key < Tk && (!CAUSAL || key <= my_row + off) && (!WINDOW || key >= row_lo) && !no_tiles;
     };
 
     // d1 / d2 are accumulated by MFMAs as well: Ones(32 x 16 keys) x P^T gives a block whose
@@ -436,7 +485,8 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // With MASKED, `lim` is this lane's largest allowed key offset inside the block (its 4*h
     // already subtracted) and, with a sliding window, `lo` its smallest: register r holds key
     // offset 8*(r/4) + r%4.
-    const int row_lim = CAUSAL ? min(my_row + off, Tk - 1) : Tk - 1;  // last key this lane's row may see
+    // last key this lane's row may see
+    const int row_lim = no_tiles ? -1 : (CAUSAL ? min(my_row + off, Tk - 1) : Tk - 1);
     auto exp_stages = [&](auto masked_tag, auto sums_tag, f32x16 &s1, f32x16 &s2, int r0, int slot,
                           int slot0, int n_slots, float neg_m, int lim, int lo) {
         constexpr bool MASKED = decltype(masked_tag)::value;
@@ -468,12 +518,12 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         return u32x4{pack_bf16(s[8 * j + 0], s[8 * j + 1]), pack_bf16(s[8 * j + 2], s[8 * j + 3]),
                      pack_bf16(s[8 * j + 4], s[8 * j + 5]), pack_bf16(s[8 * j + 6], s[8 * j + 7])};
     };
-    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int key_base_cur, const u32x4 *tk_next,
+    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int key_base_cur, int key_base_next, const u32x4 *tk_next,
                              const unsigned short *tv_cur, const u32x4 *tk_after, f32x16 &sc1,
                              f32x16 &sc2, f32x16 &sn1, f32x16 &sn2) {
         const int lim_cur = row_lim - key_base_cur - 4 * h;  // current block, next block
-        const int lim_next = lim_cur - kKB;
-        const int lo_cur = row_lo - key_base_cur - 4 * h, lo_next = lo_cur - kKB;
+        const int lim_next = row_lim - key_base_next - 4 * h;
+        const int lo_cur = row_lo - key_base_cur - 4 * h, lo_next = row_lo - key_base_next - 4 * h;
         constexpr int SLOTS1 = 2 * KSTEPS;           // phase 1: one slot per score MFMA
         constexpr bool DMA = decltype(dma_tag)::value;  // this step also fetches tile (dma_tk, dma_tv)
         constexpr bool MASKED = decltype(masked_tag)::value;
@@ -558,7 +608,10 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // stages kt % 3 and (kt+1) % 3 and visible to all waves. The barrier (every wave first waits
     // for its own tile loads) also proves that nobody reads tile kt-1 any more, whose stage then
     // receives tile kt+2: each tile load has a whole iteration to land.
-    if (Tk >= kDist * kBC) {  // workgroup-uniform
+    if constexpr (SPARSE) {  // (the clamping form only: it needs no per-lane offsets kept alive)
+#pragma unroll
+        for (int t = 0; t < kDist; ++t) dma_tile(tile_at(t), t);
+    } else if (Tk >= kDist * kBC) {  // workgroup-uniform
 #pragma unroll
         for (int t = 0; t < kDist; ++t) dma_full_tile(t, t);
     } else {
@@ -591,11 +644,13 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         scores(0, 0, sa1, sa2);
 #pragma unroll
         for (int f = 0; f < kLookAhead; ++f) load_kfrag(k_block_ptr(0, 1), f);
+        int kb0 = tile_at(0) * kBC;  // 0 unless block-sparse
+        if constexpr (SPARSE) asm volatile("" : "+s"(kb0));  // (opaque, for the same reason as n_tiles)
         float tmax = kNegInf;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, key_ok(0, r) ? sa1[r] : kNegInf);
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, key_ok(kb0, r) ? sa1[r] : kNegInf);
         tmax = halves_max(tmax);
-        if constexpr (WINDOW) {
+        if constexpr (WINDOW || SPARSE) {
             // a row whose window starts behind this block takes the block's plain maximum: any
             // finite reference will do (the check after the loops catches one that was too far off)
             float tall = sa1[0];
@@ -607,18 +662,19 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         m_ref = tmax * scale_log2;
 #pragma unroll
         for (int sl = 0; sl < 12; ++sl)
-            exp_stages(std::true_type{}, std::false_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - 4 * h,
-                       row_lo - 4 * h);
+            exp_stages(std::true_type{}, std::false_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - kb0 - 4 * h,
+                       row_lo - kb0 - 4 * h);
         pb1[0] = pack_group(sa1, 0);
         if constexpr (USE_R) pb2[0] = pack_group(sa2, 0);
     }
     PLX_STAMP(3);
-    auto tile_steps = [&](auto masked_tag, auto dma_tag, int kt, int stage, int next_stage) {
-        // block (kt,0) -> P, PV; scores of (kt,1); K fragments of (kt+1,0); loads of tile kt+2
-        pipeline_step(masked_tag, dma_tag, kt * kBC, k_block_ptr(stage, 1), v_block_ptr(stage, 0),
-                      k_block_ptr(next_stage, 0), sa1, sa2, sb1, sb2);
-        // block (kt,1) -> P, PV; scores of (kt+1,0); K fragments of (kt+1,1)
-        pipeline_step(masked_tag, std::false_type{}, kt * kBC + kKB, k_block_ptr(next_stage, 0),
+    // kt: key tile in `stage`, kt_next: key tile in `next_stage` (kt + 1 unless block-sparse)
+    auto tile_steps = [&](auto masked_tag, auto dma_tag, int kt, int kt_next, int stage, int next_stage) {
+        // block (kt,0) -> P, PV; scores of (kt,1); K fragments of (kt_next,0); loads of the tile after
+        pipeline_step(masked_tag, dma_tag, kt * kBC, kt * kBC + kKB, k_block_ptr(stage, 1),
+                      v_block_ptr(stage, 0), k_block_ptr(next_stage, 0), sa1, sa2, sb1, sb2);
+        // block (kt,1) -> P, PV; scores of (kt_next,0); K fragments of (kt_next,1)
+        pipeline_step(masked_tag, std::false_type{}, kt * kBC + kKB, kt_next * kBC, k_block_ptr(next_stage, 0),
                       v_block_ptr(stage, 1), k_block_ptr(next_stage, 1), sb1, sb2, sa1, sa2);
     };
     // One tile of the pipeline with per-lane key masks. Blocks a wave cannot see at all
@@ -628,12 +684,13 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
         tile_barrier();
         if (kt + kDist < n_tiles) {              // workgroup-uniform
-            if ((kt + kDist + 1) * kBC <= Tk)    // the tile exists completely
-                dma_full_tile(kt + kDist, free_stage);
+            const int k2 = tile_at(kt + kDist);
+            if (!SPARSE && (k2 + 1) * kBC <= Tk)  // the tile exists completely
+                dma_full_tile(k2, free_stage);
             else
-                dma_tile(kt + kDist, free_stage);
+                dma_tile(k2, free_stage);
         }
-        tile_steps(std::true_type{}, std::false_type{}, kt, stage, next_stage);
+        tile_steps(std::true_type{}, std::false_type{}, tile_at(kt), tile_at(kt + 1), stage, next_stage);
         stage = next_stage;
     };
     int kt = 0;
@@ -651,12 +708,20 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         if (!(PLX_PF_ABLATE & 4)) tile_barrier<(kDist - 2) * kTileLoads>();
         dma_dk = stage_k_addr(free_stage);  // tile kt + kDist <= T/64 - 1 in this loop: complete
         dma_dv = stage_v_addr(free_stage);
+        if constexpr (SPARSE) {
+            // (a list that does not ascend gives wrong results, but never a read past the last key)
+            const int k2 = min(tile_at(kt + kDist), Tk / kBC - 1);
+            dma_tk = (const char *)kbase + k2 * k_tile_bytes;
+            dma_tv = (const char *)vbase + k2 * v_tile_bytes;
+        }
         if (PLX_PF_ABLATE & 8)
-            tile_steps(std::false_type{}, std::false_type{}, kt, stage, next_stage);
+            tile_steps(std::false_type{}, std::false_type{}, tile_at(kt), tile_at(kt + 1), stage, next_stage);
         else
-            tile_steps(std::false_type{}, std::true_type{}, kt, stage, next_stage);
-        dma_tk += k_tile_bytes;
-        dma_tv += v_tile_bytes;
+            tile_steps(std::false_type{}, std::true_type{}, tile_at(kt), tile_at(kt + 1), stage, next_stage);
+        if constexpr (!SPARSE) {
+            dma_tk += k_tile_bytes;
+            dma_tv += v_tile_bytes;
+        }
         stage = next_stage;
     }
     PLX_STAMP(4);
@@ -673,11 +738,13 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             chk = fmaf(o1[n][r], 0.f, chk);
             if constexpr (USE_R) chk = fmaf(o2[n][r], 0.f, chk);
         }
-    if constexpr (WINDOW) {
+    if constexpr (WINDOW || SPARSE) {
         // the reference of a row may come from keys outside its window; if it was so far above
         // the row's own scores that the sum underflowed, take the exact path as well
+        // (block-sparse: only for rows that do see a listed key -- the list is ascending, so that
+        // is decided by its first tile)
         const float d1 = dacc1[0] + halves_sum(vsum1[0] + vsum1[1]);
-        if (my_row < T && !(d1 > 1e-30f)) chk = 1.f;
+        if (my_row < T && (!SPARSE || tile_at(0) * kBC <= row_lim) && !(d1 > 1e-30f)) chk = 1.f;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // tile loads past the end have landed
     const bool overflow = __syncthreads_or(chk != 0.f);  // NaN != 0 is true; all waves agree
@@ -688,15 +755,15 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         zero_state();
         vsum1[0] = vsum1[1] = vsum2[0] = vsum2[1] = 0.f;
         m_ref = kNegInf;
-        dma_tile(0, 0);
+        dma_tile(tile_at(0), 0);
         stage = 0;
         for (int t = 0; t < n_tiles; ++t) {
             const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
             tile_barrier();  // tile t has landed; tile t-2's stage is free for tile t+1
-            dma_tile(t + 1, next_stage);
+            dma_tile(tile_at(t + 1), next_stage);
 #pragma unroll 1
             for (int kb = 0; kb < kBC / kKB; ++kb) {
-                const int key_base = t * kBC + kb * kKB;
+                const int key_base = tile_at(t) * kBC + kb * kKB;
                 if (!block_visible(key_base)) continue;
                 scores(stage, kb, sa1, sa2);
                 float tmax = kNegInf;
@@ -817,7 +884,12 @@ static hipError_t launch_prefill_d(const PrefillParams &p, hipStream_t stream) {
     const long long total = (long long)nrb * p.Hq * p.B;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)total), block(256);
-    if (p.row_stats != nullptr) {  // with the row cache of the backward pass (use_r, no window)
+    if (p.sparse_row_ptr != nullptr) {  // block-sparse tile iterator (use_r, no window, no row cache)
+        if (p.causal)
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false, false, true>), grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, false, false, false, true>), grid, block, 0, stream, p);
+    } else if (p.row_stats != nullptr) {  // with the row cache of the backward pass (use_r, no window)
         if (p.causal)
             hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false, true>), grid, block, 0, stream, p);
         else

@@ -41,7 +41,7 @@ def test_struct_sizes_match_c_layout(binding):
     # pointer, 4 int32, int32 (+pad), pointer
     assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16 + 8 + 8
     # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, 2 int32, 2 pointers
-    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8 + 16
+    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8 + 16 + 16 + 8
     # 12 pointers, 6 int32, float + int32, enum (+pad), pointer, size_t
     assert ctypes.sizeof(binding.plx_prefill_bwd_args) == 12 * 8 + 24 + 8 + 8 + 16
 
@@ -190,6 +190,23 @@ def test_prefill_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_SHAPE
     a = good(); a.window, a.causal = 64, 0  # a window needs the rows' positions
     assert call(a) == binding.PLX_ERR_SHAPE
+    # block-sparse lists: both arrays, shared or per batch / head, bf16 with the probe, no window
+    def sparse():
+        a = good()
+        a.sparse_row_ptr, a.sparse_tile_idx, a.sparse_batch, a.sparse_heads = 0x5000, 0x6000, 1, 1
+        return a
+    a = sparse(); a.sparse_tile_idx = None
+    assert call(a) == binding.PLX_ERR_NULL
+    a = sparse(); a.sparse_heads = 3
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = sparse(); a.sparse_batch = 2
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = sparse(); a.window = 8
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = sparse(); a.use_r = 0
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = sparse(); a.sparse_row_ptr = 0x5002
+    assert call(a) == binding.PLX_ERR_ALIGN
 
 
 def test_util_argument_checks(binding):
