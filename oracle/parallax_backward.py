@@ -15,7 +15,8 @@ explicit T x L matrices, in the paper's notation:
     dV_j = sum_i p_ij (1 + ubar_i - u_ij) dO_i
 
 The sums run over the allowed (row, key) pairs: causal with the rows as the last Tq positions
-(key j allowed iff j <= i + (Lk - Tq)), else every key. GQA: the gradients of a KV head add up
+(key j allowed iff j <= i + (Lk - Tq)), else every key; with a sliding window of W > 0 (causal
+only) a row also does not see keys before its own position minus W - 1. GQA: the gradients of a KV head add up
 over the query heads of its group. No tiling, no recomputation tricks: every matrix is formed.
 
 Pins (tests/test_oracle_backward.py): central finite differences of the forward oracle (the C
@@ -29,20 +30,26 @@ from __future__ import annotations
 import numpy as np
 
 
-def _mask(Tq, Lk, causal):
+def _mask(Tq, Lk, causal, window=0):
     if not causal:
+        assert window == 0, "a sliding window is defined for causal attention"
         return np.ones((Tq, Lk), dtype=bool)
-    return np.tril(np.ones((Tq, Lk), dtype=bool), k=Lk - Tq)
+    pos = np.arange(Tq)[:, None] + (Lk - Tq)               # the row's own position among the keys
+    key = np.arange(Lk)[None, :]
+    mask = key <= pos
+    if window > 0:
+        mask &= key >= pos - (window - 1)                  # itself and the window - 1 positions before it
+    return mask
 
 
-def forward_with_cache(q, r, k, v, scale, causal=True):
+def forward_with_cache(q, r, k, v, scale, causal=True, window=0):
     """Forward by the definition plus the per-row cache the paper's backward reads:
     o, vbar [B, Hq, Tq, d]; ubar, log_omega (natural log of sum_j exp(scale q.k)) [B, Hq, Tq]."""
     q, r, k, v = (np.asarray(x, dtype=np.float64) for x in (q, r, k, v))
     B, Hq, Tq, d = q.shape
     _, Hkv, Lk, _ = k.shape
     G = Hq // Hkv
-    mask = _mask(Tq, Lk, causal)
+    mask = _mask(Tq, Lk, causal, window)
     o, vbar = np.zeros_like(q), np.zeros_like(q)
     ubar, log_omega = np.zeros((B, Hq, Tq)), np.zeros((B, Hq, Tq))
     for b in range(B):
@@ -62,13 +69,13 @@ def forward_with_cache(q, r, k, v, scale, causal=True):
     return o, vbar, ubar, log_omega
 
 
-def backward(q, r, k, v, d_o, scale, causal=True):
+def backward(q, r, k, v, d_o, scale, causal=True, window=0):
     """dQ, dR [B, Hq, Tq, d] and dK, dV [B, Hkv, Lk, d] by the closed forms of App. D."""
     q, r, k, v, d_o = (np.asarray(x, dtype=np.float64) for x in (q, r, k, v, d_o))
     B, Hq, Tq, d = q.shape
     _, Hkv, Lk, _ = k.shape
     G = Hq // Hkv
-    mask = _mask(Tq, Lk, causal)
+    mask = _mask(Tq, Lk, causal, window)
     dq, dr = np.zeros_like(q), np.zeros_like(q)
     dk, dv = np.zeros_like(k), np.zeros_like(k)
     for b in range(B):

@@ -48,7 +48,7 @@ def test_closed_forms_match_finite_differences_of_the_forward_oracle(causal, Tq,
         np.testing.assert_allclose(a, b, rtol=2e-6, atol=2e-7, err_msg=name)
 
 
-def _torch_forward(q, r, k, v, scale, causal):
+def _torch_forward(q, r, k, v, scale, causal, window=0):
     """The forward definition (Sec. 3.1, re-weighted softmax form) in PyTorch float64."""
     B, Hq, Tq, d = q.shape
     Hkv, Lk = k.shape[1], k.shape[2]
@@ -57,6 +57,8 @@ def _torch_forward(q, r, k, v, scale, causal):
     a = scale * q @ kk.transpose(-1, -2)
     if causal:
         keep = torch.tril(torch.ones(Tq, Lk, dtype=torch.bool), diagonal=Lk - Tq)
+        if window > 0:   # a row sees its own position and the window - 1 before it
+            keep &= torch.triu(torch.ones(Tq, Lk, dtype=torch.bool), diagonal=Lk - Tq - (window - 1))
         a = a.masked_fill(~keep, float("-inf"))
     p = torch.softmax(a, dim=-1)
     u = r @ kk.transpose(-1, -2)
@@ -77,6 +79,53 @@ def test_closed_forms_match_autograd_of_the_definition(causal, Tq, Lk, Hq, Hkv):
     got = pb.backward(q, r, k, v, g, 0.35, causal=causal)
     for name, a, t in zip(("dq", "dr", "dk", "dv"), got, (tq, tr, tk, tv)):
         np.testing.assert_allclose(a, t.grad.numpy(), rtol=1e-10, atol=1e-11, err_msg=name)
+
+
+@pytest.mark.parametrize("Tq,Lk,window", [(12, 12, 1), (12, 12, 4), (9, 20, 5), (7, 7, 50)])
+def test_sliding_window_closed_forms_match_autograd_and_finite_differences(Tq, Lk, window):
+    """The same closed forms over the window's key set: against autograd of the definition with
+    the window written as a band mask, and against central differences of the C forward oracle
+    (which has its own window code and its own pins)."""
+    q, r, k, v, g = _problem(17, B=1, Hq=4, Hkv=2, Tq=Tq, Lk=Lk, d=3)
+    tq, tr, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, r, k, v))
+    out = _torch_forward(tq, tr, tk, tv, 0.5, True, window)
+    np.testing.assert_allclose(out.detach().numpy(), po.forward(q, r, k, v, 0.5, causal=True, window=window),
+                               rtol=1e-11, atol=1e-12)
+    (out * torch.tensor(g)).sum().backward()
+    got = pb.backward(q, r, k, v, g, 0.5, causal=True, window=window)
+    for name, a, t in zip(("dq", "dr", "dk", "dv"), got, (tq, tr, tk, tv)):
+        np.testing.assert_allclose(a, t.grad.numpy(), rtol=1e-10, atol=1e-11, err_msg=name)
+    if window >= Tq + (Lk - Tq):   # a window that covers everything is no window
+        for a, b in zip(got, pb.backward(q, r, k, v, g, 0.5, causal=True)):
+            np.testing.assert_array_equal(a, b)
+    if window == 1:                # one key per row: o_i = v_i', so dV_i' = sum over heads of dO_i, the rest is zero
+        np.testing.assert_allclose(got[0], 0.0, atol=1e-12)
+        np.testing.assert_allclose(got[1], 0.0, atol=1e-12)
+        np.testing.assert_allclose(got[2], 0.0, atol=1e-12)
+        np.testing.assert_allclose(got[3][:, :, Lk - Tq:], g.reshape(1, 2, 2, Tq, 3).sum(axis=2), atol=1e-12)
+    o, vbar, ubar, lw = pb.forward_with_cache(q, r, k, v, 0.5, causal=True, window=window)
+    np.testing.assert_allclose(o, po.forward(q, r, k, v, 0.5, causal=True, window=window), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(vbar, po.forward(q, np.zeros_like(r), k, v, 0.5, causal=True, window=window),
+                               rtol=1e-12, atol=1e-13)
+
+
+def test_sliding_window_finite_differences():
+    q, r, k, v, g = _problem(18, B=1, Hq=2, Hkv=1, Tq=6, Lk=8, d=3)
+    xs = [q, r, k, v]
+    got = pb.backward(q, r, k, v, g, 0.6, causal=True, window=3)
+    eps = 1e-6
+    for n in range(4):
+        x = xs[n]
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = x[idx]
+            x[idx] = old + eps
+            up = (g * po.forward(*xs, 0.6, causal=True, window=3)).sum()
+            x[idx] = old - eps
+            dn = (g * po.forward(*xs, 0.6, causal=True, window=3)).sum()
+            x[idx] = old
+            assert abs((up - dn) / (2 * eps) - got[n][idx]) <= 2e-6 * max(1.0, abs(got[n][idx])), (n, idx)
 
 
 def test_zero_probe_is_the_textbook_softmax_backward():
@@ -139,6 +188,11 @@ MUTANTS = {
     "gqa_not_summed": ("dk[b, hk] += scale", "dk[b, hk] = scale"),
     "beta_from_o": ("beta = (d_o[b, h] * vbar)", "beta = (d_o[b, h] * o)"),
 }
+WINDOW_MUTANTS = {
+    "window_one_short": ("mask &= key >= pos - (window - 1)", "mask &= key >= pos - (window - 2)"),
+    "window_one_long": ("mask &= key >= pos - (window - 1)", "mask &= key >= pos - window"),
+    "window_from_row_index": ("mask &= key >= pos - (window - 1)", "mask &= key >= np.arange(Tq)[:, None] - (window - 1)"),
+}
 
 
 @pytest.mark.parametrize("name", sorted(MUTANTS))
@@ -155,5 +209,22 @@ def test_planted_mistake_is_rejected(name):
     tq, tr, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, r, k, v))
     (_torch_forward(tq, tr, tk, tv, 0.6, True) * torch.tensor(g)).sum().backward()
     got = ns["backward"](q, r, k, v, g, 0.6, causal=True)
+    worst = max(np.abs(a - t.grad.numpy()).max() for a, t in zip(got, (tq, tr, tk, tv)))
+    assert worst > 1e-6, "no pin noticed the planted mistake '%s'" % name
+
+
+@pytest.mark.parametrize("name", sorted(WINDOW_MUTANTS))
+def test_planted_window_mistake_is_rejected(name):
+    import inspect
+
+    src = inspect.getsource(pb)
+    old, new = WINDOW_MUTANTS[name]
+    assert src.count(old) == 1, "mutation site vanished from the oracle source"
+    ns = {}
+    exec(compile(src.replace(old, new), "<mutant>", "exec"), ns)
+    q, r, k, v, g = _problem(19, B=1, Hq=4, Hkv=2, Tq=7, Lk=11, d=4)
+    tq, tr, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, r, k, v))
+    (_torch_forward(tq, tr, tk, tv, 0.6, True, 4) * torch.tensor(g)).sum().backward()
+    got = ns["backward"](q, r, k, v, g, 0.6, causal=True, window=4)
     worst = max(np.abs(a - t.grad.numpy()).max() for a, t in zip(got, (tq, tr, tk, tv)))
     assert worst > 1e-6, "no pin noticed the planted mistake '%s'" % name
