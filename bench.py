@@ -610,7 +610,20 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
         win.append({"workload": "causal prefill B=%d T=%d window=%d d=128" % (B, T, W),
                     "us": round(us, 1), "TFLOPs": round(flops / us / 1e6, 1),
                     "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
-        del y, po
+        # ... and its backward (22 d flops per allowed pair)
+        g = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1015, device=dev)["q"].contiguous()
+        o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True,
+                                              save_for_backward=True, window=W)
+        bws = torch.empty(plx.parallax_prefill_backward_workspace_bytes(B, Hq, T) // 4,
+                          dtype=torch.float32, device=dev)
+        us = _time_events(
+            torch, lambda: plx.parallax_prefill_backward(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g,
+                                                         y["scale"], causal=True, workspace=bws, window=W), 2, 5)
+        bflops = B * Hq * 22 * d * pairs
+        win.append({"workload": "backward of causal prefill B=%d T=%d window=%d d=128" % (B, T, W),
+                    "us": round(us, 1), "TFLOPs": round(bflops / us / 1e6, 1),
+                    "frac_of_bf16_mfma_peak": round(bflops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
+        del y, po, g, o, vbar, stats, bws
     for (B, L, W) in [(16, 65536, 4096), (16, 4096, 0)]:
         Hq, Hkv, d = 16, 8, 128
         xs = [synth.decode_inputs(B, Hq, Hkv, L, d, seed=1008 + i, device=dev)

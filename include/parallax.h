@@ -183,7 +183,7 @@ typedef struct {
     plx_dtype dtype;
     int32_t Tkv; /* keys per sequence; 0 = T */
     int32_t window; /* sliding window in keys (needs causal); 0 = none */
-    /* Row cache for parallax_prefill_backward (App. D), both or neither (use_r, no window):
+    /* Row cache for parallax_prefill_backward (App. D), both or neither (use_r):
      *   vbar       [B, Hq, T, d] like o (same strides): the softmax value mean O1 / d1
      *   row_stats  [B, Hq, T, 2] fp32 contiguous: log2 of sum_j exp(scale q.k_j) (i.e. the
      *              log-sum-exp in the exp2 domain) and ubar = sum_j p_j rho.k_j */
@@ -198,8 +198,9 @@ typedef struct {
      * sparse_batch / sparse_heads are 1 (lists shared by all sequences / heads) or B / Hq. Both
      * arrays are int32 on the device; entries are clamped to existing tiles but not otherwise
      * checked (a list that does not ascend gives wrong results for its row block, never an access
-     * outside the tensors); the arrays must not be written while the kernel runs. A row block with an empty list (and any row none of whose listed keys is causal-
-     * visible) returns zeros. NULL sparse_row_ptr = dense. */
+     * outside the tensors); the arrays must not be written while the kernel runs. A row block
+     * with an empty list (and any row none of whose listed keys is causal-visible) returns
+     * zeros. NULL sparse_row_ptr = dense. */
     const int32_t *sparse_row_ptr;
     const int32_t *sparse_tile_idx;
     int32_t sparse_batch, sparse_heads;
@@ -213,7 +214,8 @@ plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
  * [B, Hq, T, d] and dk, dv [B, Hkv, Tkv, d]; the gradients of a KV head add up over the query
  * heads of its group. EVERY tensor contiguous (row-major, head dimension innermost), 16-byte
  * aligned; bf16 (d = 64 or 128; MFMA kernels) or fp32 (d <= 256, plain untuned path, vbar in fp32
- * too). causal and Tkv as in the forward (no window).
+ * too). causal, Tkv and window as in the forward (window > 0 needs causal != 0; the row cache
+ * must come from a forward call with the same window).
  *   workspace  fp32 scratch, >= parallax_prefill_backward_workspace_bytes(B, Hq, T) = 16 bytes
  *              per query row (lse, ubar, tau = dO.o, beta = dO.vbar)
  * Three kernels are enqueued (row scalars; dQ, dR; dK, dV); nothing is accumulated with atomics,
@@ -229,6 +231,7 @@ typedef struct {
     float scale;
     int32_t causal;
     plx_dtype dtype;
+    int32_t window; /* 0 = none; W > 0: a row sees its own position and the W - 1 before it */
     void *workspace;
     size_t workspace_bytes;
 } plx_prefill_bwd_args;

@@ -87,7 +87,7 @@ class plx_prefill_bwd_args(ctypes.Structure):
         ("T", ctypes.c_int32), ("Tkv", ctypes.c_int32), ("d", ctypes.c_int32),
         ("scale", ctypes.c_float),
         ("causal", ctypes.c_int32),
-        ("dtype", ctypes.c_int),
+        ("dtype", ctypes.c_int), ("window", ctypes.c_int32),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
     ]
 
@@ -376,7 +376,7 @@ def parallax_prefill_backward_workspace_bytes(B, Hq, T) -> int:
     return int(load_library().parallax_prefill_backward_workspace_bytes(B, Hq, T))
 
 
-def prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale, causal, workspace):
+def prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale, causal, workspace, window=0):
     """Fill a plx_prefill_bwd_args from contiguous tensors."""
     for t in (q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, workspace):
         if not t.is_cuda or not t.is_contiguous():
@@ -389,6 +389,7 @@ def prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale,
     a.B, a.Hq, a.Hkv, a.T, a.Tkv, a.d = B, Hq, k.shape[1], T, k.shape[2], d
     a.scale = float(scale)
     a.causal = 1 if causal else 0
+    a.window = int(window)
     a.dtype = _dtype_code(q)
     a.workspace = workspace.data_ptr()
     a.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -396,15 +397,15 @@ def prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale,
 
 
 def parallax_prefill_backward(q, r, k, v, o, vbar, row_stats, d_o, scale, causal=True, stream=None,
-                              workspace=None):
+                              workspace=None, window=0):
     """Gradients (dq, dr, dk, dv) of parallax_prefill for the upstream gradient d_o, from the
-    forward's output and row cache (save_for_backward=True)."""
+    forward's output and row cache (save_for_backward=True, same causal / window)."""
     dq, dr = torch.empty_like(q), torch.empty_like(q)
     dk, dv = torch.empty_like(k), torch.empty_like(k)
     if workspace is None:
         workspace = torch.empty(q.shape[0] * q.shape[1] * q.shape[2] * 4, dtype=torch.float32,
                                 device=q.device)
-    a = prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale, causal, workspace)
+    a = prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale, causal, workspace, window)
     st = load_library().parallax_prefill_backward(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_prefill_backward")

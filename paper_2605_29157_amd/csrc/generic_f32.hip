@@ -209,8 +209,9 @@ __global__ __launch_bounds__(kGenThreads) void generic_bwd_rows_f32_kernel(Prefi
     if (t == 0) ((f32x4 *)p.row_cache)[row] = f32x4{lse, ubar, tau, beta};
     const float scale_log2 = p.scale * kLog2e;
     const int n_keys = p.causal ? min(i + 1 + off, p.Tk) : p.Tk;
+    const int j_first = (p.window > 0 && n_keys > p.window) ? n_keys - p.window : 0;
     float dq = 0.f, dr = 0.f;  // dimension t
-    for (int j0 = 0; j0 < n_keys; j0 += kGenThreads) {
+    for (int j0 = j_first; j0 < n_keys; j0 += kGenThreads) {
         const int j = j0 + t;
         float g1 = 0.f, g2 = 0.f;
         if (j < n_keys) {
@@ -257,16 +258,17 @@ __global__ __launch_bounds__(kGenThreads) void generic_bwd_cols_f32_kernel(Prefi
     }
     __syncthreads();
     const float scale_log2 = p.scale * kLog2e;
-    const int i_lo = p.causal ? max(j - off, 0) : 0;  // rows that see key j
+    const int i_lo = p.causal ? max(j - off, 0) : 0;  // rows that see key j: i_lo .. i_end - 1
+    const int i_end = p.window > 0 ? min(p.T, max(j - off + p.window, 0)) : p.T;
     float dk = 0.f, dv = 0.f;  // dimension t
     for (int g = 0; g < p.G; ++g) {
         const int64_t head = ((int64_t)b * p.Hq + hk * p.G + g) * p.T;
         const float *q = (const float *)p.q + head * d, *r = (const float *)p.r + head * d;
         const float *go = (const float *)p.d_o + head * d;
-        for (int i0 = i_lo; i0 < p.T; i0 += kGenThreads) {
+        for (int i0 = i_lo; i0 < i_end; i0 += kGenThreads) {
             const int i = i0 + t;
             float g1 = 0.f, g2 = 0.f, w = 0.f;
-            if (i < p.T) {
+            if (i < i_end) {
                 float a1 = 0.f, a2 = 0.f, a3 = 0.f;
                 for (int c = 0; c < d; ++c) {
                     a1 = fmaf(q[(int64_t)i * d + c], sk[c], a1);
@@ -283,7 +285,7 @@ __global__ __launch_bounds__(kGenThreads) void generic_bwd_cols_f32_kernel(Prefi
             s1s[t] = g1, s2s[t] = g2, sws[t] = w;
             __syncthreads();
             if (t < d) {
-                const int n = min(kGenThreads, p.T - i0);
+                const int n = min(kGenThreads, i_end - i0);
                 for (int ii = 0; ii < n; ++ii) {
                     const int64_t e = (int64_t)(i0 + ii) * d + t;
                     dk = fmaf(s1s[ii], q[e], dk);

@@ -285,7 +285,7 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
     }
     if ((a->vbar != nullptr) != (a->row_stats != nullptr)) return PLX_ERR_NULL;
     if (a->row_stats) {
-        if (!a->use_r || a->window > 0) return PLX_ERR_SHAPE;
+        if (!a->use_r) return PLX_ERR_SHAPE;
         if (!aligned16(a->vbar) || (reinterpret_cast<uintptr_t>(a->row_stats) & 7u)) return PLX_ERR_ALIGN;
         p.vbar = a->vbar, p.row_stats = a->row_stats;
     }
@@ -313,6 +313,7 @@ plx_status parallax_prefill_backward(const plx_prefill_bwd_args *a, void *hip_st
     if (a->Tkv < 0) return PLX_ERR_SHAPE;
     const int32_t Tk = a->Tkv ? a->Tkv : a->T;
     if (a->causal && Tk < a->T) return PLX_ERR_SHAPE;
+    if (a->window < 0 || (a->window > 0 && !a->causal)) return PLX_ERR_SHAPE;
     if (a->dtype == PLX_F32 && (a->T > 65535 || Tk > 0x7fffffff / 2)) return PLX_ERR_SHAPE;
     if ((int64_t)a->B * a->Hq * a->T > 0x7fffffffLL || (int64_t)a->B * a->Hkv * Tk > 0x7fffffffLL)
         return PLX_ERR_SHAPE;
@@ -327,6 +328,8 @@ plx_status parallax_prefill_backward(const plx_prefill_bwd_args *a, void *hip_st
     p.dq = a->dq, p.dr = a->dr, p.dk = a->dk, p.dv = a->dv;
     p.B = a->B, p.Hq = a->Hq, p.Hkv = a->Hkv, p.G = a->Hq / a->Hkv, p.T = a->T, p.Tk = Tk, p.d = a->d;
     p.scale = a->scale, p.causal = a->causal ? 1 : 0;
+    // a window that reaches back past the first key is no window
+    p.window = (a->window > 0 && a->window < Tk) ? a->window : 0;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const hipError_t err = a->dtype == PLX_F32 ? plx::launch_prefill_bwd_f32(p, stream)
                                                : plx::launch_prefill_bwd_bf16(p, stream);

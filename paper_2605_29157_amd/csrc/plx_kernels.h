@@ -57,6 +57,7 @@ struct PrefillBwdParams {
     int32_t B, Hq, Hkv, G, T, Tk, d;
     float scale;
     int32_t causal;
+    int32_t window;  // > 0 (causal only): a row sees its own position and the window - 1 before it
 };
 
 // RMSNorm + RoPE on up to three contiguous [B, H, T, d] tensors of one (B, T, d).

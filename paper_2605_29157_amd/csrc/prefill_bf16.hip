@@ -78,7 +78,7 @@ __device__ unsigned long long plx_pf_stamps[8192 * 12];
 template <int D, bool USE_R, bool CAUSAL, bool WINDOW, bool STATS = false, bool SPARSE = false>
 __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     static_assert(CAUSAL || !WINDOW, "a sliding window needs the rows' positions");
-    static_assert(!STATS || (USE_R && !WINDOW), "the row cache is written for the backward pass only");
+    static_assert(!STATS || USE_R, "the row cache is written for the backward pass only");
     static_assert(!SPARSE || (!WINDOW && !STATS), "block-sparse: its own tile iterator, forward only");
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int KSTEPS = D / 16;        // k-steps of the score contraction
@@ -889,7 +889,9 @@ static hipError_t launch_prefill_d(const PrefillParams &p, hipStream_t stream) {
             hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false, false, true>), grid, block, 0, stream, p);
         else
             hipLaunchKernelGGL((prefill_bf16_kernel<D, true, false, false, false, true>), grid, block, 0, stream, p);
-    } else if (p.row_stats != nullptr) {  // with the row cache of the backward pass (use_r, no window)
+    } else if (p.row_stats != nullptr && p.window > 0) {  // row cache + sliding window (causal, use_r)
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, true, true>), grid, block, 0, stream, p);
+    } else if (p.row_stats != nullptr) {  // with the row cache of the backward pass (use_r)
         if (p.causal)
             hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false, true>), grid, block, 0, stream, p);
         else

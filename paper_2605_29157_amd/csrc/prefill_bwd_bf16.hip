@@ -149,8 +149,12 @@ __global__ __launch_bounds__(256) void bwd_rows_prepare_kernel(PrefillBwdParams 
 //             already turns the lower 16 keys of the NEXT block into its g1 / g2.
 // Each slot that first uses an LDS fragment issues the read of the fragment needed three
 // fragments later ([K, V of the next block | K^T of the current block | K, V of the block after]).
-template <int D, bool CAUSAL>
+// WINDOW (sliding window, causal only): the key tiles before the window of the block's first row
+// are skipped by moving the key origin; the leading tiles that some row sees only in part take
+// the masked form of the pipeline, like the diagonal ones.
+template <int D, bool CAUSAL, bool WINDOW = false>
 __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
+    static_assert(CAUSAL || !WINDOW, "a sliding window is causal");
     using TL = BwdTile<D>;
     constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
     constexpr int STAGES = 3, STAGE_CHUNKS = 2 * TL::CHUNKS;  // ring of [K tile | V tile]
@@ -159,10 +163,13 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int col = lane & 31, h = lane >> 5;
-    const int T = p.T, Tk = p.Tk, off = Tk - T;
+    const int T = p.T;
     const int nrb = (T + 127) / 128;
     const int rbi = blockIdx.x % nrb;
     const int rb = CAUSAL ? nrb - 1 - rbi : rbi;  // heavy row blocks first
+    // key tiles no row of this block sees (all keys before the window of its first row)
+    const int kt_skip = WINDOW ? max(rb * 128 + (p.Tk - T) - p.window + 1, 0) / kTileRows : 0;
+    const int Tk = p.Tk - kt_skip * kTileRows, off = Tk - T;  // keys from the first tile read on
     const int hq = (blockIdx.x / nrb) % p.Hq, b = blockIdx.x / (nrb * p.Hq);
     const int hk = hq / p.G;
     const int row0 = rb * 128 + w * 32, my_row = row0 + col;
@@ -182,8 +189,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     const float scale_log2 = p.scale * kLog2e;
     const BwdLaneOffsets<D> lo(lane);
 
-    const __bf16 *kbase = (const __bf16 *)p.k + ((int64_t)b * p.Hkv + hk) * Tk * D;
-    const __bf16 *vbase = (const __bf16 *)p.v + ((int64_t)b * p.Hkv + hk) * Tk * D;
+    const __bf16 *kbase = (const __bf16 *)p.k + (((int64_t)b * p.Hkv + hk) * p.Tk + kt_skip * kTileRows) * D;
+    const __bf16 *vbase = (const __bf16 *)p.v + (((int64_t)b * p.Hkv + hk) * p.Tk + kt_skip * kTileRows) * D;
     const uint32_t lds_base = lds_byte_address(lds);
     auto issue_tile = [&](int t, int stage) __attribute__((always_inline)) {
         load_tile64<D>(kbase, t * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u, w, lane);
@@ -241,7 +248,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     // Element-wise work of the 8 score registers [r0, r0 + 8) of a block, as four stages in
     // consecutive slots so that a slot holds independent instructions only; the results replace
     // the scores: g1 in aa, g2 in s2. Register r holds key offset 8*(r/4) + r%4 (+ 4h, already
-    // taken off lim).
+    // taken off lim). With a window a key counts iff 0 <= lim - offset < window: one unsigned compare.
+    const unsigned wspan = WINDOW ? (unsigned)p.window : 0u;
     float dl[8];
     auto elem_stages = [&](auto masked_tag, f32x16 &s1, f32x16 &s2, f32x16 &aa, int r0, int slot, int slot0,
                            int n_slots, int lim) __attribute__((always_inline)) {
@@ -261,7 +269,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
                 aa[r] = fmaf(s2[r], dl[u], aa[r]);   // a - tau + (ubar - u) delta
             }
             if constexpr (MASKED)
-                if (slot == first + 2) s1[r] = (8 * (r >> 2) + (r & 3) <= lim) ? s1[r] : 0.f;
+                if (slot == first + 2) {
+                    if constexpr (WINDOW)
+                        s1[r] = ((unsigned)(lim - (8 * (r >> 2) + (r & 3))) < wspan) ? s1[r] : 0.f;
+                    else
+                        s1[r] = (8 * (r >> 2) + (r & 3) <= lim) ? s1[r] : 0.f;
+                }
             if (slot == first + 3) {
                 aa[r] = s1[r] * aa[r];    // g1
                 s2[r] = -(s1[r] * dl[u]);  // g2
@@ -375,9 +388,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     // fetches exists completely.
     const int n_full = min(CAUSAL ? (rb * 128 + off + 1) / kTileRows : Tk / kTileRows, Tk / kTileRows - 1);
     int t = 0;
+    if constexpr (WINDOW) {
+        // leading tiles that hold a key before the window of the block's last row
+        const int n_left = min(n_tiles, max(rb * 128 + 128 + off - p.window + kTileRows - 1, 0) / kTileRows);
+        for (; t < n_left; ++t) tile_steps(std::true_type{}, std::false_type{}, t);
+    }
     const int64_t tile_bytes = (int64_t)kTileRows * D * 2;
-    dma_k = (const char *)kbase + 2 * tile_bytes;
-    dma_v = (const char *)vbase + 2 * tile_bytes;
+    dma_k = (const char *)kbase + (t + 2) * tile_bytes;
+    dma_v = (const char *)vbase + (t + 2) * tile_bytes;
     for (; t < n_full - 1; ++t) {
         tile_steps(std::false_type{}, std::true_type{}, t);
         dma_k += tile_bytes;
@@ -414,8 +432,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
 //             alternate), while the vector ALU turns the lower 16 rows of the NEXT block.
 // A lane owns a key, its registers the rows: the row scalars (lse, ubar, tau, beta) come from LDS,
 // one float4 per register, read one slot ahead of their use.
-template <int D, bool CAUSAL>
+// WINDOW: key j is seen by the rows [j - off, j - off + window) only; the row tiles past the
+// last of them are not visited, those cut by the upper edge take the masked form.
+template <int D, bool CAUSAL, bool WINDOW = false>
 __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
+    static_assert(CAUSAL || !WINDOW, "a sliding window is causal");
     using TL = BwdTile<D>;
     constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
     constexpr int STAGES = 3;
@@ -446,13 +467,20 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     // row tiles that hold a row which sees a key of this block: rows i >= key - off
     const int rt_lo = CAUSAL ? max(cb * 128 - off, 0) / kTileRows : 0;
     const int n_rt = (T + kTileRows - 1) / kTileRows;
-    const int per_head = n_rt - rt_lo;
+    // window: rows up to (last key of the block) - off + window - 1. A block no row sees at all
+    // (keys before every window) still visits one tile, with every pair masked: zeros.
+    const int rt_hi =
+        WINDOW ? max(min(n_rt, (min(cb * 128 + 127, Tk - 1) - off + p.window + kTileRows - 1) / kTileRows), rt_lo + 1)
+               : n_rt;
+    const int per_head = rt_hi - rt_lo;
     const int n_items = per_head * G;  // (head of the group, row tile)
     // Row tiles in which every (row, key) pair counts -- all rows exist and see every key of the
     // block, and the key block is complete -- need no masks. The items are taken in an order that
     // puts those of all heads first, so that the two forms of the pipeline are two loops.
     const int rt_full_lo = max(CAUSAL ? max(cb * 128 + 127 - off + kTileRows - 1, 0) / kTileRows : 0, rt_lo);
-    const int rt_full_hi = (cb + 1) * 128 <= Tk ? T / kTileRows : 0;
+    // (window: the first key of the block is the first to drop out of a row's window)
+    const int rt_full_hi =
+        (cb + 1) * 128 <= Tk ? (WINDOW ? min(T, max(cb * 128 - off + p.window, 0)) : T) / kTileRows : 0;
     const int full_per_head = max(rt_full_hi - rt_full_lo, 0);
     const int n_full_items = full_per_head * G;
     const int rest_per_head = per_head - full_per_head;
@@ -602,8 +630,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     // offsets [lo, hi) relative to row_base + 4h
     auto row_window = [&](int row_base, int &neg_lo, unsigned &span) __attribute__((always_inline)) {
         const int first_row = my_key < Tk ? (CAUSAL ? max(my_key - off, 0) : 0) : T;  // no row at all
+        const int end_row = WINDOW ? min(T, max(my_key - off + p.window, 0)) : T;
         const int lo_off = max(first_row - row_base - 4 * h, 0);
-        const int hi_off = T - row_base - 4 * h;
+        const int hi_off = end_row - row_base - 4 * h;
         neg_lo = -lo_off;
         span = (unsigned)max(hi_off - lo_off, 0);
     };
@@ -761,7 +790,10 @@ static hipError_t launch_bwd_d(const PrefillBwdParams &p, hipStream_t stream) {
     const long long g2 = (long long)((p.Tk + 127) / 128) * p.Hkv * p.B;
     if (g0 > 0x7fffffffLL || g1 > 0x7fffffffLL || g2 > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((bwd_rows_prepare_kernel<D>), dim3((unsigned)g0), dim3(256), 0, stream, p);
-    if (p.causal) {
+    if (p.causal && p.window > 0) {
+        hipLaunchKernelGGL((bwd_dq_dr_kernel<D, true, true>), dim3((unsigned)g1), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+    } else if (p.causal) {
         hipLaunchKernelGGL((bwd_dq_dr_kernel<D, true>), dim3((unsigned)g1), dim3(256), 0, stream, p);
         hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
     } else {

@@ -246,7 +246,11 @@ def test_prefill_backward_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_SCALE
     a = good(); a.workspace_bytes -= 1
     assert call(a) == binding.PLX_ERR_WORKSPACE
-    # the forward's row cache: both pointers or neither, bf16 with the probe and no window
+    a = good(); a.window = -1
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.window, a.causal = 16, 0     # a sliding window is causal
+    assert call(a) == binding.PLX_ERR_SHAPE
+    # the forward's row cache: both pointers or neither, with the probe
     f = binding.plx_prefill_args()
     f.q = f.r = f.k = f.v = f.o = 0x1000
     f.B, f.Hq, f.Hkv, f.T, f.d = 1, 4, 2, 128, 128
@@ -256,9 +260,7 @@ def test_prefill_backward_rejects_bad_arguments_before_launch(binding):
     f.vbar = 0x3000
     assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_NULL
     f.row_stats = 0x4000
-    f.window = 16
-    assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_SHAPE
-    f.window, f.use_r = 0, 0
+    f.use_r = 0
     assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_SHAPE
 
 

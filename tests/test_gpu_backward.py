@@ -43,19 +43,19 @@ def _inputs(synth, B, Hq, Hkv, T, Tkv, d, seed, r_scale=1.0):
     return y, g
 
 
-def _run(plx, y, g, causal):
+def _run(plx, y, g, causal, window=0):
     o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=causal,
-                                          save_for_backward=True)
+                                          save_for_backward=True, window=window)
     grads = plx.parallax_prefill_backward(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g, y["scale"],
-                                          causal=causal)
+                                          causal=causal, window=window)
     torch.cuda.synchronize()
     return o, vbar, stats, grads
 
 
-def _check(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, causal, seed, r_scale=1.0, tol=BF16_REL_L2):
+def _check(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, causal, seed, r_scale=1.0, tol=BF16_REL_L2, window=0):
     y, g = _inputs(synth, B, Hq, Hkv, T, Tkv, d, seed, r_scale)
-    _, _, _, grads = _run(plx, y, g, causal)
-    want = bwd_oracle.backward(*(host(y[n]) for n in "qrkv"), host(g), y["scale"], causal=causal)
+    _, _, _, grads = _run(plx, y, g, causal, window)
+    want = bwd_oracle.backward(*(host(y[n]) for n in "qrkv"), host(g), y["scale"], causal=causal, window=window)
     for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
         got = host(got)
         assert np.isfinite(got).all(), name
@@ -85,6 +85,44 @@ def test_backward_gqa_groups_and_head_dims(plx, synth, bwd_oracle, Hq, Hkv, d):
 @pytest.mark.parametrize("T,Tkv,causal", [(128, 1000, True), (200, 777, True), (5, 300, True), (100, 333, False)])
 def test_backward_more_keys_than_rows(plx, synth, bwd_oracle, T, Tkv, causal):
     _check(plx, synth, bwd_oracle, 1, 8, 2, T, Tkv, 128, causal, seed=2200 + T)
+
+
+@pytest.mark.parametrize("T,Tkv,W,d", [(300, 300, 1, 128), (300, 300, 7, 128), (300, 300, 64, 128),
+                                        (513, 513, 100, 128), (513, 513, 128, 128), (513, 513, 200, 64),
+                                        (1000, 1000, 333, 128), (200, 777, 150, 128), (640, 2048, 512, 128),
+                                        (130, 1500, 40, 64), (300, 300, 5000, 128)])
+def test_backward_sliding_window(plx, synth, bwd_oracle, T, Tkv, W, d):
+    """Rows see their own position and the W - 1 before it: key tiles before the window are
+    skipped in the row pass, row tiles after it in the column pass (key blocks nobody sees get
+    zero gradients), the edges take the masked pipeline."""
+    # few keys per row: the bf16 rounding of the forward's ubar is not averaged out (see T = 1)
+    tol = BF16_REL_L2 * (5 if W < 4 else 2 if W < 32 else 1)
+    _check(plx, synth, bwd_oracle, 2, 4, 2, T, Tkv, d, True, seed=2900 + T + W, tol=tol, window=W)
+
+
+def test_backward_sliding_window_fp32_and_row_cache(plx, synth, bwd_oracle):
+    for (T, Tkv, W, d) in [(130, 130, 33, 64), (77, 300, 50, 32)]:
+        y = synth.prefill_inputs(2, 4, 2, Tkv, d, seed=2950 + T, dtype=torch.float32, device=DEV)
+        if Tkv > T:
+            y["q"], y["r"] = y["q"][:, :, Tkv - T:].contiguous(), y["r"][:, :, Tkv - T:].contiguous()
+        g = synth.prefill_inputs(2, 4, 2, T, d, seed=2951, dtype=torch.float32, device=DEV)["q"].contiguous()
+        _, vbar, stats, grads = _run(plx, y, g, True, W)
+        hq, hr, hk, hv = (host(y[n]) for n in "qrkv")
+        _, vb, ub, lw = bwd_oracle.forward_with_cache(hq, hr, hk, hv, y["scale"], causal=True, window=W)
+        assert max_rel(host(vbar), vb) <= F32_MAX_REL
+        np.testing.assert_allclose(host(stats)[..., 0], lw * LOG2E, rtol=0, atol=1e-4)
+        want = bwd_oracle.backward(hq, hr, hk, hv, host(g), y["scale"], causal=True, window=W)
+        for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
+            assert np.abs(host(got) - ref).max() <= F32_MAX_REL * max(np.abs(ref).max(), 1.0), name
+    # bf16 row cache under a window
+    y, g = _inputs(synth, 2, 4, 2, 400, 400, 128, 2960)
+    o, vbar, stats, _ = _run(plx, y, g, True, 100)
+    plain = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True, window=100)
+    np.testing.assert_array_equal(host(o), host(plain))
+    _, vb, ub, lw = bwd_oracle.forward_with_cache(*(host(y[n]) for n in "qrkv"), y["scale"], causal=True, window=100)
+    assert rel_l2(host(vbar), vb) <= BF16_REL_L2
+    np.testing.assert_allclose(host(stats)[..., 0], lw * LOG2E, rtol=0, atol=2e-2)
+    assert rel_l2(host(stats)[..., 1], ub) <= BF16_REL_L2
 
 
 def test_backward_small_probe_and_zero_probe(plx, synth, bwd_oracle):
