@@ -82,3 +82,72 @@ def test_random_decode_shapes(plx, synth, oracle, case):
                                 block_table=table, max_len=L, **kw)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(host(paged), got)
+
+
+@pytest.mark.parametrize("case", range(20))
+def test_random_backward_shapes_with_and_without_window(plx, synth, case):
+    """Forward with row cache + backward on random shapes against the float64 closed forms;
+    half of the causal cases under a sliding window of random width."""
+    from oracle import parallax_backward as pb
+
+    rng = np.random.default_rng(9800 + case)
+    Hq, Hkv = _heads(rng)
+    d = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 3))
+    T = int(rng.choice([2, 33, 64, 65, 127, 128, 129, 191, 200, 256, 300, 385, 520]))
+    extra = int(rng.choice([0, 0, 1, 17, 63, 64, 100, 129, 400]))
+    causal = bool(rng.integers(0, 4))   # mostly causal
+    window = int(rng.choice([0, 3, 40, 64, 65, 128, 200, 333])) if causal else 0
+    y = synth.prefill_inputs(B, Hq, Hkv, T + extra, d, seed=9850 + case, device=DEV,
+                             r_scale=float(rng.choice([1.0, 0.3])))
+    y["q"], y["r"] = y["q"][:, :, extra:].contiguous(), y["r"][:, :, extra:].contiguous()
+    g = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=9851 + case, device=DEV)["q"].contiguous()
+    o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=causal,
+                                          save_for_backward=True, window=window)
+    grads = plx.parallax_prefill_backward(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g, y["scale"],
+                                          causal=causal, window=window)
+    torch.cuda.synchronize()
+    want = pb.backward(*(host(y[n]) for n in "qrkv"), host(g), y["scale"], causal=causal, window=window)
+    # few keys per row: the bf16 rounding of the forward's ubar is not averaged out
+    tol = BF16_REL_L2 * (5 if 0 < window < 4 else 2 if 0 < window < 32 else 1)
+    for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
+        got = host(got)
+        assert np.isfinite(got).all(), name
+        err = np.linalg.norm(got - ref)
+        assert err <= tol * np.linalg.norm(ref) + 1e-3 * np.sqrt(ref.size), (
+            name, err, np.linalg.norm(ref), B, Hq, Hkv, T, extra, d, causal, window)
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_random_block_masks_and_windows_forward(plx, synth, oracle, case):
+    """Random block masks (per batch / per head / shared) and random windows on random shapes."""
+    from oracle import masked
+
+    rng = np.random.default_rng(9900 + case)
+    Hq, Hkv = _heads(rng)
+    d = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 3))
+    T = int(rng.choice([1, 64, 100, 128, 129, 300, 700, 1100]))
+    extra = int(rng.choice([0, 0, 5, 64, 130, 900]))
+    causal = bool(rng.integers(0, 3))
+    y = synth.prefill_inputs(B, Hq, Hkv, T + extra, d, seed=9950 + case, device=DEV)
+    y["q"], y["r"] = y["q"][:, :, extra:].contiguous(), y["r"][:, :, extra:].contiguous()
+    q, r, k, v = (host(y[n]) for n in "qrkv")
+    nrb, nkt = -(-T // 128), -(-(T + extra) // 64)
+    lead = [(), (Hq,), (B, 1), (B, Hq)][int(rng.integers(0, 4))]
+    bm = rng.random(lead + (nrb, nkt)) < float(rng.choice([0.15, 0.5, 0.9]))
+    out = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=causal,
+                               block_mask=torch.as_tensor(bm, device=DEV))
+    torch.cuda.synchronize()
+    bm4 = bm.reshape((1,) * (4 - bm.ndim) + bm.shape)   # missing leading dims are shared
+    dense = masked.block_mask_to_dense(bm4, T, T + extra, 128, 64, causal)
+    ref = masked.masked_forward(q, r, k, v, y["scale"], dense)
+    got = host(out)
+    assert np.isfinite(got).all()
+    assert np.linalg.norm(got - ref) <= BF16_REL_L2 * np.linalg.norm(ref) + 1e-6, (B, Hq, Hkv, T, extra, d, causal, lead)
+    if causal:
+        W = int(rng.choice([1, 5, 64, 100, 129, 500]))
+        outw = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True, window=W)
+        torch.cuda.synchronize()
+        refw = oracle.forward(q, r, k, v, y["scale"], causal=True, window=W)
+        assert rel_l2(host(outw), refw) <= BF16_REL_L2 * (2 if W < 32 else 1), (T, extra, d, W)
