@@ -212,9 +212,10 @@ plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
  * Backward of parallax_prefill (closed-form gradients, App. D): given the upstream gradient d_o,
  * the forward's inputs, its output o and its row cache (vbar, row_stats), writes dq, dr
  * [B, Hq, T, d] and dk, dv [B, Hkv, Tkv, d]; the gradients of a KV head add up over the query
- * heads of its group. EVERY tensor contiguous (row-major, head dimension innermost), 16-byte
- * aligned; bf16 (d = 64 or 128; MFMA kernels) or fp32 (d <= 256, plain untuned path, vbar in fp32
- * too). causal, Tkv and window as in the forward (window > 0 needs causal != 0; the row cache
+ * heads of its group. Every tensor 16-byte aligned with the head dimension innermost and
+ * contiguous; *_stride are element strides {batch, head, row} as in plx_prefill_args, an all-zero
+ * triple meaning the dense [B, H, T, d] layout (row_stats is always dense). bf16 (d = 64 or 128;
+ * MFMA kernels) or fp32 (d <= 256, plain untuned path, vbar in fp32 too, dense layout only). causal, Tkv and window as in the forward (window > 0 needs causal != 0; the row cache
  * must come from a forward call with the same window).
  *   workspace  fp32 scratch, >= parallax_prefill_backward_workspace_bytes(B, Hq, T) = 16 bytes
  *              per query row (lse, ubar, tau = dO.o, beta = dO.vbar)
@@ -234,6 +235,8 @@ typedef struct {
     int32_t window; /* 0 = none; W > 0: a row sees its own position and the W - 1 before it */
     void *workspace;
     size_t workspace_bytes;
+    int64_t q_stride[3], r_stride[3], k_stride[3], v_stride[3], o_stride[3], vbar_stride[3], d_o_stride[3];
+    int64_t dq_stride[3], dr_stride[3], dk_stride[3], dv_stride[3];
 } plx_prefill_bwd_args;
 
 size_t parallax_prefill_backward_workspace_bytes(int32_t B, int32_t Hq, int32_t T);

@@ -89,6 +89,10 @@ class plx_prefill_bwd_args(ctypes.Structure):
         ("causal", ctypes.c_int32),
         ("dtype", ctypes.c_int), ("window", ctypes.c_int32),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("q_stride", ctypes.c_int64 * 3), ("r_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
+        ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3), ("vbar_stride", ctypes.c_int64 * 3),
+        ("d_o_stride", ctypes.c_int64 * 3), ("dq_stride", ctypes.c_int64 * 3), ("dr_stride", ctypes.c_int64 * 3),
+        ("dk_stride", ctypes.c_int64 * 3), ("dv_stride", ctypes.c_int64 * 3),
     ]
 
 
@@ -377,10 +381,13 @@ def parallax_prefill_backward_workspace_bytes(B, Hq, T) -> int:
 
 
 def prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale, causal, workspace, window=0):
-    """Fill a plx_prefill_bwd_args from contiguous tensors."""
+    """Fill a plx_prefill_bwd_args: [B, H, T, d] tensors (views with any batch / head / row strides,
+    last dimension contiguous); row_stats and the workspace dense."""
     for t in (q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, workspace):
-        if not t.is_cuda or not t.is_contiguous():
-            raise ValueError("parallax_prefill_backward needs contiguous device tensors")
+        if not t.is_cuda or t.stride(-1) != 1:
+            raise ValueError("parallax_prefill_backward needs device tensors with a contiguous last dimension")
+    if not row_stats.is_contiguous() or not workspace.is_contiguous():
+        raise ValueError("row_stats and the workspace must be contiguous")
     B, Hq, T, d = q.shape
     a = plx_prefill_bwd_args()
     a.q, a.r, a.k, a.v = q.data_ptr(), r.data_ptr(), k.data_ptr(), v.data_ptr()
@@ -393,6 +400,9 @@ def prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale,
     a.dtype = _dtype_code(q)
     a.workspace = workspace.data_ptr()
     a.workspace_bytes = workspace.numel() * workspace.element_size()
+    for name, t in (("q", q), ("r", r), ("k", k), ("v", v), ("o", o), ("vbar", vbar), ("d_o", d_o),
+                    ("dq", dq), ("dr", dr), ("dk", dk), ("dv", dv)):
+        setattr(a, name + "_stride", (ctypes.c_int64 * 3)(*t.stride()[:3]))
     return a
 
 

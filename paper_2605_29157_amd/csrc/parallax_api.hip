@@ -330,6 +330,27 @@ plx_status parallax_prefill_backward(const plx_prefill_bwd_args *a, void *hip_st
     p.scale = a->scale, p.causal = a->causal ? 1 : 0;
     // a window that reaches back past the first key is no window
     p.window = (a->window > 0 && a->window < Tk) ? a->window : 0;
+    {
+        // strides: an all-zero triple is the dense layout; otherwise as in the forward
+        const int64_t *given[11] = {a->q_stride, a->r_stride, a->k_stride, a->v_stride, a->o_stride, a->vbar_stride,
+                                    a->d_o_stride, a->dq_stride, a->dr_stride, a->dk_stride, a->dv_stride};
+        int64_t *dst[11] = {p.qs, p.rs, p.ks, p.vs, p.os, p.vbs, p.gs, p.dqs, p.drs, p.dks, p.dvs};
+        for (int t = 0; t < 11; ++t) {
+            const bool key_side = t == 2 || t == 3 || t == 9 || t == 10;
+            const int64_t H = key_side ? a->Hkv : a->Hq, rows = key_side ? Tk : a->T;
+            const int64_t dense[3] = {H * rows * a->d, rows * a->d, a->d};
+            const bool zero = given[t][0] == 0 && given[t][1] == 0 && given[t][2] == 0;
+            for (int j = 0; j < 3; ++j) {
+                const int64_t s = zero ? dense[j] : given[t][j];
+                if (s < 0) return PLX_ERR_SHAPE;
+                if (!stride_aligned(s, a->dtype)) return PLX_ERR_ALIGN;
+                if (a->dtype == PLX_F32 && s != dense[j]) return PLX_ERR_SHAPE;  // plain path: dense only
+                dst[t][j] = s;
+            }
+            // (a 64-row tile is addressed with 32-bit byte offsets)
+            if (dst[t][2] < a->d || dst[t][2] > (1 << 23)) return PLX_ERR_SHAPE;
+        }
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const hipError_t err = a->dtype == PLX_F32 ? plx::launch_prefill_bwd_f32(p, stream)
                                                : plx::launch_prefill_bwd_bf16(p, stream);

@@ -58,6 +58,8 @@ struct PrefillBwdParams {
     float scale;
     int32_t causal;
     int32_t window;  // > 0 (causal only): a row sees its own position and the window - 1 before it
+    // element strides {batch, head, row} of every tensor (innermost dimension contiguous)
+    int64_t qs[3], rs[3], ks[3], vs[3], os[3], vbs[3], gs[3], dqs[3], drs[3], dks[3], dvs[3];
 };
 
 // RMSNorm + RoPE on up to three contiguous [B, H, T, d] tensors of one (B, T, d).

@@ -22,8 +22,9 @@
 //     are the B operands of dV^T += dO^T W, dK^T += Q^T g1 + R^T g2 (transposing LDS reads of the
 //     same tiles).
 // Eleven contractions of 2d flops per (row, key) pair against the forward's four. Tiles go
-// global -> LDS directly into a two-stage ring, one workgroup barrier per tile; the MFMA order is
-// left to the compiler (no hand-placed slots as in the forward kernel).
+// global -> LDS directly into a three-stage ring, one workgroup barrier per tile; both passes are
+// software pipelines of hand-placed slots (one MFMA + its share of vector work), as in the forward.
+// Every tensor is addressed through element strides {batch, head, row}; the workspace is dense.
 #include "plx_device.h"
 #include "plx_kernels.h"
 #include <type_traits>
@@ -54,7 +55,7 @@ struct BwdTile {
 // LDS position. Rows past the end re-read the last row (finite data; masked where it matters).
 // Each wave fills a quarter.
 template <int D>
-__device__ __forceinline__ void load_tile64(const __bf16 *base, int row0, int n_rows,
+__device__ __forceinline__ void load_tile64(const __bf16 *base, int64_t row_stride, int row0, int n_rows,
                                             uint32_t lds_tile_addr, int w, int lane) {
     using TL = BwdTile<D>;
 #pragma unroll
@@ -62,7 +63,7 @@ __device__ __forceinline__ void load_tile64(const __bf16 *base, int row0, int n_
         const int c = (w * TL::NDMA + i) * 64 + lane;
         const int row = c / TL::CPR;
         const int chunk = (c % TL::CPR) ^ lds_row_swizzle<D>(row);
-        const __bf16 *g = base + (int64_t)min(row0 + row, n_rows - 1) * D + chunk * 8;
+        const __bf16 *g = base + (int64_t)min(row0 + row, n_rows - 1) * row_stride + chunk * 8;
         tile_load16<64>(g, lds_tile_addr + (uint32_t)(w * TL::NDMA + i) * 1024u);
     }
 }
@@ -120,11 +121,13 @@ __global__ __launch_bounds__(256) void bwd_rows_prepare_kernel(PrefillBwdParams 
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t n_rows = (int64_t)p.B * p.Hq * p.T;
     if (row >= n_rows) return;
+    const int64_t bh = row / p.T, t = row - bh * p.T, b = bh / p.Hq, h = bh - b * p.Hq;
     float tau = 0.f, beta = 0.f;
     if (lane < D / 2) {
-        const uint32_t g = ((const uint32_t *)p.d_o)[row * (D / 2) + lane];
-        const uint32_t o = ((const uint32_t *)p.o)[row * (D / 2) + lane];
-        const uint32_t vb = ((const uint32_t *)p.vbar)[row * (D / 2) + lane];
+        const uint32_t g = ((const uint32_t *)((const __bf16 *)p.d_o + b * p.gs[0] + h * p.gs[1] + t * p.gs[2]))[lane];
+        const uint32_t o = ((const uint32_t *)((const __bf16 *)p.o + b * p.os[0] + h * p.os[1] + t * p.os[2]))[lane];
+        const uint32_t vb =
+            ((const uint32_t *)((const __bf16 *)p.vbar + b * p.vbs[0] + h * p.vbs[1] + t * p.vbs[2]))[lane];
         tau = bf16_lo_f32(g) * bf16_lo_f32(o) + bf16_hi_f32(g) * bf16_hi_f32(o);
         beta = bf16_lo_f32(g) * bf16_lo_f32(vb) + bf16_hi_f32(g) * bf16_hi_f32(vb);
     }
@@ -176,44 +179,50 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     const int ld_row = min(my_row, T - 1);
 
     // B operands of the score MFMAs: column = query row, k-elements = the 8 dims of chunk 2*ks + h
-    const int64_t qrow = (((int64_t)b * p.Hq + hq) * T + ld_row) * D;
     u32x4 qf[KSTEPS], rf[KSTEPS], gf[KSTEPS];
+    {
+        const __bf16 *qrow = (const __bf16 *)p.q + b * p.qs[0] + hq * p.qs[1] + ld_row * p.qs[2];
+        const __bf16 *rrow = (const __bf16 *)p.r + b * p.rs[0] + hq * p.rs[1] + ld_row * p.rs[2];
+        const __bf16 *grow = (const __bf16 *)p.d_o + b * p.gs[0] + hq * p.gs[1] + ld_row * p.gs[2];
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-        qf[ks] = *(const u32x4 *)((const __bf16 *)p.q + qrow + 8 * (2 * ks + h));
-        rf[ks] = *(const u32x4 *)((const __bf16 *)p.r + qrow + 8 * (2 * ks + h));
-        gf[ks] = *(const u32x4 *)((const __bf16 *)p.d_o + qrow + 8 * (2 * ks + h));
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            qf[ks] = *(const u32x4 *)(qrow + 8 * (2 * ks + h));
+            rf[ks] = *(const u32x4 *)(rrow + 8 * (2 * ks + h));
+            gf[ks] = *(const u32x4 *)(grow + 8 * (2 * ks + h));
+        }
     }
     const f32x4 rc = ((const f32x4 *)p.row_cache)[((int64_t)b * p.Hq + hq) * T + ld_row];
     const float neg_lse = -rc[0], ubar = rc[1], tau = rc[2], beta = rc[3];
     const float scale_log2 = p.scale * kLog2e;
     const BwdLaneOffsets<D> lo(lane);
 
-    const __bf16 *kbase = (const __bf16 *)p.k + (((int64_t)b * p.Hkv + hk) * p.Tk + kt_skip * kTileRows) * D;
-    const __bf16 *vbase = (const __bf16 *)p.v + (((int64_t)b * p.Hkv + hk) * p.Tk + kt_skip * kTileRows) * D;
+    const __bf16 *kbase = (const __bf16 *)p.k + b * p.ks[0] + hk * p.ks[1] + (int64_t)kt_skip * kTileRows * p.ks[2];
+    const __bf16 *vbase = (const __bf16 *)p.v + b * p.vs[0] + hk * p.vs[1] + (int64_t)kt_skip * kTileRows * p.vs[2];
     const uint32_t lds_base = lds_byte_address(lds);
     auto issue_tile = [&](int t, int stage) __attribute__((always_inline)) {
-        load_tile64<D>(kbase, t * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u, w, lane);
-        load_tile64<D>(vbase, t * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS + TL::CHUNKS) * 16u, w,
-                       lane);
+        load_tile64<D>(kbase, p.ks[2], t * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u, w, lane);
+        load_tile64<D>(vbase, p.vs[2], t * kTileRows, Tk,
+                       lds_base + (uint32_t)(stage * STAGE_CHUNKS + TL::CHUNKS) * 16u, w, lane);
     };
     // The steady-state loop spreads the loads of tile t + 2 over the MFMA slots of a step (as a
     // block at the top of an iteration they cost about a tenth of it): per-lane byte offsets
     // inside a complete tile, a wave-uniform tile base.
-    uint32_t toff[TL::NDMA];
+    uint32_t toffk[TL::NDMA], toffv[TL::NDMA];
 #pragma unroll
     for (int i = 0; i < TL::NDMA; ++i) {
         const int c = (w * TL::NDMA + i) * 64 + lane;
         const int row = c / CPR;
-        toff[i] = (uint32_t)(row * D + ((c % CPR) ^ lds_row_swizzle<D>(row)) * 8) * 2u;
+        const int chunk = (c % CPR) ^ lds_row_swizzle<D>(row);
+        toffk[i] = (uint32_t)(row * (int)p.ks[2] + chunk * 8) * 2u;
+        toffv[i] = (uint32_t)(row * (int)p.vs[2] + chunk * 8) * 2u;
     }
     const char *dma_k = nullptr, *dma_v = nullptr;  // tile being fetched by the current step
     uint32_t dma_lds = 0;                           // this wave's first K chunk of its stage
     auto dma_slot = [&](int i) __attribute__((always_inline)) {  // load i of 2 * NDMA (K, then V)
         if (i < TL::NDMA)
-            tile_load16_uniform<false>(toff[i], dma_k, dma_lds + 1024u * i);
+            tile_load16_uniform<false>(toffk[i], dma_k, dma_lds + 1024u * i);
         else
-            tile_load16_uniform<false>(toff[i - TL::NDMA], dma_v,
+            tile_load16_uniform<false>(toffv[i - TL::NDMA], dma_v,
                                        dma_lds + (uint32_t)TL::CHUNKS * 16u + 1024u * (i - TL::NDMA));
     };
     auto k_block = [&](int stage, int kb) __attribute__((always_inline)) { return (const u32x4 *)(lds + stage * STAGE_CHUNKS + kb * kBlk * CPR); };
@@ -393,21 +402,21 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
         const int n_left = min(n_tiles, max(rb * 128 + 128 + off - p.window + kTileRows - 1, 0) / kTileRows);
         for (; t < n_left; ++t) tile_steps(std::true_type{}, std::false_type{}, t);
     }
-    const int64_t tile_bytes = (int64_t)kTileRows * D * 2;
-    dma_k = (const char *)kbase + (t + 2) * tile_bytes;
-    dma_v = (const char *)vbase + (t + 2) * tile_bytes;
+    const int64_t k_tile_bytes = (int64_t)kTileRows * 2 * p.ks[2], v_tile_bytes = (int64_t)kTileRows * 2 * p.vs[2];
+    dma_k = (const char *)kbase + (t + 2) * k_tile_bytes;
+    dma_v = (const char *)vbase + (t + 2) * v_tile_bytes;
     for (; t < n_full - 1; ++t) {
         tile_steps(std::false_type{}, std::true_type{}, t);
-        dma_k += tile_bytes;
-        dma_v += tile_bytes;
+        dma_k += k_tile_bytes;
+        dma_v += v_tile_bytes;
     }
     for (; t < n_tiles; ++t) tile_steps(std::true_type{}, std::false_type{}, t);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no tile load may land after the workgroup ends
 
     // dQ^T / dR^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of row my_row
     if (my_row < T) {
-        __bf16 *dq_row = (__bf16 *)p.dq + qrow;
-        __bf16 *dr_row = (__bf16 *)p.dr + qrow;
+        __bf16 *dq_row = (__bf16 *)p.dq + b * p.dqs[0] + hq * p.dqs[1] + my_row * p.dqs[2];
+        __bf16 *dr_row = (__bf16 *)p.dr + b * p.drs[0] + hq * p.drs[1] + my_row * p.drs[2];
 #pragma unroll
         for (int n = 0; n < NDB; ++n)
 #pragma unroll
@@ -454,12 +463,15 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     const int ld_key = min(my_key, Tk - 1);
 
     // B operands of the score MFMAs: column = key, k-elements = the 8 dims of chunk 2*ks + h
-    const int64_t krow = (((int64_t)b * p.Hkv + hk) * Tk + ld_key) * D;
     u32x4 kf[KSTEPS], vf[KSTEPS];
+    {
+        const __bf16 *krow = (const __bf16 *)p.k + b * p.ks[0] + hk * p.ks[1] + ld_key * p.ks[2];
+        const __bf16 *vrow = (const __bf16 *)p.v + b * p.vs[0] + hk * p.vs[1] + ld_key * p.vs[2];
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-        kf[ks] = *(const u32x4 *)((const __bf16 *)p.k + krow + 8 * (2 * ks + h));
-        vf[ks] = *(const u32x4 *)((const __bf16 *)p.v + krow + 8 * (2 * ks + h));
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            kf[ks] = *(const u32x4 *)(krow + 8 * (2 * ks + h));
+            vf[ks] = *(const u32x4 *)(vrow + 8 * (2 * ks + h));
+        }
     }
     const float scale_log2 = p.scale * kLog2e, scale = p.scale;
     const BwdLaneOffsets<D> lo(lane);
@@ -500,12 +512,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     auto issue_item = [&](int it, int stage) __attribute__((always_inline)) {
         int g, rt;
         item_of(it, g, rt);
-        const int64_t head = ((int64_t)b * p.Hq + hk * G + g) * T;
+        const int hq = hk * G + g;
+        const int64_t head = ((int64_t)b * p.Hq + hq) * T;
         const uint32_t s0 = lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u;
-        load_tile64<D>((const __bf16 *)p.q + head * D, rt * kTileRows, T, s0, w, lane);
-        load_tile64<D>((const __bf16 *)p.r + head * D, rt * kTileRows, T, s0 + (uint32_t)TL::CHUNKS * 16u, w, lane);
-        load_tile64<D>((const __bf16 *)p.d_o + head * D, rt * kTileRows, T, s0 + (uint32_t)(2 * TL::CHUNKS) * 16u, w,
-                       lane);
+        load_tile64<D>((const __bf16 *)p.q + b * p.qs[0] + hq * p.qs[1], p.qs[2], rt * kTileRows, T, s0, w, lane);
+        load_tile64<D>((const __bf16 *)p.r + b * p.rs[0] + hq * p.rs[1], p.rs[2], rt * kTileRows, T,
+                       s0 + (uint32_t)TL::CHUNKS * 16u, w, lane);
+        load_tile64<D>((const __bf16 *)p.d_o + b * p.gs[0] + hq * p.gs[1], p.gs[2], rt * kTileRows, T,
+                       s0 + (uint32_t)(2 * TL::CHUNKS) * 16u, w, lane);
         if (w == 0) {  // the rows' scalars, one float4 per lane
             const f32x4 *src = (const f32x4 *)p.row_cache + head + min(rt * kTileRows + lane, T - 1);
             tile_load16<64>(src, s0 + (uint32_t)(3 * TL::CHUNKS) * 16u);
@@ -515,34 +529,38 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     // The unmasked loop spreads the loads of item it + 2 over the MFMA slots of a step: per-lane
     // byte offsets inside a complete tile, wave-uniform tile bases. (There every wave fetches the
     // 64 row scalars -- the same bytes to the same place -- so that the slots hold no branch.)
-    uint32_t toff[TL::NDMA];
+    uint32_t toffq[TL::NDMA], toffr[TL::NDMA], toffg[TL::NDMA];
 #pragma unroll
     for (int i = 0; i < TL::NDMA; ++i) {
         const int c = (w * TL::NDMA + i) * 64 + lane;
         const int row = c / CPR;
-        toff[i] = (uint32_t)(row * D + ((c % CPR) ^ lds_row_swizzle<D>(row)) * 8) * 2u;
+        const int chunk = (c % CPR) ^ lds_row_swizzle<D>(row);
+        toffq[i] = (uint32_t)(row * (int)p.qs[2] + chunk * 8) * 2u;
+        toffr[i] = (uint32_t)(row * (int)p.rs[2] + chunk * 8) * 2u;
+        toffg[i] = (uint32_t)(row * (int)p.gs[2] + chunk * 8) * 2u;
     }
     const char *dma_q = nullptr, *dma_r = nullptr, *dma_g = nullptr, *dma_rc = nullptr;
     uint32_t dma_lds = 0, dma_lds_rc = 0;
     auto set_dma_item = [&](int it, int stage) __attribute__((always_inline)) {
         int g, rt;
         item_of(it, g, rt);
-        const int64_t row = ((int64_t)b * p.Hq + hk * G + g) * T + (int64_t)rt * kTileRows;
-        dma_q = (const char *)p.q + row * D * 2;
-        dma_r = (const char *)p.r + row * D * 2;
-        dma_g = (const char *)p.d_o + row * D * 2;
-        dma_rc = (const char *)p.row_cache + row * 16;
+        const int hq = hk * G + g;
+        const int64_t row0 = (int64_t)rt * kTileRows;
+        dma_q = (const char *)p.q + (b * p.qs[0] + hq * p.qs[1] + row0 * p.qs[2]) * 2;
+        dma_r = (const char *)p.r + (b * p.rs[0] + hq * p.rs[1] + row0 * p.rs[2]) * 2;
+        dma_g = (const char *)p.d_o + (b * p.gs[0] + hq * p.gs[1] + row0 * p.gs[2]) * 2;
+        dma_rc = (const char *)p.row_cache + (((int64_t)b * p.Hq + hq) * T + row0) * 16;
         dma_lds = lds_base + (uint32_t)(stage * STAGE_CHUNKS + w * TL::NDMA * 64) * 16u;
         dma_lds_rc = lds_base + (uint32_t)(stage * STAGE_CHUNKS + 3 * TL::CHUNKS) * 16u;
     };
     auto dma_slot = [&](int i) __attribute__((always_inline)) {  // load i of 3 * NDMA + 1
         if (i < TL::NDMA)
-            tile_load16_uniform<false>(toff[i], dma_q, dma_lds + 1024u * i);
+            tile_load16_uniform<false>(toffq[i], dma_q, dma_lds + 1024u * i);
         else if (i < 2 * TL::NDMA)
-            tile_load16_uniform<false>(toff[i - TL::NDMA], dma_r,
+            tile_load16_uniform<false>(toffr[i - TL::NDMA], dma_r,
                                        dma_lds + (uint32_t)TL::CHUNKS * 16u + 1024u * (i - TL::NDMA));
         else if (i < 3 * TL::NDMA)
-            tile_load16_uniform<false>(toff[i - 2 * TL::NDMA], dma_g,
+            tile_load16_uniform<false>(toffg[i - 2 * TL::NDMA], dma_g,
                                        dma_lds + (uint32_t)(2 * TL::CHUNKS) * 16u + 1024u * (i - 2 * TL::NDMA));
         else
             tile_load16_uniform<false>((uint32_t)lane * 16u, dma_rc, dma_lds_rc);
@@ -765,8 +783,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
 
     // dK^T / dV^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of key my_key
     if (my_key < Tk) {
-        __bf16 *dk_row = (__bf16 *)p.dk + krow;
-        __bf16 *dv_row = (__bf16 *)p.dv + krow;
+        __bf16 *dk_row = (__bf16 *)p.dk + b * p.dks[0] + hk * p.dks[1] + my_key * p.dks[2];
+        __bf16 *dv_row = (__bf16 *)p.dv + b * p.dvs[0] + hk * p.dvs[1] + my_key * p.dvs[2];
 #pragma unroll
         for (int n = 0; n < NDB; ++n)
 #pragma unroll

@@ -43,7 +43,32 @@ def test_struct_sizes_match_c_layout(binding):
     # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, 2 int32, 2 pointers
     assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8 + 16 + 16 + 8
     # 12 pointers, 6 int32, float + int32, enum (+pad), pointer, size_t
-    assert ctypes.sizeof(binding.plx_prefill_bwd_args) == 12 * 8 + 24 + 8 + 8 + 16
+    assert ctypes.sizeof(binding.plx_prefill_bwd_args) == 12 * 8 + 24 + 8 + 8 + 16 + 11 * 24
+
+
+def test_struct_layouts_match_a_c_compiler(binding, tmp_path):
+    """sizeof and every field offset of the ctypes mirrors against gcc's reading of the header."""
+    import subprocess
+
+    structs = ["plx_decode_args", "plx_prefill_args", "plx_prefill_bwd_args", "plx_norm_rope_tensor",
+               "plx_norm_rope_args"]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "parallax.h"', 'int main(void) {']
+    for sname in structs:
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (sname, sname))
+        for f in getattr(binding, sname)._fields_:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (sname, f[0], sname, f[0]))
+    lines += ['return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    want = dict(l.split() for l in out if l)
+    for sname in structs:
+        cls = getattr(binding, sname)
+        assert ctypes.sizeof(cls) == int(want[sname]), sname
+        for f in cls._fields_:
+            assert getattr(cls, f[0]).offset == int(want["%s.%s" % (sname, f[0])]), (sname, f[0])
 
 
 def test_version_and_strerror(binding):

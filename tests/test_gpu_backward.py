@@ -125,6 +125,41 @@ def test_backward_sliding_window_fp32_and_row_cache(plx, synth, bwd_oracle):
     assert rel_l2(host(stats)[..., 1], ub) <= BF16_REL_L2
 
 
+@pytest.mark.parametrize("T,Tkv,causal,window,d", [(300, 300, True, 0, 128), (200, 500, True, 64, 128),
+                                                    (257, 257, False, 0, 64), (1100, 1100, True, 0, 128)])
+def test_backward_strided_views_equal_dense_tensors(plx, synth, T, Tkv, causal, window, d):
+    """q, rho, k, v as views of fused projections laid out [B, T, heads * d], d_o / o / vbar and
+    the gradients in [B, T, H, d] order: same bits as the dense [B, H, T, d] call."""
+    B, Hq, Hkv = 2, 4, 2
+    y, g = _inputs(synth, B, Hq, Hkv, T, Tkv, d, 2990 + T)
+    o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=causal,
+                                          save_for_backward=True, window=window)
+    dense = plx.parallax_prefill_backward(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g, y["scale"],
+                                          causal=causal, window=window)
+
+    def bthd(x):                      # same values, [B, T, H, d] in memory, viewed as [B, H, T, d]
+        return x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+
+    qr = torch.cat([y["q"].permute(0, 2, 1, 3), y["r"].permute(0, 2, 1, 3)], dim=2).contiguous()   # [B, T, 2 Hq, d]
+    kv = torch.cat([y["k"].permute(0, 2, 1, 3), y["v"].permute(0, 2, 1, 3)], dim=2).contiguous()   # [B, Tkv, 2 Hkv, d]
+    q2, r2 = qr[:, :, :Hq].permute(0, 2, 1, 3), qr[:, :, Hq:].permute(0, 2, 1, 3)
+    k2, v2 = kv[:, :, :Hkv].permute(0, 2, 1, 3), kv[:, :, Hkv:].permute(0, 2, 1, 3)
+    assert not q2.is_contiguous() and q2.stride(2) == 2 * Hq * d
+    dqr = torch.zeros_like(qr)
+    dkv = torch.zeros_like(kv)
+    outs = (dqr[:, :, :Hq].permute(0, 2, 1, 3), dqr[:, :, Hq:].permute(0, 2, 1, 3),
+            dkv[:, :, :Hkv].permute(0, 2, 1, 3), dkv[:, :, Hkv:].permute(0, 2, 1, 3))
+    ws = torch.empty(plx.parallax_prefill_backward_workspace_bytes(B, Hq, T) // 4, dtype=torch.float32, device=DEV)
+    a = plx.prefill_bwd_args(q2, r2, k2, v2, bthd(o), bthd(vbar), stats, bthd(g), *outs, y["scale"], causal, ws,
+                             window)
+    st = plx.load_library().parallax_prefill_backward(__import__("ctypes").byref(a),
+                                                      int(torch.cuda.current_stream().cuda_stream))
+    assert st == 0
+    torch.cuda.synchronize()
+    for name, got, ref in zip(("dq", "dr", "dk", "dv"), outs, dense):
+        assert torch.equal(got.contiguous(), ref), name
+
+
 def test_backward_small_probe_and_zero_probe(plx, synth, bwd_oracle):
     _check(plx, synth, bwd_oracle, 1, 4, 2, 400, 400, 128, True, seed=2300, r_scale=0.1)
     # R = 0: dQ, dK, dV are those of softmax attention; dR is the value/key covariance term
