@@ -353,6 +353,19 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
     us = _time_events(torch, lambda: plx.parallax_util_read(src, sink), 3, 20)
     extra["stream_read_ceiling_GBps"] = round(src.numel() / us / 1e3, 1)
     del src
+    # sustained bf16 matrix rate of a register-only MFMA loop on this machine (one and four waves per SIMD)
+    ceil = {}
+    for wgs in (256, 1024):
+        msink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+        flops = [0.0]
+
+        def mstep():
+            flops[0] = plx.parallax_util_mfma(wgs, 20000, msink)
+
+        us = _time_events(torch, mstep, 1, 3)
+        ceil["%d_workgroups_TFLOPs" % wgs] = round(flops[0] / us / 1e6, 1)
+    ceil["frac_of_bf16_mfma_peak"] = round(max(ceil.values()) / MFMA_BF16_PEAK_TFLOPS, 4)
+    extra["mfma_loop_ceiling"] = ceil
 
     # softmax-only twin on config 2
     x0 = sets
@@ -524,6 +537,8 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
         pre[key + "_us"] = round(us, 1)
         pre[key + "_TFLOPs"] = round(flops / us / 1e6, 1)
     pre["frac_of_bf16_mfma_peak"] = round(pre["parallax_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
+    pre["frac_of_mfma_loop_ceiling"] = round(
+        pre["parallax_TFLOPs"] / max(v for k, v in extra["mfma_loop_ceiling"].items() if k.endswith("TFLOPs")), 4)
     pre["workload"] = "config4: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128, K offset N(0,0.5^2)"
     extra["prefill"] = pre
     # ... and its backward pass (rows prepare + dQ/dR pass + dK/dV pass; 22 d flops per pair)

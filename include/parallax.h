@@ -286,6 +286,14 @@ plx_status parallax_util_copy(void *dst, const void *src, size_t bytes, void *hi
 plx_status parallax_util_read(const void *src, size_t bytes, void *sink, void *hip_stream);
 int32_t parallax_util_read_sink_slots(void);
 
+/* Register-only loop of dense bf16 matrix instructions (v_mfma_f32_32x32x16_bf16, eight
+ * independent accumulators per wave, no memory or LDS traffic): the matrix throughput the chip
+ * sustains on this machine, reported next to the nominal peak. `workgroups` of 4 waves each run
+ * `iters` trips of 8 instructions, i.e. workgroups * 4 * iters * 8 * 32768 flops; sink (device,
+ * >= workgroups * 1024 bytes, 4-byte aligned) receives one float per lane so that the work
+ * cannot be dropped. 1 <= workgroups <= 65536, 1 <= iters <= 2^24. */
+plx_status parallax_util_mfma(int32_t workgroups, int32_t iters, void *sink, void *hip_stream);
+
 const char *parallax_strerror(plx_status status);
 int parallax_version(void);
 

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused",
     "parallax_prefill", "parallax_prefill_backward", "parallax_prefill_backward_workspace_bytes",
     "parallax_norm_rope", "parallax_util_copy", "parallax_util_read",
-    "parallax_util_read_sink_slots", "parallax_strerror", "parallax_version",
+    "parallax_util_read_sink_slots", "parallax_util_mfma", "parallax_strerror", "parallax_version",
 )
 
 
@@ -149,6 +149,8 @@ def load_library() -> ctypes.CDLL:
         lib.parallax_util_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                            ctypes.c_void_p]
         lib.parallax_util_read.restype = ctypes.c_int
+        lib.parallax_util_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        lib.parallax_util_mfma.restype = ctypes.c_int
         lib.parallax_util_read_sink_slots.argtypes = []
         lib.parallax_util_read_sink_slots.restype = ctypes.c_int32
         lib.parallax_strerror.argtypes = [ctypes.c_int]
@@ -471,6 +473,16 @@ def parallax_util_read(src, sink, stream=None):
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_util_read")
     return sink
+
+
+def parallax_util_mfma(workgroups, iters, sink, stream=None) -> float:
+    """Register-only bf16 MFMA loop; returns the flops it performs. sink: >= workgroups * 1024 bytes."""
+    if sink.numel() * sink.element_size() < workgroups * 1024:
+        raise ValueError("sink too small")
+    st = load_library().parallax_util_mfma(int(workgroups), int(iters), sink.data_ptr(), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_util_mfma")
+    return float(workgroups) * 4 * iters * 8 * 32768
 
 
 def parallax_util_read_sink_slots() -> int:

@@ -404,6 +404,15 @@ plx_status parallax_util_read(const void *src, size_t bytes, void *sink, void *h
 
 int32_t parallax_util_read_sink_slots(void) { return plx::kReadSinkSlots; }
 
+plx_status parallax_util_mfma(int32_t workgroups, int32_t iters, void *sink, void *hip_stream) {
+    if (!sink) return PLX_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(sink) & 3u) return PLX_ERR_ALIGN;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return PLX_ERR_SHAPE;
+    return plx::launch_util_mfma(workgroups, iters, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
+}
+
 const char *parallax_strerror(plx_status status) {
     switch (status) {
         case PLX_OK: return "ok";

@@ -1,6 +1,7 @@
 // Plain streaming kernels: a device-to-device copy (calibrates hardware byte counters against
 // a known size) and a read-only stream (achievable HBM read bandwidth next to the attention
-// kernels). 16 bytes per lane, grid-stride.
+// kernels). 16 bytes per lane, grid-stride. And a register-only loop of bf16 MFMAs: the matrix
+// rate the chip sustains when nothing else limits it (no memory, no LDS, no vector work).
 #include "plx_device.h"
 #include "plx_kernels.h"
 
@@ -32,6 +33,49 @@ __global__ __launch_bounds__(256) void util_read_kernel(const u32x4 *src, size_t
         for (int j = 0; j < 256; ++j) t ^= part[j];
         sink[blockIdx.x] = t;
     }
+}
+
+// Eight independent accumulation chains per wave: an MFMA never waits for the one before it, so
+// one wave per SIMD keeps the matrix pipe full. Operands are fixed pseudo-random bf16 values in
+// (-1, 1) (all-zero operands would draw less power than real data and flatter the clock).
+__global__ __launch_bounds__(256) void util_mfma_kernel(int iters, float *sink) {
+    const unsigned tid = threadIdx.x + blockIdx.x * 256u;
+    u32x4 a[4], b[2];
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+        u32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            unsigned x = (tid * 6u + j) * 4u + e;
+            x ^= x >> 16, x *= 0x7feb352du, x ^= x >> 15, x *= 0x846ca68bu, x ^= x >> 16;
+            // two bf16 values: sign and 7 mantissa bits from the hash, exponent of [0.5, 1)
+            v[e] = (x & 0x807f807fu) | 0x3f003f00u;
+        }
+        if (j < 4)
+            a[j] = v;
+        else
+            b[j - 4] = v;
+    }
+    f32x16 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = mfma32(a[j & 3], b[j >> 2], acc[j]);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+    sink[tid] = s;
+}
+
+hipError_t launch_util_mfma(int workgroups, int iters, void *sink, hipStream_t stream) {
+    hipLaunchKernelGGL(util_mfma_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream, iters, (float *)sink);
+    return hipGetLastError();
 }
 
 hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream) {

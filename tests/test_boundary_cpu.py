@@ -240,6 +240,10 @@ def test_util_argument_checks(binding):
     assert lib.parallax_util_copy(0x1000, 0x2000, 10, None) == binding.PLX_ERR_SHAPE
     assert lib.parallax_util_copy(0x1001, 0x2000, 16, None) == binding.PLX_ERR_ALIGN
     assert binding.parallax_util_read_sink_slots() > 0
+    assert lib.parallax_util_mfma(256, 100, None, None) == binding.PLX_ERR_NULL
+    assert lib.parallax_util_mfma(0, 100, 0x1000, None) == binding.PLX_ERR_SHAPE
+    assert lib.parallax_util_mfma(256, 0, 0x1000, None) == binding.PLX_ERR_SHAPE
+    assert lib.parallax_util_mfma(256, 100, 0x1002, None) == binding.PLX_ERR_ALIGN
 
 
 def test_prefill_backward_rejects_bad_arguments_before_launch(binding):

@@ -209,3 +209,20 @@ def test_config5a_long_prefill_sampled(plx, synth, oracle):
     ref = oracle_prefill(oracle, y, rows=rows)
     sub = got[rows[:, 0], rows[:, 1], rows[:, 2]]
     assert rel_l2(sub, ref) <= BF16_REL_L2
+
+
+def test_register_only_mfma_loop_runs_and_counts_its_flops(plx):
+    """The matrix-rate ceiling kernel: every lane ends with a finite, non-trivial sum, and the
+    sustained rate is of the order of the chip's (between a tenth of and the nominal peak)."""
+    sink = torch.zeros(256 * 256, dtype=torch.float32, device=DEV)
+    plx.parallax_util_mfma(256, 50, sink)          # warm-up
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    flops = plx.parallax_util_mfma(256, 5000, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    s = sink.cpu().numpy()
+    assert np.isfinite(s).all() and np.abs(s).max() > 1.0 and len(np.unique(s)) > 1000
+    rate = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    assert 250.0 < rate < 2600.0, rate
