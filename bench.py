@@ -161,11 +161,29 @@ def main():
                 "kernel": "decode_bf16_kernel<128,true,false>", "kernel_us": round(kern_us, 2),
                 "algorithmic_bytes_per_launch": step_bytes}
 
+    # per-launch spread: one event pair per step (whole step) and per split-KV kernel launch
+    def per_launch(fn, arglist, n):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for i, (a, b) in enumerate(evs):
+            a.record(stream)
+            st = fn(ctypes.byref(arglist[i % NSETS]), sptr)
+            b.record(stream)
+            if st != 0:
+                raise plx.ParallaxError(st, "bench step")
+        torch.cuda.synchronize()
+        us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        return {"median": round(us[len(us) // 2], 2), "min": round(us[0], 2), "n": n}
+
+    n_single = min(opt.steps, 200)
+    step_spread = per_launch(lib.parallax_decode, full_args, n_single)
+    roofline["kernel_us_single_launches"] = per_launch(lib.parallax_decode_partials, part_args, n_single)
+
     result = {
         "metric": "decode_hbm_bandwidth", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": opt.steps, "warmup": opt.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 5), "us_per_step": round(sec_per_step * 1e6, 2),
         "us_per_step_stream_events": round(step_us_events, 2),
+        "us_per_step_single_launches": step_spread,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%sdecode bf16 B=%d Hq=16 Hkv=8 d=128 L=%d, "
