@@ -721,6 +721,32 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
                        "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
         del y, po
     extra["block_sparse"] = bs
+
+    # decode over an MLA-style latent cache: one row of 512 + 64 numbers per token, shared by all
+    # heads (algorithmic bytes: the cache once, q, r, o)
+    ml = []
+    for (B, Hq, L) in [(64, 16, 16384), (32, 16, 8192), (128, 16, 4096), (16, 128, 8192)]:
+        nset = max(2, min(8, int(2e9 // (B * L * 1152))))
+        xs = [synth.mla_decode_inputs(B, Hq, L, seed=1012 + i, device=dev) for i in range(nset)]
+        mo = torch.empty(B, Hq, 512, dtype=torch.bfloat16, device=dev)
+        mws = torch.empty(plx.parallax_decode_mla_workspace_bytes(B, Hq) // 4, dtype=torch.float32, device=dev)
+        m_args = [plx.decode_mla_args(x["q"], x["r"], x["ckv"], mo, x["scale"], None, 0, mws) for x in xs]
+        mc = [0]
+
+        def mstep2():
+            st = lib.parallax_decode_mla(ctypes.byref(m_args[mc[0] % nset]), sptr)
+            mc[0] += 1
+            if st != 0:
+                raise plx.ParallaxError(st, "mla bench")
+
+        us = _time_events(torch, mstep2, 5, 50)
+        nbytes = B * L * 1152 + B * Hq * (2 * 576 * 2 + 512 * 2)
+        ml.append({"workload": "MLA-style decode B=%d Hq=%d L=%d (latent 512 + rope 64)" % (B, Hq, L),
+                   "num_splits": plx.parallax_decode_mla_num_splits(B, Hq, L), "us": round(us, 1),
+                   "GBps": round(nbytes / us / 1e3, 1), "frac_of_8TBps": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                   "TFLOPs": round(B * Hq * L * 2 * (2 * 576 + 2 * 512) / us / 1e6, 1)})
+        del xs, m_args, mo, mws
+    extra["mla_decode"] = ml
     return extra
 
 

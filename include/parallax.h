@@ -209,6 +209,44 @@ typedef struct {
 plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
 
 /*
+ * Decode over an MLA-style latent cache (the closing discussion names multi-head latent
+ * attention as structurally compatible; this is its absorbed-projection decode form). Every
+ * cached token is ONE row [latent d_latent | rope part d_rope] shared by all heads: the key of
+ * the token is the whole row, its value the latent part. With a = scale * q_h . c_j over all
+ * d_latent + d_rope numbers, p = softmax_j(a), u_j = rho_h . c_j, ubar = sum_j p_j u_j:
+ *     o_h = sum_j p_j (1 + ubar - u_j) c_j[:d_latent]          (forward definition, Sec. 3.1)
+ * computed by Algorithm 1 with split-KV partials merged as in App. C. bf16 only,
+ * d_latent = 512 and d_rope = 64.
+ *   q, r       [B, Hq, 576] contiguous (already in the latent space), 16-byte aligned
+ *   ckv        [B, Lmax, 576]: element strides ckv_stride_b / ckv_stride_l (multiples of 8,
+ *              ckv_stride_l >= 576), last dimension contiguous
+ *   o          [B, Hq, 512] contiguous (the value up-projection is the caller's)
+ *   seq_lens   int32 [B] on the device or NULL (= Lmax); 0 gives a zero row
+ *   num_splits 0 = heuristic, else 1 .. PLX_MAX_SPLITS
+ *   workspace  fp32 scratch for num_splits > 1, >= parallax_decode_mla_workspace_bytes(B, Hq)
+ * Validates on the host, enqueues one or two kernels on hip_stream, does not synchronise.
+ */
+typedef struct {
+    const void *q, *r;
+    const void *ckv;
+    void *o;
+    const int32_t *seq_lens;
+    int32_t B, Hq, Lmax;
+    int32_t d_latent, d_rope;
+    int32_t num_splits;
+    int64_t ckv_stride_b, ckv_stride_l;
+    float scale;
+    plx_dtype dtype;
+    void *workspace;
+    size_t workspace_bytes;
+} plx_decode_mla_args;
+
+size_t parallax_decode_mla_workspace_bytes(int32_t B, int32_t Hq);
+/* The split count the heuristic picks (num_cus <= 0: ask the device). */
+int32_t parallax_decode_mla_num_splits(int32_t B, int32_t Hq, int32_t Lmax, int32_t num_cus);
+plx_status parallax_decode_mla(const plx_decode_mla_args *args, void *hip_stream);
+
+/*
  * Backward of parallax_prefill (closed-form gradients, App. D): given the upstream gradient d_o,
  * the forward's inputs, its output o and its row cache (vbar, row_stats), writes dq, dr
  * [B, Hq, T, d] and dk, dv [B, Hkv, Tkv, d]; the gradients of a KV head add up over the query

@@ -22,6 +22,7 @@ PLX_MAX_SPLITS = 128
 EXPORTED_SYMBOLS = (
     "parallax_decode_workspace_bytes", "parallax_decode_num_splits", "parallax_decode",
     "parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused",
+    "parallax_decode_mla", "parallax_decode_mla_workspace_bytes", "parallax_decode_mla_num_splits",
     "parallax_prefill", "parallax_prefill_backward", "parallax_prefill_backward_workspace_bytes",
     "parallax_norm_rope", "parallax_util_copy", "parallax_util_read",
     "parallax_util_read_sink_slots", "parallax_util_mfma", "parallax_strerror", "parallax_version",
@@ -96,6 +97,18 @@ class plx_prefill_bwd_args(ctypes.Structure):
     ]
 
 
+class plx_decode_mla_args(ctypes.Structure):
+    _fields_ = [
+        ("q", ctypes.c_void_p), ("r", ctypes.c_void_p), ("ckv", ctypes.c_void_p), ("o", ctypes.c_void_p),
+        ("seq_lens", ctypes.c_void_p),
+        ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Lmax", ctypes.c_int32),
+        ("d_latent", ctypes.c_int32), ("d_rope", ctypes.c_int32), ("num_splits", ctypes.c_int32),
+        ("ckv_stride_b", ctypes.c_int64), ("ckv_stride_l", ctypes.c_int64),
+        ("scale", ctypes.c_float), ("dtype", ctypes.c_int),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
 class plx_norm_rope_tensor(ctypes.Structure):
     _fields_ = [("x", ctypes.c_void_p), ("y", ctypes.c_void_p), ("gamma", ctypes.c_void_p),
                 ("H", ctypes.c_int32), ("rope", ctypes.c_int32)]
@@ -149,6 +162,12 @@ def load_library() -> ctypes.CDLL:
         lib.parallax_util_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                            ctypes.c_void_p]
         lib.parallax_util_read.restype = ctypes.c_int
+        lib.parallax_decode_mla.argtypes = [ctypes.POINTER(plx_decode_mla_args), ctypes.c_void_p]
+        lib.parallax_decode_mla.restype = ctypes.c_int
+        lib.parallax_decode_mla_workspace_bytes.argtypes = [ctypes.c_int32] * 2
+        lib.parallax_decode_mla_workspace_bytes.restype = ctypes.c_size_t
+        lib.parallax_decode_mla_num_splits.argtypes = [ctypes.c_int32] * 4
+        lib.parallax_decode_mla_num_splits.restype = ctypes.c_int32
         lib.parallax_util_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
         lib.parallax_util_mfma.restype = ctypes.c_int
         lib.parallax_util_read_sink_slots.argtypes = []
@@ -455,6 +474,53 @@ def parallax_norm_rope(tensors, pos0=None, eps=1e-6, theta=1.0e6, stream=None, i
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_norm_rope")
     return [t[3] for t in full]
+
+
+def parallax_decode_mla_workspace_bytes(B, Hq) -> int:
+    return int(load_library().parallax_decode_mla_workspace_bytes(B, Hq))
+
+
+def parallax_decode_mla_num_splits(B, Hq, Lmax, num_cus=0) -> int:
+    return int(load_library().parallax_decode_mla_num_splits(B, Hq, Lmax, num_cus))
+
+
+def decode_mla_args(q, r, ckv, out, scale, seq_lens=None, num_splits=0, workspace=None, d_latent=512):
+    """Fill a plx_decode_mla_args: q, r [B, Hq, dk] and out [B, Hq, d_latent] contiguous, ckv
+    [B, L, dk] with any batch / token strides."""
+    for t in (q, r, out):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("parallax_decode_mla needs contiguous device tensors for q, r and out")
+    if not ckv.is_cuda or ckv.stride(-1) != 1:
+        raise ValueError("the last dimension of the cache must be contiguous")
+    a = plx_decode_mla_args()
+    a.q, a.r, a.ckv, a.o = q.data_ptr(), r.data_ptr(), ckv.data_ptr(), out.data_ptr()
+    a.seq_lens = seq_lens.data_ptr() if seq_lens is not None else None
+    a.B, a.Hq, a.Lmax = q.shape[0], q.shape[1], ckv.shape[1]
+    a.d_latent, a.d_rope = d_latent, q.shape[2] - d_latent
+    a.num_splits = int(num_splits)
+    a.ckv_stride_b, a.ckv_stride_l = ckv.stride(0), ckv.stride(1)
+    a.scale = float(scale)
+    a.dtype = _dtype_code(q)
+    if workspace is not None:
+        a.workspace = workspace.data_ptr()
+        a.workspace_bytes = workspace.numel() * workspace.element_size()
+    return a
+
+
+def parallax_decode_mla(q, r, ckv, scale, seq_lens=None, num_splits=0, out=None, workspace=None,
+                        stream=None, d_latent=512):
+    """Parallax decode over an MLA-style latent cache: key = the whole cached row, value = its
+    first d_latent numbers, shared by all heads."""
+    if out is None:
+        out = torch.empty(q.shape[0], q.shape[1], d_latent, dtype=q.dtype, device=q.device)
+    if workspace is None and num_splits != 1:
+        workspace = torch.empty(parallax_decode_mla_workspace_bytes(q.shape[0], q.shape[1]) // 4,
+                                dtype=torch.float32, device=q.device)
+    a = decode_mla_args(q, r, ckv, out, scale, seq_lens, num_splits, workspace, d_latent)
+    st = load_library().parallax_decode_mla(ctypes.byref(a), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_decode_mla")
+    return out
 
 
 def parallax_util_copy(dst, src, stream=None):

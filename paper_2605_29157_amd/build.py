@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_PATH = os.path.join(PKG, "libparallax_hip.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["parallax_api.hip", "decode_bf16.hip", "prefill_bf16.hip", "prefill_bwd_bf16.hip",
+SOURCES = ["parallax_api.hip", "decode_bf16.hip", "decode_mla_bf16.hip", "prefill_bf16.hip", "prefill_bwd_bf16.hip",
            "generic_f32.hip", "norm_rope.hip", "util_kernels.hip"]
 
 # packed-fp32 instructions are disabled for all device code (hipcc's host pass prints a
@@ -86,6 +86,7 @@ def build_library(extra_flags: list[str] | None = None, verbose: bool = True) ->
     with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES) + 3) as pool:
         checks = [pool.submit(_check_prefill_assembly, extra),
                   pool.submit(_check_prefill_assembly, extra, "prefill_bwd_bf16.hip", False),
+                  pool.submit(_check_prefill_assembly, extra, "decode_mla_bf16.hip", False),
                   pool.submit(_check_decode_assembly, extra)]
         objs = list(pool.map(lambda s: _compile(s, extra), SOURCES))
         for c in checks:

@@ -514,7 +514,9 @@ hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream) {
 
 hipError_t launch_decode_combine(const DecodeParams &p, hipStream_t stream) {
     const dim3 grid(p.Hq * p.Tq, p.B);
-    if (p.d == 128)
+    if (p.d == 512)  // records of the latent-cache kernel
+        hipLaunchKernelGGL((decode_combine_kernel<512>), grid, dim3(256), 0, stream, p);
+    else if (p.d == 128)
         hipLaunchKernelGGL((decode_combine_kernel<128>), grid, dim3(256), 0, stream, p);
     else
         hipLaunchKernelGGL((decode_combine_kernel<64>), grid, dim3(256), 0, stream, p);

@@ -295,6 +295,61 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
     return err == hipSuccess ? PLX_OK : PLX_ERR_LAUNCH;
 }
 
+size_t parallax_decode_mla_workspace_bytes(int32_t B, int32_t Hq) {
+    if (B <= 0 || Hq <= 0) return 0;
+    return (size_t)B * Hq * PLX_MAX_SPLITS * (2 * 512 + 4) * sizeof(float);
+}
+
+int32_t parallax_decode_mla_num_splits(int32_t B, int32_t Hq, int32_t Lmax, int32_t num_cus) {
+    if (B <= 0 || Hq <= 0 || Lmax <= 0) return 1;
+    if (num_cus <= 0) num_cus = query_num_cus();
+    // One workgroup per compute unit is resident (its two tile buffers fill the LDS): aim at two
+    // rounds of workgroups so that the tail of a ragged batch stays short, at least 256 keys (four 64-key
+    // stretches) per split, and never more than 4096 keys in one split.
+    const int64_t pairs = (int64_t)B * ((Hq + 15) / 16);
+    const int64_t n_tiles = ((int64_t)Lmax + 63) / 64;
+    int64_t s = (2LL * num_cus + pairs - 1) / pairs;
+    const int64_t by_len = ((int64_t)Lmax + 4095) / 4096;
+    if (s < by_len) s = by_len;
+    const int64_t cap = n_tiles >= 8 ? n_tiles / 4 : 1;
+    if (s > cap) s = cap;
+    if (s > PLX_MAX_SPLITS) s = PLX_MAX_SPLITS;
+    return (int32_t)(s < 1 ? 1 : s);
+}
+
+plx_status parallax_decode_mla(const plx_decode_mla_args *a, void *hip_stream) {
+    if (!a) return PLX_ERR_NULL;
+    if (!a->q || !a->r || !a->ckv || !a->o) return PLX_ERR_NULL;
+    if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
+    if (a->B <= 0 || a->Hq <= 0 || a->Lmax <= 0) return PLX_ERR_SHAPE;
+    if (a->d_latent != 512 || a->d_rope != 64) return PLX_ERR_SHAPE;
+    if (a->B > 65535 || (a->Hq + 15) / 16 > 65535) return PLX_ERR_SHAPE;  // grid dimensions
+    if (!(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
+    if (!aligned16(a->q) || !aligned16(a->r) || !aligned16(a->ckv) || !aligned16(a->o)) return PLX_ERR_ALIGN;
+    if (a->seq_lens && (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u)) return PLX_ERR_ALIGN;
+    if (a->ckv_stride_b < 0 || a->ckv_stride_l < 576) return PLX_ERR_SHAPE;
+    if (!stride_aligned(a->ckv_stride_b, a->dtype) || !stride_aligned(a->ckv_stride_l, a->dtype))
+        return PLX_ERR_ALIGN;
+    if (a->num_splits < 0 || a->num_splits > PLX_MAX_SPLITS) return PLX_ERR_SPLITS;
+
+    plx::MlaDecodeParams p{};
+    p.q = a->q, p.r = a->r, p.ckv = a->ckv, p.o = a->o, p.seq_lens = a->seq_lens;
+    p.B = a->B, p.Hq = a->Hq, p.Lmax = a->Lmax;
+    p.csb = a->ckv_stride_b, p.csl = a->ckv_stride_l;
+    p.scale = a->scale;
+    int32_t S = a->num_splits;
+    if (S == 0) S = parallax_decode_mla_num_splits(a->B, a->Hq, a->Lmax, 0);
+    p.S = S;
+    p.direct_out = S == 1;
+    if (S > 1) {
+        if (!a->workspace || !aligned16(a->workspace)) return PLX_ERR_WORKSPACE;
+        if (a->workspace_bytes < (size_t)a->B * a->Hq * S * (2 * 512 + 4) * sizeof(float)) return PLX_ERR_WORKSPACE;
+        p.ws = static_cast<float *>(a->workspace);
+    }
+    return plx::launch_decode_mla(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? PLX_OK
+                                                                                         : PLX_ERR_LAUNCH;
+}
+
 size_t parallax_prefill_backward_workspace_bytes(int32_t B, int32_t Hq, int32_t T) {
     if (B <= 0 || Hq <= 0 || T <= 0) return 0;
     return (size_t)B * Hq * T * 4 * sizeof(float);

@@ -46,8 +46,20 @@ struct PrefillParams {
     int32_t sparse_batch, sparse_heads;
 };
 
-// Backward of the prefill forward; every tensor contiguous: q-like [B, Hq, T, d], k-like
-// [B, Hkv, Tk, d].
+// Decode over an MLA-style latent cache: one row [latent 512 | rope 64] per token shared by all
+// heads (key = the row, value = its latent part); q, r [B, Hq, 576], o [B, Hq, 512] contiguous.
+struct MlaDecodeParams {
+    const void *q, *r, *ckv;
+    void *o;
+    const int32_t *seq_lens;
+    float *ws;  // split partials: [B][Hq][S] records of (2 * 512 + 4) floats
+    int32_t B, Hq, Lmax, S;
+    int64_t csb, csl;  // element strides of the cache: batch, token
+    float scale;
+    int32_t direct_out;  // 1: S == 1, the kernel writes o itself
+};
+
+// Backward of the prefill forward: q-like tensors [B, Hq, T, d], k-like [B, Hkv, Tk, d].
 struct PrefillBwdParams {
     const void *q, *r, *k, *v, *d_o;
     const void *o, *vbar;    // forward output and cached softmax value mean
@@ -85,6 +97,7 @@ hipError_t launch_prefill_bwd_f32(const PrefillBwdParams &p, hipStream_t stream)
 hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream);
 hipError_t launch_norm_rope(const NormRopeParams &p, bool f32, hipStream_t stream);
+hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream);
 hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);
 hipError_t launch_util_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
 hipError_t launch_util_mfma(int workgroups, int iters, void *sink, hipStream_t stream);

@@ -84,3 +84,20 @@ def paged_cache(x, page_size, seed, spare_pages=3):
     k_pool[idx] = kp.permute(0, 2, 1, 3, 4).reshape(B * per_seq, Hkv, page_size, d)
     v_pool[idx] = vp.permute(0, 2, 1, 3, 4).reshape(B * per_seq, Hkv, page_size, d)
     return k_pool, v_pool, order.to(torch.int32).to(k.device)
+
+
+def mla_decode_inputs(B, Hq, L, seed, d_latent=512, d_rope=64, dtype=torch.bfloat16, device="cpu",
+                      ragged=False, r_scale=1.0):
+    """q, r: [B, Hq, d_latent + d_rope]; ckv: [B, L, d_latent + d_rope] (one latent | rope row per
+    token, shared by all heads); seq_lens: int32 [B] or None; scale = 1/sqrt(d_latent + d_rope)."""
+    gen = _generator(seed, device)
+    dk = d_latent + d_rope
+    q = _randn((B, Hq, dk), gen, device, dtype)
+    r = (_randn((B, Hq, dk), gen, device, torch.float32) * r_scale).to(dtype)
+    ckv = torch.empty((B, L, dk), device=device, dtype=dtype)
+    for b in range(B):  # per sequence: bounds the fp32 temporary
+        ckv[b] = _randn((L, dk), gen, device, dtype)
+    out = {"q": q, "r": r, "ckv": ckv, "scale": 1.0 / math.sqrt(dk), "d_latent": d_latent}
+    if ragged:
+        out["seq_lens"] = ragged_lengths(B, L, seed).to(device)
+    return out

@@ -51,7 +51,7 @@ def test_struct_layouts_match_a_c_compiler(binding, tmp_path):
     import subprocess
 
     structs = ["plx_decode_args", "plx_prefill_args", "plx_prefill_bwd_args", "plx_norm_rope_tensor",
-               "plx_norm_rope_args"]
+               "plx_norm_rope_args", "plx_decode_mla_args"]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "parallax.h"', 'int main(void) {']
     for sname in structs:
         lines.append('printf("%s %%zu\\n", sizeof(%s));' % (sname, sname))
@@ -291,6 +291,49 @@ def test_prefill_backward_rejects_bad_arguments_before_launch(binding):
     f.row_stats = 0x4000
     f.use_r = 0
     assert lib.parallax_prefill(ctypes.byref(f), None) == binding.PLX_ERR_SHAPE
+
+
+def test_decode_mla_rejects_bad_arguments_before_launch(binding):
+    lib = binding.load_library()
+
+    def good():
+        a = binding.plx_decode_mla_args()
+        a.q = a.r = a.ckv = a.o = 0x1000
+        a.B, a.Hq, a.Lmax, a.d_latent, a.d_rope, a.num_splits = 2, 16, 4096, 512, 64, 4
+        a.ckv_stride_b, a.ckv_stride_l = 4096 * 576, 576
+        a.scale, a.dtype = 0.05, binding.PLX_BF16
+        a.workspace, a.workspace_bytes = 0x2000, binding.parallax_decode_mla_workspace_bytes(2, 16)
+        return a
+
+    call = lambda a: lib.parallax_decode_mla(ctypes.byref(a), None)
+    assert binding.parallax_decode_mla_workspace_bytes(2, 16) == 2 * 16 * binding.PLX_MAX_SPLITS * 1028 * 4
+    assert lib.parallax_decode_mla(None, None) == binding.PLX_ERR_NULL
+    a = good(); a.ckv = None
+    assert call(a) == binding.PLX_ERR_NULL
+    a = good(); a.dtype = binding.PLX_F32
+    assert call(a) == binding.PLX_ERR_DTYPE
+    a = good(); a.d_latent, a.d_rope = 256, 64
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.ckv_stride_l = 512
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.ckv_stride_l = 580
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = good(); a.q = 0x1004
+    assert call(a) == binding.PLX_ERR_ALIGN
+    a = good(); a.scale = -1.0
+    assert call(a) == binding.PLX_ERR_SCALE
+    a = good(); a.num_splits = binding.PLX_MAX_SPLITS + 1
+    assert call(a) == binding.PLX_ERR_SPLITS
+    a = good(); a.workspace = None
+    assert call(a) == binding.PLX_ERR_WORKSPACE
+    a = good(); a.workspace_bytes = 100
+    assert call(a) == binding.PLX_ERR_WORKSPACE
+    # the split heuristic is host arithmetic with an explicit compute-unit count
+    f = binding.parallax_decode_mla_num_splits
+    assert f(64, 16, 16384, 256) == 8 and f(1, 16, 16384, 256) == 64 and f(1, 16, 100, 256) == 1
+    assert f(512, 128, 4096, 256) == 1
+    for (B, Hq, L) in [(1, 1, 1), (3, 17, 5000), (128, 16, 131072), (2, 128, 70000)]:
+        assert 1 <= f(B, Hq, L, 256) <= binding.PLX_MAX_SPLITS
 
 
 def test_norm_rope_rejects_bad_arguments_before_launch(binding):

@@ -1,0 +1,140 @@
+"""GPU parity of parallax_decode_mla (through the C ABI) against the MLA-style decode oracle
+(oracle/mla.py, pinned by tests/test_oracle_mla.py)."""
+import numpy as np
+import pytest
+import torch
+
+from parity import BF16_REL_L2, host, rel_l2
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def plx():
+    from paper_2605_29157_amd import binding
+
+    binding.load_library()
+    assert torch.cuda.is_available()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def synth():
+    from paper_2605_29157_amd import synth as s
+
+    return s
+
+
+@pytest.fixture(scope="module")
+def mla():
+    from oracle import mla as m
+
+    return m
+
+
+def _ref(mla, x, seqs=None):
+    q, r, c = host(x["q"]), host(x["r"]), host(x["ckv"])
+    sl = x["seq_lens"].cpu().numpy() if x.get("seq_lens") is not None else None
+    if seqs is not None:
+        q, r, c = q[seqs], r[seqs], c[seqs]
+        sl = sl[seqs] if sl is not None else None
+    return mla.mla_decode(q, r, c, x["d_latent"], x["scale"], sl)
+
+
+def _check(plx, mla, x, num_splits=0, tol=BF16_REL_L2):
+    out = plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"], seq_lens=x.get("seq_lens"),
+                                  num_splits=num_splits)
+    torch.cuda.synchronize()
+    got, ref = host(out), _ref(mla, x)
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    assert rel_l2(got, ref) <= tol, (rel_l2(got, ref), num_splits)
+    # per (sequence, head) as well: a wrong column or wave shows up in single rows
+    err = np.linalg.norm(got - ref, axis=-1) / np.maximum(np.linalg.norm(ref, axis=-1), 1e-6)
+    assert err.max() <= 4 * tol, err.max()
+    return got
+
+
+@pytest.mark.parametrize("L", [1, 2, 15, 16, 17, 63, 64, 65, 127, 129, 200, 777, 2048])
+def test_lengths_and_tails(plx, synth, mla, L):
+    x = synth.mla_decode_inputs(2, 16, L, seed=4000 + L, device=DEV)
+    _check(plx, mla, x, num_splits=1)
+    _check(plx, mla, x, num_splits=0)
+
+
+@pytest.mark.parametrize("S", [1, 2, 3, 5, 8, 32, 128])
+def test_split_counts_agree_incl_empty_splits(plx, synth, mla, S):
+    x = synth.mla_decode_inputs(2, 16, 1000, seed=4100, device=DEV)
+    got = _check(plx, mla, x, num_splits=S)
+    one = host(plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"], num_splits=1))
+    assert rel_l2(got, one) <= 4e-3       # different summation order, each output rounded to bf16 once
+
+
+@pytest.mark.parametrize("Hq", [1, 5, 16, 17, 40, 128])
+def test_head_counts_and_partial_column_groups(plx, synth, mla, Hq):
+    x = synth.mla_decode_inputs(2, Hq, 300, seed=4200 + Hq, device=DEV)
+    _check(plx, mla, x)
+    _check(plx, mla, x, num_splits=3)
+
+
+def test_ragged_lengths_with_an_empty_sequence(plx, synth, mla):
+    x = synth.mla_decode_inputs(5, 16, 900, seed=4300, device=DEV, ragged=True)
+    x["seq_lens"][2] = 0
+    x["seq_lens"][4] = 1
+    for S in (0, 1, 4):
+        got = _check(plx, mla, x, num_splits=S)
+        assert (got[2] == 0).all()
+        np.testing.assert_allclose(got[4], np.broadcast_to(host(x["ckv"])[4, 0, :512], got[4].shape), rtol=1e-2, atol=1e-2)
+
+
+def test_strided_cache_and_small_probe(plx, synth, mla):
+    x = synth.mla_decode_inputs(3, 16, 500, seed=4400, device=DEV, r_scale=0.1)
+    wide = torch.zeros(3, 520, 640, dtype=torch.bfloat16, device=DEV)   # rows of 640, 20 spare tokens
+    wide[:, :500, :576] = x["ckv"]
+    view = wide[:, :500, :576]
+    assert not view.is_contiguous()
+    a = _check(plx, mla, dict(x, ckv=view))
+    b = _check(plx, mla, x)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_large_logit_range_and_zero_scale(plx, synth, mla):
+    x = synth.mla_decode_inputs(2, 16, 700, seed=4500, device=DEV)
+    x["q"] = (x["q"].float() * 12.0).to(torch.bfloat16)     # logits spread over ~ +-40: softmax nearly one-hot
+    _check(plx, mla, x, num_splits=4)
+    _check(plx, mla, dict(x, scale=0.0), num_splits=2)       # uniform weights
+
+
+def test_zero_probe_is_softmax_attention_over_the_latent(plx, synth, mla):
+    x = synth.mla_decode_inputs(2, 16, 400, seed=4600, device=DEV)
+    x["r"] = torch.zeros_like(x["r"])
+    got = _check(plx, mla, x)
+    q, c = torch.tensor(host(x["q"])), torch.tensor(host(x["ckv"]))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        q[:, :, None, :], c[:, None].expand(2, 16, 400, 576), c[:, None, :, :512].expand(2, 16, 400, 512),
+        scale=x["scale"])[:, :, 0].numpy()
+    assert rel_l2(got, ref) <= BF16_REL_L2
+
+
+def test_deterministic_and_errors(plx, synth):
+    x = synth.mla_decode_inputs(2, 16, 1500, seed=4700, device=DEV)
+    a = plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"])
+    b = plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"])
+    assert torch.equal(a, b)
+    with pytest.raises(plx.ParallaxError):                   # only 512 + 64
+        plx.parallax_decode_mla(x["q"][..., :320].contiguous(), x["r"][..., :320].contiguous(),
+                                x["ckv"][..., :320].contiguous(), x["scale"], d_latent=256)
+    with pytest.raises(plx.ParallaxError):
+        plx.parallax_decode_mla(x["q"].float(), x["r"].float(), x["ckv"].float(), x["scale"])
+
+
+def test_serving_shape_sampled(plx, synth, mla):
+    """B = 32 sequences of up to 16 384 tokens, 16 heads (one column group, the per-GPU share of a
+    128-head model under 8-way head parallelism): all heads of four sampled sequences."""
+    x = synth.mla_decode_inputs(32, 16, 16384, seed=4800, device=DEV, ragged=True)
+    out = plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"], seq_lens=x["seq_lens"])
+    torch.cuda.synchronize()
+    lens = x["seq_lens"].cpu().numpy()
+    seqs = sorted({int(lens.argmin()), int(lens.argmax()), 7, 19})
+    ref = _ref(mla, x, seqs)
+    assert rel_l2(host(out)[seqs], ref) <= BF16_REL_L2
