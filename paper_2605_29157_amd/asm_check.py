@@ -140,6 +140,45 @@ def find_early_reads_of_asm_mfma_results(asm_text: str) -> list[str]:
     return bad
 
 
+def find_foreign_uses_of_asm_loaded_registers(asm_text: str) -> list[str]:
+    """Registers that inline-assembly global loads write may hold data that is still on its way;
+    only the inline assembly that waits for it (s_waitcnt) may touch them. Between the first such
+    load and the last inline-assembly LDS store of a kernel, report every compiler-generated
+    instruction that names one of those registers (a copy or a spill there would move stale data)."""
+    bad: list[str] = []
+    for kernel in re.split(r"\n(?=[A-Za-z_][\w$.]*:\s)", asm_text):
+        lines = kernel.split("\n")
+        in_app, loaded, first, last = False, set(), None, None
+        marks = []
+        for n, line in enumerate(lines):
+            s = line.strip()
+            if s.startswith(";;#ASMSTART"):
+                in_app = True
+            elif s.startswith(";;#ASMEND"):
+                in_app = False
+            marks.append(in_app)
+            if in_app and s.startswith("global_load_dwordx4"):
+                loaded |= _regs(s.split()[1].rstrip(","))
+                first = n if first is None else first
+            if in_app and s.startswith("ds_write_b128") and loaded:
+                last = n
+        if not loaded or first is None or last is None:
+            continue
+        for n in range(first, last + 1):
+            s = lines[n].strip()
+            if marks[n] or not _is_instruction(lines[n]):
+                continue
+            ops = s.split(None, 1)
+            used = set()
+            if len(ops) > 1:
+                for operand in ops[1].split(","):
+                    used |= _regs(operand.strip())
+            hit = used & loaded
+            if hit:
+                bad.append("line %d: %s  (touches %s)" % (n + 1, s, sorted(hit)[:4]))
+    return bad
+
+
 def check_file(path: str) -> None:
     with open(path) as f:
         text = f.read()

@@ -57,7 +57,8 @@ def _check_prefill_assembly(extra: list[str], src: str = "prefill_bf16.hip", m0:
         with open(asm) as f:
             text = f.read()
         bad = (asm_check.find_early_reads_of_asm_mfma_results(text)
-               + asm_check.find_m0_uses_outside_inline_asm(text))
+               + asm_check.find_m0_uses_outside_inline_asm(text)
+               + asm_check.find_foreign_uses_of_asm_loaded_registers(text))
         if bad:
             raise RuntimeError("hazard in %s:\n  %s" % (asm, "\n  ".join(bad[:20])))
 

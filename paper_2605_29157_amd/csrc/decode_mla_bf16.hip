@@ -10,12 +10,13 @@
 // for 70 kflop: still HBM bound, but the state of a column group -- O1^T, O2^T of 512 dimensions
 // x 16 columns -- is four times that of the d = 128 decode kernel. So the four waves of a
 // workgroup share each 64-key tile instead of streaming private ones:
-//   * grid (split, group of 16 heads, batch); tiles go global -> LDS directly (no staging
-//     registers), double buffered, 72 KB each, one tile ahead; the loads of the next tile are
-//     spread over the score MFMAs of the current one;
+//   * grid (split, group of 16 heads, batch). What buys bandwidth is bytes in flight: a tile
+//     travels global -> registers -> LDS through TWO register stages per wave, so two 72 KB tiles
+//     are on their way while a third is worked on (ordinary loads do not hold the issuing wave;
+//     global -> LDS loads did, for 1.2 - 2.5 us per tile, with one tile in flight). The registers
+//     for that come from keeping the q and rho fragments in LDS instead.
 //   * scores: wave w takes keys 16w .. 16w+15 of the tile, S^T = C [Q;R]^T over all 576
-//     dimensions (18 k-steps of v_mfma_f32_16x16x32_bf16 against q and rho fragments that stay in
-//     registers);
+//     dimensions (18 k-steps of v_mfma_f32_16x16x32_bf16);
 //   * the tile maximum of a column is agreed on through LDS (one barrier), every wave then forms
 //     P1, P2 = P1 * S2 of its 16 keys and publishes them, already packed as the B operand of the
 //     second contraction, through LDS (second barrier);
@@ -30,16 +31,23 @@
 // and are merged by the same combine kernel (App. C).
 #include "plx_device.h"
 #include "plx_kernels.h"
-#include "plx_lds_dma.h"
 
 namespace plx {
 
 namespace {
 
 constexpr int kMlaDC = 512, kMlaDR = 64, kMlaDK = kMlaDC + kMlaDR;
+constexpr int kMlaTileKeys = 64;
 constexpr int kMlaKSteps = kMlaDK / 32;      // 18 score k-steps, the last two on the rope part
 constexpr int kMlaLatBlocks = kMlaDC / 128;  // column blocks of the latent part
 constexpr int kMlaNDB = 128 / 16;            // 16-dimension output blocks per wave
+constexpr int kMlaPvSteps = kMlaTileKeys / 32;         // k-steps of the second contraction
+constexpr int kMlaBlkChunks = kMlaTileKeys * 16;       // 16-byte chunks of one column block
+constexpr int kMlaRopeChunks = kMlaTileKeys * (kMlaDR / 8);
+constexpr int kMlaTileChunks = kMlaLatBlocks * kMlaBlkChunks + kMlaRopeChunks;
+constexpr int kMlaLoadsPerWave = kMlaTileChunks / 64 / 4;  // wave-wide 1 KB loads per tile and wave
+constexpr int kRowGroups = kMlaTileKeys / 4;           // loads per latent column block (4 rows each)
+static_assert(kMlaTileChunks % 256 == 0 && kMlaLoadsPerWave == 18, "four waves fill a tile with whole loads");
 
 // Rounds four fp32 values to bf16 (one half of an MFMA B operand) and adds the ROUNDED values to
 // acc, so that row sums and numerators use identical weights.
@@ -69,27 +77,14 @@ __device__ unsigned long long plx_mla_stamps[8];
 #define MLA_STAMP(slot) ((void)0)
 #endif
 
-// TK keys per tile: 64 (two buffers, all four waves score 16 keys each; the one in use) or 32
-// (ring of four buffers, waves 0 and 1 score: more tiles in flight, but the per-tile chain of
-// barriers and LDS exchanges is paid twice as often -- measured 25 % slower).
-template <int TK>
 __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
-    constexpr int kMlaTileKeys = TK;
-    constexpr int kMlaBufs = 128 / TK;        // tile buffers: what the LDS holds
-    constexpr int kMlaScoreWaves = TK / 16;   // waves that compute scores (16 keys each)
-    constexpr int kMlaPvSteps = TK / 32;      // k-steps of the second contraction
-    constexpr int kMlaBlkChunks = kMlaTileKeys * 16;  // 16-byte chunks of one column block
-    constexpr int kMlaRopeChunks = kMlaTileKeys * (kMlaDR / 8);
-    constexpr int kMlaBufChunks = kMlaLatBlocks * kMlaBlkChunks + kMlaRopeChunks;
-    constexpr int kMlaLoadsPerWave = kMlaBufChunks / 64 / 4;  // wave-wide 1 KB loads per tile and wave
-    constexpr int kRowGroups = TK / 4;        // loads per latent column block (4 rows each)
-    static_assert(TK == 32 || TK == 64, "tile sizes in use");
-    static_assert(kMlaBufChunks % 256 == 0, "four waves fill a tile with whole loads");
-    // [ring of tile buffers] [P1 | P2 as B operands: 64 lanes each] [tile maxima] [row sums]
-    __shared__ u32x4 lds[kMlaBufs * kMlaBufChunks + 128 * kMlaPvSteps + 4 * kMlaScoreWaves + 8 * kMlaScoreWaves];
-    u32x4 *pbuf = lds + kMlaBufs * kMlaBufChunks;  // P1: [k-step][64 lanes], then P2 likewise
-    float *smax = (float *)(pbuf + 128 * kMlaPvSteps);  // [scoring waves][16 columns]
-    float *dex = smax + 16 * kMlaScoreWaves;            // [scoring waves][16 columns][2]
+    // [tile] [q fragments: k-step x lane] [rho fragments] [P1 | P2 as B operands] [tile maxima] [row sums]
+    __shared__ u32x4 lds[kMlaTileChunks + 2 * kMlaKSteps * 64 + 128 * kMlaPvSteps + 16 + 32];
+    u32x4 *qlds = lds + kMlaTileChunks;
+    u32x4 *rlds = qlds + kMlaKSteps * 64;
+    u32x4 *pbuf = rlds + kMlaKSteps * 64;               // P1: [k-step][64 lanes], then P2 likewise
+    float *smax = (float *)(pbuf + 128 * kMlaPvSteps);  // [4 waves][16 columns]
+    float *dex = smax + 64;                             // [4 waves][16 columns][2]
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -108,70 +103,143 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
     const int t_hi = min(t_lo + tiles_per_split, n_tiles);
     const int key_hi = min(t_hi * kMlaTileKeys, Lb);
 
-    // ---- B operands: q and rho of the group's heads, zero in the dead columns ---------------
-    u32x4 qf[kMlaKSteps], rf[kMlaKSteps];
+    // ---- B operands: q and rho of the group's heads (zero in the dead columns) -> LDS, in the
+    // order the MFMAs want them: entry [k-step s][lane (c, g)] = dims 32 s + 8 g .. + 7 of column c.
+    // Wave w fills the k-steps w, w + 4, ...; everybody reads them back in every tile.
     {
         const int64_t row = ((int64_t)b * p.Hq + (live ? head : 0)) * kMlaDK;
         const __bf16 *qrow = (const __bf16 *)p.q + row;
         const __bf16 *rrow = (const __bf16 *)p.r + row;
         const u32x4 z = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int s = 0; s < kMlaKSteps; ++s) {
-            qf[s] = live ? *(const u32x4 *)(qrow + 32 * s + 8 * g) : z;
-            rf[s] = live ? *(const u32x4 *)(rrow + 32 * s + 8 * g) : z;
+        for (int s = w; s < kMlaKSteps; s += 4) {
+            qlds[s * 64 + lane] = live ? *(const u32x4 *)(qrow + 32 * s + 8 * g) : z;
+            rlds[s * 64 + lane] = live ? *(const u32x4 *)(rrow + 32 * s + 8 * g) : z;
         }
     }
 
-    // ---- global -> LDS tile loads -------------------------------------------------------------
-    // Load idx (0..35) of a tile fills the 64 consecutive chunk slots [64 idx, 64 idx + 64): four
-    // rows of a latent column block (idx < 32: block idx / 8, rows 4 (idx % 8) ..) or eight rows
-    // of the rope block. Every lane fetches the global chunk that belongs at its slot. Rows past
-    // the sequence end re-read its last row (finite data, masked below).
-    // A tile whose 32 rows all exist is fetched through a wave-uniform tile base plus per-lane
-    // byte offsets computed once (no address arithmetic in the loop); the last, partial tile of a
-    // sequence takes the clamping form.
+    // ---- global -> registers -> LDS tile path ------------------------------------------------
+    // The LDS tile is four latent column blocks [64 rows][16 chunks] plus the rope block
+    // [64 rows][8 chunks], chunks permuted inside their row (lds_chunk_slot).
+    //  * dense cache (token stride = 576): a tile is 72 KB of consecutive memory and load idx
+    //    (0..71) of the tile simply fetches its bytes [1024 idx, +1024) -- the access pattern of a
+    //    plain copy; every lane then writes its chunk to the slot of its (row, chunk).
+    //  * strided cache: load idx fetches the chunks of the 64 consecutive LDS slots [64 idx, +64)
+    //    (four rows of a column block, or eight rows of the rope block), and the register -> LDS
+    //    stores are consecutive.
+    // Either way one per-lane offset per load is kept: the LDS slot (dense) or the global byte
+    // offset (strided). A partial last tile re-reads the sequence's last row for the rows past
+    // its end (finite data, masked below); its places are recomputed, not kept.
     const __bf16 *cbase = (const __bf16 *)p.ckv + (int64_t)b * p.csb;
-    const uint32_t lds_base = lds_byte_address(lds);
-    int ld_row[kMlaLoadsPerWave], ld_elem[kMlaLoadsPerWave];
-    uint32_t ld_off[kMlaLoadsPerWave];
-#pragma unroll
-    for (int i = 0; i < kMlaLoadsPerWave; ++i) {
+    const bool dense = p.csl == kMlaDK;  // workgroup-uniform
+    auto slot_place = [&](int i, int &row, int &elem) __attribute__((always_inline)) {  // strided: load i of this wave
         const int idx = w * kMlaLoadsPerWave + i;  // wave-uniform
         if (idx < kMlaLatBlocks * kRowGroups) {
-            ld_row[i] = 4 * (idx % kRowGroups) + (lane >> 4);
-            ld_elem[i] = (idx / kRowGroups) * 128 + (((lane & 15) ^ lds_row_swizzle<128>(ld_row[i])) * 8);
+            row = 4 * (idx % kRowGroups) + (lane >> 4);
+            elem = (idx / kRowGroups) * 128 + (((lane & 15) ^ lds_row_swizzle<128>(row)) * 8);
         } else {
-            ld_row[i] = 8 * (idx - kMlaLatBlocks * kRowGroups) + (lane >> 3);
-            ld_elem[i] = kMlaDC + (((lane & 7) ^ lds_row_swizzle<64>(ld_row[i])) * 8);
+            row = 8 * (idx - kMlaLatBlocks * kRowGroups) + (lane >> 3);
+            elem = kMlaDC + (((lane & 7) ^ lds_row_swizzle<64>(row)) * 8);
         }
-        ld_off[i] = (uint32_t)(ld_row[i] * (int)p.csl + ld_elem[i]) * 2u;
+    };
+    auto linear_place = [&](int i, int &row, int &chunk) __attribute__((always_inline)) {  // dense: load i of this wave
+        const int q = (w * kMlaLoadsPerWave + i) * 64 + lane;  // 16-byte chunk of the tile
+        row = q / (kMlaDK / 8);
+        chunk = q - row * (kMlaDK / 8);
+    };
+    uint32_t off[kMlaLoadsPerWave];
+#pragma unroll
+    for (int i = 0; i < kMlaLoadsPerWave; ++i) {
+        if (dense) {
+            int row, chunk;
+            linear_place(i, row, chunk);
+            off[i] = chunk < 64 ? (uint32_t)((chunk >> 4) * kMlaBlkChunks + lds_chunk_slot<128>(row, chunk & 15)) * 16u
+                                : (uint32_t)(kMlaLatBlocks * kMlaBlkChunks + lds_chunk_slot<64>(row, chunk - 64)) * 16u;
+        } else {
+            int row, elem;
+            slot_place(i, row, elem);
+            off[i] = (uint32_t)(row * (int)p.csl + elem) * 2u;
+        }
     }
     const int64_t tile_bytes = (int64_t)kMlaTileKeys * 2 * p.csl;
-    auto issue_tile = [&](int t, int buf) __attribute__((always_inline)) {
+    const uint32_t wave_lin = (uint32_t)(w * kMlaLoadsPerWave * 64 + lane) * 16u;  // this lane's first chunk, both sides
+    // The stage loads, the wait for them and the stage -> LDS stores are assembly statements:
+    // left to the compiler, the wait in front of a stage's stores also covers the loads of the
+    // OTHER stage, issued one tile later (its bookkeeping of loads in flight is pessimistic across
+    // the loop edge), which takes away half of what is in flight. The stage registers are touched
+    // by these statements only -- the build checks that on the generated code
+    // (asm_check.find_foreign_uses_of_asm_loaded_registers): nothing else may read or move a
+    // register whose load is still on its way. The stages live in accumulation registers (loads
+    // and LDS stores take those directly on this chip), which the matrix instructions of this
+    // kernel leave free. Loads complete in issue order, so "at most 18 in flight" means the older
+    // stage has landed.
+    u32x4 stg_a[kMlaLoadsPerWave], stg_b[kMlaLoadsPerWave];  // tiles t_lo + even / + odd
+    auto load_stage = [&](u32x4 (&stg)[kMlaLoadsPerWave], int t) __attribute__((always_inline)) {
         const int tk0 = t * kMlaTileKeys;
-        const uint32_t dst = lds_base + (uint32_t)(buf * kMlaBufChunks + w * kMlaLoadsPerWave * 64) * 16u;
+        const char *tile_base = (const char *)cbase + t * tile_bytes;
         if (tk0 + kMlaTileKeys <= Lb) {  // workgroup-uniform
-            const char *tile_base = (const char *)cbase + t * tile_bytes;
+            if (dense) {
 #pragma unroll
-            for (int i = 0; i < kMlaLoadsPerWave; ++i) tile_load16_uniform<false>(ld_off[i], tile_base, dst + 1024u * i);
+                for (int i = 0; i < kMlaLoadsPerWave; ++i)
+                    asm volatile("global_load_dwordx4 %0, %1, %2" : "=a"(stg[i]) : "v"(wave_lin), "s"(tile_base + 1024 * i));
+            } else {
+#pragma unroll
+                for (int i = 0; i < kMlaLoadsPerWave; ++i)
+                    asm volatile("global_load_dwordx4 %0, %1, %2" : "=a"(stg[i]) : "v"(off[i]), "s"(tile_base));
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < kMlaLoadsPerWave; ++i) {
-                const int key = min(tk0 + ld_row[i], Lb - 1);
-                tile_load16<64>(cbase + (int64_t)key * p.csl + ld_elem[i], dst + 1024u * i);
+                int row, elem;
+                if (dense) {
+                    linear_place(i, row, elem);
+                    elem *= 8;
+                } else {
+                    slot_place(i, row, elem);
+                }
+                const int key = min(tk0 + row, Lb - 1);
+                const __bf16 *src = cbase + (int64_t)key * p.csl + elem;
+                asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(stg[i]) : "v"(src));
             }
         }
     };
-    // The loads of a COMPLETE next tile are spread over the score MFMAs of the current one (a
-    // wave-wide load occupies the wave for as long as the texture path needs for its kilobyte;
-    // issued as a block, a tile's loads cost a third of an iteration): these name that tile.
-    const char *dma_base = nullptr;
-    uint32_t dma_dst = 0;
-    // per-lane LDS byte offsets inside a tile buffer of the two read patterns (set up once):
+    // Loads [i0, i1) of a COMPLETE tile (spread over the matrix work of the tile before: issued as
+    // one block, the 72 loads of a tile keep the four waves in the issue stage for 1.2 - 1.6 us,
+    // the time the texture path needs for 72 KB).
+    auto load_piece = [&](u32x4 (&stg)[kMlaLoadsPerWave], const char *tile_base, int i0, int i1)
+                          __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i) {
+            if (dense)
+                asm volatile("global_load_dwordx4 %0, %1, %2" : "=a"(stg[i]) : "v"(wave_lin), "s"(tile_base + 1024 * i));
+            else
+                asm volatile("global_load_dwordx4 %0, %1, %2" : "=a"(stg[i]) : "v"(off[i]), "s"(tile_base));
+        }
+    };
+    const uint32_t lds_tile_addr = (uint32_t)(uintptr_t)(const char __attribute__((address_space(3))) *)lds;
+    // `younger`: the other stage's 18 loads were issued after this stage's and may stay in flight
+    auto store_stage = [&](const u32x4 (&stg)[kMlaLoadsPerWave], bool younger) __attribute__((always_inline)) {
+        if (younger)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMlaLoadsPerWave) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (dense) {
+#pragma unroll
+            for (int i = 0; i < kMlaLoadsPerWave; ++i)
+                asm volatile("ds_write_b128 %0, %1" ::"v"(lds_tile_addr + off[i]), "a"(stg[i]) : "memory");
+        } else {
+            const uint32_t base = lds_tile_addr + wave_lin;
+#pragma unroll
+            for (int i = 0; i < kMlaLoadsPerWave; ++i)
+                asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(base), "a"(stg[i]), "n"(1024 * i) : "memory");
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the barrier that follows publishes the tile
+    };
+    // per-lane LDS byte offsets inside the tile of the two read patterns (set up once):
     // K operand of score k-step s: chunk 4 (s % 4) + g of row 16 w + c in column block s / 4
-    // (+ 8 KB per block as an immediate), the two rope k-steps in the rope block; V^T operand of
-    // dimension block n: rows 4 g + c / 4 (and + 16: + 4 KB, the swizzle does not see bit 4)
-    const int krow = 16 * (w % kMlaScoreWaves) + c;
+    // (+ 16 KB per block as an immediate), the two rope k-steps in the rope block; V^T operand of
+    // dimension block n: rows 4 g + c / 4 (+ 16, 32, 48 rows as immediates: the chunk permutation
+    // reads bits 0..3 of the row only)
+    const int krow = 16 * w + c;
     uint32_t k_off[4], k_off_rope[2], v_off[kMlaNDB];
 #pragma unroll
     for (int j = 0; j < 4; ++j) k_off[j] = (uint32_t)lds_chunk_slot<128>(krow, 4 * j + g) * 16u;
@@ -182,7 +250,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
     for (int n = 0; n < kMlaNDB; ++n)
         v_off[n] = (uint32_t)(w * kMlaBlkChunks + lds_chunk_slot<128>(4 * g + (c >> 2), 2 * n + ((c & 3) >> 1))) * 16u +
                    (uint32_t)(c & 1) * 8u;
-    // (rows r, r + 16, r + 32, r + 48 of a tile share the chunk permutation: it reads bits 0..3)
+    const char *tile = (const char *)lds;
 
     // ---- running state: column c; O^T rows = dimensions 128 w + 16 n + 4 g + i ---------------
     float m_run = kNegInf, dsum1 = 0.f, dsum2 = 0.f;  // sums: partial over this lane's keys
@@ -193,107 +261,72 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         o2[n] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const float scale_log2 = p.scale * kLog2e;
-
-#pragma unroll
-    for (int i = 0; i < kMlaBufs - 1; ++i)
-        if (t_lo + i < t_hi) issue_tile(t_lo + i, i);
-    const bool scorer = w < kMlaScoreWaves;  // wave-uniform
 #ifdef PLX_MLA_TIMING
     unsigned long long acc_[8] = {0, 0, 0, 0, 0, 0, 0, 0}, last_ = wall_clock64();
 #endif
-    int buf = 0;
-    for (int t = t_lo; t < t_hi; ++t, buf = (buf + 1) & (kMlaBufs - 1)) {
-        // Tile t has landed (loads complete in issue order; up to kMlaBufs - 2 younger tiles stay
-        // in flight) and is visible; every wave is past its reads of tile t - 1, whose buffer
-        // then receives tile t + kMlaBufs - 1.
-        const int younger = t_hi - 1 - t;  // workgroup-uniform
-        if (kMlaBufs >= 4 && younger >= 2)
-            tile_barrier<(kMlaBufs >= 4 ? 2 : 0) * kMlaLoadsPerWave>();
-        else if (kMlaBufs >= 3 && younger == 1)
-            tile_barrier<(kMlaBufs >= 3 ? 1 : 0) * kMlaLoadsPerWave>();
-        else
-            tile_barrier<0>();
-        MLA_STAMP(0);  // wait for the tile + barrier
-        bool spread = false;  // workgroup-uniform
-        if (t + kMlaBufs - 1 < t_hi) {
-            const int tn = t + kMlaBufs - 1, bn = (buf + kMlaBufs - 1) & (kMlaBufs - 1);
-            spread = kMlaScoreWaves == 4 && (tn + 1) * kMlaTileKeys <= Lb;
-            if (spread) {
-                dma_base = (const char *)cbase + tn * tile_bytes;
-                dma_dst = lds_base + (uint32_t)(bn * kMlaBufChunks + w * kMlaLoadsPerWave * 64) * 16u;
-            } else {
-                issue_tile(tn, bn);
-            }
-        }
-        const char *tile = (const char *)(lds + buf * kMlaBufChunks);
+
+    // One tile: on entry it is in LDS (written by all waves, not yet published); `next` holds the
+    // tile after it (in flight or landed), which is written to LDS at the end, and is then
+    // refilled with the tile three ahead.
+    // `fill` is the stage that was emptied at the end of the tile before: it receives tile t + 2.
+    auto process_tile = [&](int t, u32x4 (&next)[kMlaLoadsPerWave], u32x4 (&fill)[kMlaLoadsPerWave])
+                            __attribute__((always_inline)) {
+        __syncthreads();  // tile t (and, the first time, the q / rho fragments) are visible
+        MLA_STAMP(0);
+        // tile t + 2 sets off now: piece by piece between the matrix instructions if it is complete
+        const bool refill = t > t_lo && t + 2 < t_hi;  // (the prologue has requested t_lo + 1 and t_lo + 2)
+        const bool spread = refill && (t + 3) * kMlaTileKeys <= Lb;  // workgroup-uniform
+        const char *fill_base = (const char *)cbase + (t + 2) * tile_bytes;
+        if (refill && !spread) load_stage(fill, t + 2);
 
         // ---- S1^T = C q^T, S2^T = C rho^T for the keys 16 w .. 16 w + 15 of the tile ---------
-        // (all fragment reads of a half first, so that their latencies overlap; two accumulation
-        // chains per product, so that an MFMA does not wait for the one before it)
+        // (the fragment reads of three k-steps are issued together so that their latencies
+        // overlap; two accumulation chains per product)
         f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
-        if (scorer) {
-            f32x4 s1b = {0.f, 0.f, 0.f, 0.f}, s2b = {0.f, 0.f, 0.f, 0.f};
+        f32x4 s1b = {0.f, 0.f, 0.f, 0.f}, s2b = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                constexpr int HS = kMlaKSteps / 2;
-                u32x4 kf[HS];
+        for (int part = 0; part < 6; ++part) {
+            constexpr int HS = kMlaKSteps / 6;
+            u32x4 kf[HS], qv[HS], rv[HS];
 #pragma unroll
-                for (int j = 0; j < HS; ++j) {
-                    const int ks = half * HS + j;
-                    kf[j] = ks < kMlaLatBlocks * 4
-                                ? *(const u32x4 *)(tile + k_off[ks & 3] + (ks >> 2) * (kMlaBlkChunks * 16))
-                                : *(const u32x4 *)(tile + k_off_rope[ks - kMlaLatBlocks * 4]);
-                }
-                if (spread) {
+            for (int j = 0; j < HS; ++j) {
+                const int ks = part * HS + j;
+                kf[j] = ks < kMlaLatBlocks * 4 ? *(const u32x4 *)(tile + k_off[ks & 3] + (ks >> 2) * (kMlaBlkChunks * 16))
+                                               : *(const u32x4 *)(tile + k_off_rope[ks - kMlaLatBlocks * 4]);
+                qv[j] = qlds[ks * 64 + lane];
+                rv[j] = rlds[ks * 64 + lane];
+            }
+            if (spread) load_piece(fill, fill_base, 2 * part, 2 * part + 2);
 #pragma unroll
-                    for (int j = 0; j < HS; ++j) {
-                        const int ks = half * HS + j;
-                        if (ks < kMlaLoadsPerWave) tile_load16_uniform<false>(ld_off[ks], dma_base, dma_dst + 1024u * ks);
-                        if (j & 1) {
-                            s1b = mfma16(kf[j], qf[ks], s1b);
-                            s2b = mfma16(kf[j], rf[ks], s2b);
-                        } else {
-                            s1 = mfma16(kf[j], qf[ks], s1);
-                            s2 = mfma16(kf[j], rf[ks], s2);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
+            for (int j = 0; j < HS; ++j) {
+                if ((part * HS + j) & 1) {
+                    s1b = mfma16(kf[j], qv[j], s1b);
+                    s2b = mfma16(kf[j], rv[j], s2b);
                 } else {
-#pragma unroll
-                    for (int j = 0; j < HS; ++j) {
-                        const int ks = half * HS + j;
-                        if (j & 1) {
-                            s1b = mfma16(kf[j], qf[ks], s1b);
-                            s2b = mfma16(kf[j], rf[ks], s2b);
-                        } else {
-                            s1 = mfma16(kf[j], qf[ks], s1);
-                            s2 = mfma16(kf[j], rf[ks], s2);
-                        }
-                    }
+                    s1 = mfma16(kf[j], qv[j], s1);
+                    s2 = mfma16(kf[j], rv[j], s2);
                 }
             }
-            s1 += s1b;
-            s2 += s2b;
         }
+        s1 += s1b;
+        s2 += s2b;
+        MLA_STAMP(1);
 
-        MLA_STAMP(1);  // (block issue of the loads) + scores
         // ---- tile maximum of every column, agreed on by the four waves ------------------------
         const int key0 = t * kMlaTileKeys + 16 * w + 4 * g;  // this lane's keys: key0 + i
         float x[4];
         float tmax = kNegInf;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            x[i] = scorer && key0 + i < key_hi ? s1[i] * scale_log2 : kNegInf;
+            x[i] = key0 + i < key_hi ? s1[i] * scale_log2 : kNegInf;
             tmax = fmaxf(tmax, x[i]);
         }
         tmax = rows_max(tmax);
-        if (scorer && g == 0) smax[w * 16 + c] = tmax;
-        MLA_STAMP(2);  // mask, wave maximum
+        if (g == 0) smax[w * 16 + c] = tmax;
+        MLA_STAMP(2);
         __syncthreads();
-        MLA_STAMP(3);  // barrier
-        float m_tile = smax[c];
-#pragma unroll
-        for (int ww = 1; ww < kMlaScoreWaves; ++ww) m_tile = fmaxf(m_tile, smax[16 * ww + c]);
+        MLA_STAMP(3);
+        const float m_tile = fmaxf(fmaxf(smax[c], smax[16 + c]), fmaxf(smax[32 + c], smax[48 + c]));
         const float m_new = fmaxf(m_run, m_tile);
         const float m_use = m_new == kNegInf ? 0.f : m_new;
         const float alpha = fast_exp2(m_run - m_use);  // 0 on the first live tile
@@ -313,14 +346,14 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         dsum2 *= alpha;
         const u32x2 pk1 = pack4_bf16_accumulate(p1[0], p1[1], p1[2], p1[3], dsum1);
         const u32x2 pk2 = pack4_bf16_accumulate(p2[0], p2[1], p2[2], p2[3], dsum2);
-        if (scorer) {
+        {
             u32x2 *dst = (u32x2 *)(pbuf + (w >> 1) * 64 + lane) + (w & 1);
             dst[0] = pk1;
             dst[128 * kMlaPvSteps] = pk2;  // P2 follows P1: 64 chunks = 128 half-chunks per k-step
         }
-        MLA_STAMP(4);  // softmax, P
+        MLA_STAMP(4);
         __syncthreads();
-        MLA_STAMP(5);  // barrier
+        MLA_STAMP(5);
 
         if (!__all(alpha == 1.f)) {
 #pragma unroll
@@ -336,20 +369,45 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
 #pragma unroll
         for (int j = 0; j < kMlaPvSteps; ++j) {
             const u32x4 pb1 = pbuf[j * 64 + lane], pb2 = pbuf[(kMlaPvSteps + j) * 64 + lane];
-            u32x2 vlo[kMlaNDB], vhi[kMlaNDB];
 #pragma unroll
-            for (int n = 0; n < kMlaNDB; ++n) {
-                vlo[n] = lds_read_tr16(tile + v_off[n] + j * (32 * 16 * 16));
-                vhi[n] = lds_read_tr16(tile + v_off[n] + j * (32 * 16 * 16) + 16 * 16 * 16);
-            }
+            for (int nh = 0; nh < kMlaNDB; nh += 4) {
+                u32x2 vlo[4], vhi[4];
 #pragma unroll
-            for (int n = 0; n < kMlaNDB; ++n) {
-                const u32x4 vt = {vlo[n][0], vlo[n][1], vhi[n][0], vhi[n][1]};
-                o1[n] = mfma16(vt, pb1, o1[n]);
-                o2[n] = mfma16(vt, pb2, o2[n]);
+                for (int n = 0; n < 4; ++n) {
+                    vlo[n] = lds_read_tr16(tile + v_off[nh + n] + j * (32 * 16 * 16));
+                    vhi[n] = lds_read_tr16(tile + v_off[nh + n] + j * (32 * 16 * 16) + 16 * 16 * 16);
+                }
+                if (spread) {
+                    const int piece = 2 * j + nh / 4;  // 0..3
+                    load_piece(fill, fill_base, 12 + (piece * 6) / 4, 12 + ((piece + 1) * 6) / 4);
+                }
+#pragma unroll
+                for (int n = 0; n < 4; ++n) {
+                    const u32x4 vt = {vlo[n][0], vlo[n][1], vhi[n][0], vhi[n][1]};
+                    o1[nh + n] = mfma16(vt, pb1, o1[nh + n]);
+                    o2[nh + n] = mfma16(vt, pb2, o2[nh + n]);
+                }
             }
         }
-        MLA_STAMP(6);  // rescale + second contraction
+        MLA_STAMP(6);
+
+        // ---- everybody is done with tile t: the next one moves in, the one three ahead sets off
+        if (t + 1 < t_hi) {
+            __syncthreads();
+            store_stage(next, t + 2 < t_hi);
+        }
+        MLA_STAMP(7);
+    };
+
+    if (t_lo < t_hi) {
+        load_stage(stg_a, t_lo);
+        if (t_lo + 1 < t_hi) load_stage(stg_b, t_lo + 1);
+        store_stage(stg_a, t_lo + 1 < t_hi);
+        if (t_lo + 2 < t_hi) load_stage(stg_a, t_lo + 2);
+    }
+    for (int t = t_lo; t < t_hi; t += 2) {
+        process_tile(t, stg_b, stg_a);
+        if (t + 1 < t_hi) process_tile(t + 1, stg_a, stg_b);
     }
 #ifdef PLX_MLA_TIMING
     if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
@@ -359,14 +417,14 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
     // ---- row sums over the four waves; write the split partial or the output -----------------
     dsum1 = rows_sum(dsum1);
     dsum2 = rows_sum(dsum2);
-    if (scorer && g == 0) {
+    if (g == 0) {
         dex[(w * 16 + c) * 2] = dsum1;
         dex[(w * 16 + c) * 2 + 1] = dsum2;
     }
     __syncthreads();
     float d1 = 0.f, d2 = 0.f;
 #pragma unroll
-    for (int ww = 0; ww < kMlaScoreWaves; ++ww) {
+    for (int ww = 0; ww < 4; ++ww) {
         d1 += dex[(ww * 16 + c) * 2];
         d2 += dex[(ww * 16 + c) * 2 + 1];
     }
@@ -404,7 +462,7 @@ extern "C" int parallax_debug_read_mla_stamps(void *host_dst, size_t bytes) {
 
 hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream) {
     const dim3 grid(p.S, (p.Hq + 15) / 16, p.B);
-    hipLaunchKernelGGL(decode_mla_kernel<64>, grid, dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(decode_mla_kernel, grid, dim3(256), 0, stream, p);
     if (!p.direct_out) {
         DecodeParams c{};
         c.ws = p.ws, c.o = p.o, c.B = p.B, c.Hq = p.Hq, c.Tq = 1, c.S = p.S, c.d = kMlaDC;

@@ -303,12 +303,14 @@ size_t parallax_decode_mla_workspace_bytes(int32_t B, int32_t Hq) {
 int32_t parallax_decode_mla_num_splits(int32_t B, int32_t Hq, int32_t Lmax, int32_t num_cus) {
     if (B <= 0 || Hq <= 0 || Lmax <= 0) return 1;
     if (num_cus <= 0) num_cus = query_num_cus();
-    // One workgroup per compute unit is resident (its two tile buffers fill the LDS): aim at two
-    // rounds of workgroups so that the tail of a ragged batch stays short, at least 256 keys (four 64-key
-    // stretches) per split, and never more than 4096 keys in one split.
+    // One workgroup per compute unit is resident (tile, q / rho fragments and the two register
+    // stages fill its LDS and registers) and a workgroup pays about 10 us to start and finish:
+    // aim at ONE round of workgroups (measured: B = 64, L = 16384 takes 236 us with 4 splits, 261
+    // with 8), at least 256 keys per split, and at most 4096 keys per split so that the tail of a
+    // long or ragged batch stays short.
     const int64_t pairs = (int64_t)B * ((Hq + 15) / 16);
     const int64_t n_tiles = ((int64_t)Lmax + 63) / 64;
-    int64_t s = (2LL * num_cus + pairs - 1) / pairs;
+    int64_t s = ((int64_t)num_cus + pairs - 1) / pairs;
     const int64_t by_len = ((int64_t)Lmax + 4095) / 4096;
     if (s < by_len) s = by_len;
     const int64_t cap = n_tiles >= 8 ? n_tiles / 4 : 1;

@@ -68,3 +68,27 @@ def test_late_reads_chained_mfmas_and_writes_pass():
     # other registers; an MFMA the compiler knows about is its own business
     assert check(ASM_MFMA + "\tv_add_f32 v1, v50, v2\n\tv_mov_b32_e32 v60, v33\n") == []
     assert check(OTHER_MFMA + "\tv_accvgpr_read_b32 v1, a0\n") == []
+
+
+def test_foreign_use_of_an_assembly_loaded_register_is_reported():
+    """Registers written by inline-assembly global loads may only be touched by inline assembly
+    until the last inline-assembly LDS store: a compiler-made copy in between is reported."""
+    ok = """
+kernel_a:
+	;;#ASMSTART
+	global_load_dwordx4 a[0:3], v1, s[2:3]
+	;;#ASMEND
+	v_add_u32_e32 v9, v8, v7
+	;;#ASMSTART
+	s_waitcnt vmcnt(0)
+	;;#ASMEND
+	;;#ASMSTART
+	ds_write_b128 v5, a[0:3]
+	;;#ASMEND
+	v_accvgpr_read_b32 v2, a1
+	s_endpgm
+"""
+    assert asm_check.find_foreign_uses_of_asm_loaded_registers(ok) == []
+    bad = ok.replace("v_add_u32_e32 v9, v8, v7", "v_accvgpr_read_b32 v9, a2")
+    found = asm_check.find_foreign_uses_of_asm_loaded_registers(bad)
+    assert len(found) == 1 and "a2" in found[0].replace("('a', 2)", "a2")

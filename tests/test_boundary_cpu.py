@@ -330,7 +330,7 @@ def test_decode_mla_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_WORKSPACE
     # the split heuristic is host arithmetic with an explicit compute-unit count
     f = binding.parallax_decode_mla_num_splits
-    assert f(64, 16, 16384, 256) == 8 and f(1, 16, 16384, 256) == 64 and f(1, 16, 100, 256) == 1
+    assert f(64, 16, 16384, 256) == 4 and f(1, 16, 16384, 256) == 64 and f(1, 16, 100, 256) == 1
     assert f(512, 128, 4096, 256) == 1
     for (B, Hq, L) in [(1, 1, 1), (3, 17, 5000), (128, 16, 131072), (2, 128, 70000)]:
         assert 1 <= f(B, Hq, L, 256) <= binding.PLX_MAX_SPLITS
