@@ -138,3 +138,46 @@ def test_serving_shape_sampled(plx, synth, mla):
     seqs = sorted({int(lens.argmin()), int(lens.argmax()), 7, 19})
     ref = _ref(mla, x, seqs)
     assert rel_l2(host(out)[seqs], ref) <= BF16_REL_L2
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_shapes(plx, synth, mla, case):
+    rng = np.random.default_rng(4900 + case)
+    B = int(rng.integers(1, 5))
+    Hq = int(rng.choice([1, 3, 8, 16, 24, 33, 64]))
+    L = int(rng.choice([1, 31, 64, 100, 255, 256, 257, 600, 1500, 4097]))
+    S = int(rng.choice([0, 0, 1, 2, 7, 19]))
+    x = synth.mla_decode_inputs(B, Hq, L, seed=4950 + case, device=DEV, ragged=bool(rng.integers(0, 2)),
+                                r_scale=float(rng.choice([1.0, 0.2])))
+    if rng.integers(0, 2):   # a cache with padded rows and spare tokens
+        wide = torch.zeros(B, L + 5, 576 + 64, dtype=torch.bfloat16, device=DEV)
+        wide[:, :L, :576] = x["ckv"]
+        x["ckv"] = wide[:, :L, :576]
+    _check(plx, mla, x, num_splits=S)
+
+
+def test_hip_graph_replays_match_eager(plx, synth):
+    """The two launches of a split step captured once and replayed with new cache contents."""
+    import ctypes
+
+    x = synth.mla_decode_inputs(4, 16, 3000, seed=4990, device=DEV, ragged=True)
+    out = torch.empty(4, 16, 512, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(plx.parallax_decode_mla_workspace_bytes(4, 16) // 4, dtype=torch.float32, device=DEV)
+    a = plx.decode_mla_args(x["q"], x["r"], x["ckv"], out, x["scale"], x["seq_lens"], 6, ws)
+    lib = plx.load_library()
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        assert lib.parallax_decode_mla(ctypes.byref(a), int(torch.cuda.current_stream().cuda_stream)) == 0
+    torch.cuda.current_stream().wait_stream(side)
+    gen = torch.Generator(device=DEV).manual_seed(4991)
+    for rep in range(3):
+        if rep:
+            x["ckv"].copy_(torch.randn(x["ckv"].shape, generator=gen, device=DEV))
+            x["q"].copy_(torch.randn(x["q"].shape, generator=gen, device=DEV))
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"], seq_lens=x["seq_lens"], num_splits=6)
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
