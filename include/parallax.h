@@ -219,7 +219,7 @@ plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
  * d_latent = 512 and d_rope = 64.
  *   q, r       [B, Hq, 576] contiguous (already in the latent space), 16-byte aligned
  *   ckv        [B, Lmax, 576]: element strides ckv_stride_b / ckv_stride_l (multiples of 8,
- *              ckv_stride_l >= 576), last dimension contiguous
+ *              576 <= ckv_stride_l <= 2^23), last dimension contiguous
  *   o          [B, Hq, 512] contiguous (the value up-projection is the caller's)
  *   seq_lens   int32 [B] on the device or NULL (= Lmax); 0 gives a zero row
  *   num_splits 0 = heuristic, else 1 .. PLX_MAX_SPLITS

@@ -329,7 +329,8 @@ plx_status parallax_decode_mla(const plx_decode_mla_args *a, void *hip_stream) {
     if (!(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
     if (!aligned16(a->q) || !aligned16(a->r) || !aligned16(a->ckv) || !aligned16(a->o)) return PLX_ERR_ALIGN;
     if (a->seq_lens && (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u)) return PLX_ERR_ALIGN;
-    if (a->ckv_stride_b < 0 || a->ckv_stride_l < 576) return PLX_ERR_SHAPE;
+    // (a 64-token tile is addressed with 32-bit byte offsets)
+    if (a->ckv_stride_b < 0 || a->ckv_stride_l < 576 || a->ckv_stride_l > (1 << 23)) return PLX_ERR_SHAPE;
     if (!stride_aligned(a->ckv_stride_b, a->dtype) || !stride_aligned(a->ckv_stride_l, a->dtype))
         return PLX_ERR_ALIGN;
     if (a->num_splits < 0 || a->num_splits > PLX_MAX_SPLITS) return PLX_ERR_SPLITS;

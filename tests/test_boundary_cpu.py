@@ -318,6 +318,8 @@ def test_decode_mla_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_SHAPE
     a = good(); a.ckv_stride_l = 580
     assert call(a) == binding.PLX_ERR_ALIGN
+    a = good(); a.ckv_stride_l = (1 << 23) + 8
+    assert call(a) == binding.PLX_ERR_SHAPE
     a = good(); a.q = 0x1004
     assert call(a) == binding.PLX_ERR_ALIGN
     a = good(); a.scale = -1.0
