@@ -256,7 +256,8 @@ plx_status parallax_decode_mla(const plx_decode_mla_args *args, void *hip_stream
  * MFMA kernels) or fp32 (d <= 256, plain untuned path, vbar in fp32 too, dense layout only). causal, Tkv and window as in the forward (window > 0 needs causal != 0; the row cache
  * must come from a forward call with the same window).
  *   workspace  fp32 scratch, >= parallax_prefill_backward_workspace_bytes(B, Hq, T) = 16 bytes
- *              per query row (lse, ubar, tau = dO.o, beta = dO.vbar)
+ *              per query row (four row scalars built from lse, ubar, tau = dO.o, beta = dO.vbar;
+ *              contents are private to the library)
  * Three kernels are enqueued (row scalars; dQ, dR; dK, dV); nothing is accumulated with atomics,
  * so results are deterministic and the outputs need no zeroing.
  */

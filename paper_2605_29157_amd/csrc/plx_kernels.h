@@ -64,7 +64,7 @@ struct PrefillBwdParams {
     const void *q, *r, *k, *v, *d_o;
     const void *o, *vbar;    // forward output and cached softmax value mean
     const float *row_stats;  // [B, Hq, T, 2] from the forward: (log-sum-exp in the exp2 domain, ubar)
-    float *row_cache;        // workspace [B, Hq, T, 4]: (lse, ubar, tau, beta)
+    float *row_cache;        // workspace [B, Hq, T, 4]: row scalars (lse, ubar, tau, beta or combinations of them)
     void *dq, *dr, *dk, *dv;
     int32_t B, Hq, Hkv, G, T, Tk, d;
     float scale;

@@ -8,7 +8,9 @@
 //     dV_j = sum_i p_ij (1 + ubar_i - u_ij) dO_i
 // As the appendix says, the two reduction directions make two passes:
 //   * rows prepare: one wave per query row folds (lse, ubar) of the forward's row cache and
-//     tau, beta into one float4 per row;
+//     tau, beta into one float4 per row, (lse, 1 + ubar, beta - tau, beta): with delta = a - beta
+//     and c = (1 + ubar) - u the bracket of g1 is delta * c + (beta - tau) and w = p * c, two
+//     vector instructions per pair less than the textbook order;
 //   * row pass (dQ, dR): a workgroup owns 128 query rows of one head (32 per wave), keeps their
 //     Q, R, dO fragments in registers and streams K/V tiles of 64 keys. Scores are produced
 //     transposed, as in the forward: S1^T = K Q^T, S2^T = K R^T, A^T = V dO^T, so a lane owns one
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(256) void bwd_rows_prepare_kernel(PrefillBwdParams 
         beta += __shfl_xor(beta, off, 64);
     }
     if (lane == 0) {
-        const f32x4 out = {p.row_stats[2 * row], p.row_stats[2 * row + 1], tau, beta};
+        const f32x4 out = {p.row_stats[2 * row], 1.f + p.row_stats[2 * row + 1], beta - tau, beta};
         ((f32x4 *)p.row_cache)[row] = out;
     }
 }
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
         }
     }
     const f32x4 rc = ((const f32x4 *)p.row_cache)[((int64_t)b * p.Hq + hq) * T + ld_row];
-    const float neg_lse = -rc[0], ubar = rc[1], tau = rc[2], beta = rc[3];
+    const float neg_lse = -rc[0], one_ubar = rc[1], kappa = rc[2], beta = rc[3];  // (lse, 1 + ubar, beta - tau, beta)
     const float scale_log2 = p.scale * kLog2e;
     const BwdLaneOffsets<D> lo(lane);
 
@@ -269,13 +271,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
             const int first = slot0 + u * (n_slots - 6 - slot0) / 7;
             if (slot == first) {
                 s1[r] = fmaf(s1[r], scale_log2, neg_lse);
-                dl[u] = aa[r] - beta;     // delta
-                s2[r] = ubar - s2[r];     // ubar - u
-                aa[r] = aa[r] - tau;
+                dl[u] = aa[r] - beta;        // delta
+                s2[r] = one_ubar - s2[r];    // 1 + ubar - u
             }
             if (slot == first + 1) {
-                s1[r] = fast_exp2(s1[r]);            // p
-                aa[r] = fmaf(s2[r], dl[u], aa[r]);   // a - tau + (ubar - u) delta
+                s1[r] = fast_exp2(s1[r]);             // p
+                aa[r] = fmaf(s2[r], dl[u], kappa);    // a - tau + (ubar - u) delta
             }
             if constexpr (MASKED)
                 if (slot == first + 2) {
@@ -616,22 +617,21 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
             // (the row scalars are read two slots ahead of their use: an LDS read takes longer
             // than one MFMA slot)
             const int first = slot0 + u * (n_slots - 8 - slot0) / 7;
-            if (slot == first) rcv[u] = rows[8 * (r >> 2) + (r & 3)];  // (lse, ubar, tau, beta)
+            if (slot == first) rcv[u] = rows[8 * (r >> 2) + (r & 3)];  // (lse, 1 + ubar, beta - tau, beta)
             if (slot == first + 2) {
                 s1[r] = fmaf(s1[r], scale_log2, -rcv[u][0]);
                 dl[u] = aa[r] - rcv[u][3];       // delta
-                s2[r] = rcv[u][1] - s2[r];       // ubar - u
-                aa[r] = aa[r] - rcv[u][2];
+                s2[r] = rcv[u][1] - s2[r];       // 1 + ubar - u
             }
             if (slot == first + 3) {
-                s1[r] = fast_exp2(s1[r]);           // p
-                aa[r] = fmaf(s2[r], dl[u], aa[r]);  // a - tau + (ubar - u) delta
+                s1[r] = fast_exp2(s1[r]);                // p
+                aa[r] = fmaf(s2[r], dl[u], rcv[u][2]);   // a - tau + (ubar - u) delta
             }
             if constexpr (MASKED)
                 if (slot == first + 4)
                     s1[r] = ((unsigned)(8 * (r >> 2) + (r & 3) + neg_lo) < span) ? s1[r] : 0.f;
             if (slot == first + 5) {
-                const float wgt = fmaf(s1[r], s2[r], s1[r]);  // p (1 + ubar - u)
+                const float wgt = s1[r] * s2[r];  // p (1 + ubar - u)
                 if (u % 2 == 0)
                     wodd = wgt;
                 else
