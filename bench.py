@@ -745,6 +745,22 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
                    "num_splits": plx.parallax_decode_mla_num_splits(B, Hq, L), "us": round(us, 1),
                    "GBps": round(nbytes / us / 1e3, 1), "frac_of_8TBps": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
                    "TFLOPs": round(B * Hq * L * 2 * (2 * 576 + 2 * 512) / us / 1e6, 1)})
+        if (B, L) == (64, 16384):  # the same tokens behind a block table, pages of 256 tokens in random order
+            pools = [synth.mla_paged_cache(x, 256, seed=1013 + i) for i, x in enumerate(xs)]
+            p_args = [plx.decode_mla_args(x["q"], x["r"], pool, mo, x["scale"], None, 0, mws, block_table=table,
+                                          max_len=L) for x, (pool, table) in zip(xs, pools)]
+
+            def pstep():
+                st = lib.parallax_decode_mla(ctypes.byref(p_args[mc[0] % nset]), sptr)
+                mc[0] += 1
+                if st != 0:
+                    raise plx.ParallaxError(st, "paged mla bench")
+
+            us = _time_events(torch, pstep, 5, 50)
+            ml.append({"workload": "MLA-style decode B=%d Hq=%d L=%d, paged cache (256 tokens per page)" % (B, Hq, L),
+                       "us": round(us, 1), "GBps": round(nbytes / us / 1e3, 1),
+                       "frac_of_8TBps": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
+            del pools, p_args
         del xs, m_args, mo, mws
     extra["mla_decode"] = ml
     return extra

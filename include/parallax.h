@@ -224,6 +224,11 @@ plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
  *   seq_lens   int32 [B] on the device or NULL (= Lmax); 0 gives a zero row
  *   num_splits 0 = heuristic, else 1 .. PLX_MAX_SPLITS
  *   workspace  fp32 scratch for num_splits > 1, >= parallax_decode_mla_workspace_bytes(B, Hq)
+ *   block_table  NULL, or int32 [B, block_table_stride] on the device: the cache is then a pool
+ *              ckv [num_pages, page_size, 576] (ckv_stride_b = page stride) and token j of
+ *              sequence b is row j % page_size of page block_table[b][j / page_size]; entries
+ *              are clamped to existing pages. block_table_stride * page_size >= Lmax. Any page
+ *              size works; multiples of 64 are fetched page-wise, others row by row (slower).
  * Validates on the host, enqueues one or two kernels on hip_stream, does not synchronise.
  */
 typedef struct {
@@ -239,6 +244,8 @@ typedef struct {
     plx_dtype dtype;
     void *workspace;
     size_t workspace_bytes;
+    const int32_t *block_table;
+    int32_t page_size, num_pages, block_table_stride;
 } plx_decode_mla_args;
 
 size_t parallax_decode_mla_workspace_bytes(int32_t B, int32_t Hq);

@@ -106,6 +106,8 @@ class plx_decode_mla_args(ctypes.Structure):
         ("ckv_stride_b", ctypes.c_int64), ("ckv_stride_l", ctypes.c_int64),
         ("scale", ctypes.c_float), ("dtype", ctypes.c_int),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("block_table", ctypes.c_void_p),
+        ("page_size", ctypes.c_int32), ("num_pages", ctypes.c_int32), ("block_table_stride", ctypes.c_int32),
     ]
 
 
@@ -484,9 +486,11 @@ def parallax_decode_mla_num_splits(B, Hq, Lmax, num_cus=0) -> int:
     return int(load_library().parallax_decode_mla_num_splits(B, Hq, Lmax, num_cus))
 
 
-def decode_mla_args(q, r, ckv, out, scale, seq_lens=None, num_splits=0, workspace=None, d_latent=512):
+def decode_mla_args(q, r, ckv, out, scale, seq_lens=None, num_splits=0, workspace=None, d_latent=512,
+                    block_table=None, max_len=None):
     """Fill a plx_decode_mla_args: q, r [B, Hq, dk] and out [B, Hq, d_latent] contiguous, ckv
-    [B, L, dk] with any batch / token strides."""
+    [B, L, dk] with any batch / token strides -- or, with an int32 block_table [B, pages], a page
+    pool [num_pages, page_size, dk] (max_len = capacity in tokens, default pages * page_size)."""
     for t in (q, r, out):
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError("parallax_decode_mla needs contiguous device tensors for q, r and out")
@@ -496,6 +500,12 @@ def decode_mla_args(q, r, ckv, out, scale, seq_lens=None, num_splits=0, workspac
     a.q, a.r, a.ckv, a.o = q.data_ptr(), r.data_ptr(), ckv.data_ptr(), out.data_ptr()
     a.seq_lens = seq_lens.data_ptr() if seq_lens is not None else None
     a.B, a.Hq, a.Lmax = q.shape[0], q.shape[1], ckv.shape[1]
+    if block_table is not None:
+        if block_table.dtype != torch.int32 or not block_table.is_cuda or block_table.stride(-1) != 1:
+            raise ValueError("block_table must be a device int32 tensor with a contiguous last dimension")
+        a.block_table = block_table.data_ptr()
+        a.page_size, a.num_pages, a.block_table_stride = ckv.shape[1], ckv.shape[0], block_table.stride(0)
+        a.Lmax = int(max_len) if max_len is not None else block_table.shape[1] * ckv.shape[1]
     a.d_latent, a.d_rope = d_latent, q.shape[2] - d_latent
     a.num_splits = int(num_splits)
     a.ckv_stride_b, a.ckv_stride_l = ckv.stride(0), ckv.stride(1)
@@ -508,7 +518,7 @@ def decode_mla_args(q, r, ckv, out, scale, seq_lens=None, num_splits=0, workspac
 
 
 def parallax_decode_mla(q, r, ckv, scale, seq_lens=None, num_splits=0, out=None, workspace=None,
-                        stream=None, d_latent=512):
+                        stream=None, d_latent=512, block_table=None, max_len=None):
     """Parallax decode over an MLA-style latent cache: key = the whole cached row, value = its
     first d_latent numbers, shared by all heads."""
     if out is None:
@@ -516,7 +526,7 @@ def parallax_decode_mla(q, r, ckv, scale, seq_lens=None, num_splits=0, out=None,
     if workspace is None and num_splits != 1:
         workspace = torch.empty(parallax_decode_mla_workspace_bytes(q.shape[0], q.shape[1]) // 4,
                                 dtype=torch.float32, device=q.device)
-    a = decode_mla_args(q, r, ckv, out, scale, seq_lens, num_splits, workspace, d_latent)
+    a = decode_mla_args(q, r, ckv, out, scale, seq_lens, num_splits, workspace, d_latent, block_table, max_len)
     st = load_library().parallax_decode_mla(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_decode_mla")

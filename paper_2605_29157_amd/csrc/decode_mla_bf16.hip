@@ -77,6 +77,10 @@ __device__ unsigned long long plx_mla_stamps[8];
 #define MLA_STAMP(slot) ((void)0)
 #endif
 
+// PAGED: the cache is a pool of pages behind a block table. A tile that lies inside one page
+// (page size a multiple of 64) is fetched like a tile of a contiguous cache from its page;
+// otherwise every lane looks up the page of its row.
+template <bool PAGED>
 __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
     // [tile] [q fragments: k-step x lane] [rho fragments] [P1 | P2 as B operands] [tile maxima] [row sums]
     __shared__ u32x4 lds[kMlaTileChunks + 2 * kMlaKSteps * 64 + 128 * kMlaPvSteps + 16 + 32];
@@ -129,8 +133,31 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
     // Either way one per-lane offset per load is kept: the LDS slot (dense) or the global byte
     // offset (strided). A partial last tile re-reads the sequence's last row for the rows past
     // its end (finite data, masked below); its places are recomputed, not kept.
-    const __bf16 *cbase = (const __bf16 *)p.ckv + (int64_t)b * p.csb;
+    const __bf16 *cbase = (const __bf16 *)p.ckv + (PAGED ? 0 : (int64_t)b * p.csb);
     const bool dense = p.csl == kMlaDK;  // workgroup-uniform
+    // (the table is read through the constant address space where the index is uniform: scalar loads)
+    using const_i32 = const __attribute__((address_space(4))) int32_t;
+    const int32_t *table = PAGED ? p.block_table + (int64_t)b * p.table_stride : nullptr;
+    const_i32 *table_c = (const_i32 *)(uintptr_t)table;
+    const bool tiles_in_pages = !PAGED || p.page_size % kMlaTileKeys == 0;  // workgroup-uniform
+    auto page_of = [&](int32_t entry) { return (int64_t)min(max(entry, 0), p.num_pages - 1); };
+    // first byte of tile t when it lies in one piece
+    auto tile_start = [&](int t) __attribute__((always_inline)) -> const char * {
+        if constexpr (PAGED) {
+            const int key = t * kMlaTileKeys;
+            return (const char *)(cbase + page_of(table_c[key / p.page_size]) * p.csb +
+                                  (int64_t)(key % p.page_size) * p.csl);
+        } else {
+            return (const char *)cbase + (int64_t)t * (kMlaTileKeys * 2) * p.csl;
+        }
+    };
+    // row `key` of the sequence (per lane)
+    auto row_start = [&](int key) __attribute__((always_inline)) -> const __bf16 * {
+        if constexpr (PAGED)
+            return cbase + page_of(table[key / p.page_size]) * p.csb + (int64_t)(key % p.page_size) * p.csl;
+        else
+            return cbase + (int64_t)key * p.csl;
+    };
     auto slot_place = [&](int i, int &row, int &elem) __attribute__((always_inline)) {  // strided: load i of this wave
         const int idx = w * kMlaLoadsPerWave + i;  // wave-uniform
         if (idx < kMlaLatBlocks * kRowGroups) {
@@ -160,7 +187,6 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
             off[i] = (uint32_t)(row * (int)p.csl + elem) * 2u;
         }
     }
-    const int64_t tile_bytes = (int64_t)kMlaTileKeys * 2 * p.csl;
     const uint32_t wave_lin = (uint32_t)(w * kMlaLoadsPerWave * 64 + lane) * 16u;  // this lane's first chunk, both sides
     // The stage loads, the wait for them and the stage -> LDS stores are assembly statements:
     // left to the compiler, the wait in front of a stage's stores also covers the loads of the
@@ -175,8 +201,8 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
     u32x4 stg_a[kMlaLoadsPerWave], stg_b[kMlaLoadsPerWave];  // tiles t_lo + even / + odd
     auto load_stage = [&](u32x4 (&stg)[kMlaLoadsPerWave], int t) __attribute__((always_inline)) {
         const int tk0 = t * kMlaTileKeys;
-        const char *tile_base = (const char *)cbase + t * tile_bytes;
-        if (tk0 + kMlaTileKeys <= Lb) {  // workgroup-uniform
+        if (tiles_in_pages && tk0 + kMlaTileKeys <= Lb) {  // workgroup-uniform
+            const char *tile_base = tile_start(t);
             if (dense) {
 #pragma unroll
                 for (int i = 0; i < kMlaLoadsPerWave; ++i)
@@ -196,8 +222,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
                 } else {
                     slot_place(i, row, elem);
                 }
-                const int key = min(tk0 + row, Lb - 1);
-                const __bf16 *src = cbase + (int64_t)key * p.csl + elem;
+                const __bf16 *src = row_start(min(tk0 + row, Lb - 1)) + elem;
                 asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(stg[i]) : "v"(src));
             }
         }
@@ -275,8 +300,8 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         MLA_STAMP(0);
         // tile t + 2 sets off now: piece by piece between the matrix instructions if it is complete
         const bool refill = t > t_lo && t + 2 < t_hi;  // (the prologue has requested t_lo + 1 and t_lo + 2)
-        const bool spread = refill && (t + 3) * kMlaTileKeys <= Lb;  // workgroup-uniform
-        const char *fill_base = (const char *)cbase + (t + 2) * tile_bytes;
+        const bool spread = refill && tiles_in_pages && (t + 3) * kMlaTileKeys <= Lb;  // workgroup-uniform
+        const char *fill_base = spread ? tile_start(t + 2) : nullptr;
         if (refill && !spread) load_stage(fill, t + 2);
 
         // ---- S1^T = C q^T, S2^T = C rho^T for the keys 16 w .. 16 w + 15 of the tile ---------
@@ -462,7 +487,10 @@ extern "C" int parallax_debug_read_mla_stamps(void *host_dst, size_t bytes) {
 
 hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream) {
     const dim3 grid(p.S, (p.Hq + 15) / 16, p.B);
-    hipLaunchKernelGGL(decode_mla_kernel, grid, dim3(256), 0, stream, p);
+    if (p.block_table)
+        hipLaunchKernelGGL(decode_mla_kernel<true>, grid, dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL(decode_mla_kernel<false>, grid, dim3(256), 0, stream, p);
     if (!p.direct_out) {
         DecodeParams c{};
         c.ws = p.ws, c.o = p.o, c.B = p.B, c.Hq = p.Hq, c.Tq = 1, c.S = p.S, c.d = kMlaDC;

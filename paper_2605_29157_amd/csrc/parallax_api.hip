@@ -334,12 +334,21 @@ plx_status parallax_decode_mla(const plx_decode_mla_args *a, void *hip_stream) {
     if (!stride_aligned(a->ckv_stride_b, a->dtype) || !stride_aligned(a->ckv_stride_l, a->dtype))
         return PLX_ERR_ALIGN;
     if (a->num_splits < 0 || a->num_splits > PLX_MAX_SPLITS) return PLX_ERR_SPLITS;
+    if (a->block_table) {
+        if (reinterpret_cast<uintptr_t>(a->block_table) & 3u) return PLX_ERR_ALIGN;
+        if (a->page_size < 1 || a->num_pages < 1 || a->block_table_stride < 1) return PLX_ERR_SHAPE;
+        if ((int64_t)a->block_table_stride * a->page_size < a->Lmax) return PLX_ERR_SHAPE;
+    }
 
     plx::MlaDecodeParams p{};
     p.q = a->q, p.r = a->r, p.ckv = a->ckv, p.o = a->o, p.seq_lens = a->seq_lens;
     p.B = a->B, p.Hq = a->Hq, p.Lmax = a->Lmax;
     p.csb = a->ckv_stride_b, p.csl = a->ckv_stride_l;
     p.scale = a->scale;
+    if (a->block_table) {
+        p.block_table = a->block_table;
+        p.page_size = a->page_size, p.table_stride = a->block_table_stride, p.num_pages = a->num_pages;
+    }
     int32_t S = a->num_splits;
     if (S == 0) S = parallax_decode_mla_num_splits(a->B, a->Hq, a->Lmax, 0);
     p.S = S;

@@ -54,9 +54,13 @@ struct MlaDecodeParams {
     const int32_t *seq_lens;
     float *ws;  // split partials: [B][Hq][S] records of (2 * 512 + 4) floats
     int32_t B, Hq, Lmax, S;
-    int64_t csb, csl;  // element strides of the cache: batch, token
+    int64_t csb, csl;  // element strides of the cache: batch (page, when paged), token
     float scale;
     int32_t direct_out;  // 1: S == 1, the kernel writes o itself
+    // paged cache: token j of sequence b is row j % page_size of page
+    // block_table[b * table_stride + j / page_size] of the pool
+    const int32_t *block_table;
+    int32_t page_size, table_stride, num_pages;
 };
 
 // Backward of the prefill forward: q-like tensors [B, Hq, T, d], k-like [B, Hkv, Tk, d].

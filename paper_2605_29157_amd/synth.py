@@ -101,3 +101,20 @@ def mla_decode_inputs(B, Hq, L, seed, d_latent=512, d_rope=64, dtype=torch.bfloa
     if ragged:
         out["seq_lens"] = ragged_lengths(B, L, seed).to(device)
     return out
+
+
+def mla_paged_cache(x, page_size, seed, spare_pages=3):
+    """Scatter the contiguous latent cache x["ckv"] [B, L, dk] into a page pool
+    [num_pages, page_size, dk] in a seeded random page order (plus a few unused pages) and return
+    (pool, block_table [B, pages per sequence] int32). Layout only."""
+    c = x["ckv"]
+    B, L, dk = c.shape
+    per_seq = (L + page_size - 1) // page_size
+    n_pages = B * per_seq + spare_pages
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    order = torch.randperm(n_pages, generator=g)[: B * per_seq].reshape(B, per_seq)
+    pad = per_seq * page_size - L
+    cp = torch.nn.functional.pad(c, (0, 0, 0, pad)).reshape(B * per_seq, page_size, dk)
+    pool = torch.zeros(n_pages, page_size, dk, dtype=c.dtype, device=c.device)
+    pool[order.reshape(-1).to(c.device)] = cp
+    return pool, order.to(torch.int32).to(c.device)

@@ -330,6 +330,12 @@ def test_decode_mla_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_WORKSPACE
     a = good(); a.workspace_bytes = 100
     assert call(a) == binding.PLX_ERR_WORKSPACE
+    a = good(); a.block_table, a.page_size, a.num_pages, a.block_table_stride = 0x3000, 64, 10, 8   # 512 < Lmax
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.block_table, a.page_size, a.num_pages, a.block_table_stride = 0x3000, 0, 10, 8
+    assert call(a) == binding.PLX_ERR_SHAPE
+    a = good(); a.block_table, a.page_size, a.num_pages, a.block_table_stride = 0x3002, 64, 100, 64
+    assert call(a) == binding.PLX_ERR_ALIGN
     # the split heuristic is host arithmetic with an explicit compute-unit count
     f = binding.parallax_decode_mla_num_splits
     assert f(64, 16, 16384, 256) == 4 and f(1, 16, 16384, 256) == 64 and f(1, 16, 100, 256) == 1

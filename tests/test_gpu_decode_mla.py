@@ -181,3 +181,30 @@ def test_hip_graph_replays_match_eager(plx, synth):
         eager = plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"], seq_lens=x["seq_lens"], num_splits=6)
         torch.cuda.synchronize()
         assert torch.equal(out, eager)
+
+
+@pytest.mark.parametrize("page_size", [1, 16, 48, 64, 100, 128, 256])
+def test_paged_cache_matches_contiguous(plx, synth, mla, page_size):
+    """The same tokens behind a block table (random page order, spare pages, a ragged batch):
+    the same bits as the contiguous cache, for page sizes fetched page-wise (multiples of 64)
+    and row by row (the others)."""
+    x = synth.mla_decode_inputs(3, 20, 700, seed=5000 + page_size, device=DEV, ragged=True)
+    x["seq_lens"][1] = 700
+    want = _check(plx, mla, x, num_splits=3)
+    pool, table = synth.mla_paged_cache(x, page_size, seed=5001)
+    for S in (3, 1):
+        got = plx.parallax_decode_mla(x["q"], x["r"], pool, x["scale"], seq_lens=x["seq_lens"], num_splits=S,
+                                      block_table=table, max_len=700)
+        torch.cuda.synchronize()
+        if S == 3:
+            np.testing.assert_array_equal(host(got), want)
+        else:
+            assert rel_l2(host(got), _ref(mla, x)) <= BF16_REL_L2
+    # a pool with padded rows and a wider table than needed
+    wide = torch.zeros(pool.shape[0], page_size, 640, dtype=torch.bfloat16, device=DEV)
+    wide[..., :576] = pool
+    table2 = torch.cat([table, torch.full_like(table[:, :2], 10 ** 6)], dim=1).contiguous()   # out-of-range entries: clamped, never read
+    got = plx.parallax_decode_mla(x["q"], x["r"], wide[..., :576], x["scale"], seq_lens=x["seq_lens"], num_splits=3,
+                                  block_table=table2, max_len=700)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(got), want)
