@@ -75,8 +75,10 @@ typedef enum {
  * Several query rows (Tq > 1; speculative rows or a short chunk, the causal set of Sec. 2.1 at
  * absolute positions): q, r, o are [B, Hq, Tq, d] and the rows are the LAST Tq positions of the
  * sequence, so row t sees key j iff j < L_b - (Tq - 1 - t). All rows of all heads of a GQA group
- * ride in one MFMA operand and share every K/V fetch: bf16 needs (Hq / Hkv) * Tq <= 16. The
- * workspace then needs Tq times parallax_decode_workspace_bytes(...).
+ * ride in one MFMA operand and share every K/V fetch as long as (Hq / Hkv) * Tq <= 16; with more
+ * columns the bf16 path takes one launch per 16 / (Hq / Hkv) rows (each reads the cache again),
+ * (bf16 GQA groups hold at most 8 heads). The workspace then needs Tq times
+ * parallax_decode_workspace_bytes(...).
  *
  * Paged cache (block_table != NULL; the paper's Sec. 5 remark that cache layouts carry over --
  * same loop, different tile iterator): k, v point to a pool of pages

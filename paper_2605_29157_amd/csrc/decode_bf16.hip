@@ -165,11 +165,14 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     const int G = p.G, S = p.S;
     // With Tq query rows per sequence (the last Tq positions: speculative rows, a short chunk)
     // column c = t * G + head: all rows of all heads of the group share every K/V fetch.
-    const int Tq = p.Tq, GC = G * Tq;
+    // A launch may cover only the rows [row0, row0 + Tq) of Tq_all (more than 16 columns take
+    // several launches): the rows behind them shorten what this launch sees of the sequence.
+    const int Tq_all = p.Tq, row0 = p.rows ? p.row0 : 0;
+    const int Tq = p.rows ? p.rows : Tq_all, GC = G * Tq;
     const int col_t = c / G, col_h = c - col_t * G;
 
     int Lb = p.seq_lens ? p.seq_lens[b] : p.Lmax;
-    Lb = min(max(Lb, 0), p.Lmax);
+    Lb = max(min(max(Lb, 0), p.Lmax) - (Tq_all - row0 - Tq), 0);
     const int n_bt = (Lb + kDecodeBlockKeys - 1) / kDecodeBlockKeys;
     // sliding window: a row at position pos sees the keys pos - window + 1 .. pos, so the block
     // tiles before the first key of the earliest row (position Lb - Tq) are never read and the
@@ -184,7 +187,7 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     u32x4 qf[KSTEPS], rf[KSTEPS];
     {
         const int64_t row =
-            (((int64_t)b * p.Hq + (int64_t)hk * G + (live ? col_h : 0)) * Tq + (live ? col_t : 0)) * D;
+            (((int64_t)b * p.Hq + (int64_t)hk * G + (live ? col_h : 0)) * Tq_all + row0 + (live ? col_t : 0)) * D;
         const __bf16 *qrow = (const __bf16 *)p.q + row;
         const __bf16 *rrow = (const __bf16 *)p.r + row;
 #pragma unroll
@@ -403,7 +406,7 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
         }
         const int ot = hh / G, oh = hh - ot * G;
         // output / workspace row of (batch, query head, query row)
-        const int64_t hq = ((int64_t)b * p.Hq + (int64_t)hk * G + oh) * Tq + ot;
+        const int64_t hq = ((int64_t)b * p.Hq + (int64_t)hk * G + oh) * Tq_all + row0 + ot;
         if (p.direct_out) {
             float out = 0.f;  // empty key set: zeros
             if (d1 > 0.f) {
@@ -457,7 +460,7 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
             MergeScratch<D> *sm = reinterpret_cast<MergeScratch<D> *>(lds);
             auto row_of = [&](int cc) {  // output / workspace row of column cc = (t, head)
                 const int ot = cc / G, oh = cc - ot * G;
-                return ((int64_t)b * p.Hq + (int64_t)hk * G + oh) * Tq + ot;
+                return ((int64_t)b * p.Hq + (int64_t)hk * G + oh) * Tq_all + row0 + ot;
             };
             constexpr int64_t REC = 2 * D + 4;
             int cc = 0;

@@ -100,7 +100,7 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
     if (a->Tq < 0 || a->Tq > 65535) return PLX_ERR_SHAPE;
     if (a->window < 0) return PLX_ERR_SHAPE;
     const int32_t Tq = a->Tq ? a->Tq : 1;
-    if (a->dtype == PLX_BF16 && (a->Hq / a->Hkv) * Tq > 16) return PLX_ERR_SHAPE;
+    // (16 MFMA columns per launch: more rows take several launches; check_common bounds the group size)
     if (need_inputs && !(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
     if (need_out && !aligned16(a->o)) return PLX_ERR_ALIGN;
     if (((int64_t)a->d * elem_size(a->dtype)) % 16 != 0) return PLX_ERR_ALIGN;
@@ -154,6 +154,22 @@ plx_status attach_workspace(const plx_decode_args *a, int32_t S, plx::DecodePara
     return PLX_OK;
 }
 
+// The bf16 split kernel has 16 MFMA columns (heads of the GQA group x query rows): a call with
+// more takes one launch per 16 / G rows. Every launch reads the cache again; they share the
+// split workspace and one combine.
+hipError_t launch_split_passes(const plx::DecodeParams &p, hipStream_t stream) {
+    if (p.G * p.Tq <= 16) return plx::launch_decode_bf16(p, stream);
+    const int32_t per = 16 / p.G;
+    for (int32_t row0 = 0; row0 < p.Tq; row0 += per) {
+        plx::DecodeParams q = p;
+        q.row0 = row0;
+        q.rows = p.Tq - row0 < per ? p.Tq - row0 : per;
+        const hipError_t err = plx::launch_decode_bf16(q, stream);
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+}
+
 }  // namespace
 
 plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
@@ -176,7 +192,7 @@ plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
         st = attach_workspace(a, S, &p);
         if (st != PLX_OK) return st;
     }
-    if (plx::launch_decode_bf16(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
+    if (launch_split_passes(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
     if (S > 1 && plx::launch_decode_combine(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
     return PLX_OK;
 }
@@ -197,9 +213,7 @@ plx_status parallax_decode_fused(const plx_decode_args *a, void *hip_stream) {
             return PLX_ERR_WORKSPACE;
         p.counters = a->split_counters;
     }
-    return plx::launch_decode_bf16(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess
-               ? PLX_OK
-               : PLX_ERR_LAUNCH;
+    return launch_split_passes(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? PLX_OK : PLX_ERR_LAUNCH;
 }
 
 plx_status parallax_decode_partials(const plx_decode_args *a, void *hip_stream) {
@@ -213,9 +227,7 @@ plx_status parallax_decode_partials(const plx_decode_args *a, void *hip_stream) 
     p.direct_out = 0;
     st = attach_workspace(a, S, &p);
     if (st != PLX_OK) return st;
-    return plx::launch_decode_bf16(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess
-               ? PLX_OK
-               : PLX_ERR_LAUNCH;
+    return launch_split_passes(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? PLX_OK : PLX_ERR_LAUNCH;
 }
 
 plx_status parallax_decode_combine(const plx_decode_args *a, void *hip_stream) {

@@ -25,6 +25,9 @@ struct DecodeParams {
     int32_t window;  // > 0: sliding window, a row at position pos sees keys pos - window + 1 .. pos
     int32_t *counters;  // in-kernel reduction: one arrival counter per (batch, kv head), zero on entry
     int32_t Tq;  // query rows per sequence (>= 1): the last Tq positions; q, r, o are [B, Hq, Tq, d]
+    // bf16 split kernel, more than 16 columns: one launch handles the rows [row0, row0 + rows) of
+    // the Tq (rows = 0: all of them)
+    int32_t row0, rows;
 };
 
 struct PrefillParams {
