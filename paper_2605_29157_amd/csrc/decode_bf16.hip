@@ -144,7 +144,9 @@ __device__ __forceinline__ void merge_records(const float *const (&rec0)[NROW], 
     }
 }
 
-template <int D, bool USE_R, bool PAGED>
+// RANGE: the launch covers the query rows [row0, row0 + rows) of Tq only (calls with more than 16
+// columns); its own instantiation, so that the one-launch kernel stays as it is.
+template <int D, bool USE_R, bool PAGED, bool RANGE = false>
 __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
     constexpr int KPI = 64 / CPR;         // rows covered by one wave-wide 16-byte load
@@ -167,12 +169,13 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     // column c = t * G + head: all rows of all heads of the group share every K/V fetch.
     // A launch may cover only the rows [row0, row0 + Tq) of Tq_all (more than 16 columns take
     // several launches): the rows behind them shorten what this launch sees of the sequence.
-    const int Tq_all = p.Tq, row0 = p.rows ? p.row0 : 0;
-    const int Tq = p.rows ? p.rows : Tq_all, GC = G * Tq;
+    const int Tq_all = p.Tq, row0 = RANGE ? p.row0 : 0;
+    const int Tq = RANGE ? p.rows : Tq_all, GC = G * Tq;
     const int col_t = c / G, col_h = c - col_t * G;
 
     int Lb = p.seq_lens ? p.seq_lens[b] : p.Lmax;
-    Lb = max(min(max(Lb, 0), p.Lmax) - (Tq_all - row0 - Tq), 0);
+    Lb = min(max(Lb, 0), p.Lmax);
+    if constexpr (RANGE) Lb = max(Lb - (Tq_all - row0 - Tq), 0);
     const int n_bt = (Lb + kDecodeBlockKeys - 1) / kDecodeBlockKeys;
     // sliding window: a row at position pos sees the keys pos - window + 1 .. pos, so the block
     // tiles before the first key of the earliest row (position Lb - Tq) are never read and the
@@ -493,10 +496,16 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
 
 template <int D, bool USE_R>
 static void launch_decode_variant(const DecodeParams &p, dim3 grid, hipStream_t stream) {
-    if (p.block_table)
+    if (p.rows > 0) {  // a range of the query rows
+        if (p.block_table)
+            hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, true, true>), grid, dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, false, true>), grid, dim3(256), 0, stream, p);
+    } else if (p.block_table) {
         hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, true>), grid, dim3(256), 0, stream, p);
-    else
+    } else {
         hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, false>), grid, dim3(256), 0, stream, p);
+    }
 }
 
 hipError_t launch_decode_bf16(const DecodeParams &p, hipStream_t stream) {
