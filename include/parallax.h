@@ -24,7 +24,7 @@
  *   - Arguments are validated on the host before anything is launched. On any error a
  *     negative plx_status is returned and nothing has been enqueued. No call aborts or throws.
  *   - GQA: G = Hq / Hkv must be an integer; query head h reads KV head h / G.
- *   - Supported: dtype bf16 (MFMA kernels, d in {64, 128}, G <= 8) and fp32 (plain
+ *   - Supported: dtype bf16 (MFMA kernels, d in {64, 128}, G <= 16) and fp32 (plain
  *     correctness kernels, d <= 256). Innermost dimension contiguous; base pointers and
  *     row strides 16-byte aligned. Output dtype = input dtype; all running state is fp32.
  */
@@ -77,7 +77,7 @@ typedef enum {
  * sequence, so row t sees key j iff j < L_b - (Tq - 1 - t). All rows of all heads of a GQA group
  * ride in one MFMA operand and share every K/V fetch as long as (Hq / Hkv) * Tq <= 16; with more
  * columns the bf16 path takes one launch per 16 / (Hq / Hkv) rows (each reads the cache again),
- * (bf16 GQA groups hold at most 8 heads). The workspace then needs Tq times
+ * (bf16 GQA groups hold at most 16 heads). The workspace then needs Tq times
  * parallax_decode_workspace_bytes(...).
  *
  * Paged cache (block_table != NULL; the paper's Sec. 5 remark that cache layouts carry over --

@@ -24,7 +24,7 @@ plx_status check_common(plx_dtype dtype, int32_t B, int32_t Hq, int32_t Hkv, int
     if (Hq % Hkv != 0) return PLX_ERR_SHAPE;
     if (dtype == PLX_BF16) {
         if (d != 64 && d != 128) return PLX_ERR_SHAPE;
-        if (Hq / Hkv > 8) return PLX_ERR_SHAPE;
+        if (Hq / Hkv > 16) return PLX_ERR_SHAPE;  // one MFMA operand holds a group's heads as 16 columns
     } else {
         if (d > 256 || d % 4 != 0) return PLX_ERR_SHAPE;
     }

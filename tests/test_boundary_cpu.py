@@ -128,7 +128,7 @@ def test_decode_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_SHAPE
     a = _good_decode_args(binding); a.d = 96
     assert call(a) == binding.PLX_ERR_SHAPE
-    a = _good_decode_args(binding); a.Hq, a.Hkv = 32, 2      # G = 16 > 8
+    a = _good_decode_args(binding); a.Hq, a.Hkv = 34, 2      # G = 17 > 16
     assert call(a) == binding.PLX_ERR_SHAPE
     a = _good_decode_args(binding); a.Lmax = 0
     assert call(a) == binding.PLX_ERR_SHAPE

@@ -76,7 +76,7 @@ def test_backward_small_lengths(plx, synth, bwd_oracle, T, causal):
            tol=BF16_REL_L2 if T > 1 else 5 * BF16_REL_L2)
 
 
-@pytest.mark.parametrize("Hq,Hkv,d", [(2, 2, 128), (8, 2, 128), (8, 1, 128), (6, 2, 64), (4, 4, 64)])
+@pytest.mark.parametrize("Hq,Hkv,d", [(2, 2, 128), (8, 2, 128), (8, 1, 128), (6, 2, 64), (4, 4, 64), (16, 1, 128), (12, 1, 64)])
 def test_backward_gqa_groups_and_head_dims(plx, synth, bwd_oracle, Hq, Hkv, d):
     """The gradients of a KV head add up over the query heads of its group."""
     _check(plx, synth, bwd_oracle, 2, Hq, Hkv, 200, 200, d, True, seed=2100 + Hq + d)

@@ -49,6 +49,7 @@ def _both(plx, x, counters, **kw):
     (3, 8, 4, 1500, 128, 5),      # ragged tail, odd split count
     (3, 8, 4, 1500, 128, 128),    # most splits empty
     (2, 8, 1, 777, 128, 3),       # one kv head, group of 8
+    (2, 16, 1, 777, 128, 3),      # group of 16: every MFMA column is a head
     (2, 8, 4, 700, 64, 4),        # d = 64
     (1, 2, 2, 300, 128, 2),
     (2, 4, 2, 64, 128, 1),        # one split: no records, no counters touched

@@ -93,7 +93,7 @@ def test_scale_zero_is_uniform_weighting(plx, synth, oracle):
     assert rel_l2(_run(plx, y), ref) <= BF16_REL_L2
 
 
-@pytest.mark.parametrize("Hq,Hkv,d", [(2, 2, 128), (8, 2, 128), (4, 2, 64), (16, 8, 64)])
+@pytest.mark.parametrize("Hq,Hkv,d", [(2, 2, 128), (8, 2, 128), (4, 2, 64), (16, 8, 64), (16, 1, 128), (24, 2, 64)])
 def test_head_layouts(plx, synth, oracle, Hq, Hkv, d):
     y = synth.prefill_inputs(1, Hq, Hkv, 333, d, seed=500 + Hq + d, device=DEV)
     ref = oracle_prefill(oracle, y)
