@@ -31,10 +31,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per launch of the split-KV kernel on config 2, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE scaled by the same counters on parallax_util_copy of known size
-# (profiles/decode_bf16_config2_hbm_counters.md): 134 877 000 read + 1 081 344 written.
+# (profiles/decode_bf16_config2_hbm_counters.md): 134 897 000 read + 1 081 344 written.
 # Prefill, config 4 (profiles/prefill_bf16_config4_hbm_counters.md): 431 631 000 read + 67 108 864
 # written.
-MEASURED_TRAFFIC_BYTES = {"config2": 135960000, "config4_prefill": 498740000}
+MEASURED_TRAFFIC_BYTES = {"config2": 135978000, "config4_prefill": 498740000}
 
 
 def decode_bytes(B, Hkv, d, lens_sum, Hq):
@@ -158,7 +158,7 @@ def main():
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES["config2"] if is_config2 else None,
-                "kernel": "decode_bf16_kernel<128,true,false>", "kernel_us": round(kern_us, 2),
+                "kernel": "decode_bf16_kernel<128,true,false,false>", "kernel_us": round(kern_us, 2),
                 "algorithmic_bytes_per_launch": step_bytes}
 
     # per-launch spread: one event pair per step (whole step) and per split-KV kernel launch
