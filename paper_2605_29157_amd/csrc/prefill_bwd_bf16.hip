@@ -170,12 +170,35 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     const int col = lane & 31, h = lane >> 5;
     const int T = p.T;
     const int nrb = (T + 127) / 128;
-    const int rbi = blockIdx.x % nrb;
+    // Work item: the row block is the slowest index, so that under a causal mask ALL heavy row
+    // blocks are dispatched before any light one (with the row block as the fastest index every
+    // head ends on its own light blocks while the last head's heavy ones have just started: the
+    // tail cost 14 % of the pass). The (batch, kv head) pairs are dealt over the 8 XCDs by
+    // workgroup id modulo 8, so that the heads of a GQA group share an L2.
+    int rbi, hq, b;
+    {
+        const int id = blockIdx.x, pairs = p.B * p.Hkv, G = p.G;
+        int pair, hg;
+        if (pairs % 8 == 0) {
+            const int x = id & 7, j = id >> 3, per = (pairs / 8) * G;
+            rbi = j / per;
+            const int rem = j - rbi * per;
+            pair = (rem / G) * 8 + x;
+            hg = rem % G;
+        } else {
+            const int per = pairs * G;
+            rbi = id / per;
+            const int rem = id - rbi * per;
+            pair = rem / G;
+            hg = rem % G;
+        }
+        b = pair / p.Hkv;
+        hq = (pair - b * p.Hkv) * G + hg;
+    }
     const int rb = CAUSAL ? nrb - 1 - rbi : rbi;  // heavy row blocks first
     // key tiles no row of this block sees (all keys before the window of its first row)
     const int kt_skip = WINDOW ? max(rb * 128 + (p.Tk - T) - p.window + 1, 0) / kTileRows : 0;
     const int Tk = p.Tk - kt_skip * kTileRows, off = Tk - T;  // keys from the first tile read on
-    const int hq = (blockIdx.x / nrb) % p.Hq, b = blockIdx.x / (nrb * p.Hq);
     const int hk = hq / p.G;
     const int row0 = rb * 128 + w * 32, my_row = row0 + col;
     const int ld_row = min(my_row, T - 1);
@@ -458,8 +481,25 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     const int col = lane & 31, h = lane >> 5;
     const int T = p.T, Tk = p.Tk, off = Tk - T, G = p.G;
     const int ncb = (Tk + 127) / 128;
-    const int cb = blockIdx.x % ncb;  // causal: low key blocks see the most rows; they come first
-    const int hk = (blockIdx.x / ncb) % p.Hkv, b = blockIdx.x / (ncb * p.Hkv);
+    // Work item: the key block is the slowest index (causal: low key blocks see the most rows;
+    // all of them come first, over every batch entry and head -- with the key block as the
+    // fastest index the tail of the pass cost a quarter of it); (batch, kv head) pairs by
+    // workgroup id modulo 8 onto the XCDs.
+    int cb, hk, b;
+    {
+        const int id = blockIdx.x, pairs = p.B * p.Hkv;
+        int pair;
+        if (pairs % 8 == 0) {
+            const int x = id & 7, j = id >> 3, per = pairs / 8;
+            cb = j / per;
+            pair = (j - cb * per) * 8 + x;
+        } else {
+            cb = id / pairs;
+            pair = id - cb * pairs;
+        }
+        b = pair / p.Hkv;
+        hk = pair - b * p.Hkv;
+    }
     const int key0 = cb * 128 + w * 32, my_key = key0 + col;
     const int ld_key = min(my_key, Tk - 1);
 
