@@ -119,26 +119,29 @@ __device__ __forceinline__ f32x16 zero16() {
 // ---- rows prepare: (lse, ubar, tau, beta) per query row ---------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void bwd_rows_prepare_kernel(PrefillBwdParams p) {
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    // 16 bytes per lane: D / 8 lanes share a row, a workgroup takes 2048 / D rows
+    constexpr int LPR = D / 8, ROWS = 256 / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int64_t row = (int64_t)blockIdx.x * ROWS + threadIdx.x / LPR;
     const int64_t n_rows = (int64_t)p.B * p.Hq * p.T;
-    if (row >= n_rows) return;
-    const int64_t bh = row / p.T, t = row - bh * p.T, b = bh / p.Hq, h = bh - b * p.Hq;
+    const bool live = row < n_rows;  // (whole row groups; every lane takes part in the shuffles)
+    const int64_t rr = live ? row : n_rows - 1;
+    const int64_t bh = rr / p.T, t = rr - bh * p.T, b = bh / p.Hq, h = bh - b * p.Hq;
+    const u32x4 g = ((const u32x4 *)((const __bf16 *)p.d_o + b * p.gs[0] + h * p.gs[1] + t * p.gs[2]))[sub];
+    const u32x4 o = ((const u32x4 *)((const __bf16 *)p.o + b * p.os[0] + h * p.os[1] + t * p.os[2]))[sub];
+    const u32x4 vb = ((const u32x4 *)((const __bf16 *)p.vbar + b * p.vbs[0] + h * p.vbs[1] + t * p.vbs[2]))[sub];
     float tau = 0.f, beta = 0.f;
-    if (lane < D / 2) {
-        const uint32_t g = ((const uint32_t *)((const __bf16 *)p.d_o + b * p.gs[0] + h * p.gs[1] + t * p.gs[2]))[lane];
-        const uint32_t o = ((const uint32_t *)((const __bf16 *)p.o + b * p.os[0] + h * p.os[1] + t * p.os[2]))[lane];
-        const uint32_t vb =
-            ((const uint32_t *)((const __bf16 *)p.vbar + b * p.vbs[0] + h * p.vbs[1] + t * p.vbs[2]))[lane];
-        tau = bf16_lo_f32(g) * bf16_lo_f32(o) + bf16_hi_f32(g) * bf16_hi_f32(o);
-        beta = bf16_lo_f32(g) * bf16_lo_f32(vb) + bf16_hi_f32(g) * bf16_hi_f32(vb);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        tau += bf16_lo_f32(g[i]) * bf16_lo_f32(o[i]) + bf16_hi_f32(g[i]) * bf16_hi_f32(o[i]);
+        beta += bf16_lo_f32(g[i]) * bf16_lo_f32(vb[i]) + bf16_hi_f32(g[i]) * bf16_hi_f32(vb[i]);
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
+    for (int off = LPR / 2; off > 0; off >>= 1) {
         tau += __shfl_xor(tau, off, 64);
         beta += __shfl_xor(beta, off, 64);
     }
-    if (lane == 0) {
+    if (live && sub == 0) {
         const f32x4 out = {p.row_stats[2 * row], 1.f + p.row_stats[2 * row + 1], beta - tau, beta};
         ((f32x4 *)p.row_cache)[row] = out;
     }
@@ -843,7 +846,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
 template <int D>
 static hipError_t launch_bwd_d(const PrefillBwdParams &p, hipStream_t stream) {
     const long long n_rows = (long long)p.B * p.Hq * p.T;
-    const long long g0 = (n_rows + 3) / 4;
+    constexpr int kPrepRows = 2048 / D;  // rows per workgroup of the rows-prepare kernel
+    const long long g0 = (n_rows + kPrepRows - 1) / kPrepRows;
     const long long g1 = (long long)((p.T + 127) / 128) * p.Hq * p.B;
     const long long g2 = (long long)((p.Tk + 127) / 128) * p.Hkv * p.B;
     if (g0 > 0x7fffffffLL || g1 > 0x7fffffffLL || g2 > 0x7fffffffLL) return hipErrorInvalidValue;
