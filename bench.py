@@ -292,8 +292,19 @@ def backward_line(torch, plx, synth, dev, opt):
     fwd_us = _time_events(
         torch, lambda: plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True,
                                             out=o), warm, steps)
+    # the forward as a training step runs it: with the row cache (o, vbar, lse, ubar) written
+    fa = plx.prefill_args(y["q"], y["r"], y["k"], y["v"], o, y["scale"], True, True, 0)
+    fa.vbar, fa.row_stats = vbar.data_ptr(), stats.data_ptr()
+
+    def fwd_cache_step():
+        st = lib.parallax_prefill(ctypes.byref(fa), sptr)
+        if st != 0:
+            raise plx.ParallaxError(st, "parallax_prefill")
+
+    fwd_cache_us = _time_events(torch, fwd_cache_step, warm, steps)
     flops = B * Hq * 22 * d * T * (T + 1) / 2
     tf = flops / us / 1e6
+    train_tf = B * Hq * 30 * d * T * (T + 1) / 2 / (us + fwd_cache_us) / 1e6
     return {
         "metric": "prefill_backward_bf16_throughput", "value": round(tf, 1), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(us / 1e3, 4),
@@ -301,7 +312,9 @@ def backward_line(torch, plx, synth, dev, opt):
         "data": "synthetic",
         "config": {"workload": "backward of causal prefill bf16 B=%d T=%d Hq=16 Hkv=8 d=128, "
                                "K offset N(0,0.5^2)" % (B, T),
-                   "algorithmic_flops": flops, "forward_ms": round(fwd_us / 1e3, 4)},
+                   "algorithmic_flops": flops, "forward_ms": round(fwd_us / 1e3, 4),
+                   "forward_with_row_cache_ms": round(fwd_cache_us / 1e3, 4),
+                   "forward_with_row_cache_plus_backward_TFLOPs": round(train_tf, 1)},
         "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                      "kernel": "bwd_dq_dr_kernel<128,true,false> + bwd_dk_dv_kernel<128,true,false>",
