@@ -60,6 +60,9 @@ def main():
                          "other shapes are for profiling the same kernels at larger sizes)")
     ap.add_argument("--prefill-shape", default="4,4096", metavar="B,T",
                     help="batch and length of the causal prefill workload (default 4,4096 = config 4)")
+    ap.add_argument("--prefill-heads", default="16,8,128", metavar="Hq,Hkv,d",
+                    help="query heads, KV heads and head dimension of the prefill workload "
+                         "(default 16,8,128; 32,16,64 is the compute-matched layout)")
     ap.add_argument("--counter-mode", action="store_true",
                     help="short run for hardware-counter collection: 5 launches of the plain copy "
                          "kernel on 1 GiB (known size, calibrates FETCH_SIZE / WRITE_SIZE) and "
@@ -233,8 +236,8 @@ def main():
 def prefill_line(torch, plx, synth, dev, opt):
     """Config 4 on its own: causal prefill bf16 B=4 T=4096 Hq=16 Hkv=8 d=128."""
     B, T = (int(v) for v in opt.prefill_shape.split(","))
-    Hq, Hkv, d = 16, 8, 128
-    is_config4 = (B, T) == (4, 4096)
+    Hq, Hkv, d = (int(v) for v in opt.prefill_heads.split(","))
+    is_config4 = (B, T, Hq, Hkv, d) == (4, 4096, 16, 8, 128)
     y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1004, device=dev, k_offset_sigma=0.5)
     out = torch.empty_like(y["q"])
     steps = min(opt.steps, 50)
@@ -251,13 +254,13 @@ def prefill_line(torch, plx, synth, dev, opt):
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(us / 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "%scausal prefill bf16 B=%d T=%d Hq=16 Hkv=8 d=128, "
-                               "K offset N(0,0.5^2)" % ("config4: " if is_config4 else "", B, T),
+        "config": {"workload": "%scausal prefill bf16 B=%d T=%d Hq=%d Hkv=%d d=%d, "
+                               "K offset N(0,0.5^2)" % ("config4: " if is_config4 else "", B, T, Hq, Hkv, d),
                    "algorithmic_flops": flops},
         "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES["config4_prefill"] if is_config4 else None,
-                     "kernel": "prefill_bf16_kernel<128,true,true,false,false,false>",
+                     "kernel": "prefill_bf16_kernel<%d,true,true,false,false,false>" % d,
                      "kernel_us": round(us, 1)},
     }
 
