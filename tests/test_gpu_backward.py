@@ -210,6 +210,35 @@ def test_backward_config4_shape_sampled(plx, synth, bwd_oracle):
         assert rel_l2(host(got), ref) <= BF16_REL_L2, name
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,T,Tkv,d,causal", [(4, 16, 8, 300, 300, 128, True), (2, 8, 4, 200, 333, 64, True),
+                                                      (8, 3, 1, 129, 129, 128, False), (1, 16, 16, 260, 260, 128, True)])
+def test_backward_pair_counts_that_are_multiples_of_eight(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, causal):
+    """B * Hkv divisible by 8: the work items take the mapping that deals (batch, kv head) pairs
+    over the eight XCDs (the benchmark's launch configuration), here at sizes the oracle covers."""
+    _check(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, causal, seed=2650 + B + T)
+
+
+def test_backward_config4_launch_equals_its_slices(plx, synth):
+    """Benchmark configuration 4 as bench.py launches it (B=4, 16 query / 8 KV heads, T=4096, d=128):
+    a workgroup's arithmetic does not depend on which work item it is, so the gradients of one
+    batch entry and two KV heads' groups must equal, bit for bit, those of a call on just that
+    slice (one pair count takes the XCD mapping, the other the plain one; the slice-sized call is
+    what test_backward_config4_shape_sampled checks against the oracle)."""
+    B, Hq, Hkv, T, d = 4, 16, 8, 4096, 128
+    y, g = _inputs(synth, B, Hq, Hkv, T, T, d, 2680)
+    o, vbar, stats, full = _run(plx, y, g, True)
+    for b, hk0 in ((0, 0), (3, 6), (2, 2)):
+        hq0, sl_b = 2 * hk0, slice(b, b + 1)
+        sub = {"q": y["q"][sl_b, hq0:hq0 + 4], "r": y["r"][sl_b, hq0:hq0 + 4],
+               "k": y["k"][sl_b, hk0:hk0 + 2], "v": y["v"][sl_b, hk0:hk0 + 2], "scale": y["scale"]}
+        part = plx.parallax_prefill_backward(sub["q"], sub["r"], sub["k"], sub["v"], o[sl_b, hq0:hq0 + 4],
+                                             vbar[sl_b, hq0:hq0 + 4], stats[sl_b, hq0:hq0 + 4].contiguous(),
+                                             g[sl_b, hq0:hq0 + 4], y["scale"], causal=True)
+        torch.cuda.synchronize()
+        for name, got, ref, h0, n in zip(("dq", "dr", "dk", "dv"), part, full, (hq0, hq0, hk0, hk0), (4, 4, 2, 2)):
+            assert torch.equal(got, ref[sl_b, h0:h0 + n]), (name, b, hk0)
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,T,Tkv,d,causal", [(1, 2, 2, 128, 128, 64, True), (2, 4, 2, 77, 77, 32, True),
                                                       (1, 6, 2, 50, 301, 128, True), (2, 4, 4, 130, 257, 16, False),
                                                       (1, 2, 1, 1, 1, 8, True), (1, 2, 2, 300, 300, 256, True)])
