@@ -216,6 +216,8 @@ def test_backward_pair_counts_that_are_multiples_of_eight(plx, synth, bwd_oracle
     """B * Hkv divisible by 8: the work items take the mapping that deals (batch, kv head) pairs
     over the eight XCDs (the benchmark's launch configuration), here at sizes the oracle covers."""
     _check(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, causal, seed=2650 + B + T)
+    if causal:  # the sliding-window kernels share the mapping
+        _check(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, True, seed=2660 + B + T, window=70, tol=2 * BF16_REL_L2)
 
 
 def test_backward_config4_launch_equals_its_slices(plx, synth):
