@@ -49,10 +49,13 @@ typedef enum {
     PLX_ERR_WORKSPACE = -5, /* split-KV workspace missing or too small             */
     PLX_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch                    */
     PLX_ERR_SPLITS = -7,    /* num_splits outside [0, PLX_MAX_SPLITS]              */
-    PLX_ERR_SCALE = -8      /* scale is negative, infinite or NaN                  */
+    PLX_ERR_SCALE = -8,     /* scale is negative, infinite or NaN                  */
+    PLX_ERR_SCRATCH = -9    /* parallax_decode_static: records exceed its scratch  */
 } plx_status;
 
 #define PLX_MAX_SPLITS 128
+/* Split records (at d = 128: 1040 bytes each) that parallax_decode_static's scratch holds. */
+#define PLX_STATIC_SCRATCH_RECORDS 16384
 
 /*
  * Single-step decode (Algorithm 1 with one query row per head, Sec. 3.3; split-KV and merge,
@@ -125,6 +128,26 @@ int32_t parallax_decode_num_splits(int32_t B, int32_t Hq, int32_t Hkv, int32_t L
                                    int32_t num_cus);
 
 plx_status parallax_decode(const plx_decode_args *args, void *hip_stream);
+
+/*
+ * parallax_decode for callers that cannot allocate or pass a workspace -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: the split records go to a
+ * fixed array inside the library's code object instead (one copy per GPU, held until the
+ * process ends; parallax_decode_static_scratch_bytes() = 17 039 360 bytes, i.e.
+ * PLX_STATIC_SCRATCH_RECORDS records at d = 128). Same arguments, kernels and results as
+ * parallax_decode (bit-identical for the same num_splits); args->workspace and
+ * args->workspace_bytes are ignored. The call allocates nothing and calls no allocating
+ * routine; the first call on a device looks the array's address up once.
+ *   Limit: B * Hq * Tq * S * (2d + 4) * 4 bytes must fit the scratch (S = num_splits, or the
+ *   heuristic's pick for num_splits = 0); otherwise PLX_ERR_SCRATCH and nothing is enqueued.
+ *   S = 1 and fp32 calls use no scratch.
+ *   Every call on a GPU shares that GPU's array: calls that may overlap on one device (two
+ *   streams, two threads) race on it -- serialise them or give the others a workspace through
+ *   parallax_decode. Nothing in the array has to start at zero (every record that is merged has
+ *   been written by the same call), so stale contents of earlier calls are harmless.
+ */
+plx_status parallax_decode_static(const plx_decode_args *args, void *hip_stream);
+size_t parallax_decode_static_scratch_bytes(void);
 
 /*
  * The two halves of parallax_decode on their own (bf16 only), for callers that merge partials

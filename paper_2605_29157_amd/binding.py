@@ -17,11 +17,13 @@ LIB_PATH = os.path.join(_PKG, "libparallax_hip.so")
 PLX_BF16, PLX_F32 = 0, 1
 PLX_MAX_SPLITS = 128
 (PLX_OK, PLX_ERR_NULL, PLX_ERR_SHAPE, PLX_ERR_DTYPE, PLX_ERR_ALIGN, PLX_ERR_WORKSPACE,
- PLX_ERR_LAUNCH, PLX_ERR_SPLITS, PLX_ERR_SCALE) = (0, -1, -2, -3, -4, -5, -6, -7, -8)
+ PLX_ERR_LAUNCH, PLX_ERR_SPLITS, PLX_ERR_SCALE, PLX_ERR_SCRATCH) = (0, -1, -2, -3, -4, -5, -6, -7, -8, -9)
+PLX_STATIC_SCRATCH_RECORDS = 16384
 
 EXPORTED_SYMBOLS = (
     "parallax_decode_workspace_bytes", "parallax_decode_num_splits", "parallax_decode",
     "parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused",
+    "parallax_decode_static", "parallax_decode_static_scratch_bytes",
     "parallax_decode_mla", "parallax_decode_mla_workspace_bytes", "parallax_decode_mla_num_splits",
     "parallax_prefill", "parallax_prefill_backward", "parallax_prefill_backward_workspace_bytes",
     "parallax_norm_rope", "parallax_util_copy", "parallax_util_read",
@@ -147,7 +149,10 @@ def load_library() -> ctypes.CDLL:
         lib.parallax_decode_num_splits.restype = ctypes.c_int32
         lib.parallax_decode.argtypes = [ctypes.POINTER(plx_decode_args), ctypes.c_void_p]
         lib.parallax_decode.restype = ctypes.c_int
-        for name in ("parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused"):
+        lib.parallax_decode_static_scratch_bytes.argtypes = []
+        lib.parallax_decode_static_scratch_bytes.restype = ctypes.c_size_t
+        for name in ("parallax_decode_partials", "parallax_decode_combine", "parallax_decode_fused",
+                     "parallax_decode_static"):
             getattr(lib, name).argtypes = [ctypes.POINTER(plx_decode_args), ctypes.c_void_p]
             getattr(lib, name).restype = ctypes.c_int
         lib.parallax_prefill.argtypes = [ctypes.POINTER(plx_prefill_args), ctypes.c_void_p]
@@ -291,6 +296,22 @@ def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, 
     st = getattr(load_library(), entry)(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, entry)
+    return out
+
+
+def parallax_decode_static_scratch_bytes() -> int:
+    return int(load_library().parallax_decode_static_scratch_bytes())
+
+
+def parallax_decode_static(q, r, k, v, scale, out, seq_lens=None, use_r=True, num_splits=0,
+                           stream=None, block_table=None, max_len=None, window=0):
+    """parallax_decode with the split records in the library's own fixed scratch: nothing is
+    allocated here or in the library; `out` is the caller's."""
+    a = decode_args(q, r, k, v, out, scale, seq_lens, use_r, num_splits, None, block_table, max_len,
+                    window)
+    st = load_library().parallax_decode_static(ctypes.byref(a), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_decode_static")
     return out
 
 

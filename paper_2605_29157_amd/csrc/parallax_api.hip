@@ -4,7 +4,16 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "plx_kernels.h"
+
+// Split workspace of parallax_decode_static, the decode entry point for callers that cannot
+// allocate: every GPU the library runs on holds its own copy of this array from the moment the
+// code object is loaded until the process ends. In host code the name below is only a handle
+// for hipGetSymbolAddress; kernels and copies get the per-device address it returns.
+#define PLX_STATIC_SCRATCH_FLOATS (PLX_STATIC_SCRATCH_RECORDS * (2 * 128 + 4))
+static __device__ __align__(256) float scratch[PLX_STATIC_SCRATCH_FLOATS];
 
 namespace {
 
@@ -42,6 +51,25 @@ int query_num_cus() {
 
 size_t ws_bytes(int64_t B, int64_t Hq, int64_t S, int64_t d) {
     return (size_t)(B * Hq * S * (2 * d + 4)) * sizeof(float);
+}
+
+// Device address of `scratch` on the current device, looked up once per device (each GPU has
+// its own copy of the array at its own address) and kept for the life of the process.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[kMaxDevices];
+
+plx_status static_scratch_of_current_device(float **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PLX_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PLX_ERR_LAUNCH;
+        g_scratch_ptr[dev] = static_cast<float *>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return PLX_OK;
 }
 
 }  // namespace
@@ -154,6 +182,14 @@ plx_status attach_workspace(const plx_decode_args *a, int32_t S, plx::DecodePara
     return PLX_OK;
 }
 
+// The split records of a call go to the library's static scratch instead of a caller's
+// workspace; a call whose records do not fit is refused.
+plx_status attach_static_scratch(const plx_decode_args *a, int32_t S, plx::DecodeParams *p) {
+    if (ws_bytes(a->B, (int64_t)a->Hq * p->Tq, S, a->d) > sizeof(float) * PLX_STATIC_SCRATCH_FLOATS)
+        return PLX_ERR_SCRATCH;
+    return static_scratch_of_current_device(&p->ws);
+}
+
 // The bf16 split kernel has 16 MFMA columns (heads of the GQA group x query rows): a call with
 // more takes one launch per 16 / G rows. Every launch reads the cache again; they share the
 // split workspace and one combine.
@@ -172,7 +208,9 @@ hipError_t launch_split_passes(const plx::DecodeParams &p, hipStream_t stream) {
 
 }  // namespace
 
-plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
+namespace {
+
+plx_status decode_two_kernels(const plx_decode_args *a, bool static_scratch, void *hip_stream) {
     plx::DecodeParams p{};
     plx_status st = prepare_decode(a, true, true, &p);
     if (st != PLX_OK) return st;
@@ -189,13 +227,25 @@ plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
     p.S = S;
     p.direct_out = S == 1;
     if (S > 1) {
-        st = attach_workspace(a, S, &p);
+        st = static_scratch ? attach_static_scratch(a, S, &p) : attach_workspace(a, S, &p);
         if (st != PLX_OK) return st;
     }
     if (launch_split_passes(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
     if (S > 1 && plx::launch_decode_combine(p, stream) != hipSuccess) return PLX_ERR_LAUNCH;
     return PLX_OK;
 }
+
+}  // namespace
+
+plx_status parallax_decode(const plx_decode_args *a, void *hip_stream) {
+    return decode_two_kernels(a, false, hip_stream);
+}
+
+plx_status parallax_decode_static(const plx_decode_args *a, void *hip_stream) {
+    return decode_two_kernels(a, true, hip_stream);
+}
+
+size_t parallax_decode_static_scratch_bytes(void) { return sizeof(float) * PLX_STATIC_SCRATCH_FLOATS; }
 
 plx_status parallax_decode_fused(const plx_decode_args *a, void *hip_stream) {
     plx::DecodeParams p{};
@@ -503,6 +553,9 @@ const char *parallax_strerror(plx_status status) {
         case PLX_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
         case PLX_ERR_SPLITS: return "num_splits outside [0, PLX_MAX_SPLITS]";
         case PLX_ERR_SCALE: return "scale must be finite and non-negative";
+        case PLX_ERR_SCRATCH:
+            return "the split records of this call do not fit parallax_decode_static's fixed scratch "
+                   "(use fewer splits, a smaller batch, or parallax_decode with a workspace)";
     }
     return "unknown status";
 }

@@ -74,7 +74,7 @@ def test_struct_layouts_match_a_c_compiler(binding, tmp_path):
 def test_version_and_strerror(binding):
     assert binding.version() >= 100
     assert binding.strerror(0) == "ok"
-    for code in range(-8, 0):
+    for code in range(-9, 0):
         assert binding.strerror(code) not in ("ok", "unknown status")
     assert binding.strerror(-99) == "unknown status"
 
@@ -104,6 +104,20 @@ def test_split_heuristic_is_sane(binding):
     assert f(16, 16, 8, 16384, 128, 256) == 4
     assert f(32, 16, 8, 4096, 128, 256) == 1
     assert f(32, 16, 8, 8192, 128, 256) == 2
+
+
+def test_static_scratch_entry_point_checks_its_limit_on_the_host(binding):
+    lib = binding.load_library()
+    static = lambda a: lib.parallax_decode_static(ctypes.byref(a), None)
+    assert binding.parallax_decode_static_scratch_bytes() == 16384 * 260 * 4
+    assert lib.parallax_decode_static(None, None) == binding.PLX_ERR_NULL
+    a = _good_decode_args(binding); a.d = 96                  # the usual validation comes first
+    assert static(a) == binding.PLX_ERR_SHAPE
+    a = _good_decode_args(binding); a.B, a.Hq, a.Hkv, a.num_splits = 17, 8, 8, 128   # 17 408 records
+    assert static(a) == binding.PLX_ERR_SCRATCH
+    a = _good_decode_args(binding); a.B, a.Hq, a.Hkv, a.num_splits, a.Tq = 16, 8, 8, 128, 2
+    assert static(a) == binding.PLX_ERR_SCRATCH
+    assert "scratch" in binding.strerror(binding.PLX_ERR_SCRATCH)
 
 
 def _good_decode_args(binding):
