@@ -360,6 +360,10 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     float m_ref = kNegInf;
     f32x16 o1[NDB], o2[NDB], dacc1, dacc2;
     float vsum1[2] = {0.f, 0.f}, vsum2[2] = {0.f, 0.f};  // per-lane partial row sums (this lane's keys)
+    // Row cache only: fp32 sums of the UNROUNDED P1, P2 over the masked tiles as well. The backward
+    // pass recomputes p and u in fp32 and forms 1 + ubar - u, which is 1 for a row with one key only
+    // if ubar carries no bf16 rounding of P2; the output keeps the sums of the rounded operands.
+    float msum1[2] = {0.f, 0.f}, msum2[2] = {0.f, 0.f};
     const u32x4 ones_frag = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const float scale_log2 = p.scale * kLog2e;  // >= 0 (checked by the host)
 
@@ -376,6 +380,10 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             s1[r] = p1;
             // s2 is finite (rows past the last key re-read it) and P1 = 0 where masked
             if constexpr (USE_R) s2[r] = p1 * s2[r];
+            if constexpr (STATS) {
+                msum1[r & 1] += s1[r];
+                msum2[r & 1] += s2[r];
+            }
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -488,9 +496,10 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // last key this lane's row may see
     const int row_lim = no_tiles ? -1 : (CAUSAL ? min(my_row + off, Tk - 1) : Tk - 1);
     auto exp_stages = [&](auto masked_tag, auto sums_tag, f32x16 &s1, f32x16 &s2, int r0, int slot,
-                          int slot0, int n_slots, float neg_m, int lim, int lo) {
+                          int slot0, int n_slots, float neg_m, int lim, int lo, float(&acc1)[2],
+                          float(&acc2)[2]) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        constexpr bool SUMS = decltype(sums_tag)::value;  // a fourth stage adds P1, P2 to the row sums
+        constexpr bool SUMS = decltype(sums_tag)::value;  // a fourth stage adds P1, P2 to acc1, acc2
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int r = r0 + u;
@@ -499,8 +508,8 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             const int first = slot0 + u * (n_slots - (SUMS ? 5 : 4) - slot0) / 8;
             if constexpr (SUMS)
                 if (slot == first + 3) {
-                    vsum1[u & 1] += s1[r];
-                    if constexpr (USE_R) vsum2[u & 1] += s2[r];
+                    acc1[u & 1] += s1[r];
+                    if constexpr (USE_R) acc2[u & 1] += s2[r];
                 }
             if (slot == first) s1[r] = fmaf(s1[r], scale_log2, neg_m);
             if (slot == first + 1) {
@@ -532,10 +541,14 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         // ones per key group. Unmasked steps: vector adds of the fp32 values, which stay in the
         // score registers until the next step -- upper key group behind its exp stages in phase
         // 1, lower key group (finished by the previous step) during phase 2.
-        constexpr bool SUMS = !MASKED && PLX_PF_VALU_SUMS;
+        constexpr bool SUMS = !MASKED;
         constexpr int GROUP2 = 2 * NDB + (SUMS ? 0 : 2);  // phase 2, per key group: PV (+ row sums)
         constexpr int SLOTS2 = 2 * GROUP2;
-        const std::integral_constant<bool, SUMS> sums_tag{};
+        // (row cache: masked steps add the fp32 values as well, to sums of their own)
+        constexpr bool ADDS = SUMS || STATS;
+        const std::integral_constant<bool, ADDS> sums_tag{};
+        float(&acc1)[2] = SUMS ? vsum1 : msum1;
+        float(&acc2)[2] = SUMS ? vsum2 : msum2;
         static_assert(NDMA_K <= KSTEPS && NDMA_V <= GROUP2, "one tile load per odd slot");
         const float neg_m = -m_ref;
         // ---- phase 1: scores of the next block | upper key group of the current block ------
@@ -556,7 +569,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             }
             if constexpr (DMA)
                 if (sl % 2 == 1 && sl / 2 < NDMA_K) k_load(sl / 2, dma_tk, dma_dk);
-            exp_stages(masked_tag, sums_tag, sc1, sc2, 8, sl, 0, SLOTS1, neg_m, lim_cur, lo_cur);
+            exp_stages(masked_tag, sums_tag, sc1, sc2, 8, sl, 0, SLOTS1, neg_m, lim_cur, lo_cur, acc1, acc2);
             if (sl == SLOTS1 - 2) pb1[1] = pack_group(sc1, 1);
             if (sl == SLOTS1 - 1) {
                 if constexpr (USE_R) pb2[1] = pack_group(sc2, 1);
@@ -586,12 +599,13 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             }
             if constexpr (DMA)
                 if (sl % 2 == 1 && sl / 2 < NDMA_V) v_load(sl / 2, dma_tv, dma_dv);
-            exp_stages(masked_tag, std::false_type{}, sn1, sn2, 0, sl, 1, SLOTS2, neg_m, lim_next, lo_next);
-            if constexpr (SUMS)
-                if (sl % (SLOTS2 / 8) == 0) {
+            exp_stages(masked_tag, std::false_type{}, sn1, sn2, 0, sl, 1, SLOTS2, neg_m, lim_next, lo_next, acc1,
+                       acc2);
+            if constexpr (ADDS)
+                if (sl % (SLOTS2 / 8) == 0 && sl / (SLOTS2 / 8) < 8) {
                     const int r = sl / (SLOTS2 / 8);  // lower key group of the current block
-                    vsum1[r & 1] += sc1[r];
-                    if constexpr (USE_R) vsum2[r & 1] += sc2[r];
+                    acc1[r & 1] += sc1[r];
+                    if constexpr (USE_R) acc2[r & 1] += sc2[r];
                 }
             if (sl == SLOTS2 - 2) nb1 = pack_group(sn1, 0);
             if (sl == SLOTS2 - 1) {
@@ -663,7 +677,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
 #pragma unroll
         for (int sl = 0; sl < 12; ++sl)
             exp_stages(std::true_type{}, std::false_type{}, sa1, sa2, 0, sl, 0, 12, -m_ref, row_lim - kb0 - 4 * h,
-                       row_lo - kb0 - 4 * h);
+                       row_lo - kb0 - 4 * h, msum1, msum2);
         pb1[0] = pack_group(sa1, 0);
         if constexpr (USE_R) pb2[0] = pack_group(sa2, 0);
     }
@@ -754,6 +768,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     if (overflow && !PLX_PF_ABLATE) {
         zero_state();
         vsum1[0] = vsum1[1] = vsum2[0] = vsum2[1] = 0.f;
+        msum1[0] = msum1[1] = msum2[0] = msum2[1] = 0.f;
         m_ref = kNegInf;
         dma_tile(tile_at(0), 0);
         stage = 0;
@@ -775,6 +790,10 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                 const float m_use = m_new == kNegInf ? 0.f : m_new;
                 const float alpha = fast_exp2(m_ref - m_use);  // 0 while m_ref = -inf
                 m_ref = m_new;
+                if constexpr (STATS) {
+                    msum1[0] *= alpha, msum1[1] *= alpha;
+                    msum2[0] *= alpha, msum2[1] *= alpha;
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     dacc1[r] *= alpha;
@@ -837,10 +856,13 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             // Row cache for the backward pass (App. D): vbar_i = O1 / d1 through the same
             // staging tile, and per row the log-sum-exp of the scaled scores in the exp2 domain
             // (P1 = exp2(S1 * scale * log2 e - lse) needs no further division) and ubar = d2 / d1.
+            // (from the fp32 sums of the unrounded P1, P2 -- see msum1 above)
+            const float fsum1 = halves_sum(vsum1[0] + vsum1[1] + msum1[0] + msum1[1]);
+            const float fsum2 = halves_sum(vsum2[0] + vsum2[1] + msum2[0] + msum2[1]);
             if (h == 0 && my_row < T) {
                 float *st = p.row_stats + (((int64_t)b * p.Hq + hq) * T + my_row) * 2;
-                st[0] = dsum1 > 0.f ? m_ref + log2f(dsum1) : kNegInf;
-                st[1] = dsum2 * inv;
+                st[0] = fsum1 > 0.f ? m_ref + log2f(fsum1) : kNegInf;
+                st[1] = fsum1 > 0.f ? fsum2 / fsum1 : 0.f;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from parity import BF16_REL_L2, host, oracle_decode, oracle_prefill, rel_l2
+from parity import BF16_REL_L2, assert_gradient_close, host, oracle_decode, oracle_prefill, rel_l2
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -108,14 +108,8 @@ def test_random_backward_shapes_with_and_without_window(plx, synth, case):
                                           causal=causal, window=window)
     torch.cuda.synchronize()
     want = pb.backward(*(host(y[n]) for n in "qrkv"), host(g), y["scale"], causal=causal, window=window)
-    # few keys per row: the bf16 rounding of the forward's ubar is not averaged out
-    tol = BF16_REL_L2 * (5 if 0 < window < 4 else 2 if 0 < window < 32 else 1)
     for name, got, ref in zip(("dq", "dr", "dk", "dv"), grads, want):
-        got = host(got)
-        assert np.isfinite(got).all(), name
-        err = np.linalg.norm(got - ref)
-        assert err <= tol * np.linalg.norm(ref) + 1e-3 * np.sqrt(ref.size), (
-            name, err, np.linalg.norm(ref), B, Hq, Hkv, T, extra, d, causal, window)
+        assert_gradient_close(name, host(got), ref, BF16_REL_L2, (B, Hq, Hkv, T, extra, d, causal, window))
 
 
 @pytest.mark.parametrize("case", range(16))
@@ -150,4 +144,4 @@ def test_random_block_masks_and_windows_forward(plx, synth, oracle, case):
         outw = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True, window=W)
         torch.cuda.synchronize()
         refw = oracle.forward(q, r, k, v, y["scale"], causal=True, window=W)
-        assert rel_l2(host(outw), refw) <= BF16_REL_L2 * (2 if W < 32 else 1), (T, extra, d, W)
+        assert rel_l2(host(outw), refw) <= BF16_REL_L2, (T, extra, d, W)
