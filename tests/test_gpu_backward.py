@@ -211,6 +211,24 @@ def test_backward_pair_counts_that_are_multiples_of_eight(plx, synth, bwd_oracle
         _check(plx, synth, bwd_oracle, B, Hq, Hkv, T, Tkv, d, True, seed=2660 + B + T, window=70)
 
 
+def test_backward_config4_launch_against_the_oracle(plx, synth, bwd_oracle):
+    """Benchmark configuration 4 as bench.py launches it (B=4, 16 query / 8 KV heads, T=4096, d=128;
+    the pair count takes the XCD mapping and the heavy-blocks-first order): the gradients of two
+    (batch, KV head) pairs of THAT launch -- dq, dr of the pair's two query heads, dk, dv of its KV
+    head -- against the oracle's, which forms one 4096 x 4096 head at a time."""
+    B, Hq, Hkv, T, d = 4, 16, 8, 4096, 128
+    y, g = _inputs(synth, B, Hq, Hkv, T, T, d, 2680)
+    y["k"] = (y["k"].float() + 0.5 * torch.randn(B, Hkv, 1, d, device=DEV,
+                                                 generator=torch.Generator(DEV).manual_seed(2681))).to(torch.bfloat16)
+    _, _, _, full = _run(plx, y, g, True)
+    for b, hk in ((1, 5), (3, 0)):
+        qs, ks = slice(2 * hk, 2 * hk + 2), slice(hk, hk + 1)
+        want = bwd_oracle.backward(host(y["q"][b:b + 1, qs]), host(y["r"][b:b + 1, qs]), host(y["k"][b:b + 1, ks]),
+                                   host(y["v"][b:b + 1, ks]), host(g[b:b + 1, qs]), y["scale"], causal=True)
+        for name, got, ref, hs in zip(("dq", "dr", "dk", "dv"), full, want, (qs, qs, ks, ks)):
+            assert_gradient_close(name, host(got[b:b + 1, hs]), ref, BF16_REL_L2, (b, hk))
+
+
 def test_backward_config4_launch_equals_its_slices(plx, synth):
     """Benchmark configuration 4 as bench.py launches it (B=4, 16 query / 8 KV heads, T=4096, d=128):
     a workgroup's arithmetic does not depend on which work item it is, so the gradients of one

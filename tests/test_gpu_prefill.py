@@ -170,34 +170,45 @@ def test_chunked_prefill_fp32_and_d64(plx, synth, oracle):
         _run(plx, bad)
 
 
-def _sample_rows(B, Hq, T, n_random, seed, tile=128):
+def _sample_rows(B, Hq, T, n_random, seed, tile=128, edge_batches=2):
+    """Row sample of a large prefill: on EVERY head of the first `edge_batches` batch entries the
+    rows 0..127, the last 128 and every 128-row boundary - 1, +0, +1; one random row of every
+    128-row block of every (batch, head), so that each workgroup of the launch has a compared
+    row; and n_random rows drawn uniformly."""
     rng = np.random.default_rng(seed)
     rows = set()
-    for b in range(B):
-        for h in (0, Hq - 1):
-            for i in list(range(0, 8)) + list(range(T - 8, T)):
+    for b in range(min(edge_batches, B)):
+        for h in range(Hq):
+            for i in list(range(0, min(tile, T))) + list(range(max(T - tile, 0), T)):
                 rows.add((b, h, i))
-    for edge in range(tile, T, max(tile, T // 16 // tile * tile)):
-        for i in (edge - 1, edge, edge + 1, edge - 33, edge + 31):
-            if 0 <= i < T:
-                rows.add((int(rng.integers(B)), int(rng.integers(Hq)), i))
-    while len(rows) < n_random:
+            for edge in range(tile, T, tile):
+                for i in (edge - 1, edge, edge + 1):
+                    if 0 <= i < T:
+                        rows.add((b, h, i))
+    for b in range(B):
+        for h in range(Hq):
+            for blk in range(0, T, tile):
+                rows.add((b, h, int(rng.integers(blk, min(blk + tile, T)))))
+    for _ in range(n_random):
         rows.add((int(rng.integers(B)), int(rng.integers(Hq)), int(rng.integers(T))))
     return np.array(sorted(rows), dtype=np.int32)
 
 
 def test_config4_prefill_bf16_sampled(plx, synth, oracle):
     """benchmark configuration 4: B=4, T=4096, 16/8 heads, d=128, keys offset per (b, kv head) by
-    N(0, 0.5^2); oracle on sampled rows (first/last rows, tile edges, random)."""
+    N(0, 0.5^2), the launch bench.py times; oracle on about 15 000 sampled rows: first and last
+    128 rows and every 128-row boundary +- 1 on all heads of two batch entries, a row of every
+    workgroup, 2048 random rows. Bound over the sample and per row."""
     y = synth.prefill_inputs(4, 16, 8, 4096, 128, seed=1004, device=DEV, k_offset_sigma=0.5)
     got = _run(plx, y)
     assert np.isfinite(got).all()
-    rows = _sample_rows(4, 16, 4096, 700, seed=4)
+    rows = _sample_rows(4, 16, 4096, 2048, seed=4)
+    assert len(rows) >= 2 * 16 * (256 + 3 * 31) + 2048
     ref = oracle_prefill(oracle, y, rows=rows)
     sub = got[rows[:, 0], rows[:, 1], rows[:, 2]]
     assert rel_l2(sub, ref) <= BF16_REL_L2
     per_row = np.linalg.norm(sub - ref, axis=1) / np.linalg.norm(ref, axis=1)
-    assert per_row.max() <= 5e-2
+    assert per_row.max() <= 5e-2, rows[int(per_row.argmax())]
 
 
 def test_config5a_long_prefill_sampled(plx, synth, oracle):
@@ -205,7 +216,7 @@ def test_config5a_long_prefill_sampled(plx, synth, oracle):
     y = synth.prefill_inputs(2, 16, 8, 16384, 128, seed=1005, device=DEV, r_scale=0.1)
     got = _run(plx, y)
     assert np.isfinite(got).all()
-    rows = _sample_rows(2, 16, 16384, 300, seed=5)
+    rows = _sample_rows(2, 16, 16384, 300, seed=5, edge_batches=0)
     ref = oracle_prefill(oracle, y, rows=rows)
     sub = got[rows[:, 0], rows[:, 1], rows[:, 2]]
     assert rel_l2(sub, ref) <= BF16_REL_L2
