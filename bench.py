@@ -30,12 +30,28 @@ HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 PREROLL_SECONDS = 0.06  # untimed load in front of every timed loop (see _preroll)
 
-# HBM bytes per launch of the split-KV kernel on config 2, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE scaled by the same counters on parallax_util_copy of known size
-# (profiles/decode_bf16_config2_hbm_counters.md): 134 897 000 read + 1 081 344 written.
-# Prefill, config 4 (profiles/prefill_bf16_config4_hbm_counters.md): 431 631 000 read + 67 108 864
-# written.
-MEASURED_TRAFFIC_BYTES = {"config2": 135978000, "config4_prefill": 498740000}
+# HBM bytes per launch of the dominant kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled
+# by the same counters on parallax_util_copy of known size: written by
+# `python3 -m paper_2605_29157_amd.profiling traffic ... --out profiles/hbm_traffic.txt` from the
+# counter runs described in profiles/*_hbm_counters.md; a key that is not there reads as null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(key):
+    from paper_2605_29157_amd.profiling import read_traffic_file
+
+    return read_traffic_file(TRAFFIC_FILE).get(key)
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def decode_bytes(B, Hkv, d, lens_sum, Hq):
@@ -163,7 +179,7 @@ def main():
     achieved = step_bytes / (kern_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES["config2"] if is_config2 else None,
+                "traffic": measured_traffic("decode_bf16_config2") if is_config2 else None,
                 "kernel": "decode_bf16_kernel<128,true,false,false>", "kernel_us": round(kern_us, 2),
                 "algorithmic_bytes_per_launch": step_bytes}
 
@@ -208,23 +224,41 @@ def main():
         qh = x["q"].float().cpu().numpy()[:, :, None, :]
         rh = x["r"].float().cpu().numpy()[:, :, None, :]
         kh, vh = x["k"].float().cpu().numpy(), x["v"].float().cpu().numpy()
-        reps, tot = 0, 0.0
-        while tot < 12.0 and reps < 1000:  # about 12 s of oracle work
-            c0 = time.perf_counter()
-            ref = parallax_oracle.forward(qh, rh, kh, vh, x["scale"])
-            tot += time.perf_counter() - c0
-            reps += 1
+
+        def time_oracle(budget_s):
+            reps, tot, ref = 0, 0.0, None
+            while tot < budget_s and reps < 1000:
+                c0 = time.perf_counter()
+                ref = parallax_oracle.forward(qh, rh, kh, vh, x["scale"])
+                tot += time.perf_counter() - c0
+                reps += 1
+            return reps, tot, ref
+
+        n_threads = parallax_oracle.num_threads()
+        reps, tot, ref = time_oracle(10.0)  # about 10 s of oracle work on all host threads
         got = plx.parallax_decode(x["q"], x["r"], x["k"], x["v"], x["scale"], workspace=ws)
         torch.cuda.synchronize()
         err = float(np.linalg.norm(got.float().cpu().numpy()[:, :, None, :] - ref) /
                     np.linalg.norm(ref))
         result["cpu_baseline"] = {
             "value": round(step_bytes / (tot / reps) / 1e9, 3), "unit": "GB/s",
-            "cores": parallax_oracle.num_threads(), "kind": "oracle",
+            "cores": n_threads, "kind": "oracle", "cpu_model": cpu_model(),
             "sample": "the full config-2 batch (8 sequences x 4096 keys), %d passes of the "
-                      "double-precision C oracle, %.2f s each" % (reps, tot / reps),
+                      "double-precision C oracle, %.3f s each" % (reps, tot / reps),
             "gpu_vs_oracle_rel_l2": err,
         }
+        # ... and on one thread (the oracle is OpenMP code: its runtime's own switch, the oracle
+        # itself is not touched)
+        try:
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            reps1, tot1, _ = time_oracle(5.0)
+            gomp.omp_set_num_threads(n_threads)
+            result["cpu_baseline"]["single_thread"] = {
+                "value": round(step_bytes / (tot1 / reps1) / 1e9, 3), "unit": "GB/s", "cores": 1,
+                "sample": "the same batch, %d passes, %.3f s each" % (reps1, tot1 / reps1)}
+        except OSError:
+            pass
 
     # ------------------------------------------------------------------ extra lines
     if not opt.no_extra and is_config2:
@@ -259,7 +293,7 @@ def prefill_line(torch, plx, synth, dev, opt):
                    "algorithmic_flops": flops},
         "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES["config4_prefill"] if is_config4 else None,
+                     "traffic": measured_traffic("prefill_bf16_config4") if is_config4 else None,
                      "kernel": "prefill_bf16_kernel<%d,true,true,false,false,false>" % d,
                      "kernel_us": round(us, 1)},
     }
@@ -574,6 +608,73 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
         sweep.append(row)
         del xs, al
     extra["decode_sweep"] = sweep
+
+    # Few sequences at long context (the region where a step is short enough for launch and ramp
+    # to weigh): B in {1, 8} x L in {8192, 16384, 65536}, fixed and ragged lengths, each next to
+    # the best a plain read kernel does on the same number of bytes on this machine (grids of 256 ...
+    # 4096 workgroups; 256 = one persistent workgroup per compute unit), rotating over a 1.6 GB
+    # buffer so that nothing is found in the Infinity Cache. And config 5b (B = 32, L = 131072).
+    big = torch.empty(1600 << 20, dtype=torch.uint8, device=dev).zero_()
+    floor_cache = {}
+
+    def read_floor_us(nbytes):
+        nbytes = (int(nbytes) + 4095) // 4096 * 4096
+        if nbytes not in floor_cache:
+            span = max(1, (big.numel() - nbytes) // 4096)
+            best = None
+            for wgs in (256, 512, 1024, 2048, 4096):
+                k = [0]
+
+                def rstep():
+                    off = (k[0] * 977 % span) * 4096 if nbytes < big.numel() else 0
+                    plx.parallax_util_read_grid(big[off:], sink, wgs, nbytes=min(nbytes, big.numel()))
+                    k[0] += 1
+
+                us = _time_events(torch, rstep, 5, 60)
+                if best is None or us < best[0]:
+                    best = (us, wgs)
+            floor_cache[nbytes] = best
+        return floor_cache[nbytes]
+
+    small = []
+    for (B, L) in [(1, 8192), (1, 16384), (1, 65536), (8, 8192), (8, 16384), (8, 65536), (32, 131072)]:
+        Hq, Hkv, d = 16, 8, 128
+        per_set = B * Hkv * L * d * 4
+        nset = max(1, min(8, int(2.2e9 // per_set)))
+        for ragged in ((False, True) if L < 131072 else (False,)):
+            xs = [synth.decode_inputs(B, Hq, Hkv, L, d, seed=3400 + i, device=dev, ragged=ragged,
+                                      r_scale=0.1 if L == 131072 else 1.0) for i in range(nset)]
+            o = torch.empty_like(xs[0]["q"])
+            w = torch.empty(plx.parallax_decode_workspace_bytes(B, Hq, Hkv, L, d) // 4,
+                            dtype=torch.float32, device=dev)
+            al = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], o, x["scale"], x.get("seq_lens"), True, 0, w)
+                  for x in xs]
+            c = [0]
+
+            def step():
+                lib.parallax_decode(ctypes.byref(al[c[0] % nset]), sptr)
+                c[0] += 1
+
+            us = _time_events(torch, step, 5, 200 if per_set < 5e8 else 20)
+            byts = sum(decode_bytes(B, Hkv, d, int(x["seq_lens"].sum().item()) if ragged else B * L, Hq)
+                       for x in xs) / nset
+            row = {"B": B, "L": L, "ragged": ragged, "kv_sets": nset,
+                   "num_splits": plx.parallax_decode_num_splits(B, Hq, Hkv, L, d),
+                   "us": round(us, 2), "GBps": round(byts / us / 1e3, 1),
+                   "frac_of_8TBps": round(byts / us / 1e3 / HBM_PEAK_GBPS, 4)}
+            if per_set <= big.numel():
+                f_us, f_wgs = read_floor_us(byts)
+                row["plain_read_same_bytes_us"] = round(f_us, 2)
+                row["plain_read_workgroups"] = f_wgs
+                row["step_over_plain_read"] = round(us / f_us, 3)
+            if L == 131072:
+                row["workload"] = "config5b: decode bf16 B=32 L=131072, R x0.1"
+            small.append(row)
+            del xs, al, o, w
+    extra["decode_few_sequences_long_context"] = small
+    f_us, f_wgs = read_floor_us(decode_bytes(8, 8, 128, 8 * 4096, 16))
+    extra["config2_plain_read_same_bytes"] = {"us": round(f_us, 2), "workgroups": f_wgs}
+    del big
 
     # causal prefill, config 4
     B, T, Hq, Hkv, d = 4, 4096, 16, 8, 128

@@ -21,8 +21,11 @@
  *   - Kernels are enqueued on the caller's hipStream_t (passed as void*, NULL = default
  *     stream). Calls return without synchronising; outputs are valid once the stream
  *     reaches that point.
- *   - Arguments are validated on the host before anything is launched. On any error a
- *     negative plx_status is returned and nothing has been enqueued. No call aborts or throws.
+ *   - Arguments are validated on the host before anything is launched: on a validation error
+ *     (every status but PLX_ERR_LAUNCH) a negative plx_status is returned and nothing has been
+ *     enqueued. PLX_ERR_LAUNCH means the HIP runtime refused a kernel launch; an entry point
+ *     that enqueues several kernels may by then have enqueued the earlier ones, so treat its
+ *     outputs and workspace as undefined. No call aborts or throws.
  *   - GQA: G = Hq / Hkv must be an integer; query head h reads KV head h / G.
  *   - Supported: dtype bf16 (MFMA kernels, d in {64, 128}, G <= 16) and fp32 (plain
  *     correctness kernels, d <= 256). Innermost dimension contiguous; base pointers and
@@ -346,24 +349,6 @@ typedef struct {
 } plx_norm_rope_args;
 
 plx_status parallax_norm_rope(const plx_norm_rope_args *args, void *hip_stream);
-
-/* Plain device-to-device copy kernel (16 bytes per lane, grid-stride). Used to calibrate
- * hardware byte counters and to measure the achievable streaming bandwidth next to the
- * attention kernels. bytes must be a multiple of 16; pointers 16-byte aligned. */
-plx_status parallax_util_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
-
-/* Streams `bytes` from src and writes one 16-byte checksum per workgroup to sink
- * (>= 16 * parallax_util_read_sink_slots() bytes): a read-only bandwidth ceiling. */
-plx_status parallax_util_read(const void *src, size_t bytes, void *sink, void *hip_stream);
-int32_t parallax_util_read_sink_slots(void);
-
-/* Register-only loop of dense bf16 matrix instructions (v_mfma_f32_32x32x16_bf16, eight
- * independent accumulators per wave, no memory or LDS traffic): the matrix throughput the chip
- * sustains on this machine, reported next to the nominal peak. `workgroups` of 4 waves each run
- * `iters` trips of 8 instructions, i.e. workgroups * 4 * iters * 8 * 32768 flops; sink (device,
- * >= workgroups * 1024 bytes, 4-byte aligned) receives one float per lane so that the work
- * cannot be dropped. 1 <= workgroups <= 65536, 1 <= iters <= 2^24. */
-plx_status parallax_util_mfma(int32_t workgroups, int32_t iters, void *sink, void *hip_stream);
 
 const char *parallax_strerror(plx_status status);
 int parallax_version(void);

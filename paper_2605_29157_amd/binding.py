@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "parallax_decode_mla", "parallax_decode_mla_workspace_bytes", "parallax_decode_mla_num_splits",
     "parallax_prefill", "parallax_prefill_backward", "parallax_prefill_backward_workspace_bytes",
     "parallax_norm_rope", "parallax_util_copy", "parallax_util_read",
-    "parallax_util_read_sink_slots", "parallax_util_mfma", "parallax_strerror", "parallax_version",
+    "parallax_util_read_grid", "parallax_util_read_sink_slots", "parallax_util_mfma", "parallax_strerror", "parallax_version",
 )
 
 
@@ -169,6 +169,9 @@ def load_library() -> ctypes.CDLL:
         lib.parallax_util_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                            ctypes.c_void_p]
         lib.parallax_util_read.restype = ctypes.c_int
+        lib.parallax_util_read_grid.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int32,
+                                                ctypes.c_void_p]
+        lib.parallax_util_read_grid.restype = ctypes.c_int
         lib.parallax_decode_mla.argtypes = [ctypes.POINTER(plx_decode_mla_args), ctypes.c_void_p]
         lib.parallax_decode_mla.restype = ctypes.c_int
         lib.parallax_decode_mla_workspace_bytes.argtypes = [ctypes.c_int32] * 2
@@ -569,6 +572,17 @@ def parallax_util_read(src, sink, stream=None):
                                            _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_util_read")
+    return sink
+
+
+def parallax_util_read_grid(src, sink, workgroups, nbytes=None, stream=None):
+    """Plain read of the first nbytes of src (default: all of it) by `workgroups` workgroups."""
+    if nbytes is None:
+        nbytes = src.numel() * src.element_size()
+    st = load_library().parallax_util_read_grid(src.data_ptr(), int(nbytes), sink.data_ptr(), int(workgroups),
+                                                _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_util_read_grid")
     return sink
 
 

@@ -28,9 +28,16 @@ def _hipcc() -> str:
     return exe
 
 
+def _device_asm_path(src: str) -> str:
+    """Device assembly that hipcc leaves next to the object when asked to keep its temporaries."""
+    return os.path.join(BUILD_DIR, os.path.splitext(src)[0] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+
+
 def _compile(src: str, extra: list[str]) -> str:
+    """Compile one source to an object. The intermediate files are kept, so that the assembly
+    checks below read the device code of THIS compile, the one that is linked."""
     obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-c",
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "--save-temps=obj", "-c",
            os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     noise = "is not a recognized feature for this target"
@@ -42,38 +49,27 @@ def _compile(src: str, extra: list[str]) -> str:
     return obj
 
 
-def _check_prefill_assembly(extra: list[str], src: str = "prefill_bf16.hip", m0: bool = True) -> None:  # m0: full check
-    """Emit the device assembly of a prefill kernel file and verify its hand-placed MFMAs."""
+def _check_pipelined_assembly(src: str, full: bool) -> None:
+    """Verify the hand-placed assembly of a kernel file on the device code that was linked."""
     from . import asm_check
-    asm = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".gfx950.s")
-    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-S",
-           "--cuda-device-only", os.path.join(CSRC, src), "-o", asm]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc -S failed on %s:\n%s" % (src, res.stdout))
-    if m0:
+    asm = _device_asm_path(src)
+    if full:  # prefill forward: also its unguarded score MFMAs
         asm_check.check_file(asm)
-    else:  # the backward kernels use guarded assembly MFMAs only (nothing "unguarded" to find)
-        with open(asm) as f:
-            text = f.read()
-        bad = (asm_check.find_early_reads_of_asm_mfma_results(text)
-               + asm_check.find_m0_uses_outside_inline_asm(text)
-               + asm_check.find_foreign_uses_of_asm_loaded_registers(text))
-        if bad:
-            raise RuntimeError("hazard in %s:\n  %s" % (asm, "\n  ".join(bad[:20])))
+        return
+    with open(asm) as f:
+        text = f.read()
+    bad = (asm_check.find_early_reads_of_asm_mfma_results(text)
+           + asm_check.find_m0_uses_outside_inline_asm(text)
+           + asm_check.find_foreign_uses_of_asm_loaded_registers(text))
+    if bad:
+        raise RuntimeError("hazard in %s:\n  %s" % (asm, "\n  ".join(bad[:20])))
 
 
-def _check_decode_assembly(extra: list[str]) -> None:
+def _check_decode_assembly() -> None:
     """The bf16 decode kernel sits at the 256-register limit of two workgroups per compute
     unit; one spilled register costs it 10 %. Fail the build if any decode kernel spills."""
     import re
-    asm = os.path.join(BUILD_DIR, "decode_bf16.gfx950.s")
-    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-S",
-           "--cuda-device-only", os.path.join(CSRC, "decode_bf16.hip"), "-o", asm]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc -S failed on decode_bf16.hip:\n" + res.stdout)
-    with open(asm) as f:
+    with open(_device_asm_path("decode_bf16.hip")) as f:
         text = f.read()
     spills = re.findall(r"\.vgpr_spill_count:\s+(\d+)", text)
     if not spills or any(int(n) for n in spills):
@@ -84,14 +80,12 @@ def build_library(extra_flags: list[str] | None = None, verbose: bool = True) ->
     """Compile every kernel file for gfx950 and link libparallax_hip.so next to this file."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     extra = list(extra_flags or [])
-    with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES) + 3) as pool:
-        checks = [pool.submit(_check_prefill_assembly, extra),
-                  pool.submit(_check_prefill_assembly, extra, "prefill_bwd_bf16.hip", False),
-                  pool.submit(_check_prefill_assembly, extra, "decode_mla_bf16.hip", False),
-                  pool.submit(_check_decode_assembly, extra)]
-        objs = list(pool.map(lambda s: _compile(s, extra), SOURCES))
-        for c in checks:
-            c.result()
+    with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+        objs = list(pool.map(lambda src: _compile(src, extra), SOURCES))
+    _check_pipelined_assembly("prefill_bf16.hip", True)
+    _check_pipelined_assembly("prefill_bwd_bf16.hip", False)
+    _check_pipelined_assembly("decode_mla_bf16.hip", False)
+    _check_decode_assembly()
     tmp = LIB_PATH + ".tmp%d" % os.getpid()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

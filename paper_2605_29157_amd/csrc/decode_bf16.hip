@@ -445,13 +445,16 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     // merges the group's records itself; nobody waits on anybody. The XCDs have private L2
     // caches, and a device-scope release / acquire fence pair would write back and invalidate a
     // whole L2 per workgroup (measured: the step takes four times as long). Instead only the
-    // records travel at device scope: written with device-scope stores above, which the barrier
-    // below waits for (it drains the wave's outstanding stores) before the group's arrival
-    // counter is bumped with a device-scope atomic, and read back with device-scope loads by
-    // the workgroup that reads S - 1. That one also puts the counter back to zero for the next
-    // launch.
+    // records travel at device scope: written with device-scope stores above (written through to
+    // where every XCD sees them), read back with device-scope loads by the workgroup that reads
+    // S - 1 from the group's arrival counter. What orders the record stores before the counter
+    // update is spelled out here, not left to how a workgroup barrier happens to be lowered:
+    // every thread waits until its own stores have been acknowledged (vmcnt counts stores on
+    // this chip), then the barrier collects all threads, then one thread bumps the counter with
+    // a device-scope atomic. The merger also puts the counter back to zero for the next launch.
     if (fused) {
         __shared__ int is_last;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid == 0) {
             const int arrived = __hip_atomic_fetch_add(p.counters + (int64_t)b * p.Hkv + hk, 1,

@@ -63,20 +63,6 @@ __device__ __forceinline__ u32x2 pack4_bf16_accumulate(float p0, float p1, float
 
 }  // namespace
 
-// Timing instrumentation for kernel analysis (off in the product build): wave 0 of workgroup 0 adds
-// up the wall-clock time (10 ns units) between the phase boundaries of its iterations.
-#ifdef PLX_MLA_TIMING
-__device__ unsigned long long plx_mla_stamps[8];
-#define MLA_STAMP(slot)                                  \
-    do {                                                 \
-        const unsigned long long now_ = wall_clock64();  \
-        acc_[slot] += now_ - last_;                      \
-        last_ = now_;                                    \
-    } while (0)
-#else
-#define MLA_STAMP(slot) ((void)0)
-#endif
-
 // PAGED: the cache is a pool of pages behind a block table. A tile that lies inside one page
 // (page size a multiple of 64) is fetched like a tile of a contiguous cache from its page;
 // otherwise every lane looks up the page of its row.
@@ -286,9 +272,6 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         o2[n] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const float scale_log2 = p.scale * kLog2e;
-#ifdef PLX_MLA_TIMING
-    unsigned long long acc_[8] = {0, 0, 0, 0, 0, 0, 0, 0}, last_ = wall_clock64();
-#endif
 
     // One tile: on entry it is in LDS (written by all waves, not yet published); `next` holds the
     // tile after it (in flight or landed), which is written to LDS at the end, and is then
@@ -297,7 +280,6 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
     auto process_tile = [&](int t, u32x4 (&next)[kMlaLoadsPerWave], u32x4 (&fill)[kMlaLoadsPerWave])
                             __attribute__((always_inline)) {
         __syncthreads();  // tile t (and, the first time, the q / rho fragments) are visible
-        MLA_STAMP(0);
         // tile t + 2 sets off now: piece by piece between the matrix instructions if it is complete
         const bool refill = t > t_lo && t + 2 < t_hi;  // (the prologue has requested t_lo + 1 and t_lo + 2)
         const bool spread = refill && tiles_in_pages && (t + 3) * kMlaTileKeys <= Lb;  // workgroup-uniform
@@ -335,7 +317,6 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         }
         s1 += s1b;
         s2 += s2b;
-        MLA_STAMP(1);
 
         // ---- tile maximum of every column, agreed on by the four waves ------------------------
         const int key0 = t * kMlaTileKeys + 16 * w + 4 * g;  // this lane's keys: key0 + i
@@ -348,9 +329,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         }
         tmax = rows_max(tmax);
         if (g == 0) smax[w * 16 + c] = tmax;
-        MLA_STAMP(2);
         __syncthreads();
-        MLA_STAMP(3);
         const float m_tile = fmaxf(fmaxf(smax[c], smax[16 + c]), fmaxf(smax[32 + c], smax[48 + c]));
         const float m_new = fmaxf(m_run, m_tile);
         const float m_use = m_new == kNegInf ? 0.f : m_new;
@@ -376,9 +355,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
             dst[0] = pk1;
             dst[128 * kMlaPvSteps] = pk2;  // P2 follows P1: 64 chunks = 128 half-chunks per k-step
         }
-        MLA_STAMP(4);
         __syncthreads();
-        MLA_STAMP(5);
 
         if (!__all(alpha == 1.f)) {
 #pragma unroll
@@ -414,14 +391,12 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
                 }
             }
         }
-        MLA_STAMP(6);
 
         // ---- everybody is done with tile t: the next one moves in, the one three ahead sets off
         if (t + 1 < t_hi) {
             __syncthreads();
             store_stage(next, t + 2 < t_hi);
         }
-        MLA_STAMP(7);
     };
 
     if (t_lo < t_hi) {
@@ -434,10 +409,6 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         process_tile(t, stg_b, stg_a);
         if (t + 1 < t_hi) process_tile(t + 1, stg_a, stg_b);
     }
-#ifdef PLX_MLA_TIMING
-    if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
-        for (int i = 0; i < 8; ++i) plx_mla_stamps[i] = acc_[i];
-#endif
 
     // ---- row sums over the four waves; write the split partial or the output -----------------
     dsum1 = rows_sum(dsum1);
@@ -479,11 +450,6 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
     }
 }
 
-#ifdef PLX_MLA_TIMING
-extern "C" int parallax_debug_read_mla_stamps(void *host_dst, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(plx_mla_stamps), bytes, 0, hipMemcpyDeviceToHost);
-}
-#endif
 
 hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream) {
     const dim3 grid(p.S, (p.Hq + 15) / 16, p.B);

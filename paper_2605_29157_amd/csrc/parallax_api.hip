@@ -1,9 +1,11 @@
 // C ABI of the Parallax attention library: argument validation, split heuristic, dispatch.
 // Everything is checked on the host before the first launch; no call allocates or synchronises.
 #include "../../include/parallax.h"
+#include "../../include/parallax_util.h"
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "plx_kernels.h"
@@ -40,12 +42,20 @@ plx_status check_common(plx_dtype dtype, int32_t B, int32_t Hq, int32_t Hkv, int
     return PLX_OK;
 }
 
+constexpr int kMaxDevices = 64;
+
+// Compute units of the current device, asked once per device (the split heuristics run on every
+// call). 256 when no device answers.
 int query_num_cus() {
+    static std::atomic<int> cached[kMaxDevices];
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 256;
+    const bool slot = dev >= 0 && dev < kMaxDevices;
+    if (slot && (cus = cached[dev].load(std::memory_order_relaxed)) > 0) return cus;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
         cus <= 0)
         return 256;
+    if (slot) cached[dev].store(cus, std::memory_order_relaxed);
     return cus;
 }
 
@@ -55,7 +65,6 @@ size_t ws_bytes(int64_t B, int64_t Hq, int64_t S, int64_t d) {
 
 // Device address of `scratch` on the current device, looked up once per device (each GPU has
 // its own copy of the array at its own address) and kept for the life of the process.
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 float *g_scratch_ptr[kMaxDevices];
 
@@ -527,6 +536,17 @@ plx_status parallax_util_read(const void *src, size_t bytes, void *sink, void *h
     if (bytes % 16 != 0) return PLX_ERR_SHAPE;
     if (!aligned16(src) || !aligned16(sink)) return PLX_ERR_ALIGN;
     return plx::launch_util_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
+}
+
+plx_status parallax_util_read_grid(const void *src, size_t bytes, void *sink, int32_t workgroups,
+                                   void *hip_stream) {
+    if (!src || !sink) return PLX_ERR_NULL;
+    if (bytes % 16 != 0 || workgroups < 1 || workgroups > plx::kReadSinkSlots) return PLX_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(sink)) return PLX_ERR_ALIGN;
+    return plx::launch_util_read_grid(src, bytes, sink, workgroups, static_cast<hipStream_t>(hip_stream)) ==
+                   hipSuccess
                ? PLX_OK
                : PLX_ERR_LAUNCH;
 }

@@ -107,6 +107,7 @@ hipError_t launch_norm_rope(const NormRopeParams &p, bool f32, hipStream_t strea
 hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream);
 hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);
 hipError_t launch_util_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
+hipError_t launch_util_read_grid(const void *src, size_t bytes, void *sink, int workgroups, hipStream_t stream);
 hipError_t launch_util_mfma(int workgroups, int iters, void *sink, hipStream_t stream);
 constexpr int kReadSinkSlots = 4096;
 

@@ -5,13 +5,6 @@
 
 namespace plx {
 
-// Timing-only ablation switches for kernel analysis (results are wrong when non-zero; every
-// access stays inside the same buffers): 4 = no barrier in the steady-state loop, 8 = no tile
-// loads there, 64 = tile loads without their LDS address updates.
-#ifndef PLX_PF_ABLATE
-#define PLX_PF_ABLATE 0
-#endif
-
 // Tile loads go global -> LDS directly (global_load_lds_dwordx4: LDS address = M0 + 16 * lane).
 // They are emitted as inline assembly: through the compiler builtin, the first LDS read after
 // a tile load waits for that load to land (the compiler assumes every LDS read may alias the
@@ -36,7 +29,8 @@ __device__ __forceinline__ void tile_load16(const void *gptr, uint32_t lds_byte_
             "s_mov_b64 exec, %1\n\t"
             "s_mov_b32 m0, %0"
             : "=&s"(saved_m0), "=&s"(saved_exec)
-            : "v"(gptr), "s"(m0v), "n"((1ull << (LANES % 64)) - 1ull));
+            : "v"(gptr), "s"(m0v), "n"((1ull << (LANES % 64)) - 1ull)
+            : "memory");
     else
         asm volatile(
             "s_mov_b32 %0, m0\n\t"
@@ -44,12 +38,16 @@ __device__ __forceinline__ void tile_load16(const void *gptr, uint32_t lds_byte_
             "global_load_lds_dwordx4 %1, off\n\t"
             "s_mov_b32 m0, %0"
             : "=&s"(saved_m0)
-            : "v"(gptr), "s"(m0v));
+            : "v"(gptr), "s"(m0v)
+            : "memory");
 }
 // Same load with a wave-uniform tile base (scalar registers) plus a 32-bit per-lane byte offset:
-// no per-lane 64-bit address arithmetic. M0 is not restored: nothing the compiler emits for this
-// kernel touches M0 (no other LDS-DMA, no GWS / message / relative-index instructions) -- the
-// build checks that on the generated assembly (asm_check.py).
+// no per-lane 64-bit address arithmetic. The statement writes LDS, hence the memory clobber. M0
+// is left modified and cannot be declared: this compiler treats M0 as a reserved register and
+// answers an "m0" clobber with "may lead to undefined behaviour". What holds instead: nothing
+// the compiler emits for these kernels touches M0 (no other LDS-DMA, no GWS / message /
+// relative-index instructions), and the build verifies exactly that on the generated assembly
+// of every file that includes this header (asm_check.py), failing otherwise.
 template <bool QUARTER = false>
 __device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, const void *tile_base,
                                                     uint32_t lds_byte_addr) {
@@ -62,15 +60,15 @@ __device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, cons
             "global_load_lds_dwordx4 %1, %2\n\t"
             "s_mov_b64 exec, %0"
             : "=&s"(saved_exec)
-            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
-    else if (PLX_PF_ABLATE & 64)  // timing only: every load lands at the same LDS address
-        asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(lane_byte_off), "s"(tile_base));
+            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr)
+            : "memory");
     else
         asm volatile(
             "s_mov_b32 m0, %2\n\t"
             "global_load_lds_dwordx4 %0, %1"
             :
-            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr));
+            : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr)
+            : "memory");
 }
 // Wait until at most PENDING of this wave's tile loads are still in flight (loads complete in
 // issue order), then the workgroup barrier that publishes the landed tiles.

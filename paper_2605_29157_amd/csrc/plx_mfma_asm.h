@@ -13,10 +13,6 @@ namespace plx {
 // handled here: the first read of a finished score block is kept >= 16 issue slots behind its
 // last MFMA (s_nop below; the ISA asks for 11 after an 8-pass MFMA), and operand order is
 // pinned by the scheduling fences of the pipeline.
-#ifndef PLX_PF_ASM_SCORES
-#define PLX_PF_ASM_SCORES 1
-#endif
-
 // An MFMA may not read a register that a vector-ALU instruction wrote less than two wait states
 // before it (the hardware does not interlock this). For MFMAs the compiler knows about it keeps
 // that distance itself; for these statements it cannot, and it does place copies directly in
@@ -27,29 +23,18 @@ namespace plx {
 // acc = A * B (first k-step) and acc += A * B, 32x32x16 bf16, all operands in vector registers.
 template <bool GUARD>
 __device__ __forceinline__ void mfma32_scores_first(f32x16 &acc, u32x4 a, u32x4 b) {
-#if PLX_PF_ASM_SCORES
     // early clobber: the destination block must not share registers with A or B
     if constexpr (GUARD)
         asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
     else
         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0 ; unguarded" : "=&v"(acc) : "v"(a), "a"(b));
-#else
-    f32x16 z;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) z[r] = 0.f;
-    acc = mfma32(a, b, z);
-#endif
 }
 template <bool GUARD>
 __device__ __forceinline__ void mfma32_scores(f32x16 &acc, u32x4 a, u32x4 b) {
-#if PLX_PF_ASM_SCORES
     if constexpr (GUARD)
         asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
     else
         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0 ; unguarded" : "+v"(acc) : "v"(a), "a"(b));
-#else
-    acc = mfma32(a, b, acc);
-#endif
 }
 
 }  // namespace plx

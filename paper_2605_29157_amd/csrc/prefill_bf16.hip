@@ -51,29 +51,6 @@ constexpr int kBC = 64;   // keys per LDS tile
 constexpr int kKB = 32;   // keys per inner block (one MFMA row block)
 
 
-// Row sums d1, d2 of tiles that every row sees completely: per-lane fp32 adds of the unrounded
-// P1 / P2 (1) instead of MFMAs against a matrix of ones over the bf16-rounded values (0).
-#ifndef PLX_PF_VALU_SUMS
-#define PLX_PF_VALU_SUMS 1
-#endif
-
-#ifndef PLX_PF_LOOKAHEAD
-#define PLX_PF_LOOKAHEAD 3  // fragments read ahead of their MFMAs
-#endif
-
-// Timing instrumentation for kernel analysis (off in the product build): wave 0 of every
-// workgroup records wall-clock stamps (10 ns units) at phase boundaries.
-#ifdef PLX_PF_TIMING
-__device__ unsigned long long plx_pf_stamps[8192 * 12];
-#define PLX_STAMP(slot)                                                          \
-    do {                                                                         \
-        if (tid == 0 && blockIdx.x < 8192)                                       \
-            plx_pf_stamps[blockIdx.x * 12 + (slot)] = wall_clock64();            \
-    } while (0)
-#else
-#define PLX_STAMP(slot) ((void)0)
-#endif
-
 
 template <int D, bool USE_R, bool CAUSAL, bool WINDOW, bool STATS = false, bool SPARSE = false>
 __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
@@ -109,13 +86,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     __shared__ u32x4 lds[STAGES * STAGE_CHUNKS + 4 * WAVE_TILE_CHUNKS];  // [stage][K tile | V tile], Q
 
     const int tid = threadIdx.x;
-    PLX_STAMP(0);
-#ifdef PLX_PF_TIMING
-    if (tid == 0 && blockIdx.x < 8192) {
-        plx_pf_stamps[blockIdx.x * 12 + 10] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);   // HW_ID
-        plx_pf_stamps[blockIdx.x * 12 + 11] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20);  // XCC_ID
-    }
-#endif
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int col = lane & 31;  // MFMA column: query row within the wave's 32 rows
     const int h = lane >> 5;    // half-wave
@@ -151,9 +121,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const int off = Tk - T;               // causal: row i sits at key position i + off
     const int b = pair / p.Hkv, hk = pair - b * p.Hkv;
     const int hq = hk * G + hg;
-#ifdef PLX_PF_TIMING
-    if (hq >= 0) PLX_STAMP(9);
-#endif
 
     const int row0 = rb * kBR + w * 32;  // first query row of this wave
     const int my_row = row0 + col;       // this lane's query row (may be >= T)
@@ -456,7 +423,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // Every fragment slot issues the LDS read of the fragment needed kLookAhead fragments later
     // ([K of next block | V^T of current block | K of the block after]). The scheduling fences
     // keep this order.
-    constexpr int kLookAhead = PLX_PF_LOOKAHEAD;
+    constexpr int kLookAhead = 3;  // fragments read ahead of their MFMAs
     static_assert(2 * NDB == KSTEPS, "as many V^T fragments as K fragments per key block");
     u32x4 kf[KSTEPS], vt[KSTEPS];
     auto k_block_ptr = [&](int stage, int kb) {
@@ -633,10 +600,8 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         for (int t = 0; t < kDist; ++t) dma_tile(t, t);
     }
     zero_state();
-    PLX_STAMP(1);
     static_assert(kDist == 2, "the wait below leaves exactly tile 1 in flight");
     tile_barrier<kTileLoads>();  // Q, R and tile 0 have landed
-    PLX_STAMP(2);
     {
         // B operands: column = query row, k-elements = the 8 dims of chunk 2*ks + h
         const u32x4 *zq = lds + QZONE + w * WAVE_TILE_CHUNKS + col * KROW + h;
@@ -681,7 +646,6 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         pb1[0] = pack_group(sa1, 0);
         if constexpr (USE_R) pb2[0] = pack_group(sa2, 0);
     }
-    PLX_STAMP(3);
     // kt: key tile in `stage`, kt_next: key tile in `next_stage` (kt + 1 unless block-sparse)
     auto tile_steps = [&](auto masked_tag, auto dma_tag, int kt, int kt_next, int stage, int next_stage) {
         // block (kt,0) -> P, PV; scores of (kt,1); K fragments of (kt_next,0); loads of the tile after
@@ -719,7 +683,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
         const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;  // held tile kt - 1
         // tile kt + 1 has landed; the kDist - 2 tiles after it may still be in flight
-        if (!(PLX_PF_ABLATE & 4)) tile_barrier<(kDist - 2) * kTileLoads>();
+        tile_barrier<(kDist - 2) * kTileLoads>();
         dma_dk = stage_k_addr(free_stage);  // tile kt + kDist <= T/64 - 1 in this loop: complete
         dma_dv = stage_v_addr(free_stage);
         if constexpr (SPARSE) {
@@ -728,21 +692,15 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             dma_tk = (const char *)kbase + k2 * k_tile_bytes;
             dma_tv = (const char *)vbase + k2 * v_tile_bytes;
         }
-        if (PLX_PF_ABLATE & 8)
-            tile_steps(std::false_type{}, std::false_type{}, tile_at(kt), tile_at(kt + 1), stage, next_stage);
-        else
-            tile_steps(std::false_type{}, std::true_type{}, tile_at(kt), tile_at(kt + 1), stage, next_stage);
+        tile_steps(std::false_type{}, std::true_type{}, tile_at(kt), tile_at(kt + 1), stage, next_stage);
         if constexpr (!SPARSE) {
             dma_tk += k_tile_bytes;
             dma_tv += v_tile_bytes;
         }
         stage = next_stage;
     }
-    PLX_STAMP(4);
     // Remaining tiles (diagonal / tail): the same pipeline with per-lane key masks.
     for (; kt < n_tiles; ++kt) masked_tile(kt);
-
-    PLX_STAMP(5);
     // overflow check: any inf/NaN in the sums means the fixed reference was too small
     float chk = dacc1[0] * 0.f + dacc2[0] * 0.f + (vsum1[0] + vsum1[1]) * 0.f + (vsum2[0] + vsum2[1]) * 0.f;
 #pragma unroll
@@ -762,10 +720,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // tile loads past the end have landed
     const bool overflow = __syncthreads_or(chk != 0.f);  // NaN != 0 is true; all waves agree
-    PLX_STAMP(6);
 
     // =========================== fallback: online max / rescale ============================
-    if (overflow && !PLX_PF_ABLATE) {
+    if (overflow) {
         zero_state();
         vsum1[0] = vsum1[1] = vsum2[0] = vsum2[1] = 0.f;
         msum1[0] = msum1[1] = msum2[0] = msum2[1] = 0.f;
@@ -887,18 +844,8 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             }
         }
     }
-    PLX_STAMP(7);
-#ifdef PLX_PF_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    PLX_STAMP(8);
-#endif
 }
 
-#ifdef PLX_PF_TIMING
-extern "C" int parallax_debug_read_prefill_stamps(void *host_dst, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(plx_pf_stamps), bytes, 0, hipMemcpyDeviceToHost);
-}
-#endif
 
 template <int D>
 static hipError_t launch_prefill_d(const PrefillParams &p, hipStream_t stream) {

@@ -483,7 +483,6 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int col = lane & 31, h = lane >> 5;
     const int T = p.T, Tk = p.Tk, off = Tk - T, G = p.G;
-    const int ncb = (Tk + 127) / 128;
     // Work item: the key block is the slowest index (causal: low key blocks see the most rows;
     // all of them come first, over every batch entry and head -- with the key block as the
     // fastest index the tail of the pass cost a quarter of it); (batch, kv head) pairs by

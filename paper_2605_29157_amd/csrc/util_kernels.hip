@@ -35,6 +35,29 @@ __global__ __launch_bounds__(256) void util_read_kernel(const u32x4 *src, size_t
     }
 }
 
+// The same stream with a chosen grid and eight 16-byte loads per lane in flight (32 KB per
+// workgroup and trip): few fat workgroups (one per compute unit) up to many thin ones.
+__global__ __launch_bounds__(256) void util_read_grid_kernel(const u32x4 *src, size_t n, u32x4 *sink) {
+    const size_t stride = (size_t)gridDim.x * 2048;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    u32x4 acc = zero;
+    for (size_t i = (size_t)blockIdx.x * 2048 + threadIdx.x; i < n; i += stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = i + 256 * j < n ? src[i + 256 * j] : zero;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j];
+    }
+    __shared__ u32x4 part[256];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32x4 t = zero;
+        for (int j = 0; j < 256; ++j) t ^= part[j];
+        sink[blockIdx.x] = t;
+    }
+}
+
 // Eight independent accumulation chains per wave: an MFMA never waits for the one before it, so
 // one wave per SIMD keeps the matrix pipe full. Operands are fixed pseudo-random bf16 values in
 // (-1, 1) (all-zero operands would draw less power than real data and flatter the clock).
@@ -92,6 +115,12 @@ hipError_t launch_util_read(const void *src, size_t bytes, void *sink, hipStream
     const size_t n = bytes / 16;
     hipLaunchKernelGGL(util_read_kernel, dim3(kReadSinkSlots), dim3(256), 0, stream,
                        (const u32x4 *)src, n, (u32x4 *)sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_util_read_grid(const void *src, size_t bytes, void *sink, int workgroups, hipStream_t stream) {
+    hipLaunchKernelGGL(util_read_grid_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream,
+                       (const u32x4 *)src, bytes / 16, (u32x4 *)sink);
     return hipGetLastError();
 }
 

@@ -22,9 +22,14 @@ def binding():
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "parallax.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(parallax_\w+)\s*\(", text)))
+    """Every function declared by the headers under include/ (the attention ABI and the
+    measurement helpers)."""
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(parallax_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported(binding):
