@@ -701,22 +701,51 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     }
     // Remaining tiles (diagonal / tail): the same pipeline with per-lane key masks.
     for (; kt < n_tiles; ++kt) masked_tile(kt);
-    // overflow check: any inf/NaN in the sums means the fixed reference was too small
-    float chk = dacc1[0] * 0.f + dacc2[0] * 0.f + (vsum1[0] + vsum1[1]) * 0.f + (vsum2[0] + vsum2[1]) * 0.f;
+    // ---- closing formula into the wave's staging tile, and the check of the fast pass -------
+    // O^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4 of row my_row. A lane owns one
+    // output ROW, so direct stores would scatter 8 bytes over 32 rows per instruction; the wave
+    // instead transposes its 32 x D tile through LDS (its Q landing zone, which nobody else
+    // touches) and later writes whole 256-byte rows, 16 bytes a lane.
+    // The same pass over the accumulators decides whether the fixed reference held: an inf / NaN
+    // anywhere in the sums or accumulators (the reference was too small) shows as a non-finite
+    // row sum or output. Only then the workgroup redoes its rows with the online update below
+    // and comes back here once more.
+    constexpr int OROW = CPR + 1;  // padded row of the staging tile, in 16-byte chunks
+    static_assert(OROW == KROW, "the staging tile is the wave's Q tile");
+    u32x4 *otile = lds + QZONE + w * WAVE_TILE_CHUNKS;
+    unsigned short *otile16 = (unsigned short *)otile;
+    float inv = 0.f, dsum1 = 0.f;
+    auto stage_outputs = [&]() {
+        // Every row of the MFMA row-sum accumulators holds the sum over this lane's query row;
+        // the vector partial sums cover this lane's keys only: add the other half-wave's.
+        dsum1 = dacc1[0] + halves_sum(vsum1[0] + vsum1[1]);
+        const float dsum2 = dacc2[0] + halves_sum(vsum2[0] + vsum2[1]);
+        inv = dsum1 > 0.f ? 1.f / dsum1 : 0.f;  // empty key set: zeros
+        const float gain = inv * (1.f + dsum2 * inv);
+        float chk = (dsum1 + dsum2) * 0.f;  // inf or NaN -> NaN
 #pragma unroll
-    for (int n = 0; n < NDB; ++n)
+        for (int n = 0; n < NDB; ++n)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            chk = fmaf(o1[n][r], 0.f, chk);
-            if constexpr (USE_R) chk = fmaf(o2[n][r], 0.f, chk);
-        }
+            for (int q4 = 0; q4 < 4; ++q4) {
+                float y[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int r = 4 * q4 + i;
+                    y[i] = o1[n][r] * gain - (USE_R ? o2[n][r] * inv : 0.f);
+                    chk = fmaf(y[i], 0.f, chk);
+                }
+                const u32x2 packed = {pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
+                *(u32x2 *)(otile16 + col * (OROW * 8) + 32 * n + 8 * q4 + 4 * h) = packed;
+            }
+        return chk;
+    };
+    float chk = stage_outputs();
     if constexpr (WINDOW || SPARSE) {
         // the reference of a row may come from keys outside its window; if it was so far above
         // the row's own scores that the sum underflowed, take the exact path as well
         // (block-sparse: only for rows that do see a listed key -- the list is ascending, so that
         // is decided by its first tile)
-        const float d1 = dacc1[0] + halves_sum(vsum1[0] + vsum1[1]);
-        if (my_row < T && (!SPARSE || tile_at(0) * kBC <= row_lim) && !(d1 > 1e-30f)) chk = 1.f;
+        if (my_row < T && (!SPARSE || tile_at(0) * kBC <= row_lim) && !(dsum1 > 1e-30f)) chk = 1.f;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // tile loads past the end have landed
     const bool overflow = __syncthreads_or(chk != 0.f);  // NaN != 0 is true; all waves agree
@@ -767,37 +796,11 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             stage = next_stage;
         }
         tile_barrier();  // outstanding tile loads land before the workgroup may exit
+        (void)stage_outputs();
     }
 
-    // ---- epilogue: O^T register r of block n <-> dim 32n + 8*(r/4) + 4h + r%4, row my_row ----
-    // Every row of the row-sum accumulators holds the sum over all keys of this lane's query
-    // row. A lane owns one output ROW, so direct stores would scatter 8 bytes over 32 rows per
-    // instruction; the wave instead transposes its 32 x D tile through LDS (all tile loads have
-    // landed, every wave is past its last read) and writes whole 256-byte rows, 16 bytes a lane.
+    // ---- epilogue: the staged rows go out as whole rows ------------------------------------
     {
-        // Every row of the MFMA row-sum accumulators holds the sum over this lane's query row;
-        // the vector partial sums cover this lane's keys only: add the other half-wave's.
-        const float dsum1 = dacc1[0] + halves_sum(vsum1[0] + vsum1[1]);
-        const float dsum2 = dacc2[0] + halves_sum(vsum2[0] + vsum2[1]);
-        const float inv = dsum1 > 0.f ? 1.f / dsum1 : 0.f;  // empty key set: zeros
-        const float gain = inv * (1.f + dsum2 * inv);
-        constexpr int OROW = CPR + 1;  // padded row of the staging tile, in 16-byte chunks
-        static_assert(OROW == KROW, "the staging tile is the wave's Q tile");
-        u32x4 *otile = lds + QZONE + w * WAVE_TILE_CHUNKS;
-        unsigned short *otile16 = (unsigned short *)otile;
-#pragma unroll
-        for (int n = 0; n < NDB; ++n)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                float y[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int r = 4 * q4 + i;
-                    y[i] = o1[n][r] * gain - (USE_R ? o2[n][r] * inv : 0.f);
-                }
-                const u32x2 packed = {pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
-                *(u32x2 *)(otile16 + col * (OROW * 8) + 32 * n + 8 * q4 + 4 * h) = packed;
-            }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
