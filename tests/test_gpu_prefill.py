@@ -85,6 +85,45 @@ def test_large_logit_range_takes_the_safe_path(plx, synth, oracle, gain, causal)
     assert rel_l2(got, ref) <= BF16_REL_L2
 
 
+@pytest.mark.parametrize("T,Tkv,causal,window", [(1, 1, True, 0), (31, 31, True, 0), (255, 255, True, 0),
+                                                   (256, 256, True, 0), (257, 257, True, 0), (300, 300, False, 0),
+                                                   (513, 513, True, 0), (1100, 1100, True, 0), (200, 777, True, 0),
+                                                   (5, 600, True, 0), (130, 515, False, 0), (700, 700, True, 1),
+                                                   (700, 700, True, 40), (520, 1500, True, 300)])
+def test_head_dim_64_two_row_sub_blocks_per_wave(plx, synth, oracle, T, Tkv, causal, window):
+    """d = 64 runs 64 query rows per wave (256 per workgroup): lengths around and far from
+    multiples of 256, chunks behind a cache, windows, the softmax-only twin, the online-rescale
+    pass, and the row cache written by the same kernel family."""
+    from oracle import parallax_backward as pb
+
+    y = synth.prefill_inputs(2, 4, 2, Tkv, 64, seed=860 + T + window, device=DEV, k_offset_sigma=0.5)
+    y["q"], y["r"] = y["q"][:, :, Tkv - T:].contiguous(), y["r"][:, :, Tkv - T:].contiguous()
+    q, r, k, v = (host(y[n]) for n in "qrkv")
+    ref = oracle.forward(q, r, k, v, y["scale"], causal=causal, window=window)
+    got = host(plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=causal, window=window))
+    assert rel_l2(got, ref) <= BF16_REL_L2
+    ref0 = oracle.forward(q, np.zeros_like(r), k, v, y["scale"], causal=causal, window=window)
+    got0 = host(plx.parallax_prefill(y["q"], None, y["k"], y["v"], y["scale"], causal=causal, window=window, use_r=False))
+    assert rel_l2(got0, ref0) <= BF16_REL_L2
+    # row cache: same output bits, vbar / ubar / log-sum-exp against the definition
+    o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=causal, window=window,
+                                          save_for_backward=True)
+    np.testing.assert_array_equal(host(o), got)
+    _, vb, ub, lw = pb.forward_with_cache(q, r, k, v, y["scale"], causal=causal, window=window)
+    assert rel_l2(host(vbar), vb) <= BF16_REL_L2
+    np.testing.assert_allclose(host(stats)[..., 0], lw * 1.4426950408889634, rtol=0, atol=2e-2)
+    assert np.linalg.norm(host(stats)[..., 1] - ub) <= BF16_REL_L2 * np.linalg.norm(ub) + 1e-6
+    # scores spread over hundreds of binades: the fixed reference overflows, the online pass takes over
+    if window == 0:
+        big = dict(y)
+        big["q"] = (y["q"].float() * 30.0).to(torch.bfloat16)
+        big["k"] = (y["k"].float() * torch.linspace(0.2, 3.0, Tkv, device=DEV).view(1, 1, Tkv, 1)).to(torch.bfloat16)
+        refb = oracle.forward(host(big["q"]), r, host(big["k"]), v, y["scale"], causal=causal)
+        gotb = host(plx.parallax_prefill(big["q"], y["r"], big["k"], y["v"], y["scale"], causal=causal))
+        assert np.isfinite(gotb).all()
+        assert rel_l2(gotb, refb) <= BF16_REL_L2
+
+
 def test_scale_zero_is_uniform_weighting(plx, synth, oracle):
     """scale = 0 is the wide-bandwidth limit (uniform softmax weights)."""
     y = synth.prefill_inputs(1, 4, 2, 260, 128, seed=821, device=DEV, r_scale=0.2)
