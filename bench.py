@@ -762,7 +762,32 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
     extra["norm_rope"] = {"workload": "RMSNorm + RoPE on q, rho [4,16,4096,128] and k [4,8,4096,128] bf16, one launch",
                           "us": round(us, 1), "GBps": round(nbytes / us / 1e3, 1),
                           "frac_of_8TBps": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
-    del y, outs
+    # the same preparation of q and rho inside the prefill kernel (k alone goes through the
+    # launch above): bare prefill on prepared inputs / the two-launch chain / fused
+    po = torch.empty_like(y["q"])
+    table = plx.parallax_rope_table(T, d, device=dev)
+    na_k = plx.norm_rope_args([(y["k"], gam[2], True, outs[2])])
+    a_bare = plx.prefill_args(outs[0], outs[1], outs[2], y["v"], po, y["scale"], True, True)
+    a_fused = plx.prefill_args(y["q"], y["r"], outs[2], y["v"], po, y["scale"], True, True)
+    a_fused.prep = plx.qr_prep(gam[0], gam[1], table, None)
+
+    def call(fn, args):
+        st = fn(ctypes.byref(args), sptr)
+        if st != 0:
+            raise plx.ParallaxError(st, "fused preparation")
+
+    variants = {"prefill_on_prepared_inputs_us": lambda: call(lib.parallax_prefill, a_bare),
+                "norm_rope_qrk_then_prefill_us": lambda: (call(lib.parallax_norm_rope, na), call(lib.parallax_prefill, a_bare)),
+                "norm_rope_k_then_prefill_preparing_q_rho_us": lambda: (call(lib.parallax_norm_rope, na_k),
+                                                                        call(lib.parallax_prefill, a_fused)),
+                "prefill_preparing_q_rho_us": lambda: call(lib.parallax_prefill, a_fused)}
+    fz = {"workload": "config-4 shape [4,16/8,4096,128] bf16 causal; RMSNorm + RoPE (theta 1e6) on q, rho, k"}
+    for name, fn in variants.items():
+        fz[name] = round(_time_events(torch, fn, 3, 20), 1)
+    fz["in_kernel_preparation_over_bare_prefill"] = round(
+        fz["prefill_preparing_q_rho_us"] / fz["prefill_on_prepared_inputs_us"] - 1.0, 4)
+    extra["norm_rope_fused_into_prefill"] = fz
+    del y, outs, po
 
     # sliding window (a row sees its own position and the window - 1 before it)
     win = []

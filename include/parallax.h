@@ -61,6 +61,32 @@ typedef enum {
 #define PLX_STATIC_SCRATCH_RECORDS 16384
 
 /*
+ * RMSNorm + RoPE on the raw q and rho rows INSIDE the attention kernels (the paper's language-model
+ * runs apply both in front of the attention call: Sec. 5 experiment setup, backbone appendix;
+ * formulas as for parallax_norm_rope below): the rows are normalised, rotated and rounded to bf16 in
+ * the kernel's prologue, so q and rho make no extra trip through HBM. K is prepared beforehand by
+ * parallax_norm_rope (it is shared by all query heads and row blocks). bf16 only.
+ *   q_gamma, r_gamma  [d] fp32 on the device: RMSNorm weights; both non-NULL switches the
+ *                     preparation on (r_gamma may be NULL when use_r == 0)
+ *   eps               >= 0, under the root
+ *   rope_table        NULL = RMSNorm only, else [rope_positions, d/2, 2] fp32 from
+ *                     parallax_rope_table: (cos, sin) of pos * theta^(-2i/d)
+ *   rope_q, rope_r    rotate q / rho (the paper: RoPE on q, k, optionally on rho)
+ *   pos0              [B] int32 on the device or NULL (= 0): position of query row 0 of each
+ *                     sequence (prefill: row i sits at pos0[b] + i; decode: NULL means the rows
+ *                     are the last Tq positions, L_b - Tq + t, else pos0[b] + t); positions are
+ *                     clamped to the table
+ */
+typedef struct {
+    const float *q_gamma, *r_gamma;
+    const float *rope_table;
+    const int32_t *pos0;
+    int32_t rope_positions;
+    int32_t rope_q, rope_r;
+    float eps;
+} plx_qr_prep;
+
+/*
  * Single-step decode (Algorithm 1 with one query row per head, Sec. 3.3; split-KV and merge,
  * App. C). The KV cache already contains the current token: key j of sequence b is allowed
  * iff j < L_b, L_b = seq_lens[b] (or Lmax when seq_lens is NULL).
@@ -119,6 +145,7 @@ typedef struct {
     int32_t Tq; /* query rows per sequence; 0 or 1 = one */
     int32_t window; /* sliding window in keys; 0 = none */
     int32_t *split_counters; /* parallax_decode_fused only: B*Hkv int32 on the device */
+    plx_qr_prep prep; /* RMSNorm + RoPE on q, rho as they are loaded; all zero = q, rho used as given */
 } plx_decode_args;
 
 /* Bytes of workspace that is enough for any split count the library may pick or accept
@@ -232,6 +259,9 @@ typedef struct {
     const int32_t *sparse_row_ptr;
     const int32_t *sparse_tile_idx;
     int32_t sparse_batch, sparse_heads;
+    /* RMSNorm + RoPE on q, rho in the kernel's prologue (bf16, use_r, dense, no window, no row
+     * cache); all zero = q, rho used as given */
+    plx_qr_prep prep;
 } plx_prefill_args;
 
 plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
@@ -349,6 +379,12 @@ typedef struct {
 } plx_norm_rope_args;
 
 plx_status parallax_norm_rope(const plx_norm_rope_args *args, void *hip_stream);
+
+/* The rotation table of plx_qr_prep: table[(pos * d/2 + i) * 2 + {0, 1}] = cos, sin of
+ * pos * theta^(-2i/d) for pos in [0, n_pos), i in [0, d/2) -- the angle reduced modulo 2 pi in double
+ * precision, as parallax_norm_rope does. fp32 on the device, 16-byte aligned, n_pos * d floats;
+ * d even, 2 <= d <= 256; theta > 1. Computed once per (d, theta, longest context). */
+plx_status parallax_rope_table(float *table, int32_t n_pos, int32_t d, float theta, void *hip_stream);
 
 const char *parallax_strerror(plx_status status);
 int parallax_version(void);

@@ -140,6 +140,47 @@ def find_early_reads_of_asm_mfma_results(asm_text: str) -> list[str]:
     return bad
 
 
+DOT_RESULT_WAIT_STATES = 3  # a dot-product result may be read by a different instruction after 3
+
+
+def find_early_reads_of_asm_dot_results(asm_text: str) -> list[str]:
+    """The packed dot products (v_dot2c_f32_bf16) are written as inline assembly, so the compiler
+    does not know that their result needs DOT_RESULT_WAIT_STATES wait states before any other
+    vector instruction may read it (the next dot product of the same accumulation chain, which
+    takes it as its addend, is exempt). Verify that on the generated code."""
+    instrs = []
+    inside = False
+    for n, line in enumerate(asm_text.splitlines(), 1):
+        t = line.strip()
+        if t.startswith(";;#ASMSTART"):
+            inside = True
+        elif t.startswith(";;#ASMEND"):
+            inside = False
+        elif _is_instruction(line):
+            instrs.append((n, t.split(";")[0].strip(), inside))
+    bad = []
+    for i, (n, ins, inside) in enumerate(instrs):
+        if not (inside and ins.startswith("v_dot2c")):
+            continue
+        ops = ins.split(None, 1)[1].split(",")
+        dst = _regs(ops[0])
+        states = 0
+        for pn, nxt, _ in instrs[i + 1:]:
+            if states >= DOT_RESULT_WAIT_STATES or nxt.endswith(":") or nxt.startswith("s_endpgm"):
+                break
+            parts = nxt.split(None, 1)
+            if len(parts) == 2 and not parts[0].startswith("s_"):
+                nops = parts[1].split(",")
+                if parts[0].startswith("v_dot2c") and _regs(nops[0]) == dst and not any(_regs(o) & dst for o in nops[1:]):
+                    break  # the chain goes on: its end is checked from there
+                if any(_regs(o) & dst for o in nops):
+                    bad.append("line %d: '%s' touches the result of the assembly dot product at line %d after "
+                               "only %d wait states" % (pn, nxt, n, states))
+                    break
+            states += _wait_states(nxt)
+    return bad
+
+
 def find_foreign_uses_of_asm_loaded_registers(asm_text: str) -> list[str]:
     """Registers that inline-assembly global loads write may hold data that is still on its way;
     only the inline assembly that waits for it (s_waitcnt) may touch them. Between the first such
@@ -183,6 +224,6 @@ def check_file(path: str) -> None:
     with open(path) as f:
         text = f.read()
     bad = (find_violations(text) + find_m0_uses_outside_inline_asm(text)
-           + find_early_reads_of_asm_mfma_results(text))
+           + find_early_reads_of_asm_mfma_results(text) + find_early_reads_of_asm_dot_results(text))
     if bad:
         raise RuntimeError("MFMA source hazard in %s:\n  %s" % (path, "\n  ".join(bad[:20])))

@@ -26,9 +26,15 @@ EXPORTED_SYMBOLS = (
     "parallax_decode_static", "parallax_decode_static_scratch_bytes",
     "parallax_decode_mla", "parallax_decode_mla_workspace_bytes", "parallax_decode_mla_num_splits",
     "parallax_prefill", "parallax_prefill_backward", "parallax_prefill_backward_workspace_bytes",
-    "parallax_norm_rope", "parallax_util_copy", "parallax_util_read",
+    "parallax_norm_rope", "parallax_rope_table", "parallax_util_copy", "parallax_util_read",
     "parallax_util_read_grid", "parallax_util_read_sink_slots", "parallax_util_mfma", "parallax_strerror", "parallax_version",
 )
+
+
+class plx_qr_prep(ctypes.Structure):
+    _fields_ = [("q_gamma", ctypes.c_void_p), ("r_gamma", ctypes.c_void_p), ("rope_table", ctypes.c_void_p),
+                ("pos0", ctypes.c_void_p), ("rope_positions", ctypes.c_int32), ("rope_q", ctypes.c_int32),
+                ("rope_r", ctypes.c_int32), ("eps", ctypes.c_float)]
 
 
 class plx_decode_args(ctypes.Structure):
@@ -52,6 +58,7 @@ class plx_decode_args(ctypes.Structure):
         ("Tq", ctypes.c_int32),
         ("window", ctypes.c_int32),
         ("split_counters", ctypes.c_void_p),
+        ("prep", plx_qr_prep),
     ]
 
 
@@ -74,6 +81,7 @@ class plx_prefill_args(ctypes.Structure):
         ("vbar", ctypes.c_void_p), ("row_stats", ctypes.c_void_p),
         ("sparse_row_ptr", ctypes.c_void_p), ("sparse_tile_idx", ctypes.c_void_p),
         ("sparse_batch", ctypes.c_int32), ("sparse_heads", ctypes.c_int32),
+        ("prep", plx_qr_prep),
     ]
 
 
@@ -163,6 +171,9 @@ def load_library() -> ctypes.CDLL:
         lib.parallax_prefill_backward_workspace_bytes.restype = ctypes.c_size_t
         lib.parallax_norm_rope.argtypes = [ctypes.POINTER(plx_norm_rope_args), ctypes.c_void_p]
         lib.parallax_norm_rope.restype = ctypes.c_int
+        lib.parallax_rope_table.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                            ctypes.c_void_p]
+        lib.parallax_rope_table.restype = ctypes.c_int
         lib.parallax_util_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                            ctypes.c_void_p]
         lib.parallax_util_copy.restype = ctypes.c_int
@@ -212,6 +223,37 @@ def _stream_ptr(stream) -> int:
     return int(stream.cuda_stream)
 
 
+def parallax_rope_table(n_pos, d, theta=1.0e6, device="cuda:0", stream=None):
+    """(cos, sin) of pos * theta^(-2i/d): fp32 tensor [n_pos, d/2, 2] for qr_prep()."""
+    table = torch.empty(n_pos, d // 2, 2, dtype=torch.float32, device=device)
+    st = load_library().parallax_rope_table(table.data_ptr(), int(n_pos), int(d), float(theta), _stream_ptr(stream))
+    if st != PLX_OK:
+        raise ParallaxError(st, "parallax_rope_table")
+    return table
+
+
+def qr_prep(q_gamma, r_gamma, rope_table=None, pos0=None, rope_q=True, rope_r=True, eps=1e-6):
+    """Fill a plx_qr_prep (RMSNorm + RoPE on q, rho inside the attention kernels) from tensors. The
+    returned struct only holds pointers: keep the tensors alive until the call has been enqueued."""
+    a = plx_qr_prep()
+    for g in (q_gamma, r_gamma):
+        if g is not None and (g.dtype != torch.float32 or not g.is_cuda or not g.is_contiguous()):
+            raise TypeError("RMSNorm weights must be contiguous fp32 device tensors")
+    a.q_gamma = q_gamma.data_ptr()
+    a.r_gamma = r_gamma.data_ptr() if r_gamma is not None else None
+    if rope_table is not None:
+        if rope_table.dtype != torch.float32 or not rope_table.is_contiguous():
+            raise TypeError("rope_table must be a contiguous fp32 tensor [n_pos, d/2, 2]")
+        a.rope_table, a.rope_positions = rope_table.data_ptr(), rope_table.shape[0]
+        a.rope_q, a.rope_r = (1 if rope_q else 0), (1 if rope_r else 0)
+    if pos0 is not None:
+        if pos0.dtype != torch.int32:
+            raise TypeError("pos0 must be int32")
+        a.pos0 = pos0.data_ptr()
+    a.eps = float(eps)
+    return a
+
+
 def parallax_decode_workspace_bytes(B, Hq, Hkv, Lmax, d) -> int:
     return int(load_library().parallax_decode_workspace_bytes(B, Hq, Hkv, Lmax, d))
 
@@ -257,7 +299,7 @@ def decode_args(q, r, k, v, out, scale, seq_lens=None, use_r=True, num_splits=0,
 
 def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, workspace=None,
                     out=None, stream=None, block_table=None, max_len=None, split_counters=None,
-                    window=0):
+                    window=0, prep=None):
     """Single-step Parallax decode. Allocates `out` / `workspace` with torch when not given
     (allocation only; all arithmetic is in the library). With `split_counters` (zeroed int32
     device tensor, >= B * Hkv entries) the call goes to parallax_decode_fused: one launch, the
@@ -289,6 +331,8 @@ def parallax_decode(q, r, k, v, scale, seq_lens=None, use_r=True, num_splits=0, 
                                     device=q.device)
     a = decode_args(q, r, k, v, out, scale, seq_lens, use_r, num_splits, workspace, block_table,
                     max_len, window)
+    if prep is not None:
+        a.prep = prep
     entry = "parallax_decode"
     if split_counters is not None:
         if (split_counters.dtype != torch.int32 or not split_counters.is_cuda
@@ -392,7 +436,7 @@ def block_mask_lists(block_mask):
 
 
 def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None, window=0,
-                     save_for_backward=False, block_mask=None):
+                     save_for_backward=False, block_mask=None, prep=None):
     """Parallax prefill forward over T query rows and Tkv keys (causal: the rows are the last
     T positions of the Tkv-long sequence). With save_for_backward the kernel also writes the row
     cache of the backward pass and (out, vbar, row_stats) is returned."""
@@ -413,6 +457,8 @@ def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, strea
         row_ptr, tile_idx, Bs, Hs = block_mask_lists(block_mask.to(q.device))
         a.sparse_row_ptr, a.sparse_tile_idx = row_ptr.data_ptr(), tile_idx.data_ptr()
         a.sparse_batch, a.sparse_heads = Bs, Hs
+    if prep is not None:
+        a.prep = prep
     if save_for_backward:
         vbar = torch.empty_like(out)
         row_stats = torch.empty(q.shape[:3] + (2,), dtype=torch.float32, device=q.device)

@@ -146,7 +146,8 @@ __device__ __forceinline__ void merge_records(const float *const (&rec0)[NROW], 
 
 // RANGE: the launch covers the query rows [row0, row0 + rows) of Tq only (calls with more than 16
 // columns); its own instantiation, so that the one-launch kernel stays as it is.
-template <int D, bool USE_R, bool PAGED, bool RANGE = false>
+// PREP: RMSNorm + RoPE on the q / rho rows after they are loaded (own instantiations as well).
+template <int D, bool USE_R, bool PAGED, bool RANGE = false, bool PREP = false>
 __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
     constexpr int KPI = 64 / CPR;         // rows covered by one wave-wide 16-byte load
@@ -260,6 +261,56 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
         issue_loads(tk);
         if (tk + kWaves * kTileKeys < key_hi) lookup_pages(tk + kWaves * kTileKeys);
     }
+    // ---- RMSNorm + RoPE on the q / rho rows in their operand registers (the operations the
+    // paper's language-model runs apply in front of the attention call; formulas of
+    // norm_rope.hip, rotation from the (cos, sin) table). Placed behind the first tile's loads:
+    // they are on their way while this runs. Lane (c, g) holds dims 8 (4 s + g) .. + 7 of column c's
+    // row for every k-step s, so the row's sum of squares is this lane's plus those of the
+    // three lanes c + 16, 32, 48.
+    if constexpr (PREP) {
+        const QrPrep &pr = p.prep;
+        int Lfull = p.seq_lens ? p.seq_lens[b] : p.Lmax;
+        Lfull = min(max(Lfull, 0), p.Lmax);
+        const int t = row0 + (live ? col_t : 0);
+        const int64_t pos = min(max(pr.pos0 ? pr.pos0[b] + t : Lfull - Tq_all + t, 0), max(pr.n_pos - 1, 0));
+        auto prepare = [&](u32x4(&f)[KSTEPS], const float *gamma, bool rot) {
+            float ss = 0.f;
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lo = bf16_lo_f32(f[s][e]), hi = bf16_hi_f32(f[s][e]);
+                    ss = fmaf(lo, lo, ss);
+                    ss = fmaf(hi, hi, ss);
+                }
+            ss = rows_sum(ss);
+            const float rinv = 1.0f / sqrtf(ss * (1.0f / (float)D) + pr.eps);
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const int dim = 8 * (4 * s + g);
+                const f32x4 g0 = *(const f32x4 *)(gamma + dim), g1 = *(const f32x4 *)(gamma + dim + 4);
+                f32x4 t0 = {1.f, 0.f, 1.f, 0.f}, t1 = {1.f, 0.f, 1.f, 0.f};
+                if (rot) {
+                    const float *e = pr.table + (pos * (D / 2) + dim / 2) * 2;
+                    t0 = *(const f32x4 *)e, t1 = *(const f32x4 *)(e + 4);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float gm0 = j < 2 ? g0[2 * j] : g1[2 * j - 4], gm1 = j < 2 ? g0[2 * j + 1] : g1[2 * j - 3];
+                    float y0 = bf16_lo_f32(f[s][j]) * rinv * gm0, y1 = bf16_hi_f32(f[s][j]) * rinv * gm1;
+                    if (rot) {
+                        const float cs = j < 2 ? t0[2 * j] : t1[2 * j - 4], sn = j < 2 ? t0[2 * j + 1] : t1[2 * j - 3];
+                        const float r0 = y0 * cs - y1 * sn, r1 = y0 * sn + y1 * cs;
+                        y0 = r0, y1 = r1;
+                    }
+                    f[s][j] = live ? pack_bf16(y0, y1) : 0u;
+                }
+            }
+        };
+        prepare(qf, pr.gamma_q, pr.rope_q != 0);
+        if constexpr (USE_R) prepare(rf, pr.gamma_r, pr.rope_r != 0);
+    }
+
     for (; tk < key_hi; tk += kWaves * kTileKeys) {
         // registers -> swizzled LDS tile (private to this wave)
 #pragma unroll
@@ -499,7 +550,14 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
 
 template <int D, bool USE_R>
 static void launch_decode_variant(const DecodeParams &p, dim3 grid, hipStream_t stream) {
-    if (p.rows > 0) {  // a range of the query rows
+    if (p.prep.gamma_q != nullptr) {  // q / rho prepared in the kernel (the row-range form serves every call)
+        DecodeParams pr = p;
+        if (pr.rows == 0) pr.row0 = 0, pr.rows = pr.Tq;
+        if (p.block_table)
+            hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, true, true, true>), grid, dim3(256), 0, stream, pr);
+        else
+            hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, false, true, true>), grid, dim3(256), 0, stream, pr);
+    } else if (p.rows > 0) {  // a range of the query rows
         if (p.block_table)
             hipLaunchKernelGGL((decode_bf16_kernel<D, USE_R, true, true>), grid, dim3(256), 0, stream, p);
         else

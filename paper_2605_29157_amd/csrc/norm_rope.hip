@@ -101,6 +101,29 @@ __global__ __launch_bounds__(256) void norm_rope_kernel(NormRopeParams p) {
     }
 }
 
+// (cos, sin) of pos * theta^(-2i/d), one thread per (position, pair): the same double-precision
+// angle reduction as above, so that the attention kernels that apply the rotation themselves
+// (from this table) see the values this file's kernel would have used.
+__global__ __launch_bounds__(256) void rope_table_kernel(float *table, int n_pos, int d, float theta) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int half = d / 2;
+    if (idx >= (int64_t)n_pos * half) return;
+    const int pos = (int)(idx / half), i = (int)(idx % half);
+    double ang = (double)pos * exp2(-(double)(2 * i) / (double)d * log2((double)theta));
+    ang -= floor(ang * 0.15915494309189535) * 6.283185307179586;  // modulo 2 pi
+    float sn, cs;
+    sincosf((float)ang, &sn, &cs);
+    table[2 * idx] = cs;
+    table[2 * idx + 1] = sn;
+}
+
+hipError_t launch_rope_table(float *table, int n_pos, int d, float theta, hipStream_t stream) {
+    const int64_t blocks = ((int64_t)n_pos * (d / 2) + 255) / 256;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, table, n_pos, d, theta);
+    return hipGetLastError();
+}
+
 hipError_t launch_norm_rope(const NormRopeParams &p, bool f32, hipStream_t stream) {
     const int elems = f32 ? 4 : 8;
     const int rows_per_wave = 64 / (p.d / elems);

@@ -59,6 +59,30 @@ int query_num_cus() {
     return cus;
 }
 
+// The in-kernel q / rho preparation of a call: validated and copied, or left switched off.
+plx_status take_prep(const plx_qr_prep &a, plx_dtype dtype, bool use_r, plx::QrPrep *out) {
+    *out = plx::QrPrep{};
+    const bool any = a.q_gamma || a.r_gamma || a.rope_table || a.pos0 || a.rope_q || a.rope_r;
+    if (!any) return PLX_OK;
+    if (dtype != PLX_BF16) return PLX_ERR_DTYPE;
+    if (!a.q_gamma || (use_r && !a.r_gamma)) return PLX_ERR_NULL;
+    if (!(a.eps >= 0.f && a.eps <= 3.0e38f)) return PLX_ERR_SCALE;
+    if ((reinterpret_cast<uintptr_t>(a.q_gamma) | reinterpret_cast<uintptr_t>(a.r_gamma) |
+         reinterpret_cast<uintptr_t>(a.pos0)) & 3u)
+        return PLX_ERR_ALIGN;
+    if (a.rope_table) {
+        if (!aligned16(a.rope_table)) return PLX_ERR_ALIGN;
+        if (a.rope_positions < 1) return PLX_ERR_SHAPE;
+    } else if (a.rope_q || a.rope_r) {
+        return PLX_ERR_NULL;
+    }
+    out->gamma_q = a.q_gamma, out->gamma_r = use_r ? a.r_gamma : a.q_gamma;
+    out->table = a.rope_table, out->pos0 = a.pos0, out->n_pos = a.rope_positions;
+    out->rope_q = a.rope_table && a.rope_q, out->rope_r = a.rope_table && a.rope_r;
+    out->eps = a.eps;
+    return PLX_OK;
+}
+
 size_t ws_bytes(int64_t B, int64_t Hq, int64_t S, int64_t d) {
     return (size_t)(B * Hq * S * (2 * d + 4)) * sizeof(float);
 }
@@ -172,6 +196,10 @@ plx_status prepare_decode(const plx_decode_args *a, bool need_inputs, bool need_
         p.block_table = a->block_table;
         p.page_size = a->page_size, p.table_stride = a->block_table_stride;
         p.num_pages = a->num_pages;
+    }
+    if (need_inputs) {
+        st = take_prep(a->prep, a->dtype, a->use_r != 0, &p.prep);
+        if (st != PLX_OK) return st;
     }
     *out = p;
     return PLX_OK;
@@ -354,6 +382,10 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
         p.sparse_row_ptr = a->sparse_row_ptr, p.sparse_tile_idx = a->sparse_tile_idx;
         p.sparse_batch = a->sparse_batch, p.sparse_heads = a->sparse_heads;
     }
+    st = take_prep(a->prep, a->dtype, a->use_r != 0, &p.prep);
+    if (st != PLX_OK) return st;
+    if (p.prep.gamma_q && (!a->use_r || a->window > 0 || a->sparse_row_ptr || a->row_stats || a->vbar))
+        return PLX_ERR_SHAPE;
     if ((a->vbar != nullptr) != (a->row_stats != nullptr)) return PLX_ERR_NULL;
     if (a->row_stats) {
         if (!a->use_r) return PLX_ERR_SHAPE;
@@ -518,6 +550,16 @@ plx_status parallax_norm_rope(const plx_norm_rope_args *a, void *hip_stream) {
     p.n_tensors = a->n_tensors, p.B = a->B, p.T = a->T, p.d = d;
     p.pos0 = a->pos0, p.eps = a->eps, p.theta = a->theta;
     return plx::launch_norm_rope(p, f32, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PLX_OK
+               : PLX_ERR_LAUNCH;
+}
+
+plx_status parallax_rope_table(float *table, int32_t n_pos, int32_t d, float theta, void *hip_stream) {
+    if (!table) return PLX_ERR_NULL;
+    if (!aligned16(table)) return PLX_ERR_ALIGN;
+    if (n_pos < 1 || d < 2 || d > 256 || d % 2 != 0) return PLX_ERR_SHAPE;
+    if (!(theta > 1.f && theta <= 3.0e38f)) return PLX_ERR_SCALE;
+    return plx::launch_rope_table(table, n_pos, d, theta, static_cast<hipStream_t>(hip_stream)) == hipSuccess
                ? PLX_OK
                : PLX_ERR_LAUNCH;
 }

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace plx {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -93,6 +95,23 @@ __device__ __forceinline__ float rows_sum(float v) {
     v += xor_shuffle(v, 16);
     return v + xor_shuffle(v, 32);
 }
+// Sum over aligned groups of N = 8 or 16 consecutive lanes, every lane of a group receiving the
+// total, by data-parallel-primitive moves inside a 16-lane row (no LDS round trip as with a lane
+// shuffle): pairs and quads by quad permutations, then the mirrored half-row and row.
+template <int N>
+__device__ __forceinline__ float lane_group_sum(float v) {
+    static_assert(N == 8 || N == 16, "groups inside one 16-lane row");
+    auto moved = [](float x, auto ctrl) {
+        const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xf, 0xf, true);
+        return __builtin_bit_cast(float, y);
+    };
+    v += moved(v, std::integral_constant<int, 0xB1>{});   // quad_perm [1, 0, 3, 2]: lane ^ 1
+    v += moved(v, std::integral_constant<int, 0x4E>{});   // quad_perm [2, 3, 0, 1]: lane ^ 2
+    v += moved(v, std::integral_constant<int, 0x141>{});  // row_half_mirror: lane i <-> 7 - i of its half-row
+    if constexpr (N == 16) v += moved(v, std::integral_constant<int, 0x140>{});  // row_mirror: i <-> 15 - i
+    return v;
+}
+
 // max / sum over the two 32-lane halves of a wave
 __device__ __forceinline__ float halves_max(float v) { return fmaxf(v, xor_shuffle(v, 32)); }
 __device__ __forceinline__ float halves_sum(float v) { return v + xor_shuffle(v, 32); }

@@ -8,6 +8,15 @@ namespace plx {
 // Keys handled by one workgroup iteration of the bf16 decode kernel (4 waves x 32 keys).
 constexpr int kDecodeBlockKeys = 128;
 
+// RMSNorm + RoPE applied to q, rho as the attention kernels load them (gamma_q == nullptr: off).
+struct QrPrep {
+    const float *gamma_q, *gamma_r;  // [d]
+    const float *table;              // [n_pos, d/2, 2] (cos, sin), or nullptr: RMSNorm only
+    const int32_t *pos0;             // [B] or nullptr
+    int32_t n_pos, rope_q, rope_r;
+    float eps;
+};
+
 struct DecodeParams {
     const void *q, *r, *k, *v;
     void *o;
@@ -28,6 +37,7 @@ struct DecodeParams {
     // bf16 split kernel, more than 16 columns: one launch handles the rows [row0, row0 + rows) of
     // the Tq (rows = 0: all of them)
     int32_t row0, rows;
+    QrPrep prep;
 };
 
 struct PrefillParams {
@@ -47,6 +57,7 @@ struct PrefillParams {
     // sh) * ceil(T / 128) + rb, ascending; sparse_batch / sparse_heads = 1 shares the lists
     const int32_t *sparse_row_ptr, *sparse_tile_idx;
     int32_t sparse_batch, sparse_heads;
+    QrPrep prep;
 };
 
 // Decode over an MLA-style latent cache: one row [latent 512 | rope 64] per token shared by all
@@ -104,6 +115,7 @@ hipError_t launch_prefill_bwd_f32(const PrefillBwdParams &p, hipStream_t stream)
 hipError_t launch_decode_f32(const DecodeParams &p, hipStream_t stream);
 hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream);
 hipError_t launch_norm_rope(const NormRopeParams &p, bool f32, hipStream_t stream);
+hipError_t launch_rope_table(float *table, int n_pos, int d, float theta, hipStream_t stream);
 hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream);
 hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);
 hipError_t launch_util_read(const void *src, size_t bytes, void *sink, hipStream_t stream);

@@ -55,8 +55,14 @@ constexpr int kKB = 32;   // keys per inner block (one MFMA row block)
 
 
 // RW: sub-blocks of 32 query rows per wave (the workgroup covers 128 * RW rows).
-template <int D, bool USE_R, bool CAUSAL, bool WINDOW, bool STATS = false, bool SPARSE = false, int RW = 1>
+// PREP: RMSNorm + RoPE on the wave's Q and R rows in their LDS landing zones, before the MFMA
+// fragments are read (the operations the paper's language-model runs put in front of the attention
+// call: Sec. 5 experiment setup and the backbone appendix; same formulas and order of operations as
+// norm_rope.hip, the rotation taken from a table of (cos, sin) per position and pair).
+template <int D, bool USE_R, bool CAUSAL, bool WINDOW, bool STATS = false, bool SPARSE = false, int RW = 1,
+          bool PREP = false>
 __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
+    static_assert(!PREP || (USE_R && !WINDOW && !STATS && !SPARSE), "q / rho preparation: dense forward only");
     static_assert(RW == 1 || (RW == 2 && D == 64), "two row sub-blocks per wave fit the registers at d = 64 only");
     static_assert(!SPARSE || RW == 1, "block-sparse lists are per 128 query rows");
     constexpr int WROWS = 32 * RW;  // query rows per wave
@@ -146,6 +152,26 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     constexpr int NDMA_Q = (WAVE_TILE_CHUNKS + 63) / 64;  // full loads (+ one 32-lane load)
     constexpr int Q_LAST_LANES = WAVE_TILE_CHUNKS - 64 * (NDMA_Q - 1);
     static_assert(Q_LAST_LANES == 32 || Q_LAST_LANES == 64, "split");
+    // PREP: a wave-wide pass covers 64 / CPR rows (one 16-byte chunk = 4 pairs per lane); the
+    // weights of this lane's chunk and the table entries of its rows are requested first of all,
+    // so that they are there when the rows have landed.
+    constexpr int PREP_RPI = 64 / CPR, PREP_NIT = WROWS / PREP_RPI;
+    f32x4 prep_gq[2], prep_gr[2], prep_tab[PREP ? PREP_NIT : 1][2];
+    if constexpr (PREP) {
+        const int lr = lane % CPR, lrow = lane / CPR;
+        prep_gq[0] = *(const f32x4 *)(p.prep.gamma_q + 8 * lr), prep_gq[1] = *(const f32x4 *)(p.prep.gamma_q + 8 * lr + 4);
+        prep_gr[0] = *(const f32x4 *)(p.prep.gamma_r + 8 * lr), prep_gr[1] = *(const f32x4 *)(p.prep.gamma_r + 8 * lr + 4);
+        if (p.prep.table != nullptr) {  // workgroup-uniform
+            const int base = p.prep.pos0 ? p.prep.pos0[b] : 0;
+#pragma unroll
+            for (int it = 0; it < PREP_NIT; ++it) {
+                const int grow = min(row0 + it * PREP_RPI + lrow, T - 1);
+                const int64_t pos = min(max(base + grow, 0), p.prep.n_pos - 1);
+                const float *e = p.prep.table + (pos * (D / 2) + 4 * lr) * 2;
+                prep_tab[it][0] = *(const f32x4 *)e, prep_tab[it][1] = *(const f32x4 *)(e + 4);
+            }
+        }
+    }
     const uint32_t lds_base = lds_byte_address(lds);
     {
         const __bf16 *qhead = (const __bf16 *)p.q + b * p.qs[0] + hq * p.qs[1];
@@ -370,6 +396,12 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     const uint32_t one_top = col < 16 ? 0x3f803f80u : 0u, one_bot = col < 16 ? 0u : 0x3f803f80u;
     const u32x4 ones_top = {one_top, one_top, one_top, one_top}, ones_bot = {one_bot, one_bot, one_bot, one_bot};
     const float scale_log2 = p.scale * kLog2e;  // >= 0 (checked by the host)
+    // What multiplies S1 in front of the exponential, per row sub-block. PREP: the 1 / rms of
+    // the row's RMSNorm is a per-row scalar, so it is not applied to the q elements but rides on
+    // this factor (and that of rho on the final O2, d2, which are linear in S2): r_gain.
+    float row_scale[RW], r_gain[RW];
+#pragma unroll
+    for (int a = 0; a < RW; ++a) row_scale[a] = scale_log2, r_gain[a] = 1.f;
 
     // adds the bf16 values of a packed MFMA operand (this lane's 8 keys) to acc: one dot product
     // against (1, 1) per packed pair. Written as assembly: through the builtin, viewing a dword of
@@ -390,7 +422,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
             const float neg_m = m_ref[a] == kNegInf ? 0.f : -m_ref[a];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float p1 = fast_exp2(fmaf(s1[a][r], scale_log2, neg_m));
+                float p1 = fast_exp2(fmaf(s1[a][r], row_scale[a], neg_m));
                 if constexpr (MASKED) p1 = key_ok(key_base, r, a) ? p1 : 0.f;
                 s1[a][r] = p1;
                 // s2 is finite (rows past the last key re-read it) and P1 = 0 where masked
@@ -546,7 +578,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                     acc1[a][u & 1] += s1[a][r];
                     if constexpr (USE_R) acc2[a][u & 1] += s2[a][r];
                 }
-            if (slot == first) s1[a][r] = fmaf(s1[a][r], scale_log2, neg_m[a]);
+            if (slot == first) s1[a][r] = fmaf(s1[a][r], row_scale[a], neg_m[a]);
             if (slot == first + 1) {
                 const float p1 = fast_exp2(s1[a][r]);
                 const int key_off = 8 * (r >> 2) + (r & 3);
@@ -594,9 +626,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         };
 
         // register r of a score block pair (b1, b2); r holds key offset 8*(r/4) + r%4
-        auto chain = [&](f32x16 &b1, f32x16 &b2, int r, int start, float nm, int lim, int lo)
+        auto chain = [&](f32x16 &b1, f32x16 &b2, int r, int start, float nm, float sc, int lim, int lo)
                          __attribute__((always_inline)) {
-            if (g == start) b1[r] = pin(fmaf(b1[r], scale_log2, nm));
+            if (g == start) b1[r] = pin(fmaf(b1[r], sc, nm));
             if (g == start + 1) {
                 const float p1 = fast_exp2(b1[r]);
                 const int key_off = 8 * (r >> 2) + (r & 3);
@@ -611,13 +643,13 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
         for (int c = 0; c < NCH; ++c) {
             const int a = c / 8, u = c % 8;
             const int us = c, ls = l0 + c * l_span / (NCH - 1);
-            chain(sc1[a], sc2[a], 8 + u, us, neg_m[a], lim_cur[a], lo_cur[a]);
+            chain(sc1[a], sc2[a], 8 + u, us, neg_m[a], row_scale[a], lim_cur[a], lo_cur[a]);
             if constexpr (ADDS)
                 if (g == us + 3) {
                     acc1[a][u & 1] = pin(acc1[a][u & 1] + sc1[a][8 + u]);
                     if constexpr (USE_R) acc2[a][u & 1] = pin(acc2[a][u & 1] + sc2[a][8 + u]);
                 }
-            chain(sn1[a], sn2[a], u, ls, neg_m[a], lim_next[a], lo_next[a]);
+            chain(sn1[a], sn2[a], u, ls, neg_m[a], row_scale[a], lim_next[a], lo_next[a]);
             if (u & 1) {  // both chains of the pair (u - 1, u) are through: B operand dword u / 2
                 if (g == us + 2) pb1[a][1][u / 2] = pack_bf16(sc1[a][8 + u - 1], sc1[a][8 + u]);
                 if (g == ls + 2) nb1[a][u / 2] = pack_bf16(sn1[a][u - 1], sn1[a][u]);
@@ -773,18 +805,118 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     // stages kt % 3 and (kt+1) % 3 and visible to all waves. The barrier (every wave first waits
     // for its own tile loads) also proves that nobody reads tile kt-1 any more, whose stage then
     // receives tile kt+2: each tile load has a whole iteration to land.
-    if constexpr (SPARSE) {  // (the clamping form only: it needs no per-lane offsets kept alive)
-#pragma unroll
-        for (int t = 0; t < kDist; ++t) dma_tile(tile_at(t), t);
-    } else if (Tk >= kDist * kBC) {  // workgroup-uniform
-#pragma unroll
-        for (int t = 0; t < kDist; ++t) dma_full_tile(t, t);
-    } else {
-#pragma unroll
-        for (int t = 0; t < kDist; ++t) dma_tile(t, t);
-    }
-    zero_state();
+    // load n of the first two tiles (tile 0 first, K before V), for issuing them one at a time
+    auto initial_load = [&](int n) __attribute__((always_inline)) {
+        const int t = n / kTileLoads, i = n % kTileLoads;
+        if (Tk >= kDist * kBC) {  // workgroup-uniform: whole tiles, uniform base + lane offsets
+            if (i < NDMA_K)
+                k_load(i, (const char *)kbase + t * k_tile_bytes, stage_k_addr(t));
+            else
+                v_load(i - NDMA_K, (const char *)vbase + t * v_tile_bytes, stage_v_addr(t));
+        } else {
+            int row, pos;
+            if (i < NDMA_K) {
+                k_src(i, row, pos);
+                const __bf16 *sk = kbase + (int64_t)min(t * kBC + row, Tk - 1) * p.ks[2] + pos * 8;
+                if (i == NDMA_K - 1)
+                    tile_load16<16>(sk, stage_k_addr(t) + 1024u * i);
+                else
+                    tile_load16<64>(sk, stage_k_addr(t) + 1024u * i);
+            } else {
+                v_src(i - NDMA_K, row, pos);
+                const __bf16 *sv = vbase + (int64_t)min(t * kBC + row, Tk - 1) * p.vs[2] + pos * 8;
+                tile_load16<64>(sv, stage_v_addr(t) + 1024u * (i - NDMA_K));
+            }
+        }
+    };
     static_assert(kDist == 2, "the wait below leaves exactly tile 1 in flight");
+    if constexpr (!PREP) {
+        if constexpr (SPARSE) {  // (the clamping form only: it needs no per-lane offsets kept alive)
+#pragma unroll
+            for (int t = 0; t < kDist; ++t) dma_tile(tile_at(t), t);
+        } else if (Tk >= kDist * kBC) {  // workgroup-uniform
+#pragma unroll
+            for (int t = 0; t < kDist; ++t) dma_full_tile(t, t);
+        } else {
+#pragma unroll
+            for (int t = 0; t < kDist; ++t) dma_tile(t, t);
+        }
+        zero_state();
+    } else {
+        // Normalise, rotate and round this wave's Q and R rows where they landed (nobody else
+        // reads them). Per row: sum of squares over the CPR lanes of the row, y = x / sqrt(mean
+        // + eps) * gamma, then the adjacent pairs (2i, 2i + 1) turned by the row's angle.
+        // (Issuing the loads of the first two key tiles between the row passes instead of in
+        // front of them was tried: no faster.)
+#pragma unroll
+        for (int n = 0; n < kDist * kTileLoads; ++n) initial_load(n);
+        zero_state();
+        // this wave's Q and R rows (and the table entries) are there; the two tiles may still travel
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDist * kTileLoads) : "memory");
+        const int lr = lane % CPR, lrow = lane / CPR;
+        u32x4 *zq = lds + QZONE + w * WAVE_TILE_CHUNKS, *zr = lds + RZONE + w * WAVE_TILE_CHUNKS;
+        const float inv_d = 1.0f / (float)D;
+        // sum of squares of the 8 bf16 values of a chunk (dot products of the packed pairs with
+        // themselves), over the CPR lanes of the row; 1 / rms
+        auto inv_rms = [&](const u32x4 &c) __attribute__((always_inline)) {
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < 3; ++e) asm("v_dot2c_f32_bf16_e32 %0, %1, %1" : "+v"(ss) : "v"(c[e]));
+            // (the result of a dot product needs three wait states before another kind of
+            // instruction reads it; the compiler does not see the instruction, so they are here)
+            asm("v_dot2c_f32_bf16_e32 %0, %1, %1\n\ts_nop 2" : "+v"(ss) : "v"(c[3]));
+            ss = lane_group_sum<CPR>(ss);  // the CPR lanes of a row are an aligned group
+            return __builtin_amdgcn_rsqf(fmaf(ss, inv_d, p.prep.eps));
+        };
+        // gamma, then (unless ROT is off) the rotation of the four pairs; NOT the 1 / rms factor
+        auto scale_rotate = [&](auto rot_tag, const u32x4 &c, const f32x4(&gam)[2], const f32x4(&tab)[2])
+                                __attribute__((always_inline)) {
+            u32x4 out;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float y0 = bf16_lo_f32(c[j]) * gam[j >> 1][2 * (j & 1)];
+                float y1 = bf16_hi_f32(c[j]) * gam[j >> 1][2 * (j & 1) + 1];
+                if constexpr (decltype(rot_tag)::value) {
+                    const float cs = tab[j >> 1][2 * (j & 1)], sn = tab[j >> 1][2 * (j & 1) + 1];
+                    const float r0 = y0 * cs - y1 * sn, r1 = y0 * sn + y1 * cs;
+                    y0 = r0, y1 = r1;
+                }
+                out[j] = pack_bf16(y0, y1);
+            }
+            return out;
+        };
+        // The 1 / rms of a row goes to the padding chunk of the row (no fragment reads it), from
+        // where the lane that owns the row in the MFMA layout picks it up below.
+        auto prep_rows = [&](auto rot_q_tag, auto rot_r_tag) __attribute__((always_inline)) {
+#pragma unroll
+            for (int it = 0; it < PREP_NIT; ++it) {
+                const int row = it * PREP_RPI + lrow, slot = row * KROW + lr;
+                const u32x4 cq = zq[slot], cr = zr[slot];
+                const float iq = inv_rms(cq), ir = inv_rms(cr);
+                zq[slot] = scale_rotate(rot_q_tag, cq, prep_gq, prep_tab[it]);
+                zr[slot] = scale_rotate(rot_r_tag, cr, prep_gr, prep_tab[it]);
+                if (lr == 0) {
+                    *(float *)&zq[row * KROW + CPR] = iq;
+                    *(float *)&zr[row * KROW + CPR] = ir;
+                }
+            }
+        };
+        // (rotation switches are uniform over the launch: one specialised copy of the pass each)
+        if (p.prep.rope_q != 0 && p.prep.rope_r != 0)
+            prep_rows(std::true_type{}, std::true_type{});
+        else if (p.prep.rope_q != 0)
+            prep_rows(std::true_type{}, std::false_type{});
+        else
+            prep_rows(std::false_type{}, std::false_type{});
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int a = 0; a < RW; ++a) {
+            row_scale[a] = scale_log2 * *(const float *)&zq[(32 * a + col) * KROW + CPR];
+            r_gain[a] = *(const float *)&zr[(32 * a + col) * KROW + CPR];
+        }
+    }
     tile_barrier<kTileLoads>();  // Q, R and tile 0 have landed
     {
         // B operands: column = query row, k-elements = the 8 dims of chunk 2*ks + h
@@ -828,7 +960,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                 tall = halves_max(tall);
                 tmax = tmax == kNegInf ? tall : tmax;
             }
-            m_ref[a] = tmax * scale_log2;
+            m_ref[a] = tmax * row_scale[a];
             neg_m[a] = -m_ref[a];
             lim0[a] = row_lim[a] - kb0 - 4 * h;
             lo0[a] = row_lo[a] - kb0 - 4 * h;
@@ -925,8 +1057,10 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                 dsum1[a] = halves_sum(rsum1[a] + vsum1[a][0] + vsum1[a][1]);
                 dsum2 = halves_sum(rsum2[a] + vsum2[a][0] + vsum2[a][1]);
             }
+            if constexpr (PREP) dsum2 *= r_gain[a];
             inv[a] = dsum1[a] > 0.f ? 1.f / dsum1[a] : 0.f;  // empty key set: zeros
             const float gain = inv[a] * (1.f + dsum2 * inv[a]);
+            const float inv2 = PREP ? inv[a] * r_gain[a] : inv[a];
             chk = fmaf(dsum1[a] + dsum2, 0.f, chk);  // inf or NaN -> NaN
 #pragma unroll
             for (int n = 0; n < NDB; ++n)
@@ -936,7 +1070,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int r = 4 * q4 + i;
-                        y[i] = o1[a][n][r] * gain - (USE_R ? o2[a][n][r] * inv[a] : 0.f);
+                        y[i] = o1[a][n][r] * gain - (USE_R ? o2[a][n][r] * inv2 : 0.f);
                         chk = fmaf(y[i], 0.f, chk);
                     }
                     const u32x2 packed = {pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
@@ -983,7 +1117,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                     float tmax = kNegInf;
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        tmax = fmaxf(tmax, key_ok(key_base, r, a) ? sa1[a][r] * scale_log2 : kNegInf);
+                        tmax = fmaxf(tmax, key_ok(key_base, r, a) ? sa1[a][r] * row_scale[a] : kNegInf);
                     tmax = halves_max(tmax);
                     const float m_new = fmaxf(m_ref[a], tmax);
                     const float m_use = m_new == kNegInf ? 0.f : m_new;
@@ -1089,6 +1223,13 @@ static hipError_t launch_prefill_dense(const PrefillParams &p, hipStream_t strea
     const long long total = (long long)((p.T + rows - 1) / rows) * p.Hq * p.B;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)total), block(256);
+    if (p.prep.gamma_q != nullptr) {  // RMSNorm + RoPE on q, rho in the prologue (use_r, no window, no row cache)
+        if (p.causal)
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false, false, false, RW, true>), grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, false, false, false, false, RW, true>), grid, block, 0, stream, p);
+        return hipGetLastError();
+    }
     if (p.row_stats != nullptr && p.window > 0) {  // row cache + sliding window (causal, use_r)
         hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, true, true, false, RW>), grid, block, 0, stream, p);
     } else if (p.row_stats != nullptr) {  // with the row cache of the backward pass (use_r)

@@ -92,3 +92,27 @@ kernel_a:
     bad = ok.replace("v_add_u32_e32 v9, v8, v7", "v_accvgpr_read_b32 v9, a2")
     found = asm_check.find_foreign_uses_of_asm_loaded_registers(bad)
     assert len(found) == 1 and "a2" in found[0].replace("('a', 2)", "a2")
+
+
+def _asm_dot(dst, src):
+    return "\t;;#ASMSTART\n\tv_dot2c_f32_bf16_e32 %s, %s, %s\n\t;;#ASMEND\n" % (dst, src, src)
+
+
+def test_early_read_of_an_assembly_dot_product_result_is_flagged():
+    check = asm_check.find_early_reads_of_asm_dot_results
+    dpp = "\tv_add_f32_dpp v9, v9, v9 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+    other = "\tv_mul_f32_e32 v20, v21, v22\n"
+    for gap in (0, 1, 2):
+        bad = check(_asm_dot("v9", "v3") + other * gap + dpp)
+        assert len(bad) == 1 and "%d wait states" % gap in bad[0]
+    assert check(_asm_dot("v9", "v3") + other * 3 + dpp) == []
+    assert check(_asm_dot("v9", "v3") + "\ts_nop 2\n" + dpp) == []
+    # a chain of dot products into one accumulator is fine; its END is what gets checked
+    chain = _asm_dot("v9", "v3") + _asm_dot("v9", "v4") + _asm_dot("v9", "v5")
+    assert check(chain + other * 3 + dpp) == []
+    assert len(check(chain + other + dpp)) == 1
+    # a dot product that takes the fresh result as a FACTOR is not the chain
+    assert len(check(_asm_dot("v9", "v3") + _asm_dot("v10", "v9"))) == 1
+    # overwriting the result early is reported too; other registers are nobody's business
+    assert len(check(_asm_dot("v9", "v3") + "\tv_mov_b32_e32 v9, 0\n")) == 1
+    assert check(_asm_dot("v9", "v3") + "\tv_mov_b32_e32 v8, v10\n" + dpp.replace("v9", "v7")) == []

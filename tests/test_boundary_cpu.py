@@ -43,10 +43,11 @@ def test_header_symbols_are_exported(binding):
 
 def test_struct_sizes_match_c_layout(binding):
     # 6 pointers, 5 int32 (+pad), 6 int64, float + 2 int32 (+pad), pointer, size_t, enum (+pad),
-    # pointer, 4 int32, int32 (+pad), pointer
-    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16 + 8 + 8
+    # pointer, 4 int32, int32 (+pad), pointer, the q / rho preparation (4 pointers, 3 int32, float)
+    assert ctypes.sizeof(binding.plx_qr_prep) == 4 * 8 + 16
+    assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16 + 8 + 8 + 48
     # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, 2 int32, 2 pointers
-    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8 + 16 + 16 + 8
+    assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8 + 16 + 16 + 8 + 48
     # 12 pointers, 6 int32, float + int32, enum (+pad), pointer, size_t
     assert ctypes.sizeof(binding.plx_prefill_bwd_args) == 12 * 8 + 24 + 8 + 8 + 16 + 11 * 24
 
@@ -55,7 +56,7 @@ def test_struct_layouts_match_a_c_compiler(binding, tmp_path):
     """sizeof and every field offset of the ctypes mirrors against gcc's reading of the header."""
     import subprocess
 
-    structs = ["plx_decode_args", "plx_prefill_args", "plx_prefill_bwd_args", "plx_norm_rope_tensor",
+    structs = ["plx_qr_prep", "plx_decode_args", "plx_prefill_args", "plx_prefill_bwd_args", "plx_norm_rope_tensor",
                "plx_norm_rope_args", "plx_decode_mla_args"]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "parallax.h"', 'int main(void) {']
     for sname in structs:

@@ -108,3 +108,113 @@ def test_norm_rope_rejects_bad_arguments(plx):
         plx.parallax_norm_rope([(x, g, True)], eps=-1.0)
     with pytest.raises(plx.ParallaxError):
         plx.parallax_norm_rope([(_rand((1, 2, 4, 96), 31, torch.bfloat16), torch.ones(96, device=DEV), True)])
+
+
+def test_rope_table_against_the_definition(plx):
+    """(cos, sin) of pos * theta^(-2i/d), angles up to 1.3e5 radians."""
+    for d, theta, n_pos in ((128, 1.0e6, 4100), (64, 1.0e4, 700)):
+        tab = plx.parallax_rope_table(n_pos, d, theta, device=DEV)
+        far = plx.parallax_rope_table(131072, d, theta, device=DEV)[-3:]
+        torch.cuda.synchronize()
+        for t, pos in ((tab, np.arange(n_pos)), (far, np.arange(131069, 131072))):
+            ang = pos[:, None].astype(np.float64) * theta ** (-np.arange(0, d, 2, dtype=np.float64) / d)
+            got = host(t).astype(np.float64)
+            np.testing.assert_allclose(got[..., 0], np.cos(ang), rtol=0, atol=3e-6)
+            np.testing.assert_allclose(got[..., 1], np.sin(ang), rtol=0, atol=3e-6)
+
+
+@pytest.mark.parametrize("d,T,Tkv,causal,rope_r", [(128, 300, 300, True, True), (128, 200, 517, True, False),
+                                                   (64, 513, 513, True, True), (64, 77, 300, False, True),
+                                                   (128, 129, 129, False, False)])
+def test_prefill_prepares_q_and_rho_itself(plx, nr, oracle, d, T, Tkv, causal, rope_r):
+    """RMSNorm + RoPE on q, rho inside the prefill kernel: against the two-launch chain
+    (parallax_norm_rope, then parallax_prefill on its outputs) and against the oracle chain, with
+    the chunk's rows at positions behind a cache (pos0 = Tkv - T plus a per-sequence offset)."""
+    from paper_2605_29157_amd import synth
+
+    B, Hq, Hkv = 2, 8, 4
+    y = synth.prefill_inputs(B, Hq, Hkv, Tkv, d, seed=40 + T, device=DEV)
+    q, r = y["q"][:, :, Tkv - T:].contiguous(), y["r"][:, :, Tkv - T:].contiguous()
+    gq, gr, gk = (1.0 + 0.2 * _rand((d,), 41 + i, torch.float32) for i in range(3))
+    kpos0 = torch.tensor([0, 1000], dtype=torch.int32, device=DEV)
+    qpos0 = kpos0 + (Tkv - T)
+    (k2,) = plx.parallax_norm_rope([(y["k"], gk, True)], pos0=kpos0)
+    table = plx.parallax_rope_table(1000 + Tkv, d, device=DEV)
+    prep = plx.qr_prep(gq, gr, table, qpos0, rope_q=True, rope_r=rope_r)
+    fused = plx.parallax_prefill(q, r, k2, y["v"], y["scale"], causal=causal, prep=prep)
+    q2, r2 = plx.parallax_norm_rope([(q, gq, True), (r, gr, rope_r)], pos0=qpos0)
+    chain = plx.parallax_prefill(q2, r2, k2, y["v"], y["scale"], causal=causal)
+    torch.cuda.synchronize()
+    # the same mathematics with the roundings to bf16 at other places (the kernel leaves the
+    # 1 / rms factors out of the stored rows and applies them to the scores and to O2, d2)
+    assert rel_l2(host(fused), host(chain).astype(np.float64)) <= 5e-3
+    # oracle chain: norm + rope in float64 on the raw values, then the attention oracle
+    pos_q = (host(qpos0)[:, None, None] + np.arange(T)[None, None, :])
+    pos_k = (host(kpos0)[:, None, None] + np.arange(Tkv)[None, None, :])
+    qo = nr.norm_rope(host(q), host(gq), pos_q)
+    ro = nr.norm_rope(host(r), host(gr), pos_q) if rope_r else nr.rms_norm(host(r), host(gr))
+    ko = nr.norm_rope(host(y["k"]), host(gk), pos_k)
+    ref = oracle.forward(qo, ro, ko, host(y["v"]), y["scale"], causal=causal)
+    assert rel_l2(host(fused), ref) <= BF16_REL_L2
+    # RMSNorm alone (no table)
+    prep_n = plx.qr_prep(gq, gr, None, None)
+    fused_n = plx.parallax_prefill(q, r, k2, y["v"], y["scale"], causal=causal, prep=prep_n)
+    ref_n = oracle.forward(nr.rms_norm(host(q), host(gq)), nr.rms_norm(host(r), host(gr)), host(k2), host(y["v"]),
+                           y["scale"], causal=causal)
+    assert rel_l2(host(fused_n), ref_n) <= BF16_REL_L2
+
+
+@pytest.mark.parametrize("d,Tq,S,paged", [(128, 1, 0, False), (128, 3, 4, False), (64, 1, 3, False), (128, 1, 2, True),
+                                          (128, 9, 3, False)])
+def test_decode_prepares_q_and_rho_itself(plx, nr, oracle, d, Tq, S, paged):
+    """The decode rows are the last Tq positions of each (ragged) sequence: their q, rho are
+    normalised and rotated in the split kernel, against the two-launch chain and the oracle chain."""
+    from paper_2605_29157_amd import synth
+
+    B, Hq, Hkv, L = 3, 8, 4, 700
+    x = synth.decode_inputs(B, Hq, Hkv, L, d, seed=50 + Tq, device=DEV, ragged=True)
+    q = _rand((B, Hq, Tq, d), 51, torch.bfloat16)
+    r = _rand((B, Hq, Tq, d), 52, torch.bfloat16)
+    gq, gr = (1.0 + 0.2 * _rand((d,), 53 + i, torch.float32) for i in range(2))
+    table = plx.parallax_rope_table(L, d, device=DEV)
+    prep = plx.qr_prep(gq, gr, table, None)
+    kw = {}
+    k, v = x["k"], x["v"]
+    if paged:
+        k, v, tb = synth.paged_cache(x, 48, seed=55)
+        kw = dict(block_table=tb, max_len=L)
+    qa, ra = (q, r) if Tq > 1 else (q[:, :, 0].contiguous(), r[:, :, 0].contiguous())
+    fused = plx.parallax_decode(qa, ra, k, v, x["scale"], seq_lens=x["seq_lens"], num_splits=S, prep=prep, **kw)
+    pos0 = (x["seq_lens"] - Tq).to(torch.int32)
+    q2, r2 = plx.parallax_norm_rope([(q, gq, True), (r, gr, True)], pos0=pos0)
+    q2a, r2a = (q2, r2) if Tq > 1 else (q2[:, :, 0].contiguous(), r2[:, :, 0].contiguous())
+    chain = plx.parallax_decode(q2a, r2a, k, v, x["scale"], seq_lens=x["seq_lens"], num_splits=S, **kw)
+    torch.cuda.synchronize()
+    assert rel_l2(host(fused), host(chain).astype(np.float64)) <= 1e-3
+    pos = host(pos0)[:, None, None] + np.arange(Tq)[None, None, :]
+    qo, ro = nr.norm_rope(host(q), host(gq), pos), nr.norm_rope(host(r), host(gr), pos)
+    lens = x["seq_lens"].cpu().numpy()
+    for b in range(B):  # row t of sequence b sees the keys before position L_b - (Tq - 1 - t): causal over its own length
+        ref = oracle.forward(qo[b:b + 1], ro[b:b + 1], host(x["k"])[b:b + 1, :, :lens[b]], host(x["v"])[b:b + 1, :, :lens[b]],
+                             x["scale"], causal=True)
+        got = host(fused)[b:b + 1].reshape(1, Hq, Tq, d)
+        assert rel_l2(got, ref) <= BF16_REL_L2, b
+
+
+def test_preparation_arguments_are_validated(plx):
+    from paper_2605_29157_amd import synth
+
+    y = synth.prefill_inputs(1, 4, 2, 64, 128, seed=60, device=DEV)
+    g = torch.ones(128, dtype=torch.float32, device=DEV)
+    table = plx.parallax_rope_table(64, 128, device=DEV)
+    with pytest.raises(plx.ParallaxError):   # rotation asked for, no table
+        bad = plx.qr_prep(g, g, None, None)
+        bad.rope_q = 1
+        plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], prep=bad)
+    with pytest.raises(plx.ParallaxError):   # not together with a window
+        plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], prep=plx.qr_prep(g, g, table), window=16)
+    with pytest.raises(plx.ParallaxError):   # not together with the row cache
+        plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], prep=plx.qr_prep(g, g, table),
+                             save_for_backward=True)
+    with pytest.raises(plx.ParallaxError):
+        plx.parallax_rope_table(16, 127, device=DEV)
