@@ -875,10 +875,37 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
             on_hi = int(bm[np.arange(nrb), 2 * np.arange(nrb) + 1].sum())
             pairs = below * 128 * 64 + on_lo * (64 * 65 // 2 + 64 * 64) + on_hi * (64 * 65 // 2)
             flops = B * Hq * 8 * d * pairs
-            bs.append({"workload": "block-sparse causal prefill B=%d T=%d d=128, %s" % (B, T, name),
-                       "tiles_listed": int(bm.sum()), "tiles_causal": int((np.arange(nkt)[None, :] <= diag).sum()),
-                       "us": round(us, 1), "TFLOPs": round(flops / us / 1e6, 1),
-                       "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
+            rec = {"workload": "block-sparse causal prefill B=%d T=%d d=128, %s" % (B, T, name),
+                   "tiles_listed": int(bm.sum()), "tiles_causal": int((np.arange(nkt)[None, :] <= diag).sum()),
+                   "us": round(us, 1), "TFLOPs": round(flops / us / 1e6, 1),
+                   "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
+            if B == 4:
+                # the backward over the same lists (three kernels; 22 d flops per allowed pair)
+                vbar = torch.empty_like(po)
+                stats = torch.empty(B, Hq, T, 2, dtype=torch.float32, device=dev)
+                a.vbar, a.row_stats = vbar.data_ptr(), stats.data_ptr()
+                sstep()
+                col_ptr, col_idx = plx.block_mask_column_lists(torch.as_tensor(bm, device=dev))
+                grads = [torch.empty_like(y[n]) for n in ("q", "r", "k", "v")]
+                bws = torch.empty(B * Hq * T * 4, dtype=torch.float32, device=dev)
+                ba = plx.prefill_bwd_args(y["q"], y["r"], y["k"], y["v"], po, vbar, stats, y["q"], *grads,
+                                          y["scale"], True, bws)
+                ba.sparse_row_ptr, ba.sparse_tile_idx = row_ptr.data_ptr(), tile_idx.data_ptr()
+                ba.sparse_col_ptr, ba.sparse_col_idx = col_ptr.data_ptr(), col_idx.data_ptr()
+                ba.sparse_batch, ba.sparse_heads = Bs, Hs
+
+                def bstep():
+                    st = lib.parallax_prefill_backward(ctypes.byref(ba), sptr)
+                    if st != 0:
+                        raise plx.ParallaxError(st, "block-sparse backward bench")
+
+                bus = _time_events(torch, bstep, 2, 10)
+                bflops = B * Hq * 22 * d * pairs
+                rec["backward_us"] = round(bus, 1)
+                rec["backward_frac_of_bf16_mfma_peak"] = round(bflops / bus / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)
+                a.vbar, a.row_stats = None, None
+                del vbar, stats, grads, bws
+            bs.append(rec)
         del y, po
     extra["block_sparse"] = bs
 

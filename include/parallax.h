@@ -245,7 +245,7 @@ typedef struct {
     void *vbar;
     float *row_stats;
     /* Block-sparse attention (one of the sparsity patterns Sec. 5 says carry over; bf16, use_r,
-     * no window, no row cache): softmax, ubar and the output run over the listed key tiles
+     * no window; the row cache may be asked for): softmax, ubar and the output run over the listed key tiles
      * only (intersected with the causal set when causal != 0). Blocks are the kernel's tiles:
      * 128 query rows x 64 keys. Row block rb of list-batch sb and list-head sh visits the key
      * tiles sparse_tile_idx[sparse_row_ptr[e] .. sparse_row_ptr[e + 1]),
@@ -255,7 +255,8 @@ typedef struct {
      * checked (a list that does not ascend gives wrong results for its row block, never an access
      * outside the tensors); the arrays must not be written while the kernel runs. A row block
      * with an empty list (and any row none of whose listed keys is causal-visible) returns
-     * zeros. NULL sparse_row_ptr = dense. */
+     * zeros (and, in the row cache, vbar = 0, ubar = 0 and +infinity for the log-sum-exp, which
+     * makes every probability of the row zero in the backward). NULL sparse_row_ptr = dense. */
     const int32_t *sparse_row_ptr;
     const int32_t *sparse_tile_idx;
     int32_t sparse_batch, sparse_heads;
@@ -341,6 +342,23 @@ typedef struct {
     size_t workspace_bytes;
     int64_t q_stride[3], r_stride[3], k_stride[3], v_stride[3], o_stride[3], vbar_stride[3], d_o_stride[3];
     int64_t dq_stride[3], dr_stride[3], dk_stride[3], dv_stride[3];
+    /* Block-sparse (Sec. 5's sparsity remark x App. D; bf16, no window): all four arrays or none.
+     * sparse_row_ptr / sparse_tile_idx / sparse_batch / sparse_heads: the forward's lists, as in
+     * plx_prefill_args (the row cache must come from a forward call with the same lists). The
+     * pass over the keys needs the same cells by columns: key block cb (128 keys = key tiles
+     * 2 cb and 2 cb + 1) of list-batch sb and list-head sh is listed by the row blocks
+     * sparse_col_idx[sparse_col_ptr[e] .. sparse_col_ptr[e + 1]) >> 2,
+     * e = (sb * sparse_heads + sh) * ceil(Tkv / 128) + cb, each entry 4 * row block + flags, flag
+     * bit t set iff that row block lists key tile 2 cb + t (at least one is). int32 on the
+     * device, not written while the kernels run; row blocks are clamped to existing ones. The two
+     * descriptions must name the same cells: if they differ, dq / dr follow the row lists and
+     * dk / dv the column lists (wrong gradients, never an access outside the tensors). Row and
+     * key blocks nobody lists get zero gradients. */
+    const int32_t *sparse_row_ptr;
+    const int32_t *sparse_tile_idx;
+    const int32_t *sparse_col_ptr;
+    const int32_t *sparse_col_idx;
+    int32_t sparse_batch, sparse_heads;
 } plx_prefill_bwd_args;
 
 size_t parallax_prefill_backward_workspace_bytes(int32_t B, int32_t Hq, int32_t T);

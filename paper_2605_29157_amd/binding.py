@@ -104,6 +104,9 @@ class plx_prefill_bwd_args(ctypes.Structure):
         ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3), ("vbar_stride", ctypes.c_int64 * 3),
         ("d_o_stride", ctypes.c_int64 * 3), ("dq_stride", ctypes.c_int64 * 3), ("dr_stride", ctypes.c_int64 * 3),
         ("dk_stride", ctypes.c_int64 * 3), ("dv_stride", ctypes.c_int64 * 3),
+        ("sparse_row_ptr", ctypes.c_void_p), ("sparse_tile_idx", ctypes.c_void_p),
+        ("sparse_col_ptr", ctypes.c_void_p), ("sparse_col_idx", ctypes.c_void_p),
+        ("sparse_batch", ctypes.c_int32), ("sparse_heads", ctypes.c_int32),
     ]
 
 
@@ -435,6 +438,29 @@ def block_mask_lists(block_mask):
     return row_ptr, tile_idx, Bs, Hs
 
 
+def block_mask_column_lists(block_mask):
+    """The same cells by columns, for plx_prefill_bwd_args: per key block of 128 keys (two key
+    tiles) the ascending row blocks that list one of its tiles, each entry 4 * row block + flags
+    (flag bit t: key tile 2 * cb + t is listed). Returns (col_ptr, col_idx). Index bookkeeping only."""
+    m = block_mask.to(torch.bool)
+    while m.dim() < 4:
+        m = m.unsqueeze(0)
+    Bs, Hs, nrb, nkt = m.shape
+    if nkt % 2:
+        m = torch.cat([m, torch.zeros(Bs, Hs, nrb, 1, dtype=torch.bool, device=m.device)], dim=-1)
+    pair = m.reshape(Bs, Hs, nrb, -1, 2)                      # [.., rb, cb, t]
+    flags = pair[..., 0].to(torch.int32) + 2 * pair[..., 1].to(torch.int32)
+    by_col = flags.transpose(-1, -2).reshape(-1, nrb)         # one line per (sb, sh, cb)
+    hit = by_col > 0
+    col_ptr = torch.zeros(by_col.shape[0] + 1, dtype=torch.int32, device=m.device)
+    col_ptr[1:] = torch.cumsum(hit.sum(dim=1), 0).to(torch.int32)
+    where = torch.nonzero(hit)                                # row-major: ascending row blocks per line
+    col_idx = (4 * where[:, 1].to(torch.int32) + by_col[hit]).to(torch.int32).contiguous()
+    if col_idx.numel() == 0:
+        col_idx = torch.zeros(1, dtype=torch.int32, device=m.device)
+    return col_ptr, col_idx
+
+
 def parallax_prefill(q, r, k, v, scale, causal=True, use_r=True, out=None, stream=None, window=0,
                      save_for_backward=False, block_mask=None, prep=None):
     """Parallax prefill forward over T query rows and Tkv keys (causal: the rows are the last
@@ -500,15 +526,24 @@ def prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale,
 
 
 def parallax_prefill_backward(q, r, k, v, o, vbar, row_stats, d_o, scale, causal=True, stream=None,
-                              workspace=None, window=0):
+                              workspace=None, window=0, block_mask=None):
     """Gradients (dq, dr, dk, dv) of parallax_prefill for the upstream gradient d_o, from the
-    forward's output and row cache (save_for_backward=True, same causal / window)."""
+    forward's output and row cache (save_for_backward=True, same causal / window / block_mask)."""
     dq, dr = torch.empty_like(q), torch.empty_like(q)
     dk, dv = torch.empty_like(k), torch.empty_like(k)
     if workspace is None:
         workspace = torch.empty(q.shape[0] * q.shape[1] * q.shape[2] * 4, dtype=torch.float32,
                                 device=q.device)
     a = prefill_bwd_args(q, r, k, v, o, vbar, row_stats, d_o, dq, dr, dk, dv, scale, causal, workspace, window)
+    if block_mask is not None:
+        nrb, nkt = -(-q.shape[2] // BLOCK_ROWS), -(-k.shape[2] // BLOCK_KEYS)
+        if tuple(block_mask.shape[-2:]) != (nrb, nkt):
+            raise ValueError("block_mask must end in [ceil(T/128), ceil(Tkv/64)] = [%d, %d]" % (nrb, nkt))
+        row_ptr, tile_idx, Bs, Hs = block_mask_lists(block_mask.to(q.device))
+        col_ptr, col_idx = block_mask_column_lists(block_mask.to(q.device))
+        a.sparse_row_ptr, a.sparse_tile_idx = row_ptr.data_ptr(), tile_idx.data_ptr()
+        a.sparse_col_ptr, a.sparse_col_idx = col_ptr.data_ptr(), col_idx.data_ptr()
+        a.sparse_batch, a.sparse_heads = Bs, Hs
     st = load_library().parallax_prefill_backward(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_prefill_backward")

@@ -373,7 +373,7 @@ plx_status parallax_prefill(const plx_prefill_args *a, void *hip_stream) {
     if ((a->sparse_row_ptr != nullptr) != (a->sparse_tile_idx != nullptr)) return PLX_ERR_NULL;
     if (a->sparse_row_ptr) {
         if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
-        if (!a->use_r || a->window > 0 || a->row_stats || a->vbar) return PLX_ERR_SHAPE;
+        if (!a->use_r || a->window > 0) return PLX_ERR_SHAPE;
         if ((a->sparse_batch != 1 && a->sparse_batch != a->B) ||
             (a->sparse_heads != 1 && a->sparse_heads != a->Hq))
             return PLX_ERR_SHAPE;
@@ -519,6 +519,24 @@ plx_status parallax_prefill_backward(const plx_prefill_bwd_args *a, void *hip_st
             }
             // (a 64-row tile is addressed with 32-bit byte offsets)
             if (dst[t][2] < a->d || dst[t][2] > (1 << 23)) return PLX_ERR_SHAPE;
+        }
+    }
+    {
+        const void *lists[4] = {a->sparse_row_ptr, a->sparse_tile_idx, a->sparse_col_ptr, a->sparse_col_idx};
+        int given = 0;
+        for (const void *l : lists) given += l != nullptr;
+        if (given != 0 && given != 4) return PLX_ERR_NULL;
+        if (given) {
+            if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
+            if (a->window > 0) return PLX_ERR_SHAPE;
+            if ((a->sparse_batch != 1 && a->sparse_batch != a->B) ||
+                (a->sparse_heads != 1 && a->sparse_heads != a->Hq))
+                return PLX_ERR_SHAPE;
+            for (const void *l : lists)
+                if (reinterpret_cast<uintptr_t>(l) & 3u) return PLX_ERR_ALIGN;
+            p.sparse_row_ptr = a->sparse_row_ptr, p.sparse_tile_idx = a->sparse_tile_idx;
+            p.sparse_col_ptr = a->sparse_col_ptr, p.sparse_col_idx = a->sparse_col_idx;
+            p.sparse_batch = a->sparse_batch, p.sparse_heads = a->sparse_heads;
         }
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);

@@ -90,6 +90,12 @@ struct PrefillBwdParams {
     int32_t window;  // > 0 (causal only): a row sees its own position and the window - 1 before it
     // element strides {batch, head, row} of every tensor (innermost dimension contiguous)
     int64_t qs[3], rs[3], ks[3], vs[3], os[3], vbs[3], gs[3], dqs[3], drs[3], dks[3], dvs[3];
+    // block-sparse (bf16, no window): the forward's lists per 128-row block (see PrefillParams) and
+    // their transpose per 128-key block cb of (list batch sb, list head sh): entries
+    // sparse_col_idx[sparse_col_ptr[e] .. sparse_col_ptr[e + 1]), e = (sb * sparse_heads + sh) *
+    // ceil(Tk / 128) + cb, each 4 * row block + flags (bit t: the row block lists key tile 2 cb + t)
+    const int32_t *sparse_row_ptr, *sparse_tile_idx, *sparse_col_ptr, *sparse_col_idx;
+    int32_t sparse_batch, sparse_heads;
 };
 
 // RMSNorm + RoPE on up to three contiguous [B, H, T, d] tensors of one (B, T, d).

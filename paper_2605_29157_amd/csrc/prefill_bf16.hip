@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
     constexpr int kBR = 4 * WROWS;  // query rows per workgroup
     static_assert(CAUSAL || !WINDOW, "a sliding window needs the rows' positions");
     static_assert(!STATS || USE_R, "the row cache is written for the backward pass only");
-    static_assert(!SPARSE || (!WINDOW && !STATS), "block-sparse: its own tile iterator, forward only");
+    static_assert(!SPARSE || !WINDOW, "block-sparse: its own tile iterator, no window");
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int KSTEPS = D / 16;        // k-steps of the score contraction
     constexpr int NDB = D / 32;           // 32-wide blocks of output dimensions
@@ -1171,7 +1171,9 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
                 const float fsum2 = halves_sum(vsum2[a][0] + vsum2[a][1] + msum2[a][0] + msum2[a][1]);
                 if (h == 0 && my_row(a) < T) {
                     float *st = p.row_stats + (((int64_t)b * p.Hq + hq) * T + my_row(a)) * 2;
-                    st[0] = fsum1 > 0.f ? m_ref[a] + log2f(fsum1) : kNegInf;
+                    // (a row with no visible key stores +inf: the backward's exp2(S1 - lse) is then
+                    // zero for every pair of the row, whatever the mask arithmetic does)
+                    st[0] = fsum1 > 0.f ? m_ref[a] + log2f(fsum1) : -kNegInf;
                     st[1] = fsum1 > 0.f ? fsum2 / fsum1 : 0.f;
                 }
             }
@@ -1203,12 +1205,19 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_kernel(PrefillParams p) {
 }
 
 
-// Block-sparse tile iterator (use_r, no window, no row cache): lists per 128 query rows.
+// Block-sparse tile iterator (use_r, no window): lists per 128 query rows.
 template <int D>
 static hipError_t launch_prefill_sparse(const PrefillParams &p, hipStream_t stream) {
     const long long total = (long long)((p.T + 127) / 128) * p.Hq * p.B;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)total), block(256);
+    if (p.row_stats != nullptr) {  // with the row cache of the backward pass
+        if (p.causal)
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false, true, true>), grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((prefill_bf16_kernel<D, true, false, false, true, true>), grid, block, 0, stream, p);
+        return hipGetLastError();
+    }
     if (p.causal)
         hipLaunchKernelGGL((prefill_bf16_kernel<D, true, true, false, false, true>), grid, block, 0, stream, p);
     else

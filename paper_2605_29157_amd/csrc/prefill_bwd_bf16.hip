@@ -27,6 +27,11 @@
 // global -> LDS directly into a three-stage ring, one workgroup barrier per tile; both passes are
 // software pipelines of hand-placed slots (one MFMA + its share of vector work), as in the forward.
 // Every tensor is addressed through element strides {batch, head, row}; the workspace is dense.
+// SPARSE (block lists over 128 query rows x 64 keys, the forward's cells): the row pass walks the
+// forward's list of its row block; the column pass walks the TRANSPOSED list of its 128 keys --
+// per query head of the group the row blocks that list one of its two key tiles, with two flag
+// bits saying which: a wave whose key tile a row block does not list masks all its pairs. Both
+// passes then run the masked form of their pipeline throughout.
 #include "plx_device.h"
 #include "plx_kernels.h"
 #include <type_traits>
@@ -160,9 +165,10 @@ __global__ __launch_bounds__(256) void bwd_rows_prepare_kernel(PrefillBwdParams 
 // WINDOW (sliding window, causal only): the key tiles before the window of the block's first row
 // are skipped by moving the key origin; the leading tiles that some row sees only in part take
 // the masked form of the pipeline, like the diagonal ones.
-template <int D, bool CAUSAL, bool WINDOW = false>
+template <int D, bool CAUSAL, bool WINDOW = false, bool SPARSE = false>
 __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     static_assert(CAUSAL || !WINDOW, "a sliding window is causal");
+    static_assert(!(SPARSE && WINDOW), "block lists and a sliding window do not combine");
     using TL = BwdTile<D>;
     constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
     constexpr int STAGES = 3, STAGE_CHUNKS = 2 * TL::CHUNKS;  // ring of [K tile | V tile]
@@ -227,9 +233,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     const __bf16 *kbase = (const __bf16 *)p.k + b * p.ks[0] + hk * p.ks[1] + (int64_t)kt_skip * kTileRows * p.ks[2];
     const __bf16 *vbase = (const __bf16 *)p.v + b * p.vs[0] + hk * p.vs[1] + (int64_t)kt_skip * kTileRows * p.vs[2];
     const uint32_t lds_base = lds_byte_address(lds);
-    auto issue_tile = [&](int t, int stage) __attribute__((always_inline)) {
-        load_tile64<D>(kbase, p.ks[2], t * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u, w, lane);
-        load_tile64<D>(vbase, p.vs[2], t * kTileRows, Tk,
+    auto issue_tile = [&](int tile, int stage) __attribute__((always_inline)) {  // key tile -> ring stage
+        load_tile64<D>(kbase, p.ks[2], tile * kTileRows, Tk, lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u, w, lane);
+        load_tile64<D>(vbase, p.vs[2], tile * kTileRows, Tk,
                        lds_base + (uint32_t)(stage * STAGE_CHUNKS + TL::CHUNKS) * 16u, w, lane);
     };
     // The steady-state loop spreads the loads of tile t + 2 over the MFMA slots of a step (as a
@@ -256,8 +262,50 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     auto k_block = [&](int stage, int kb) __attribute__((always_inline)) { return (const u32x4 *)(lds + stage * STAGE_CHUNKS + kb * kBlk * CPR); };
 
     const int key_end = CAUSAL ? min(Tk, (rb + 1) * 128 + off) : Tk;
-    const int n_tiles = (key_end + kTileRows - 1) / kTileRows;
+    // Block-sparse: ring position t holds key tile tile_at(t) of the row block's list (ascending,
+    // caller's arrays, read as scalar loads; entries clamped to existing tiles; listed tiles past
+    // the causal limit dropped) -- the list the forward walked.
+    using const_i32 = const __attribute__((address_space(4))) int32_t;
+    const_i32 *tile_list = nullptr;
+    int n_list = 0;
+    if constexpr (SPARSE) {
+        const int sb = p.sparse_batch > 1 ? b : 0, sh = p.sparse_heads > 1 ? hq : 0;
+        const int64_t e = ((int64_t)sb * p.sparse_heads + sh) * nrb + rb;
+        const_i32 *row_ptr = (const_i32 *)(uintptr_t)p.sparse_row_ptr;
+        const int first = row_ptr[e];
+        tile_list = (const_i32 *)(uintptr_t)p.sparse_tile_idx + first;
+        int lo_i = 0, hi_i = max(row_ptr[e + 1] - first, 0);
+        while (lo_i < hi_i) {  // leading entries whose first key lies below key_end
+            const int mid = (lo_i + hi_i) >> 1;
+            if ((int64_t)max(tile_list[mid], 0) * kTileRows < key_end)
+                lo_i = mid + 1;
+            else
+                hi_i = mid;
+        }
+        n_list = lo_i;
+    }
+    auto tile_at = [&](int i) __attribute__((always_inline)) {
+        if constexpr (SPARSE)
+            return min(max(tile_list[min(i, n_list - 1)], 0), (Tk - 1) / kTileRows);
+        else
+            return i;
+    };
+    const int n_tiles = SPARSE ? n_list : (key_end + kTileRows - 1) / kTileRows;
     const int lim_row = CAUSAL ? min(my_row + off, Tk - 1) : Tk - 1;  // last key this lane's row sees
+    if constexpr (SPARSE) {
+        if (n_tiles == 0) {  // (workgroup-uniform) a row block that lists nothing: zero gradients
+            if (my_row < T) {
+                __bf16 *dq_row = (__bf16 *)p.dq + b * p.dqs[0] + hq * p.dqs[1] + my_row * p.dqs[2];
+                __bf16 *dr_row = (__bf16 *)p.dr + b * p.drs[0] + hq * p.drs[1] + my_row * p.drs[2];
+#pragma unroll
+                for (int c = 0; c < D / 16; ++c) {
+                    *(u32x4 *)(dq_row + 8 * (2 * c + h)) = u32x4{0u, 0u, 0u, 0u};
+                    *(u32x4 *)(dr_row + 8 * (2 * c + h)) = u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+            return;
+        }
+    }
 
     f32x16 dq[NDB], dr[NDB];
 #pragma unroll
@@ -323,9 +371,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     // one out). Each brings two wait states for its operands; the first vector read of a block
     // comes in slot 1 of phase 2, behind two more MFMAs: by then the block's last MFMA retired.
     u32x4 pg1[2], pg2[2];
-    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int key_base_cur, const u32x4 *next_blk, const u32x4 *cur_blk, const u32x4 *after_blk,
+    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int key_base_cur, int key_base_next, const u32x4 *next_blk, const u32x4 *cur_blk, const u32x4 *after_blk,
                              f32x16 &c1, f32x16 &c2, f32x16 &ca, f32x16 &n1, f32x16 &n2, f32x16 &na) __attribute__((always_inline)) {
-        const int lim_cur = lim_row - key_base_cur - 4 * h, lim_next = lim_cur - kBlk;
+        const int lim_cur = lim_row - key_base_cur - 4 * h, lim_next = lim_row - key_base_next - 4 * h;
         constexpr int SLOTS1 = 3 * KSTEPS, SLOTS2 = 4 * NDB;
         constexpr bool DMA = decltype(dma_tag)::value;  // this step also fetches tile (dma_k, dma_v)
         static_assert(2 * TL::NDMA <= SLOTS1, "one tile load per slot");
@@ -373,8 +421,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     // Ring invariant at the top of iteration t: tiles t and (after the barrier) t + 1 are in
     // stages t % 3 and (t + 1) % 3; the barrier also proves that nobody reads tile t - 1 any more,
     // whose stage then receives tile t + 2.
-    issue_tile(0, 0);
-    if (n_tiles > 1) issue_tile(1, 1);
+    issue_tile(tile_at(0), 0);
+    if (n_tiles > 1) issue_tile(tile_at(1), 1);
     if (n_tiles > 1)
         tile_barrier<2 * TL::NDMA>();  // tile 0 has landed (loads complete in order)
     else
@@ -393,7 +441,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
         }
 #pragma unroll
         for (int sl = 0; sl < 12; ++sl)
-            elem_stages(std::true_type{}, a1, a2, a3, 0, sl, 0, 12, lim_row - 4 * h);
+            elem_stages(std::true_type{}, a1, a2, a3, 0, sl, 0, 12, lim_row - tile_at(0) * kTileRows - 4 * h);
         pg1[0] = pack_group(a3, 0);
         pg2[0] = pack_group(a2, 0);
 #pragma unroll
@@ -408,13 +456,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
         if constexpr (DMA) {  // tile t + 2 is complete: fetched by the first step, slot by slot
             dma_lds = lds_base + (uint32_t)(free_stage * STAGE_CHUNKS + w * TL::NDMA * 64) * 16u;
         } else {
-            if (t + 2 < n_tiles) issue_tile(t + 2, free_stage);
+            if (t + 2 < n_tiles) issue_tile(tile_at(t + 2), free_stage);
         }
+        const int key_base = tile_at(t) * kTileRows, key_base_after = tile_at(t + 1) * kTileRows;
         // block (t, 0) -> g, dQ / dR; scores of (t, 1); fragments of (t + 1, 0)
-        pipeline_step(masked_tag, dma_tag, t * kTileRows, k_block(stage, 1), k_block(stage, 0),
+        pipeline_step(masked_tag, dma_tag, key_base, key_base + kBlk, k_block(stage, 1), k_block(stage, 0),
                       k_block(next_stage, 0), a1, a2, a3, b1, b2, b3);
         // block (t, 1) -> g, dQ / dR; scores of (t + 1, 0); fragments of (t + 1, 1)
-        pipeline_step(masked_tag, std::false_type{}, t * kTileRows + kBlk, k_block(next_stage, 0),
+        pipeline_step(masked_tag, std::false_type{}, key_base + kBlk, key_base_after, k_block(next_stage, 0),
                       k_block(stage, 1), k_block(next_stage, 1), b1, b2, b3, a1, a2, a3);
         stage = next_stage;
     };
@@ -422,7 +471,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
     // next block) -- every row of the workgroup sees: no masks; then the diagonal / tail tiles.
     // The unmasked loop also stops two short of the last complete tile, so that the tile it
     // fetches exists completely.
-    const int n_full = min(CAUSAL ? (rb * 128 + off + 1) / kTileRows : Tk / kTileRows, Tk / kTileRows - 1);
+    const int n_full = SPARSE ? 0 : min(CAUSAL ? (rb * 128 + off + 1) / kTileRows : Tk / kTileRows, Tk / kTileRows - 1);
     int t = 0;
     if constexpr (WINDOW) {
         // leading tiles that hold a key before the window of the block's last row
@@ -470,9 +519,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_dr_kernel(PrefillBwdParams p) {
 // one float4 per register, read one slot ahead of their use.
 // WINDOW: key j is seen by the rows [j - off, j - off + window) only; the row tiles past the
 // last of them are not visited, those cut by the upper edge take the masked form.
-template <int D, bool CAUSAL, bool WINDOW = false>
+template <int D, bool CAUSAL, bool WINDOW = false, bool SPARSE = false>
 __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     static_assert(CAUSAL || !WINDOW, "a sliding window is causal");
+    static_assert(!(SPARSE && WINDOW), "block lists and a sliding window do not combine");
     using TL = BwdTile<D>;
     constexpr int CPR = TL::CPR, KSTEPS = D / 16, NDB = D / 32;
     constexpr int STAGES = 3;
@@ -528,7 +578,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         WINDOW ? max(min(n_rt, (min(cb * 128 + 127, Tk - 1) - off + p.window + kTileRows - 1) / kTileRows), rt_lo + 1)
                : n_rt;
     const int per_head = rt_hi - rt_lo;
-    const int n_items = per_head * G;  // (head of the group, row tile)
+    int n_items = per_head * G;  // (head of the group, row tile)
     // Row tiles in which every (row, key) pair counts -- all rows exist and see every key of the
     // block, and the key block is complete -- need no masks. The items are taken in an order that
     // puts those of all heads first, so that the two forms of the pipeline are two loops.
@@ -539,6 +589,54 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     const int full_per_head = max(rt_full_hi - rt_full_lo, 0);
     const int n_full_items = full_per_head * G;
     const int rest_per_head = per_head - full_per_head;
+    // Block-sparse: the items are, head after head of the group, the two row tiles of every row
+    // block in the head's column list (entry = 4 * row block + flags; flag bit t: the row block
+    // lists key tile 2 * cb + t). A cursor walks the lists; items are decoded in order, once each.
+    using const_i32 = const __attribute__((address_space(4))) int32_t;
+    const int n_cb = (Tk + 127) / 128, n_rb = (T + 127) / 128;
+    auto col_list = [&](int g, int &first, int &end) __attribute__((always_inline)) {
+        const int hq = hk * G + g;
+        const int sb = p.sparse_batch > 1 ? b : 0, sh = p.sparse_heads > 1 ? hq : 0;
+        const int64_t e = ((int64_t)sb * p.sparse_heads + sh) * n_cb + cb;
+        const_i32 *col_ptr = (const_i32 *)(uintptr_t)p.sparse_col_ptr;
+        first = col_ptr[e];
+        end = max(col_ptr[e + 1], first);
+    };
+    int cur_g = 0, cur_pos = 0, cur_end = 0, cur_half = 0;  // the cursor: next item to decode
+    if constexpr (SPARSE) {
+        n_items = 0;
+        for (int g = 0; g < G; ++g) {
+            int first, end;
+            col_list(g, first, end);
+            n_items += 2 * (end - first);
+        }
+        cur_g = -1;
+        while (cur_pos == cur_end && ++cur_g < G) col_list(cur_g, cur_pos, cur_end);  // first non-empty list
+        if (n_items == 0) {  // (workgroup-uniform) nobody lists these keys: zero gradients
+            if (my_key < Tk) {
+                __bf16 *dk_row = (__bf16 *)p.dk + b * p.dks[0] + hk * p.dks[1] + my_key * p.dks[2];
+                __bf16 *dv_row = (__bf16 *)p.dv + b * p.dvs[0] + hk * p.dvs[1] + my_key * p.dvs[2];
+#pragma unroll
+                for (int c = 0; c < D / 16; ++c) {
+                    *(u32x4 *)(dk_row + 8 * (2 * c + h)) = u32x4{0u, 0u, 0u, 0u};
+                    *(u32x4 *)(dv_row + 8 * (2 * c + h)) = u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+            return;
+        }
+    }
+    // decodes the item under the cursor into (head of the group, row tile, flags) and moves on
+    auto next_sparse_item = [&](int &g, int &rt, int &flags) __attribute__((always_inline)) {
+        const int entry = ((const_i32 *)(uintptr_t)p.sparse_col_idx)[cur_pos];
+        g = cur_g;
+        rt = 2 * min(max(entry >> 2, 0), n_rb - 1) + cur_half;
+        flags = entry & 3;
+        cur_half ^= 1;
+        if (cur_half == 0) {
+            ++cur_pos;
+            while (cur_pos == cur_end && ++cur_g < G) col_list(cur_g, cur_pos, cur_end);
+        }
+    };
     auto item_of = [&](int it, int &g, int &rt) __attribute__((always_inline)) {
         if (it < n_full_items) {
             g = it / full_per_head;
@@ -552,9 +650,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     };
 
     const uint32_t lds_base = lds_byte_address(lds);
-    auto issue_item = [&](int it, int stage) __attribute__((always_inline)) {
-        int g, rt;
-        item_of(it, g, rt);
+    auto issue_item_at = [&](int g, int rt, int stage) __attribute__((always_inline)) {
         const int hq = hk * G + g;
         const int64_t head = ((int64_t)b * p.Hq + hq) * T;
         const uint32_t s0 = lds_base + (uint32_t)(stage * STAGE_CHUNKS) * 16u;
@@ -567,6 +663,15 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
             const f32x4 *src = (const f32x4 *)p.row_cache + head + min(rt * kTileRows + lane, T - 1);
             tile_load16<64>(src, s0 + (uint32_t)(3 * TL::CHUNKS) * 16u);
         }
+    };
+    // The three items in flight: (head, row tile, flags) of item it, it + 1 and it + 2.
+    int it_g[3] = {0, 0, 0}, it_rt[3] = {0, 0, 0}, it_flags[3] = {3, 3, 3};
+    auto issue_item = [&](int it, int stage, int slot) __attribute__((always_inline)) {
+        if constexpr (SPARSE)
+            next_sparse_item(it_g[slot], it_rt[slot], it_flags[slot]);
+        else
+            item_of(it, it_g[slot], it_rt[slot]);
+        issue_item_at(it_g[slot], it_rt[slot], stage);
     };
     constexpr int kItemLoads = 3 * TL::NDMA;  // per wave (wave 0 issues one more, last)
     // The unmasked loop spreads the loads of item it + 2 over the MFMA slots of a step: per-lane
@@ -584,9 +689,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     }
     const char *dma_q = nullptr, *dma_r = nullptr, *dma_g = nullptr, *dma_rc = nullptr;
     uint32_t dma_lds = 0, dma_lds_rc = 0;
-    auto set_dma_item = [&](int it, int stage) __attribute__((always_inline)) {
-        int g, rt;
-        item_of(it, g, rt);
+    auto set_dma_item = [&](int g, int rt, int stage) __attribute__((always_inline)) {
         const int hq = hk * G + g;
         const int64_t row0 = (int64_t)rt * kTileRows;
         dma_q = (const char *)p.q + (b * p.qs[0] + hq * p.qs[1] + row0 * p.qs[2]) * 2;
@@ -688,22 +791,25 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     u32x4 pw[2], pg1[2], pg2[2];
     // rows of the block that starts at row_base which exist and see this lane's key:
     // offsets [lo, hi) relative to row_base + 4h
-    auto row_window = [&](int row_base, int &neg_lo, unsigned &span) __attribute__((always_inline)) {
-        const int first_row = my_key < Tk ? (CAUSAL ? max(my_key - off, 0) : 0) : T;  // no row at all
+    auto row_window = [&](int row_base, int flags, int &neg_lo, unsigned &span) __attribute__((always_inline)) {
+        // (block-sparse: a row block that does not list this wave's key tile -- none of its rows)
+        const bool listed = !SPARSE || ((flags >> (w >> 1)) & 1) != 0;
+        const int first_row = (my_key < Tk && listed) ? (CAUSAL ? max(my_key - off, 0) : 0) : T;  // no row at all
         const int end_row = WINDOW ? min(T, max(my_key - off + p.window, 0)) : T;
         const int lo_off = max(first_row - row_base - 4 * h, 0);
         const int hi_off = end_row - row_base - 4 * h;
         neg_lo = -lo_off;
         span = (unsigned)max(hi_off - lo_off, 0);
     };
-    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int row_base_cur, int row_base_next, const u32x4 *next_blk,
+    auto pipeline_step = [&](auto masked_tag, auto dma_tag, int row_base_cur, int flags_cur, int row_base_next,
+                             int flags_next, const u32x4 *next_blk,
                              const u32x4 *cur_blk, const u32x4 *after_blk, const f32x4 *rows_cur,
                              const f32x4 *rows_next, f32x16 &c1, f32x16 &c2, f32x16 &ca, f32x16 &n1,
                              f32x16 &n2, f32x16 &na) __attribute__((always_inline)) {
         int nlo_c, nlo_n;
         unsigned span_c, span_n;
-        row_window(row_base_cur, nlo_c, span_c);
-        row_window(row_base_next, nlo_n, span_n);
+        row_window(row_base_cur, flags_cur, nlo_c, span_c);
+        row_window(row_base_next, flags_next, nlo_n, span_n);
         constexpr int SLOTS1 = 3 * KSTEPS, SLOTS2 = 6 * NDB;
         constexpr bool DMA = decltype(dma_tag)::value;  // this step also fetches the item set_dma_item named
         static_assert(3 * TL::NDMA + 1 <= SLOTS1, "one tile load per slot");
@@ -753,8 +859,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
     // Ring invariant at the top of iteration it: items it and (after the barrier) it + 1 are in
     // stages it % 3 and (it + 1) % 3; the barrier also proves that nobody reads item it - 1 any
     // more, whose stage then receives item it + 2.
-    issue_item(0, 0);
-    if (n_items > 1) issue_item(1, 1);
+    issue_item(0, 0, 0);
+    if (n_items > 1) issue_item(1, 1, 1);
     // item 0 has landed (loads complete in order; wave 0 has one more in flight per item)
     if (n_items > 1) {
         if (w == 0)
@@ -778,9 +884,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         }
         int nlo;
         unsigned span;
-        int g0, rt0;
-        item_of(0, g0, rt0);
-        row_window(rt0 * kTileRows, nlo, span);
+        row_window(it_rt[0] * kTileRows, it_flags[0], nlo, span);
 #pragma unroll
         for (int sl = 0; sl < 16; ++sl)
             elem_stages(std::true_type{}, a1, a2, a3, row_scalars(0, 0), 0, sl, 0, 16, nlo, span);
@@ -796,30 +900,33 @@ __global__ __launch_bounds__(256, 1) void bwd_dk_dv_kernel(PrefillBwdParams p) {
         const int next_stage = stage == STAGES - 1 ? 0 : stage + 1;
         const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;
         tile_barrier<0>();  // item it + 1 has landed; item it - 1 is free
+        // (items it, it + 1, it + 2 sit in slots 0, 1, 2 of the item record)
         if constexpr (DMA) {  // item it + 2 is a complete tile: fetched by the first step, slot by slot
-            set_dma_item(it + 2, free_stage);
+            item_of(it + 2, it_g[2], it_rt[2]);
+            set_dma_item(it_g[2], it_rt[2], free_stage);
         } else {
-            if (it + 2 < n_items) issue_item(it + 2, free_stage);
+            if (it + 2 < n_items) issue_item(it + 2, free_stage, 2);
         }
-        int g_cur, rt_cur, g_after, rt_after;
-        item_of(it, g_cur, rt_cur);
-        item_of(it + 1 < n_items ? it + 1 : it, g_after, rt_after);  // (past the end: never used)
-        const int row_base = rt_cur * kTileRows, row_base_after = rt_after * kTileRows;
+        const int row_base = it_rt[0] * kTileRows, row_base_after = it_rt[1] * kTileRows;  // (past the end: never used)
+        const int flags = it_flags[0], flags_after = it_flags[1];
         // row block 0 -> w, g; dV / dK; scores of row block 1; fragments of the next item
-        pipeline_step(masked_tag, dma_tag, row_base, row_base + kBlk, q_block(stage, 1), q_block(stage, 0),
+        pipeline_step(masked_tag, dma_tag, row_base, flags, row_base + kBlk, flags, q_block(stage, 1), q_block(stage, 0),
                       q_block(next_stage, 0), row_scalars(stage, 0), row_scalars(stage, 1), a1, a2, a3, b1, b2,
                       b3);
         // row block 1 -> w, g; dV / dK; scores of row block 0 of the next item
-        pipeline_step(masked_tag, std::false_type{}, row_base + kBlk, row_base_after, q_block(next_stage, 0),
-                      q_block(stage, 1),
+        pipeline_step(masked_tag, std::false_type{}, row_base + kBlk, flags, row_base_after, flags_after,
+                      q_block(next_stage, 0), q_block(stage, 1),
                       q_block(next_stage, 1), row_scalars(stage, 1), row_scalars(next_stage, 0), b1, b2, b3, a1,
                       a2, a3);
         stage = next_stage;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) it_g[j] = it_g[j + 1], it_rt[j] = it_rt[j + 1], it_flags[j] = it_flags[j + 1];
     };
     // a step also prepares the lower half of the next item's first block, and the unmasked loop
     // fetches item it + 2 as a complete tile: it stops two short of the last unmasked item
     int it = 0;
-    for (; it < n_full_items - 2; ++it) item_steps(std::false_type{}, std::true_type{}, it);
+    if constexpr (!SPARSE)
+        for (; it < n_full_items - 2; ++it) item_steps(std::false_type{}, std::true_type{}, it);
     for (; it < n_items; ++it) item_steps(std::true_type{}, std::false_type{}, it);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no tile load may land after the workgroup ends
 
@@ -851,7 +958,15 @@ static hipError_t launch_bwd_d(const PrefillBwdParams &p, hipStream_t stream) {
     const long long g2 = (long long)((p.Tk + 127) / 128) * p.Hkv * p.B;
     if (g0 > 0x7fffffffLL || g1 > 0x7fffffffLL || g2 > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((bwd_rows_prepare_kernel<D>), dim3((unsigned)g0), dim3(256), 0, stream, p);
-    if (p.causal && p.window > 0) {
+    if (p.sparse_row_ptr != nullptr) {  // block lists (no window; checked by the caller)
+        if (p.causal) {
+            hipLaunchKernelGGL((bwd_dq_dr_kernel<D, true, false, true>), dim3((unsigned)g1), dim3(256), 0, stream, p);
+            hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true, false, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+        } else {
+            hipLaunchKernelGGL((bwd_dq_dr_kernel<D, false, false, true>), dim3((unsigned)g1), dim3(256), 0, stream, p);
+            hipLaunchKernelGGL((bwd_dk_dv_kernel<D, false, false, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
+        }
+    } else if (p.causal && p.window > 0) {
         hipLaunchKernelGGL((bwd_dq_dr_kernel<D, true, true>), dim3((unsigned)g1), dim3(256), 0, stream, p);
         hipLaunchKernelGGL((bwd_dk_dv_kernel<D, true, true>), dim3((unsigned)g2), dim3(256), 0, stream, p);
     } else if (p.causal) {

@@ -48,8 +48,9 @@ def test_struct_sizes_match_c_layout(binding):
     assert ctypes.sizeof(binding.plx_decode_args) == 6 * 8 + 24 + 6 * 8 + 16 + 8 + 8 + 8 + 8 + 16 + 8 + 8 + 48
     # 5 pointers, 5 int32 (+pad), 15 int64, float + 2 int32 + enum, 2 int32, 2 pointers
     assert ctypes.sizeof(binding.plx_prefill_args) == 5 * 8 + 24 + 15 * 8 + 16 + 8 + 16 + 16 + 8 + 48
-    # 12 pointers, 6 int32, float + int32, enum (+pad), pointer, size_t
-    assert ctypes.sizeof(binding.plx_prefill_bwd_args) == 12 * 8 + 24 + 8 + 8 + 16 + 11 * 24
+    # 12 pointers, 6 int32, float + int32, enum (+pad), pointer, size_t, 11 stride triples,
+    # 4 list pointers, 2 int32
+    assert ctypes.sizeof(binding.plx_prefill_bwd_args) == 12 * 8 + 24 + 8 + 8 + 16 + 11 * 24 + 4 * 8 + 8
 
 
 def test_struct_layouts_match_a_c_compiler(binding, tmp_path):
@@ -397,3 +398,41 @@ def test_norm_rope_rejects_bad_arguments_before_launch(binding):
     a = good(); a.pos0 = 0x3001
     assert call(a) == binding.PLX_ERR_ALIGN
     assert ctypes.sizeof(binding.plx_norm_rope_args) == 3 * 32 + 16 + 8 + 8 + 8
+
+
+def test_block_mask_lists_by_rows_and_by_columns(binding):
+    """The two list forms of a block mask (row blocks -> key tiles for the forward and the dQ / dR
+    pass, key blocks of two tiles -> row blocks + flags for the dK / dV pass) against a
+    brute-force reading of the mask."""
+    import numpy as np
+    import torch
+
+    rng = np.random.default_rng(0)
+    for shape in [(3, 5), (2, 3, 4, 7), (1, 4, 4, 8), (5, 1), (2, 6)]:
+        bm = rng.random(shape) < 0.4
+        if shape == (2, 6):
+            bm[:] = False
+        m = bm.reshape((1,) * (4 - bm.ndim) + bm.shape)
+        Bs, Hs, nrb, nkt = m.shape
+        row_ptr, tile_idx, gb, gh = binding.block_mask_lists(torch.as_tensor(bm))
+        col_ptr, col_idx = binding.block_mask_column_lists(torch.as_tensor(bm))
+        assert (gb, gh) == (Bs, Hs)
+        assert len(row_ptr) == Bs * Hs * nrb + 1 and len(col_ptr) == Bs * Hs * ((nkt + 1) // 2) + 1
+        e = 0
+        for sb in range(Bs):
+            for sh in range(Hs):
+                for rb in range(nrb):
+                    want = [t for t in range(nkt) if m[sb, sh, rb, t]]
+                    assert tile_idx[row_ptr[e]:row_ptr[e + 1]].tolist() == want
+                    e += 1
+        e = 0
+        for sb in range(Bs):
+            for sh in range(Hs):
+                for cb in range((nkt + 1) // 2):
+                    want = []
+                    for rb in range(nrb):
+                        f = int(m[sb, sh, rb, 2 * cb]) + (2 * int(m[sb, sh, rb, 2 * cb + 1]) if 2 * cb + 1 < nkt else 0)
+                        if f:
+                            want.append(4 * rb + f)
+                    assert col_idx[col_ptr[e]:col_ptr[e + 1]].tolist() == want
+                    e += 1

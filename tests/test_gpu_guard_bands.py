@@ -180,6 +180,25 @@ def test_prefill_fp32_block_sparse_and_norm_rope(plx, synth):
     a.sparse_row_ptr, a.sparse_tile_idx, a.sparse_batch, a.sparse_heads = row_ptr.data_ptr(), tile_idx.data_ptr(), Bs, Hs
     _call(plx, "parallax_prefill", a)
     g.check("block-sparse prefill")
+    # ... with the row cache, and the backward over the same lists (row and column form)
+    g = Guarded()
+    out, vbar = g.like(y["q"]), g.like(y["q"])
+    stats = g.empty((2, 4, 450, 2), torch.float32)
+    a.o, a.vbar, a.row_stats = out.data_ptr(), vbar.data_ptr(), stats.data_ptr()
+    _call(plx, "parallax_prefill", a)
+    g.check("block-sparse prefill + row cache")
+    g2 = Guarded()
+    dq, dr, dk, dv = g2.like(y["q"]), g2.like(y["q"]), g2.like(y["k"]), g2.like(y["k"])
+    ws = g2.empty((2 * 4 * 450 * 4,), torch.float32)
+    ba = plx.prefill_bwd_args(y["q"], y["r"], y["k"], y["v"], out, vbar, stats, y["q"], dq, dr, dk, dv, y["scale"],
+                              True, ws)
+    col_ptr, col_idx = plx.block_mask_column_lists(bm)
+    ba.sparse_row_ptr, ba.sparse_tile_idx = row_ptr.data_ptr(), tile_idx.data_ptr()
+    ba.sparse_col_ptr, ba.sparse_col_idx = col_ptr.data_ptr(), col_idx.data_ptr()
+    ba.sparse_batch, ba.sparse_heads = Bs, Hs
+    _call(plx, "parallax_prefill_backward", ba)
+    g2.check("block-sparse backward")
+    g.check("block-sparse backward reads")
     # RMSNorm + RoPE out of place
     g = Guarded()
     gam = torch.ones(128, dtype=torch.float32, device=DEV)
