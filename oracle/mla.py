@@ -16,6 +16,12 @@ part only:
 q, rho are [B, Hq, d_c + d_r] (already in the latent space), the output is [B, Hq, d_c] (the
 value up-projection is applied outside). Written with explicit per-head vectors, no tiling.
 
+`mla_rows` is the same for Tq query rows per head that sit at the LAST Tq positions of the
+cached sequence (several rows of a speculative / chunked decode step, or -- with Tq = the prompt
+length -- the causal prefill over the latent cache): row t sees the tokens 0 .. n - Tq + t, and
+with a sliding window of W > 0 only the last W of those (its own position and the W - 1 before).
+A row that sees no token returns zeros.
+
 Pins (tests/test_oracle_mla.py): equality with the C forward oracle run on one shared KV head
 whose values are the latent part padded with zeros (a different program, with its own pins);
 rho = 0 against a library softmax attention whose value width differs from its key width; a
@@ -47,4 +53,32 @@ def mla_decode(q, r, ckv, d_latent, scale, seq_lens=None):
             u = keys @ r[b, h]
             ubar = p @ u
             out[b, h] = (p * (1.0 + ubar - u)) @ values
+    return out
+
+
+def mla_rows(q, r, ckv, d_latent, scale, seq_lens=None, window=0):
+    """q, r [B, Hq, Tq, dk]; ckv [B, L, dk]; returns o [B, Hq, Tq, d_latent]. Row t of sequence b
+    (n = seq_lens[b] tokens) is at position n - Tq + t and sees the tokens j with
+    max(0, pos - window + 1) <= j <= pos (window = 0: from token 0)."""
+    q, r, ckv = (np.asarray(x, dtype=np.float64) for x in (q, r, ckv))
+    B, Hq, Tq, dk = q.shape
+    L = ckv.shape[1]
+    assert ckv.shape == (B, L, dk) and r.shape == q.shape and 0 < d_latent <= dk and window >= 0
+    out = np.zeros((B, Hq, Tq, d_latent))
+    for b in range(B):
+        n = L if seq_lens is None else int(seq_lens[b])
+        for t in range(Tq):
+            pos = n - Tq + t
+            first = max(0, pos - window + 1) if window > 0 else 0
+            if pos < first:
+                continue                          # (pos < 0: the row lies before the sequence)
+            keys = ckv[b, first:pos + 1]
+            values = keys[:, :d_latent]
+            for h in range(Hq):
+                a = scale * (keys @ q[b, h, t])
+                w = np.exp(a - a.max())
+                p = w / w.sum()
+                u = keys @ r[b, h, t]
+                ubar = p @ u
+                out[b, h, t] = (p * (1.0 + ubar - u)) @ values
     return out
