@@ -950,6 +950,30 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
             del pools, p_args
         del xs, m_args, mo, mws
     extra["mla_decode"] = ml
+
+    # several rows per head over the latent cache: a 4-row decode step, and the causal prefill
+    # (rows = prompt; flops = 4352 per (head, row, visible token), bytes = the cache once per batch entry)
+    mr = []
+    for (B, Hq, Tq, L) in [(64, 16, 4, 16384), (2, 16, 4096, 4096)]:
+        x = synth.mla_decode_inputs(B, Hq * Tq, L, seed=1030, device=dev)
+        q4, r4 = x["q"].view(B, Hq, Tq, 576), x["r"].view(B, Hq, Tq, 576)
+        mo = torch.empty(B, Hq, Tq, 512, dtype=torch.bfloat16, device=dev)
+        S = plx.parallax_decode_mla_num_splits(B, Hq * Tq, L)
+        mws = torch.empty(max(B * Hq * Tq * S * 1028, 4), dtype=torch.float32, device=dev)
+        ma = plx.decode_mla_args(q4, r4, x["ckv"], mo, x["scale"], None, S, mws)
+
+        def rstep():
+            st = lib.parallax_decode_mla(ctypes.byref(ma), sptr)
+            if st != 0:
+                raise plx.ParallaxError(st, "mla rows bench")
+
+        us = _time_events(torch, rstep, 2, 10)
+        pairs = B * Hq * sum(L - Tq + t + 1 for t in range(Tq))
+        mr.append({"workload": "latent cache, B=%d Hq=%d, %d rows per head at the end of L=%d" % (B, Hq, Tq, L),
+                   "num_splits": S, "us": round(us, 1), "TFLOPs": round(4352.0 * pairs / us / 1e6, 1),
+                   "cache_GBps": round(B * L * 1152 / us / 1e3, 1)})
+        del x, mo, mws
+    extra["mla_rows"] = mr
     return extra
 
 

@@ -276,6 +276,12 @@ plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
  *     o_h = sum_j p_j (1 + ubar - u_j) c_j[:d_latent]          (forward definition, Sec. 3.1)
  * computed by Algorithm 1 with split-KV partials merged as in App. C. bf16 only,
  * d_latent = 512 and d_rope = 64.
+ * Tq > 1 (0 means 1): every head has Tq query rows, which sit at the LAST Tq positions of the
+ * cached sequence; row t sees the tokens 0 .. L_b - Tq + t (the rows of a speculative or chunked
+ * decode step; with Tq = the prompt length, the causal prefill over the latent cache). window > 0:
+ * a row sees its own position and the window - 1 before it only (Sec. 5's sliding-window remark).
+ * A row that sees no token (L_b < Tq - t) returns zeros. q, r are then [B, Hq, Tq, 576] and o
+ * [B, Hq, Tq, 512], contiguous; the workspace and split-count queries take Hq * Tq as their Hq.
  *   q, r       [B, Hq, 576] contiguous (already in the latent space), 16-byte aligned
  *   ckv        [B, Lmax, 576]: element strides ckv_stride_b / ckv_stride_l (multiples of 8,
  *              576 <= ckv_stride_l <= 2^23), last dimension contiguous
@@ -305,6 +311,8 @@ typedef struct {
     size_t workspace_bytes;
     const int32_t *block_table;
     int32_t page_size, num_pages, block_table_stride;
+    int32_t Tq;     /* query rows per head; 0 = 1 */
+    int32_t window; /* 0 = none */
 } plx_decode_mla_args;
 
 size_t parallax_decode_mla_workspace_bytes(int32_t B, int32_t Hq);

@@ -121,6 +121,7 @@ class plx_decode_mla_args(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("block_table", ctypes.c_void_p),
         ("page_size", ctypes.c_int32), ("num_pages", ctypes.c_int32), ("block_table_stride", ctypes.c_int32),
+        ("Tq", ctypes.c_int32), ("window", ctypes.c_int32),
     ]
 
 
@@ -592,10 +593,12 @@ def parallax_decode_mla_num_splits(B, Hq, Lmax, num_cus=0) -> int:
 
 
 def decode_mla_args(q, r, ckv, out, scale, seq_lens=None, num_splits=0, workspace=None, d_latent=512,
-                    block_table=None, max_len=None):
-    """Fill a plx_decode_mla_args: q, r [B, Hq, dk] and out [B, Hq, d_latent] contiguous, ckv
-    [B, L, dk] with any batch / token strides -- or, with an int32 block_table [B, pages], a page
-    pool [num_pages, page_size, dk] (max_len = capacity in tokens, default pages * page_size)."""
+                    block_table=None, max_len=None, window=0):
+    """Fill a plx_decode_mla_args: q, r [B, Hq, dk] and out [B, Hq, d_latent] contiguous (or, with
+    several query rows per head at the last positions of the sequence, [B, Hq, Tq, dk] and
+    [B, Hq, Tq, d_latent]), ckv [B, L, dk] with any batch / token strides -- or, with an int32
+    block_table [B, pages], a page pool [num_pages, page_size, dk] (max_len = capacity in tokens,
+    default pages * page_size)."""
     for t in (q, r, out):
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError("parallax_decode_mla needs contiguous device tensors for q, r and out")
@@ -611,7 +614,9 @@ def decode_mla_args(q, r, ckv, out, scale, seq_lens=None, num_splits=0, workspac
         a.block_table = block_table.data_ptr()
         a.page_size, a.num_pages, a.block_table_stride = ckv.shape[1], ckv.shape[0], block_table.stride(0)
         a.Lmax = int(max_len) if max_len is not None else block_table.shape[1] * ckv.shape[1]
-    a.d_latent, a.d_rope = d_latent, q.shape[2] - d_latent
+    a.d_latent, a.d_rope = d_latent, q.shape[-1] - d_latent
+    a.Tq = q.shape[2] if q.dim() == 4 else 1
+    a.window = int(window)
     a.num_splits = int(num_splits)
     a.ckv_stride_b, a.ckv_stride_l = ckv.stride(0), ckv.stride(1)
     a.scale = float(scale)
@@ -623,15 +628,23 @@ def decode_mla_args(q, r, ckv, out, scale, seq_lens=None, num_splits=0, workspac
 
 
 def parallax_decode_mla(q, r, ckv, scale, seq_lens=None, num_splits=0, out=None, workspace=None,
-                        stream=None, d_latent=512, block_table=None, max_len=None):
-    """Parallax decode over an MLA-style latent cache: key = the whole cached row, value = its
-    first d_latent numbers, shared by all heads."""
+                        stream=None, d_latent=512, block_table=None, max_len=None, window=0):
+    """Parallax attention over an MLA-style latent cache: key = the whole cached row, value = its
+    first d_latent numbers, shared by all heads. q, r [B, Hq, dk] (one decode row) or
+    [B, Hq, Tq, dk] (rows at the last Tq positions, causal among themselves: a chunked decode
+    step, or the prefill over the latent cache with Tq = prompt length); window > 0 = sliding."""
     if out is None:
-        out = torch.empty(q.shape[0], q.shape[1], d_latent, dtype=q.dtype, device=q.device)
+        out = torch.empty(q.shape[:-1] + (d_latent,), dtype=q.dtype, device=q.device)
+    n_cols = q.shape[1] * (q.shape[2] if q.dim() == 4 else 1)
     if workspace is None and num_splits != 1:
-        workspace = torch.empty(parallax_decode_mla_workspace_bytes(q.shape[0], q.shape[1]) // 4,
-                                dtype=torch.float32, device=q.device)
-    a = decode_mla_args(q, r, ckv, out, scale, seq_lens, num_splits, workspace, d_latent, block_table, max_len)
+        lmax = ckv.shape[1] if block_table is None else (
+            int(max_len) if max_len is not None else block_table.shape[1] * ckv.shape[1])
+        S = num_splits or parallax_decode_mla_num_splits(q.shape[0], n_cols, lmax)
+        if S > 1:
+            workspace = torch.empty(q.shape[0] * n_cols * S * (2 * d_latent + 4), dtype=torch.float32,
+                                    device=q.device)
+    a = decode_mla_args(q, r, ckv, out, scale, seq_lens, num_splits, workspace, d_latent, block_table, max_len,
+                        window)
     st = load_library().parallax_decode_mla(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_decode_mla")

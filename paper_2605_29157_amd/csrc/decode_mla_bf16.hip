@@ -4,7 +4,12 @@
 // cached token is ONE row c_j = [latent (512) | rope part (64)] shared by all heads: the key is
 // the whole row, the value its latent part (the absorbed-projection decode form of multi-head
 // latent attention, which the paper's closing discussion names as structurally compatible).
-// q and rho arrive in the latent space ([B, Hq, 576]), the output is [B, Hq, 512].
+// q and rho arrive in the latent space ([B, Hq, Tq, 576]), the output is [B, Hq, Tq, 512].
+// Tq > 1: the rows of a head sit at the last Tq positions of the sequence and row t sees the
+// tokens up to its own (a speculative / chunked decode step, or the causal prefill over the
+// latent cache with Tq = prompt length); `window` > 0 cuts a row's tokens to the last `window`.
+// A (head, row) pair is simply one more MFMA column with its own first and last token: a
+// workgroup's tile range is the union over its 16 columns.
 //
 // How it is laid out for CDNA4. With 16 heads per column group the step reads 1152 bytes per token
 // for 70 kflop: still HBM bound, but the state of a column group -- O1^T, O2^T of 512 dimensions
@@ -78,26 +83,39 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int c = lane & 15;  // MFMA column: head 16 * group + c
+    const int c = lane & 15;  // MFMA column: (head, row) pair 16 * group + c, row fastest
     const int g = lane >> 4;  // 16-lane row of the wave
     const int split = blockIdx.x, hgroup = blockIdx.y, b = blockIdx.z;
     const int S = p.S;
-    const int head = hgroup * 16 + c;
-    const bool live = head < p.Hq;
+    const int n_cols = p.Hq * p.Tq;
+    const int head = hgroup * 16 + c;  // column index in [0, Hq * Tq)
+    const bool live = head < n_cols;
 
     int Lb = p.seq_lens ? p.seq_lens[b] : p.Lmax;
     Lb = min(max(Lb, 0), p.Lmax);
-    const int n_tiles = (Lb + kMlaTileKeys - 1) / kMlaTileKeys;
+    // tokens [key_lo, key_end) of this lane's column: row t of a head is at position Lb - Tq + t
+    const int key_end = live ? max(Lb - p.Tq + (head % p.Tq) + 1, 0) : 0;
+    const int key_lo = p.window > 0 ? max(key_end - p.window, 0) : 0;
+    // the workgroup's tiles: the union over its live columns (the same value in every wave)
+    int wg_end = key_end, wg_lo = live && key_end > 0 ? key_lo : 0x7fffffff;
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+        wg_end = max(wg_end, __shfl_xor(wg_end, off, 64));
+        wg_lo = min(wg_lo, __shfl_xor(wg_lo, off, 64));
+    }
+    wg_end = __builtin_amdgcn_readfirstlane(wg_end);
+    wg_lo = __builtin_amdgcn_readfirstlane(min(wg_lo, wg_end));
+    const int tile0 = wg_lo / kMlaTileKeys;
+    const int n_tiles = (wg_end + kMlaTileKeys - 1) / kMlaTileKeys - tile0;
     const int tiles_per_split = (n_tiles + S - 1) / S;
-    const int t_lo = split * tiles_per_split;
-    const int t_hi = min(t_lo + tiles_per_split, n_tiles);
-    const int key_hi = min(t_hi * kMlaTileKeys, Lb);
+    const int t_lo = tile0 + split * tiles_per_split;
+    const int t_hi = min(t_lo + tiles_per_split, tile0 + n_tiles);
 
     // ---- B operands: q and rho of the group's heads (zero in the dead columns) -> LDS, in the
     // order the MFMAs want them: entry [k-step s][lane (c, g)] = dims 32 s + 8 g .. + 7 of column c.
     // Wave w fills the k-steps w, w + 4, ...; everybody reads them back in every tile.
     {
-        const int64_t row = ((int64_t)b * p.Hq + (live ? head : 0)) * kMlaDK;
+        const int64_t row = ((int64_t)b * n_cols + (live ? head : 0)) * kMlaDK;
         const __bf16 *qrow = (const __bf16 *)p.q + row;
         const __bf16 *rrow = (const __bf16 *)p.r + row;
         const u32x4 z = {0u, 0u, 0u, 0u};
@@ -324,7 +342,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         float tmax = kNegInf;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            x[i] = key0 + i < key_hi ? s1[i] * scale_log2 : kNegInf;
+            x[i] = (key0 + i >= key_lo && key0 + i < key_end) ? s1[i] * scale_log2 : kNegInf;
             tmax = fmaxf(tmax, x[i]);
         }
         tmax = rows_max(tmax);
@@ -425,7 +443,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
         d2 += dex[(ww * 16 + c) * 2 + 1];
     }
     if (!live) return;
-    const int64_t hq = (int64_t)b * p.Hq + head;
+    const int64_t hq = (int64_t)b * n_cols + head;
     if (p.direct_out) {
         float inv = 0.f, gain = 0.f;  // empty key set: zeros
         if (d1 > 0.f) {
@@ -452,14 +470,14 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
 
 
 hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream) {
-    const dim3 grid(p.S, (p.Hq + 15) / 16, p.B);
+    const dim3 grid(p.S, (p.Hq * p.Tq + 15) / 16, p.B);
     if (p.block_table)
         hipLaunchKernelGGL(decode_mla_kernel<true>, grid, dim3(256), 0, stream, p);
     else
         hipLaunchKernelGGL(decode_mla_kernel<false>, grid, dim3(256), 0, stream, p);
     if (!p.direct_out) {
         DecodeParams c{};
-        c.ws = p.ws, c.o = p.o, c.B = p.B, c.Hq = p.Hq, c.Tq = 1, c.S = p.S, c.d = kMlaDC;
+        c.ws = p.ws, c.o = p.o, c.B = p.B, c.Hq = p.Hq * p.Tq, c.Tq = 1, c.S = p.S, c.d = kMlaDC;
         const hipError_t err = launch_decode_combine(c, stream);
         if (err != hipSuccess) return err;
     }

@@ -428,7 +428,10 @@ plx_status parallax_decode_mla(const plx_decode_mla_args *a, void *hip_stream) {
     if (a->dtype != PLX_BF16) return PLX_ERR_DTYPE;
     if (a->B <= 0 || a->Hq <= 0 || a->Lmax <= 0) return PLX_ERR_SHAPE;
     if (a->d_latent != 512 || a->d_rope != 64) return PLX_ERR_SHAPE;
-    if (a->B > 65535 || (a->Hq + 15) / 16 > 65535) return PLX_ERR_SHAPE;  // grid dimensions
+    if (a->Tq < 0 || a->window < 0) return PLX_ERR_SHAPE;
+    const int32_t Tq = a->Tq ? a->Tq : 1;
+    const int64_t n_cols = (int64_t)a->Hq * Tq;  // (head, row) pairs: the kernel's columns
+    if (a->B > 65535 || (n_cols + 15) / 16 > 65535) return PLX_ERR_SHAPE;  // grid dimensions
     if (!(a->scale >= 0.f && a->scale <= 3.0e38f)) return PLX_ERR_SCALE;
     if (!aligned16(a->q) || !aligned16(a->r) || !aligned16(a->ckv) || !aligned16(a->o)) return PLX_ERR_ALIGN;
     if (a->seq_lens && (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u)) return PLX_ERR_ALIGN;
@@ -446,6 +449,7 @@ plx_status parallax_decode_mla(const plx_decode_mla_args *a, void *hip_stream) {
     plx::MlaDecodeParams p{};
     p.q = a->q, p.r = a->r, p.ckv = a->ckv, p.o = a->o, p.seq_lens = a->seq_lens;
     p.B = a->B, p.Hq = a->Hq, p.Lmax = a->Lmax;
+    p.Tq = Tq, p.window = a->window;
     p.csb = a->ckv_stride_b, p.csl = a->ckv_stride_l;
     p.scale = a->scale;
     if (a->block_table) {
@@ -453,12 +457,12 @@ plx_status parallax_decode_mla(const plx_decode_mla_args *a, void *hip_stream) {
         p.page_size = a->page_size, p.table_stride = a->block_table_stride, p.num_pages = a->num_pages;
     }
     int32_t S = a->num_splits;
-    if (S == 0) S = parallax_decode_mla_num_splits(a->B, a->Hq, a->Lmax, 0);
+    if (S == 0) S = parallax_decode_mla_num_splits(a->B, (int32_t)n_cols, a->Lmax, 0);
     p.S = S;
     p.direct_out = S == 1;
     if (S > 1) {
         if (!a->workspace || !aligned16(a->workspace)) return PLX_ERR_WORKSPACE;
-        if (a->workspace_bytes < (size_t)a->B * a->Hq * S * (2 * 512 + 4) * sizeof(float)) return PLX_ERR_WORKSPACE;
+        if (a->workspace_bytes < (size_t)a->B * n_cols * S * (2 * 512 + 4) * sizeof(float)) return PLX_ERR_WORKSPACE;
         p.ws = static_cast<float *>(a->workspace);
     }
     return plx::launch_decode_mla(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? PLX_OK

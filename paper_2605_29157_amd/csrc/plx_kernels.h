@@ -66,8 +66,10 @@ struct MlaDecodeParams {
     const void *q, *r, *ckv;
     void *o;
     const int32_t *seq_lens;
-    float *ws;  // split partials: [B][Hq][S] records of (2 * 512 + 4) floats
+    float *ws;  // split partials: [B][Hq * Tq][S] records of (2 * 512 + 4) floats
     int32_t B, Hq, Lmax, S;
+    int32_t Tq;      // query rows per head (q, r [B, Hq, Tq, 576]) at the last Tq positions
+    int32_t window;  // > 0: a row sees its own position and the window - 1 before it
     int64_t csb, csl;  // element strides of the cache: batch (page, when paged), token
     float scale;
     int32_t direct_out;  // 1: S == 1, the kernel writes o itself

@@ -208,3 +208,93 @@ def test_paged_cache_matches_contiguous(plx, synth, mla, page_size):
                                   block_table=table2, max_len=700)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(host(got), want)
+
+
+# ---- several query rows per head, sliding window, prefill over the latent cache ----------------
+def _rows_inputs(synth, B, Hq, Tq, L, seed, ragged=False):
+    x = synth.mla_decode_inputs(B, Hq * Tq, L, seed=seed, device=DEV, ragged=ragged)
+    x["q"] = x["q"].view(B, Hq, Tq, -1)
+    x["r"] = x["r"].view(B, Hq, Tq, -1)
+    return x
+
+
+def _check_rows(plx, mla, x, window=0, num_splits=0, paged=None, tol=BF16_REL_L2):
+    kw = {}
+    ckv = x["ckv"]
+    if paged is not None:
+        ckv, kw["block_table"], kw["max_len"] = paged[0], paged[1], x["ckv"].shape[1]
+    out = plx.parallax_decode_mla(x["q"], x["r"], ckv, x["scale"], seq_lens=x.get("seq_lens"),
+                                  num_splits=num_splits, window=window, **kw)
+    torch.cuda.synchronize()
+    sl = x["seq_lens"].cpu().numpy() if x.get("seq_lens") is not None else None
+    ref = mla.mla_rows(host(x["q"]), host(x["r"]), host(x["ckv"]), x["d_latent"], x["scale"], sl, window=window)
+    got = host(out)
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    assert rel_l2(got, ref) <= tol, (rel_l2(got, ref), window, num_splits)
+    norm = np.linalg.norm(ref, axis=-1)
+    err = np.linalg.norm(got - ref, axis=-1)[norm > 0] / norm[norm > 0]
+    assert err.max() <= 4 * tol, err.max()
+    assert (got[norm == 0] == 0).all()        # rows that see no token: zeros, exactly
+    return got
+
+
+@pytest.mark.parametrize("Hq,Tq,L", [(16, 2, 300), (16, 4, 1000), (5, 3, 129), (2, 8, 64), (1, 16, 500),
+                                      (3, 7, 70), (16, 5, 4)])
+def test_several_query_rows_at_the_last_positions(plx, synth, mla, Hq, Tq, L):
+    """Row t of a head sees the tokens up to position L - Tq + t: every (head, row) pair is a
+    column of its own; L < Tq leaves the first rows without a token."""
+    x = _rows_inputs(synth, 2, Hq, Tq, L, seed=4600 + L)
+    _check_rows(plx, mla, x, num_splits=1)
+    _check_rows(plx, mla, x, num_splits=0)
+    _check_rows(plx, mla, x, num_splits=3)
+
+
+def test_several_query_rows_ragged_and_paged(plx, synth, mla):
+    x = _rows_inputs(synth, 5, 8, 4, 900, seed=4700, ragged=True)
+    x["seq_lens"][1] = 0
+    x["seq_lens"][2] = 2                       # shorter than Tq
+    _check_rows(plx, mla, x)
+    _check_rows(plx, mla, x, num_splits=4)
+    pool, table = synth.mla_paged_cache(x, 64, seed=4701)
+    _check_rows(plx, mla, x, paged=(pool, table))
+    pool, table = synth.mla_paged_cache(x, 48, seed=4702)
+    _check_rows(plx, mla, x, window=100, paged=(pool, table))
+
+
+@pytest.mark.parametrize("Tq,L,W", [(1, 1000, 1), (1, 1000, 64), (1, 1000, 65), (1, 1000, 300), (1, 300, 5000),
+                                     (4, 1000, 130), (3, 200, 2), (8, 2048, 1000)])
+def test_sliding_window(plx, synth, mla, Tq, L, W):
+    """A row sees its own position and the W - 1 before it: the tiles before the earliest window
+    of the workgroup's columns are not visited."""
+    x = _rows_inputs(synth, 2, 16, Tq, L, seed=4800 + L + W)
+    _check_rows(plx, mla, x, window=W, num_splits=1)
+    _check_rows(plx, mla, x, window=W, num_splits=0)
+    _check_rows(plx, mla, x, window=W, num_splits=5)
+
+
+@pytest.mark.parametrize("Hq,T,W", [(2, 300, 0), (4, 513, 0), (1, 1000, 0), (3, 400, 100)])
+def test_causal_prefill_over_the_latent_cache(plx, synth, mla, Hq, T, W):
+    """Tq = the prompt length: every row of the prompt attends to the latent rows up to its own."""
+    x = _rows_inputs(synth, 2, Hq, T, T, seed=4900 + T)
+    _check_rows(plx, mla, x, window=W)
+    # a chunk of 128 rows behind 500 cached tokens
+    x = _rows_inputs(synth, 1, Hq, 128, 628, seed=4901 + T)
+    _check_rows(plx, mla, x, window=W)
+
+
+def test_rows_and_window_arguments_are_validated(plx, synth):
+    import ctypes
+
+    x = _rows_inputs(synth, 1, 4, 2, 100, seed=4950)
+    out = torch.empty(1, 4, 2, 512, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(8 * 4 * 1028, dtype=torch.float32, device=DEV)
+    lib, sptr = plx.load_library(), int(torch.cuda.current_stream().cuda_stream)
+    a = plx.decode_mla_args(x["q"], x["r"], x["ckv"], out, x["scale"], None, 4, ws)
+    assert lib.parallax_decode_mla(ctypes.byref(a), sptr) == 0
+    a.window = -1
+    assert lib.parallax_decode_mla(ctypes.byref(a), sptr) == plx.PLX_ERR_SHAPE
+    a.window, a.Tq = 0, -2
+    assert lib.parallax_decode_mla(ctypes.byref(a), sptr) == plx.PLX_ERR_SHAPE
+    a.Tq, a.num_splits = 2, 8                  # the workspace holds 4 splits of 8 columns
+    assert lib.parallax_decode_mla(ctypes.byref(a), sptr) == plx.PLX_ERR_WORKSPACE
+    torch.cuda.synchronize()

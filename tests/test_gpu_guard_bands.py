@@ -120,6 +120,19 @@ def test_decode_mla_outputs_and_workspace(plx, synth, B, Hq, L, S):
     g.check(("parallax_decode_mla", B, Hq, L, S))
 
 
+@pytest.mark.parametrize("Hq,Tq,L,S,W", [(5, 3, 700, 4, 0), (2, 70, 130, 1, 0), (16, 2, 1000, 7, 200)])
+def test_decode_mla_rows_and_window(plx, synth, Hq, Tq, L, S, W):
+    B = 2
+    x = synth.mla_decode_inputs(B, Hq * Tq, L, seed=7350 + L, device=DEV, ragged=True)
+    q, r = x["q"].view(B, Hq, Tq, 576), x["r"].view(B, Hq, Tq, 576)
+    g = Guarded()
+    out = g.empty((B, Hq, Tq, 512), torch.bfloat16)
+    ws = g.empty((B * Hq * Tq * S * (2 * 512 + 4),), torch.float32) if S > 1 else None
+    a = plx.decode_mla_args(q, r, x["ckv"], out, x["scale"], x["seq_lens"], S, ws, window=W)
+    _call(plx, "parallax_decode_mla", a)
+    g.check(("parallax_decode_mla", Hq, Tq, L, S, W))
+
+
 @pytest.mark.parametrize("T,Tkv,d,causal,window", [(300, 300, 128, True, 0), (129, 129, 64, True, 0),
                                                     (77, 500, 128, True, 0), (300, 300, 128, False, 0),
                                                     (333, 333, 128, True, 50), (1, 1, 128, True, 0),
