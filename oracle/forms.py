@@ -3,15 +3,19 @@
 * ``covariance_form``  -- o = vbar - Sigma_KV rho, the right-hand side of the paper's
   forward equation (Sec. 3.1), with the d x d softmax-weighted KV covariance formed
   explicitly.
-* ``streaming_*``      -- the tile loop of Algorithm 1 (Sec. 3.3) taken step by step in the
-  paper's notation (S1, m, alpha, P1, S2, P2, d1, d2, O1, O2), with tile size and split
-  boundaries as parameters, plus the split merge and final formula of App. C
-  ("in-kernel reduction": log-sum-exp rescale of the partials (m, d1, d2, O1, O2), then
-  O1/d1 * (1 + d2/d1) - O2/d1).
+* ``streaming_*``      -- the forward as a fold over keys. From the re-weighted softmax form
+  of Sec. 3.1, o = sum_j p_j (1 + ubar - u_j) v_j with p_j = w_j / omega, everything a row
+  needs from a set J of keys is five moments of the unnormalised weights w_j = 2^(a_j - lam)
+  (a_j = scale * log2(e) * q.k_j, lam any reference):
+      omega = sum w_j,  mu = sum w_j u_j,  Mv = sum w_j v_j,  Muv = sum w_j u_j v_j
+  and then  o = Mv / omega * (1 + mu / omega) - Muv / omega.  The state (lam, omega, mu, Mv, Muv)
+  of one key is (a_j, 1, u_j, v_j, u_j v_j); the states of disjoint key sets merge by bringing
+  both to the larger reference and adding (``merge_states``). A split-KV workspace record
+  (Sec. 3.3, App. C) is exactly such a state for the keys of the split, which is what the tests
+  compare the kernels' records with; tiling enters only through the order of the merges.
 
-Reading taken where the listing is ambiguous: the listing exponentiates with exp2 while
-the definition uses exp(q.k/h); the user-facing ``scale`` is 1/h for the natural
-exponential and the loop multiplies it by log2(e) before using exp2.
+The user-facing ``scale`` is 1/h of the natural exponential exp(q.k/h); states are kept in the
+base-2 domain (a_j carries the factor log2 e), as the split records are.
 
 These are used by the tests to check that the three forms agree for any tiling / split
 (an algebraic identity of the paper) and as the reference for what a split-KV workspace
@@ -56,70 +60,70 @@ def covariance_form(q, r, k, v, scale, causal=False, seq_lens=None):
     return out
 
 
+def _key_state(Qr, Rr, kj, vj, s, allowed):
+    """State of the single key j for every row: (a_j, 1, u_j, v_j, u_j v_j), or the empty state
+    (-inf, 0, 0, 0, 0) for rows that may not see the key."""
+    lam = np.where(allowed, s * (Qr @ kj), -np.inf)
+    w = allowed.astype(np.float64)
+    u = w * (Rr @ kj)
+    return lam, w, u, w[:, None] * vj[None, :], u[:, None] * vj[None, :]
+
+
+def merge_states(A, B):
+    """States of two disjoint key sets -> state of their union: both are brought to the larger
+    reference, then the moments add. The empty state is the neutral element."""
+    lam = np.maximum(A[0], B[0])
+    safe = np.where(np.isfinite(lam), lam, 0.0)
+    fa = np.where(np.isfinite(A[0]), np.exp2(A[0] - safe), 0.0)
+    fb = np.where(np.isfinite(B[0]), np.exp2(B[0] - safe), 0.0)
+    return (lam, fa * A[1] + fb * B[1], fa * A[2] + fb * B[2],
+            fa[:, None] * A[3] + fb[:, None] * B[3], fa[:, None] * A[4] + fb[:, None] * B[4])
+
+
+def _empty_state(rows, dv):
+    return np.full(rows, -np.inf), np.zeros(rows), np.zeros(rows), np.zeros((rows, dv)), np.zeros((rows, dv))
+
+
 def streaming_partial(Qr, Rr, K, V, scale, tile, key_lo, key_hi, row_limit=None):
-    """Algorithm 1's loop over the keys [key_lo, key_hi) in column tiles of ``tile``.
+    """State (lam, omega, mu, Mv, Muv) of the keys [key_lo, key_hi) for every row, built key by
+    key: the keys of a group of ``tile`` are merged among themselves first, the group then joins
+    the running state (any grouping gives the same state up to rounding -- the tests vary it).
 
     Qr, Rr : [rows, d]; K, V : [L, d]. row_limit[row] (optional) = number of allowed keys
-    for that row (causal / ragged masking is applied to S1 as the listing's comment says).
-    Returns the unnormalised running state (m, d1, d2, O1, O2) in the exp2 domain.
+    for that row: it sees the keys j < row_limit[row] (causal / ragged masking).
     """
-    rows, d = Qr.shape
+    rows = Qr.shape[0]
     s = scale * LOG2E
-    m_r = np.full(rows, -np.inf)
-    d1 = np.zeros(rows)
-    d2 = np.zeros(rows)
-    O1 = np.zeros((rows, V.shape[1]))
-    O2 = np.zeros((rows, V.shape[1]))
-    c0 = key_lo
-    while c0 < key_hi:
-        c1 = min(c0 + tile, key_hi)
-        Kc, Vc = K[c0:c1], V[c0:c1]
-        S1 = (Qr @ Kc.T) * s
-        if row_limit is not None:
-            cols = np.arange(c0, c1)[None, :]
-            S1 = np.where(cols < np.asarray(row_limit)[:, None], S1, -np.inf)
-        m = np.maximum(m_r, S1.max(axis=1))
-        # rows that have seen no allowed key yet keep m = -inf; alpha and P1 are 0 there
-        safe_m = np.where(np.isfinite(m), m, 0.0)
-        alpha = np.where(np.isfinite(m_r), np.exp2(m_r - safe_m), 0.0)
-        P1 = np.exp2(S1 - safe_m[:, None])
-        P1 = np.where(np.isfinite(S1), P1, 0.0)
-        m_r = m
-        S2 = Rr @ Kc.T
-        P2 = np.where(P1 > 0.0, P1 * S2, 0.0)
-        d1 = alpha * d1 + P1.sum(axis=1)
-        d2 = alpha * d2 + P2.sum(axis=1)
-        O1 = alpha[:, None] * O1 + P1 @ Vc
-        O2 = alpha[:, None] * O2 + P2 @ Vc
-        c0 = c1
-    return m_r, d1, d2, O1, O2
+    limit = None if row_limit is None else np.asarray(row_limit)
+    total = _empty_state(rows, V.shape[1])
+    for c0 in range(key_lo, key_hi, tile):
+        group = _empty_state(rows, V.shape[1])
+        for j in range(c0, min(c0 + tile, key_hi)):
+            allowed = np.ones(rows, dtype=bool) if limit is None else (j < limit)
+            group = merge_states(group, _key_state(Qr, Rr, K[j], V[j], s, allowed))
+        total = merge_states(total, group)
+    return total
 
 
 def merge_partials(parts):
-    """Log-sum-exp merge of split partials (App. C, in-kernel reduction)."""
-    ms = np.stack([p[0] for p in parts])  # [S, rows]
-    m_star = ms.max(axis=0)
-    safe = np.where(np.isfinite(m_star), m_star, 0.0)
-    d1 = d2 = O1 = O2 = 0.0
-    for (m, a1, a2, A1, A2) in parts:
-        w = np.where(np.isfinite(m), np.exp2(m - safe), 0.0)
-        d1 = d1 + w * a1
-        d2 = d2 + w * a2
-        O1 = O1 + w[:, None] * A1
-        O2 = O2 + w[:, None] * A2
-    return m_star, d1, d2, O1, O2
+    """States of the splits of one row block -> state of all keys (the merge of App. C)."""
+    total = parts[0]
+    for part in parts[1:]:
+        total = merge_states(total, part)
+    return total
 
 
 def finalize(state):
-    """Last line of Algorithm 1: O = O1/d1 * (1 + d2/d1) - O2/d1."""
-    _, d1, d2, O1, O2 = state
-    return (O1 / d1[:, None]) * (1.0 + d2 / d1)[:, None] - O2 / d1[:, None]
+    """o = Mv / omega * (1 + mu / omega) - Muv / omega (the re-weighted softmax form of Sec. 3.1
+    written in the five moments)."""
+    _, omega, mu, Mv, Muv = state
+    return (Mv / omega[:, None]) * (1.0 + mu / omega)[:, None] - Muv / omega[:, None]
 
 
 def streaming_form(q, r, k, v, scale, causal=False, seq_lens=None, tile=16, row_block=8,
                    split_points=None):
-    """Whole forward through Algorithm 1 + split merge. ``split_points`` is an increasing list
-    of key indices cutting [0, Lk) into parts (empty parts allowed)."""
+    """Whole forward as a fold over keys with split merge. ``split_points`` is an increasing
+    list of key indices cutting [0, Lk) into parts (empty parts allowed)."""
     q, r, k, v = (np.asarray(x, dtype=np.float64) for x in (q, r, k, v))
     B, Hq, Tq, d = q.shape
     _, Hkv, Lk, _ = k.shape

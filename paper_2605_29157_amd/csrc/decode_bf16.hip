@@ -88,7 +88,9 @@ __device__ __forceinline__ void merge_records(const float *const (&rec0)[NROW], 
                                               MergeScratch<D> *sm) {
     constexpr int DL = MergeScratch<D>::DL, SL = MergeScratch<D>::SL;
     constexpr int REC = 2 * D + 4;
-    constexpr int U = NROW == 1 ? 4 : 2;  // records per thread and trip
+    // records per thread and trip: with D = 128 a trip covers 64 records (32 per row for two
+    // rows), so that up to 64 splits are merged with every load in flight at once
+    constexpr int U = NROW == 1 ? 8 : 4;
     const int sl = tid / DL, dl = tid % DL;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 

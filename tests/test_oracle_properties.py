@@ -24,7 +24,7 @@ def test_forms_weights_and_invariances(oracle, shape, causal):
     rng = np.random.default_rng(seed)
     q, r, k, v = _draw(rng, B, Hq, Hkv, Tq, Lk, d)
     out = oracle.forward(q, r, k, v, scale, causal=causal)
-    # the covariance form and Algorithm 1 with odd tiles and split points agree
+    # the covariance form and the fold over keys with odd groupings and split points agree
     np.testing.assert_allclose(forms.covariance_form(q, r, k, v, scale, causal=causal), out,
                                rtol=1e-9, atol=1e-9)
     cuts = sorted(set(int(c) for c in rng.integers(0, Lk + 1, size=2)))
