@@ -82,7 +82,8 @@ def main():
     ap.add_argument("--counter-mode", action="store_true",
                     help="short run for hardware-counter collection: 5 launches of the plain copy "
                          "kernel on 1 GiB (known size, calibrates FETCH_SIZE / WRITE_SIZE) and "
-                         "--steps launches of the split-KV kernel; prints nothing to parse")
+                         "--steps launches of the split-KV kernel (with --workload prefill: of the "
+                        "prefill kernel); prints nothing to parse")
     opt = ap.parse_args()
     if opt.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path "
@@ -279,6 +280,16 @@ def prefill_line(torch, plx, synth, dev, opt):
 
     def step():
         plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True, out=out)
+
+    if opt.counter_mode:  # hardware-counter collection: the copy of known size, then the kernel
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            plx.parallax_util_copy(dst, src)
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return {"counter_mode": True, "copy_bytes_each_way": src.numel()}
 
     us = _time_events(torch, step, warm, steps)
     flops = B * Hq * 8 * d * T * (T + 1) / 2
