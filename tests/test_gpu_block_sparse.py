@@ -243,3 +243,29 @@ def test_sparse_lists_are_validated(plx, synth):
     with pytest.raises(plx.ParallaxError):    # no window together with a block mask
         plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], window=64,
                              block_mask=torch.ones(2, 4, device=DEV))
+
+
+def test_backward_at_the_benchmark_launch(plx, synth, masked):
+    """The block-sparse backward bench.py times (config-4 shape, causal, a random quarter of the
+    tiles): the gradients of two (batch, KV head) pairs of that launch against the oracle."""
+    B, Hq, Hkv, T, d = 4, 16, 8, 4096, 128
+    y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1010, device=DEV)
+    g = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=3700, device=DEV)["q"].contiguous()
+    nrb, nkt = T // 128, T // 64
+    bm = np.random.default_rng(1011).random((nrb, nkt)) < 0.25
+    bm &= np.arange(nkt)[None, :] <= 2 * np.arange(nrb)[:, None] + 1
+    bm[5] = False                                   # a row block that lists nothing
+    mask_t = torch.as_tensor(bm, device=DEV)
+    o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True,
+                                          block_mask=mask_t, save_for_backward=True)
+    grads = plx.parallax_prefill_backward(y["q"], y["r"], y["k"], y["v"], o, vbar, stats, g, y["scale"],
+                                          causal=True, block_mask=mask_t)
+    torch.cuda.synchronize()
+    dense = masked.block_mask_to_dense(bm, T, T, 128, 64, True)
+    for b, hk in ((0, 3), (3, 6)):
+        qs, ks = slice(2 * hk, 2 * hk + 2), slice(hk, hk + 1)
+        want = masked.masked_backward(host(y["q"][b:b + 1, qs]), host(y["r"][b:b + 1, qs]),
+                                      host(y["k"][b:b + 1, ks]), host(y["v"][b:b + 1, ks]), host(g[b:b + 1, qs]),
+                                      y["scale"], dense)
+        for name, got, ref, hs in zip(("dq", "dr", "dk", "dv"), grads, want, (qs, qs, ks, ks)):
+            assert_gradient_close(name, host(got[b:b + 1, hs]), ref, BF16_REL_L2, (b, hk))

@@ -298,3 +298,39 @@ def test_rows_and_window_arguments_are_validated(plx, synth):
     a.Tq, a.num_splits = 2, 8                  # the workspace holds 4 splits of 8 columns
     assert lib.parallax_decode_mla(ctypes.byref(a), sptr) == plx.PLX_ERR_WORKSPACE
     torch.cuda.synchronize()
+
+
+def test_many_heads_and_rows_at_the_benchmark_launches(plx, synth, mla):
+    """The launches bench.py times: B=16 x 128 heads x L=8192 (eight column groups per sequence,
+    heuristic splits), 4 rows x 16 heads at the end of L=16384, and the causal prefill of 4096
+    latent rows -- the oracle on sampled sequences / rows."""
+    x = synth.mla_decode_inputs(16, 128, 8192, seed=4960, device=DEV)
+    out = plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"])
+    torch.cuda.synchronize()
+    seqs = [0, 7, 15]
+    assert rel_l2(host(out)[seqs], _ref(mla, x, seqs)) <= BF16_REL_L2
+
+    x = _rows_inputs(synth, 8, 16, 4, 16384, seed=4961)
+    out = plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"])
+    torch.cuda.synchronize()
+    for b in (0, 5):
+        ref = mla.mla_rows(host(x["q"][b:b + 1]), host(x["r"][b:b + 1]), host(x["ckv"][b:b + 1]), 512, x["scale"])
+        assert rel_l2(host(out[b:b + 1]), ref) <= BF16_REL_L2
+
+    T = 4096
+    x = _rows_inputs(synth, 1, 16, T, T, seed=4962)
+    out = host(plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"]))
+    assert np.isfinite(out).all()
+    rng = np.random.default_rng(4963)
+    # a row of every 16-row workgroup of two heads, the first and last 32 rows of another
+    picks = [(h, int(rng.integers(blk, blk + 16))) for h in (0, 9) for blk in range(0, T, 16)]
+    picks += [(15, t) for t in list(range(32)) + list(range(T - 32, T))]
+    c = host(x["ckv"])
+    q, r = host(x["q"]), host(x["r"])
+    err2 = ref2 = 0.0
+    for (h, t) in picks:
+        one = mla.mla_decode(q[:, h:h + 1, t], r[:, h:h + 1, t], c, 512, x["scale"], np.array([t + 1]))[0, 0]
+        err2 += float(((out[0, h, t] - one) ** 2).sum())
+        ref2 += float((one ** 2).sum())
+        assert np.linalg.norm(out[0, h, t] - one) <= 4e-2 * np.linalg.norm(one), (h, t)
+    assert (err2 / ref2) ** 0.5 <= BF16_REL_L2

@@ -218,3 +218,43 @@ def test_preparation_arguments_are_validated(plx):
                              save_for_backward=True)
     with pytest.raises(plx.ParallaxError):
         plx.parallax_rope_table(16, 127, device=DEV)
+
+
+def test_prefill_preparing_q_and_rho_at_the_benchmark_launch(plx, nr, oracle):
+    """The launch bench.py times for the in-kernel preparation (config-4 shape, theta 1e6,
+    positions 0..4095): oracle chain on a row of every workgroup plus the first and last 128 rows
+    of two heads -- norm + rope in float64 on the raw rows, then the attention oracle on the
+    prepared keys."""
+    from paper_2605_29157_amd import synth
+
+    B, T, Hq, Hkv, d = 4, 4096, 16, 8, 128
+    y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1009, device=DEV, k_offset_sigma=0.5)
+    gq, gr, gk = (1.0 + 0.1 * _rand((d,), 71 + i, torch.float32) for i in range(3))
+    (k2,) = plx.parallax_norm_rope([(y["k"], gk, True)])
+    table = plx.parallax_rope_table(T, d, device=DEV)
+    out = plx.parallax_prefill(y["q"], y["r"], k2, y["v"], y["scale"], causal=True,
+                               prep=plx.qr_prep(gq, gr, table, None))
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(72)
+    rows = {(b, h, int(rng.integers(blk, blk + 128))) for b in range(B) for h in range(Hq) for blk in range(0, T, 128)}
+    for (b, h) in ((0, 0), (3, 15)):
+        rows |= {(b, h, i) for i in list(range(128)) + list(range(T - 128, T))}
+    rows = np.array(sorted(rows), dtype=np.int32)
+    # the sampled rows, prepared by the oracle (one row block per sampled row: [1, 1, 1, d])
+    qs = host(y["q"])[rows[:, 0], rows[:, 1], rows[:, 2]][:, None, None, :]
+    rs = host(y["r"])[rows[:, 0], rows[:, 1], rows[:, 2]][:, None, None, :]
+    pos = rows[:, 2][:, None, None]
+    qo, ro = nr.norm_rope(qs, host(gq), pos)[:, 0, 0], nr.norm_rope(rs, host(gr), pos)[:, 0, 0]
+    ko = nr.norm_rope(host(y["k"]), host(gk), np.arange(T)[None, None, :])
+    # attention oracle row by row through its row-sample interface: put the prepared rows back
+    # into otherwise-zero q, r tensors (only the sampled rows are evaluated)
+    qfull, rfull = np.zeros((B, Hq, T, d)), np.zeros((B, Hq, T, d))
+    qfull[rows[:, 0], rows[:, 1], rows[:, 2]] = qo
+    rfull[rows[:, 0], rows[:, 1], rows[:, 2]] = ro
+    ref = oracle.forward(qfull, rfull, ko, host(y["v"]), y["scale"], causal=True, rows=rows)
+    sub = got[rows[:, 0], rows[:, 1], rows[:, 2]]
+    assert rel_l2(sub, ref) <= BF16_REL_L2
+    per_row = np.linalg.norm(sub - ref, axis=1) / np.linalg.norm(ref, axis=1)
+    assert per_row.max() <= 5e-2, rows[int(per_row.argmax())]
