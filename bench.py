@@ -315,7 +315,7 @@ def backward_line(torch, plx, synth, dev, opt):
     dK/dV pass, from the row cache a forward call left behind. 22 d flops per allowed (row, key)
     pair: eleven contractions of 2 d flops (five in the row pass, six in the column pass)."""
     B, T = (int(v) for v in opt.prefill_shape.split(","))
-    Hq, Hkv, d = 16, 8, 128
+    Hq, Hkv, d = (int(v) for v in opt.prefill_heads.split(","))
     y = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1004, device=dev, k_offset_sigma=0.5)
     g = synth.prefill_inputs(B, Hq, Hkv, T, d, seed=1014, device=dev)["q"].contiguous()
     o, vbar, stats = plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], causal=True,
@@ -358,14 +358,14 @@ def backward_line(torch, plx, synth, dev, opt):
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(us / 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "backward of causal prefill bf16 B=%d T=%d Hq=16 Hkv=8 d=128, "
-                               "K offset N(0,0.5^2)" % (B, T),
+        "config": {"workload": "backward of causal prefill bf16 B=%d T=%d Hq=%d Hkv=%d d=%d, "
+                               "K offset N(0,0.5^2)" % (B, T, Hq, Hkv, d),
                    "algorithmic_flops": flops, "forward_ms": round(fwd_us / 1e3, 4),
                    "forward_with_row_cache_ms": round(fwd_cache_us / 1e3, 4),
                    "forward_with_row_cache_plus_backward_TFLOPs": round(train_tf, 1)},
         "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "bwd_dq_dr_kernel<128,true,false> + bwd_dk_dv_kernel<128,true,false>",
+                     "kernel": "bwd_dq_dr_kernel<%d,true,false> + bwd_dk_dv_kernel<%d,true,false>" % (d, d),
                      "kernel_us": round(us, 1)},
     }
 
