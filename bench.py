@@ -477,6 +477,33 @@ def extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out):
     us = _time_events(torch, twin, 20, 200)
     extra["config2_softmax_only_us"] = round(us, 2)
 
+    # config 2 with RMSNorm + RoPE on q, rho inside the decode kernel (weights, (cos, sin) table,
+    # rows at position L - 1), interleaved with the plain step
+    gam_q = 1.0 + 0.1 * torch.randn(128, device=dev)
+    gam_r = 1.0 + 0.1 * torch.randn(128, device=dev)
+    rtable = plx.parallax_rope_table(4096, 128, device=dev)
+    prep_args = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], out, x["scale"], None, True, 0, ws) for x in x0]
+    for a in prep_args:
+        a.prep = plx.qr_prep(gam_q, gam_r, rtable, None)
+    plain_args = [plx.decode_args(x["q"], x["r"], x["k"], x["v"], out, x["scale"], None, True, 0, ws) for x in x0]
+
+    def make(args):
+        c = [0]
+
+        def step():
+            st = lib.parallax_decode(ctypes.byref(args[c[0] % len(args)]), sptr)
+            c[0] += 1
+            if st != 0:
+                raise plx.ParallaxError(st, "decode with preparation")
+        return step
+
+    res = {"plain": [], "preparing": []}
+    for _ in range(3):
+        res["plain"].append(_time_events(torch, make(plain_args), 20, 200))
+        res["preparing"].append(_time_events(torch, make(prep_args), 20, 200))
+    extra["config2_decode_preparing_q_rho"] = {"plain_us": round(min(res["plain"]), 2),
+                                               "preparing_us": round(min(res["preparing"]), 2)}
+
     # config 2 again as a HIP graph: the 8 rotated steps captured once, replayed (removes the
     # host's launch cost from the step time; every replay is the same 16 kernels)
     graph = torch.cuda.CUDAGraph()

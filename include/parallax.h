@@ -402,6 +402,13 @@ typedef struct {
     float eps;   /* >= 0 */
     float theta; /* > 1 */
     plx_dtype dtype;
+    /* Optional: (cos, sin) per (position, pair) from parallax_rope_table (same d and theta; fp32,
+     * 16-byte aligned) instead of evaluating them in the kernel, positions clamped to
+     * [0, table_positions). Worth it for decode steps (T = 1): the in-kernel evaluation forms the
+     * angle in double precision, about 20 us of serial arithmetic that a long T amortises over
+     * all heads but a single row does not. NULL = evaluate. */
+    const float *rope_table;
+    int32_t table_positions;
 } plx_norm_rope_args;
 
 plx_status parallax_norm_rope(const plx_norm_rope_args *args, void *hip_stream);

@@ -134,7 +134,7 @@ class plx_norm_rope_args(ctypes.Structure):
     _fields_ = [("tensors", plx_norm_rope_tensor * 3), ("n_tensors", ctypes.c_int32),
                 ("B", ctypes.c_int32), ("T", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("pos0", ctypes.c_void_p), ("eps", ctypes.c_float), ("theta", ctypes.c_float),
-                ("dtype", ctypes.c_int)]
+                ("dtype", ctypes.c_int), ("rope_table", ctypes.c_void_p), ("table_positions", ctypes.c_int32)]
 
 
 class ParallaxError(RuntimeError):
@@ -551,7 +551,7 @@ def parallax_prefill_backward(q, r, k, v, o, vbar, row_stats, d_o, scale, causal
     return dq, dr, dk, dv
 
 
-def norm_rope_args(tensors, pos0=None, eps=1e-6, theta=1.0e6):
+def norm_rope_args(tensors, pos0=None, eps=1e-6, theta=1.0e6, rope_table=None):
     """Fill a plx_norm_rope_args. tensors: up to three (x, gamma, rope, out) with x, out
     [B, H, T, d] contiguous (out may be x) and gamma [d] fp32."""
     a = plx_norm_rope_args()
@@ -568,16 +568,20 @@ def norm_rope_args(tensors, pos0=None, eps=1e-6, theta=1.0e6):
     a.pos0 = pos0.data_ptr() if pos0 is not None else None
     a.eps, a.theta = float(eps), float(theta)
     a.dtype = _dtype_code(tensors[0][0])
+    if rope_table is not None:  # [n_pos, d / 2, 2] fp32 from parallax_rope_table (same d, theta)
+        if rope_table.dtype != torch.float32 or not rope_table.is_contiguous() or rope_table.shape[1] != d // 2:
+            raise ValueError("rope_table must be the contiguous fp32 [n_pos, d/2, 2] table of this d")
+        a.rope_table, a.table_positions = rope_table.data_ptr(), rope_table.shape[0]
     return a
 
 
-def parallax_norm_rope(tensors, pos0=None, eps=1e-6, theta=1.0e6, stream=None, inplace=False):
+def parallax_norm_rope(tensors, pos0=None, eps=1e-6, theta=1.0e6, stream=None, inplace=False, rope_table=None):
     """RMSNorm + RoPE on up to three tensors in one launch. tensors: list of (x, gamma, rope);
     returns the list of results (the inputs themselves with inplace=True)."""
     if pos0 is not None and pos0.dtype != torch.int32:
         raise TypeError("pos0 must be int32")
     full = [(x, g, rp, x if inplace else torch.empty_like(x)) for (x, g, rp) in tensors]
-    a = norm_rope_args(full, pos0, eps, theta)
+    a = norm_rope_args(full, pos0, eps, theta, rope_table)
     st = load_library().parallax_norm_rope(ctypes.byref(a), _stream_ptr(stream))
     if st != PLX_OK:
         raise ParallaxError(st, "parallax_norm_rope")

@@ -77,8 +77,11 @@ def _check_decode_assembly() -> None:
         if "decode_bf16_kernel" in name:
             spills[name] = int(re.search(r"\.vgpr_spill_count:\s+(\d+)", block).group(1))
     # (the instantiations that normalise and rotate q, rho first -- last template flag set -- may
-    # park a few registers around that prologue; the loop is what must not spill)
-    bad = {n: c for n, c in spills.items() if c and not n.endswith("Lb1EEEvNS_12DecodeParamsE")}
+    # park a few registers around that prologue: the paged one does, 9 of them, which costs it
+    # 6 us of a 38 us step; with 50 and more spilled, as a first form of that prologue had, the
+    # reloads queue up behind the tile loads and the step takes half as long again)
+    prep = "Lb1EEEvNS_12DecodeParamsE"
+    bad = {n: c for n, c in spills.items() if c > (16 if n.endswith(prep) else 0)}
     if not spills or bad:
         raise RuntimeError("decode_bf16.hip: register spills in a decode kernel (%s)" % bad)
 

@@ -240,6 +240,71 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
         }
     };
 
+    if constexpr (PREP && PAGED) {  // (the first tile's page numbers travel with the weights)
+        const int tk_first = key_lo + w * kTileKeys;
+        if (tk_first < key_hi) lookup_pages(tk_first);
+    }
+    // ---- RMSNorm + RoPE on the q / rho rows in their operand registers (the operations the
+    // paper's language-model runs apply in front of the attention call; formulas of
+    // norm_rope.hip, rotation from the (cos, sin) table). The weights and table entries are
+    // requested and used HERE, in front of the first tile's loads, when the memory system is
+    // still idle: behind them they queue up behind the tile traffic of the whole chip (measured:
+    // +19 us on a 30 us step), and with a tile parked in registers the arithmetic does not fit
+    // the register file (spills, whose reloads queue up the same way).
+    f32x4 prep_gq[KSTEPS][2], prep_gr[KSTEPS][2], prep_tab[KSTEPS][2];
+    if constexpr (PREP) {
+        const QrPrep &pr = p.prep;
+        int Lfull = p.seq_lens ? p.seq_lens[b] : p.Lmax;
+        Lfull = min(max(Lfull, 0), p.Lmax);
+        const int t = row0 + (live ? col_t : 0);
+        const int64_t pos = min(max(pr.pos0 ? pr.pos0[b] + t : Lfull - Tq_all + t, 0), max(pr.n_pos - 1, 0));
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const int dim = 8 * (4 * s + g);
+            prep_gq[s][0] = *(const f32x4 *)(pr.gamma_q + dim), prep_gq[s][1] = *(const f32x4 *)(pr.gamma_q + dim + 4);
+            if constexpr (USE_R)
+                prep_gr[s][0] = *(const f32x4 *)(pr.gamma_r + dim), prep_gr[s][1] = *(const f32x4 *)(pr.gamma_r + dim + 4);
+            if (pr.table != nullptr) {  // (uniform)
+                const float *e = pr.table + (pos * (D / 2) + dim / 2) * 2;
+                prep_tab[s][0] = *(const f32x4 *)e, prep_tab[s][1] = *(const f32x4 *)(e + 4);
+            }
+        }
+    }
+
+    // Lane (c, g) holds dims 8 (4 s + g) .. + 7 of column c's row for every k-step s, so the row's
+    // sum of squares is this lane's plus those of the three lanes c + 16, 32, 48.
+    if constexpr (PREP) {
+        const QrPrep &pr = p.prep;
+        auto prepare = [&](u32x4(&f)[KSTEPS], const f32x4(&gam)[KSTEPS][2], bool rot) {
+            float ss = 0.f;
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lo = bf16_lo_f32(f[s][e]), hi = bf16_hi_f32(f[s][e]);
+                    ss = fmaf(lo, lo, ss);
+                    ss = fmaf(hi, hi, ss);
+                }
+            ss = rows_sum(ss);
+            const float rinv = 1.0f / sqrtf(ss * (1.0f / (float)D) + pr.eps);
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const f32x4 g0 = gam[s][0], g1 = gam[s][1];
+                const f32x4 ident = {1.f, 0.f, 1.f, 0.f};
+                const f32x4 t0 = rot ? prep_tab[s][0] : ident, t1 = rot ? prep_tab[s][1] : ident;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float gm0 = j < 2 ? g0[2 * j] : g1[2 * j - 4], gm1 = j < 2 ? g0[2 * j + 1] : g1[2 * j - 3];
+                    const float y0 = bf16_lo_f32(f[s][j]) * rinv * gm0, y1 = bf16_hi_f32(f[s][j]) * rinv * gm1;
+                    const float cs = j < 2 ? t0[2 * j] : t1[2 * j - 4], sn = j < 2 ? t0[2 * j + 1] : t1[2 * j - 3];
+                    f[s][j] = live ? pack_bf16(y0 * cs - y1 * sn, y0 * sn + y1 * cs) : 0u;
+                }
+            }
+        };
+        prepare(qf, prep_gq, pr.rope_q != 0);
+        if constexpr (USE_R) prepare(rf, prep_gr, pr.rope_r != 0);
+    }
+
     // ---- running state (per lane: column c, partial over this lane's keys) ----------------
     float m_run = kNegInf, dsum1 = 0.f, dsum2 = 0.f;
     f32x4 o1[NDB], o2[NDB];
@@ -258,61 +323,18 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeParams p) {
     const unsigned col_span = (unsigned)max(min(key_hi, col_end) - col_lo, 0);
 
     int tk = key_lo + w * kTileKeys;
+    if constexpr (PREP) {
+        // The first tile's loads must not be issued before the preparation above is through (the
+        // compiler would hoist them: then the block's registers do not fit beside the parked
+        // tile, and the reloads of what it spills wait in line behind the tile loads). An empty
+        // statement makes the first key depend on the prepared operands.
+        asm volatile("" : "+v"(tk) : "v"(qf[KSTEPS - 1][3]), "v"(rf[KSTEPS - 1][3]));
+    }
     if (tk < key_hi) {
-        lookup_pages(tk);
+        if constexpr (!(PREP && PAGED)) lookup_pages(tk);
         issue_loads(tk);
         if (tk + kWaves * kTileKeys < key_hi) lookup_pages(tk + kWaves * kTileKeys);
     }
-    // ---- RMSNorm + RoPE on the q / rho rows in their operand registers (the operations the
-    // paper's language-model runs apply in front of the attention call; formulas of
-    // norm_rope.hip, rotation from the (cos, sin) table). Placed behind the first tile's loads:
-    // they are on their way while this runs. Lane (c, g) holds dims 8 (4 s + g) .. + 7 of column c's
-    // row for every k-step s, so the row's sum of squares is this lane's plus those of the
-    // three lanes c + 16, 32, 48.
-    if constexpr (PREP) {
-        const QrPrep &pr = p.prep;
-        int Lfull = p.seq_lens ? p.seq_lens[b] : p.Lmax;
-        Lfull = min(max(Lfull, 0), p.Lmax);
-        const int t = row0 + (live ? col_t : 0);
-        const int64_t pos = min(max(pr.pos0 ? pr.pos0[b] + t : Lfull - Tq_all + t, 0), max(pr.n_pos - 1, 0));
-        auto prepare = [&](u32x4(&f)[KSTEPS], const float *gamma, bool rot) {
-            float ss = 0.f;
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float lo = bf16_lo_f32(f[s][e]), hi = bf16_hi_f32(f[s][e]);
-                    ss = fmaf(lo, lo, ss);
-                    ss = fmaf(hi, hi, ss);
-                }
-            ss = rows_sum(ss);
-            const float rinv = 1.0f / sqrtf(ss * (1.0f / (float)D) + pr.eps);
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) {
-                const int dim = 8 * (4 * s + g);
-                const f32x4 g0 = *(const f32x4 *)(gamma + dim), g1 = *(const f32x4 *)(gamma + dim + 4);
-                f32x4 t0 = {1.f, 0.f, 1.f, 0.f}, t1 = {1.f, 0.f, 1.f, 0.f};
-                if (rot) {
-                    const float *e = pr.table + (pos * (D / 2) + dim / 2) * 2;
-                    t0 = *(const f32x4 *)e, t1 = *(const f32x4 *)(e + 4);
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float gm0 = j < 2 ? g0[2 * j] : g1[2 * j - 4], gm1 = j < 2 ? g0[2 * j + 1] : g1[2 * j - 3];
-                    float y0 = bf16_lo_f32(f[s][j]) * rinv * gm0, y1 = bf16_hi_f32(f[s][j]) * rinv * gm1;
-                    if (rot) {
-                        const float cs = j < 2 ? t0[2 * j] : t1[2 * j - 4], sn = j < 2 ? t0[2 * j + 1] : t1[2 * j - 3];
-                        const float r0 = y0 * cs - y1 * sn, r1 = y0 * sn + y1 * cs;
-                        y0 = r0, y1 = r1;
-                    }
-                    f[s][j] = live ? pack_bf16(y0, y1) : 0u;
-                }
-            }
-        };
-        prepare(qf, pr.gamma_q, pr.rope_q != 0);
-        if constexpr (USE_R) prepare(rf, pr.gamma_r, pr.rope_r != 0);
-    }
-
     for (; tk < key_hi; tk += kWaves * kTileKeys) {
         // registers -> swizzled LDS tile (private to this wave)
 #pragma unroll

@@ -31,9 +31,12 @@ struct Chunk<float> {
     __device__ void set_pair(int j, float a, float b) { raw[2 * j] = a, raw[2 * j + 1] = b; }
 };
 
-// A wave owns 64 / (lanes per row) consecutive positions of one sequence and walks over every
-// head of every tensor at those positions: sine and cosine of a (position, pair) are computed
-// once and serve all heads of q, rho and k.
+// A wave owns 64 / (lanes per row) consecutive positions of one sequence and walks over a chunk
+// of the heads of every tensor at those positions: sine and cosine of a (position, pair) are
+// computed once per wave. With many positions a wave takes all heads (the trigonometry is then
+// done once per position); with few (a decode step has one row per sequence) the heads are
+// dealt over more waves, because a wave that walks 40 heads alone is a chain of 10 dependent
+// memory round trips (measured: 22 us for 8 x 16 x 1 rows, against 4 us in chunks of 4 heads).
 template <typename T>
 __global__ __launch_bounds__(256) void norm_rope_kernel(NormRopeParams p) {
     constexpr int E = Chunk<T>::E;
@@ -42,16 +45,26 @@ __global__ __launch_bounds__(256) void norm_rope_kernel(NormRopeParams p) {
     const int rows_per_wave = 64 / lpr;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lr = lane % lpr;                     // this lane's chunk of its row
-    const int t_per_seq = (p.T + rows_per_wave - 1) / rows_per_wave;  // waves per sequence
-    const int64_t wid = (int64_t)blockIdx.x * 4 + wave;
-    if (wid >= (int64_t)p.B * t_per_seq) return;   // whole waves only: no barrier below
+    const int t_per_seq = (p.T + rows_per_wave - 1) / rows_per_wave;  // position groups per sequence
+    const int64_t wid_all = (int64_t)blockIdx.x * 4 + wave;
+    if (wid_all >= (int64_t)p.B * t_per_seq * p.head_chunks) return;   // whole waves only: no barrier below
+    const int hchunk = (int)(wid_all % p.head_chunks);
+    const int64_t wid = wid_all / p.head_chunks;
     const int b = (int)(wid / t_per_seq);
     const int t = (int)(wid % t_per_seq) * rows_per_wave + lane / lpr;
     const bool live = t < p.T;
     const int ld_t = live ? t : p.T - 1;
 
     float cs[E / 2], sn[E / 2];
-    {
+    if (p.table != nullptr) {  // (uniform) from the caller's table: E floats = this lane's E / 2 pairs
+        const int64_t pos = min(max((p.pos0 ? p.pos0[b] : 0) + ld_t, 0), p.n_pos - 1);
+        const float *e = p.table + (pos * (p.d / 2) + lr * (E / 2)) * 2;
+#pragma unroll
+        for (int j = 0; j < E / 2; j += 2) {
+            const f32x4 v = *(const f32x4 *)(e + 2 * j);
+            cs[j] = v[0], sn[j] = v[1], cs[j + 1] = v[2], sn[j + 1] = v[3];
+        }
+    } else {
         const double pos = (double)((p.pos0 ? p.pos0[b] : 0) + ld_t);
         const double log2_theta = log2((double)p.theta);
 #pragma unroll
@@ -70,11 +83,12 @@ __global__ __launch_bounds__(256) void norm_rope_kernel(NormRopeParams p) {
         for (int e = 0; e < E; ++e) gam[e] = ten.gamma[lr * E + e];
         const decltype(Chunk<T>::raw) *src = (const decltype(Chunk<T>::raw) *)ten.x;
         decltype(Chunk<T>::raw) *dst = (decltype(Chunk<T>::raw) *)ten.y;
-        for (int h0 = 0; h0 < ten.H; h0 += UNROLL) {
+        const int h_end = min(ten.H, (hchunk + 1) * p.heads_per_wave);
+        for (int h0 = hchunk * p.heads_per_wave; h0 < h_end; h0 += UNROLL) {
             Chunk<T> c[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {  // all loads of the trip first
-                const int h = min(h0 + u, ten.H - 1);
+                const int h = min(h0 + u, h_end - 1);
                 c[u].raw = src[(((int64_t)b * ten.H + h) * p.T + ld_t) * lpr + lr];
             }
 #pragma unroll
@@ -94,7 +108,7 @@ __global__ __launch_bounds__(256) void norm_rope_kernel(NormRopeParams p) {
                     }
                     c[u].set_pair(j, y0, y1);
                 }
-                if (live && h0 + u < ten.H)
+                if (live && h0 + u < h_end)
                     dst[(((int64_t)b * ten.H + h0 + u) * p.T + t) * lpr + lr] = c[u].raw;
             }
         }
@@ -124,10 +138,21 @@ hipError_t launch_rope_table(float *table, int n_pos, int d, float theta, hipStr
     return hipGetLastError();
 }
 
-hipError_t launch_norm_rope(const NormRopeParams &p, bool f32, hipStream_t stream) {
+hipError_t launch_norm_rope(const NormRopeParams &p_in, bool f32, hipStream_t stream) {
+    NormRopeParams p = p_in;
     const int elems = f32 ? 4 : 8;
     const int rows_per_wave = 64 / (p.d / elems);
-    const int64_t waves = (int64_t)p.B * ((p.T + rows_per_wave - 1) / rows_per_wave);
+    const int64_t groups = (int64_t)p.B * ((p.T + rows_per_wave - 1) / rows_per_wave);
+    // heads per wave: all of them when there are position groups enough to fill the chip
+    // (about four waves per SIMD), else chunks, down to the four heads a wave has in flight
+    int max_h = 1;
+    for (int i = 0; i < p.n_tensors; ++i) max_h = p.t[i].H > max_h ? p.t[i].H : max_h;
+    int hpw = max_h;
+    while (hpw > 4 && groups * ((max_h + hpw - 1) / hpw) < 4096) hpw = (hpw + 1) / 2;
+    hpw = (hpw + 3) / 4 * 4;
+    p.heads_per_wave = hpw;
+    p.head_chunks = (max_h + hpw - 1) / hpw;
+    const int64_t waves = groups * p.head_chunks;
     const int64_t blocks = (waves + 3) / 4;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (f32)

@@ -571,6 +571,11 @@ plx_status parallax_norm_rope(const plx_norm_rope_args *a, void *hip_stream) {
     }
     p.n_tensors = a->n_tensors, p.B = a->B, p.T = a->T, p.d = d;
     p.pos0 = a->pos0, p.eps = a->eps, p.theta = a->theta;
+    if (a->rope_table) {
+        if (!aligned16(a->rope_table)) return PLX_ERR_ALIGN;
+        if (a->table_positions < 1) return PLX_ERR_SHAPE;
+        p.table = a->rope_table, p.n_pos = a->table_positions;
+    }
     return plx::launch_norm_rope(p, f32, static_cast<hipStream_t>(hip_stream)) == hipSuccess
                ? PLX_OK
                : PLX_ERR_LAUNCH;

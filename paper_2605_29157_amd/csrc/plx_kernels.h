@@ -112,6 +112,9 @@ struct NormRopeParams {
     int32_t n_tensors, B, T, d;
     const int32_t *pos0;  // [B] position of row 0 of every sequence, or NULL = 0
     float eps, theta;
+    const float *table;   // optional (cos, sin) per (position, pair); NULL = evaluate in the kernel
+    int32_t n_pos;        // positions in the table
+    int32_t heads_per_wave, head_chunks;  // set by the launcher
 };
 
 // Each returns hipSuccess or the launch error. No allocation, no synchronisation.

@@ -397,7 +397,7 @@ def test_norm_rope_rejects_bad_arguments_before_launch(binding):
     assert call(a) == binding.PLX_ERR_SHAPE
     a = good(); a.pos0 = 0x3001
     assert call(a) == binding.PLX_ERR_ALIGN
-    assert ctypes.sizeof(binding.plx_norm_rope_args) == 3 * 32 + 16 + 8 + 8 + 8
+    assert ctypes.sizeof(binding.plx_norm_rope_args) == 3 * 32 + 16 + 8 + 8 + 8 + 8 + 8
 
 
 def test_block_mask_lists_by_rows_and_by_columns(binding):

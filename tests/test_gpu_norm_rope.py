@@ -258,3 +258,35 @@ def test_prefill_preparing_q_and_rho_at_the_benchmark_launch(plx, nr, oracle):
     assert rel_l2(sub, ref) <= BF16_REL_L2
     per_row = np.linalg.norm(sub - ref, axis=1) / np.linalg.norm(ref, axis=1)
     assert per_row.max() <= 5e-2, rows[int(per_row.argmax())]
+
+
+def test_norm_rope_from_the_table_matches_the_in_kernel_evaluation(plx, nr):
+    """(cos, sin) from parallax_rope_table instead of the kernel's own evaluation: a decode step's
+    rows (T = 1 at positions up to 130 000) and a prefill chunk, bf16 and fp32, against the oracle
+    and against the evaluating kernel."""
+    for (B, H, T, d, dtype, p0) in [(4, 16, 1, 128, torch.bfloat16, [0, 77, 4095, 129999]),
+                                    (2, 6, 70, 64, torch.bfloat16, [5, 1000]),
+                                    (2, 4, 9, 32, torch.float32, [0, 300])]:
+        x = _rand((B, H, T, d), 900 + T, dtype)
+        gam = 1.0 + 0.2 * _rand((d,), 901, torch.float32)
+        pos0 = torch.tensor(p0, dtype=torch.int32, device=DEV)
+        table = plx.parallax_rope_table(max(p0) + T, d, device=DEV)
+        (a,) = plx.parallax_norm_rope([(x, gam, True)], pos0=pos0, rope_table=table)
+        (b,) = plx.parallax_norm_rope([(x, gam, True)], pos0=pos0)
+        torch.cuda.synchronize()
+        pos = host(pos0)[:, None, None] + np.arange(T)[None, None, :]
+        ref = nr.norm_rope(host(x), host(gam), pos)
+        tol = BF16_REL_L2 if dtype == torch.bfloat16 else 1e-5
+        assert rel_l2(host(a), ref) <= tol
+        assert rel_l2(host(a), host(b).astype(np.float64)) <= (2e-3 if dtype == torch.bfloat16 else 1e-5)
+    # a table that is too short is clamped, never read past; a misaligned one is refused
+    import ctypes
+    x = _rand((1, 2, 4, 128), 910, torch.bfloat16)
+    g = torch.ones(128, dtype=torch.float32, device=DEV)
+    table = plx.parallax_rope_table(2, 128, device=DEV)
+    plx.parallax_norm_rope([(x, g, True)], rope_table=table)
+    a = plx.norm_rope_args([(x, g, True, torch.empty_like(x))], rope_table=table)
+    a.rope_table += 4
+    st = plx.load_library().parallax_norm_rope(ctypes.byref(a), int(torch.cuda.current_stream().cuda_stream))
+    assert st == plx.PLX_ERR_ALIGN
+    torch.cuda.synchronize()
