@@ -66,8 +66,8 @@ typedef enum {
  * formulas as for parallax_norm_rope below): the rows are normalised, rotated and rounded to bf16 in
  * the kernel's prologue, so q and rho make no extra trip through HBM. K is prepared beforehand by
  * parallax_norm_rope (it is shared by all query heads and row blocks). bf16 only.
- *   q_gamma, r_gamma  [d] fp32 on the device: RMSNorm weights; both non-NULL switches the
- *                     preparation on (r_gamma may be NULL when use_r == 0)
+ *   q_gamma, r_gamma  [d] fp32 on the device, 16-byte aligned: RMSNorm weights; both non-NULL
+ *                     switches the preparation on (r_gamma may be NULL when use_r == 0)
  *   eps               >= 0, under the root
  *   rope_table        NULL = RMSNorm only, else [rope_positions, d/2, 2] fp32 from
  *                     parallax_rope_table: (cos, sin) of pos * theta^(-2i/d)

@@ -67,8 +67,8 @@ plx_status take_prep(const plx_qr_prep &a, plx_dtype dtype, bool use_r, plx::QrP
     if (dtype != PLX_BF16) return PLX_ERR_DTYPE;
     if (!a.q_gamma || (use_r && !a.r_gamma)) return PLX_ERR_NULL;
     if (!(a.eps >= 0.f && a.eps <= 3.0e38f)) return PLX_ERR_SCALE;
-    if ((reinterpret_cast<uintptr_t>(a.q_gamma) | reinterpret_cast<uintptr_t>(a.r_gamma) |
-         reinterpret_cast<uintptr_t>(a.pos0)) & 3u)
+    // (the kernels fetch the weights four at a time)
+    if (!aligned16(a.q_gamma) || !aligned16(a.r_gamma) || (reinterpret_cast<uintptr_t>(a.pos0) & 3u))
         return PLX_ERR_ALIGN;
     if (a.rope_table) {
         if (!aligned16(a.rope_table)) return PLX_ERR_ALIGN;

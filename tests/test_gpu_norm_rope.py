@@ -218,6 +218,11 @@ def test_preparation_arguments_are_validated(plx):
                              save_for_backward=True)
     with pytest.raises(plx.ParallaxError):
         plx.parallax_rope_table(16, 127, device=DEV)
+    with pytest.raises(plx.ParallaxError):   # weights must be 16-byte aligned (fetched four at a time)
+        g2 = torch.ones(132, dtype=torch.float32, device=DEV)[1:129]
+        bad = plx.qr_prep(g, g, table)
+        bad.q_gamma = g2.data_ptr()
+        plx.parallax_prefill(y["q"], y["r"], y["k"], y["v"], y["scale"], prep=bad)
 
 
 def test_prefill_preparing_q_and_rho_at_the_benchmark_launch(plx, nr, oracle):
