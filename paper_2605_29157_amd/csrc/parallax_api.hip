@@ -407,19 +407,39 @@ int32_t parallax_decode_mla_num_splits(int32_t B, int32_t Hq, int32_t Lmax, int3
     if (B <= 0 || Hq <= 0 || Lmax <= 0) return 1;
     if (num_cus <= 0) num_cus = query_num_cus();
     // One workgroup per compute unit is resident (tile, q / rho fragments and the two register
-    // stages fill its LDS and registers) and a workgroup pays about 10 us to start and finish:
-    // aim at ONE round of workgroups (measured: B = 64, L = 16384 takes 236 us with 4 splits, 261
-    // with 8), at least 256 keys per split, and at most 4096 keys per split so that the tail of a
-    // long or ragged batch stays short.
+    // stages fill its LDS and registers), so a launch runs in ROUNDS of num_cus workgroups. A
+    // workgroup costs about 10 us to start and finish plus, per 64-key tile, 3.2 us when the chip
+    // is full (72 KB x 256 per 3.2 us is what the memory delivers) and no less than 2.4 us (the
+    // tile's chain of phases) when W < num_cus workgroups share the memory; merging splits costs
+    // one more launch (about 6 us). The split count is the one with the smallest
+    //     (rounds - 1) * (tiles * 3.2 + 10) + (tiles * max(2.4, 3.2 * W_last / num_cus) + 10) + (S > 1 ? 6 : 0)
+    // with at least 256 keys per split. Against sweeps of S on MI355X (model / measured us):
+    // 64 pairs of (sequence, column group) x L = 16384: S = 4 221 / 226 (8: 242); 96 pairs: S = 2
+    // 323 / 344 (3, a round and an eighth: 501 / 505); 160 pairs x L = 8192: S = 3 284 / 289 (2:
+    // 384 / 392, 1: 317 / 334); 256 pairs: unsplit 829 / 813 (2: 836, 4: 864); 40 pairs x
+    // L = 32768: S = 14 362 / 356, 7: 434 / 424, 4: 323 / 340.
     const int64_t pairs = (int64_t)B * ((Hq + 15) / 16);
     const int64_t n_tiles = ((int64_t)Lmax + 63) / 64;
-    int64_t s = ((int64_t)num_cus + pairs - 1) / pairs;
-    const int64_t by_len = ((int64_t)Lmax + 4095) / 4096;
-    if (s < by_len) s = by_len;
-    const int64_t cap = n_tiles >= 8 ? n_tiles / 4 : 1;
-    if (s > cap) s = cap;
-    if (s > PLX_MAX_SPLITS) s = PLX_MAX_SPLITS;
-    return (int32_t)(s < 1 ? 1 : s);
+    int64_t cap = n_tiles >= 8 ? n_tiles / 4 : 1;
+    if (cap > PLX_MAX_SPLITS) cap = PLX_MAX_SPLITS;
+    auto cost_of = [&](int64_t s) {
+        const int64_t rounds = (pairs * s + num_cus - 1) / num_cus;
+        const int64_t tiles = (n_tiles + s - 1) / s;
+        const double w_last = (double)(pairs * s - (rounds - 1) * num_cus) / (double)num_cus;
+        const double t_last = 3.2 * w_last > 2.4 ? 3.2 * w_last : 2.4;
+        return (double)(rounds - 1) * ((double)tiles * 3.2 + 10.0) + ((double)tiles * t_last + 10.0) +
+               (s > 1 ? 6.0 : 0.0);
+    };
+    int64_t best = 1;
+    for (int64_t s = 2; s <= cap; ++s)
+        if (cost_of(s) < cost_of(best)) best = s;
+    // (among counts with as many rounds that the model cannot tell apart, the larger: a fuller
+    // round measured a few per cent better than the model gives it credit for)
+    const int64_t best_rounds = (pairs * best + num_cus - 1) / num_cus;
+    const double limit = 1.02 * cost_of(best);
+    for (int64_t s = best + 1; s <= cap && (pairs * s + num_cus - 1) / num_cus == best_rounds; ++s)
+        if (cost_of(s) <= limit) best = s;
+    return (int32_t)best;
 }
 
 plx_status parallax_decode_mla(const plx_decode_mla_args *a, void *hip_stream) {
