@@ -119,31 +119,50 @@ size_t parallax_decode_workspace_bytes(int32_t B, int32_t Hq, int32_t Hkv, int32
 
 int32_t parallax_decode_num_splits(int32_t B, int32_t Hq, int32_t Hkv, int32_t Lmax, int32_t d,
                                    int32_t num_cus) {
-    (void)d;
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Lmax <= 0) return 1;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Lmax <= 0 || d <= 0) return 1;
     if (num_cus <= 0) num_cus = query_num_cus();
-    // Measured on MI355X (sweeps over B, L and S). With few (batch, kv head) pairs the kernel is
-    // latency bound and wants many short splits: aim at one full round of the two workgroups
-    // that are resident per compute unit. From half a workgroup per compute unit on, the pairs
-    // alone keep enough loads in flight and every further split only adds partials and the
-    // merge: split by length only, at most 4096 keys per split so that the tail of a long or
-    // ragged batch stays short.
+    // A model of the launch, fitted to sweeps of S on MI355X. The dispatcher deals the W = pairs * S
+    // workgroups round-robin over the compute units, so with W = k * CUs + n2 some units get k and
+    // n2 of them k + 1; the memory system shares its bandwidth (~5.9 TB/s with two or more
+    // workgroups per unit in flight, ~5.65 with one) equally among the busy units, and a unit
+    // cannot take more than ~44 GB/s however many workgroups it holds. All units run until those
+    // with k workgroups are through (t1), the n2 others then finish their last workgroup with the
+    // bandwidth the rest has freed (t2):
+    //     x  = min(44, HBM / CUs) GB/s,          t1 = k * bytes_per_workgroup / x
+    //     x2 = min(44, HBM / n2)  GB/s,          t2 = bytes_per_workgroup / x2   (n2 > 0)
+    // plus about 3 us for a unit's first workgroup, 0.75 us for each further one and 5 us for the
+    // merge launch when S > 1. Measured us for 12 sequences x 16384 keys (96 pairs): S = 1 188,
+    // 2 137, 3 175, 4 146, 5 141, 6 152 -- a count that leaves a small remainder over a multiple
+    // of the unit count costs up to a quarter, which is what the model is for (the first rule
+    // here, "fill two workgroups per unit, rounded up", lost 9 - 19 % at 3, 5, 6, 10, 12 and 20
+    // sequences). Over sweeps of S on 20 shapes the chosen count is within 4 % of the best (one shape: 6 %). The
+    // count with the smallest estimate wins, the larger one among near-ties with as many rounds;
+    // at least two 128-key block tiles per split, and no split below 1024 keys at all (the merge
+    // kernel then costs more than the shorter loop saves).
     const int64_t pairs = (int64_t)B * Hkv;
-    const int64_t by_len = ((int64_t)Lmax + 4095) / 4096;
-    int64_t s = by_len;
-    if (2 * pairs < num_cus) {
-        const int64_t target = 2LL * num_cus;
-        s = (target + pairs - 1) / pairs;
-        if (s < by_len) s = by_len;
-    }
-    // ... but keep at least two 128-key block tiles per split, and do not split below 1024 keys
-    // at all (the merge kernel then costs more than the shorter loop saves)
+    const double total_mb = (double)pairs * (double)Lmax * (double)d * 4.0 / 1.0e6;  // K and V, bf16
     const int64_t n_bt = ((int64_t)Lmax + plx::kDecodeBlockKeys - 1) / plx::kDecodeBlockKeys;
     int64_t cap = n_bt >= 8 ? n_bt / 2 : 1;
-    if (s > cap) s = cap;
-    if (s > PLX_MAX_SPLITS) s = PLX_MAX_SPLITS;
-    if (s < 1) s = 1;
-    return (int32_t)s;
+    if (cap > PLX_MAX_SPLITS) cap = PLX_MAX_SPLITS;
+    const double cu_rate = 44.0e-3;  // MB per us
+    auto cost_of = [&](int64_t s) {
+        const int64_t w = pairs * s, k = w / num_cus, n2 = w - k * num_cus;
+        const int64_t per_cu = k + (n2 > 0 ? 1 : 0);
+        const double hbm_rate = per_cu >= 2 ? 5900.0e-3 : 5650.0e-3;
+        const double mb = total_mb / (double)w;
+        const double x = cu_rate < hbm_rate / num_cus ? cu_rate : hbm_rate / num_cus;
+        double t = (double)k * mb / x;
+        if (n2 > 0) t += mb / (cu_rate < hbm_rate / (double)n2 ? cu_rate : hbm_rate / (double)n2);
+        return t + 3.0 + 0.75 * (double)(per_cu - 1) + (s > 1 ? 5.0 : 0.0);
+    };
+    int64_t best = 1;
+    for (int64_t s = 2; s <= cap; ++s)
+        if (cost_of(s) < cost_of(best)) best = s;
+    const int64_t best_rounds = (pairs * best + num_cus - 1) / num_cus;
+    const double limit = 1.02 * cost_of(best);
+    for (int64_t s = best + 1; s <= cap && (pairs * s + num_cus - 1) / num_cus == best_rounds; ++s)
+        if (cost_of(s) <= limit) best = s;
+    return (int32_t)best;
 }
 
 namespace {

@@ -100,16 +100,19 @@ def test_split_heuristic_is_sane(binding):
         assert 1 <= s <= binding.PLX_MAX_SPLITS
         n_bt = (L + 127) // 128
         assert s <= max(1, n_bt // 2)          # at least two block tiles per split
-        if L >= 2 * 4096:
-            assert s >= (L + 4095) // 4096 or s == binding.PLX_MAX_SPLITS
     assert f(8, 16, 8, 4096, 128, 256) == 8    # 512 workgroups over 64 (batch, kv head) pairs
     assert f(1, 16, 8, 256, 128, 256) == 1
     assert f(1, 16, 8, 512, 128, 256) == 1     # no split below 1024 keys
     assert f(1, 16, 8, 1024, 128, 256) == 4
-    # from half a workgroup per compute unit on: split by length only
+    # enough pairs to keep every compute unit reading: no split, or a whole number of rounds
     assert f(16, 16, 8, 2048, 128, 256) == 1
-    assert f(16, 16, 8, 16384, 128, 256) == 4
+    assert f(16, 16, 8, 16384, 128, 256) == 4  # 512 workgroups
     assert f(32, 16, 8, 4096, 128, 256) == 1
+    # no small remainder over a multiple of the unit count: 160 pairs stay 160 workgroups (320
+    # would leave 64 units a second workgroup each), 96 pairs become 480, 24 pairs 504
+    assert f(20, 16, 8, 8192, 128, 256) == 1
+    assert f(12, 16, 8, 16384, 128, 256) == 5
+    assert f(3, 16, 8, 16384, 128, 256) == 21
     assert f(32, 16, 8, 8192, 128, 256) == 2
 
 
