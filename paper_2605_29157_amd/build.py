@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_PATH = os.path.join(PKG, "libparallax_hip.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["parallax_api.hip", "decode_bf16.hip", "decode_mla_bf16.hip", "prefill_bf16.hip", "prefill_bwd_bf16.hip",
+SOURCES = ["parallax_api.hip", "decode_bf16.hip", "decode_mla_bf16.hip", "decode_mla_wide_bf16.hip", "prefill_bf16.hip", "prefill_bwd_bf16.hip",
            "generic_f32.hip", "norm_rope.hip", "util_kernels.hip"]
 
 # packed-fp32 instructions are disabled for all device code (hipcc's host pass prints a
@@ -95,6 +95,7 @@ def build_library(extra_flags: list[str] | None = None, verbose: bool = True) ->
     _check_pipelined_assembly("prefill_bf16.hip", True)
     _check_pipelined_assembly("prefill_bwd_bf16.hip", False)
     _check_pipelined_assembly("decode_mla_bf16.hip", False)
+    _check_pipelined_assembly("decode_mla_wide_bf16.hip", False)
     _check_decode_assembly()
     tmp = LIB_PATH + ".tmp%d" % os.getpid()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]

@@ -36,37 +36,9 @@
 // and are merged by the same combine kernel (App. C).
 #include "plx_device.h"
 #include "plx_kernels.h"
+#include "plx_mla_tile.h"
 
 namespace plx {
-
-namespace {
-
-constexpr int kMlaDC = 512, kMlaDR = 64, kMlaDK = kMlaDC + kMlaDR;
-constexpr int kMlaTileKeys = 64;
-constexpr int kMlaKSteps = kMlaDK / 32;      // 18 score k-steps, the last two on the rope part
-constexpr int kMlaLatBlocks = kMlaDC / 128;  // column blocks of the latent part
-constexpr int kMlaNDB = 128 / 16;            // 16-dimension output blocks per wave
-constexpr int kMlaPvSteps = kMlaTileKeys / 32;         // k-steps of the second contraction
-constexpr int kMlaBlkChunks = kMlaTileKeys * 16;       // 16-byte chunks of one column block
-constexpr int kMlaRopeChunks = kMlaTileKeys * (kMlaDR / 8);
-constexpr int kMlaTileChunks = kMlaLatBlocks * kMlaBlkChunks + kMlaRopeChunks;
-constexpr int kMlaLoadsPerWave = kMlaTileChunks / 64 / 4;  // wave-wide 1 KB loads per tile and wave
-constexpr int kRowGroups = kMlaTileKeys / 4;           // loads per latent column block (4 rows each)
-static_assert(kMlaTileChunks % 256 == 0 && kMlaLoadsPerWave == 18, "four waves fill a tile with whole loads");
-
-// Rounds four fp32 values to bf16 (one half of an MFMA B operand) and adds the ROUNDED values to
-// acc, so that row sums and numerators use identical weights.
-__device__ __forceinline__ u32x2 pack4_bf16_accumulate(float p0, float p1, float p2, float p3, float &acc) {
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    bf16x2 a, b;
-    a[0] = (__bf16)p0, a[1] = (__bf16)p1;
-    b[0] = (__bf16)p2, b[1] = (__bf16)p3;
-    acc = __builtin_amdgcn_fdot2_f32_bf16(a, ones, acc, false);
-    acc = __builtin_amdgcn_fdot2_f32_bf16(b, ones, acc, false);
-    return u32x2{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b)};
-}
-
-}  // namespace
 
 // PAGED: the cache is a pool of pages behind a block table. A tile that lies inside one page
 // (page size a multiple of 64) is fetched like a tile of a contiguous cache from its page;
@@ -470,11 +442,17 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(MlaDecodeParams p) {
 
 
 hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream) {
-    const dim3 grid(p.S, (p.Hq * p.Tq + 15) / 16, p.B);
-    if (p.block_table)
-        hipLaunchKernelGGL(decode_mla_kernel<true>, grid, dim3(256), 0, stream, p);
-    else
-        hipLaunchKernelGGL(decode_mla_kernel<false>, grid, dim3(256), 0, stream, p);
+    // more than one group of 16 columns: the step is matrix bound -- the 32-column form
+    if (p.Hq * p.Tq > 16) {
+        const hipError_t err = launch_decode_mla_wide(p, stream);
+        if (err != hipSuccess) return err;
+    } else {
+        const dim3 grid(p.S, 1, p.B);
+        if (p.block_table)
+            hipLaunchKernelGGL(decode_mla_kernel<true>, grid, dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL(decode_mla_kernel<false>, grid, dim3(256), 0, stream, p);
+    }
     if (!p.direct_out) {
         DecodeParams c{};
         c.ws = p.ws, c.o = p.o, c.B = p.B, c.Hq = p.Hq * p.Tq, c.Tq = 1, c.S = p.S, c.d = kMlaDC;

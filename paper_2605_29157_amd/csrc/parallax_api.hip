@@ -437,7 +437,11 @@ int32_t parallax_decode_mla_num_splits(int32_t B, int32_t Hq, int32_t Lmax, int3
     // 323 / 344 (3, a round and an eighth: 501 / 505); 160 pairs x L = 8192: S = 3 284 / 289 (2:
     // 384 / 392, 1: 317 / 334); 256 pairs: unsplit 829 / 813 (2: 836, 4: 864); 40 pairs x
     // L = 32768: S = 14 362 / 356, 7: 434 / 424, 4: 323 / 340.
-    const int64_t pairs = (int64_t)B * ((Hq + 15) / 16);
+    // More than 16 columns take the 32-column kernel, which is bound by its matrix work and the
+    // LDS, not by the memory: 2.6 us per tile when every unit holds a workgroup, 2.3 us at least.
+    const bool wide = Hq > 16;
+    const double t_full = wide ? 2.6 : 3.2, t_least = wide ? 2.3 : 2.4;
+    const int64_t pairs = (int64_t)B * (wide ? (Hq + 31) / 32 : 1);
     const int64_t n_tiles = ((int64_t)Lmax + 63) / 64;
     int64_t cap = n_tiles >= 8 ? n_tiles / 4 : 1;
     if (cap > PLX_MAX_SPLITS) cap = PLX_MAX_SPLITS;
@@ -445,8 +449,8 @@ int32_t parallax_decode_mla_num_splits(int32_t B, int32_t Hq, int32_t Lmax, int3
         const int64_t rounds = (pairs * s + num_cus - 1) / num_cus;
         const int64_t tiles = (n_tiles + s - 1) / s;
         const double w_last = (double)(pairs * s - (rounds - 1) * num_cus) / (double)num_cus;
-        const double t_last = 3.2 * w_last > 2.4 ? 3.2 * w_last : 2.4;
-        return (double)(rounds - 1) * ((double)tiles * 3.2 + 10.0) + ((double)tiles * t_last + 10.0) +
+        const double t_last = t_full * w_last > t_least ? t_full * w_last : t_least;
+        return (double)(rounds - 1) * ((double)tiles * t_full + 10.0) + ((double)tiles * t_last + 10.0) +
                (s > 1 ? 6.0 : 0.0);
     };
     int64_t best = 1;

@@ -128,6 +128,7 @@ hipError_t launch_prefill_f32(const PrefillParams &p, hipStream_t stream);
 hipError_t launch_norm_rope(const NormRopeParams &p, bool f32, hipStream_t stream);
 hipError_t launch_rope_table(float *table, int n_pos, int d, float theta, hipStream_t stream);
 hipError_t launch_decode_mla(const MlaDecodeParams &p, hipStream_t stream);
+hipError_t launch_decode_mla_wide(const MlaDecodeParams &p, hipStream_t stream);  // the kernel launch only: more than 16 columns
 hipError_t launch_util_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);
 hipError_t launch_util_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
 hipError_t launch_util_read_grid(const void *src, size_t bytes, void *sink, int workgroups, hipStream_t stream);

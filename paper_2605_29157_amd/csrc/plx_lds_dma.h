@@ -70,6 +70,24 @@ __device__ __forceinline__ void tile_load16_uniform(uint32_t lane_byte_off, cons
             : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr)
             : "memory");
 }
+// The same load under a wave-uniform execution mask (`on` = -1: all lanes, 0: none): a loop body that issues
+// the next tile's loads between its matrix instructions stays free of branches when there is no
+// next tile to fetch -- with no lane enabled the instruction does nothing.
+__device__ __forceinline__ void tile_load16_uniform_if(int32_t on, uint32_t lane_byte_off, const void *tile_base,
+                                                       uint32_t lds_byte_addr) {
+    on = __builtin_amdgcn_readfirstlane(on);  // (a scalar register, whatever the compiler kept it in)
+    uint64_t saved_exec;
+    asm volatile(
+        "s_mov_b64 %0, exec\n\t"
+        "s_mov_b32 exec_lo, %4\n\t"
+        "s_mov_b32 exec_hi, %4\n\t"
+        "s_mov_b32 m0, %3\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
+        "s_mov_b64 exec, %0"
+        : "=&s"(saved_exec)
+        : "v"(lane_byte_off), "s"(tile_base), "s"(lds_byte_addr), "s"(on)
+        : "memory");
+}
 // Wait until at most PENDING of this wave's tile loads are still in flight (loads complete in
 // issue order), then the workgroup barrier that publishes the landed tiles.
 template <int PENDING = 0>

@@ -364,6 +364,9 @@ def test_decode_mla_rejects_bad_arguments_before_launch(binding):
     f = binding.parallax_decode_mla_num_splits
     assert f(64, 16, 16384, 256) == 4 and f(1, 16, 16384, 256) == 64 and f(1, 16, 100, 256) == 1
     assert f(512, 128, 4096, 256) == 1
+    # more than 16 columns: 32 per workgroup, so 128 heads are four workgroups per (sequence, split)
+    assert f(16, 128, 8192, 256) == 4 and f(64, 128, 4096, 256) == 1 and f(4, 128, 16384, 256) == 16
+    assert f(24, 128, 8192, 256) == 5      # 96 x 5 = 480 workgroups: two rounds, the second nearly full
     for (B, Hq, L) in [(1, 1, 1), (3, 17, 5000), (128, 16, 131072), (2, 128, 70000)]:
         assert 1 <= f(B, Hq, L, 256) <= binding.PLX_MAX_SPLITS
 

@@ -55,16 +55,23 @@ def _check(plx, mla, x, num_splits=0, tol=BF16_REL_L2):
     return got
 
 
+# Up to 16 columns (heads x rows) take the 16-column kernel, more the 32-column one: the basic
+# cases run on both (48 heads: one full group of 32 columns and a half-filled one).
+HEADS = [16, 48]
+
+
+@pytest.mark.parametrize("Hq", HEADS)
 @pytest.mark.parametrize("L", [1, 2, 15, 16, 17, 63, 64, 65, 127, 129, 200, 777, 2048])
-def test_lengths_and_tails(plx, synth, mla, L):
-    x = synth.mla_decode_inputs(2, 16, L, seed=4000 + L, device=DEV)
+def test_lengths_and_tails(plx, synth, mla, L, Hq):
+    x = synth.mla_decode_inputs(2, Hq, L, seed=4000 + L, device=DEV)
     _check(plx, mla, x, num_splits=1)
     _check(plx, mla, x, num_splits=0)
 
 
+@pytest.mark.parametrize("Hq", HEADS)
 @pytest.mark.parametrize("S", [1, 2, 3, 5, 8, 32, 128])
-def test_split_counts_agree_incl_empty_splits(plx, synth, mla, S):
-    x = synth.mla_decode_inputs(2, 16, 1000, seed=4100, device=DEV)
+def test_split_counts_agree_incl_empty_splits(plx, synth, mla, S, Hq):
+    x = synth.mla_decode_inputs(2, Hq, 1000, seed=4100, device=DEV)
     got = _check(plx, mla, x, num_splits=S)
     one = host(plx.parallax_decode_mla(x["q"], x["r"], x["ckv"], x["scale"], num_splits=1))
     assert rel_l2(got, one) <= 4e-3       # different summation order, each output rounded to bf16 once
@@ -77,8 +84,9 @@ def test_head_counts_and_partial_column_groups(plx, synth, mla, Hq):
     _check(plx, mla, x, num_splits=3)
 
 
-def test_ragged_lengths_with_an_empty_sequence(plx, synth, mla):
-    x = synth.mla_decode_inputs(5, 16, 900, seed=4300, device=DEV, ragged=True)
+@pytest.mark.parametrize("Hq", HEADS)
+def test_ragged_lengths_with_an_empty_sequence(plx, synth, mla, Hq):
+    x = synth.mla_decode_inputs(5, Hq, 900, seed=4300, device=DEV, ragged=True)
     x["seq_lens"][2] = 0
     x["seq_lens"][4] = 1
     for S in (0, 1, 4):
@@ -87,8 +95,9 @@ def test_ragged_lengths_with_an_empty_sequence(plx, synth, mla):
         np.testing.assert_allclose(got[4], np.broadcast_to(host(x["ckv"])[4, 0, :512], got[4].shape), rtol=1e-2, atol=1e-2)
 
 
-def test_strided_cache_and_small_probe(plx, synth, mla):
-    x = synth.mla_decode_inputs(3, 16, 500, seed=4400, device=DEV, r_scale=0.1)
+@pytest.mark.parametrize("Hq", HEADS)
+def test_strided_cache_and_small_probe(plx, synth, mla, Hq):
+    x = synth.mla_decode_inputs(3, Hq, 500, seed=4400, device=DEV, r_scale=0.1)
     wide = torch.zeros(3, 520, 640, dtype=torch.bfloat16, device=DEV)   # rows of 640, 20 spare tokens
     wide[:, :500, :576] = x["ckv"]
     view = wide[:, :500, :576]
@@ -98,20 +107,44 @@ def test_strided_cache_and_small_probe(plx, synth, mla):
     np.testing.assert_array_equal(a, b)
 
 
-def test_large_logit_range_and_zero_scale(plx, synth, mla):
-    x = synth.mla_decode_inputs(2, 16, 700, seed=4500, device=DEV)
+@pytest.mark.parametrize("Hq", HEADS)
+def test_large_logit_range_and_zero_scale(plx, synth, mla, Hq):
+    x = synth.mla_decode_inputs(2, Hq, 700, seed=4500, device=DEV)
     x["q"] = (x["q"].float() * 12.0).to(torch.bfloat16)     # logits spread over ~ +-40: softmax nearly one-hot
     _check(plx, mla, x, num_splits=4)
     _check(plx, mla, dict(x, scale=0.0), num_splits=2)       # uniform weights
 
 
-def test_zero_probe_is_softmax_attention_over_the_latent(plx, synth, mla):
-    x = synth.mla_decode_inputs(2, 16, 400, seed=4600, device=DEV)
+@pytest.mark.parametrize("Hq", HEADS)
+@pytest.mark.parametrize("rise", [-300.0, 6.0, 40.0, 300.0])
+def test_logits_that_drift_along_the_sequence(plx, synth, mla, Hq, rise):
+    """Every key carries a component, growing linearly with its position, along a direction all
+    queries share: the running maximum of every column rises (or falls) by `rise` (log2 domain)
+    over the sequence -- by a fraction of a binade per tile, by a few, or by more than ten, so the
+    softmax reference stays for many tiles, moves now and then, or moves in every tile. The
+    32-column kernel lets its reference lag the maximum by up to eight binades."""
+    L = 1500
+    x = synth.mla_decode_inputs(2, Hq, L, seed=4550 + Hq, device=DEV)
+    q = x["q"].float()
+    q[..., 0] = 8.0
+    x["q"] = q.to(torch.bfloat16)
+    x["r"][..., 0] = 0                      # (the probe does not see the drifting component)
+    c = x["ckv"].float()
+    per_key = rise / (x["scale"] * 8.0 * 1.4426950408889634) / L        # logit = scale * 8 * c[j, 0]
+    c[..., 0] = per_key * torch.arange(L, device=DEV, dtype=torch.float32)
+    x["ckv"] = c.to(torch.bfloat16)
+    for S in (1, 3):
+        _check(plx, mla, x, num_splits=S)
+
+
+@pytest.mark.parametrize("Hq", HEADS)
+def test_zero_probe_is_softmax_attention_over_the_latent(plx, synth, mla, Hq):
+    x = synth.mla_decode_inputs(2, Hq, 400, seed=4600, device=DEV)
     x["r"] = torch.zeros_like(x["r"])
     got = _check(plx, mla, x)
     q, c = torch.tensor(host(x["q"])), torch.tensor(host(x["ckv"]))
     ref = torch.nn.functional.scaled_dot_product_attention(
-        q[:, :, None, :], c[:, None].expand(2, 16, 400, 576), c[:, None, :, :512].expand(2, 16, 400, 512),
+        q[:, :, None, :], c[:, None].expand(2, Hq, 400, 576), c[:, None, :, :512].expand(2, Hq, 400, 512),
         scale=x["scale"])[:, :, 0].numpy()
     assert rel_l2(got, ref) <= BF16_REL_L2
 
