@@ -66,11 +66,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-extra", action="store_true", help="skip the sweep / prefill lines")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["decode", "prefill", "backward", "sweep"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "prefill", "backward", "sweep", "mla"], default="decode",
                     help="decode = config 2 (the headline line); prefill = config 4 causal "
                          "prefill alone, for profiling that kernel; backward = the backward pass "
                          "of that prefill shape; sweep = the config 3 decode "
-                         "grid (B x L, fixed and ragged lengths, d = 128 and 64), one JSON line")
+                         "grid (B x L, fixed and ragged lengths, d = 128 and 64), one JSON line; "
+                         "mla = attention over a latent cache alone (--mla-shape)")
+    ap.add_argument("--mla-shape", default="16,128,1,8192", metavar="B,Hq,Tq,L",
+                    help="sequences, heads, rows per head and cached tokens of the latent-cache workload "
+                         "(default: 128 heads on one GPU; up to 16 heads x rows run the memory-bound "
+                         "kernel, more the 32-column one)")
     ap.add_argument("--decode-shape", default="8,4096", metavar="B,L",
                     help="batch and KV length of the decode workload (default 8,4096 = config 2; "
                          "other shapes are for profiling the same kernels at larger sizes)")
@@ -113,6 +118,9 @@ def main():
         return
     if opt.workload == "sweep":
         print(json.dumps(decode_sweep(torch, plx, synth, lib, dev, sptr)))
+        return
+    if opt.workload == "mla":
+        print(json.dumps(mla_line(torch, plx, synth, lib, dev, sptr, opt)))
         return
 
     # ------------------------------------------------------------------ workload: config 2
@@ -266,6 +274,51 @@ def main():
         result["extra"] = extra_measurements(torch, plx, synth, lib, dev, sptr, sets, ws, out)
 
     print(json.dumps(result))
+
+
+def mla_line(torch, plx, synth, lib, dev, sptr, opt):
+    """Attention over an MLA-style latent cache on its own (R21): Tq rows per head at the end of L
+    cached tokens. Algorithmic flops: 2 * (2 * 576 + 2 * 512) per (head, row, visible token);
+    algorithmic bytes: the cache once + q, rho, o."""
+    B, Hq, Tq, L = (int(v) for v in opt.mla_shape.split(","))
+    n_cols = Hq * Tq
+    nset = max(1, min(8, int(2e9 // (B * L * 1152))))  # rotated caches: every call reads cold data
+    xs = [synth.mla_decode_inputs(B, n_cols, L, seed=1040 + i, device=dev) for i in range(nset)]
+    out = torch.empty(B, Hq, Tq, 512, dtype=torch.bfloat16, device=dev)
+    S = plx.parallax_decode_mla_num_splits(B, n_cols, L)
+    ws = torch.empty(max(B * n_cols * S * 1028, 4), dtype=torch.float32, device=dev)
+    args = [plx.decode_mla_args(x["q"].view(B, Hq, Tq, 576), x["r"].view(B, Hq, Tq, 576), x["ckv"], out, x["scale"],
+                                None, S, ws) for x in xs]
+    k = [0]
+
+    def step():
+        st = lib.parallax_decode_mla(ctypes.byref(args[k[0] % nset]), sptr)
+        k[0] += 1
+        if st != 0:
+            raise plx.ParallaxError(st, "mla bench")
+
+    steps, warm = min(opt.steps, 100), min(opt.warmup, 5)
+    us = _time_events(torch, step, warm, steps)
+    pairs = B * Hq * sum(max(L - Tq + t + 1, 0) for t in range(Tq))
+    flops = 4352.0 * pairs
+    nbytes = B * L * 1152 + B * n_cols * (2 * 576 * 2 + 512 * 2)
+    wide = n_cols > 16
+    tf, gbps = flops / us / 1e6, nbytes / us / 1e3
+    roof = ({"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+             "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "decode_mla_wide_kernel"}
+            if wide else
+            {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+             "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": "decode_mla_kernel"})
+    roof["step_us_incl_combine"] = round(us, 1)
+    return {
+        "metric": "latent_cache_attention_bf16", "value": round(tf if wide else gbps, 1),
+        "unit": "TFLOP/s" if wide else "GB/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": round(us / 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "latent cache (512 + 64) bf16 B=%d Hq=%d rows=%d L=%d, %d splits" % (B, Hq, Tq, L, S),
+                   "algorithmic_flops": flops, "algorithmic_bytes": nbytes},
+        "roofline": roof,
+    }
 
 
 def prefill_line(torch, plx, synth, dev, opt):
