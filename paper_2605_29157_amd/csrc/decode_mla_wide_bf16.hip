@@ -14,13 +14,14 @@
 //     v_mfma_f32_16x16x32_bf16. Its q and rho fragments (144 registers) stay in registers; a K
 //     fragment read from the LDS feeds two matrix instructions, the fragment pair of a k-step
 //     four independent accumulation chains.
-//   * the tile maximum of a column is agreed on through the LDS by the two waves that scored it;
-//     P1 and P2 = P1 * S2 are published through the LDS in the B-operand order of the second
-//     contraction;
+//   * P1 and P2 = P1 * S2 are published through the LDS in the B-operand order of the second
+//     contraction, computed against the softmax reference the column has at that moment; the
+//     tile maxima of the two waves that scored a column travel with them, and the reference
+//     follows the maximum afterwards, in steps (see kRefSlack, kRefGuard);
 //   * values: wave w owns the output dimensions 128 w .. 128 w + 127 and accumulates
 //     O^T += V^T P^T over all 64 keys and all 32 columns with v_mfma_f32_32x32x16_bf16: a V^T
 //     fragment (two transposing LDS reads) feeds two matrix instructions of twice the size.
-// Three barriers per tile. A lane therefore has two column identities: its score column
+// Two barriers per tile. A lane therefore has two column identities: its score column
 // (16 ch + lane % 16, rows of the score block are keys) and its output column (lane % 32); the
 // running maximum is kept for both, from the same agreed tile maxima.
 // Split partials and their merge are those of the narrow form.
@@ -40,6 +41,8 @@ constexpr int kGroupsPerXcdRun = 8;  // column groups of one (batch, split) that
 // every tile (with 32 columns some maximum rises in most tiles; the rescale alone cost a quarter
 // of the tile time).
 constexpr float kRefSlack = 8.f;
+// ... and weights computed before the tile's maximum is known may reach 2^kRefGuard (see the loop)
+constexpr float kRefGuard = 64.f;
 
 template <bool PAGED>
 __global__ __launch_bounds__(256, 1) void decode_mla_wide_kernel(MlaDecodeParams p) {
@@ -221,6 +224,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_wide_kernel(MlaDecodeParams
     // score column: reference m_s and the row sums over this lane's keys; output column c32:
     // reference m_o and O^T, register i of block n = dimension 128 w + 32 n + 8 (i / 4) + 4 hi + i % 4
     float m_s = kNegInf, m_o = kNegInf, dsum1 = 0.f, dsum2 = 0.f;
+    float rescale_s = 1.f, rescale_o = 1.f;  // owed to the sums since the references last moved
     f32x16 o1[4], o2[4];
 #pragma unroll
     for (int n = 0; n < 4; ++n)
@@ -278,7 +282,16 @@ __global__ __launch_bounds__(256, 1) void decode_mla_wide_kernel(MlaDecodeParams
             }
         }
 
-        // ---- tile maximum of every column, agreed on by the two waves that scored it ----------
+        // ---- P1, P2 of this lane's keys -> LDS in B-operand order, against the reference the
+        // column has NOW: no agreement on the tile's maximum first (that cost a barrier and an LDS
+        // round trip per tile). The tile maxima travel with P and are looked at behind the
+        // barrier: if some column's maximum lies more than kRefGuard binades above its reference
+        // (or the column has no reference yet: its first visible tile), the workgroup moves the
+        // references and publishes P again before anybody uses it -- rare; otherwise the weights
+        // stand (they are at most 2^kRefGuard) and the references move, in steps, for the next tile.
+        // 16-key step kk = 2 kh + rb of the second contraction; k-elements 8 hi' .. 8 hi' + 7 of
+        // the consuming lane (column, hi') are the keys 8 hi' + (0 .. 7) of the step, i.e. the
+        // producing lanes g = 2 hi' (elements 0 .. 3) and g = 2 hi' + 1 (elements 4 .. 7).
         const int key0 = t * kMlaTileKeys + 32 * kh + 4 * g;  // this lane's keys: key0 + 16 rb + i
         float x[8];
         float tmax = kNegInf;
@@ -288,48 +301,57 @@ __global__ __launch_bounds__(256, 1) void decode_mla_wide_kernel(MlaDecodeParams
             x[e] = (key >= key_lo && key < key_end) ? s1[e >> 2][e & 3] * scale_log2 : kNegInf;
             tmax = fmaxf(tmax, x[e]);
         }
+        float d1_tile, d2_tile;  // this lane's share of the tile's row sums, under the reference used
+        auto publish = [&](float reference) __attribute__((always_inline)) {
+            const float ref_use = reference == kNegInf ? 0.f : reference;
+            d1_tile = 0.f, d2_tile = 0.f;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                float p1[4], p2[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    p1[i] = fast_exp2(x[4 * rb + i] - ref_use);  // 0 if masked
+                    p2[i] = x[4 * rb + i] == kNegInf ? 0.f : p1[i] * s2[rb][i];
+                }
+                const u32x2 pk1 = pack4_bf16_accumulate(p1[0], p1[1], p1[2], p1[3], d1_tile);
+                const u32x2 pk2 = pack4_bf16_accumulate(p2[0], p2[1], p2[2], p2[3], d2_tile);
+                u32x2 *dst = (u32x2 *)(pbuf + (2 * kh + rb) * 64 + 32 * (g >> 1) + 16 * ch + c16) + (g & 1);
+                dst[0] = pk1;
+                dst[2 * kPvSteps16 * 64] = pk2;  // P2 follows P1: 4 steps x 64 chunks = 512 half-chunks
+            }
+        };
+        // a column's reference follows its maximum in steps of more than kRefSlack binades;
+        // returns the factor that brings sums under the old reference to the new one
+        auto move_reference = [&](float &reference, float tile_max) __attribute__((always_inline)) {
+            const float moved = tile_max > reference + kRefSlack ? tile_max : reference;
+            const float factor = fast_exp2(reference - (moved == kNegInf ? 0.f : moved));  // 0 from "none yet"
+            reference = moved;
+            return factor;
+        };
+        publish(m_s);
         tmax = rows_max(tmax);
         if (g == 0) smax[w * 16 + c16] = tmax;
         __syncthreads();
         // (wave 2 kh + ch holds column 16 ch + c16 at index 16 (2 kh + ch) + c16 = 32 kh + column)
         const float mt_s = fmaxf(smax[16 * ch + c16], smax[32 + 16 * ch + c16]);
         const float mt_o = fmaxf(smax[c32], smax[32 + c32]);
-        // (the same rule on the same agreed maxima: m_s and m_o of a column never differ)
-        const float ms_new = mt_s > m_s + kRefSlack ? mt_s : m_s, mo_new = mt_o > m_o + kRefSlack ? mt_o : m_o;
-        const float ms_use = ms_new == kNegInf ? 0.f : ms_new, mo_use = mo_new == kNegInf ? 0.f : mo_new;
-        const float alpha_s = fast_exp2(m_s - ms_use);  // 0 on the first live tile, 1 while the reference stays
-        const float alpha_o = fast_exp2(m_o - mo_use);
-        m_s = ms_new;
-        m_o = mo_new;
-
-        // ---- P1, P2 of this lane's keys -> LDS in B-operand order ----------------------------
-        // 16-key step kk = 2 kh + rb of the second contraction; k-elements 8 hi' .. 8 hi' + 7 of
-        // the consuming lane (column, hi') are the keys 8 hi' + (0 .. 7) of the step, i.e. the
-        // producing lanes g = 2 hi' (elements 0 .. 3) and g = 2 hi' + 1 (elements 4 .. 7).
-        dsum1 *= alpha_s;
-        dsum2 *= alpha_s;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            float p1[4], p2[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                p1[i] = fast_exp2(x[4 * rb + i] - ms_use);  // 0 if masked
-                p2[i] = x[4 * rb + i] == kNegInf ? 0.f : p1[i] * s2[rb][i];
-            }
-            const u32x2 pk1 = pack4_bf16_accumulate(p1[0], p1[1], p1[2], p1[3], dsum1);
-            const u32x2 pk2 = pack4_bf16_accumulate(p2[0], p2[1], p2[2], p2[3], dsum2);
-            u32x2 *dst = (u32x2 *)(pbuf + (2 * kh + rb) * 64 + 32 * (g >> 1) + 16 * ch + c16) + (g & 1);
-            dst[0] = pk1;
-            dst[2 * kPvSteps16 * 64] = pk2;  // P2 follows P1: 4 steps x 64 chunks = 512 half-chunks
+        // (every wave looks at all 32 columns through its output columns: the same decision in all)
+        if (__any(mt_o > m_o + kRefGuard || (m_o == kNegInf && mt_o != kNegInf))) {
+            rescale_s *= move_reference(m_s, mt_s);
+            rescale_o *= move_reference(m_o, mt_o);
+            publish(m_s);
+            __syncthreads();
         }
-        __syncthreads();
-
+        // the sums so far come under the columns' present references (moved at the end of the
+        // tile before, or just now), then the tile joins them
+        dsum1 = dsum1 * rescale_s + d1_tile;
+        dsum2 = dsum2 * rescale_s + d2_tile;
         // The rescale works on the accumulation registers in place (assembly: written as plain
         // multiplications it made the compiler carry a second copy of all 128 accumulators in
         // vector registers around the loop, 128 moves per tile and as many registers short). The
         // matrix instructions that wrote these registers were issued a whole score phase ago,
         // the ones that read them follow behind the wait states below.
-        if (!__all(alpha_o == 1.f)) {
+        if (!__all(rescale_o == 1.f)) {
 #pragma unroll
             for (int n = 0; n < 4; ++n)
 #pragma unroll
@@ -343,10 +365,18 @@ __global__ __launch_bounds__(256, 1) void decode_mla_wide_kernel(MlaDecodeParams
                         "v_accvgpr_write_b32 %0, %2\n\t"
                         "v_accvgpr_write_b32 %1, %3"
                         : "+a"(a), "+a"(b2), "=&v"(ta), "=&v"(tb)
-                        : "v"(alpha_o));
+                        : "v"(rescale_o));
                     o1[n][i] = a, o2[n][i] = b2;
                 }
             asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");
+        }
+        // the references for the next tile (nothing moves right behind the slow path above); the
+        // sums follow at this place of the next tile. Not behind the last tile: the record's
+        // reference is the one its sums are under.
+        rescale_s = 1.f, rescale_o = 1.f;
+        if (more) {
+            rescale_s = move_reference(m_s, mt_s);
+            rescale_o = move_reference(m_o, mt_o);
         }
 
         // ---- O1^T += V^T P1^T, O2^T += V^T P2^T: dimensions 128 w .. 128 w + 127, 32 columns ---

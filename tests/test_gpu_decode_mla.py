@@ -116,13 +116,15 @@ def test_large_logit_range_and_zero_scale(plx, synth, mla, Hq):
 
 
 @pytest.mark.parametrize("Hq", HEADS)
-@pytest.mark.parametrize("rise", [-300.0, 6.0, 40.0, 300.0])
+@pytest.mark.parametrize("rise", [-3000.0, -300.0, 6.0, 40.0, 300.0, 3000.0])
 def test_logits_that_drift_along_the_sequence(plx, synth, mla, Hq, rise):
     """Every key carries a component, growing linearly with its position, along a direction all
     queries share: the running maximum of every column rises (or falls) by `rise` (log2 domain)
-    over the sequence -- by a fraction of a binade per tile, by a few, or by more than ten, so the
-    softmax reference stays for many tiles, moves now and then, or moves in every tile. The
-    32-column kernel lets its reference lag the maximum by up to eight binades."""
+    over the sequence -- by a fraction of a binade per tile, by a few, by more than ten or by more
+    than a hundred, so the softmax reference stays for many tiles, moves now and then, moves in
+    every tile, or has to move before the tile's weights can be used at all. The 32-column kernel
+    lets its reference lag the maximum by up to eight binades and computes a tile's weights before
+    it knows the tile's maximum (up to 64 binades above the reference they stand)."""
     L = 1500
     x = synth.mla_decode_inputs(2, Hq, L, seed=4550 + Hq, device=DEV)
     q = x["q"].float()
