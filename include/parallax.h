@@ -294,6 +294,9 @@ plx_status parallax_prefill(const plx_prefill_args *args, void *hip_stream);
  *              sequence b is row j % page_size of page block_table[b][j / page_size]; entries
  *              are clamped to existing pages. block_table_stride * page_size >= Lmax. Any page
  *              size works; multiples of 64 are fetched page-wise, others row by row (slower).
+ * Up to 16 (head, row) pairs per sequence run a memory-bound kernel (16 MFMA columns per
+ * workgroup); more run a matrix-bound one (32 columns per workgroup, the workgroups of one
+ * sequence placed so that they share an L2). Same results contract, same workspace format.
  * Validates on the host, enqueues one or two kernels on hip_stream, does not synchronise.
  */
 typedef struct {
