@@ -307,6 +307,16 @@ def test_sliding_window(plx, synth, mla, Tq, L, W):
     _check_rows(plx, mla, x, window=W, num_splits=5)
 
 
+@pytest.mark.parametrize("Hq,Tq,L,W", [(48, 1, 1000, 1), (48, 1, 1000, 65), (48, 1, 1000, 300), (40, 2, 700, 130),
+                                        (17, 1, 300, 5000)])
+def test_sliding_window_with_more_than_16_columns(plx, synth, mla, Hq, Tq, L, W):
+    """The same on the 32-column kernel with one row per head (above, only several rows per head
+    reach it): full and half-filled column groups, ragged lengths."""
+    x = _rows_inputs(synth, 3, Hq, Tq, L, seed=4850 + L + W, ragged=True)
+    for S in (1, 0, 3):
+        _check_rows(plx, mla, x, window=W, num_splits=S)
+
+
 @pytest.mark.parametrize("Hq,T,W", [(2, 300, 0), (4, 513, 0), (1, 1000, 0), (3, 400, 100)])
 def test_causal_prefill_over_the_latent_cache(plx, synth, mla, Hq, T, W):
     """Tq = the prompt length: every row of the prompt attends to the latent rows up to its own."""
