@@ -191,13 +191,14 @@ def test_random_shapes(plx, synth, mla, case):
     _check(plx, mla, x, num_splits=S)
 
 
-def test_hip_graph_replays_match_eager(plx, synth):
+@pytest.mark.parametrize("Hq", HEADS)
+def test_hip_graph_replays_match_eager(plx, synth, Hq):
     """The two launches of a split step captured once and replayed with new cache contents."""
     import ctypes
 
-    x = synth.mla_decode_inputs(4, 16, 3000, seed=4990, device=DEV, ragged=True)
-    out = torch.empty(4, 16, 512, dtype=torch.bfloat16, device=DEV)
-    ws = torch.empty(plx.parallax_decode_mla_workspace_bytes(4, 16) // 4, dtype=torch.float32, device=DEV)
+    x = synth.mla_decode_inputs(4, Hq, 3000, seed=4990, device=DEV, ragged=True)
+    out = torch.empty(4, Hq, 512, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(plx.parallax_decode_mla_workspace_bytes(4, Hq) // 4, dtype=torch.float32, device=DEV)
     a = plx.decode_mla_args(x["q"], x["r"], x["ckv"], out, x["scale"], x["seq_lens"], 6, ws)
     lib = plx.load_library()
     graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
