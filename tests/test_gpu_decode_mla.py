@@ -347,7 +347,7 @@ def test_rows_and_window_arguments_are_validated(plx, synth):
 
 
 def test_many_heads_and_rows_at_the_benchmark_launches(plx, synth, mla):
-    """The launches bench.py times: B=16 x 128 heads x L=8192 (eight column groups per sequence,
+    """The launches bench.py times: B=16 x 128 heads x L=8192 (four groups of 32 columns per sequence,
     heuristic splits), 4 rows x 16 heads at the end of L=16384, and the causal prefill of 4096
     latent rows -- the oracle on sampled sequences / rows."""
     x = synth.mla_decode_inputs(16, 128, 8192, seed=4960, device=DEV)
