@@ -21,9 +21,10 @@
 //   * values: wave w owns the output dimensions 128 w .. 128 w + 127 and accumulates
 //     O^T += V^T P^T over all 64 keys and all 32 columns with v_mfma_f32_32x32x16_bf16: a V^T
 //     fragment (two transposing LDS reads) feeds two matrix instructions of twice the size.
-// Two barriers per tile. A lane therefore has two column identities: its score column
-// (16 ch + lane % 16, rows of the score block are keys) and its output column (lane % 32); the
-// running maximum is kept for both, from the same agreed tile maxima.
+// Two barriers per tile (the tile has landed; P and the maxima are published). A lane has two
+// column identities: its score column (16 ch + lane % 16, rows of the score block are keys) and
+// its output column (lane % 32); the softmax reference is kept for both, moved by the same rule
+// from the same agreed tile maxima.
 // Split partials and their merge are those of the narrow form.
 #include "plx_device.h"
 #include "plx_kernels.h"
