@@ -7,8 +7,9 @@
 // is no longer memory bound: every group walks the same tokens, so what counts is matrix work per
 // byte read out of the LDS. This form therefore takes 32 columns per workgroup:
 //   * two 64-key tiles in the LDS (the tile layout of the narrow form), filled by direct
-//     global -> LDS loads one tile ahead, one load between the matrix instructions of every
-//     score k-step. No register stages: the registers hold the operands instead.
+//     global -> LDS loads one tile ahead, spread between the matrix instructions of the score
+//     k-steps and the wait in front of the exchange. No register stages: the registers hold the
+//     operands instead.
 //   * scores: wave (kh, ch) takes the keys 32 kh .. 32 kh + 31 of the tile and the columns
 //     16 ch .. 16 ch + 15, S^T = C [Q; R]^T over all 576 dimensions with
 //     v_mfma_f32_16x16x32_bf16. Its q and rho fragments (144 registers) stay in registers; a K
@@ -233,12 +234,16 @@ __global__ __launch_bounds__(256, 1) void decode_mla_wide_kernel(MlaDecodeParams
         for (int i = 0; i < 16; ++i) o1[n][i] = 0.f, o2[n][i] = 0.f;
     const float scale_log2 = p.scale * kLog2e;
 
-    // One tile. If tile t + 1 is whole and lies in one piece, its 18 loads go one per score k-step
-    // between the matrix instructions (under an execution mask, so the body has no branches);
-    // otherwise they were issued as a block in front.
+    // One tile. If tile t + 1 is whole and lies in one piece, twelve of its 18 loads go between
+    // the matrix instructions of the score k-steps (two of every three steps) and six in front of
+    // the barrier that publishes P (under an execution mask, so the body has no branches);
+    // otherwise they were issued as a block in front. (One load in every k-step asks the CU's
+    // vector-memory path for exactly what it can deliver, and the waves queue up behind it: 3 %
+    // slower. Later than the barrier the loads land too late.)
     // The LDS fragment reads run two steps ahead of the matrix instructions that use them (three
     // fragment sets in rotation); scheduling fences keep the compiler from sinking a read down to
     // its first use, which exposes the LDS latency once per step.
+    constexpr int kScoreLoads = kMlaKSteps - kMlaKSteps / 3;  // 12
     if (t_lo < t_hi) issue_tile(t_lo, 0);
     for (int t = t_lo; t < t_hi; ++t) {
         const int buf = (t - t_lo) & 1;
@@ -272,7 +277,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_wide_kernel(MlaDecodeParams
 #pragma unroll
             for (int ks = 0; ks < kMlaKSteps; ++ks) {
                 if (ks + 2 < kMlaKSteps) read_step(ks + 2);
-                issue_load(fill_base, buf ^ 1, ks, stride_now, fill_lanes);
+                if (ks % 3 != 2) issue_load(fill_base, buf ^ 1, ks - ks / 3, stride_now, fill_lanes);  // loads 0 .. 11
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb) {
@@ -332,6 +337,9 @@ __global__ __launch_bounds__(256, 1) void decode_mla_wide_kernel(MlaDecodeParams
         publish(m_s);
         tmax = rows_max(tmax);
         if (g == 0) smax[w * 16 + c16] = tmax;
+        // the last six loads of the next tile: here the wave is about to wait anyway
+#pragma unroll
+        for (int i = kScoreLoads; i < kMlaLoadsPerWave; ++i) issue_load(fill_base, buf ^ 1, i, stride_now, fill_lanes);
         __syncthreads();
         // (wave 2 kh + ch holds column 16 ch + c16 at index 16 (2 kh + ch) + c16 = 32 kh + column)
         const float mt_s = fmaxf(smax[16 * ch + c16], smax[32 + 16 * ch + c16]);
